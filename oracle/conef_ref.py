@@ -1,0 +1,237 @@
+"""ctypes face of the CPU oracle (oracle/conef_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  The product package never imports this module.
+
+Every function takes and returns numpy arrays; the arithmetic is all in the C
+file (Algorithm 2 lines 5, 6, 9; eq. (3) with the block max-norm; the rank-r
+factorisation of Section 5.2).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "conef_ref.c")
+_LIB = os.path.join(_HERE, "libconef_ref.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
+    in the source is an explicit fmaf(), nothing else may be contracted."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        L = ctypes.CDLL(_LIB)
+        vp, i64, i32, u64, u32 = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint64,
+                                  ctypes.c_uint32)
+        L.ref_philox4x32_10.argtypes = [vp, vp, vp]
+        L.ref_philox4x32_10.restype = None
+        L.ref_rand16.argtypes = [u64, u32, u64, u64]
+        L.ref_rand16.restype = u32
+        L.ref_get_code.argtypes = [vp, i64, i32]
+        L.ref_get_code.restype = ctypes.c_int32
+        L.ref_decode.argtypes = [vp, vp, i64, i32, i32, vp]
+        L.ref_decode.restype = None
+        L.ref_form_p.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp]
+        L.ref_form_p.restype = None
+        L.ref_lowrank_P.argtypes = [vp, i64, i64, vp, i32, vp]
+        L.ref_lowrank_P.restype = None
+        L.ref_orthonormalise.argtypes = [vp, i64, i32]
+        L.ref_orthonormalise.restype = None
+        L.ref_lowrank_Q.argtypes = [vp, i64, i64, vp, i32, vp]
+        L.ref_lowrank_Q.restype = None
+        L.ref_residual.argtypes = [vp, i64, i64, vp, vp, i32, vp]
+        L.ref_residual.restype = None
+        L.ref_quantise.argtypes = [vp, i64, i32, i32, u64, u32, u64, vp, vp, vp]
+        L.ref_quantise.restype = None
+        L.ref_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, i32, u64, u32, u64,
+                                      vp, vp, vp, vp, vp, vp]
+        L.ref_step_matrix.restype = None
+        L.ref_step_matrix_efsgd.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp]
+        L.ref_step_matrix_efsgd.restype = None
+        L.ref_num_threads.argtypes = []
+        L.ref_num_threads.restype = i32
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def levels(bits: int) -> int:
+    return (1 << (bits - 1)) - 1
+
+
+def n_words(N: int, bits: int) -> int:
+    W = 32 // bits
+    return (N + W - 1) // W
+
+
+def n_blocks(N: int, block: int) -> int:
+    return (N + block - 1) // block
+
+
+def num_threads() -> int:
+    return int(lib().ref_num_threads())
+
+
+# ---------------------------------------------------------------- random bits
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c, k = _c(ctr, np.uint32), _c(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().ref_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def rand16(seed: int, mat: int, step: int, j: int) -> int:
+    return int(lib().ref_rand16(seed, mat, step, j))
+
+
+# ---------------------------------------------------------------- codec
+def grad_array(g: np.ndarray):
+    """Returns (contiguous array, dtype tag).  bf16 gradients travel as uint16 bit patterns."""
+    if g.dtype == np.float32:
+        return np.ascontiguousarray(g), F32
+    if g.dtype == np.uint16:
+        return np.ascontiguousarray(g), BF16
+    raise TypeError("gradient must be float32 or uint16 (bf16 bits)")
+
+
+def unpack_codes(codes: np.ndarray, N: int, bits: int) -> np.ndarray:
+    c = _c(codes, np.uint32)
+    return np.array([lib().ref_get_code(_p(c), j, bits) for j in range(N)], np.int32)
+
+
+def decode(codes, scales, N: int, bits: int, block: int) -> np.ndarray:
+    c, s = _c(codes, np.uint32), _c(scales, np.float32)
+    e = np.empty(N, np.float32)
+    lib().ref_decode(_p(c), _p(s), N, bits, block, _p(e))
+    return e
+
+
+def form_p(g, codes, scales, bits: int, block: int) -> np.ndarray:
+    ga, dt = grad_array(g)
+    N = ga.size
+    c, s = _c(codes, np.uint32), _c(scales, np.float32)
+    p = np.empty(N, np.float32)
+    lib().ref_form_p(_p(ga), dt, _p(c), _p(s), N, bits, block, _p(p))
+    return p.reshape(g.shape)
+
+
+def quantise(x, bits: int, block: int, seed: int = 0, mat: int = 0, step: int = 0, draw=None):
+    """eq. (3) with block max-norm.  Returns (codes uint32[n_words], scales float32[n_blocks])."""
+    xa = _c(x, np.float32).ravel()
+    N = xa.size
+    assert block % (32 // bits) == 0
+    codes = np.zeros(n_words(N, bits), np.uint32)
+    scales = np.zeros(n_blocks(N, block), np.float32)
+    d = None if draw is None else _c(draw, np.uint16).ravel()
+    lib().ref_quantise(_p(xa), N, bits, block, seed, mat, step,
+                       None if d is None else _p(d), _p(codes), _p(scales))
+    return codes, scales
+
+
+# ---------------------------------------------------------------- rank-r compressor
+def lowrank_P(p, Q) -> np.ndarray:
+    pa, Qa = _c(p, np.float32), _c(Q, np.float32)
+    n, m = pa.shape
+    r = Qa.shape[1]
+    assert Qa.shape[0] == m and r <= 64
+    P = np.empty((n, r), np.float32)
+    lib().ref_lowrank_P(_p(pa), n, m, _p(Qa), r, _p(P))
+    return P
+
+
+def orthonormalise(P) -> np.ndarray:
+    Pa = np.array(P, dtype=np.float32, order="C", copy=True)
+    n, r = Pa.shape
+    lib().ref_orthonormalise(_p(Pa), n, r)
+    return Pa
+
+
+def lowrank_Q(p, Phat) -> np.ndarray:
+    pa, Pa = _c(p, np.float32), _c(Phat, np.float32)
+    n, m = pa.shape
+    r = Pa.shape[1]
+    Qn = np.empty((m, r), np.float32)
+    lib().ref_lowrank_Q(_p(pa), n, m, _p(Pa), r, _p(Qn))
+    return Qn
+
+
+def residual(p, Phat, Qn) -> np.ndarray:
+    pa, Pa, Qa = _c(p, np.float32), _c(Phat, np.float32), _c(Qn, np.float32)
+    n, m = pa.shape
+    x = np.empty((n, m), np.float32)
+    lib().ref_residual(_p(pa), n, m, _p(Pa), _p(Qa), Pa.shape[1], _p(x))
+    return x
+
+
+# ---------------------------------------------------------------- whole step
+@dataclass
+class MatState:
+    """Per-matrix persistent state of the path: compressed error and the warm-started Q."""
+    n: int
+    m: int
+    codes: np.ndarray
+    scales: np.ndarray
+    Q: np.ndarray
+
+    @staticmethod
+    def fresh(n: int, m: int, bits: int, block: int, Q0: np.ndarray) -> "MatState":
+        N = n * m
+        return MatState(n, m, np.zeros(n_words(N, bits), np.uint32),
+                        np.zeros(n_blocks(N, block), np.float32),
+                        np.array(Q0, np.float32, order="C", copy=True))
+
+
+def step_matrix(g, st: MatState, rank: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """Runs one ConEF step on one matrix; updates `st` in place; returns (Phat, Qn)."""
+    ga, dt = grad_array(g)
+    n, m = st.n, st.m
+    assert ga.size == n * m and st.Q.shape == (m, rank)
+    P = np.empty((n, rank), np.float32)
+    Qn = np.empty((m, rank), np.float32)
+    work = np.empty(2 * n * m, np.float32)
+    lib().ref_step_matrix(_p(ga), dt, n, m, rank, bits, block, seed, mat, step,
+                          _p(st.codes), _p(st.scales), _p(st.Q), _p(P), _p(Qn), _p(work))
+    st.Q = Qn
+    return P, Qn
+
+
+def step_matrix_efsgd(g, e, Q):
+    """Algorithm 1 (uncompressed error) with the same rank-r compressor. e updated in place."""
+    ga = _c(g, np.float32)
+    n, m = ga.shape
+    Qa = _c(Q, np.float32)
+    r = Qa.shape[1]
+    assert e.dtype == np.float32 and e.flags.c_contiguous and e.shape == (n, m)
+    P = np.empty((n, r), np.float32)
+    Qn = np.empty((m, r), np.float32)
+    work = np.empty(n * m, np.float32)
+    lib().ref_step_matrix_efsgd(_p(ga), n, m, r, _p(e), _p(Qa), _p(P), _p(Qn), _p(work))
+    return P, Qn

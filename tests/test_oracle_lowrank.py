@@ -1,0 +1,177 @@
+"""Pins for the oracle's gradient compressor: the rank-r factorisation of Section 5.2
+(P = p Q, orthonormalise, Q+ = p^T P^, Delta = P^ Q+^T) and its contraction (Assumption 4)."""
+import numpy as np
+import pytest
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def test_P_is_p_times_Q(ref):
+    rng = _rng(0)
+    n, m, r = 37, 53, 3                                # non-square: a transposed operand would not even fit
+    p = rng.standard_normal((n, m)).astype(np.float32)
+    Q = rng.standard_normal((m, r)).astype(np.float32)
+    want = (p.astype(np.float64) @ Q.astype(np.float64)).astype(np.float32)
+    got = ref.lowrank_P(p, Q)
+    assert got.shape == (n, r)
+    assert np.max(np.abs(got - want)) <= 1e-6 * np.abs(want).max()
+
+
+def test_Q_is_p_transposed_times_P(ref):
+    rng = _rng(1)
+    n, m, r = 41, 150, 4                               # m > column chunk of the oracle (64) and ragged
+    p = rng.standard_normal((n, m)).astype(np.float32)
+    Ph = rng.standard_normal((n, r)).astype(np.float32)
+    want = (p.astype(np.float64).T @ Ph.astype(np.float64)).astype(np.float32)
+    got = ref.lowrank_Q(p, Ph)
+    assert got.shape == (m, r)
+    assert np.max(np.abs(got - want)) <= 1e-6 * np.abs(want).max()
+
+
+def test_tiny_brute_force_in_python_floats(ref):
+    """3x4 matrix, rank 2, every sum written out with Python floats (fp64)."""
+    p = np.array([[1, 2, 3, 4], [0.5, -1, 2, 0], [3, 0, -2, 1]], np.float32)
+    Q = np.array([[1, 0], [0.5, 1], [-1, 2], [0, -0.5]], np.float32)
+    P = [[sum(float(p[i, k]) * float(Q[k, c]) for k in range(4)) for c in range(2)] for i in range(3)]
+    assert np.allclose(ref.lowrank_P(p, Q), np.array(P), rtol=1e-7)
+    # Gram-Schmidt by hand
+    c0 = np.array([P[i][0] for i in range(3)])
+    c1 = np.array([P[i][1] for i in range(3)])
+    u0 = c0 / np.sqrt((c0 * c0).sum())
+    v1 = c1 - (u0 * c1).sum() * u0
+    u1 = v1 / np.sqrt((v1 * v1).sum())
+    Ph = ref.orthonormalise(ref.lowrank_P(p, Q))
+    assert np.allclose(Ph[:, 0], u0, atol=1e-6) and np.allclose(Ph[:, 1], u1, atol=1e-6)
+    Qn = [[sum(float(p[i, k]) * float(Ph[i, c]) for i in range(3)) for c in range(2)] for k in range(4)]
+    got_Q = ref.lowrank_Q(p, Ph)
+    assert np.allclose(got_Q, np.array(Qn), rtol=1e-6, atol=1e-7)
+    x = [[float(p[i, k]) - sum(float(Ph[i, c]) * float(got_Q[k, c]) for c in range(2)) for k in range(4)]
+         for i in range(3)]
+    assert np.allclose(ref.residual(p, Ph, got_Q), np.array(x), atol=1e-6)
+
+
+@pytest.mark.parametrize("n,r", [(64, 1), (300, 4), (1000, 8), (257, 32)])
+def test_orthonormalise_is_the_positive_diagonal_thin_QR(ref, n, r):
+    rng = _rng(2)
+    P = (rng.standard_normal((n, r)) * np.logspace(0, 2, r)).astype(np.float32)
+    Ph = ref.orthonormalise(P)
+    Qf, Rf = np.linalg.qr(P.astype(np.float64))
+    sgn = np.sign(np.diag(Rf))
+    Qf = Qf * sgn
+    assert np.max(np.abs(Ph - Qf)) <= 2e-7 * 4
+    G = Ph.astype(np.float64).T @ Ph.astype(np.float64)
+    assert np.max(np.abs(G - np.eye(r))) <= 1e-5
+    R = Ph.astype(np.float64).T @ P.astype(np.float64)      # = R of the factorisation
+    assert np.all(np.diag(R) > 0)
+    assert np.max(np.abs(np.tril(R, -1))) <= 1e-5 * np.abs(R).max()
+
+
+def test_orthonormalise_ill_conditioned_still_orthogonal(ref):
+    """Columns nearly parallel (condition ~1e5): projecting twice keeps orthogonality."""
+    rng = _rng(3)
+    n, r = 500, 4
+    base = rng.standard_normal((n, 1))
+    P = (base + 1e-5 * rng.standard_normal((n, r))).astype(np.float32)
+    Ph = ref.orthonormalise(P).astype(np.float64)
+    assert np.max(np.abs(Ph.T @ Ph - np.eye(r))) <= 1e-5
+
+
+def test_orthonormalise_dependent_column_becomes_zero(ref):
+    rng = _rng(4)
+    n = 100
+    A = rng.standard_normal((n, 3)).astype(np.float32)
+    P = np.stack([A[:, 0], 2 * A[:, 0], A[:, 1], np.zeros(n, np.float32)], 1)
+    Ph = ref.orthonormalise(P)
+    assert np.all(np.isfinite(Ph))
+    assert np.all(Ph[:, 1] == 0) and np.all(Ph[:, 3] == 0)
+    assert abs(np.linalg.norm(Ph[:, 0]) - 1) < 1e-6 and abs(np.linalg.norm(Ph[:, 2]) - 1) < 1e-6
+    assert abs(float(Ph[:, 0] @ Ph[:, 2])) < 1e-6
+    assert np.all(ref.orthonormalise(np.zeros((10, 2), np.float32)) == 0)
+
+
+def _compress(ref, p, Q):
+    P = ref.lowrank_P(p, Q)
+    Ph = ref.orthonormalise(P)
+    Qn = ref.lowrank_Q(p, Ph)
+    return Ph, Qn
+
+
+@pytest.mark.parametrize("n,m,r,true_rank", [(60, 90, 4, 4), (90, 60, 4, 2), (33, 129, 8, 8), (128, 64, 2, 1)])
+def test_exact_recovery_of_low_rank_input(ref, n, m, r, true_rank):
+    """If rank(p) <= r then one step reproduces p: ||p - P^ Q+^T|| <= 1e-5 ||p||."""
+    rng = _rng(5)
+    p = (rng.standard_normal((n, true_rank)) @ rng.standard_normal((true_rank, m))).astype(np.float32)
+    Q = rng.standard_normal((m, r)).astype(np.float32)
+    Ph, Qn = _compress(ref, p, Q)
+    x = ref.residual(p, Ph, Qn)
+    assert np.linalg.norm(x) <= 1e-5 * np.linalg.norm(p)
+
+
+def test_full_rank_r_reproduces_any_matrix(ref):
+    rng = _rng(6)
+    n, m = 12, 7                                       # r = min(n, m) = m
+    p = rng.standard_normal((n, m)).astype(np.float32)
+    Ph, Qn = _compress(ref, p, rng.standard_normal((m, m)).astype(np.float32))
+    assert np.linalg.norm(ref.residual(p, Ph, Qn)) <= 1e-5 * np.linalg.norm(p)
+
+
+@pytest.mark.parametrize("n,m,r", [(256, 128, 2), (200, 333, 4), (96, 512, 32)])
+def test_projection_invariants_and_contraction(ref, n, m, r):
+    """Delta = P^ P^^T p is an orthogonal projection: P^^T (p - Delta) = 0 and
+    ||p - Delta||^2 = ||p||^2 - ||Q+||_F^2, hence ||Q(p) - p||^2 = rho ||p||^2 with rho in [0,1):
+    the contraction of Assumption 4 for this compressor."""
+    rng = _rng(7)
+    p = rng.standard_normal((n, m)).astype(np.float32)
+    Q0 = rng.standard_normal((m, r)).astype(np.float32)
+    Ph, Qn = _compress(ref, p, Q0)
+    x = ref.residual(p, Ph, Qn).astype(np.float64)
+    assert np.max(np.abs(Ph.astype(np.float64).T @ x)) <= 1e-4
+    np2 = float((p.astype(np.float64) ** 2).sum())
+    lhs = float((x ** 2).sum())
+    rhs = np2 - float((Qn.astype(np.float64) ** 2).sum())
+    assert abs(lhs - rhs) <= 1e-5 * np2
+    rho = lhs / np2
+    assert 0.0 <= rho < 1.0
+    # Delta equals the projection onto range(p Q) built with a library QR
+    Qf, _ = np.linalg.qr(p.astype(np.float64) @ Q0.astype(np.float64))
+    delta = Qf @ (Qf.T @ p.astype(np.float64))
+    assert np.max(np.abs((p - x) - delta)) <= 1e-5 * np.abs(p).max()
+
+
+def test_warm_started_steps_converge_to_truncated_svd(ref):
+    """Repeating the step on a fixed p with Q fed back is subspace iteration: the residual
+    decreases monotonically to the tail energy sum_{i>r} sigma_i^2 of numpy's SVD."""
+    rng = _rng(8)
+    n, m, r = 80, 60, 3
+    U, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    V, _ = np.linalg.qr(rng.standard_normal((m, m)))
+    sig = np.concatenate([[10, 8, 6], 0.5 * rng.random(m - 3)])
+    p = ((U[:, :m] * sig) @ V.T).astype(np.float32)
+    tail = float((np.linalg.svd(p.astype(np.float64), compute_uv=False)[r:] ** 2).sum())
+    Q = rng.standard_normal((m, r)).astype(np.float32)
+    prev = np.inf
+    for _ in range(12):
+        Ph, Q = _compress(ref, p, Q)
+        res = float((ref.residual(p, Ph, Q).astype(np.float64) ** 2).sum())
+        assert res <= prev * (1 + 1e-6)
+        prev = res
+    assert tail * (1 - 1e-4) <= prev <= tail * 1.01
+
+
+def test_residual_is_fp32_fma_chain(ref):
+    """x = p - sum_c P^[i,c] Q+[k,c], the sum taken in fp32 as an fma chain in ascending c
+    (np.float32 arithmetic with an exact product emulates the single rounding of fma)."""
+    rng = _rng(9)
+    n, m, r = 9, 11, 5
+    p = rng.standard_normal((n, m)).astype(np.float32)
+    Ph = rng.standard_normal((n, r)).astype(np.float32)
+    Qn = rng.standard_normal((m, r)).astype(np.float32)
+    got = ref.residual(p, Ph, Qn)
+    for i in range(n):
+        for k in range(m):
+            acc = np.float32(0)
+            for c in range(r):
+                acc = np.float32(np.float64(Ph[i, c]) * np.float64(Qn[k, c]) + np.float64(acc))
+            assert got[i, k] == np.float32(p[i, k] - acc)

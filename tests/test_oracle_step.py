@@ -1,0 +1,159 @@
+"""Pins for the oracle's whole step: Algorithm 2 (ConEF) lines 5, 6, 9 and its relation to
+Algorithm 1 (EFSGD).  The paper prints no number for this path, so absolute values of a
+multi-step run are unpinned; what is checked are the algorithm's identities."""
+import numpy as np
+import pytest
+
+from paper_2312_08538_amd import workloads as wl
+
+
+def test_form_p_adds_decoded_error(ref):
+    """Line 5 (eta folded into g): p = g + e with e = scale/s * q per block."""
+    rng = np.random.default_rng(0)
+    for bits, block in [(8, 64), (4, 128), (2, 256)]:
+        N = 5 * block + 24
+        x = rng.standard_normal(N).astype(np.float32)
+        codes, scales = ref.quantise(x, bits, block, seed=3)
+        g = rng.standard_normal(N).astype(np.float32)
+        p = ref.form_p(g, codes, scales, bits, block)
+        q = ref.unpack_codes(codes, N, bits).astype(np.float64)
+        a = np.repeat(scales.astype(np.float64), block)[:N]
+        want = g.astype(np.float64) + a / ref.levels(bits) * q
+        assert np.max(np.abs(p - want)) <= 2e-7 * np.abs(want).max() + 1e-7 * np.abs(a).max()
+        e = ref.decode(codes, scales, N, bits, block)
+        assert np.max(np.abs((p - g) - e)) <= 4e-7 * max(1.0, np.abs(p).max())
+
+
+def test_bf16_gradients_are_widened_exactly(ref):
+    vals = np.array([1.0, -2.5, 3.140625, 1e-3, -65280.0, 0.0], np.float32)
+    bits16 = wl.f32_to_bf16_bits(vals)
+    back = wl.bf16_bits_to_f32(bits16)
+    N = 64
+    g = np.resize(bits16, N)
+    p = ref.form_p(g, np.zeros(ref.n_words(N, 8), np.uint32), np.zeros(1, np.float32), 8, 64)
+    assert np.array_equal(p, np.resize(back, N))
+    assert back[0] == 1.0 and back[1] == -2.5 and back[2] == 3.140625
+    # round to nearest even of the generator: 1 + 2^-8 is a tie -> 1.0; 1 + 3*2^-8 -> 1 + 2^-6
+    t = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8], np.float32)
+    assert np.array_equal(wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(t)), np.array([1.0, 1 + 2.0 ** -6], np.float32))
+
+
+def test_step_is_the_composition_of_its_parts(ref):
+    rng = np.random.default_rng(1)
+    n, m, r, bits, block = 48, 160, 3, 4, 32
+    g = rng.standard_normal((n, m)).astype(np.float32)
+    Q0 = rng.standard_normal((m, r)).astype(np.float32)
+    x0 = rng.standard_normal(n * m).astype(np.float32) * 0.3
+    codes, scales = ref.quantise(x0, bits, block, seed=1)
+    st = ref.MatState(n, m, codes.copy(), scales.copy(), Q0.copy())
+    Ph, Qn = ref.step_matrix(g, st, r, bits, block, seed=77, mat=4, step=6)
+    p = ref.form_p(g, codes, scales, bits, block)
+    P = ref.lowrank_P(p, Q0)
+    Ph2 = ref.orthonormalise(P)
+    Qn2 = ref.lowrank_Q(p, Ph2)
+    x = ref.residual(p, Ph2, Qn2)
+    c2, s2 = ref.quantise(x, bits, block, seed=77, mat=4, step=6)
+    assert np.array_equal(Ph, Ph2) and np.array_equal(Qn, Qn2)
+    assert np.array_equal(st.codes, c2) and np.array_equal(st.scales, s2)
+    assert np.array_equal(st.Q, Qn2)
+
+
+def test_identity_error_compressor_is_efsgd_and_telescopes(ref):
+    """With C = identity, Algorithm 2 is Algorithm 1, and sum_t Delta_t + e_T = sum_t g_t."""
+    rng = np.random.default_rng(2)
+    n, m, r, T = 40, 56, 2, 6
+    e = np.zeros((n, m), np.float32)
+    Q = rng.standard_normal((m, r)).astype(np.float32)
+    sum_g = np.zeros((n, m))
+    sum_delta = np.zeros((n, m))
+    for t in range(T):
+        g = rng.standard_normal((n, m)).astype(np.float32)
+        sum_g += g
+        Ph, Q = ref.step_matrix_efsgd(g, e, Q)
+        sum_delta += Ph.astype(np.float64) @ Q.astype(np.float64).T
+    assert np.max(np.abs(sum_delta + e - sum_g)) <= 1e-5 * np.abs(sum_g).max()
+
+
+def test_conef_error_tracks_the_residual_within_one_level(ref):
+    """Line 9: the stored error is C(p - Delta): per element within a/s of the exact residual,
+    and the accumulated-update identity of ConEF holds up to that compression noise:
+    sum_t Delta_t + e_T - sum_t g_t = sum_t (C(x_t) - x_t)."""
+    rng = np.random.default_rng(3)
+    n, m, r, bits, block, T = 64, 128, 2, 8, 64, 5
+    st = ref.MatState.fresh(n, m, bits, block, rng.standard_normal((m, r)))
+    sum_g = np.zeros((n, m))
+    sum_delta = np.zeros((n, m))
+    noise = np.zeros((n, m))
+    for t in range(T):
+        g = rng.standard_normal((n, m)).astype(np.float32)
+        p = ref.form_p(g, st.codes, st.scales, bits, block)
+        Ph, Qn = ref.step_matrix(g, st, r, bits, block, seed=9, mat=0, step=t)
+        x = ref.residual(p, Ph, Qn)
+        e_new = ref.decode(st.codes, st.scales, n * m, bits, block).reshape(n, m)
+        a = np.repeat(st.scales, block).reshape(n, m)
+        assert np.all(np.abs(e_new - x) < a / ref.levels(bits) * (1 + 1e-6))
+        sum_g += g
+        sum_delta += Ph.astype(np.float64) @ Qn.astype(np.float64).T
+        noise += e_new.astype(np.float64) - x
+    e_T = ref.decode(st.codes, st.scales, n * m, bits, block).reshape(n, m)
+    assert np.max(np.abs(sum_delta + e_T - sum_g - noise)) <= 2e-5 * np.abs(sum_g).max()
+    # the noise is zero-mean (unbiased C): its average over 8192 elements is small
+    assert abs(noise.mean()) <= 5 * noise.std() / np.sqrt(noise.size)
+
+
+def test_tiny_workload_ten_steps_invariants(ref):
+    """Configuration 'tiny': 256x128 fp32 N(0,1), rank 2, 8-bit codes, block 64, zero initial
+    error, fresh gradient every step.  Per step: P^ orthonormal, residual orthogonal to P^,
+    contraction factor in [0,1), codes within range, state decodes to the residual within a level."""
+    w = wl.WORKLOADS["tiny"]
+    (n, m), r, bits, block = w.layout[0], w.rank, w.bits, w.block
+    st = ref.MatState.fresh(n, m, bits, block, wl.host_q0(w, 0))
+    s = ref.levels(bits)
+    for t in range(10):
+        g = wl.host_gradient(w, t, 0)
+        p = ref.form_p(g, st.codes, st.scales, bits, block)
+        if t == 0:
+            assert np.array_equal(p, g)               # e_0 = 0
+        Ph, Qn = ref.step_matrix(g, st, r, bits, block, w.lib_seed, 0, t)
+        assert np.max(np.abs(Ph.astype(np.float64).T @ Ph.astype(np.float64) - np.eye(r))) < 1e-5
+        x = ref.residual(p, Ph, Qn).astype(np.float64)
+        assert np.max(np.abs(Ph.astype(np.float64).T @ x)) < 1e-3
+        rho = (x ** 2).sum() / (p.astype(np.float64) ** 2).sum()
+        assert 0.9 < rho < 1.0                        # iid Gaussian input: little energy in rank 2
+        q = ref.unpack_codes(st.codes, n * m, bits)
+        assert q.min() >= -s and q.max() <= s
+        e = ref.decode(st.codes, st.scales, n * m, bits, block).astype(np.float64)
+        a = np.repeat(st.scales, block)
+        assert np.all(np.abs(e - x.ravel()) < a / s * (1 + 1e-6))
+
+
+def test_same_inputs_same_outputs_and_seed_matters(ref):
+    rng = np.random.default_rng(4)
+    n, m, r, bits, block = 32, 64, 2, 4, 64
+    g = rng.standard_normal((n, m)).astype(np.float32)
+    Q0 = rng.standard_normal((m, r))
+    outs = []
+    for seed, step in [(1, 0), (1, 0), (2, 0), (1, 1)]:
+        st = ref.MatState.fresh(n, m, bits, block, Q0)
+        ref.step_matrix(g, st, r, bits, block, seed, 0, step)
+        outs.append(st.codes.copy())
+    assert np.array_equal(outs[0], outs[1])
+    assert not np.array_equal(outs[0], outs[2]) and not np.array_equal(outs[0], outs[3])
+
+
+@pytest.mark.parametrize("name", ["cnn", "lm", "translation", "large"])
+def test_workload_shapes_one_small_matrix_each(ref, name):
+    """One cut-down matrix per workload with that workload's dtype / rank / bits / block and value
+    distribution: the step runs, the projection identity holds and the state stays in range."""
+    w = wl.WORKLOADS[name]
+    n, m = 96, 2 * w.block + (64 if name == "cnn" else 0)     # cnn: rows not a multiple of the block
+    g = wl.host_gradient(w, 0, 1, shape=(n, m))
+    st = ref.MatState.fresh(n, m, w.bits, w.block, wl.host_q0(w, 1, shape=(n, m)))
+    for t in range(2):
+        p = ref.form_p(g, st.codes, st.scales, w.bits, w.block)
+        Ph, Qn = ref.step_matrix(g, st, w.rank, w.bits, w.block, w.lib_seed, 1, t)
+        x = ref.residual(p, Ph, Qn).astype(np.float64)
+        np2 = (p.astype(np.float64) ** 2).sum()
+        assert abs((x ** 2).sum() - (np2 - (Qn.astype(np.float64) ** 2).sum())) <= 1e-5 * np2
+        q = ref.unpack_codes(st.codes, n * m, w.bits)
+        assert np.abs(q).max() <= ref.levels(w.bits)
