@@ -1,0 +1,122 @@
+/*
+ * conef.h -- C ABI of the MI355X (gfx950) implementation of one worker's share of
+ * contractive error feedback (ConEF, arXiv 2312.08538, Algorithm 2) with a rank-r
+ * PowerSGD-style gradient compressor (Section 5.2) and the block-wise stochastic
+ * quantiser of Section 4.2.1, eq. (3) (max-norm variant, Section 5.1) as the error
+ * compressor.
+ *
+ * Conventions
+ *   - Every function returns CONEF_OK (0) or a negative CONEF_E* code; nothing throws,
+ *     aborts or synchronises the stream.  conef_strerror() names a code.
+ *   - "device" pointers are HIP device memory owned by the caller (allocated, kept alive
+ *     until the stream has drained, and freed by the caller).  The library owns only the
+ *     context and the small device-side tables it uploads on first use.
+ *   - A model is a list of matrices ("layerwise" application, Section 5); matrix l is
+ *     rows x cols, row-major.  All per-matrix data live in flat buffers at the element
+ *     offsets reported by conef_offsets(); conef_sizes() gives the buffer lengths.
+ *   - Compressed error state: b-bit two's-complement codes, W = 32/b per uint32 word,
+ *     element j of a matrix in bits [b*(j mod W), b*(j mod W)+b) of word j/W; one fp32
+ *     scale (the block's max-norm) per `block` consecutive elements of the flat row-major
+ *     index, the last block of a matrix possibly short.  Decoded value: scale * fl(1/s) * q
+ *     with s = 2^(b-1)-1.  All-zero codes and scales are the state e_0 = 0 (Algorithm 2,
+ *     line 1), so zero-filled buffers are a valid initial state.
+ *   - Random draws: Philox4x32-10, counter (j>>3, l, lo32(step), hi32(step)), key
+ *     (lo32(seed), hi32(seed)); element j uses 16 bits: half (j&1) of output word (j&7)>>1.
+ *   - Calls on one context must not overlap in time (they share the workspace).
+ */
+#ifndef CONEF_H
+#define CONEF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct conef_ctx conef_ctx;                 /* opaque; host memory owned by the library */
+typedef struct { int64_t rows, cols; } conef_mat;   /* one layout entry */
+
+enum { CONEF_F32 = 0, CONEF_BF16 = 1 };             /* gradient element type; P, Q, scales are fp32 */
+enum { CONEF_OK = 0, CONEF_EINVAL = -1, CONEF_ENOMEM = -2, CONEF_EHIP = -3, CONEF_ESTATE = -4 };
+
+/* Plans a model.  Host only: no device is touched until the first call that launches.
+ *   layout[n_mats]  matrices in model order (each rows, cols >= 1, rows*cols < 2^35)
+ *   rank            r of the gradient compressor, 1 <= r <= 32 and r <= min(rows, cols) of every matrix
+ *   bits            2, 4 or 8 (s = 1, 7, 127 levels per sign)
+ *   block           elements per scale: a positive multiple of 32/bits, at most 2^20
+ *   grad_dtype      CONEF_F32 or CONEF_BF16
+ *   seed            key of the random draws
+ * Errors: CONEF_EINVAL for any violated constraint or null pointer, CONEF_ENOMEM. */
+int conef_init(conef_ctx **out, const conef_mat *layout, int n_mats, int rank, int bits,
+               int block, int grad_dtype, uint64_t seed);
+
+/* Lengths of the flat buffers, in elements of their type (any pointer may be null):
+ *   grad_elems   gradient elements (fp32 or bf16)       code_words  uint32 words of codes
+ *   n_scales     fp32 scales                            p_elems     fp32, all P factors (sum rows*r, padded)
+ *   q_elems      fp32, all Q factors (sum cols*r, padded)
+ *   workspace_bytes  scratch the caller passes to the step calls (256-byte aligned) */
+int conef_sizes(const conef_ctx *ctx, size_t *grad_elems, size_t *code_words, size_t *n_scales,
+                size_t *p_elems, size_t *q_elems, size_t *workspace_bytes);
+
+/* Element offsets of matrix `mat` inside the flat buffers (any pointer may be null).  Every
+ * offset is a multiple of 64 elements, so each matrix starts on a 128-byte boundary or better.
+ * Padding between matrices is never read or written. */
+int conef_offsets(const conef_ctx *ctx, int mat, size_t *grad_off, size_t *word_off,
+                  size_t *scale_off, size_t *p_off, size_t *q_off);
+
+/* One ConEF step for every matrix of the model (Algorithm 2, lines 5, 6 and 9; the
+ * aggregation of line 7 is the identity for a single worker and line 8 is the caller's):
+ *   p = g + decode(err)            g = grads, already scaled by the step size eta
+ *   P = p * Q_state ; P^ = orthonormalise(P) ; Q+ = p^T * P^
+ *   err <- quantise(p - P^ * Q+^T) with draws keyed by (seed, matrix, step, element)
+ * grads       device, in   flat gradients (grad_dtype), 16-byte aligned
+ * err_codes   device, in/out   err_scales  device, in/out      (updated in place)
+ * Q_state     device, in   right factors from the previous step (or the caller's initial draw)
+ * P_out       device, out  orthonormal left factors P^
+ * Q_out       device, out  new right factors Q+; may alias Q_state
+ * workspace   device, scratch of conef_sizes().workspace_bytes bytes
+ * step        iteration counter t (part of the Philox counter)
+ * hip_stream  hipStream_t to enqueue on (null = default stream).  Asynchronous.
+ * Errors: CONEF_EINVAL (null or misaligned pointer), CONEF_EHIP (a HIP call failed). */
+int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+               const float *Q_state, float *P_out, float *Q_out, void *workspace,
+               uint64_t step, void *hip_stream);
+
+/* The same step in its four stages, for callers that all-reduce P and Q between them
+ * (the two exchange points of an all-reducable compressor, Section 2 "How gradients are
+ * communicated") and for per-stage testing.  conef_step == p, orthonormalise, q, err. */
+int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes,
+                 const float *err_scales, const float *Q_state, float *P_raw_out,
+                 void *workspace, void *hip_stream);              /* P = (g + e) * Q_state          */
+int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace,
+                         void *hip_stream);                       /* P <- thin-QR factor, diag(R)>0 */
+int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes,
+                 const float *err_scales, const float *P_hat, float *Q_out,
+                 void *workspace, void *hip_stream);              /* Q+ = (g + e)^T * P^            */
+int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+                   const float *P_hat, const float *Q_new, uint64_t step,
+                   void *hip_stream);                             /* err <- C(g + e - P^ Q+^T)      */
+
+/* e := 0 for the whole model (zero codes and scales), enqueued on the stream. */
+int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream);
+
+/* Decodes the stored error into fp32 (e_out flat, laid out like an fp32 gradient buffer with
+ * the same element offsets).  For tests and export; not on the timed path. */
+int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *err_scales,
+                       float *e_out, void *hip_stream);
+
+/* Milliseconds between the first and the last kernel of the most recent conef_step /
+ * stage call on this context, per stage, measured with HIP events recorded on the caller's
+ * stream when timing was switched on with conef_set_timing(ctx, 1).  conef_get_timing
+ * synchronises on the recorded events.  ms[4] = {p, orthonormalise, q, err}. */
+int conef_set_timing(conef_ctx *ctx, int on);
+int conef_get_timing(conef_ctx *ctx, float ms[4]);
+
+void conef_destroy(conef_ctx *ctx);
+const char *conef_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONEF_H */

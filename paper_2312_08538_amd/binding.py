@@ -1,0 +1,203 @@
+"""Thin ctypes face of libconef.so: the functions of include/conef.h under the same names,
+plus `Model`, a holder of one context with its buffer sizes and offsets.  Argument
+marshalling only -- every step of the path runs in the library's HIP kernels.  There is no
+fallback: if the compiled library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconef.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+
+EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_p",
+           "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
+           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_destroy",
+           "conef_strerror"]
+
+
+class conef_mat(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libconef.so (built by paper_2312_08538_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2312_08538_amd.build`; "
+                           "there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sz, u64, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_int
+    szp = ctypes.POINTER(sz)
+    L.conef_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), i32, i32, i32, i32, i32, u64]
+    L.conef_sizes.argtypes = [vp, szp, szp, szp, szp, szp, szp]
+    L.conef_offsets.argtypes = [vp, i32, szp, szp, szp, szp, szp]
+    L.conef_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.conef_orthonormalise.argtypes = [vp, vp, vp, vp]
+    L.conef_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.conef_step_err.argtypes = [vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_reset_error.argtypes = [vp, vp, vp, vp]
+    L.conef_decode_error.argtypes = [vp, vp, vp, vp, vp]
+    L.conef_set_timing.argtypes = [vp, i32]
+    L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    L.conef_destroy.argtypes = [vp]
+    L.conef_destroy.restype = None
+    L.conef_strerror.argtypes = [i32]
+    L.conef_strerror.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("conef_destroy", "conef_strerror"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+class ConefError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lib().conef_strerror(code).decode()} ({code})")
+
+
+def _check(code: int, where: str) -> None:
+    if code != OK:
+        raise ConefError(code, where)
+
+
+def _ptr(t) -> int:
+    """Device (or host) address of a torch tensor / numpy array / raw int."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+# ------------------------------------------------------------------ plain functions, C names
+def conef_init(layout: Sequence[Tuple[int, int]], rank: int, bits: int, block: int, grad_dtype: int, seed: int):
+    arr = (conef_mat * max(1, len(layout)))()
+    for i, (n, m) in enumerate(layout):
+        arr[i].rows, arr[i].cols = n, m
+    ctx = ctypes.c_void_p()
+    _check(lib().conef_init(ctypes.byref(ctx), arr, len(layout), rank, bits, block, grad_dtype, seed), "conef_init")
+    return ctx
+
+
+def conef_sizes(ctx) -> dict:
+    v = [ctypes.c_size_t() for _ in range(6)]
+    _check(lib().conef_sizes(ctx, *[ctypes.byref(x) for x in v]), "conef_sizes")
+    keys = ["grad_elems", "code_words", "n_scales", "p_elems", "q_elems", "workspace_bytes"]
+    return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+def conef_offsets(ctx, mat: int) -> dict:
+    v = [ctypes.c_size_t() for _ in range(5)]
+    _check(lib().conef_offsets(ctx, mat, *[ctypes.byref(x) for x in v]), "conef_offsets")
+    keys = ["grad_off", "word_off", "scale_off", "p_off", "q_off"]
+    return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+def conef_step(ctx, grads, err_codes, err_scales, Q_state, P_out, Q_out, workspace, step: int, stream=0):
+    _check(lib().conef_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(Q_state), _ptr(P_out),
+                            _ptr(Q_out), _ptr(workspace), step, stream), "conef_step")
+
+
+def conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_raw_out, workspace, stream=0):
+    _check(lib().conef_step_p(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(Q_state), _ptr(P_raw_out),
+                              _ptr(workspace), stream), "conef_step_p")
+
+
+def conef_orthonormalise(ctx, P_inout, workspace, stream=0):
+    _check(lib().conef_orthonormalise(ctx, _ptr(P_inout), _ptr(workspace), stream), "conef_orthonormalise")
+
+
+def conef_step_q(ctx, grads, err_codes, err_scales, P_hat, Q_out, workspace, stream=0):
+    _check(lib().conef_step_q(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(P_hat), _ptr(Q_out),
+                              _ptr(workspace), stream), "conef_step_q")
+
+
+def conef_step_err(ctx, grads, err_codes, err_scales, P_hat, Q_new, step: int, stream=0):
+    _check(lib().conef_step_err(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(P_hat), _ptr(Q_new),
+                                step, stream), "conef_step_err")
+
+
+def conef_reset_error(ctx, err_codes, err_scales, stream=0):
+    _check(lib().conef_reset_error(ctx, _ptr(err_codes), _ptr(err_scales), stream), "conef_reset_error")
+
+
+def conef_decode_error(ctx, err_codes, err_scales, e_out, stream=0):
+    _check(lib().conef_decode_error(ctx, _ptr(err_codes), _ptr(err_scales), _ptr(e_out), stream),
+           "conef_decode_error")
+
+
+def conef_set_timing(ctx, on: bool):
+    _check(lib().conef_set_timing(ctx, 1 if on else 0), "conef_set_timing")
+
+
+def conef_get_timing(ctx) -> List[float]:
+    ms = (ctypes.c_float * 4)()
+    _check(lib().conef_get_timing(ctx, ms), "conef_get_timing")
+    return [float(x) for x in ms]
+
+
+def conef_destroy(ctx):
+    lib().conef_destroy(ctx)
+
+
+# ------------------------------------------------------------------ holder
+class Model:
+    """One context plus its sizes and per-matrix offsets.  `alloc(device)` returns zeroed torch
+    buffers of the right lengths (device memory management is all torch is used for)."""
+
+    def __init__(self, layout, rank, bits, block, grad_dtype, seed):
+        self.layout = [tuple(x) for x in layout]
+        self.rank, self.bits, self.block, self.grad_dtype, self.seed = rank, bits, block, grad_dtype, seed
+        self.ctx = conef_init(self.layout, rank, bits, block, grad_dtype, seed)
+        self.sizes = conef_sizes(self.ctx)
+        self.offsets = [conef_offsets(self.ctx, l) for l in range(len(self.layout))]
+
+    def close(self):
+        if self.ctx is not None:
+            conef_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def alloc(self, device="cuda:0"):
+        import torch
+
+        s = self.sizes
+        gdt = torch.float32 if self.grad_dtype == F32 else torch.bfloat16
+        return {
+            "grads": torch.zeros(s["grad_elems"], dtype=gdt, device=device),
+            "codes": torch.zeros(s["code_words"], dtype=torch.int32, device=device),
+            "scales": torch.zeros(s["n_scales"], dtype=torch.float32, device=device),
+            "Q": torch.zeros(s["q_elems"], dtype=torch.float32, device=device),
+            "P": torch.zeros(s["p_elems"], dtype=torch.float32, device=device),
+            "ws": torch.zeros(max(256, s["workspace_bytes"]), dtype=torch.uint8, device=device),
+        }
+
+    @staticmethod
+    def stream_handle() -> int:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream
+
+    def step(self, buf, step: int, Q_out=None):
+        conef_step(self.ctx, buf["grads"], buf["codes"], buf["scales"], buf["Q"], buf["P"],
+                   buf["Q"] if Q_out is None else Q_out, buf["ws"], step, self.stream_handle())

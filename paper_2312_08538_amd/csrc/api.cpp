@@ -1,0 +1,273 @@
+// C ABI of libconef: argument checks, the context, lazy upload of the plan to the device,
+// and the sequence of grouped launches that makes one step.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/conef.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace conef;
+
+struct conef_ctx {
+    Plan plan;
+    DevicePlan dev;
+    bool uploaded = false;
+    int device = -1;
+    std::vector<void *> device_allocs;
+    bool timing = false;
+    bool timing_valid[4] = {false, false, false, false};
+    hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+};
+
+namespace {
+
+template <typename T>
+int upload(conef_ctx *ctx, const std::vector<T> &host, const T **dev_out)
+{
+    *dev_out = nullptr;
+    if (host.empty()) return CONEF_OK;
+    void *p = nullptr;
+    if (hipMalloc(&p, host.size() * sizeof(T)) != hipSuccess) return CONEF_EHIP;
+    ctx->device_allocs.push_back(p);
+    if (hipMemcpy(p, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return CONEF_EHIP;
+    *dev_out = static_cast<const T *>(p);
+    return CONEF_OK;
+}
+
+int ensure_uploaded(conef_ctx *ctx)
+{
+    if (ctx->uploaded) return CONEF_OK;
+    if (hipGetDevice(&ctx->device) != hipSuccess) return CONEF_EHIP;
+    const Plan &pl = ctx->plan;
+    DevicePlan &d = ctx->dev;
+    int rc;
+    if ((rc = upload(ctx, pl.mats, &d.mats))) return rc;
+    if ((rc = upload(ctx, pl.p_items, &d.p_items))) return rc;
+    if ((rc = upload(ctx, pl.gram_items, &d.gram_items))) return rc;
+    if ((rc = upload(ctx, pl.apply_items, &d.apply_items))) return rc;
+    if ((rc = upload(ctx, pl.q_items, &d.q_items))) return rc;
+    if ((rc = upload(ctx, pl.qred_items, &d.qred_items))) return rc;
+    if ((rc = upload(ctx, pl.err_items, &d.err_items))) return rc;
+    if ((rc = upload(ctx, pl.elem_items, &d.elem_items))) return rc;
+    d.n_mats = (int)pl.mats.size();
+    d.n_p = (int)pl.p_items.size();
+    d.n_gram = (int)pl.gram_items.size();
+    d.n_apply = (int)pl.apply_items.size();
+    d.n_q = (int)pl.q_items.size();
+    d.n_qred = (int)pl.qred_items.size();
+    d.n_err = (int)pl.err_items.size();
+    d.n_elem = (int)pl.elem_items.size();
+    d.rank = pl.rank; d.rpad = pl.rpad; d.bits = pl.bits; d.block = pl.block; d.dtype = pl.dtype;
+    d.seed_lo = (uint32_t)pl.seed; d.seed_hi = (uint32_t)(pl.seed >> 32);
+    for (auto &e : ctx->ev)
+        if (hipEventCreate(&e) != hipSuccess) return CONEF_EHIP;
+    ctx->uploaded = true;
+    return CONEF_OK;
+}
+
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? CONEF_OK : CONEF_EHIP; }
+
+// stage index: 0 p, 1 orthonormalise, 2 q, 3 err
+struct StageTimer {
+    conef_ctx *ctx; int stage; hipStream_t st;
+    StageTimer(conef_ctx *c, int s, hipStream_t stream) : ctx(c), stage(s), st(stream)
+    {
+        if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * stage], st);
+    }
+    ~StageTimer()
+    {
+        if (ctx->timing) { (void)hipEventRecord(ctx->ev[2 * stage + 1], st); ctx->timing_valid[stage] = true; }
+    }
+};
+
+double *ws_doubles(const conef_ctx *, void *ws) { return static_cast<double *>(ws); }
+double *ws_qpart(const conef_ctx *ctx, void *ws) { return static_cast<double *>(ws) + ctx->plan.ws_doubles; }
+
+}  // namespace
+
+extern "C" {
+
+int conef_init(conef_ctx **out, const conef_mat *layout, int n_mats, int rank, int bits, int block,
+               int grad_dtype, uint64_t seed)
+{
+    if (!out) return CONEF_EINVAL;
+    *out = nullptr;
+    if (!layout || n_mats < 1) return CONEF_EINVAL;
+    conef_ctx *ctx = new (std::nothrow) conef_ctx();
+    if (!ctx) return CONEF_ENOMEM;
+    int rc = CONEF_OK;
+    try {
+        std::vector<int64_t> rows(n_mats), cols(n_mats);
+        for (int l = 0; l < n_mats; ++l) { rows[l] = layout[l].rows; cols[l] = layout[l].cols; }
+        rc = make_plan(ctx->plan, rows.data(), cols.data(), n_mats, rank, bits, block, grad_dtype, seed);
+    } catch (const std::bad_alloc &) {
+        rc = CONEF_ENOMEM;
+    }
+    if (rc != CONEF_OK) { delete ctx; return rc; }
+    *out = ctx;
+    return CONEF_OK;
+}
+
+int conef_sizes(const conef_ctx *ctx, size_t *grad_elems, size_t *code_words, size_t *n_scales,
+                size_t *p_elems, size_t *q_elems, size_t *workspace_bytes)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (grad_elems) *grad_elems = ctx->plan.grad_elems;
+    if (code_words) *code_words = ctx->plan.code_words;
+    if (n_scales) *n_scales = ctx->plan.n_scales;
+    if (p_elems) *p_elems = ctx->plan.p_elems;
+    if (q_elems) *q_elems = ctx->plan.q_elems;
+    if (workspace_bytes) *workspace_bytes = ctx->plan.workspace_bytes;
+    return CONEF_OK;
+}
+
+int conef_offsets(const conef_ctx *ctx, int mat, size_t *grad_off, size_t *word_off, size_t *scale_off,
+                  size_t *p_off, size_t *q_off)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    const MatDesc &d = ctx->plan.mats[mat];
+    if (grad_off) *grad_off = (size_t)d.grad_off;
+    if (word_off) *word_off = (size_t)d.word_off;
+    if (scale_off) *scale_off = (size_t)d.scale_off;
+    if (p_off) *p_off = (size_t)d.p_off;
+    if (q_off) *q_off = (size_t)d.q_off;
+    return CONEF_OK;
+}
+
+int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                 const float *Q_state, float *P_raw_out, void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !Q_state || !P_raw_out || !workspace) return CONEF_EINVAL;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(Q_state, 16) ||
+        misaligned(P_raw_out, 16) || misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    StageTimer t(ctx, 0, st);
+    return hip_rc(launch_pass_p(ctx->dev, grads, err_codes, err_scales, Q_state, P_raw_out, st));
+}
+
+int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
+{
+    if (!ctx || !P_inout || !workspace) return CONEF_EINVAL;
+    if (misaligned(P_inout, 16) || misaligned(workspace, 256)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    StageTimer t(ctx, 1, st);
+    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st));
+}
+
+int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                 const float *P_hat, float *Q_out, void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
+        misaligned(Q_out, 16) || misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    StageTimer t(ctx, 2, st);
+    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_qpart(ctx, workspace), st));
+}
+
+int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+                   const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_new) return CONEF_EINVAL;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
+        misaligned(Q_new, 16))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    StageTimer t(ctx, 3, st);
+    return hip_rc(launch_pass_err(ctx->dev, grads, err_codes, err_scales, P_hat, Q_new, step, st));
+}
+
+int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+               const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
+               void *hip_stream)
+{
+    int rc;
+    if ((rc = conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_out, workspace, hip_stream))) return rc;
+    /* exchange point 1: mean of P over the workers -- identity for one worker */
+    if ((rc = conef_orthonormalise(ctx, P_out, workspace, hip_stream))) return rc;
+    if ((rc = conef_step_q(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream))) return rc;
+    /* exchange point 2: mean of Q over the workers -- identity for one worker */
+    return conef_step_err(ctx, grads, err_codes, err_scales, P_out, Q_out, step, hip_stream);
+}
+
+int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream)
+{
+    if (!ctx || !err_codes || !err_scales) return CONEF_EINVAL;
+    if (misaligned(err_codes, 4) || misaligned(err_scales, 4)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_reset(ctx->dev, err_codes, err_scales, ctx->plan.code_words, ctx->plan.n_scales,
+                               static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *err_scales, float *e_out,
+                       void *hip_stream)
+{
+    if (!ctx || !err_codes || !err_scales || !e_out) return CONEF_EINVAL;
+    if (misaligned(err_codes, 4) || misaligned(err_scales, 4) || misaligned(e_out, 4)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_decode(ctx->dev, err_codes, err_scales, e_out, static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_set_timing(conef_ctx *ctx, int on)
+{
+    if (!ctx) return CONEF_EINVAL;
+    ctx->timing = on != 0;
+    for (bool &v : ctx->timing_valid) v = false;
+    return CONEF_OK;
+}
+
+int conef_get_timing(conef_ctx *ctx, float ms[4])
+{
+    if (!ctx || !ms) return CONEF_EINVAL;
+    if (!ctx->timing || !ctx->uploaded) return CONEF_ESTATE;
+    for (int s = 0; s < 4; ++s) {
+        ms[s] = 0.0f;
+        if (!ctx->timing_valid[s]) continue;
+        if (hipEventSynchronize(ctx->ev[2 * s + 1]) != hipSuccess) return CONEF_EHIP;
+        if (hipEventElapsedTime(&ms[s], ctx->ev[2 * s], ctx->ev[2 * s + 1]) != hipSuccess) return CONEF_EHIP;
+    }
+    return CONEF_OK;
+}
+
+void conef_destroy(conef_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->uploaded) {
+        for (auto &e : ctx->ev)
+            if (e) (void)hipEventDestroy(e);
+    }
+    for (void *p : ctx->device_allocs) (void)hipFree(p);
+    delete ctx;
+}
+
+const char *conef_strerror(int code)
+{
+    switch (code) {
+    case CONEF_OK: return "ok";
+    case CONEF_EINVAL: return "invalid argument";
+    case CONEF_ENOMEM: return "out of host memory";
+    case CONEF_EHIP: return "a HIP runtime call failed";
+    case CONEF_ESTATE: return "call not valid in the current state";
+    default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

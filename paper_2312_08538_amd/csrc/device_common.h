@@ -1,0 +1,90 @@
+// Device helpers shared by all kernel families: gradient widening, code fields, the
+// Philox4x32-10 counter-based generator and the stochastic-rounding decision of eq. (3).
+// Compiled with -ffp-contract=off: every fused multiply-add below is written explicitly.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace conef {
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ float load_grad(const void *g, int dtype, int64_t idx)
+{
+    if (dtype == 0) return reinterpret_cast<const float *>(g)[idx];
+    return bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(g)[idx]);
+}
+
+// Signed b-bit field number e (0-based, LSB first) of a code word.
+__device__ __forceinline__ int code_field(uint32_t w, int e, int bits)
+{
+    return (int)(w << (32 - bits * (e + 1))) >> (32 - bits);
+}
+
+__device__ __forceinline__ float inv_levels(int bits)
+{
+    // fl32(1/s) for s = 2^(b-1)-1: 1, 1/7, 1/127
+    return bits == 2 ? 1.0f : (bits == 4 ? 0.142857149243354797363281250f : 0.007874015718698501586914062500f);
+}
+
+// Philox4x32-10 (Salmon et al., SC'11): 10 rounds of two 32x32->64 multiplies and xors.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4])
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// 16-bit draw of element j from the four output words of the call that covers j>>3.
+__device__ __forceinline__ uint32_t draw16(const uint32_t out[4], int j_low3)
+{
+    const uint32_t w = out[j_low3 >> 1];
+    return (j_low3 & 1) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+// Stochastic rounding of one value (eq. (3) with max-norm a, inv = s/a): returns the signed code.
+__device__ __forceinline__ int quantise_value(float x, float inv, float s_f, uint32_t r16)
+{
+    const float u = fabsf(x) * inv;
+    float l, f;
+    if (!(u < s_f)) { l = s_f; f = 0.0f; }
+    else { l = floorf(u); f = u - l; }
+    const float xi = (float)r16 * (1.0f / 65536.0f);
+    const int mag = (int)l + ((xi < f) ? 1 : 0);
+    return (x < 0.0f) ? -mag : mag;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace conef

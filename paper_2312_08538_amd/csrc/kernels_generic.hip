@@ -1,0 +1,348 @@
+// Generic kernel family: correct for every layout the plan accepts (any cols, any block
+// that is a multiple of 32/bits, any rank <= 32, fp32 or bf16 gradients).  One element per
+// lane and per access; the shape-specialised families replace it where their conditions hold.
+//
+// All reductions run in a fixed order (no floating-point atomics), so results are
+// reproducible from run to run.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace conef {
+
+namespace {
+
+// p_j = fma(d_blk, q_j, g_j): Algorithm 2 line 5 with the decode of eq. (3) fused in.
+__device__ __forceinline__ float form_p(const MatDesc &d, const void *grads, const uint32_t *codes,
+                                        const float *scales, int dtype, int bits, int block, int64_t j)
+{
+    const int W = 32 / bits;
+    const uint32_t w = codes[d.word_off + j / W];
+    const int q = code_field(w, (int)(j % W), bits);
+    const float step = scales[d.scale_off + j / block] * inv_levels(bits);
+    return __builtin_fmaf(step, (float)q, load_grad(grads, dtype, d.grad_off + j));
+}
+
+// ---------------------------------------------------------------- pass 1: P = p * Q
+// One wave per row; lanes stride along the row; wave-level tree sum.
+template <int RP>
+__global__ __launch_bounds__(256) void k_pass_p_generic(DevicePlan dp, const void *grads, const uint32_t *codes,
+                                                        const float *scales, const float *Q, float *P)
+{
+    const WorkItem it = dp.p_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)it.a + (threadIdx.x >> 6);
+    if (row >= d.n) return;
+    const int r = dp.rank;
+    double acc[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) acc[c] = 0.0;
+    for (int64_t k = lane; k < d.m; k += 64) {
+        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, row * d.m + k);
+        const float *qrow = Q + d.q_off + k * r;
+#pragma unroll
+        for (int c = 0; c < RP; ++c)
+            if (c < r) acc[c] = __builtin_fma(pv, (double)qrow[c], acc[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < RP; ++c) acc[c] = wave_sum(acc[c]);
+    if (lane == 0) {
+#pragma unroll
+        for (int c = 0; c < RP; ++c)
+            if (c < r) P[d.p_off + row * r + c] = (float)acc[c];
+    }
+}
+
+// ---------------------------------------------------------------- orthonormalisation
+// Cholesky-QR in fp64: G = P^T P from fixed-order partial sums, G = R^T R, P^ = P R^-1.
+// In exact arithmetic this is the thin-QR factor with positive diagonal of R, the same
+// matrix Gram-Schmidt produces.
+__global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float *P, double *ws_d)
+{
+    const WorkItem it = dp.gram_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    __shared__ float tile[kGramRows * kMaxRank];
+    const int64_t row0 = (int64_t)it.a * kGramRows;
+    const int rows = (int)((d.n - row0 < kGramRows) ? d.n - row0 : kGramRows);
+    const float *src = P + d.p_off + row0 * r;
+    for (int e = threadIdx.x; e < rows * r; e += 256) tile[e] = src[e];
+    __syncthreads();
+    double *out = ws_d + d.gram_off + (int64_t)it.a * r * r;
+    for (int e = threadIdx.x; e < r * r; e += 256) {
+        const int a = e / r, b = e % r;
+        double s = 0.0;
+        for (int i = 0; i < rows; ++i) s += (double)tile[i * r + a] * (double)tile[i * r + b];
+        out[e] = s;
+    }
+}
+
+// One wave per matrix: sum the partial Gram matrices, factor, invert the triangle.
+// A column whose squared norm after projection is not above 1e-12 of its squared norm is
+// linearly dependent on the earlier ones: its P^ column is set to zero.
+__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws_d)
+{
+    const MatDesc d = dp.mats[blockIdx.x];
+    const int r = dp.rank;
+    const int lane = threadIdx.x;
+    __shared__ double G[kMaxRank * kMaxRank];
+    __shared__ double R[kMaxRank * kMaxRank];
+    __shared__ int dead[kMaxRank];
+    for (int e = lane; e < r * r; e += 64) {
+        double s = 0.0;
+        const double *src = ws_d + d.gram_off + e;
+        for (int t = 0; t < d.n_gram_tiles; ++t) s += src[(int64_t)t * r * r];
+        G[e] = s;
+        R[e] = 0.0;
+    }
+    __syncthreads();
+    for (int c = 0; c < r; ++c) {
+        // diagonal entry (every lane computes the same value)
+        double dd = G[c * r + c];
+        for (int k = 0; k < c; ++k) dd -= R[k * r + c] * R[k * r + c];
+        const bool is_dead = !(dd > 1e-12 * G[c * r + c]);
+        const double rcc = is_dead ? 1.0 : sqrt(dd);
+        if (lane == c) { R[c * r + c] = rcc; dead[c] = is_dead ? 1 : 0; }
+        if (lane > c && lane < r) {
+            double v = G[c * r + lane];
+            for (int k = 0; k < c; ++k) v -= R[k * r + c] * R[k * r + lane];
+            R[c * r + lane] = is_dead ? 0.0 : v / rcc;
+        }
+        __syncthreads();
+    }
+    // inverse of the upper triangle, one column per lane, by back substitution
+    double *rinv = ws_d + d.rinv_off;
+    if (lane < r) {
+        const int j = lane;
+        double col[kMaxRank];
+#pragma unroll
+        for (int i = 0; i < kMaxRank; ++i) col[i] = 0.0;
+        if (!dead[j]) {
+#pragma unroll
+            for (int i = kMaxRank - 1; i >= 0; --i) {
+                if (i > j || i >= r) continue;
+                if (i == j) { col[i] = 1.0 / R[j * r + j]; continue; }
+                double s = 0.0;
+#pragma unroll
+                for (int k = 0; k < kMaxRank; ++k)
+                    if (k > i && k <= j) s += R[i * r + k] * col[k];
+                col[i] = -s / R[i * r + i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kMaxRank; ++i)
+            if (i < r) rinv[i * r + j] = col[i];
+    }
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws_d)
+{
+    const WorkItem it = dp.apply_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    __shared__ double rinv[kMaxRank * kMaxRank];
+    for (int e = threadIdx.x; e < r * r; e += 256) rinv[e] = ws_d[d.rinv_off + e];
+    __syncthreads();
+    const int64_t row = (int64_t)it.a + threadIdx.x;
+    if (row >= d.n) return;
+    float *prow = P + d.p_off + row * r;
+    float in[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) in[c] = (c < r) ? prow[c] : 0.0f;
+#pragma unroll
+    for (int c = 0; c < RP; ++c) {
+        if (c < r) {
+            double s = 0.0;
+#pragma unroll
+            for (int k = 0; k < RP; ++k)
+                if (k <= c) s += (double)in[k] * rinv[k * r + c];
+            prow[c] = (float)s;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- pass 2: Q+ = p^T * P^
+// One thread per column, one workgroup per (column tile, row tile); partial sums per row
+// tile go to the workspace and are added in row-tile order by k_q_reduce.
+template <int RP>
+__global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, const void *grads, const uint32_t *codes,
+                                                              const float *scales, const float *Phat, double *ws_q)
+{
+    const WorkItem it = dp.q_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int64_t k = (int64_t)it.a * kGenQCols + threadIdx.x;
+    const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
+    const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
+    if (k >= d.m) return;
+    double acc[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) acc[c] = 0.0;
+    for (int64_t i = row0; i < row1; ++i) {
+        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, i * d.m + k);
+        const float *prow = Phat + d.p_off + i * r;
+#pragma unroll
+        for (int c = 0; c < RP; ++c)
+            if (c < r) acc[c] = __builtin_fma(pv, (double)prow[c], acc[c]);
+    }
+    double *out = ws_q + d.qpart_off + ((int64_t)it.b * d.m + k) * r;
+#pragma unroll
+    for (int c = 0; c < RP; ++c)
+        if (c < r) out[c] = acc[c];
+}
+
+__global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws_q, float *Qout)
+{
+    const WorkItem it = dp.qred_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t e = (int64_t)it.a + threadIdx.x;
+    const int64_t len = d.m * dp.rank;
+    if (e >= len) return;
+    const double *src = ws_q + d.qpart_off + e;
+    double s = 0.0;
+    for (int t = 0; t < d.n_q_tiles; ++t) s += src[(int64_t)t * len];
+    Qout[d.q_off + e] = (float)s;
+}
+
+// ---------------------------------------------------------------- pass 3: err <- C(p - P^ Q+^T)
+// One wave per scale block; two sweeps over the block (max-norm, then rounding) so that any
+// block length fits.  The residual is the fp32 fma chain over c = 0..r-1.
+template <int RP>
+__device__ __forceinline__ float residual_at(const DevicePlan &dp, const MatDesc &d, const void *grads,
+                                             const uint32_t *codes, const float *scales, const float *Phat,
+                                             const float *Qn, int64_t j)
+{
+    const int r = dp.rank;
+    const int64_t i = j / d.m, k = j - i * d.m;
+    const float pv = form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, j);
+    const float *prow = Phat + d.p_off + i * r;
+    const float *qrow = Qn + d.q_off + k * r;
+    float acc = 0.0f;
+#pragma unroll
+    for (int c = 0; c < RP; ++c)
+        if (c < r) acc = __builtin_fmaf(prow[c], qrow[c], acc);
+    return pv - acc;
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const void *grads, uint32_t *codes,
+                                                          float *scales, const float *Phat, const float *Qn,
+                                                          uint32_t step_lo, uint32_t step_hi)
+{
+    const WorkItem it = dp.err_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bits = dp.bits, W = 32 / bits, B = dp.block;
+    const float s_f = (float)((1 << (bits - 1)) - 1);
+    for (int t = 0; t < 16; ++t) {
+        const int64_t blk = (int64_t)it.a * 64 + wave + 4 * t;
+        if (blk >= d.nblk) break;                                   // uniform per wave
+        const int64_t j0 = blk * B;
+        const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
+        float a = 0.0f;
+        for (int e = lane; e < cnt; e += 64)
+            a = fmaxf(a, fabsf(residual_at<RP>(dp, d, grads, codes, scales, Phat, Qn, j0 + e)));
+        a = wave_max(a);
+        // the old scale of this block is read by nobody else; codes are overwritten word by word below
+        const float inv = (a > 0.0f) ? s_f / a : 0.0f;
+        const int sweeps = (cnt + 63) / 64;
+        for (int sw = 0; sw < sweeps; ++sw) {
+            const int e = sw * 64 + lane;
+            uint32_t field = 0;
+            if (e < cnt && a > 0.0f) {
+                const int64_t j = j0 + e;
+                const float x = residual_at<RP>(dp, d, grads, codes, scales, Phat, Qn, j);
+                uint32_t out[4];
+                philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                const int q = quantise_value(x, inv, s_f, draw16(out, (int)(j & 7)));
+                field = ((uint32_t)q & ((1u << bits) - 1u)) << (bits * (e % W));
+            }
+            // every lane of the wave has computed its residual before any word of the sweep is stored
+            for (int o = 1; o < W; o <<= 1) field |= __shfl_xor(field, o, 64);
+            if ((lane % W) == 0 && e < cnt) codes[d.word_off + (j0 + e) / W] = field;
+        }
+        if (lane == 0) scales[d.scale_off + blk] = a;
+    }
+}
+
+// ---------------------------------------------------------------- helpers
+__global__ __launch_bounds__(256) void k_decode(DevicePlan dp, const uint32_t *codes, const float *scales, float *e_out)
+{
+    const WorkItem it = dp.elem_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int W = 32 / dp.bits;
+    for (int t = 0; t < 4; ++t) {
+        const int64_t j = ((int64_t)it.a << 10) + t * 256 + threadIdx.x;
+        if (j >= d.N) return;
+        const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
+        e_out[d.grad_off + j] = scales[d.scale_off + j / dp.block] * inv_levels(dp.bits) * (float)q;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero(uint32_t *a, size_t na, uint32_t *b, size_t nb)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < na; i += stride) a[i] = 0u;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nb; i += stride) b[i] = 0u;
+}
+
+}  // namespace
+
+#define CONEF_DISPATCH_RP(KERNEL, GRID, BLOCK, ST, ...)                                          \
+    do {                                                                                          \
+        switch (dp.rpad) {                                                                        \
+        case 4: hipLaunchKernelGGL(KERNEL<4>, GRID, BLOCK, 0, ST, __VA_ARGS__); break;            \
+        case 8: hipLaunchKernelGGL(KERNEL<8>, GRID, BLOCK, 0, ST, __VA_ARGS__); break;            \
+        case 16: hipLaunchKernelGGL(KERNEL<16>, GRID, BLOCK, 0, ST, __VA_ARGS__); break;          \
+        default: hipLaunchKernelGGL(KERNEL<32>, GRID, BLOCK, 0, ST, __VA_ARGS__); break;          \
+        }                                                                                         \
+    } while (0)
+
+hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                         const float *Q, float *P, hipStream_t st)
+{
+    if (dp.n_p > 0) CONEF_DISPATCH_RP(k_pass_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, codes, scales, Q, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws_d);
+    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(64), 0, st, dp, ws_d);
+    CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws_d);
+    return hipGetLastError();
+}
+
+hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                         const float *Phat, float *Qout, double *ws_q, hipStream_t st)
+{
+    CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws_q);
+    hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws_q, Qout);
+    return hipGetLastError();
+}
+
+hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
+                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st)
+{
+    CONEF_DISPATCH_RP(k_pass_err_generic, dim3(dp.n_err), dim3(256), st, dp, grads, codes, scales, Phat, Qn,
+                      (uint32_t)step, (uint32_t)(step >> 32));
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_decode, dim3(dp.n_elem), dim3(256), 0, st, dp, codes, scales, e_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,
+                        hipStream_t st)
+{
+    (void)dp;
+    hipLaunchKernelGGL(k_zero, dim3(1024), dim3(256), 0, st, codes, n_words, reinterpret_cast<uint32_t *>(scales),
+                       n_scales);
+    return hipGetLastError();
+}
+
+}  // namespace conef

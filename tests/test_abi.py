@@ -1,0 +1,102 @@
+"""CPU-side tests of the C ABI: the library loads, exports every function the header declares,
+validates its arguments, and plans buffer layouts as documented.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2312_08538_amd import binding as B
+from paper_2312_08538_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_function():
+    header = open(os.path.join(ROOT, "include", "conef.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(conef_[a-z_]+)\s*\(", header)))
+    assert declared, "no declarations found"
+    L = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), f"{name} is declared in conef.h but not exported"
+    assert sorted(B.EXPORTS) == declared          # the binding covers the same set
+
+
+def test_init_rejects_bad_arguments():
+    ok = [(64, 64)]
+    bad = [
+        (ok, 0, 4, 128), (ok, 33, 4, 128), (ok, 65, 4, 128),      # rank
+        (ok, 4, 3, 128), (ok, 4, 16, 128), (ok, 4, 0, 128),       # bits
+        (ok, 4, 4, 0), (ok, 4, 4, 12), (ok, 4, 4, -8), (ok, 4, 8, 6), (ok, 4, 2, 8), (ok, 4, 4, 1 << 21),  # block
+        ([(0, 64)], 1, 4, 128), ([(64, -1)], 1, 4, 128),          # dims
+        ([(3, 64)], 4, 4, 128), ([(64, 2)], 4, 4, 128),           # rank > min(rows, cols)
+        ([(1 << 20, 1 << 15)], 4, 4, 128),                        # rows*cols >= 2^35
+        ([], 4, 4, 128),
+    ]
+    for layout, rank, bits, block in bad:
+        with pytest.raises(B.ConefError) as e:
+            B.conef_init(layout, rank, bits, block, B.F32, 0)
+        assert e.value.code == B.EINVAL
+    with pytest.raises(B.ConefError):
+        B.conef_init(ok, 4, 4, 128, 7, 0)                          # dtype
+    assert B.lib().conef_init(None, None, 1, 4, 4, 128, 0, 0) == B.EINVAL
+    ctx = ctypes.c_void_p()
+    assert B.lib().conef_init(ctypes.byref(ctx), None, 1, 4, 4, 128, 0, 0) == B.EINVAL
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
+    ctx = B.conef_init([(64, 64)], 4, 4, 128, B.F32, 0)
+    L = B.lib()
+    assert L.conef_step(ctx, 0, 0, 0, 0, 0, 0, 0, 0, 0) == B.EINVAL
+    assert L.conef_step(ctx, 256, 256, 256, 0, 256, 256, 256, 0, 0) == B.EINVAL       # null Q_state
+    assert L.conef_step(ctx, 260, 256, 256, 256, 256, 256, 256, 0, 0) == B.EINVAL     # grads not 16-byte aligned
+    assert L.conef_step(ctx, 256, 256, 256, 256, 256, 256, 128, 0, 0) == B.EINVAL     # workspace not 256-byte aligned
+    assert L.conef_step_err(ctx, 256, 256, 258, 256, 256, 0, 0) == B.EINVAL           # scales not 4-byte aligned
+    assert L.conef_step(None, 256, 256, 256, 256, 256, 256, 256, 0, 0) == B.EINVAL
+    assert L.conef_reset_error(ctx, 0, 0, 0) == B.EINVAL
+    assert L.conef_decode_error(ctx, 256, 256, 0, 0) == B.EINVAL
+    assert L.conef_sizes(None, None, None, None, None, None, None) == B.EINVAL
+    assert L.conef_offsets(ctx, 1, None, None, None, None, None) == B.EINVAL
+    assert L.conef_offsets(ctx, -1, None, None, None, None, None) == B.EINVAL
+    ms = (ctypes.c_float * 4)()
+    assert L.conef_get_timing(ctx, ms) == B.ESTATE                                     # timing never switched on
+    assert B.lib().conef_strerror(B.EINVAL) == b"invalid argument"
+    B.conef_destroy(ctx)
+    B.conef_destroy(None)
+
+
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_sizes_and_offsets_follow_the_documented_layout(name):
+    w = wl.WORKLOADS[name]
+    m = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+    W = 32 // w.bits
+    ru = lambda v: (v + 63) // 64 * 64
+    g = c = s = p = q = 0
+    for l, (n, mm) in enumerate(w.layout):
+        o = m.offsets[l]
+        assert (o["grad_off"], o["word_off"], o["scale_off"], o["p_off"], o["q_off"]) == (g, c, s, p, q)
+        N = n * mm
+        g += ru(N); c += ru(-(-N // W)); s += ru(-(-N // w.block)); p += ru(n * w.rank); q += ru(mm * w.rank)
+    sz = m.sizes
+    assert (sz["grad_elems"], sz["code_words"], sz["n_scales"], sz["p_elems"], sz["q_elems"]) == (g, c, s, p, q)
+    assert sz["workspace_bytes"] % 256 == 0 and sz["workspace_bytes"] > 0
+    m.close()
+
+
+def test_state_memory_matches_the_closed_form():
+    """Compressed error vs an fp32 error vector: 1 - (b + 32/B)/32 up to padding."""
+    w = wl.WORKLOADS["lm"]
+    m = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, 0)
+    kept = 4 * (m.sizes["code_words"] + m.sizes["n_scales"])
+    saving = 1 - kept / (4 * w.elements)
+    assert abs(saving - (1 - (w.bits + 32 / w.block) / 32)) < 1e-3
+    m.close()
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libconef.so"))
+    with pytest.raises(RuntimeError):
+        B.lib()
