@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the ConEF per-worker step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|lm|translation|cnn|tiny]
+
+One "step" is one conef_step call: the whole hot path (decode + add, P = pQ, orthonormalise,
+Q+ = p^T P^, residual, stochastic quantise + pack) over every matrix of the workload, inputs
+resident in HBM.  Prints ONE JSON line: gradient GB/s processed (metric), the roofline of the
+dominant kernel from HIP events recorded on the launch stream inside the timed region, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+STAGES = ["p", "orthonormalise", "q", "err"]
+KERNEL_OF_STAGE = {"p": "pass_p (P = (g+e) Q)", "orthonormalise": "gram + cholesky + apply",
+                   "q": "pass_q (Q+ = (g+e)^T P^)", "err": "pass_err (residual + quantise + pack)"}
+
+
+def stage_bytes(w, stage: str) -> float:
+    """Algorithmic HBM bytes of one launch of a stage's main kernel over the whole workload:
+    per element the gradient (G bytes), b/8 bytes of codes and 4/B bytes of scales are read once
+    (and codes + scales written once by the err pass), plus the P and Q factors it touches."""
+    G = 4 if w.grad_dtype == 0 else 2
+    per_elem_read = G + w.bits / 8 + 4.0 / w.block
+    tot = 0.0
+    for n, m in w.layout:
+        N = n * m
+        if stage == "p":
+            tot += N * per_elem_read + (m + n) * w.rank * 4
+        elif stage == "q":
+            tot += N * per_elem_read + (n + m) * w.rank * 4
+        elif stage == "err":
+            tot += N * per_elem_read + N * (w.bits / 8 + 4.0 / w.block) + (n + m) * w.rank * 4
+        else:  # orthonormalise: read P for the Gram matrix, read + write it for the apply
+            tot += 3 * n * w.rank * 4
+    return tot
+
+
+def run_gpu(w, steps: int, warmup: int):
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+    from paper_2312_08538_amd import workloads as wl
+
+    dev = "cuda:0"
+    model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+    buf = model.alloc(dev)
+    goffs = [o["grad_off"] for o in model.offsets]
+    qoffs = [o["q_off"] for o in model.offsets]
+    # gradient sets to rotate through, so that a small workload is not served from the last-level
+    # cache left by the previous step: enough sets to exceed 512 MiB, at least 2, at most 8
+    n_sets = max(2, min(8, int(512 * 2**20 // max(1, w.grad_bytes)) + 1))
+    gsets = [buf["grads"]] + [torch.empty_like(buf["grads"]) for _ in range(n_sets - 1)]
+    for i, g in enumerate(gsets):
+        wl.device_fill_gradients(w, i, g, goffs)
+    wl.device_q0(w, buf["Q"], qoffs)
+    torch.cuda.synchronize()
+    st = model.stream_handle()
+
+    def one_step(t):
+        B.conef_step(model.ctx, gsets[t % n_sets], buf["codes"], buf["scales"], buf["Q"], buf["P"], buf["Q"],
+                     buf["ws"], t, st)
+
+    # the error state grows from step to step on iid synthetic gradients (no decay as in real
+    # training); a reset every 16 steps keeps every value finite for any K.  It is a fill kernel
+    # of the state buffers on the same stream and is part of the timed work when it happens.
+    def maybe_reset(t):
+        if t > 0 and t % 16 == 0:
+            B.conef_reset_error(model.ctx, buf["codes"], buf["scales"], st)
+
+    for t in range(warmup):
+        maybe_reset(t)
+        one_step(t)
+    torch.cuda.synchronize()
+    B.conef_set_timing(model.ctx, True)
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        maybe_reset(t)
+        one_step(t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stage_ms = B.conef_get_timing(model.ctx)
+    B.conef_set_timing(model.ctx, False)
+    finite = bool(torch.isfinite(buf["P"]).all()) and bool(torch.isfinite(buf["Q"]).all())
+    model.close()
+    del buf, gsets
+    torch.cuda.empty_cache()
+    return (t1 - t0) * 1e3 / steps, dict(zip(STAGES, stage_ms)), finite
+
+
+def run_oracle_sample(w):
+    """Times the oracle (as it stands) on a bounded sample of the workload: whole matrices in
+    layout order after the first (the first is the large embedding in the language-model
+    layouts), until about 60 M elements are covered."""
+    import numpy as np
+
+    from oracle import conef_ref as R
+    from paper_2312_08538_amd import workloads as wl
+
+    budget, picked, tot = 60e6, [], 0
+    order = list(range(1, len(w.layout))) + [0] if len(w.layout) > 1 else [0]
+    for l in order:
+        n, m = w.layout[l]
+        if picked and tot + n * m > budget:
+            continue
+        picked.append(l)
+        tot += n * m
+        if tot >= budget:
+            break
+    states, grads = [], []
+    for l in picked:
+        n, m = w.layout[l]
+        grads.append(wl.host_gradient(w, 0, l))
+        states.append(R.MatState.fresh(n, m, w.bits, w.block, wl.host_q0(w, l)))
+    R.lib()
+    t0 = time.perf_counter()
+    for l, g, stt in zip(picked, grads, states):
+        R.step_matrix(g, stt, w.rank, w.bits, w.block, w.lib_seed, l, 0)
+    dt = time.perf_counter() - t0
+    G = 4 if w.grad_dtype == 0 else 2
+    return tot * G / dt / 1e9, R.num_threads(), f"{len(picked)} whole matrices of the workload ({tot} elements, " \
+                                                 f"{100.0 * tot / w.elements:.1f} % of it), one step from zero error"
+
+
+def load_traffic(workload: str, stage: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if
+    one exists for this workload (profiles/hbm_traffic.json), else None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        return json.load(open(path)).get(workload, {}).get(stage)
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is one worker's share of the method on ONE GPU; it has no collectives "
+              "and no sharding, so --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if a.steps < 1 or a.steps > 64:
+        print("bench.py: --steps must be in 1..64 (one event set per timed step is kept)", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2312_08538_amd import workloads as wl
+
+    w = wl.WORKLOADS[a.workload]
+    ms, stage_ms, finite = run_gpu(w, a.steps, a.warmup)
+    if not finite:
+        print("bench.py: non-finite factors after the timed run", file=sys.stderr)
+        sys.exit(1)
+    value = w.grad_bytes / (ms * 1e-3) / 1e9
+    dom = max(("p", "q", "err"), key=lambda s: stage_ms[s])
+    dom_bytes = stage_bytes(w, dom)
+    achieved = dom_bytes / (stage_ms[dom] * 1e-3) / 1e9
+    out = {
+        "metric": "ConEF step throughput: gradient GB/s processed",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.grad_dtype == 0 else "bf16->f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "matrices": len(w.layout), "elements": w.elements,
+                   "grad_dtype": "f32" if w.grad_dtype == 0 else "bf16", "rank": w.rank, "bits": w.bits,
+                   "block": w.block, "dist": w.dist},
+        "model_hbm": {"bytes_per_step": w.model_bytes(),
+                      "GB/s": round(w.model_bytes() / (ms * 1e-3) / 1e9, 1),
+                      "frac_of_peak": round(w.model_bytes() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "roofline": {"kernel": KERNEL_OF_STAGE[dom], "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "bytes_per_launch": int(dom_bytes), "ms_per_launch": round(stage_ms[dom], 4),
+                     "traffic": load_traffic(w.name, dom)},
+    }
+    if not a.no_extra:
+        extra = {}
+        for name in ("cnn", "lm", "translation", "large"):
+            if name == w.name:
+                continue
+            ww = wl.WORKLOADS[name]
+            ms2, st2, _ = run_gpu(ww, 10, 3)
+            extra[name] = {"ms_per_step": round(ms2, 4), "grad_GB/s": round(ww.grad_bytes / (ms2 * 1e-3) / 1e9, 2),
+                           "model_hbm_frac": round(ww.model_bytes() / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "stage_ms": {k: round(v, 4) for k, v in st2.items()}}
+        out["other_workloads"] = extra
+    if not a.no_cpu_baseline:
+        v, cores, sample = run_oracle_sample(w)
+        out["cpu_baseline"] = {"value": round(v, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+                               "sample": sample}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -106,10 +106,13 @@ int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, vo
 int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *err_scales,
                        float *e_out, void *hip_stream);
 
-/* Milliseconds between the first and the last kernel of the most recent conef_step /
- * stage call on this context, per stage, measured with HIP events recorded on the caller's
- * stream when timing was switched on with conef_set_timing(ctx, 1).  conef_get_timing
- * synchronises on the recorded events.  ms[4] = {p, orthonormalise, q, err}. */
+/* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
+ * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
+ * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to
+ * 64 conef_step calls are kept (a ring); stage calls made on their own share one slot.
+ * conef_get_timing waits for the recorded events and returns the mean duration per stage in
+ * milliseconds over the kept calls: ms[4] = {p, orthonormalise, q, err}.  Switching timing on
+ * again clears the ring.  Errors: CONEF_ESTATE if timing is off, CONEF_EHIP. */
 int conef_set_timing(conef_ctx *ctx, int on);
 int conef_get_timing(conef_ctx *ctx, float ms[4]);
 

@@ -18,9 +18,12 @@ struct conef_ctx {
     bool uploaded = false;
     int device = -1;
     std::vector<void *> device_allocs;
+    // stage timing: a ring of kTimingSlots event sets (8 events: begin/end of the 4 stages)
     bool timing = false;
-    bool timing_valid[4] = {false, false, false, false};
-    hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> ev;
+    std::vector<unsigned char> ev_valid;      // per slot and stage
+    int slot = 0;
+    uint64_t steps_timed = 0;
 };
 
 namespace {
@@ -63,8 +66,6 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_elem = (int)pl.elem_items.size();
     d.rank = pl.rank; d.rpad = pl.rpad; d.bits = pl.bits; d.block = pl.block; d.dtype = pl.dtype;
     d.seed_lo = (uint32_t)pl.seed; d.seed_hi = (uint32_t)(pl.seed >> 32);
-    for (auto &e : ctx->ev)
-        if (hipEventCreate(&e) != hipSuccess) return CONEF_EHIP;
     ctx->uploaded = true;
     return CONEF_OK;
 }
@@ -73,18 +74,19 @@ inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintp
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? CONEF_OK : CONEF_EHIP; }
 
+constexpr int kTimingSlots = 64;
+
 // stage index: 0 p, 1 orthonormalise, 2 q, 3 err
-struct StageTimer {
-    conef_ctx *ctx; int stage; hipStream_t st;
-    StageTimer(conef_ctx *c, int s, hipStream_t stream) : ctx(c), stage(s), st(stream)
-    {
-        if (ctx->timing) (void)hipEventRecord(ctx->ev[2 * stage], st);
+Span stage_span(conef_ctx *ctx, int stage)
+{
+    Span sp;
+    if (ctx->timing && !ctx->ev.empty()) {
+        sp.begin = ctx->ev[(size_t)ctx->slot * 8 + 2 * stage];
+        sp.end = ctx->ev[(size_t)ctx->slot * 8 + 2 * stage + 1];
+        ctx->ev_valid[(size_t)ctx->slot * 4 + stage] = 1;
     }
-    ~StageTimer()
-    {
-        if (ctx->timing) { (void)hipEventRecord(ctx->ev[2 * stage + 1], st); ctx->timing_valid[stage] = true; }
-    }
-};
+    return sp;
+}
 
 double *ws_doubles(const conef_ctx *, void *ws) { return static_cast<double *>(ws); }
 double *ws_qpart(const conef_ctx *ctx, void *ws) { return static_cast<double *>(ws) + ctx->plan.ws_doubles; }
@@ -150,8 +152,7 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    StageTimer t(ctx, 0, st);
-    return hip_rc(launch_pass_p(ctx->dev, grads, err_codes, err_scales, Q_state, P_raw_out, st));
+    return hip_rc(launch_pass_p(ctx->dev, grads, err_codes, err_scales, Q_state, P_raw_out, st, stage_span(ctx, 0)));
 }
 
 int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
@@ -161,8 +162,7 @@ int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    StageTimer t(ctx, 1, st);
-    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st));
+    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st, stage_span(ctx, 1)));
 }
 
 int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
@@ -175,8 +175,8 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    StageTimer t(ctx, 2, st);
-    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_qpart(ctx, workspace), st));
+    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_qpart(ctx, workspace), st,
+                                stage_span(ctx, 2)));
 }
 
 int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
@@ -189,8 +189,7 @@ int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    StageTimer t(ctx, 3, st);
-    return hip_rc(launch_pass_err(ctx->dev, grads, err_codes, err_scales, P_hat, Q_new, step, st));
+    return hip_rc(launch_pass_err(ctx->dev, grads, err_codes, err_scales, P_hat, Q_new, step, st, stage_span(ctx, 3)));
 }
 
 int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
@@ -198,6 +197,7 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
                void *hip_stream)
 {
     int rc;
+    if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_out, workspace, hip_stream))) return rc;
     /* exchange point 1: mean of P over the workers -- identity for one worker */
     if ((rc = conef_orthonormalise(ctx, P_out, workspace, hip_stream))) return rc;
@@ -229,20 +229,40 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
 int conef_set_timing(conef_ctx *ctx, int on)
 {
     if (!ctx) return CONEF_EINVAL;
+    if (on && ctx->ev.empty()) {
+        try {
+            ctx->ev.assign((size_t)kTimingSlots * 8, nullptr);
+            ctx->ev_valid.assign((size_t)kTimingSlots * 4, 0);
+        } catch (const std::bad_alloc &) {
+            return CONEF_ENOMEM;
+        }
+        for (auto &e : ctx->ev)
+            if (hipEventCreate(&e) != hipSuccess) return CONEF_EHIP;
+    }
     ctx->timing = on != 0;
-    for (bool &v : ctx->timing_valid) v = false;
+    ctx->slot = 0;
+    ctx->steps_timed = 0;
+    for (auto &v : ctx->ev_valid) v = 0;
     return CONEF_OK;
 }
 
 int conef_get_timing(conef_ctx *ctx, float ms[4])
 {
     if (!ctx || !ms) return CONEF_EINVAL;
-    if (!ctx->timing || !ctx->uploaded) return CONEF_ESTATE;
+    if (!ctx->timing) return CONEF_ESTATE;
     for (int s = 0; s < 4; ++s) {
-        ms[s] = 0.0f;
-        if (!ctx->timing_valid[s]) continue;
-        if (hipEventSynchronize(ctx->ev[2 * s + 1]) != hipSuccess) return CONEF_EHIP;
-        if (hipEventElapsedTime(&ms[s], ctx->ev[2 * s], ctx->ev[2 * s + 1]) != hipSuccess) return CONEF_EHIP;
+        double sum = 0.0;
+        int cnt = 0;
+        for (int k = 0; k < kTimingSlots; ++k) {
+            if (!ctx->ev_valid[(size_t)k * 4 + s]) continue;
+            hipEvent_t a = ctx->ev[(size_t)k * 8 + 2 * s], b = ctx->ev[(size_t)k * 8 + 2 * s + 1];
+            float t = 0.0f;
+            if (hipEventSynchronize(b) != hipSuccess) return CONEF_EHIP;
+            if (hipEventElapsedTime(&t, a, b) != hipSuccess) return CONEF_EHIP;
+            sum += t;
+            ++cnt;
+        }
+        ms[s] = cnt ? (float)(sum / cnt) : 0.0f;
     }
     return CONEF_OK;
 }
@@ -250,10 +270,8 @@ int conef_get_timing(conef_ctx *ctx, float ms[4])
 void conef_destroy(conef_ctx *ctx)
 {
     if (!ctx) return;
-    if (ctx->uploaded) {
-        for (auto &e : ctx->ev)
-            if (e) (void)hipEventDestroy(e);
-    }
+    for (auto &e : ctx->ev)
+        if (e) (void)hipEventDestroy(e);
     for (void *p : ctx->device_allocs) (void)hipFree(p);
     delete ctx;
 }

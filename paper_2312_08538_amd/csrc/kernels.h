@@ -17,14 +17,19 @@ struct DevicePlan {
     uint32_t seed_lo = 0, seed_hi = 0;
 };
 
+// Optional pair of events recorded immediately before and after a stage's main kernel.
+struct Span {
+    hipEvent_t begin = nullptr, end = nullptr;
+};
+
 // Each launcher enqueues on `st` and returns hipGetLastError().
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Q, float *P, hipStream_t st);
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st);
+                         const float *Q, float *P, hipStream_t st, Span span = Span());
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st, Span span = Span());
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws_q, hipStream_t st);
+                         const float *Phat, float *Qout, double *ws_q, hipStream_t st, Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
-                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st);
+                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span = Span());
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);
 hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,

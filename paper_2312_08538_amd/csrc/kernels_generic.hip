@@ -300,33 +300,42 @@ __global__ __launch_bounds__(256) void k_zero(uint32_t *a, size_t na, uint32_t *
     } while (0)
 
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Q, float *P, hipStream_t st)
+                         const float *Q, float *P, hipStream_t st, Span span)
 {
-    if (dp.n_p > 0) CONEF_DISPATCH_RP(k_pass_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, codes, scales, Q, P);
+    if (span.begin) (void)hipEventRecord(span.begin, st);
+    CONEF_DISPATCH_RP(k_pass_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, codes, scales, Q, P);
+    if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
 
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st)
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st, Span span)
 {
+    // the span covers all three small kernels of this stage
+    if (span.begin) (void)hipEventRecord(span.begin, st);
     hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws_d);
     hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(64), 0, st, dp, ws_d);
     CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws_d);
+    if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
 
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws_q, hipStream_t st)
+                         const float *Phat, float *Qout, double *ws_q, hipStream_t st, Span span)
 {
+    if (span.begin) (void)hipEventRecord(span.begin, st);
     CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws_q);
+    if (span.end) (void)hipEventRecord(span.end, st);
     hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws_q, Qout);
     return hipGetLastError();
 }
 
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
-                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st)
+                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
 {
+    if (span.begin) (void)hipEventRecord(span.begin, st);
     CONEF_DISPATCH_RP(k_pass_err_generic, dim3(dp.n_err), dim3(256), st, dp, grads, codes, scales, Phat, Qn,
                       (uint32_t)step, (uint32_t)(step >> 32));
+    if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
 
