@@ -244,15 +244,17 @@ void ref_quantise(const float *x, int64_t N, int bits, int block,
         for (int64_t j = j0; j < j1; ++j) { float ax = fabsf(x[j]); if (ax > a) a = ax; }
         scales[blk] = a;
         if (!(a > 0.0f)) continue;                         /* all-zero block: codes 0, scale 0 */
-        float inv = (float)s / a;                          /* IEEE fp32 division */
+        /* eq. (3): |x|/a*s lies in [l, l+1] and is rounded up with probability |x|/a*s - l.
+         * Taken in 16.16 fixed point: U = floor(|x| * (s/a) * 2^16) (fp32 product, truncated),
+         * a uniform 16-bit draw is added and the integer part kept, so the value is rounded up
+         * exactly when the fraction of U exceeds 2^16 - 1 - draw, i.e. with probability
+         * (U mod 2^16) / 2^16.  For finite input U <= s * 2^16 (the product exceeds it by less
+         * than 1/2), so the magnitude never exceeds s.  Non-finite input is outside the contract. */
+        float inv16 = ((float)s / a) * 65536.0f;           /* IEEE fp32 division, exact scaling */
         for (int64_t j = j0; j < j1; ++j) {
-            float u = fabsf(x[j]) * inv;                   /* |x|/a * s, in [0, s] up to rounding */
-            float l, f;
-            if (!(u < (float)s)) { l = (float)s; f = 0.0f; }
-            else { l = floorf(u); f = u - l; }             /* exact: f = frac(u) */
+            uint32_t U = (uint32_t)(fabsf(x[j]) * inv16);
             uint32_t r16 = draw ? draw[j] : ref_rand16(seed, mat, step, (uint64_t)j);
-            float xi = (float)r16 * (1.0f / 65536.0f);     /* uniform on {0, 2^-16, ..., 1-2^-16} */
-            int32_t mag = (int32_t)l + ((xi < f) ? 1 : 0); /* up with probability ~ f */
+            int32_t mag = (int32_t)((U + r16) >> 16);
             int32_t q = (x[j] < 0.0f) ? -mag : mag;
             uint32_t field = (uint32_t)q & ((1u << bits) - 1u);
             codes[j / W] |= field << (bits * (int)(j % W));

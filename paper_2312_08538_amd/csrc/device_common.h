@@ -54,16 +54,15 @@ __device__ __forceinline__ uint32_t draw16(const uint32_t out[4], int j_low3)
     return (j_low3 & 1) ? (w >> 16) : (w & 0xFFFFu);
 }
 
-// Stochastic rounding of one value (eq. (3) with max-norm a, inv = s/a): returns the signed code.
-__device__ __forceinline__ int quantise_value(float x, float inv, float s_f, uint32_t r16)
+// Stochastic rounding of one value (eq. (3) with max-norm a; inv16 = (s/a) * 2^16) in 16.16
+// fixed point: the truncated product plus a uniform 16-bit draw, integer part kept.  Returns
+// the b-bit two's-complement field (not yet shifted into place).
+__device__ __forceinline__ uint32_t quantise_field(float x, float inv16, uint32_t r16, uint32_t mask)
 {
-    const float u = fabsf(x) * inv;
-    float l, f;
-    if (!(u < s_f)) { l = s_f; f = 0.0f; }
-    else { l = floorf(u); f = u - l; }
-    const float xi = (float)r16 * (1.0f / 65536.0f);
-    const int mag = (int)l + ((xi < f) ? 1 : 0);
-    return (x < 0.0f) ? -mag : mag;
+    const uint32_t U = (uint32_t)(fabsf(x) * inv16);
+    const uint32_t mag = (U + r16) >> 16;
+    const uint32_t sgn = (uint32_t)((int32_t)__float_as_uint(x) >> 31);     // 0 or 0xFFFFFFFF
+    return ((mag ^ sgn) - sgn) & mask;      // -mag for negative x; -0.0f gives mag 0 -> field 0
 }
 
 __device__ __forceinline__ float wave_max(float v)

@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
             a = fmaxf(a, fabsf(residual_at<RP>(dp, d, grads, codes, scales, Phat, Qn, j0 + e)));
         a = wave_max(a);
         // the old scale of this block is read by nobody else; codes are overwritten word by word below
-        const float inv = (a > 0.0f) ? s_f / a : 0.0f;
+        const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
         const int sweeps = (cnt + 63) / 64;
         for (int sw = 0; sw < sweeps; ++sw) {
             const int e = sw * 64 + lane;
@@ -255,8 +255,7 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
                 const float x = residual_at<RP>(dp, d, grads, codes, scales, Phat, Qn, j);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
-                const int q = quantise_value(x, inv, s_f, draw16(out, (int)(j & 7)));
-                field = ((uint32_t)q & ((1u << bits) - 1u)) << (bits * (e % W));
+                field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
             }
             // every lane of the wave has computed its residual before any word of the sweep is stored
             for (int o = 1; o < W; o <<= 1) field |= __shfl_xor(field, o, 64);
