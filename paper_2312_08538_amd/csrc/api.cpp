@@ -50,20 +50,30 @@ int ensure_uploaded(conef_ctx *ctx)
     int rc;
     if ((rc = upload(ctx, pl.mats, &d.mats))) return rc;
     if ((rc = upload(ctx, pl.p_items, &d.p_items))) return rc;
+    if ((rc = upload(ctx, pl.q_items, &d.q_items))) return rc;
+    if ((rc = upload(ctx, pl.err_items, &d.err_items))) return rc;
+    if ((rc = upload(ctx, pl.p_f_items, &d.p_f_items))) return rc;
+    if ((rc = upload(ctx, pl.q_f_items, &d.q_f_items))) return rc;
+    if ((rc = upload(ctx, pl.err_f_items, &d.err_f_items))) return rc;
+    if ((rc = upload(ctx, pl.pred_items, &d.pred_items))) return rc;
     if ((rc = upload(ctx, pl.gram_items, &d.gram_items))) return rc;
     if ((rc = upload(ctx, pl.apply_items, &d.apply_items))) return rc;
-    if ((rc = upload(ctx, pl.q_items, &d.q_items))) return rc;
     if ((rc = upload(ctx, pl.qred_items, &d.qred_items))) return rc;
-    if ((rc = upload(ctx, pl.err_items, &d.err_items))) return rc;
     if ((rc = upload(ctx, pl.elem_items, &d.elem_items))) return rc;
     d.n_mats = (int)pl.mats.size();
     d.n_p = (int)pl.p_items.size();
+    d.n_q = (int)pl.q_items.size();
+    d.n_err = (int)pl.err_items.size();
+    d.n_p_f = (int)pl.p_f_items.size();
+    d.n_q_f = (int)pl.q_f_items.size();
+    d.n_err_f = (int)pl.err_f_items.size();
+    d.n_pred = (int)pl.pred_items.size();
     d.n_gram = (int)pl.gram_items.size();
     d.n_apply = (int)pl.apply_items.size();
-    d.n_q = (int)pl.q_items.size();
     d.n_qred = (int)pl.qred_items.size();
-    d.n_err = (int)pl.err_items.size();
     d.n_elem = (int)pl.elem_items.size();
+    d.qd_off = (long long)pl.qd_off;
+    d.q_elems = (long long)pl.q_elems;
     d.rank = pl.rank; d.rpad = pl.rpad; d.bits = pl.bits; d.block = pl.block; d.dtype = pl.dtype;
     d.seed_lo = (uint32_t)pl.seed; d.seed_hi = (uint32_t)(pl.seed >> 32);
     ctx->uploaded = true;
@@ -89,7 +99,6 @@ Span stage_span(conef_ctx *ctx, int stage)
 }
 
 double *ws_doubles(const conef_ctx *, void *ws) { return static_cast<double *>(ws); }
-double *ws_qpart(const conef_ctx *ctx, void *ws) { return static_cast<double *>(ws) + ctx->plan.ws_doubles; }
 
 }  // namespace
 
@@ -152,7 +161,8 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_pass_p(ctx->dev, grads, err_codes, err_scales, Q_state, P_raw_out, st, stage_span(ctx, 0)));
+    return hip_rc(launch_pass_p(ctx->dev, grads, err_codes, err_scales, Q_state, P_raw_out, ws_doubles(ctx, workspace), st,
+                                stage_span(ctx, 0)));
 }
 
 int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
@@ -175,7 +185,7 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_qpart(ctx, workspace), st,
+    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_doubles(ctx, workspace), st,
                                 stage_span(ctx, 2)));
 }
 

@@ -9,12 +9,17 @@ namespace conef {
 // Device-resident copy of a plan: descriptor array and work tables.
 struct DevicePlan {
     const MatDesc *mats = nullptr;
-    const WorkItem *p_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *q_items = nullptr,
-                   *qred_items = nullptr, *err_items = nullptr, *elem_items = nullptr;
+    const WorkItem *p_items = nullptr, *q_items = nullptr, *err_items = nullptr;          // generic family
+    const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
+    const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
+                   *elem_items = nullptr;
     int n_mats = 0;
-    int n_p = 0, n_gram = 0, n_apply = 0, n_q = 0, n_qred = 0, n_err = 0, n_elem = 0;
+    int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0;
+    int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
+    long long qd_off = 0;           // doubles from the workspace start: fp64 copy of Q_state
+    long long q_elems = 0;
 };
 
 // Optional pair of events recorded immediately before and after a stage's main kernel.
@@ -22,17 +27,32 @@ struct Span {
     hipEvent_t begin = nullptr, end = nullptr;
 };
 
-// Each launcher enqueues on `st` and returns hipGetLastError().
+// Each launcher enqueues on `st` and returns hipGetLastError().  `ws` is the caller's workspace.
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Q, float *P, hipStream_t st, Span span = Span());
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st, Span span = Span());
+                         const float *Q, float *P, double *ws, hipStream_t st, Span span = Span());
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span = Span());
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws_q, hipStream_t st, Span span = Span());
+                         const float *Phat, float *Qout, double *ws, hipStream_t st, Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
                            const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span = Span());
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);
 hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,
                         hipStream_t st);
+
+// Kernel families (each enqueues its own grouped launches; no-ops when their tables are empty).
+void generic_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                    const float *Q, float *P, hipStream_t st);
+void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                    const float *Phat, double *ws, hipStream_t st);
+void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                      const float *Qn, uint64_t step, hipStream_t st);
+void octet_widen_q(const DevicePlan &dp, const float *Q, double *ws, hipStream_t st);
+void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, float *P,
+                  double *ws, hipStream_t st);
+void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                  const float *Phat, double *ws, hipStream_t st);
+void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                    const float *Qn, uint64_t step, hipStream_t st);
 
 }  // namespace conef

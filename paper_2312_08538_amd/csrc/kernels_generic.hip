@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void k_pass_p_generic(DevicePlan dp, const voi
 // Cholesky-QR in fp64: G = P^T P from fixed-order partial sums, G = R^T R, P^ = P R^-1.
 // In exact arithmetic this is the thin-QR factor with positive diagonal of R, the same
 // matrix Gram-Schmidt produces.
-__global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float *P, double *ws_d)
+__global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float *P, double *ws)
 {
     const WorkItem it = dp.gram_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
     const float *src = P + d.p_off + row0 * r;
     for (int e = threadIdx.x; e < rows * r; e += 256) tile[e] = src[e];
     __syncthreads();
-    double *out = ws_d + d.gram_off + (int64_t)it.a * r * r;
+    double *out = ws + d.gram_off + (int64_t)it.a * r * r;
     for (int e = threadIdx.x; e < r * r; e += 256) {
         const int a = e / r, b = e % r;
         double s = 0.0;
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
 // One wave per matrix: sum the partial Gram matrices, factor, invert the triangle.
 // A column whose squared norm after projection is not above 1e-12 of its squared norm is
 // linearly dependent on the earlier ones: its P^ column is set to zero.
-__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws_d)
+__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws)
 {
     const MatDesc d = dp.mats[blockIdx.x];
     const int r = dp.rank;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *
     __shared__ int dead[kMaxRank];
     for (int e = lane; e < r * r; e += 64) {
         double s = 0.0;
-        const double *src = ws_d + d.gram_off + e;
+        const double *src = ws + d.gram_off + e;
         for (int t = 0; t < d.n_gram_tiles; ++t) s += src[(int64_t)t * r * r];
         G[e] = s;
         R[e] = 0.0;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *
         __syncthreads();
     }
     // inverse of the upper triangle, one column per lane, by back substitution
-    double *rinv = ws_d + d.rinv_off;
+    double *rinv = ws + d.rinv_off;
     if (lane < r) {
         const int j = lane;
         double col[kMaxRank];
@@ -136,13 +136,13 @@ __global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *
 }
 
 template <int RP>
-__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws_d)
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws)
 {
     const WorkItem it = dp.apply_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int r = dp.rank;
     __shared__ double rinv[kMaxRank * kMaxRank];
-    for (int e = threadIdx.x; e < r * r; e += 256) rinv[e] = ws_d[d.rinv_off + e];
+    for (int e = threadIdx.x; e < r * r; e += 256) rinv[e] = ws[d.rinv_off + e];
     __syncthreads();
     const int64_t row = (int64_t)it.a + threadIdx.x;
     if (row >= d.n) return;
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
 // tile go to the workspace and are added in row-tile order by k_q_reduce.
 template <int RP>
 __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, const void *grads, const uint32_t *codes,
-                                                              const float *scales, const float *Phat, double *ws_q)
+                                                              const float *scales, const float *Phat, double *ws)
 {
     const WorkItem it = dp.q_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -186,20 +186,20 @@ __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, con
         for (int c = 0; c < RP; ++c)
             if (c < r) acc[c] = __builtin_fma(pv, (double)prow[c], acc[c]);
     }
-    double *out = ws_q + d.qpart_off + ((int64_t)it.b * d.m + k) * r;
+    double *out = ws + d.qpart_off + ((int64_t)it.b * d.m + k) * r;
 #pragma unroll
     for (int c = 0; c < RP; ++c)
         if (c < r) out[c] = acc[c];
 }
 
-__global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws_q, float *Qout)
+__global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws, float *Qout)
 {
     const WorkItem it = dp.qred_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int64_t e = (int64_t)it.a + threadIdx.x;
     const int64_t len = d.m * dp.rank;
     if (e >= len) return;
-    const double *src = ws_q + d.qpart_off + e;
+    const double *src = ws + d.qpart_off + e;
     double s = 0.0;
     for (int t = 0; t < d.n_q_tiles; ++t) s += src[(int64_t)t * len];
     Qout[d.q_off + e] = (float)s;
@@ -265,6 +265,20 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
     }
 }
 
+// Adds the column-chunk partial sums of P in chunk order and rounds once to fp32.
+__global__ __launch_bounds__(256) void k_p_reduce(DevicePlan dp, const double *ws, float *P)
+{
+    const WorkItem it = dp.pred_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t e = (int64_t)it.a + threadIdx.x;
+    const int64_t len = d.n * dp.rank;
+    if (e >= len) return;
+    const double *src = ws + d.ppart_off + e;
+    double s = 0.0;
+    for (int t = 0; t < d.n_p_chunks; ++t) s += src[(int64_t)t * len];
+    P[d.p_off + e] = (float)s;
+}
+
 // ---------------------------------------------------------------- helpers
 __global__ __launch_bounds__(256) void k_decode(DevicePlan dp, const uint32_t *codes, const float *scales, float *e_out)
 {
@@ -298,33 +312,59 @@ __global__ __launch_bounds__(256) void k_zero(uint32_t *a, size_t na, uint32_t *
         }                                                                                         \
     } while (0)
 
-hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Q, float *P, hipStream_t st, Span span)
+void generic_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                    const float *Q, float *P, hipStream_t st)
 {
+    if (dp.n_p > 0) CONEF_DISPATCH_RP(k_pass_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, codes, scales, Q, P);
+}
+
+void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                    const float *Phat, double *ws, hipStream_t st)
+{
+    if (dp.n_q > 0)
+        CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws);
+}
+
+void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                      const float *Qn, uint64_t step, hipStream_t st)
+{
+    if (dp.n_err > 0)
+        CONEF_DISPATCH_RP(k_pass_err_generic, dim3(dp.n_err), dim3(256), st, dp, grads, codes, scales, Phat, Qn,
+                          (uint32_t)step, (uint32_t)(step >> 32));
+}
+
+// A stage's span brackets its main pass kernels (both families), not the small reductions after them.
+hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                         const float *Q, float *P, double *ws, hipStream_t st, Span span)
+{
+    octet_widen_q(dp, Q, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    CONEF_DISPATCH_RP(k_pass_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, codes, scales, Q, P);
+    octet_pass_p(dp, grads, codes, scales, P, ws, st);
+    generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
+    if (dp.n_pred > 0) hipLaunchKernelGGL(k_p_reduce, dim3(dp.n_pred), dim3(256), 0, st, dp, (const double *)ws, P);
     return hipGetLastError();
 }
 
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws_d, hipStream_t st, Span span)
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
 {
     // the span covers all three small kernels of this stage
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws_d);
-    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(64), 0, st, dp, ws_d);
-    CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws_d);
+    hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws);
+    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(64), 0, st, dp, ws);
+    CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
 
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws_q, hipStream_t st, Span span)
+                         const float *Phat, float *Qout, double *ws, hipStream_t st, Span span)
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws_q);
+    octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
+    generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);
-    hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws_q, Qout);
+    hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, Qout);
     return hipGetLastError();
 }
 
@@ -332,8 +372,8 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
                            const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    CONEF_DISPATCH_RP(k_pass_err_generic, dim3(dp.n_err), dim3(256), st, dp, grads, codes, scales, Phat, Qn,
-                      (uint32_t)step, (uint32_t)(step >> 32));
+    octet_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
+    generic_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }

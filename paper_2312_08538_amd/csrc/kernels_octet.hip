@@ -1,0 +1,451 @@
+// Octet kernel family: the streaming passes for matrices whose rows hold whole scale blocks
+// (cols % block == 0, block/8 a power of two <= 64) and rank <= 8.
+//
+// A lane owns an "octet": 8 consecutive elements of a row -- one 16-byte (bf16) or two 16-byte
+// (fp32) gradient loads, 16/32/64 bits of codes, one Philox call in the error pass.  `lr` lanes
+// (8..64, a power of two) cover a row segment; 64/lr rows share a wave.
+//
+//   P pass    one wave per 64-row x column-chunk item.  Octets are decoded in the coalesced load
+//             layout, p goes through a wave-private LDS tile and is read back with one lane per
+//             ROW, so the rank-r dot products run down the row inside a lane: Q (an fp64 copy,
+//             wave-uniform address, scalar loads) is an SGPR operand, and no cross-lane sum is
+//             needed.  fp64 accumulation: products of fp32 values are exact, one rounding at the end.
+//   Q+ pass   one workgroup per 512-column strip x row tile; a lane keeps 8 x r fp64 sums for its
+//             8 columns while the waves walk down the rows; P^ rows are per-lane broadcast loads.
+//   err pass  one wave per strip x row range, Q+ tile (8 x r) in registers, residual as the fp32
+//             fma chain, block max-norm by DPP, fixed-point stochastic rounding, pack, in place.
+//
+// All sums are combined in a fixed order: results do not depend on scheduling.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace conef {
+
+namespace {
+
+// ------------------------------------------------------------------ octet load / decode
+template <bool BF16, int BITS>
+struct RawOctet {
+    uint4 g0, g1;        // gradient bits (g1 only for fp32)
+    uint32_t c0, c1;     // code bits: 8-bit: two words; 4-bit: c0; 2-bit: low 16 bits of c0
+    float scale;
+};
+
+template <bool BF16, int BITS>
+__device__ __forceinline__ RawOctet<BF16, BITS> load_octet(const MatDesc &d, const void *__restrict__ grads,
+                                                           const uint32_t *codes, const float *scales,
+                                                           int64_t o /* octet index in the matrix */, bool valid)
+{
+    RawOctet<BF16, BITS> r;
+    r.g0 = make_uint4(0, 0, 0, 0); r.g1 = make_uint4(0, 0, 0, 0); r.c0 = 0; r.c1 = 0; r.scale = 0.0f;
+    if (valid) {
+        if (BF16) {
+            r.g0 = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(grads) + d.grad_off + o * 8);
+        } else {
+            const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(grads) + d.grad_off + o * 8);
+            r.g0 = gp[0];
+            r.g1 = gp[1];
+        }
+        if (BITS == 8) {
+            const uint2 c = *reinterpret_cast<const uint2 *>(codes + d.word_off + o * 2);
+            r.c0 = c.x; r.c1 = c.y;
+        } else if (BITS == 4) {
+            r.c0 = codes[d.word_off + o];
+        } else {
+            r.c0 = reinterpret_cast<const uint16_t *>(codes + d.word_off)[o];
+        }
+        r.scale = scales[d.scale_off + (o >> d.lb_shift)];
+    }
+    return r;
+}
+
+template <bool BF16, int BITS>
+__device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, float p[8])
+{
+    float g[8];
+    if (BF16) {
+        const uint32_t w[4] = {r.g0.x, r.g0.y, r.g0.z, r.g0.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            g[2 * i] = __uint_as_float(w[i] << 16);
+            g[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    } else {
+        g[0] = __uint_as_float(r.g0.x); g[1] = __uint_as_float(r.g0.y); g[2] = __uint_as_float(r.g0.z);
+        g[3] = __uint_as_float(r.g0.w); g[4] = __uint_as_float(r.g1.x); g[5] = __uint_as_float(r.g1.y);
+        g[6] = __uint_as_float(r.g1.z); g[7] = __uint_as_float(r.g1.w);
+    }
+    const float step = r.scale * inv_levels(BITS);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        int q;
+        if (BITS == 8) q = code_field(e < 4 ? r.c0 : r.c1, e & 3, 8);
+        else q = code_field(r.c0, e, BITS);
+        p[e] = __builtin_fmaf(step, (float)q, g[e]);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void store_codes(const MatDesc &d, uint32_t *codes, int64_t o, const uint32_t f[8])
+{
+    if (BITS == 8) {
+        uint2 c;
+        c.x = f[0] | (f[1] << 8) | (f[2] << 16) | (f[3] << 24);
+        c.y = f[4] | (f[5] << 8) | (f[6] << 16) | (f[7] << 24);
+        *reinterpret_cast<uint2 *>(codes + d.word_off + o * 2) = c;
+    } else if (BITS == 4) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c |= f[e] << (4 * e);
+        codes[d.word_off + o] = c;
+    } else {
+        uint32_t c = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c |= f[e] << (2 * e);
+        reinterpret_cast<uint16_t *>(codes + d.word_off)[o] = (uint16_t)c;
+    }
+}
+
+// max over the 2^lb_shift lanes of a scale block (aligned group of lanes)
+__device__ __forceinline__ float block_max(float a, int lb_shift)
+{
+    // quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140
+    if (lb_shift >= 1) a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0xB1, 0xF, 0xF, true)));
+    if (lb_shift >= 2) a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x4E, 0xF, 0xF, true)));
+    if (lb_shift >= 3) a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
+    if (lb_shift >= 4) a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
+    if (lb_shift >= 5) a = fmaxf(a, __shfl_xor(a, 16, 64));
+    if (lb_shift >= 6) a = fmaxf(a, __shfl_xor(a, 32, 64));
+    return a;
+}
+
+// One row (RP = rank floats, 8- or 16-byte aligned) of a factor matrix; zeros if !valid.
+template <int RP>
+__device__ __forceinline__ void load_factor_row(const float *__restrict__ F, int64_t off, bool valid, float out[RP])
+{
+#pragma unroll
+    for (int c = 0; c < RP; ++c) out[c] = 0.0f;
+    if (!valid) return;
+    if (RP == 2) {
+        const float2 v = *reinterpret_cast<const float2 *>(F + off);
+        out[0] = v.x; out[1] = v.y;
+    } else {
+#pragma unroll
+        for (int c4 = 0; c4 < RP / 4; ++c4) {
+            const float4 v = reinterpret_cast<const float4 *>(F + off)[c4];
+            out[4 * c4] = v.x; out[4 * c4 + 1] = v.y; out[4 * c4 + 2] = v.z; out[4 * c4 + 3] = v.w;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ err pass
+template <bool BF16, int BITS, int RP>
+__global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes,
+                                                   float *scales, const float *__restrict__ Phat,
+                                                   const float *__restrict__ Qn, uint32_t step_lo, uint32_t step_hi)
+{
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_err_f) return;
+    const WorkItem it = dp.err_f_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    constexpr int r = RP;                 // this family is instantiated for the exact rank
+    const int lr = 1 << d.lr_shift, rw = 64 >> d.lr_shift;
+    const int sub = lane >> d.lr_shift, lc = lane & (lr - 1);
+    const int oc = it.a * lr + lc;
+    const float s_f = (float)((1 << (BITS - 1)) - 1);
+    const uint32_t mask = (1u << BITS) - 1u;
+
+    float q[8][RP];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) load_factor_row<RP>(Qn, d.q_off + ((int64_t)oc * 8 + e) * r, true, q[e]);
+
+    const int row_end = it.b + it.c;
+    int row = it.b + sub;
+    bool valid = row < row_end;
+    RawOctet<BF16, BITS> cur = load_octet<BF16, BITS>(d, grads, codes, scales, (int64_t)row * d.m8 + oc, valid);
+    float ph[RP];
+    load_factor_row<RP>(Phat, d.p_off + (int64_t)row * r, valid, ph);
+
+    for (int r0 = it.b; r0 < row_end; r0 += rw) {
+        // prefetch the next row of this lane before working on the current one
+        const int nrow = row + rw;
+        const bool nvalid = nrow < row_end;
+        const RawOctet<BF16, BITS> nxt = load_octet<BF16, BITS>(d, grads, codes, scales, (int64_t)nrow * d.m8 + oc, nvalid);
+        float nph[RP];
+        load_factor_row<RP>(Phat, d.p_off + (int64_t)nrow * r, nvalid, nph);
+
+        float x[8];
+        decode_octet<BF16, BITS>(cur, x);
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int c = 0; c < RP; ++c) acc = __builtin_fmaf(ph[c], q[e][c], acc);
+            x[e] = x[e] - acc;
+            a = fmaxf(a, fabsf(x[e]));
+        }
+        a = block_max(a, d.lb_shift);
+        const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
+        const int64_t o = (int64_t)row * d.m8 + oc;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+        uint32_t f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16, draw16(rnd, e), mask);
+        if (valid) {
+            store_codes<BITS>(d, codes, o, f);
+            if ((lc & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
+        }
+        cur = nxt;
+#pragma unroll
+        for (int c = 0; c < RP; ++c) ph[c] = nph[c];
+        row = nrow;
+        valid = nvalid;
+    }
+}
+
+// ------------------------------------------------------------------ Q+ pass
+template <bool BF16, int BITS, int RP>
+__global__ __launch_bounds__(256) void k_q_octet(DevicePlan dp, const void *__restrict__ grads,
+                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
+                                                 const float *__restrict__ Phat, double *ws)
+{
+    __shared__ double red[64 * 8 * RP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const WorkItem it = dp.q_f_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    constexpr int r = RP;                 // this family is instantiated for the exact rank
+    const int lr = 1 << d.lr_shift, rw = 64 >> d.lr_shift;
+    const int sub = lane >> d.lr_shift, lc = lane & (lr - 1);
+    const int oc = it.a * lr + lc;
+    const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
+    const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
+
+    double acc[8][RP];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int c = 0; c < RP; ++c) acc[e][c] = 0.0;
+
+    int64_t row = row0 + wave * rw + sub;
+    bool valid = row < row1;
+    RawOctet<BF16, BITS> cur = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oc, valid);
+    float ph[RP];
+    load_factor_row<RP>(Phat, d.p_off + row * r, valid, ph);
+    for (int64_t r0 = row0 + wave * rw; r0 < row1; r0 += 4 * rw) {
+        const int64_t nrow = row + 4 * rw;
+        const bool nvalid = nrow < row1;
+        const RawOctet<BF16, BITS> nxt = load_octet<BF16, BITS>(d, grads, codes, scales, nrow * d.m8 + oc, nvalid);
+        float nph[RP];
+        load_factor_row<RP>(Phat, d.p_off + nrow * r, nvalid, nph);
+
+        float p[8];
+        decode_octet<BF16, BITS>(cur, p);           // an invalid lane holds zeros: p = 0, ph = 0
+        double pd[RP];
+#pragma unroll
+        for (int c = 0; c < RP; ++c) pd[c] = (double)ph[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double pe = (double)p[e];
+#pragma unroll
+            for (int c = 0; c < RP; ++c) acc[e][c] = __builtin_fma(pe, pd[c], acc[e][c]);
+        }
+        cur = nxt;
+#pragma unroll
+        for (int c = 0; c < RP; ++c) ph[c] = nph[c];
+        row = nrow;
+        valid = nvalid;
+    }
+    // rows that shared the wave (lane groups above lr) hold sums for the same columns
+    for (int o = lr; o < 64; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int c = 0; c < RP; ++c) acc[e][c] += __shfl_xor(acc[e][c], o, 64);
+    }
+    // waves 0..3 are added in that order
+    for (int w2 = 0; w2 < 4; ++w2) {
+        if (wave == w2 && sub == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int c = 0; c < RP; ++c) {
+                    const int idx = (e * RP + c) * lr + lc;
+                    red[idx] = (w2 == 0) ? acc[e][c] : red[idx] + acc[e][c];
+                }
+        }
+        __syncthreads();
+    }
+    if (wave == 0 && sub == 0) {
+        double *out = ws + d.qpart_off + ((int64_t)it.b * d.m + (int64_t)oc * 8) * r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int c = 0; c < RP; ++c)
+                out[e * r + c] = red[(e * RP + c) * lr + lc];
+    }
+}
+
+// ------------------------------------------------------------------ P pass
+constexpr int kSubCols = 32;        // columns per LDS sub-tile
+constexpr int kTileStride = 36;     // floats per LDS tile row: 32 columns + 4 of padding
+
+template <bool BF16, int BITS, int RP>
+__global__ __launch_bounds__(256) void k_p_octet(DevicePlan dp, const void *__restrict__ grads,
+                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
+                                                 const double *__restrict__ Qd, float *P, double *ws)
+{
+    __shared__ float tiles[4][kPTileRows * kTileStride];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_p_f) return;
+    float *T = tiles[wave];
+    const WorkItem it = dp.p_f_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    constexpr int r = RP;
+    const int64_t row0 = it.a;
+    const int c_begin = it.b * d.p_chunk_cols;
+    const int c_end = (c_begin + d.p_chunk_cols < d.m) ? c_begin + d.p_chunk_cols : (int)d.m;
+    const int lrow = lane >> 2, loct = lane & 3;      // load layout: 4 lanes per row, 16 rows per step
+
+    double acc[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) acc[c] = 0.0;
+
+    RawOctet<BF16, BITS> cur[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int64_t row = row0 + s * 16 + lrow;
+        const int col = c_begin + loct * 8;
+        cur[s] = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + (col >> 3), row < d.n && col < c_end);
+    }
+    for (int col0 = c_begin; col0 < c_end; col0 += kSubCols) {
+        // decode the loaded sub-tile into the wave's LDS tile (row-major, padded)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float p[8];
+            decode_octet<BF16, BITS>(cur[s], p);
+            float4 *dst = reinterpret_cast<float4 *>(T + (s * 16 + lrow) * kTileStride + loct * 8);
+            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
+            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+        }
+        // issue the loads of the next sub-tile
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int64_t row = row0 + s * 16 + lrow;
+            const int col = col0 + kSubCols + loct * 8;
+            cur[s] = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + (col >> 3), row < d.n && col < c_end);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // one lane per row: run down the row against the wave-uniform rows of Q
+        const int kmax = (c_end - col0 < kSubCols) ? c_end - col0 : kSubCols;          // multiple of 8
+        const double *qrow = Qd + d.q_off + (int64_t)col0 * r;
+        if (kmax == kSubCols) {
+            // full sub-tile: fixed trip count, so the scalar loads of Q can be batched ahead of their use
+#pragma unroll
+            for (int k4 = 0; k4 < kSubCols; k4 += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(T + lane * kTileStride + k4);
+                const float pv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double pe = (double)pv[j];
+#pragma unroll
+                    for (int c = 0; c < RP; ++c) acc[c] = __builtin_fma(pe, qrow[(k4 + j) * r + c], acc[c]);
+                }
+            }
+        } else {
+            for (int k4 = 0; k4 < kmax; k4 += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(T + lane * kTileStride + k4);
+                const float pv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double pe = (double)pv[j];
+#pragma unroll
+                    for (int c = 0; c < RP; ++c) acc[c] = __builtin_fma(pe, qrow[(k4 + j) * r + c], acc[c]);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    const int64_t row = row0 + lane;
+    if (row < d.n) {
+        if (d.n_p_chunks == 1) {
+#pragma unroll
+            for (int c = 0; c < RP; ++c) P[d.p_off + row * r + c] = (float)acc[c];
+        } else {
+            double *out = ws + d.ppart_off + ((int64_t)it.b * d.n + row) * r;
+#pragma unroll
+            for (int c = 0; c < RP; ++c) out[c] = acc[c];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_widen(const float *__restrict__ in, double *__restrict__ out, long long n)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = (double)in[i];
+}
+
+}  // namespace
+
+#define CONEF_OCTET_CASE(KERNEL, BF, B, R, GRID, ST, ...) \
+    case ((BF ? 1 : 0) << 8) | (B << 4) | R: hipLaunchKernelGGL((KERNEL<BF, B, R>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;
+
+#define CONEF_OCTET_DISPATCH(KERNEL, GRID, ST, ...)                                  \
+    do {                                                                             \
+        switch ((dp.dtype << 8) | (dp.bits << 4) | dp.rank) {                        \
+            CONEF_OCTET_CASE(KERNEL, false, 2, 2, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 2, 4, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 2, 8, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 4, 2, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 4, 4, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 4, 8, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 8, 2, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 8, 4, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, false, 8, 8, GRID, ST, __VA_ARGS__)             \
+            CONEF_OCTET_CASE(KERNEL, true, 2, 2, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 2, 4, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 2, 8, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 4, 2, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 4, 4, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 4, 8, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 8, 2, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 8, 4, GRID, ST, __VA_ARGS__)              \
+            CONEF_OCTET_CASE(KERNEL, true, 8, 8, GRID, ST, __VA_ARGS__)              \
+        default: break; /* the plan selects this family for ranks 2, 4, 8 only */    \
+        }                                                                            \
+    } while (0)
+
+void octet_widen_q(const DevicePlan &dp, const float *Q, double *ws, hipStream_t st)
+{
+    if (dp.n_p_f <= 0) return;
+    hipLaunchKernelGGL(k_widen, dim3(512), dim3(256), 0, st, Q, ws + dp.qd_off, dp.q_elems);
+}
+
+void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, float *P,
+                  double *ws, hipStream_t st)
+{
+    if (dp.n_p_f <= 0) return;
+    const double *Qd = ws + dp.qd_off;
+    CONEF_OCTET_DISPATCH(k_p_octet, dim3((dp.n_p_f + 3) / 4), st, dp, grads, codes, scales, Qd, P, ws);
+}
+
+void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                  const float *Phat, double *ws, hipStream_t st)
+{
+    if (dp.n_q_f <= 0) return;
+    CONEF_OCTET_DISPATCH(k_q_octet, dim3(dp.n_q_f), st, dp, grads, codes, scales, Phat, ws);
+}
+
+void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                    const float *Qn, uint64_t step, hipStream_t st)
+{
+    if (dp.n_err_f <= 0) return;
+    CONEF_OCTET_DISPATCH(k_err_octet, dim3((dp.n_err_f + 3) / 4), st, dp, grads, codes, scales, Phat, Qn,
+                         (uint32_t)step, (uint32_t)(step >> 32));
+}
+
+}  // namespace conef

@@ -1,5 +1,6 @@
 #include "plan.h"
 
+#include <algorithm>
 #include <new>
 
 namespace conef {
@@ -9,6 +10,8 @@ constexpr int kOk = 0, kEinval = -1, kEnomem = -2;
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t v, int64_t a) { return (v + a - 1) / a; }
+inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+inline int log2i(int64_t v) { int s = 0; while ((int64_t(1) << s) < v) ++s; return s; }
 }  // namespace
 
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,
@@ -31,9 +34,26 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         plan.rank = rank; plan.bits = bits; plan.block = block; plan.dtype = dtype; plan.seed = seed;
         plan.rpad = rank <= 4 ? 4 : rank <= 8 ? 8 : rank <= 16 ? 16 : 32;
         plan.mats.resize(n_mats);
-        int64_t g = 0, w = 0, s = 0, p = 0, q = 0, wd = 0, wf = 0;
+
+        // The octet family needs whole octets and whole scale blocks per row, a power-of-two
+        // number of lanes (8 elements each) per block, at most one wave wide, and rank 2, 4 or 8.
+        const bool block_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64;
+        int64_t total_elems = 0;
+        for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
+        // rows per wave item of the err pass: aim at >= ~4096 wave items over the model
+        int err_rows = 128;
+        while (err_rows > 8 && total_elems / ((int64_t)err_rows * 512) < 4096) err_rows >>= 1;
+        // rows per workgroup item of the Q+ pass (512 columns wide): aim at >= ~768 workgroups
+        int q_rows = 512;
+        while (q_rows > 32 && total_elems / ((int64_t)q_rows * 512) < 768) q_rows >>= 1;
+        // columns per wave item of the P pass (64 rows high): aim at >= ~2048 wave items
+        int p_cols = 512;
+        while (p_cols > 64 && total_elems / ((int64_t)kPTileRows * p_cols) < 2048) p_cols >>= 1;
+
+        int64_t g = 0, w = 0, s = 0, p = 0, q = 0, wd = 0;
         for (int l = 0; l < n_mats; ++l) {
             MatDesc &d = plan.mats[l];
+            d = MatDesc();
             d.n = rows[l]; d.m = cols[l]; d.N = d.n * d.m;
             d.nblk = ceil_div(d.N, block);
             d.grad_off = g;  g += round_up(d.N, kAlign);
@@ -41,34 +61,69 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             d.scale_off = s; s += round_up(d.nblk, kAlign);
             d.p_off = p;     p += round_up(d.n * rank, kAlign);
             d.q_off = q;     q += round_up(d.m * rank, kAlign);
+            d.path = (block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 8 == 0 && d.m % block == 0) ? kPathOctet
+                                                                                             : kPathGeneric;
+            d.m8 = (int32_t)(d.m / 8);
+            d.lb_shift = block_ok ? log2i(block / 8) : 0;
+            if (d.path == kPathOctet) {
+                // lanes per row segment: the largest power of two <= 64 that divides m/8 and holds a block
+                int lr = 64;
+                while (lr > 8 && (d.m8 % lr) != 0) lr >>= 1;
+                if ((d.m8 % lr) != 0 || lr < (block / 8)) d.path = kPathGeneric;
+                d.lr_shift = log2i(lr);
+            }
+            if (d.path == kPathOctet) plan.any_octet = true; else plan.any_generic = true;
+
             d.n_gram_tiles = (int32_t)ceil_div(d.n, kGramRows);
             d.gram_off = wd; wd += (int64_t)d.n_gram_tiles * rank * rank;
             d.rinv_off = wd; wd += rank * rank;
-            d.q_tile_rows = kGenQRows;
+            d.q_tile_rows = d.path == kPathOctet ? q_rows : kGenQRows;
             d.n_q_tiles = (int32_t)ceil_div(d.n, d.q_tile_rows);
-            d.qpart_off = wf; wf += round_up((int64_t)d.n_q_tiles * d.m * rank, kAlign);
-            d.path = 0;
+            d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * rank, 32);
+            d.n_p_chunks = 1;
+            d.p_chunk_cols = (int32_t)d.m;
+            if (d.path == kPathOctet) {
+                d.p_chunk_cols = p_cols;
+                d.n_p_chunks = (int32_t)ceil_div(d.m, d.p_chunk_cols);
+                if (d.n_p_chunks > 1) {
+                    d.ppart_off = wd; wd += round_up((int64_t)d.n_p_chunks * d.n * rank, 32);
+                    plan.any_p_chunks = true;
+                }
+            }
         }
         plan.grad_elems = (size_t)g; plan.code_words = (size_t)w; plan.n_scales = (size_t)s;
         plan.p_elems = (size_t)p; plan.q_elems = (size_t)q;
+        if (plan.any_octet) { plan.qd_off = (size_t)round_up(wd, 32); wd = (int64_t)plan.qd_off + q; }
         plan.ws_doubles = (size_t)round_up(wd, 32);
-        plan.ws_qpart = (size_t)wf;
-        plan.workspace_bytes = (size_t)round_up((plan.ws_doubles + plan.ws_qpart) * 8, 256);
+        plan.workspace_bytes = (size_t)round_up((int64_t)plan.ws_doubles * 8, 256);
 
         for (int l = 0; l < n_mats; ++l) {
             const MatDesc &d = plan.mats[l];
-            for (int64_t r0 = 0; r0 < d.n; r0 += 4) plan.p_items.push_back({l, (int32_t)r0, 0, 0});
+            if (d.path == kPathGeneric) {
+                for (int64_t r0 = 0; r0 < d.n; r0 += 4) plan.p_items.push_back({l, (int32_t)r0, 0, 0});
+                const int32_t nct = (int32_t)ceil_div(d.m, kGenQCols);
+                for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
+                    for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
+                // 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ... (16 per wave)
+                for (int64_t b0 = 0; b0 < d.nblk; b0 += 64) plan.err_items.push_back({l, (int32_t)(b0 / 64), 0, 0});
+            } else {
+                const int lr = 1 << d.lr_shift, rw = 64 / lr;
+                const int32_t strips = d.m8 / lr;
+                for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows)
+                    for (int32_t cc = 0; cc < d.n_p_chunks; ++cc) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
+                for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
+                    for (int32_t st = 0; st < strips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
+                const int64_t rows_item = (int64_t)std::max(err_rows, rw);
+                for (int64_t r0 = 0; r0 < d.n; r0 += rows_item)
+                    for (int32_t st = 0; st < strips; ++st)
+                        plan.err_f_items.push_back({l, st, (int32_t)r0, (int32_t)std::min<int64_t>(rows_item, d.n - r0)});
+                if (d.n_p_chunks > 1)
+                    for (int64_t e0 = 0; e0 < d.n * rank; e0 += 256) plan.pred_items.push_back({l, (int32_t)e0, 0, 0});
+            }
             for (int32_t t = 0; t < d.n_gram_tiles; ++t) plan.gram_items.push_back({l, t, 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += 256) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
-            const int32_t nct = (int32_t)ceil_div(d.m, kGenQCols);
-            for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
-                for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
             for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
-            // pass 3: 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ... (16 per wave)
-            for (int64_t b0 = 0; b0 < d.nblk; b0 += 64)
-                plan.err_items.push_back({l, (int32_t)(b0 / 64), 0, 0});
-            for (int64_t e0 = 0; e0 < d.N; e0 += 1024)
-                plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
+            for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
         }
     } catch (const std::bad_alloc &) {
         return kEnomem;

@@ -12,21 +12,33 @@ constexpr int kMaxRank = 32;
 constexpr int kGramRows = 256;      // rows per partial Gram matrix
 constexpr int kGenQRows = 128;      // rows per partial of Q+ in the generic pass 2
 constexpr int kGenQCols = 256;      // columns per workgroup in the generic pass 2
+constexpr int kFastMaxRank = 8;     // the octet family holds rank <= 8 in registers
+constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (one lane per row)
+
+enum Path { kPathGeneric = 0, kPathOctet = 1 };
 
 // One matrix of the model as the kernels see it (device copy is an array of these).
+// Workspace offsets are in doubles from the start of the workspace.
 struct MatDesc {
     int64_t n, m, N;                // rows, cols, n*m
     int64_t grad_off, word_off, scale_off, p_off, q_off;   // element offsets in the flat buffers
     int64_t nblk;                   // number of scale blocks
-    int64_t gram_off;               // doubles: partial Gram matrices, [n_gram_tiles][r*r]
-    int64_t rinv_off;               // doubles: r*r inverse triangular factor
-    int64_t qpart_off;              // doubles, relative to the Q+ partial area: [n_q_tiles][m*r]
-    int32_t n_gram_tiles, n_q_tiles;
+    int64_t gram_off;               // partial Gram matrices, [n_gram_tiles][r*r]
+    int64_t rinv_off;               // r*r inverse triangular factor
+    int64_t qpart_off;              // partial sums of Q+, [n_q_tiles][m*r]
+    int64_t ppart_off;              // partial sums of P, [n_p_chunks][n*r] (only if n_p_chunks > 1)
+    int32_t n_gram_tiles, n_q_tiles, n_p_chunks;
     int32_t q_tile_rows;            // rows per partial of Q+
-    int32_t path;                   // kernel family chosen for this matrix (0 = generic)
+    int32_t p_chunk_cols;           // columns per partial of P
+    int32_t path;                   // kernel family chosen for this matrix
+    // octet family: a lane owns 8 consecutive elements of a row; lr lanes share a row
+    int32_t lr_shift;               // log2(lanes per row segment), 3..6
+    int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
+    int32_t m8;                     // m / 8
+    int32_t pad_;
 };
 
-// One unit of work of a grouped launch: matrix index and two kernel-specific coordinates.
+// One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
 struct WorkItem {
     int32_t mat, a, b, c;
 };
@@ -36,17 +48,24 @@ struct Plan {
     uint64_t seed = 0;
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
-    size_t ws_doubles = 0;          // Gram partials and triangular inverses (first), in doubles
-    size_t ws_qpart = 0;            // partial sums of Q+ (after them), in doubles
+    size_t qd_off = 0;              // doubles: fp64 copy of Q_state (q_elems entries), 0 if unused
+    bool any_octet = false, any_generic = false, any_p_chunks = false;
+    size_t ws_doubles = 0;
     size_t workspace_bytes = 0;
-    // work tables (generic kernel family)
+    // generic family
     std::vector<WorkItem> p_items;      // pass 1: (mat, first row)            4 rows per workgroup
+    std::vector<WorkItem> q_items;      // pass 2: (mat, column tile, row tile)
+    std::vector<WorkItem> err_items;    // pass 3: (mat, first block / 64)
+    // octet family (one item per wave for p and err, per workgroup for q)
+    std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk)
+    std::vector<WorkItem> q_f_items;    // (mat, strip, row tile)
+    std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
+    // shared
+    std::vector<WorkItem> pred_items;   // reduce partial P: (mat, first entry of n*r)
     std::vector<WorkItem> gram_items;   // (mat, gram tile)
     std::vector<WorkItem> apply_items;  // (mat, first row)                    256 rows per workgroup
-    std::vector<WorkItem> q_items;      // pass 2: (mat, column tile, row tile)
-    std::vector<WorkItem> qred_items;   // (mat, first entry of m*r)           256 entries per workgroup
-    std::vector<WorkItem> err_items;    // pass 3: (mat, first block)          blocks per workgroup in .b
-    std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element/1024)
+    std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
+    std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
 };
 
 // Returns 0 or a negative CONEF_E* code.  `rows`/`cols` have n_mats entries.
