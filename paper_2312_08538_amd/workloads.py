@@ -146,7 +146,8 @@ def device_fill_gradients(w: Workload, step: int, flat, offsets) -> None:
             x = torch.randn(N, device=flat.device, generator=gen) * sc
         elif w.dist == "laplace":
             u = torch.rand(N, device=flat.device, generator=gen) - 0.5
-            x = -w.scale * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+            # inverse CDF; 1 - 2|u| is kept away from 0 (rand() can return exactly 0)
+            x = -w.scale * torch.sign(u) * torch.log(torch.clamp(1.0 - 2.0 * u.abs(), min=2.0 ** -24))
         elif w.dist == "student_t3":
             z = torch.randn(N, device=flat.device, generator=gen)
             chi = torch.zeros(N, device=flat.device)
