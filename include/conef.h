@@ -95,7 +95,7 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes,
                  const float *err_scales, const float *P_hat, float *Q_out,
                  void *workspace, void *hip_stream);              /* Q+ = (g + e)^T * P^            */
 int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
-                   const float *P_hat, const float *Q_new, uint64_t step,
+                   const float *P_hat, const float *Q_new, void *workspace, uint64_t step,
                    void *hip_stream);                             /* err <- C(g + e - P^ Q+^T)      */
 
 /* e := 0 for the whole model (zero codes and scales), enqueued on the stream. */

@@ -46,7 +46,7 @@ def lib() -> ctypes.CDLL:
     L.conef_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.conef_orthonormalise.argtypes = [vp, vp, vp, vp]
     L.conef_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
-    L.conef_step_err.argtypes = [vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_reset_error.argtypes = [vp, vp, vp, vp]
     L.conef_decode_error.argtypes = [vp, vp, vp, vp, vp]
     L.conef_set_timing.argtypes = [vp, i32]
@@ -127,9 +127,9 @@ def conef_step_q(ctx, grads, err_codes, err_scales, P_hat, Q_out, workspace, str
                               _ptr(workspace), stream), "conef_step_q")
 
 
-def conef_step_err(ctx, grads, err_codes, err_scales, P_hat, Q_new, step: int, stream=0):
+def conef_step_err(ctx, grads, err_codes, err_scales, P_hat, Q_new, workspace, step: int, stream=0):
     _check(lib().conef_step_err(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(P_hat), _ptr(Q_new),
-                                step, stream), "conef_step_err")
+                                _ptr(workspace), step, stream), "conef_step_err")
 
 
 def conef_reset_error(ctx, err_codes, err_scales, stream=0):

@@ -55,6 +55,12 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.p_f_items, &d.p_f_items))) return rc;
     if ((rc = upload(ctx, pl.q_f_items, &d.q_f_items))) return rc;
     if ((rc = upload(ctx, pl.err_f_items, &d.err_f_items))) return rc;
+    if ((rc = upload(ctx, pl.p_m_items, &d.p_m_items))) return rc;
+    if ((rc = upload(ctx, pl.q_m_items, &d.q_m_items))) return rc;
+    if ((rc = upload(ctx, pl.err_m_items, &d.err_m_items))) return rc;
+    if ((rc = upload(ctx, pl.split_q_items, &d.split_q_items))) return rc;
+    if ((rc = upload(ctx, pl.split_p_items, &d.split_p_items))) return rc;
+    if ((rc = upload(ctx, pl.split_qn_items, &d.split_qn_items))) return rc;
     if ((rc = upload(ctx, pl.pred_items, &d.pred_items))) return rc;
     if ((rc = upload(ctx, pl.gram_items, &d.gram_items))) return rc;
     if ((rc = upload(ctx, pl.apply_items, &d.apply_items))) return rc;
@@ -67,6 +73,12 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_p_f = (int)pl.p_f_items.size();
     d.n_q_f = (int)pl.q_f_items.size();
     d.n_err_f = (int)pl.err_f_items.size();
+    d.n_p_m = (int)pl.p_m_items.size();
+    d.n_q_m = (int)pl.q_m_items.size();
+    d.n_err_m = (int)pl.err_m_items.size();
+    d.n_split_q = (int)pl.split_q_items.size();
+    d.n_split_p = (int)pl.split_p_items.size();
+    d.n_split_qn = (int)pl.split_qn_items.size();
     d.n_pred = (int)pl.pred_items.size();
     d.n_gram = (int)pl.gram_items.size();
     d.n_apply = (int)pl.apply_items.size();
@@ -189,17 +201,26 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
                                 stage_span(ctx, 2)));
 }
 
-int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
-                   const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream)
+namespace {
+int step_err_impl(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, const float *P_hat,
+                  const float *Q_new, void *workspace, uint64_t step, void *hip_stream, bool splits_ready)
 {
-    if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_new) return CONEF_EINVAL;
+    if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_new || !workspace) return CONEF_EINVAL;
     if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
-        misaligned(Q_new, 16))
+        misaligned(Q_new, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_pass_err(ctx->dev, grads, err_codes, err_scales, P_hat, Q_new, step, st, stage_span(ctx, 3)));
+    return hip_rc(launch_pass_err(ctx->dev, grads, err_codes, err_scales, P_hat, Q_new, step, ws_doubles(ctx, workspace),
+                                  splits_ready, st, stage_span(ctx, 3)));
+}
+}  // namespace
+
+int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+                   const float *P_hat, const float *Q_new, void *workspace, uint64_t step, void *hip_stream)
+{
+    return step_err_impl(ctx, grads, err_codes, err_scales, P_hat, Q_new, workspace, step, hip_stream, false);
 }
 
 int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
@@ -212,8 +233,9 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     /* exchange point 1: mean of P over the workers -- identity for one worker */
     if ((rc = conef_orthonormalise(ctx, P_out, workspace, hip_stream))) return rc;
     if ((rc = conef_step_q(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream))) return rc;
-    /* exchange point 2: mean of Q over the workers -- identity for one worker */
-    return conef_step_err(ctx, grads, err_codes, err_scales, P_out, Q_out, step, hip_stream);
+    /* exchange point 2: mean of Q over the workers -- identity for one worker; the operand splits
+       of P^ and Q+ made by the Q+ stage are therefore still valid for the err stage */
+    return step_err_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, step, hip_stream, true);
 }
 
 int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream)

@@ -11,10 +11,13 @@ struct DevicePlan {
     const MatDesc *mats = nullptr;
     const WorkItem *p_items = nullptr, *q_items = nullptr, *err_items = nullptr;          // generic family
     const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
+    const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
+    const WorkItem *split_q_items = nullptr, *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
                    *elem_items = nullptr;
     int n_mats = 0;
     int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0;
+    int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_q = 0, n_split_p = 0, n_split_qn = 0;
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
@@ -34,7 +37,8 @@ hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hip
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Phat, float *Qout, double *ws, hipStream_t st, Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
-                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span = Span());
+                           const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
+                           hipStream_t st, Span span = Span());
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);
 hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,
@@ -54,5 +58,16 @@ void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes
                   const float *Phat, double *ws, hipStream_t st);
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                     const float *Qn, uint64_t step, hipStream_t st);
+
+// MFMA family.  `prep_only` / `main_only` select the operand-split kernels or the pass itself.
+void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                 const float *Q, float *P, double *ws, hipStream_t st, bool prep_only, bool main_only);
+
+void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st);
+void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, double *ws,
+                 hipStream_t st);
+void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,
+                   uint64_t step, hipStream_t st);
+void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st);
 
 }  // namespace conef

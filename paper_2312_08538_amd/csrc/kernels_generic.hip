@@ -22,6 +22,23 @@ __device__ __forceinline__ float form_p(const MatDesc &d, const void *grads, con
     return __builtin_fmaf(step, (float)q, load_grad(grads, dtype, d.grad_off + j));
 }
 
+// Sum of T values src[0], src[stride], ... added in index order; loads are issued 8 at a time so
+// the chain of additions, not the memory latency, sets the pace.
+__device__ __forceinline__ double ordered_sum(const double *src, int T, int64_t stride)
+{
+    double s = 0.0;
+    int t = 0;
+    for (; t + 8 <= T; t += 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(t + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; t < T; ++t) s += src[(int64_t)t * stride];
+    return s;
+}
+
 // ---------------------------------------------------------------- pass 1: P = p * Q
 // One wave per row; lanes stride along the row; wave-level tree sum.
 template <int RP>
@@ -80,19 +97,16 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
 // One wave per matrix: sum the partial Gram matrices, factor, invert the triangle.
 // A column whose squared norm after projection is not above 1e-12 of its squared norm is
 // linearly dependent on the earlier ones: its P^ column is set to zero.
-__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws)
+__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws)
 {
     const MatDesc d = dp.mats[blockIdx.x];
     const int r = dp.rank;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x;          // the factorisation itself uses the first r threads
     __shared__ double G[kMaxRank * kMaxRank];
     __shared__ double R[kMaxRank * kMaxRank];
     __shared__ int dead[kMaxRank];
-    for (int e = lane; e < r * r; e += 64) {
-        double s = 0.0;
-        const double *src = ws + d.gram_off + e;
-        for (int t = 0; t < d.n_gram_tiles; ++t) s += src[(int64_t)t * r * r];
-        G[e] = s;
+    for (int e = lane; e < r * r; e += 256) {
+        G[e] = ordered_sum(ws + d.gram_off + e, d.n_gram_tiles, (int64_t)r * r);
         R[e] = 0.0;
     }
     __syncthreads();
@@ -199,10 +213,7 @@ __global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *w
     const int64_t e = (int64_t)it.a + threadIdx.x;
     const int64_t len = d.m * dp.rank;
     if (e >= len) return;
-    const double *src = ws + d.qpart_off + e;
-    double s = 0.0;
-    for (int t = 0; t < d.n_q_tiles; ++t) s += src[(int64_t)t * len];
-    Qout[d.q_off + e] = (float)s;
+    Qout[d.q_off + e] = (float)ordered_sum(ws + d.qpart_off + e, d.n_q_tiles, len);
 }
 
 // ---------------------------------------------------------------- pass 3: err <- C(p - P^ Q+^T)
@@ -273,10 +284,7 @@ __global__ __launch_bounds__(256) void k_p_reduce(DevicePlan dp, const double *w
     const int64_t e = (int64_t)it.a + threadIdx.x;
     const int64_t len = d.n * dp.rank;
     if (e >= len) return;
-    const double *src = ws + d.ppart_off + e;
-    double s = 0.0;
-    for (int t = 0; t < d.n_p_chunks; ++t) s += src[(int64_t)t * len];
-    P[d.p_off + e] = (float)s;
+    P[d.p_off + e] = (float)ordered_sum(ws + d.ppart_off + e, d.n_p_chunks, len);
 }
 
 // ---------------------------------------------------------------- helpers
@@ -338,7 +346,9 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
                          const float *Q, float *P, double *ws, hipStream_t st, Span span)
 {
     octet_widen_q(dp, Q, ws, st);
+    mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, true, false);
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, false, true);
     octet_pass_p(dp, grads, codes, scales, P, ws, st);
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
@@ -351,7 +361,7 @@ hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hip
     // the span covers all three small kernels of this stage
     if (span.begin) (void)hipEventRecord(span.begin, st);
     hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws);
-    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(64), 0, st, dp, ws);
+    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(256), 0, st, dp, ws);
     CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
@@ -360,18 +370,28 @@ hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hip
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Phat, float *Qout, double *ws, hipStream_t st, Span span)
 {
+    mfma_split_p_hat(dp, Phat, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_pass_q(dp, grads, codes, scales, ws, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
     generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);
     hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, Qout);
+    mfma_split_q_new(dp, Qout, ws, st);
     return hipGetLastError();
 }
 
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
-                           const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
+                           const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
+                           hipStream_t st, Span span)
 {
+    if (!splits_ready) {
+        // the factors handed in may differ from those the Q+ stage saw (e.g. after an all-reduce)
+        mfma_split_p_hat(dp, Phat, ws, st);
+        mfma_split_q_new(dp, Qn, ws, st);
+    }
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_pass_err(dp, grads, codes, scales, ws, step, st);
     octet_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     generic_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     if (span.end) (void)hipEventRecord(span.end, st);

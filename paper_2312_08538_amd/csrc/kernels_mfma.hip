@@ -1,0 +1,538 @@
+// MFMA kernel family: rank-32 contractions on the matrix cores (v_mfma_f32_32x32x16_bf16) for
+// bf16 gradients, 4-bit codes, block 128, cols % 128 == 0.
+//
+// fp32-level accuracy from bf16 matrix cores comes from exact operand splits:
+//   - a factor entry x (fp32) is written as hi + mid + lo, three bf16 values obtained by
+//     truncation (each remainder is exact), so hi + mid + lo == x to 24 bits;
+//   - in the P pass the other operand is exact in bf16 by construction: the gradient is bf16,
+//     and the 4-bit codes are small integers; the block step size d multiplies the code part
+//     once per 128-column block, on the accumulators:
+//         P[i,c] = sum_k g[i,k] Q[k,c] + sum_blocks d[i,blk] * sum_{k in blk} q[i,k] Q[k,c]
+//     All products are exact; sums are fp32 inside the matrix core.
+// Results agree with fp64 accumulation to about 1e-6 relative, not bit for bit.
+//
+// Operand layout of v_mfma_f32_32x32x16_bf16 (D = A*B, A 32x16, B 16x32, 64 lanes):
+//   lane l holds A[l%32][8*(l/32) + j], B[8*(l/32) + j][l%32], j = 0..7, and
+//   D[8*(v/4) + 4*(l/32) + v%4][l%32], v = 0..15.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace conef {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+union Frag {
+    bf16x8 v;
+    uint4 u;
+};
+
+__device__ __forceinline__ f32x16 mfma(const Frag &a, const Frag &b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+// two fp32 values -> their upper halves (bf16 by truncation) packed: lo in bits 0..15, hi in 16..31
+__device__ __forceinline__ uint32_t pack_hi16(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+
+__device__ __forceinline__ float trunc_bf16(float x) { return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u); }
+
+// x = h + m + l with h, m, l representable in bf16 (truncation; each remainder is exact in fp32)
+__device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
+{
+    h = trunc_bf16(x);
+    const float r1 = x - h;
+    m = trunc_bf16(r1);
+    l = trunc_bf16(r1 - m);
+}
+
+// ------------------------------------------------------------------ factor splits
+// src: rows x 32 fp32 (row-major).  dst: [3][32][rows_pad] bf16, transposed; rows >= `rows` are zero.
+// One workgroup per 64 source rows starting at r0.
+__device__ __forceinline__ void split_transposed_tile(const float *__restrict__ src, uint16_t *__restrict__ dst,
+                                                      int rows, int rows_pad, int r0)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t t[3][32][64 + 8];
+    for (int e = threadIdx.x; e < 64 * 32; e += 256) {
+        const int rr = e >> 5, c = e & 31;
+        const int row = r0 + rr;
+        const float x = row < rows ? src[(int64_t)row * 32 + c] : 0.0f;
+        float h, m, l;
+        split3(x, h, m, l);
+        t[0][c][rr] = (uint16_t)(__float_as_uint(h) >> 16);
+        t[1][c][rr] = (uint16_t)(__float_as_uint(m) >> 16);
+        t[2][c][rr] = (uint16_t)(__float_as_uint(l) >> 16);
+    }
+    __syncthreads();
+    // 96 (split, column) rows of 64 entries = 128 bytes each; 8 threads of 16 bytes per row
+    for (int e = threadIdx.x; e < 96 * 8; e += 256) {
+        const int sc = e >> 3, part = e & 7;
+        const int col0 = r0 + part * 8;
+        if (col0 < rows_pad) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(&t[sc >> 5][sc & 31][part * 8]);
+            *reinterpret_cast<uint4 *>(dst + (int64_t)sc * rows_pad + col0) = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_split_q_state(DevicePlan dp, const float *__restrict__ Q, double *ws)
+{
+    const WorkItem it = dp.split_q_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    split_transposed_tile(Q + d.q_off, reinterpret_cast<uint16_t *>(ws + d.qsT_off), (int)d.m, (int)d.m, it.a * 64);
+}
+
+// ------------------------------------------------------------------ P pass
+// One workgroup per 128 rows (wave w owns rows 32w..32w+31), walking the whole row in stages of
+// 64 columns.  Per stage the gradient tile, the code words and the three splits of Q^T go through
+// LDS (coalesced global loads, operand-shaped LDS reads).  D = Q^T-split (A, 32 c x 16 k) times
+// p^T (B, 16 k x 32 rows): a lane's accumulators all belong to ONE row, so the block step size is
+// a per-lane scalar.
+constexpr int kStage = 64;                  // columns per LDS stage
+constexpr int kGStride = kStage + 8;        // bf16 per gradient row in LDS (144 bytes)
+constexpr int kCStride = kStage / 8 + 4;    // code words per row in LDS (48 bytes)
+
+__global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
+                                                const uint32_t *__restrict__ codes, const float *__restrict__ scales,
+                                                float *P, const double *ws)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sg[kMfmaRows * kGStride];
+    __shared__ __attribute__((aligned(16))) uint32_t sc[kMfmaRows * kCStride];
+    __shared__ __attribute__((aligned(16))) uint16_t sq[96 * kGStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const WorkItem it = dp.p_m_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t row0 = it.a;
+    const int m = (int)d.m;
+    const uint16_t *g = grads + d.grad_off;
+    const uint32_t *cw = codes + d.word_off;
+    const uint16_t *qsT = reinterpret_cast<const uint16_t *>(ws + d.qsT_off);
+
+    // global-load roles
+    uint4 rg[4], rq[3], rc;
+    auto load_stage = [&](int k0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
+            const int64_t row = row0 + rr;
+            rg[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
+        }
+        {
+            const int rr = tid >> 1, half = tid & 1;
+            const int64_t row = row0 + rr;
+            rc = (row < d.n) ? *reinterpret_cast<const uint4 *>(cw + (row * m + k0) / 8 + half * 4) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
+            rq[s] = *reinterpret_cast<const uint4 *>(qsT + (int64_t)qr * m + k0 + oct * 8);
+        }
+    };
+    auto store_stage = [&]() {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
+            *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = rg[s];
+        }
+        *reinterpret_cast<uint4 *>(sc + (tid >> 1) * kCStride + (tid & 1) * 4) = rc;
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
+            *reinterpret_cast<uint4 *>(sq + qr * kGStride + oct * 8) = rq[s];
+        }
+    };
+
+    // fp32 accumulators of the matrix cores cover one scale block (8 steps); block results are
+    // added up in fp64, which keeps the rounding of the long sum out of the result
+    f32x16 accP, accS;
+    double acc64[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { accP[v] = 0.0f; accS[v] = 0.0f; acc64[v] = 0.0; }
+    const int r32 = lane & 31, kg = lane >> 5;
+    const int my_row_in_tile = 32 * wave + r32;
+    const int64_t my_row = row0 + my_row_in_tile;
+    const int nblk_row = m >> 7;
+
+    load_stage(0);
+    for (int k0 = 0; k0 < m; k0 += kStage) {
+        __syncthreads();                 // everybody is done reading the previous stage
+        store_stage();
+        __syncthreads();
+        if (k0 + kStage < m) load_stage(k0 + kStage);
+#pragma unroll
+        for (int ks = 0; ks < kStage / 16; ++ks) {
+            Frag bg, bq, a0, a1, a2;
+            bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
+            const uint32_t w = sc[my_row_in_tile * kCStride + ks * 2 + kg];
+            uint32_t qb[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float lo = (float)code_field(w, 2 * e2, 4);
+                const float hi = (float)code_field(w, 2 * e2 + 1, 4);
+                qb[e2] = pack_hi16(lo, hi);          // small integers: exact in bf16
+            }
+            bq.u = make_uint4(qb[0], qb[1], qb[2], qb[3]);
+            a0.u = *reinterpret_cast<const uint4 *>(sq + (0 * 32 + r32) * kGStride + ks * 16 + kg * 8);
+            a1.u = *reinterpret_cast<const uint4 *>(sq + (1 * 32 + r32) * kGStride + ks * 16 + kg * 8);
+            a2.u = *reinterpret_cast<const uint4 *>(sq + (2 * 32 + r32) * kGStride + ks * 16 + kg * 8);
+            accP = mfma(a0, bg, accP);
+            accS = mfma(a0, bq, accS);
+            accP = mfma(a1, bg, accP);
+            accS = mfma(a1, bq, accS);
+            accP = mfma(a2, bg, accP);
+            accS = mfma(a2, bq, accS);
+        }
+        if (((k0 + kStage) & 127) == 0) {
+            // end of a scale block: fold the code part in with this row's step size
+            const int blk = k0 >> 7;
+            const float dstep = (my_row < d.n) ? scales[d.scale_off + my_row * nblk_row + blk] * inv_levels(4) : 0.0f;
+            const double dd = (double)dstep;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                acc64[v] += (double)accP[v] + dd * (double)accS[v];
+                accP[v] = 0.0f;
+                accS[v] = 0.0f;
+            }
+        }
+    }
+    if (my_row < d.n) {
+        float *out = P + d.p_off + my_row * 32;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+            *reinterpret_cast<float4 *>(out + 8 * g4 + 4 * kg) =
+                make_float4((float)acc64[4 * g4], (float)acc64[4 * g4 + 1], (float)acc64[4 * g4 + 2], (float)acc64[4 * g4 + 3]);
+    }
+}
+
+// ------------------------------------------------------------------ splits of P^ and Q+
+// P^ (n x 32): transposed splits for the Q+ pass and row-major splits for the err pass.
+__global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float *__restrict__ Phat, double *ws)
+{
+    const WorkItem it = dp.split_p_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const float *src = Phat + d.p_off;
+    const int r0 = it.a * 64;
+    uint16_t *rm = reinterpret_cast<uint16_t *>(ws + d.ps_off);            // [3][n][32]
+    for (int e = threadIdx.x; e < 64 * 32; e += 256) {
+        const int row = r0 + (e >> 5), c = e & 31;
+        if (row < d.n) {
+            float h, m, l;
+            split3(src[(int64_t)row * 32 + c], h, m, l);
+            rm[((int64_t)0 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(h) >> 16);
+            rm[((int64_t)1 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(m) >> 16);
+            rm[((int64_t)2 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
+        }
+    }
+    split_transposed_tile(src, reinterpret_cast<uint16_t *>(ws + d.psT_off), (int)d.n, d.n_pad, r0);
+}
+
+// Q+ (m x 32): row-major splits for the err pass.
+__global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float *__restrict__ Qn, double *ws)
+{
+    const WorkItem it = dp.split_qn_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const float *src = Qn + d.q_off;
+    const int r0 = it.a * 64;
+    uint16_t *rm = reinterpret_cast<uint16_t *>(ws + d.qs_off);            // [3][m][32]
+    for (int e = threadIdx.x; e < 64 * 32; e += 256) {
+        const int row = r0 + (e >> 5), c = e & 31;
+        if (row < d.m) {
+            float h, m, l;
+            split3(src[(int64_t)row * 32 + c], h, m, l);
+            rm[((int64_t)0 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(h) >> 16);
+            rm[((int64_t)1 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(m) >> 16);
+            rm[((int64_t)2 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Q+ pass
+// One workgroup per (128-column block, row tile); wave w owns columns 32w..32w+31 of the block.
+// Rows are walked in chunks of 64: octets are decoded to p (fp32) in the coalesced load layout and
+// written to an LDS tile; each lane then reads its column down 8 rows at a time (the contraction
+// runs over rows), splits p into three bf16 parts and feeds D[k][c] += p^T-split * P^-split.
+// Six products keep every term down to 2^-24 relative: (h,h) (h,m) (m,h) (h,l) (l,h) (m,m).
+constexpr int kQRows = 64;                  // rows per chunk
+constexpr int kPStride = 128 + 4;           // floats per row of the p tile in LDS
+constexpr int kBStride = kQRows + 8;        // bf16 per (split, c) row of the P^ tile in LDS
+
+__global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
+                                                const uint32_t *__restrict__ codes, const float *__restrict__ scales,
+                                                double *ws)
+{
+    __shared__ __attribute__((aligned(16))) float sp[kQRows * kPStride];
+    __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const WorkItem it = dp.q_m_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int m = (int)d.m, cb = it.a;
+    const int col0 = cb * 128;
+    const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
+    const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
+    const uint16_t *g = grads + d.grad_off;
+    const uint32_t *cw = codes + d.word_off;
+    const uint16_t *psT = reinterpret_cast<const uint16_t *>(ws + d.psT_off);
+    const int nblk_row = m >> 7;
+
+    uint4 rg[4], rb[3];
+    uint32_t rcw[4];
+    float rs[4];
+    auto load_chunk = [&](int64_t i0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 4, oct = idx & 15;
+            const int64_t row = i0 + rr;
+            if (row < row1) {
+                rg[s] = *reinterpret_cast<const uint4 *>(g + row * m + col0 + oct * 8);
+                rcw[s] = cw[(row * m + col0) / 8 + oct];
+                rs[s] = scales[d.scale_off + row * nblk_row + cb];
+            } else {
+                rg[s] = make_uint4(0, 0, 0, 0); rcw[s] = 0; rs[s] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int idx = tid + 256 * s, br = idx >> 3, part = idx & 7;
+            const int64_t i = i0 + part * 8;
+            rb[s] = (i < d.n_pad) ? *reinterpret_cast<const uint4 *>(psT + (int64_t)br * d.n_pad + i) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 4, oct = idx & 15;
+            const uint32_t w4[4] = {rg[s].x, rg[s].y, rg[s].z, rg[s].w};
+            const float step = rs[s] * inv_levels(4);
+            float p[8];
+#pragma unroll
+            for (int i2 = 0; i2 < 4; ++i2) {
+                p[2 * i2] = __builtin_fmaf(step, (float)code_field(rcw[s], 2 * i2, 4), __uint_as_float(w4[i2] << 16));
+                p[2 * i2 + 1] = __builtin_fmaf(step, (float)code_field(rcw[s], 2 * i2 + 1, 4),
+                                               __uint_as_float(w4[i2] & 0xFFFF0000u));
+            }
+            float4 *dst = reinterpret_cast<float4 *>(sp + rr * kPStride + oct * 8);
+            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
+            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+        }
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int idx = tid + 256 * s, br = idx >> 3, part = idx & 7;
+            *reinterpret_cast<uint4 *>(sb + br * kBStride + part * 8) = rb[s];
+        }
+    };
+
+    // the matrix cores accumulate one 64-row chunk in fp32; chunks are added up in fp64
+    f32x16 acc;
+    double acc64[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc64[v] = 0.0; }
+    const int r32 = lane & 31, ig = lane >> 5;
+
+    load_chunk(row0);
+    for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
+        __syncthreads();
+        store_chunk();
+        __syncthreads();
+        if (i0 + kQRows < row1) load_chunk(i0 + kQRows);
+#pragma unroll
+        for (int ks = 0; ks < kQRows / 16; ++ks) {
+            Frag b0, b1, b2, ah, am, al;
+            b0.u = *reinterpret_cast<const uint4 *>(sb + (0 * 32 + r32) * kBStride + ks * 16 + ig * 8);
+            b1.u = *reinterpret_cast<const uint4 *>(sb + (1 * 32 + r32) * kBStride + ks * 16 + ig * 8);
+            b2.u = *reinterpret_cast<const uint4 *>(sb + (2 * 32 + r32) * kBStride + ks * 16 + ig * 8);
+            float h[8], mm[8], l[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float x = sp[(ks * 16 + ig * 8 + j) * kPStride + 32 * wave + r32];
+                split3(x, h[j], mm[j], l[j]);
+            }
+            ah.u = make_uint4(pack_hi16(h[0], h[1]), pack_hi16(h[2], h[3]), pack_hi16(h[4], h[5]), pack_hi16(h[6], h[7]));
+            am.u = make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+            al.u = make_uint4(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]), pack_hi16(l[4], l[5]), pack_hi16(l[6], l[7]));
+            acc = mfma(ah, b0, acc);
+            acc = mfma(ah, b1, acc);
+            acc = mfma(am, b0, acc);
+            acc = mfma(ah, b2, acc);
+            acc = mfma(al, b0, acc);
+            acc = mfma(am, b1, acc);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
+    }
+    // partial sums of this row tile, added in tile order by the reduction kernel
+    double *out = ws + d.qpart_off + ((int64_t)it.b * m + col0 + 32 * wave) * 32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int krow = 8 * (v >> 2) + 4 * ig + (v & 3);
+        out[krow * 32 + r32] = acc64[v];
+    }
+}
+
+// ------------------------------------------------------------------ err pass
+// One wave per (32 rows, run of 128-column blocks).  The rank-32 reconstruction P^ Q+^T of a
+// 32 x 128 tile comes from the matrix cores (splits of both factors, six products), goes through a
+// wave-private LDS tile to turn the accumulator layout into the octet layout (lane = 8 consecutive
+// columns of a row, 16 lanes = one scale block), and the rest is the element-wise work of the
+// octet family: decode, subtract, block max-norm by DPP, fixed-point stochastic rounding, pack.
+// The gradient loads of a block are issued before its matrix-core phase and consumed after it.
+constexpr int kEStride = 128 + 4;           // floats per row of the reconstruction tile in LDS
+
+__global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
+                                                  float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
+{
+    __shared__ __attribute__((aligned(16))) float sacc_all[2][32 * kEStride];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 2 + (threadIdx.x >> 6)));
+    if (item >= dp.n_err_m) return;
+    float *sacc = sacc_all[wave];
+    const WorkItem it = dp.err_m_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int m = (int)d.m;
+    const int64_t row0 = it.a;
+    const uint16_t *g = grads + d.grad_off;
+    uint32_t *cw = codes + d.word_off;
+    const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
+    const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
+    const int r32 = lane & 31, cg = lane >> 5;
+    const int rsub = lane >> 4, oct = lane & 15;
+    const int nblk_row = m >> 7;
+
+    Frag A[3][2];
+    {
+        const int64_t row = row0 + r32;
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                A[s][ks].u = (row < d.n) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row) * 32 + ks * 16 + cg * 8)
+                                         : make_uint4(0, 0, 0, 0);
+    }
+    for (int cb = it.b; cb < it.b + it.c; ++cb) {
+        const int col0 = cb * 128;
+        uint4 rg[8];
+        uint32_t rcw[8];
+        float rs[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t row = row0 + 4 * u + rsub;
+            if (row < d.n) {
+                rg[u] = *reinterpret_cast<const uint4 *>(g + row * m + col0 + oct * 8);
+                rcw[u] = cw[(row * m + col0) / 8 + oct];
+                rs[u] = scales[d.scale_off + row * nblk_row + cb];
+            } else {
+                rg[u] = make_uint4(0, 0, 0, 0); rcw[u] = 0; rs[u] = 0.0f;
+            }
+        }
+        // matrix-core phase: four 32 x 32 tiles of the reconstruction
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            Frag B[3][2];
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    B[s][ks].u = *reinterpret_cast<const uint4 *>(Qs + ((int64_t)s * m + col0 + 32 * t + r32) * 32 + ks * 16 + cg * 8);
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                acc = mfma(A[0][ks], B[0][ks], acc);
+                acc = mfma(A[0][ks], B[1][ks], acc);
+                acc = mfma(A[1][ks], B[0][ks], acc);
+                acc = mfma(A[0][ks], B[2][ks], acc);
+                acc = mfma(A[2][ks], B[0][ks], acc);
+                acc = mfma(A[1][ks], B[1][ks], acc);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[(8 * (v >> 2) + 4 * cg + (v & 3)) * kEStride + 32 * t + r32] = acc[v];
+        }
+        __builtin_amdgcn_wave_barrier();
+        // element-wise phase in the octet layout
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int rr = 4 * u + rsub;
+            const int64_t row = row0 + rr;
+            const float4 a0 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 8);
+            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 8 + 4);
+            const float rec[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const uint32_t w4[4] = {rg[u].x, rg[u].y, rg[u].z, rg[u].w};
+            const float step = rs[u] * inv_levels(4);
+            float x[8];
+            float a = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
+                const float pv = __builtin_fmaf(step, (float)code_field(rcw[u], e, 4), gv);
+                x[e] = pv - rec[e];
+                a = fmaxf(a, fabsf(x[e]));
+            }
+            // 16 lanes = one 128-column block
+            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0xB1, 0xF, 0xF, true)));
+            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x4E, 0xF, 0xF, true)));
+            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
+            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
+            const float inv16 = (a > 0.0f) ? (7.0f / a) * 65536.0f : 0.0f;
+            const int64_t o = (row * m + col0) / 8 + oct;
+            uint32_t rnd[4];
+            philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) word |= quantise_field(x[e], inv16, draw16(rnd, e), 0xFu) << (4 * e);
+            if (row < d.n) {
+                cw[o] = word;
+                if (oct == 0) scales[d.scale_off + row * nblk_row + cb] = a;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+}  // namespace
+
+void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                 const float *Q, float *P, double *ws, hipStream_t st, bool prep_only, bool main_only)
+{
+    if (dp.n_p_m <= 0) return;
+    if (!main_only)
+        hipLaunchKernelGGL(k_split_q_state, dim3(dp.n_split_q), dim3(256), 0, st, dp, Q, ws);
+    if (!prep_only)
+        hipLaunchKernelGGL(k_p_mfma, dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                           codes, scales, P, (const double *)ws);
+}
+
+void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st)
+{
+    if (dp.n_split_p <= 0) return;
+    hipLaunchKernelGGL(k_split_p_hat, dim3(dp.n_split_p), dim3(256), 0, st, dp, Phat, ws);
+}
+
+void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, double *ws,
+                 hipStream_t st)
+{
+    if (dp.n_q_m <= 0) return;
+    hipLaunchKernelGGL(k_q_mfma, dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
+                       scales, ws);
+}
+
+void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,
+                   uint64_t step, hipStream_t st)
+{
+    if (dp.n_err_m <= 0) return;
+    hipLaunchKernelGGL(k_err_mfma, dim3((dp.n_err_m + 1) / 2), dim3(128), 0, st, dp,
+                       reinterpret_cast<const uint16_t *>(grads), codes, scales, ws, (uint32_t)step, (uint32_t)(step >> 32));
+}
+
+void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st)
+{
+    if (dp.n_split_qn <= 0) return;
+    hipLaunchKernelGGL(k_split_q_new, dim3(dp.n_split_qn), dim3(256), 0, st, dp, Qn, ws);
+}
+
+}  // namespace conef

@@ -7,6 +7,7 @@ namespace conef {
 
 namespace {
 constexpr int kOk = 0, kEinval = -1, kEnomem = -2;
+constexpr int kMfmaPasses = 7;      // bit 0: P pass, bit 1: Q+ pass, bit 2: err pass
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t v, int64_t a) { return (v + a - 1) / a; }
@@ -72,12 +73,23 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 if ((d.m8 % lr) != 0 || lr < (block / 8)) d.path = kPathGeneric;
                 d.lr_shift = log2i(lr);
             }
-            if (d.path == kPathOctet) plan.any_octet = true; else plan.any_generic = true;
+            // MFMA family: dense rank-32 contractions on the matrix cores
+            if (rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0) d.path = kPathMfma;
+            if (d.path == kPathOctet) plan.any_octet = true;
+            else if (d.path == kPathMfma) plan.any_mfma = true;
+            else plan.any_generic = true;
+            d.n_pad = (int32_t)round_up(d.n, 32);
+            if (d.path == kPathMfma) {
+                d.qsT_off = wd; wd += round_up(3 * 32 * d.m * 2 / 8, 32);
+                d.psT_off = wd; wd += round_up(3 * 32 * (int64_t)d.n_pad * 2 / 8, 32);
+                d.ps_off = wd;  wd += round_up(3 * 32 * d.n * 2 / 8, 32);
+                d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
+            }
 
             d.n_gram_tiles = (int32_t)ceil_div(d.n, kGramRows);
             d.gram_off = wd; wd += (int64_t)d.n_gram_tiles * rank * rank;
             d.rinv_off = wd; wd += rank * rank;
-            d.q_tile_rows = d.path == kPathOctet ? q_rows : kGenQRows;
+            d.q_tile_rows = d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : kGenQRows;
             d.n_q_tiles = (int32_t)ceil_div(d.n, d.q_tile_rows);
             d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * rank, 32);
             d.n_p_chunks = 1;
@@ -99,13 +111,36 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
 
         for (int l = 0; l < n_mats; ++l) {
             const MatDesc &d = plan.mats[l];
-            if (d.path == kPathGeneric) {
-                for (int64_t r0 = 0; r0 < d.n; r0 += 4) plan.p_items.push_back({l, (int32_t)r0, 0, 0});
-                const int32_t nct = (int32_t)ceil_div(d.m, kGenQCols);
+            // passes of the MFMA family that exist; the others fall back to the generic kernels
+            const bool mf = d.path == kPathMfma;
+            const bool mf_p = mf && (kMfmaPasses & 1), mf_q = mf && (kMfmaPasses & 2), mf_e = mf && (kMfmaPasses & 4);
+            if (mf_p) {
+                for (int64_t r0 = 0; r0 < d.n; r0 += kMfmaRows) plan.p_m_items.push_back({l, (int32_t)r0, 0, 0});
+                for (int64_t k0 = 0; k0 < d.m; k0 += 64) plan.split_q_items.push_back({l, (int32_t)(k0 / 64), 0, 0});
+            }
+            if (mf_q) {
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
-                    for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
+                    for (int32_t cb = 0; cb < (int32_t)(d.m / 128); ++cb) plan.q_m_items.push_back({l, cb, rt, 0});
+            }
+            if (mf_q || mf_e)
+                for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.split_p_items.push_back({l, (int32_t)(r0 / 64), 0, 0});
+            if (mf_e) {
+                for (int64_t k0 = 0; k0 < d.m; k0 += 64) plan.split_qn_items.push_back({l, (int32_t)(k0 / 64), 0, 0});
+                const int32_t ncb = (int32_t)(d.m / 128);
+                for (int64_t r0 = 0; r0 < d.n; r0 += 32)
+                    for (int32_t cb0 = 0; cb0 < ncb; cb0 += 8)
+                        plan.err_m_items.push_back({l, (int32_t)r0, cb0, std::min<int32_t>(8, ncb - cb0)});
+            }
+            if (d.path == kPathGeneric || mf) {
+                if (!mf_p)
+                    for (int64_t r0 = 0; r0 < d.n; r0 += 4) plan.p_items.push_back({l, (int32_t)r0, 0, 0});
+                const int32_t nct = (int32_t)ceil_div(d.m, kGenQCols);
+                if (!mf_q)
+                    for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
+                        for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
                 // 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ... (16 per wave)
-                for (int64_t b0 = 0; b0 < d.nblk; b0 += 64) plan.err_items.push_back({l, (int32_t)(b0 / 64), 0, 0});
+                if (!mf_e)
+                    for (int64_t b0 = 0; b0 < d.nblk; b0 += 64) plan.err_items.push_back({l, (int32_t)(b0 / 64), 0, 0});
             } else {
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;

@@ -15,7 +15,8 @@ constexpr int kGenQCols = 256;      // columns per workgroup in the generic pass
 constexpr int kFastMaxRank = 8;     // the octet family holds rank <= 8 in registers
 constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (one lane per row)
 
-enum Path { kPathGeneric = 0, kPathOctet = 1 };
+enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
+constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
 
 // One matrix of the model as the kernels see it (device copy is an array of these).
 // Workspace offsets are in doubles from the start of the workspace.
@@ -35,7 +36,12 @@ struct MatDesc {
     int32_t lr_shift;               // log2(lanes per row segment), 3..6
     int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
     int32_t m8;                     // m / 8
-    int32_t pad_;
+    int32_t n_pad;                  // MFMA family: n rounded up to a multiple of 32
+    // MFMA family: bf16 triple splits of the factors (x = hi + mid + lo), offsets in doubles
+    int64_t qsT_off;                // Q_state, transposed: [3][32][m]
+    int64_t psT_off;                // P^, transposed:      [3][32][n_pad]
+    int64_t ps_off;                 // P^, row-major:       [3][n][32]
+    int64_t qs_off;                 // Q+, row-major:       [3][m][32]
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -49,7 +55,7 @@ struct Plan {
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
     size_t qd_off = 0;              // doubles: fp64 copy of Q_state (q_elems entries), 0 if unused
-    bool any_octet = false, any_generic = false, any_p_chunks = false;
+    bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;
     size_t ws_doubles = 0;
     size_t workspace_bytes = 0;
     // generic family
@@ -60,6 +66,13 @@ struct Plan {
     std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk)
     std::vector<WorkItem> q_f_items;    // (mat, strip, row tile)
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
+    // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
+    std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
+    std::vector<WorkItem> q_m_items;    // (mat, column block of 128, row tile)
+    std::vector<WorkItem> err_m_items;  // (mat, column block of 128, first row, rows)
+    std::vector<WorkItem> split_q_items;   // split Q_state  (transposed):  (mat, first k / 64)
+    std::vector<WorkItem> split_p_items;   // split P^ (both layouts):      (mat, first row / 64)
+    std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
     // shared
     std::vector<WorkItem> pred_items;   // reduce partial P: (mat, first entry of n*r)
     std::vector<WorkItem> gram_items;   // (mat, gram tile)

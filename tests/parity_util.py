@@ -32,9 +32,12 @@ def unpack(codes: np.ndarray, N: int, bits: int) -> np.ndarray:
     return np.where(f >= (1 << (bits - 1)), f - (1 << bits), f).astype(np.int32)
 
 
-def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what=""):
+def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what="", rec_oracle=None):
     """Applies the boundary rule.  x_oracle: the oracle's residual (fp32, flat).  Returns the number
-    of excused mismatches."""
+    of excused mismatches.  rec_oracle (flat, sum_c |P^[i,c]| |Q+[k,c]|: the size of the terms of
+    the reconstruction) is given for the matrix-core family only: there the factors carry fp32
+    rounding, so the residual p - P^ Q+^T has an absolute error of ~1e-6 of those terms, and the
+    1e-6 window is taken relative to max(a, rec_block) instead of the block max-norm a."""
     s = R.levels(bits)
     g = unpack(np.asarray(got_codes), N, bits)
     w = unpack(np.asarray(want_codes), N, bits)
@@ -52,6 +55,8 @@ def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step
         f = float(u - np.floor(u))
         xi = R.rand16(seed, mat, step, int(j)) / 65536.0
         tol = 1e-6 * max(1.0, float(u))
+        if rec_oracle is not None:
+            tol *= max(1.0, float(np.abs(rec_oracle[b0:min(N, b0 + block)]).max()) / float(a))
         near_draw = abs(f - xi) <= tol
         near_grid = abs(float(u) - round(float(u))) <= tol
         assert near_draw or near_grid, (f"{what}: code {j} differs although the pre-rounding value is not near a "
@@ -125,6 +130,11 @@ class GpuModel:
         off = self.m.offsets[l]["scale_off"]
         return self.buf["scales"][off:off + R.n_blocks(n * m, self.m.block)].cpu().numpy()
 
+    def set_Q(self, l, Q):
+        off = self.m.offsets[l]["q_off"]
+        t = self.torch.from_numpy(np.ascontiguousarray(Q, np.float32).ravel())
+        self.buf["Q"][off:off + t.numel()] = t.to(self.buf["Q"].device)
+
     def set_state(self, l, codes, scales):
         torch = self.torch
         dev = self.buf["codes"].device
@@ -133,8 +143,9 @@ class GpuModel:
         self.buf["scales"][o["scale_off"]:o["scale_off"] + scales.size] = torch.from_numpy(scales).to(dev)
 
 
-def compare_step(gpu: GpuModel, oracle_out, oracle: OracleModel, step, pq_tol, what=""):
-    """Compares P, Q, scales and codes of every matrix after a step; returns total excused codes."""
+def compare_step(gpu: GpuModel, oracle_out, oracle: OracleModel, step, pq_tol, what="", fp32_factors=False):
+    """Compares P, Q, scales and codes of every matrix after a step; returns total excused codes.
+    fp32_factors: the path under test accumulates the factors in fp32 (matrix cores), see check_codes."""
     excused = 0
     for l, (Ph, Qn, x) in enumerate(oracle_out):
         st = oracle.states[l]
@@ -145,6 +156,15 @@ def compare_step(gpu: GpuModel, oracle_out, oracle: OracleModel, step, pq_tol, w
         assert eP <= pq_tol, f"{tag}: P rel err {eP}"
         assert eQ <= pq_tol, f"{tag}: Q rel err {eQ}"
         gs = gpu.mat_scales(l)
-        assert np.all(np.abs(gs - st.scales) <= 1e-6 * np.abs(st.scales)), f"{tag}: scales differ"
-        excused += check_codes(gpu.mat_codes(l), st.codes, x, N, oracle.bits, oracle.block, oracle.seed, l, step, tag)
+        rec = None
+        ref_mag = np.abs(st.scales)
+        if fp32_factors:
+            # magnitude of the terms of the reconstruction: sum_c |P^[i,c]| |Q+[k,c]|
+            rec = (np.abs(Ph).astype(np.float64) @ np.abs(Qn).astype(np.float64).T).astype(np.float32).ravel()
+            pad = (-N) % oracle.block
+            blk_rec = np.abs(np.concatenate([rec, np.zeros(pad, np.float32)])).reshape(-1, oracle.block).max(1)
+            ref_mag = np.maximum(ref_mag, blk_rec)
+        assert np.all(np.abs(gs - st.scales) <= 1e-6 * ref_mag), f"{tag}: scales differ"
+        excused += check_codes(gpu.mat_codes(l), st.codes, x, N, oracle.bits, oracle.block, oracle.seed, l, step, tag,
+                               rec_oracle=rec)
     return excused

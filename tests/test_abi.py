@@ -53,7 +53,7 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.conef_step(ctx, 256, 256, 256, 0, 256, 256, 256, 0, 0) == B.EINVAL       # null Q_state
     assert L.conef_step(ctx, 260, 256, 256, 256, 256, 256, 256, 0, 0) == B.EINVAL     # grads not 16-byte aligned
     assert L.conef_step(ctx, 256, 256, 256, 256, 256, 256, 128, 0, 0) == B.EINVAL     # workspace not 256-byte aligned
-    assert L.conef_step_err(ctx, 256, 256, 258, 256, 256, 0, 0) == B.EINVAL           # scales not 4-byte aligned
+    assert L.conef_step_err(ctx, 256, 256, 258, 256, 256, 256, 0, 0) == B.EINVAL           # scales not 4-byte aligned
     assert L.conef_step(None, 256, 256, 256, 256, 256, 256, 256, 0, 0) == B.EINVAL
     assert L.conef_reset_error(ctx, 0, 0, 0) == B.EINVAL
     assert L.conef_decode_error(ctx, 256, 256, 0, 0) == B.EINVAL
