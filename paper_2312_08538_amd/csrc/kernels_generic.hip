@@ -149,31 +149,48 @@ __global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double 
     }
 }
 
+// P^ = P * R^-1, one thread per row.  The rows of R^-1 are at wave-uniform addresses (scalar
+// loads, SGPR operands of the fp64 FMAs); each output column is accumulated over k <= c.
 template <int RP>
-__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws)
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *__restrict__ ws)
 {
     const WorkItem it = dp.apply_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int r = dp.rank;
-    __shared__ double rinv[kMaxRank * kMaxRank];
-    for (int e = threadIdx.x; e < r * r; e += 256) rinv[e] = ws[d.rinv_off + e];
-    __syncthreads();
+    const double *__restrict__ rinv = ws + d.rinv_off;
     const int64_t row = (int64_t)it.a + threadIdx.x;
     if (row >= d.n) return;
     float *prow = P + d.p_off + row * r;
-    float in[RP];
+    double out[RP];
 #pragma unroll
-    for (int c = 0; c < RP; ++c) in[c] = (c < r) ? prow[c] : 0.0f;
+    for (int c = 0; c < RP; ++c) out[c] = 0.0;
+    if (r == RP) {
+        // full rank for this instantiation: fixed trip counts, whole rows of R^-1 per scalar load
+        float in32[RP];
 #pragma unroll
-    for (int c = 0; c < RP; ++c) {
-        if (c < r) {
-            double s = 0.0;
+        for (int c4 = 0; c4 < RP / 4; ++c4) {
+            const float4 v = reinterpret_cast<const float4 *>(prow)[c4];
+            in32[4 * c4] = v.x; in32[4 * c4 + 1] = v.y; in32[4 * c4 + 2] = v.z; in32[4 * c4 + 3] = v.w;
+        }
 #pragma unroll
-            for (int k = 0; k < RP; ++k)
-                if (k <= c) s += (double)in[k] * rinv[k * r + c];
-            prow[c] = (float)s;
+        for (int k = 0; k < RP; ++k) {
+            const double in = (double)in32[k];
+#pragma unroll
+            for (int c = 0; c < RP; ++c)
+                if (c >= k) out[c] = __builtin_fma(in, rinv[k * RP + c], out[c]);
+        }
+    } else {
+        for (int k = 0; k < r; ++k) {
+            const double in = (double)prow[k];
+            const double *rk = rinv + k * r;
+#pragma unroll
+            for (int c = 0; c < RP; ++c)
+                if (c < r) out[c] = __builtin_fma(in, rk[c], out[c]);      // rinv[k][c] = 0 for c < k
         }
     }
+#pragma unroll
+    for (int c = 0; c < RP; ++c)
+        if (c < r) prow[c] = (float)out[c];
 }
 
 // ---------------------------------------------------------------- pass 2: Q+ = p^T * P^

@@ -113,37 +113,39 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const uint32_t *cw = codes + d.word_off;
     const uint16_t *qsT = reinterpret_cast<const uint16_t *>(ws + d.qsT_off);
 
-    // global-load roles
-    uint4 rg[4], rq[3], rc;
-    auto load_stage = [&](int k0) {
+    // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
+    struct StageRegs {
+        uint4 g[4], q[3], c;
+    };
+    auto load_stage = [&](StageRegs &r, int k0) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
             const int64_t row = row0 + rr;
-            rg[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
+            r.g[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
         }
         {
             const int rr = tid >> 1, half = tid & 1;
             const int64_t row = row0 + rr;
-            rc = (row < d.n) ? *reinterpret_cast<const uint4 *>(cw + (row * m + k0) / 8 + half * 4) : make_uint4(0, 0, 0, 0);
+            r.c = (row < d.n) ? *reinterpret_cast<const uint4 *>(cw + (row * m + k0) / 8 + half * 4) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
-            rq[s] = *reinterpret_cast<const uint4 *>(qsT + (int64_t)qr * m + k0 + oct * 8);
+            r.q[s] = *reinterpret_cast<const uint4 *>(qsT + (int64_t)qr * m + k0 + oct * 8);
         }
     };
-    auto store_stage = [&]() {
+    auto store_stage = [&](const StageRegs &r) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
-            *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = rg[s];
+            *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
         }
-        *reinterpret_cast<uint4 *>(sc + (tid >> 1) * kCStride + (tid & 1) * 4) = rc;
+        *reinterpret_cast<uint4 *>(sc + (tid >> 1) * kCStride + (tid & 1) * 4) = r.c;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
-            *reinterpret_cast<uint4 *>(sq + qr * kGStride + oct * 8) = rq[s];
+            *reinterpret_cast<uint4 *>(sq + qr * kGStride + oct * 8) = r.q[s];
         }
     };
 
@@ -158,12 +160,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const int64_t my_row = row0 + my_row_in_tile;
     const int nblk_row = m >> 7;
 
-    load_stage(0);
-    for (int k0 = 0; k0 < m; k0 += kStage) {
-        __syncthreads();                 // everybody is done reading the previous stage
-        store_stage();
-        __syncthreads();
-        if (k0 + kStage < m) load_stage(k0 + kStage);
+    auto compute_stage = [&](int k0) {
 #pragma unroll
         for (int ks = 0; ks < kStage / 16; ++ks) {
             Frag bg, bq, a0, a1, a2;
@@ -199,6 +196,23 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
                 accS[v] = 0.0f;
             }
         }
+    };
+
+    // m is a multiple of 128, so the number of stages is even: two stages per trip, one register set each
+    StageRegs ra, rb;
+    load_stage(ra, 0);
+    load_stage(rb, kStage);
+    for (int k0 = 0; k0 < m; k0 += 2 * kStage) {
+        __syncthreads();                 // everybody is done reading the previous stage
+        store_stage(ra);
+        __syncthreads();
+        if (k0 + 2 * kStage < m) load_stage(ra, k0 + 2 * kStage);
+        compute_stage(k0);
+        __syncthreads();
+        store_stage(rb);
+        __syncthreads();
+        if (k0 + 3 * kStage < m) load_stage(rb, k0 + 3 * kStage);
+        compute_stage(k0 + kStage);
     }
     if (my_row < d.n) {
         float *out = P + d.p_off + my_row * 32;
@@ -380,7 +394,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 // columns of a row, 16 lanes = one scale block), and the rest is the element-wise work of the
 // octet family: decode, subtract, block max-norm by DPP, fixed-point stochastic rounding, pack.
 // The gradient loads of a block are issued before its matrix-core phase and consumed after it.
-constexpr int kEStride = 128 + 4;           // floats per row of the reconstruction tile in LDS
+// LDS tile of the reconstruction: a row holds its 32 four-column chunks in two regions, the even
+// chunks (first half of every octet) at words 0..63 and the odd chunks at words 80..143.  A lane
+// that owns octet `oct` reads chunk oct of each region, so consecutive lanes read consecutive
+// 16-byte chunks; the writers (32 consecutive columns per half-wave) cover all 32 banks once.
+constexpr int kEStride = 144;               // floats per row of the reconstruction tile in LDS
+__device__ __forceinline__ int rec_pos(int k) { return ((k >> 3) << 2) + (k & 3) + ((k >> 2) & 1) * 80; }
 
 __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
@@ -395,13 +414,17 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
     const MatDesc d = dp.mats[it.mat];
     const int m = (int)d.m;
     const int64_t row0 = it.a;
-    const uint16_t *g = grads + d.grad_off;
-    uint32_t *cw = codes + d.word_off;
+    const int nblk_row = m >> 7;
+    // wave-uniform bases; everything a lane adds to them fits in 32 bits (32 rows of one matrix)
+    const uint16_t *g = grads + d.grad_off + row0 * m;
+    uint32_t *cw = codes + d.word_off + row0 * (m >> 3);
+    float *sc = scales + d.scale_off + row0 * nblk_row;
     const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
     const int r32 = lane & 31, cg = lane >> 5;
     const int rsub = lane >> 4, oct = lane & 15;
-    const int nblk_row = m >> 7;
+    const int rows_left = (int)((d.n - row0 < 32) ? d.n - row0 : 32);
+    const uint32_t octet0 = (uint32_t)((row0 * m) >> 3);       // index of the tile's first octet in the matrix
 
     Frag A[3][2];
     {
@@ -410,8 +433,8 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
         for (int s = 0; s < 3; ++s)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                A[s][ks].u = (row < d.n) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row) * 32 + ks * 16 + cg * 8)
-                                         : make_uint4(0, 0, 0, 0);
+                A[s][ks].u = (r32 < rows_left) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row) * 32 + ks * 16 + cg * 8)
+                                               : make_uint4(0, 0, 0, 0);
     }
     for (int cb = it.b; cb < it.b + it.c; ++cb) {
         const int col0 = cb * 128;
@@ -420,47 +443,51 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
         float rs[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int64_t row = row0 + 4 * u + rsub;
-            if (row < d.n) {
-                rg[u] = *reinterpret_cast<const uint4 *>(g + row * m + col0 + oct * 8);
-                rcw[u] = cw[(row * m + col0) / 8 + oct];
-                rs[u] = scales[d.scale_off + row * nblk_row + cb];
+            const int rr = 4 * u + rsub;
+            if (rr < rows_left) {
+                rg[u] = *reinterpret_cast<const uint4 *>(g + (uint32_t)(rr * m + col0 + oct * 8));
+                rcw[u] = cw[(uint32_t)(rr * (m >> 3) + (col0 >> 3) + oct)];
+                rs[u] = sc[(uint32_t)(rr * nblk_row + cb)];
             } else {
                 rg[u] = make_uint4(0, 0, 0, 0); rcw[u] = 0; rs[u] = 0.0f;
             }
         }
-        // matrix-core phase: four 32 x 32 tiles of the reconstruction
+        // operand splits of Q+ for the four 32-column tiles: all loads issued up front
+        Frag B[4][3][2];
+        const uint16_t *qb = Qs + (int64_t)col0 * 32;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            Frag B[3][2];
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int s = 0; s < 3; ++s)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
-                    B[s][ks].u = *reinterpret_cast<const uint4 *>(Qs + ((int64_t)s * m + col0 + 32 * t + r32) * 32 + ks * 16 + cg * 8);
+                    B[t][s][ks].u = *reinterpret_cast<const uint4 *>(qb + (uint32_t)((s * m + 32 * t + r32) * 32 + ks * 16 + cg * 8));
+        // matrix-core phase: four 32 x 32 tiles of the reconstruction
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                acc = mfma(A[0][ks], B[0][ks], acc);
-                acc = mfma(A[0][ks], B[1][ks], acc);
-                acc = mfma(A[1][ks], B[0][ks], acc);
-                acc = mfma(A[0][ks], B[2][ks], acc);
-                acc = mfma(A[2][ks], B[0][ks], acc);
-                acc = mfma(A[1][ks], B[1][ks], acc);
+                acc = mfma(A[0][ks], B[t][0][ks], acc);
+                acc = mfma(A[0][ks], B[t][1][ks], acc);
+                acc = mfma(A[1][ks], B[t][0][ks], acc);
+                acc = mfma(A[0][ks], B[t][2][ks], acc);
+                acc = mfma(A[2][ks], B[t][0][ks], acc);
+                acc = mfma(A[1][ks], B[t][1][ks], acc);
             }
+            const int pos = rec_pos(32 * t + r32);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[(8 * (v >> 2) + 4 * cg + (v & 3)) * kEStride + 32 * t + r32] = acc[v];
+            for (int v = 0; v < 16; ++v) sacc[(8 * (v >> 2) + 4 * cg + (v & 3)) * kEStride + pos] = acc[v];
         }
         __builtin_amdgcn_wave_barrier();
         // element-wise phase in the octet layout
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int rr = 4 * u + rsub;
-            const int64_t row = row0 + rr;
-            const float4 a0 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 8);
-            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 8 + 4);
+            const float4 a0 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 4);
+            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + 80 + oct * 4);
             const float rec[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
             const uint32_t w4[4] = {rg[u].x, rg[u].y, rg[u].z, rg[u].w};
             const float step = rs[u] * inv_levels(4);
@@ -479,15 +506,15 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
             const float inv16 = (a > 0.0f) ? (7.0f / a) * 65536.0f : 0.0f;
-            const int64_t o = (row * m + col0) / 8 + oct;
+            const uint32_t orel = (uint32_t)(rr * (m >> 3) + (col0 >> 3) + oct);
             uint32_t rnd[4];
-            philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+            philox4x32_10(octet0 + orel, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
             uint32_t word = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) word |= quantise_field(x[e], inv16, draw16(rnd, e), 0xFu) << (4 * e);
-            if (row < d.n) {
-                cw[o] = word;
-                if (oct == 0) scales[d.scale_off + row * nblk_row + cb] = a;
+            if (rr < rows_left) {
+                cw[orel] = word;
+                if (oct == 0) sc[(uint32_t)(rr * nblk_row + cb)] = a;
             }
         }
         __builtin_amdgcn_wave_barrier();
