@@ -388,26 +388,39 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 }
 
 // ------------------------------------------------------------------ err pass
-// One wave per (32 rows, run of 128-column blocks).  The rank-32 reconstruction P^ Q+^T of a
-// 32 x 128 tile comes from the matrix cores (splits of both factors, six products), goes through a
-// wave-private LDS tile to turn the accumulator layout into the octet layout (lane = 8 consecutive
-// columns of a row, 16 lanes = one scale block), and the rest is the element-wise work of the
-// octet family: decode, subtract, block max-norm by DPP, fixed-point stochastic rounding, pack.
-// The gradient loads of a block are issued before its matrix-core phase and consumed after it.
-// LDS tile of the reconstruction: a row holds its 32 four-column chunks in two regions, the even
-// chunks (first half of every octet) at words 0..63 and the odd chunks at words 80..143.  A lane
-// that owns octet `oct` reads chunk oct of each region, so consecutive lanes read consecutive
-// 16-byte chunks; the writers (32 consecutive columns per half-wave) cover all 32 banks once.
-constexpr int kEStride = 144;               // floats per row of the reconstruction tile in LDS
-__device__ __forceinline__ int rec_pos(int k) { return ((k >> 3) << 2) + (k & 3) + ((k >> 2) & 1) * 80; }
+// One wave per (16 rows, run of 128-column blocks).  The rank-32 reconstruction P^ Q+^T of a
+// 16 x 128 tile comes from the matrix cores (v_mfma_f32_16x16x32_bf16: the whole rank in one
+// instruction; splits of both factors, six products per 16 x 16 tile), goes through a wave-private
+// LDS tile to turn the accumulator layout into the octet layout (lane = 8 consecutive columns of
+// a row, 16 lanes = one scale block), and the rest is the element-wise work of the octet family:
+// decode, subtract, block max-norm by DPP, fixed-point stochastic rounding, pack.  The gradient
+// loads of the next block are issued before the element-wise phase of the current one.
+//
+// Operand layout of v_mfma_f32_16x16x32_bf16: lane l holds A[l%16][8*(l/16) + j],
+// B[8*(l/16) + j][l%16], j = 0..7, and D[4*(l/16) + v][l%16], v = 0..3.
+//
+// LDS tile: a row holds its 32 four-column chunks in two regions, the even chunks (first half of
+// every octet) at words 0..63 and the odd chunks at words 72..135.  A lane that owns octet `oct`
+// reads chunk oct of each region, so consecutive lanes read consecutive 16-byte chunks; the
+// writers (16 consecutive columns per quarter-wave, rows 4 apart) spread over all banks.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kERows = 16;
+constexpr int kEStride = 148;               // floats per row of the reconstruction tile in LDS
+__device__ __forceinline__ int rec_pos(int k) { return ((k >> 3) << 2) + (k & 3) + ((k >> 2) & 1) * 72; }
 
-__global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
+struct ErrOctets {
+    uint4 g[4];
+    uint32_t cw[4];
+    float s[4];
+};
+
+__global__ __launch_bounds__(256) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
 {
-    __shared__ __attribute__((aligned(16))) float sacc_all[2][32 * kEStride];
+    __shared__ __attribute__((aligned(16))) float sacc_all[4][kERows * kEStride];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 2 + (threadIdx.x >> 6)));
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     if (item >= dp.n_err_m) return;
     float *sacc = sacc_all[wave];
     const WorkItem it = dp.err_m_items[item];
@@ -415,88 +428,79 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
     const int m = (int)d.m;
     const int64_t row0 = it.a;
     const int nblk_row = m >> 7;
-    // wave-uniform bases; everything a lane adds to them fits in 32 bits (32 rows of one matrix)
+    // wave-uniform bases; everything a lane adds to them fits in 32 bits (16 rows of one matrix)
     const uint16_t *g = grads + d.grad_off + row0 * m;
     uint32_t *cw = codes + d.word_off + row0 * (m >> 3);
     float *sc = scales + d.scale_off + row0 * nblk_row;
     const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
-    const int r32 = lane & 31, cg = lane >> 5;
-    const int rsub = lane >> 4, oct = lane & 15;
-    const int rows_left = (int)((d.n - row0 < 32) ? d.n - row0 : 32);
+    const int r16 = lane & 15, kg = lane >> 4;       // matrix-core roles
+    const int rsub = lane >> 4, oct = lane & 15;     // octet roles: row 4u + rsub, columns 8 oct ..
+    const int rows_left = (int)((d.n - row0 < kERows) ? d.n - row0 : kERows);
     const uint32_t octet0 = (uint32_t)((row0 * m) >> 3);       // index of the tile's first octet in the matrix
 
-    Frag A[3][2];
-    {
-        const int64_t row = row0 + r32;
+    Frag A[3];
 #pragma unroll
-        for (int s = 0; s < 3; ++s)
+    for (int s = 0; s < 3; ++s)
+        A[s].u = (r16 < rows_left) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row0 + r16) * 32 + kg * 8)
+                                   : make_uint4(0, 0, 0, 0);
+
+    auto load_octets = [&](ErrOctets &o, int cb) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                A[s][ks].u = (r32 < rows_left) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row) * 32 + ks * 16 + cg * 8)
-                                               : make_uint4(0, 0, 0, 0);
-    }
-    for (int cb = it.b; cb < it.b + it.c; ++cb) {
-        const int col0 = cb * 128;
-        uint4 rg[8];
-        uint32_t rcw[8];
-        float rs[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int rr = 4 * u + rsub;
             if (rr < rows_left) {
-                rg[u] = *reinterpret_cast<const uint4 *>(g + (uint32_t)(rr * m + col0 + oct * 8));
-                rcw[u] = cw[(uint32_t)(rr * (m >> 3) + (col0 >> 3) + oct)];
-                rs[u] = sc[(uint32_t)(rr * nblk_row + cb)];
+                o.g[u] = *reinterpret_cast<const uint4 *>(g + (uint32_t)(rr * m + cb * 128 + oct * 8));
+                o.cw[u] = cw[(uint32_t)(rr * (m >> 3) + cb * 16 + oct)];
+                o.s[u] = sc[(uint32_t)(rr * nblk_row + cb)];
             } else {
-                rg[u] = make_uint4(0, 0, 0, 0); rcw[u] = 0; rs[u] = 0.0f;
+                o.g[u] = make_uint4(0, 0, 0, 0); o.cw[u] = 0; o.s[u] = 0.0f;
             }
         }
-        // operand splits of Q+ for the four 32-column tiles: all loads issued up front
-        Frag B[4][3][2];
-        const uint16_t *qb = Qs + (int64_t)col0 * 32;
+    };
+
+    ErrOctets cur;
+    load_octets(cur, it.b);
+    const int cb_end = it.b + it.c;
+    for (int cb = it.b; cb < cb_end; ++cb) {
+        // matrix-core phase: eight 16 x 16 tiles of the reconstruction
+        const uint16_t *qb = Qs + (int64_t)cb * 128 * 32;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 8; ++t) {
+            Frag B[3];
 #pragma unroll
             for (int s = 0; s < 3; ++s)
+                B[s].u = *reinterpret_cast<const uint4 *>(qb + (uint32_t)((s * m + 16 * t + r16) * 32 + kg * 8));
+            f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[0].v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[1].v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[0].v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[2].v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[2].v, B[0].v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[1].v, acc, 0, 0, 0);
+            const int pos = rec_pos(16 * t + r16);
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    B[t][s][ks].u = *reinterpret_cast<const uint4 *>(qb + (uint32_t)((s * m + 32 * t + r32) * 32 + ks * 16 + cg * 8));
-        // matrix-core phase: four 32 x 32 tiles of the reconstruction
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            f32x16 acc;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                acc = mfma(A[0][ks], B[t][0][ks], acc);
-                acc = mfma(A[0][ks], B[t][1][ks], acc);
-                acc = mfma(A[1][ks], B[t][0][ks], acc);
-                acc = mfma(A[0][ks], B[t][2][ks], acc);
-                acc = mfma(A[2][ks], B[t][0][ks], acc);
-                acc = mfma(A[1][ks], B[t][1][ks], acc);
-            }
-            const int pos = rec_pos(32 * t + r32);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[(8 * (v >> 2) + 4 * cg + (v & 3)) * kEStride + pos] = acc[v];
+            for (int v = 0; v < 4; ++v) sacc[(4 * kg + v) * kEStride + pos] = acc[v];
         }
+        // the next block's gradient, codes and scales travel while this block is worked on
+        ErrOctets nxt;
+        if (cb + 1 < cb_end) load_octets(nxt, cb + 1);
         __builtin_amdgcn_wave_barrier();
         // element-wise phase in the octet layout
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int rr = 4 * u + rsub;
             const float4 a0 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 4);
-            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + 80 + oct * 4);
+            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + 72 + oct * 4);
             const float rec[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-            const uint32_t w4[4] = {rg[u].x, rg[u].y, rg[u].z, rg[u].w};
-            const float step = rs[u] * inv_levels(4);
+            const uint32_t w4[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
+            const float step = cur.s[u] * inv_levels(4);
             float x[8];
             float a = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
-                const float pv = __builtin_fmaf(step, (float)code_field(rcw[u], e, 4), gv);
+                const float pv = __builtin_fmaf(step, (float)code_field(cur.cw[u], e, 4), gv);
                 x[e] = pv - rec[e];
                 a = fmaxf(a, fabsf(x[e]));
             }
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
             const float inv16 = (a > 0.0f) ? (7.0f / a) * 65536.0f : 0.0f;
-            const uint32_t orel = (uint32_t)(rr * (m >> 3) + (col0 >> 3) + oct);
+            const uint32_t orel = (uint32_t)(rr * (m >> 3) + cb * 16 + oct);
             uint32_t rnd[4];
             philox4x32_10(octet0 + orel, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
             uint32_t word = 0;
@@ -518,6 +522,7 @@ __global__ __launch_bounds__(128) void k_err_mfma(DevicePlan dp, const uint16_t 
             }
         }
         __builtin_amdgcn_wave_barrier();
+        if (cb + 1 < cb_end) cur = nxt;
     }
 }
 
@@ -552,7 +557,7 @@ void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, flo
                    uint64_t step, hipStream_t st)
 {
     if (dp.n_err_m <= 0) return;
-    hipLaunchKernelGGL(k_err_mfma, dim3((dp.n_err_m + 1) / 2), dim3(128), 0, st, dp,
+    hipLaunchKernelGGL(k_err_mfma, dim3((dp.n_err_m + 3) / 4), dim3(256), 0, st, dp,
                        reinterpret_cast<const uint16_t *>(grads), codes, scales, ws, (uint32_t)step, (uint32_t)(step >> 32));
 }
 
