@@ -132,6 +132,26 @@ def run_oracle_sample(w):
                                                  f"{100.0 * tot / w.elements:.1f} % of it), one step from zero error"
 
 
+def calibrate_copy(w):
+    """One launch of the library's plain decode kernel over the workload's (zero) state: it reads
+    every code word and scale once and writes one fp32 value per element, nothing else, so the
+    byte counters of this launch give the scale of FETCH_SIZE / WRITE_SIZE."""
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+
+    model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+    codes = torch.zeros(model.sizes["code_words"], dtype=torch.int32, device="cuda:0")
+    scales = torch.zeros(model.sizes["n_scales"], dtype=torch.float32, device="cuda:0")
+    e = torch.zeros(model.sizes["grad_elems"], dtype=torch.float32, device="cuda:0")   # also evicts the state from the caches
+    torch.cuda.synchronize()
+    B.conef_decode_error(model.ctx, codes, scales, e, model.stream_handle())
+    torch.cuda.synchronize()
+    rd = 4 * (sum(-(-n * m // (32 // w.bits)) for n, m in w.layout) + sum(-(-n * m // w.block) for n, m in w.layout))
+    print(f"calibration launch k_decode: reads {rd} bytes, writes {4 * w.elements} bytes", file=sys.stderr)
+    model.close()
+
+
 def load_traffic(workload: str, stage: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if
     one exists for this workload (profiles/hbm_traffic.json), else None."""
@@ -152,6 +172,9 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
+                         "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is one worker's share of the method on ONE GPU; it has no collectives "
@@ -164,6 +187,8 @@ def main():
     from paper_2312_08538_amd import workloads as wl
 
     w = wl.WORKLOADS[a.workload]
+    if a.calibrate_copy:
+        calibrate_copy(w)
     ms, stage_ms, finite = run_gpu(w, a.steps, a.warmup)
     if not finite:
         print("bench.py: non-finite factors after the timed run", file=sys.stderr)
