@@ -24,6 +24,8 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+constexpr int kErrTileElems = 3 * 128 * 32;    // bf16 entries of one column block's splits of Q+
+
 union Frag {
     bf16x8 v;
     uint4 u;
@@ -245,22 +247,27 @@ __global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float 
     split_transposed_tile(src, reinterpret_cast<uint16_t *>(ws + d.psT_off), (int)d.n, d.n_pad, r0);
 }
 
-// Q+ (m x 32): row-major splits for the err pass.
+// Q+ (m x 32): splits for the err pass, in the order its matrix-core tiles read them:
+// [column block of 128][split][t][cc][32] holds row k = 128 cb + 8 cc + t of the split, so that a
+// block's operands are one contiguous 24 KB piece and tile t's 16 rows (one per octet cc) are adjacent.
 __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float *__restrict__ Qn, double *ws)
 {
     const WorkItem it = dp.split_qn_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const float *src = Qn + d.q_off;
     const int r0 = it.a * 64;
-    uint16_t *rm = reinterpret_cast<uint16_t *>(ws + d.qs_off);            // [3][m][32]
+    uint16_t *dst = reinterpret_cast<uint16_t *>(ws + d.qs_off);
     for (int e = threadIdx.x; e < 64 * 32; e += 256) {
-        const int row = r0 + (e >> 5), c = e & 31;
-        if (row < d.m) {
+        const int k = r0 + (e >> 5), c = e & 31;
+        if (k < d.m) {
             float h, m, l;
-            split3(src[(int64_t)row * 32 + c], h, m, l);
-            rm[((int64_t)0 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(h) >> 16);
-            rm[((int64_t)1 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(m) >> 16);
-            rm[((int64_t)2 * d.m + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
+            split3(src[(int64_t)k * 32 + c], h, m, l);
+            const int64_t cb = k >> 7;
+            const int cc = (k >> 3) & 15, t = k & 7;
+            uint16_t *o = dst + cb * kErrTileElems + (t * 16 + cc) * 32 + c;
+            o[0 * 128 * 32] = (uint16_t)(__float_as_uint(h) >> 16);
+            o[1 * 128 * 32] = (uint16_t)(__float_as_uint(m) >> 16);
+            o[2 * 128 * 32] = (uint16_t)(__float_as_uint(l) >> 16);
         }
     }
 }
@@ -388,120 +395,170 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 }
 
 // ------------------------------------------------------------------ err pass
-// One wave per (16 rows, run of 128-column blocks).  The rank-32 reconstruction P^ Q+^T of a
-// 16 x 128 tile comes from the matrix cores (v_mfma_f32_16x16x32_bf16: the whole rank in one
-// instruction; splits of both factors, six products per 16 x 16 tile), goes through a wave-private
-// LDS tile to turn the accumulator layout into the octet layout (lane = 8 consecutive columns of
-// a row, 16 lanes = one scale block), and the rest is the element-wise work of the octet family:
-// decode, subtract, block max-norm by DPP, fixed-point stochastic rounding, pack.  The gradient
-// loads of the next block are issued before the element-wise phase of the current one.
+// One workgroup of 8 waves per (128 rows, run of up to 16 column blocks of 128); wave w owns rows
+// 16w..16w+15.  Per column block the residual x = p - P^ Q+^T of the wave's 16 x 128 tile is formed
+// in the accumulators of eight v_mfma_f32_16x16x32_bf16 tiles: they are initialised with p (decoded
+// in place) and the negated splits of P^ are multiplied by the splits of Q+ (six products per tile).
 //
 // Operand layout of v_mfma_f32_16x16x32_bf16: lane l holds A[l%16][8*(l/16) + j],
 // B[8*(l/16) + j][l%16], j = 0..7, and D[4*(l/16) + v][l%16], v = 0..3.
 //
-// LDS tile: a row holds its 32 four-column chunks in two regions, the even chunks (first half of
-// every octet) at words 0..63 and the odd chunks at words 72..135.  A lane that owns octet `oct`
-// reads chunk oct of each region, so consecutive lanes read consecutive 16-byte chunks; the
-// writers (16 consecutive columns per quarter-wave, rows 4 apart) spread over all banks.
+// Tile t takes as its 16 columns one column of every octet of the block: column 8 cc + t for
+// cc = l%16.  After the eight tiles lane l therefore holds, for each of its four rows 4*(l/16) + v,
+// the eight consecutive columns 8 cc .. 8 cc + 7: exactly the octet it loaded with one 16-byte
+// gradient load and one code word, with 16 lanes (a DPP row) covering one scale block.  No data
+// moves between lanes except the block max-norm.
+//
+// The splits of Q+ of a block (24 KB, laid out by k_split_q_new in tile order) are shared by the
+// eight waves through LDS, double buffered: one barrier per block.  The gradient, code and scale
+// loads of block b+1 are issued as soon as block b has been decoded and land during the
+// matrix-core and rounding phases of block b.  Scales are kept in registers (lane cc keeps block
+// cc of the run) and stored once per run, 64 contiguous bytes per row.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int kERows = 16;
-constexpr int kEStride = 148;               // floats per row of the reconstruction tile in LDS
-__device__ __forceinline__ int rec_pos(int k) { return ((k >> 3) << 2) + (k & 3) + ((k >> 2) & 1) * 72; }
 
-struct ErrOctets {
+struct ErrIn {
     uint4 g[4];
     uint32_t cw[4];
     float s[4];
 };
 
-__global__ __launch_bounds__(256) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
+// Fixed-point stochastic rounding of an octet into a word of eight 4-bit two's-complement fields.
+// Magnitudes (0..7) and sign bits are gathered nibble by nibble; the negation is done on the whole
+// word: for a negative field ((mag ^ 7) + 1) ^ 8 = 16 - mag for mag = 1..7 and 0 for mag = 0,
+// without carries between fields.
+__device__ __forceinline__ uint32_t quantise_octet4(const float x[8], float inv16, const uint32_t rnd[4])
+{
+    uint32_t mags = 0, sg = 0;
+#pragma unroll
+    for (int e = 7; e >= 0; --e) {
+        const uint32_t U = (uint32_t)(fabsf(x[e]) * inv16);
+        const uint32_t r16 = (e & 1) ? (rnd[e >> 1] >> 16) : (rnd[e >> 1] & 0xFFFFu);
+        mags = (mags << 4) | ((U + r16) >> 16);
+        sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(x[e]), 28);      // (sg << 4) | top nibble of x
+    }
+    sg &= 0x88888888u;
+    const uint32_t s1 = sg >> 3, s7 = sg - s1;
+    return ((mags ^ s7) + s1) ^ sg;
+}
+
+__global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
 {
-    __shared__ __attribute__((aligned(16))) float sacc_all[4][kERows * kEStride];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
-    if (item >= dp.n_err_m) return;
-    float *sacc = sacc_all[wave];
-    const WorkItem it = dp.err_m_items[item];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][kErrTileElems];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const WorkItem it = dp.err_m_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
-    const int m = (int)d.m;
-    const int64_t row0 = it.a;
-    const int nblk_row = m >> 7;
-    // wave-uniform bases; everything a lane adds to them fits in 32 bits (16 rows of one matrix)
-    const uint16_t *g = grads + d.grad_off + row0 * m;
-    uint32_t *cw = codes + d.word_off + row0 * (m >> 3);
-    float *sc = scales + d.scale_off + row0 * nblk_row;
+    const int m = (int)d.m, m8 = m >> 3, nblk_row = m >> 7;
+    const int64_t row0 = (int64_t)it.a + 16 * wave;
+    const int cb0 = it.b, nb = it.c;
+    const int cc = lane & 15, kg = lane >> 4;
+    // rows of this wave that exist; a wave below the matrix still fills LDS and joins the barriers
+    const int rows_left = (int)((d.n - row0 < 16) ? (d.n - row0 > 0 ? d.n - row0 : 0) : 16);
+    const uint16_t *g = grads + d.grad_off;
+    uint32_t *cw = codes + d.word_off;
+    float *sc = scales + d.scale_off;
     const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
-    const int r16 = lane & 15, kg = lane >> 4;       // matrix-core roles
-    const int rsub = lane >> 4, oct = lane & 15;     // octet roles: row 4u + rsub, columns 8 oct ..
-    const int rows_left = (int)((d.n - row0 < kERows) ? d.n - row0 : kERows);
-    const uint32_t octet0 = (uint32_t)((row0 * m) >> 3);       // index of the tile's first octet in the matrix
 
+    // Rows of the tile that lie below the matrix are clamped to the matrix's last row for loading
+    // (their results are never stored), so every load of the loop is unconditional.
+    bool valid[4];
+    int64_t grow[4];                 // element offset of the row start
+    uint32_t orow[4], srow[4];       // octet / scale offset of the row start (both below 2^32)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int rr = 4 * kg + v;
+        valid[v] = rr < rows_left;
+        const int64_t row = (row0 + rr < d.n) ? row0 + rr : d.n - 1;
+        grow[v] = row * m;
+        orow[v] = (uint32_t)(row * m8);
+        srow[v] = (uint32_t)(row * nblk_row);
+    }
+
+    // negated splits of this wave's rows of P^
     Frag A[3];
+    {
+        const int64_t arow = (row0 + cc < d.n) ? row0 + cc : d.n - 1;
 #pragma unroll
-    for (int s = 0; s < 3; ++s)
-        A[s].u = (r16 < rows_left) ? *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + row0 + r16) * 32 + kg * 8)
-                                   : make_uint4(0, 0, 0, 0);
+        for (int s = 0; s < 3; ++s) {
+            uint4 a = *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + arow) * 32 + kg * 8);
+            a.x ^= 0x80008000u; a.y ^= 0x80008000u; a.z ^= 0x80008000u; a.w ^= 0x80008000u;
+            A[s].u = a;
+        }
+    }
 
-    auto load_octets = [&](ErrOctets &o, int cb) {
+    auto load_in = [&](ErrIn &in, int cb) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int rr = 4 * u + rsub;
-            if (rr < rows_left) {
-                o.g[u] = *reinterpret_cast<const uint4 *>(g + (uint32_t)(rr * m + cb * 128 + oct * 8));
-                o.cw[u] = cw[(uint32_t)(rr * (m >> 3) + cb * 16 + oct)];
-                o.s[u] = sc[(uint32_t)(rr * nblk_row + cb)];
-            } else {
-                o.g[u] = make_uint4(0, 0, 0, 0); o.cw[u] = 0; o.s[u] = 0.0f;
-            }
+        for (int v = 0; v < 4; ++v) {
+            in.g[v] = *reinterpret_cast<const uint4 *>(g + grow[v] + cb * 128 + cc * 8);
+            in.cw[v] = cw[orow[v] + (uint32_t)(cb * 16 + cc)];
+            in.s[v] = sc[srow[v] + (uint32_t)cb];
         }
     };
+    // a block's splits of Q+: 1536 chunks of 16 bytes, three per thread
+    const uint4 *qsrc = reinterpret_cast<const uint4 *>(Qs) + tid;
+    constexpr int kChunks = kErrTileElems / 8;      // 16-byte chunks per block
 
-    ErrOctets cur;
-    load_octets(cur, it.b);
-    const int cb_end = it.b + it.c;
-    for (int cb = it.b; cb < cb_end; ++cb) {
-        // matrix-core phase: eight 16 x 16 tiles of the reconstruction
-        const uint16_t *qb = Qs + (int64_t)cb * 128 * 32;
+    ErrIn in;
+    load_in(in, cb0);
+    {
+        const uint4 *src = qsrc + (int64_t)cb0 * kChunks;
+        uint4 *dst = reinterpret_cast<uint4 *>(sB[0]) + tid;
+        const uint4 b0 = src[0], b1 = src[512], b2 = src[1024];
+        dst[0] = b0; dst[512] = b1; dst[1024] = b2;
+    }
+    __syncthreads();
+
+    float keep[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int b = 0; b < nb; ++b) {
+        const int cb = cb0 + b;
+        const int cbn = (b + 1 < nb) ? cb + 1 : cb;      // the last trip reloads its own block (unused)
+        const uint4 *bsrc = qsrc + (int64_t)cbn * kChunks;
+        const uint4 bq0 = bsrc[0], bq1 = bsrc[512], bq2 = bsrc[1024];
+        // decode p into the accumulators: acc[t][v] = p[row 4 kg + v][column 8 cc + t]
+        f32x4 acc[8];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const uint32_t w4[4] = {in.g[v].x, in.g[v].y, in.g[v].z, in.g[v].w};
+            const float step = in.s[v] * inv_levels(4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
+                acc[e][v] = __builtin_fmaf(step, (float)code_field(in.cw[v], e, 4), gv);
+            }
+        }
+        load_in(in, cbn);
+        // matrix-core phase: acc[t] -= P^ Q+^T over the rank, six split products
+        const uint16_t *buf = sB[b & 1];
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             Frag B[3];
 #pragma unroll
             for (int s = 0; s < 3; ++s)
-                B[s].u = *reinterpret_cast<const uint4 *>(qb + (uint32_t)((s * m + 16 * t + r16) * 32 + kg * 8));
-            f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[0].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[1].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[0].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[2].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[2].v, B[0].v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[1].v, acc, 0, 0, 0);
-            const int pos = rec_pos(16 * t + r16);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sacc[(4 * kg + v) * kEStride + pos] = acc[v];
+                B[s].u = *reinterpret_cast<const uint4 *>(buf + ((s * 8 + t) * 16 + cc) * 32 + kg * 8);
+            f32x4 a = acc[t];
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[0].v, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[1].v, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[0].v, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0].v, B[2].v, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[2].v, B[0].v, a, 0, 0, 0);
+            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1].v, B[1].v, a, 0, 0, 0);
+            acc[t] = a;
         }
-        // the next block's gradient, codes and scales travel while this block is worked on
-        ErrOctets nxt;
-        if (cb + 1 < cb_end) load_octets(nxt, cb + 1);
-        __builtin_amdgcn_wave_barrier();
-        // element-wise phase in the octet layout
+        {
+            // the buffer written here was last read before the previous barrier
+            uint4 *dst = reinterpret_cast<uint4 *>(sB[(b + 1) & 1]) + tid;
+            dst[0] = bq0; dst[512] = bq1; dst[1024] = bq2;
+        }
+        // rounding phase, one octet (row 4 kg + v, columns 8 cc ..) at a time
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int rr = 4 * u + rsub;
-            const float4 a0 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + oct * 4);
-            const float4 a1 = *reinterpret_cast<const float4 *>(sacc + rr * kEStride + 72 + oct * 4);
-            const float rec[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-            const uint32_t w4[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
-            const float step = cur.s[u] * inv_levels(4);
+        for (int v = 0; v < 4; ++v) {
             float x[8];
             float a = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
-                const float pv = __builtin_fmaf(step, (float)code_field(cur.cw[u], e, 4), gv);
-                x[e] = pv - rec[e];
+                x[e] = acc[e][v];
                 a = fmaxf(a, fabsf(x[e]));
             }
             // 16 lanes = one 128-column block
@@ -510,19 +567,19 @@ __global__ __launch_bounds__(256) void k_err_mfma(DevicePlan dp, const uint16_t 
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
             const float inv16 = (a > 0.0f) ? (7.0f / a) * 65536.0f : 0.0f;
-            const uint32_t orel = (uint32_t)(rr * (m >> 3) + cb * 16 + oct);
+            const uint32_t o = orow[v] + (uint32_t)(cb * 16 + cc);
             uint32_t rnd[4];
-            philox4x32_10(octet0 + orel, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
-            uint32_t word = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) word |= quantise_field(x[e], inv16, draw16(rnd, e), 0xFu) << (4 * e);
-            if (rr < rows_left) {
-                cw[orel] = word;
-                if (oct == 0) sc[(uint32_t)(rr * nblk_row + cb)] = a;
-            }
+            philox4x32_10(o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+            const uint32_t word = quantise_octet4(x, inv16, rnd);
+            if (valid[v]) cw[o] = word;
+            keep[v] = (cc == b) ? a : keep[v];
         }
-        __builtin_amdgcn_wave_barrier();
-        if (cb + 1 < cb_end) cur = nxt;
+        __syncthreads();        // the next block's splits are in LDS; everybody is done with this block's
+    }
+    if (cc < nb) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (valid[v]) sc[srow[v] + (uint32_t)(cb0 + cc)] = keep[v];
     }
 }
 
@@ -557,7 +614,7 @@ void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, flo
                    uint64_t step, hipStream_t st)
 {
     if (dp.n_err_m <= 0) return;
-    hipLaunchKernelGGL(k_err_mfma, dim3((dp.n_err_m + 3) / 4), dim3(256), 0, st, dp,
+    hipLaunchKernelGGL(k_err_mfma, dim3(dp.n_err_m), dim3(512), 0, st, dp,
                        reinterpret_cast<const uint16_t *>(grads), codes, scales, ws, (uint32_t)step, (uint32_t)(step >> 32));
 }
 

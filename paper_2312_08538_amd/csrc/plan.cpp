@@ -127,9 +127,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             if (mf_e) {
                 for (int64_t k0 = 0; k0 < d.m; k0 += 64) plan.split_qn_items.push_back({l, (int32_t)(k0 / 64), 0, 0});
                 const int32_t ncb = (int32_t)(d.m / 128);
-                for (int64_t r0 = 0; r0 < d.n; r0 += 16)
-                    for (int32_t cb0 = 0; cb0 < ncb; cb0 += 8)
-                        plan.err_m_items.push_back({l, (int32_t)r0, cb0, std::min<int32_t>(8, ncb - cb0)});
+                for (int64_t r0 = 0; r0 < d.n; r0 += kErrRows)
+                    for (int32_t cb0 = 0; cb0 < ncb; cb0 += kErrRun)
+                        plan.err_m_items.push_back({l, (int32_t)r0, cb0, std::min<int32_t>(kErrRun, ncb - cb0)});
             }
             if (d.path == kPathGeneric || mf) {
                 if (!mf_p)

@@ -17,6 +17,8 @@ constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (on
 
 enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
 constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
+constexpr int kErrRows = 128;       // rows per workgroup item of the MFMA err pass (8 waves x 16)
+constexpr int kErrRun = 16;         // column blocks of 128 per item of the MFMA err pass (at most 16)
 
 // One matrix of the model as the kernels see it (device copy is an array of these).
 // Workspace offsets are in doubles from the start of the workspace.
@@ -41,7 +43,7 @@ struct MatDesc {
     int64_t qsT_off;                // Q_state, transposed: [3][32][m]
     int64_t psT_off;                // P^, transposed:      [3][32][n_pad]
     int64_t ps_off;                 // P^, row-major:       [3][n][32]
-    int64_t qs_off;                 // Q+, row-major:       [3][m][32]
+    int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -69,7 +71,7 @@ struct Plan {
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
     std::vector<WorkItem> q_m_items;    // (mat, column block of 128, row tile)
-    std::vector<WorkItem> err_m_items;  // (mat, column block of 128, first row, rows)
+    std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
     std::vector<WorkItem> split_q_items;   // split Q_state  (transposed):  (mat, first k / 64)
     std::vector<WorkItem> split_p_items;   // split P^ (both layouts):      (mat, first row / 64)
     std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
