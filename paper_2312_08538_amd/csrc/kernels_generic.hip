@@ -70,129 +70,6 @@ __global__ __launch_bounds__(256) void k_pass_p_generic(DevicePlan dp, const voi
     }
 }
 
-// ---------------------------------------------------------------- orthonormalisation
-// Cholesky-QR in fp64: G = P^T P from fixed-order partial sums, G = R^T R, P^ = P R^-1.
-// In exact arithmetic this is the thin-QR factor with positive diagonal of R, the same
-// matrix Gram-Schmidt produces.
-__global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float *P, double *ws)
-{
-    const WorkItem it = dp.gram_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    const int r = dp.rank;
-    __shared__ float tile[kGramRows * kMaxRank];
-    const int64_t row0 = (int64_t)it.a * kGramRows;
-    const int rows = (int)((d.n - row0 < kGramRows) ? d.n - row0 : kGramRows);
-    const float *src = P + d.p_off + row0 * r;
-    for (int e = threadIdx.x; e < rows * r; e += 256) tile[e] = src[e];
-    __syncthreads();
-    double *out = ws + d.gram_off + (int64_t)it.a * r * r;
-    for (int e = threadIdx.x; e < r * r; e += 256) {
-        const int a = e / r, b = e % r;
-        double s = 0.0;
-        for (int i = 0; i < rows; ++i) s += (double)tile[i * r + a] * (double)tile[i * r + b];
-        out[e] = s;
-    }
-}
-
-// One wave per matrix: sum the partial Gram matrices, factor, invert the triangle.
-// A column whose squared norm after projection is not above 1e-12 of its squared norm is
-// linearly dependent on the earlier ones: its P^ column is set to zero.
-__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws)
-{
-    const MatDesc d = dp.mats[blockIdx.x];
-    const int r = dp.rank;
-    const int lane = threadIdx.x;          // the factorisation itself uses the first r threads
-    __shared__ double G[kMaxRank * kMaxRank];
-    __shared__ double R[kMaxRank * kMaxRank];
-    __shared__ int dead[kMaxRank];
-    for (int e = lane; e < r * r; e += 256) {
-        G[e] = ordered_sum(ws + d.gram_off + e, d.n_gram_tiles, (int64_t)r * r);
-        R[e] = 0.0;
-    }
-    __syncthreads();
-    for (int c = 0; c < r; ++c) {
-        // diagonal entry (every lane computes the same value)
-        double dd = G[c * r + c];
-        for (int k = 0; k < c; ++k) dd -= R[k * r + c] * R[k * r + c];
-        const bool is_dead = !(dd > 1e-12 * G[c * r + c]);
-        const double rcc = is_dead ? 1.0 : sqrt(dd);
-        if (lane == c) { R[c * r + c] = rcc; dead[c] = is_dead ? 1 : 0; }
-        if (lane > c && lane < r) {
-            double v = G[c * r + lane];
-            for (int k = 0; k < c; ++k) v -= R[k * r + c] * R[k * r + lane];
-            R[c * r + lane] = is_dead ? 0.0 : v / rcc;
-        }
-        __syncthreads();
-    }
-    // inverse of the upper triangle, one column per lane, by back substitution
-    double *rinv = ws + d.rinv_off;
-    if (lane < r) {
-        const int j = lane;
-        double col[kMaxRank];
-#pragma unroll
-        for (int i = 0; i < kMaxRank; ++i) col[i] = 0.0;
-        if (!dead[j]) {
-#pragma unroll
-            for (int i = kMaxRank - 1; i >= 0; --i) {
-                if (i > j || i >= r) continue;
-                if (i == j) { col[i] = 1.0 / R[j * r + j]; continue; }
-                double s = 0.0;
-#pragma unroll
-                for (int k = 0; k < kMaxRank; ++k)
-                    if (k > i && k <= j) s += R[i * r + k] * col[k];
-                col[i] = -s / R[i * r + i];
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < kMaxRank; ++i)
-            if (i < r) rinv[i * r + j] = col[i];
-    }
-}
-
-// P^ = P * R^-1, one thread per row.  The rows of R^-1 are at wave-uniform addresses (scalar
-// loads, SGPR operands of the fp64 FMAs); each output column is accumulated over k <= c.
-template <int RP>
-__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *__restrict__ ws)
-{
-    const WorkItem it = dp.apply_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    const int r = dp.rank;
-    const double *__restrict__ rinv = ws + d.rinv_off;
-    const int64_t row = (int64_t)it.a + threadIdx.x;
-    if (row >= d.n) return;
-    float *prow = P + d.p_off + row * r;
-    double out[RP];
-#pragma unroll
-    for (int c = 0; c < RP; ++c) out[c] = 0.0;
-    if (r == RP) {
-        // full rank for this instantiation: fixed trip counts, whole rows of R^-1 per scalar load
-        float in32[RP];
-#pragma unroll
-        for (int c4 = 0; c4 < RP / 4; ++c4) {
-            const float4 v = reinterpret_cast<const float4 *>(prow)[c4];
-            in32[4 * c4] = v.x; in32[4 * c4 + 1] = v.y; in32[4 * c4 + 2] = v.z; in32[4 * c4 + 3] = v.w;
-        }
-#pragma unroll
-        for (int k = 0; k < RP; ++k) {
-            const double in = (double)in32[k];
-#pragma unroll
-            for (int c = 0; c < RP; ++c)
-                if (c >= k) out[c] = __builtin_fma(in, rinv[k * RP + c], out[c]);
-        }
-    } else {
-        for (int k = 0; k < r; ++k) {
-            const double in = (double)prow[k];
-            const double *rk = rinv + k * r;
-#pragma unroll
-            for (int c = 0; c < RP; ++c)
-                if (c < r) out[c] = __builtin_fma(in, rk[c], out[c]);      // rinv[k][c] = 0 for c < k
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < RP; ++c)
-        if (c < r) prow[c] = (float)out[c];
-}
-
 // ---------------------------------------------------------------- pass 2: Q+ = p^T * P^
 // One thread per column, one workgroup per (column tile, row tile); partial sums per row
 // tile go to the workspace and are added in row-tile order by k_q_reduce.
@@ -370,17 +247,6 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
     if (dp.n_pred > 0) hipLaunchKernelGGL(k_p_reduce, dim3(dp.n_pred), dim3(256), 0, st, dp, (const double *)ws, P);
-    return hipGetLastError();
-}
-
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
-{
-    // the span covers all three small kernels of this stage
-    if (span.begin) (void)hipEventRecord(span.begin, st);
-    hipLaunchKernelGGL(k_gram_partial, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws);
-    hipLaunchKernelGGL(k_cholesky_inverse, dim3(dp.n_mats), dim3(256), 0, st, dp, ws);
-    CONEF_DISPATCH_RP(k_apply_rinv, dim3(dp.n_apply), dim3(256), st, dp, P, (const double *)ws);
-    if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
 

@@ -45,12 +45,14 @@ __device__ __forceinline__ uint32_t pack_hi16(float lo, float hi)
 __device__ __forceinline__ float trunc_bf16(float x) { return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u); }
 
 // x = h + m + l with h, m, l representable in bf16 (truncation; each remainder is exact in fp32)
+// (24 significant bits: 8 go to h, 8 to m, and the last remainder has at most 8 left, so it needs
+// no truncation)
 __device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
 {
     h = trunc_bf16(x);
     const float r1 = x - h;
     m = trunc_bf16(r1);
-    l = trunc_bf16(r1 - m);
+    l = r1 - m;
 }
 
 // ------------------------------------------------------------------ factor splits

@@ -1,0 +1,243 @@
+// Orthonormalisation of all left factors of a model: P^ = thin-QR factor of P with positive
+// diagonal of R, by Cholesky-QR in fp64:  G = P^T P,  G = R^T R,  P^ = P R^-1.  In exact arithmetic
+// this is the matrix Gram-Schmidt produces.  Three grouped launches:
+//   k_gram_partial      fp64 Gram matrices of row tiles (4 x 4 register blocks per thread),
+//   k_cholesky_inverse  per matrix: ordered sum of the tiles, then factorisation and inversion of
+//                       the triangle inside one wave (a lane owns a column; rows are broadcast
+//                       with v_readlane, no LDS traffic and no barriers in the O(r^3) part),
+//   k_apply_rinv        P^ = P R^-1 on 64-row tiles staged through LDS.
+// All sums run in a fixed order.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace conef {
+
+namespace {
+
+__device__ __forceinline__ double bcast(double v, int src_lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+    return __hiloint2double(hi, lo);
+}
+
+// ---------------------------------------------------------------- partial Gram matrices
+// One workgroup per row tile (d.gram_tile_rows rows, walked in pieces of kGramRows).  The RP x RP
+// result is cut into 4 x 4 blocks; thread t owns block t % B and every PH-th row of the piece
+// (B = (RP/4)^2 blocks, PH = 256 / B row phases).  Phases are added by a fixed butterfly inside
+// the wave and in wave order across the workgroup.
+template <int RP>
+__global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float *__restrict__ P, double *ws)
+{
+    constexpr int NB = RP / 4, B = NB * NB, PH = 256 / B;
+    constexpr int kStride = RP;
+    __shared__ __attribute__((aligned(16))) float tile[kGramRows * kStride];
+    __shared__ double red[4][B * 16];
+    const WorkItem it = dp.gram_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int t = threadIdx.x, blk = t % B, ph = t / B;
+    const int bi = blk / NB, bj = blk % NB;
+    const int64_t tile0 = (int64_t)it.a * d.gram_tile_rows;
+    const int64_t tile1 = (tile0 + d.gram_tile_rows < d.n) ? tile0 + d.gram_tile_rows : d.n;
+
+    double acc[4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) acc[x][y] = 0.0;
+
+    for (int64_t row0 = tile0; row0 < tile1; row0 += kGramRows) {
+        const int rows = (int)((tile1 - row0 < kGramRows) ? tile1 - row0 : kGramRows);
+        const float *src = P + d.p_off + row0 * r;
+        __syncthreads();                                    // the previous piece has been consumed
+        if (r == RP) {
+            for (int e = t; e < rows * RP / 4; e += 256)
+                reinterpret_cast<float4 *>(tile)[e] = reinterpret_cast<const float4 *>(src)[e];
+        } else {
+            for (int e = t; e < rows * RP; e += 256) {
+                const int i = e / RP, c = e % RP;
+                tile[e] = c < r ? src[i * r + c] : 0.0f;
+            }
+        }
+        __syncthreads();
+        for (int i = ph; i < rows; i += PH) {
+            const float4 a = *reinterpret_cast<const float4 *>(tile + i * kStride + 4 * bi);
+            const float4 b = *reinterpret_cast<const float4 *>(tile + i * kStride + 4 * bj);
+            const double av[4] = {(double)a.x, (double)a.y, (double)a.z, (double)a.w};
+            const double bv[4] = {(double)b.x, (double)b.y, (double)b.z, (double)b.w};
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) acc[x][y] = __builtin_fma(av[x], bv[y], acc[x][y]);
+        }
+    }
+    // phases that share a wave: lanes B, 2B, ... apart
+#pragma unroll
+    for (int o = B; o < 64; o <<= 1)
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int y = 0; y < 4; ++y) acc[x][y] += __shfl_xor(acc[x][y], o, 64);
+    const int lane = t & 63, wave = t >> 6;
+    if (lane < B || B >= 64) {
+        const int slot = (B >= 64) ? blk : lane;            // B >= 64: one phase per wave, blk == lane
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int y = 0; y < 4; ++y) red[wave][slot * 16 + x * 4 + y] = acc[x][y];
+    }
+    __syncthreads();
+    double *out = ws + d.gram_off + (int64_t)it.a * r * r;
+    for (int e = t; e < B * 16; e += 256) {
+        const int b2 = e >> 4, x = (e >> 2) & 3, y = e & 3;
+        const int a = 4 * (b2 / NB) + x, b = 4 * (b2 % NB) + y;
+        if (a < r && b < r) out[a * r + b] = ((red[0][e] + red[1][e]) + red[2][e]) + red[3][e];
+    }
+}
+
+// ---------------------------------------------------------------- Cholesky factor and its inverse
+// One workgroup per matrix.  All threads add up the partial Gram matrices (tile order) into LDS;
+// then wave 0 factors G = R^T R and inverts R with lane j holding column j in registers.
+// A column whose squared norm after projection is not above 1e-12 of its squared norm is linearly
+// dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.
+template <int RP>
+__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws)
+{
+    __shared__ double G[RP * RP];
+    const MatDesc d = dp.mats[blockIdx.x];
+    const int r = dp.rank;
+    const int t = threadIdx.x;
+    for (int e = t; e < r * r; e += 256) {
+        const double *src = ws + d.gram_off + e;
+        const int64_t stride = (int64_t)r * r;
+        const int T = d.n_gram_tiles;
+        double s = 0.0;
+        int k = 0;
+        for (; k + 8 <= T; k += 8) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(k + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; k < T; ++k) s += src[(int64_t)k * stride];
+        G[(e / r) * RP + (e % r)] = s;
+    }
+    __syncthreads();
+    if (t >= 64) return;
+    const int j = t;                                   // this lane's column (lanes >= r idle along)
+    double col[RP];
+#pragma unroll
+    for (int i = 0; i < RP; ++i) col[i] = (i < r && j < r) ? G[i * RP + j] : 0.0;
+    double dg = 0.0;                                   // G[j][j] before any update (selected without dynamic indexing)
+#pragma unroll
+    for (int i = 0; i < RP; ++i) dg = (i == j) ? col[i] : dg;
+    bool dead_j = false;
+    // right-looking Cholesky: after step c, col[c] holds R[c][j]
+#pragma unroll
+    for (int c = 0; c < RP; ++c) {
+        if (c < r) {                                   // uniform
+            const double dcc = bcast(col[c], c), gcc = bcast(dg, c);
+            const bool dead = !(dcc > 1e-12 * gcc);
+            const double rcc = dead ? 1.0 : sqrt(dcc);
+            double rcj = 0.0;
+            if (j == c) { rcj = rcc; dead_j = dead; }
+            else if (j > c && !dead) rcj = col[c] / rcc;
+            col[c] = rcj;
+#pragma unroll
+            for (int i = c + 1; i < RP; ++i)
+                if (i < r) col[i] = __builtin_fma(-bcast(rcj, i), rcj, col[i]);
+        }
+    }
+    // inverse of the upper triangle: x[i] = (R^-1)[i][j]
+    double dinv = 0.0;                                 // 1 / R[j][j]
+#pragma unroll
+    for (int i = 0; i < RP; ++i) dinv = (i == j) ? 1.0 / col[i] : dinv;
+    double x[RP];
+#pragma unroll
+    for (int i = 0; i < RP; ++i) x[i] = (i == j && !dead_j) ? dinv : 0.0;
+#pragma unroll
+    for (int i = RP - 2; i >= 0; --i) {
+        if (i < r) {
+            double s = 0.0;
+#pragma unroll
+            for (int k = i + 1; k < RP; ++k)
+                if (k < r) s = __builtin_fma(bcast(col[i], k), x[k], s);      // R[i][k] * x[k]; x[k] = 0 for k > j
+            const double di = bcast(dinv, i);
+            if (i < j && !dead_j) x[i] = -s * di;
+        }
+    }
+    double *rinv = ws + d.rinv_off;
+    if (j < r) {
+#pragma unroll
+        for (int i = 0; i < RP; ++i)
+            if (i < r) rinv[i * r + j] = x[i];
+    }
+}
+
+// ---------------------------------------------------------------- P^ = P R^-1
+// One workgroup per 64 rows; wave g computes the output columns c = g, g + 4, g + 8, ... (equal
+// work per wave: column c takes c + 1 products), one lane per row.  The entries of R^-1 are at
+// wave-uniform addresses (scalar loads, SGPR operands of the fp64 FMAs).
+template <int RP>
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *__restrict__ ws)
+{
+    constexpr int kS = RP + 1;
+    __shared__ float tin[64 * kS];
+    __shared__ float tout[64 * kS];
+    const WorkItem it = dp.apply_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int t = threadIdx.x, row = t & 63;
+    const int g = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int64_t row0 = it.a;
+    const int rows = (int)((d.n - row0 < 64) ? d.n - row0 : 64);
+    float *base = P + d.p_off + row0 * r;
+    for (int e = t; e < rows * r; e += 256) tin[(e / r) * kS + (e % r)] = base[e];
+    __syncthreads();
+    const double *__restrict__ rinv = ws + d.rinv_off;
+    if (row < rows) {
+        double in[RP];
+#pragma unroll
+        for (int k = 0; k < RP; ++k) in[k] = (k < r) ? (double)tin[row * kS + k] : 0.0;
+#pragma unroll
+        for (int jj = 0; jj < (RP + 3) / 4; ++jj) {
+            const int c = g + 4 * jj;
+            if (c < r) {                                // uniform per wave
+                double acc = 0.0;
+#pragma unroll
+                for (int k = 0; k < RP; ++k)
+                    if (k <= c) acc = __builtin_fma(in[k], rinv[k * r + c], acc);
+                tout[row * kS + c] = (float)acc;
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = t; e < rows * r; e += 256) base[e] = tout[(e / r) * kS + (e % r)];
+}
+
+}  // namespace
+
+#define CONEF_ORTH_DISPATCH(KERNEL, GRID, ST, ...)                                                \
+    do {                                                                                          \
+        switch (dp.rpad) {                                                                        \
+        case 4: hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;        \
+        case 8: hipLaunchKernelGGL(KERNEL<8>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;        \
+        case 16: hipLaunchKernelGGL(KERNEL<16>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
+        default: hipLaunchKernelGGL(KERNEL<32>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
+        }                                                                                         \
+    } while (0)
+
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
+{
+    // the span covers all three kernels of this stage
+    if (span.begin) (void)hipEventRecord(span.begin, st);
+    CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), st, dp, (const float *)P, ws);
+    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats), st, dp, ws);
+    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), st, dp, P, (const double *)ws);
+    if (span.end) (void)hipEventRecord(span.end, st);
+    return hipGetLastError();
+}
+
+}  // namespace conef

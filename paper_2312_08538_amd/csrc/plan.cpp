@@ -74,7 +74,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 d.lr_shift = log2i(lr);
             }
             // MFMA family: dense rank-32 contractions on the matrix cores
-            if (rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0) d.path = kPathMfma;
+            if (rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0 && d.m <= (1 << 24)) d.path = kPathMfma;
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
@@ -86,7 +86,8 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
             }
 
-            d.n_gram_tiles = (int32_t)ceil_div(d.n, kGramRows);
+            d.gram_tile_rows = d.n > 8192 ? 2 * kGramRows : kGramRows;
+            d.n_gram_tiles = (int32_t)ceil_div(d.n, d.gram_tile_rows);
             d.gram_off = wd; wd += (int64_t)d.n_gram_tiles * rank * rank;
             d.rinv_off = wd; wd += rank * rank;
             d.q_tile_rows = d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : kGenQRows;
@@ -156,10 +157,15 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                     for (int64_t e0 = 0; e0 < d.n * rank; e0 += 256) plan.pred_items.push_back({l, (int32_t)e0, 0, 0});
             }
             for (int32_t t = 0; t < d.n_gram_tiles; ++t) plan.gram_items.push_back({l, t, 0, 0});
-            for (int64_t r0 = 0; r0 < d.n; r0 += 256) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
+            for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
             for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
         }
+        // A workgroup of the MFMA P pass walks a whole row range, so its duration grows with the
+        // number of columns: longest first, so that the last workgroups to start are the short ones.
+        std::stable_sort(plan.p_m_items.begin(), plan.p_m_items.end(), [&](const WorkItem &x, const WorkItem &y) {
+            return plan.mats[x.mat].m > plan.mats[y.mat].m;
+        });
     } catch (const std::bad_alloc &) {
         return kEnomem;
     }

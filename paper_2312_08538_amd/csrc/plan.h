@@ -9,7 +9,7 @@ namespace conef {
 
 constexpr int kAlign = 64;          // every per-matrix offset is a multiple of 64 elements
 constexpr int kMaxRank = 32;
-constexpr int kGramRows = 256;      // rows per partial Gram matrix
+constexpr int kGramRows = 256;      // rows per LDS piece of the Gram kernel
 constexpr int kGenQRows = 128;      // rows per partial of Q+ in the generic pass 2
 constexpr int kGenQCols = 256;      // columns per workgroup in the generic pass 2
 constexpr int kFastMaxRank = 8;     // the octet family holds rank <= 8 in registers
@@ -31,6 +31,7 @@ struct MatDesc {
     int64_t qpart_off;              // partial sums of Q+, [n_q_tiles][m*r]
     int64_t ppart_off;              // partial sums of P, [n_p_chunks][n*r] (only if n_p_chunks > 1)
     int32_t n_gram_tiles, n_q_tiles, n_p_chunks;
+    int32_t gram_tile_rows;         // rows per partial Gram matrix (a multiple of kGramRows)
     int32_t q_tile_rows;            // rows per partial of Q+
     int32_t p_chunk_cols;           // columns per partial of P
     int32_t path;                   // kernel family chosen for this matrix
@@ -78,7 +79,7 @@ struct Plan {
     // shared
     std::vector<WorkItem> pred_items;   // reduce partial P: (mat, first entry of n*r)
     std::vector<WorkItem> gram_items;   // (mat, gram tile)
-    std::vector<WorkItem> apply_items;  // (mat, first row)                    256 rows per workgroup
+    std::vector<WorkItem> apply_items;  // (mat, first row)                    64 rows per workgroup
     std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
     std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
 };

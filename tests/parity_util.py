@@ -57,7 +57,7 @@ def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step
         tol = 1e-6 * max(1.0, float(u))
         if rec_oracle is not None:
             tol *= max(1.0, float(np.abs(rec_oracle[b0:min(N, b0 + block)]).max()) / float(a))
-        near_draw = abs(f - xi) <= tol
+        near_draw = abs(f + xi - 1.0) <= tol          # rounded up exactly when fraction + draw / 2^16 >= 1
         near_grid = abs(float(u) - round(float(u))) <= tol
         assert near_draw or near_grid, (f"{what}: code {j} differs although the pre-rounding value is not near a "
                                         f"boundary (u={u}, f={f}, xi={xi})")
