@@ -177,18 +177,38 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
                                 stage_span(ctx, 0)));
 }
 
-int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
+namespace {
+// fused: the call is part of conef_step, so the stage that follows works on exactly what this one
+// leaves behind (the operand splits of P^ written by the orthonormalisation are still valid for
+// the Q+ stage, which then need not make them again)
+int orthonormalise_impl(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream, bool fused)
 {
     if (!ctx || !P_inout || !workspace) return CONEF_EINVAL;
     if (misaligned(P_inout, 16) || misaligned(workspace, 256)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st, stage_span(ctx, 1)));
+    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), fused, st, stage_span(ctx, 1)));
+}
+
+int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused);
+}  // namespace
+
+int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
+{
+    return orthonormalise_impl(ctx, P_inout, workspace, hip_stream, false);
 }
 
 int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
                  const float *P_hat, float *Q_out, void *workspace, void *hip_stream)
+{
+    return step_q_impl(ctx, grads, err_codes, err_scales, P_hat, Q_out, workspace, hip_stream, false);
+}
+
+namespace {
+int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
     if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
@@ -197,11 +217,10 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_doubles(ctx, workspace), st,
+    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_doubles(ctx, workspace), fused, st,
                                 stage_span(ctx, 2)));
 }
 
-namespace {
 int step_err_impl(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, const float *P_hat,
                   const float *Q_new, void *workspace, uint64_t step, void *hip_stream, bool splits_ready)
 {
@@ -231,8 +250,8 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_out, workspace, hip_stream))) return rc;
     /* exchange point 1: mean of P over the workers -- identity for one worker */
-    if ((rc = conef_orthonormalise(ctx, P_out, workspace, hip_stream))) return rc;
-    if ((rc = conef_step_q(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream))) return rc;
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = step_q_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream, true))) return rc;
     /* exchange point 2: mean of Q over the workers -- identity for one worker; the operand splits
        of P^ and Q+ made by the Q+ stage are therefore still valid for the err stage */
     return step_err_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, step, hip_stream, true);

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "plan.h"
+
 namespace conef {
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -69,6 +71,22 @@ __device__ __forceinline__ uint32_t quantise_field(float x, float inv16, uint32_
     const uint32_t mag = (U + r16) >> 16;
     const uint32_t sgn = (uint32_t)((int32_t)__float_as_uint(x) >> 31);     // 0 or 0xFFFFFFFF
     return ((mag ^ sgn) - sgn) & mask;      // -mag for negative x; -0.0f gives mag 0 -> field 0
+}
+
+// Operand splits of Q+ for the matrix-core err pass: entry (k, c) of Q+ written as three bf16 parts
+// (x = hi + mid + lo by truncation) in tile order [column block of 128][split][k % 8][(k / 8) % 16][32].
+__device__ __forceinline__ void mfma_store_q_split(const MatDesc &d, double *ws, int k, int c, float x)
+{
+    const uint32_t xb = __float_as_uint(x);
+    const float h = __uint_as_float(xb & 0xFFFF0000u);
+    const float r1 = x - h;
+    const float m = __uint_as_float(__float_as_uint(r1) & 0xFFFF0000u);
+    const float l = r1 - m;
+    uint16_t *o = reinterpret_cast<uint16_t *>(ws + d.qs_off) + (int64_t)(k >> 7) * (3 * 128 * 32) +
+                  ((k & 7) * 16 + ((k >> 3) & 15)) * 32 + c;
+    o[0 * 128 * 32] = (uint16_t)(xb >> 16);
+    o[1 * 128 * 32] = (uint16_t)(__float_as_uint(m) >> 16);
+    o[2 * 128 * 32] = (uint16_t)(__float_as_uint(l) >> 16);
 }
 
 __device__ __forceinline__ float wave_max(float v)

@@ -33,9 +33,11 @@ struct Span {
 // Each launcher enqueues on `st` and returns hipGetLastError().  `ws` is the caller's workspace.
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Q, float *P, double *ws, hipStream_t st, Span span = Span());
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span = Span());
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, bool write_splits, hipStream_t st,
+                                 Span span = Span());
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, hipStream_t st, Span span = Span());
+                         const float *Phat, float *Qout, double *ws, bool p_splits_ready, hipStream_t st,
+                         Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
                            const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
                            hipStream_t st, Span span = Span());
@@ -65,7 +67,7 @@ void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes,
 
 void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st);
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, double *ws,
-                 hipStream_t st);
+                 float *Qout, hipStream_t st);
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,
                    uint64_t step, hipStream_t st);
 void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st);

@@ -100,14 +100,16 @@ __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, con
         if (c < r) out[c] = acc[c];
 }
 
-__global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws, float *Qout)
+__global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws, double *ws_rw, float *Qout)
 {
     const WorkItem it = dp.qred_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int64_t e = (int64_t)it.a + threadIdx.x;
     const int64_t len = d.m * dp.rank;
     if (e >= len) return;
-    Qout[d.q_off + e] = (float)ordered_sum(ws + d.qpart_off + e, d.n_q_tiles, len);
+    const float v = (float)ordered_sum(ws + d.qpart_off + e, d.n_q_tiles, len);
+    Qout[d.q_off + e] = v;
+    if (d.path == kPathMfma) mfma_store_q_split(d, ws_rw, (int)(e >> 5), (int)(e & 31), v);
 }
 
 // ---------------------------------------------------------------- pass 3: err <- C(p - P^ Q+^T)
@@ -251,16 +253,19 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
 }
 
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, hipStream_t st, Span span)
+                         const float *Phat, float *Qout, double *ws, bool p_splits_ready, hipStream_t st, Span span)
 {
-    mfma_split_p_hat(dp, Phat, ws, st);
+    // the factors handed in may differ from those the orthonormalisation stage produced (e.g. after
+    // an all-reduce), unless the caller says otherwise
+    if (!p_splits_ready) mfma_split_p_hat(dp, Phat, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    mfma_pass_q(dp, grads, codes, scales, ws, st);
+    mfma_pass_q(dp, grads, codes, scales, ws, Qout, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
     generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);
-    hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, Qout);
-    mfma_split_q_new(dp, Qout, ws, st);
+    // the reduction also writes the matrix-core family's operand splits of Q+
+    if (dp.n_qred > 0)
+        hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, ws, Qout);
     return hipGetLastError();
 }
 

@@ -252,25 +252,17 @@ __global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float 
 // Q+ (m x 32): splits for the err pass, in the order its matrix-core tiles read them:
 // [column block of 128][split][t][cc][32] holds row k = 128 cb + 8 cc + t of the split, so that a
 // block's operands are one contiguous 24 KB piece and tile t's 16 rows (one per octet cc) are adjacent.
+// (The reduction that ends the Q+ pass writes the same layout itself; this kernel serves the err
+// stage when it is called on its own.)
 __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float *__restrict__ Qn, double *ws)
 {
     const WorkItem it = dp.split_qn_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const float *src = Qn + d.q_off;
     const int r0 = it.a * 64;
-    uint16_t *dst = reinterpret_cast<uint16_t *>(ws + d.qs_off);
     for (int e = threadIdx.x; e < 64 * 32; e += 256) {
         const int k = r0 + (e >> 5), c = e & 31;
-        if (k < d.m) {
-            float h, m, l;
-            split3(src[(int64_t)k * 32 + c], h, m, l);
-            const int64_t cb = k >> 7;
-            const int cc = (k >> 3) & 15, t = k & 7;
-            uint16_t *o = dst + cb * kErrTileElems + (t * 16 + cc) * 32 + c;
-            o[0 * 128 * 32] = (uint16_t)(__float_as_uint(h) >> 16);
-            o[1 * 128 * 32] = (uint16_t)(__float_as_uint(m) >> 16);
-            o[2 * 128 * 32] = (uint16_t)(__float_as_uint(l) >> 16);
-        }
+        if (k < d.m) mfma_store_q_split(d, ws, k, c, src[(int64_t)k * 32 + c]);
     }
 }
 
@@ -286,7 +278,7 @@ constexpr int kBStride = kQRows + 8;        // bf16 per (split, c) row of the P^
 
 __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                double *ws)
+                                                double *ws, float *Qout)
 {
     __shared__ __attribute__((aligned(16))) float sp[kQRows * kPStride];
     __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];
@@ -386,6 +378,18 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
+    }
+    if (d.n_q_tiles == 1) {
+        // the only row tile of this matrix: Q+ and its operand splits are final
+        float *qo = Qout + d.q_off + (int64_t)(col0 + 32 * wave) * 32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int krow = 8 * (v >> 2) + 4 * ig + (v & 3);
+            const float x = (float)acc64[v];
+            qo[krow * 32 + r32] = x;
+            mfma_store_q_split(d, ws, col0 + 32 * wave + krow, r32, x);
+        }
+        return;
     }
     // partial sums of this row tile, added in tile order by the reduction kernel
     double *out = ws + d.qpart_off + ((int64_t)it.b * m + col0 + 32 * wave) * 32;
@@ -605,11 +609,11 @@ void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipSt
 }
 
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, double *ws,
-                 hipStream_t st)
+                 float *Qout, hipStream_t st)
 {
     if (dp.n_q_m <= 0) return;
     hipLaunchKernelGGL(k_q_mfma, dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
-                       scales, ws);
+                       scales, ws, Qout);
 }
 
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,

@@ -31,8 +31,11 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
 {
     constexpr int NB = RP / 4, B = NB * NB, PH = 256 / B;
     constexpr int kStride = RP;
-    __shared__ __attribute__((aligned(16))) float tile[kGramRows * kStride];
-    __shared__ double red[4][B * 16];
+    // the row piece and, after the last piece has been consumed, the per-wave partial blocks
+    constexpr size_t kTileBytes = sizeof(float) * kGramRows * kStride, kRedBytes = sizeof(double) * 4 * B * 16;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kTileBytes > kRedBytes ? kTileBytes : kRedBytes];
+    float *tile = reinterpret_cast<float *>(smem);
+    double (*red)[B * 16] = reinterpret_cast<double (*)[B * 16]>(smem);
     const WorkItem it = dp.gram_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int r = dp.rank;
@@ -80,6 +83,7 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
 #pragma unroll
             for (int y = 0; y < 4; ++y) acc[x][y] += __shfl_xor(acc[x][y], o, 64);
     const int lane = t & 63, wave = t >> 6;
+    __syncthreads();                                        // every wave is done reading the last piece
     if (lane < B || B >= 64) {
         const int slot = (B >= 64) ? blk : lane;            // B >= 64: one phase per wave, blk == lane
 #pragma unroll
@@ -180,8 +184,24 @@ __global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double 
 // One workgroup per 64 rows; wave g computes the output columns c = g, g + 4, g + 8, ... (equal
 // work per wave: column c takes c + 1 products), one lane per row.  The entries of R^-1 are at
 // wave-uniform addresses (scalar loads, SGPR operands of the fp64 FMAs).
+template <int RP, int G>
+__device__ __forceinline__ void apply_columns(const double (&in)[RP], const double *__restrict__ rinv, int r, float *out_row)
+{
+#pragma unroll
+    for (int jj = 0; jj < (RP + 3) / 4; ++jj) {
+        const int c = G + 4 * jj;                       // compile-time after unrolling
+        if (c < RP && c < r) {
+            double acc = 0.0;
+#pragma unroll
+            for (int k = 0; k < RP; ++k)
+                if (k <= c) acc = __builtin_fma(in[k], rinv[k * r + c], acc);
+            out_row[c] = (float)acc;
+        }
+    }
+}
+
 template <int RP>
-__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *__restrict__ ws)
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws, bool write_splits)
 {
     constexpr int kS = RP + 1;
     __shared__ float tin[64 * kS];
@@ -194,27 +214,65 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     const int64_t row0 = it.a;
     const int rows = (int)((d.n - row0 < 64) ? d.n - row0 : 64);
     float *base = P + d.p_off + row0 * r;
-    for (int e = t; e < rows * r; e += 256) tin[(e / r) * kS + (e % r)] = base[e];
+    if (r == RP) {
+        for (int e = t; e < rows * RP; e += 256) tin[(e / RP) * kS + (e % RP)] = base[e];
+    } else {
+        for (int e = t; e < rows * r; e += 256) tin[(e / r) * kS + (e % r)] = base[e];
+    }
     __syncthreads();
-    const double *__restrict__ rinv = ws + d.rinv_off;
+    const double *__restrict__ rinv = ws + d.rinv_off;      // written by the previous kernel, read-only here
     if (row < rows) {
         double in[RP];
 #pragma unroll
         for (int k = 0; k < RP; ++k) in[k] = (k < r) ? (double)tin[row * kS + k] : 0.0;
-#pragma unroll
-        for (int jj = 0; jj < (RP + 3) / 4; ++jj) {
-            const int c = g + 4 * jj;
-            if (c < r) {                                // uniform per wave
-                double acc = 0.0;
-#pragma unroll
-                for (int k = 0; k < RP; ++k)
-                    if (k <= c) acc = __builtin_fma(in[k], rinv[k * r + c], acc);
-                tout[row * kS + c] = (float)acc;
-            }
+        float *out_row = tout + row * kS;
+        switch (g) {                                    // wave-uniform
+        case 0: apply_columns<RP, 0>(in, rinv, r, out_row); break;
+        case 1: apply_columns<RP, 1>(in, rinv, r, out_row); break;
+        case 2: apply_columns<RP, 2>(in, rinv, r, out_row); break;
+        default: apply_columns<RP, 3>(in, rinv, r, out_row); break;
         }
     }
     __syncthreads();
-    for (int e = t; e < rows * r; e += 256) base[e] = tout[(e / r) * kS + (e % r)];
+    if (r == RP) {
+        for (int e = t; e < rows * RP; e += 256) base[e] = tout[(e / RP) * kS + (e % RP)];
+    } else {
+        for (int e = t; e < rows * r; e += 256) base[e] = tout[(e / r) * kS + (e % r)];
+    }
+    if constexpr (RP == 32) {
+        // Matrix-core family: the operand splits of P^ (x = hi + mid + lo, three bf16 values by
+        // truncation) that its Q+ and err passes read, written while the tile is at hand:
+        // row-major [3][n][32] and transposed [3][32][n_pad] (rows >= n zero).
+        if (write_splits && d.path == kPathMfma) {          // uniform
+            __shared__ __attribute__((aligned(16))) uint16_t ts[3][32][64 + 8];
+            uint16_t *rm = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.ps_off);
+            for (int e = t; e < 64 * 32; e += 256) {
+                const int rr = e >> 5, c = e & 31;
+                const float x = rr < rows ? tout[rr * kS + c] : 0.0f;
+                const uint32_t xb = __float_as_uint(x);
+                const float r1 = x - __uint_as_float(xb & 0xFFFF0000u);
+                const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
+                const float l = r1 - __uint_as_float(mb);
+                const uint16_t bh = (uint16_t)(xb >> 16), bm = (uint16_t)(mb >> 16), bl = (uint16_t)(__float_as_uint(l) >> 16);
+                if (rr < rows) {
+                    const int64_t row = row0 + rr;
+                    rm[((int64_t)0 * d.n + row) * 32 + c] = bh;
+                    rm[((int64_t)1 * d.n + row) * 32 + c] = bm;
+                    rm[((int64_t)2 * d.n + row) * 32 + c] = bl;
+                }
+                ts[0][c][rr] = bh; ts[1][c][rr] = bm; ts[2][c][rr] = bl;
+            }
+            __syncthreads();
+            uint16_t *tr = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.psT_off);
+            for (int e = t; e < 96 * 8; e += 256) {
+                const int sc = e >> 3, part = e & 7;
+                const int64_t i0 = row0 + part * 8;
+                if (i0 < d.n_pad)
+                    *reinterpret_cast<uint4 *>(tr + (int64_t)sc * d.n_pad + i0) =
+                        *reinterpret_cast<const uint4 *>(&ts[sc >> 5][sc & 31][part * 8]);
+            }
+        }
+    }
 }
 
 }  // namespace
@@ -229,13 +287,13 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
         }                                                                                         \
     } while (0)
 
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, bool write_splits, hipStream_t st, Span span)
 {
     // the span covers all three kernels of this stage
     if (span.begin) (void)hipEventRecord(span.begin, st);
     CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), st, dp, (const float *)P, ws);
     CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats), st, dp, ws);
-    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), st, dp, P, (const double *)ws);
+    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), st, dp, P, (const double *)ws, write_splits && dp.n_split_p > 0);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }

@@ -158,7 +158,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             }
             for (int32_t t = 0; t < d.n_gram_tiles; ++t) plan.gram_items.push_back({l, t, 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
-            for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
+            // a matrix-core matrix with a single row tile gets its Q+ straight from the Q+ pass
+            if (!(mf_q && d.n_q_tiles == 1))
+                for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
         }
         // A workgroup of the MFMA P pass walks a whole row range, so its duration grows with the
