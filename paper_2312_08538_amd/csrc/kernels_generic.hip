@@ -142,8 +142,8 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int bits = dp.bits, W = 32 / bits, B = dp.block;
     const float s_f = (float)((1 << (bits - 1)) - 1);
-    for (int t = 0; t < 16; ++t) {
-        const int64_t blk = (int64_t)it.a * 64 + wave + 4 * t;
+    for (int t = 0; t < it.b; ++t) {
+        const int64_t blk = (int64_t)it.a + wave + 4 * t;
         if (blk >= d.nblk) break;                                   // uniform per wave
         const int64_t j0 = blk * B;
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);

@@ -90,7 +90,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             d.n_gram_tiles = (int32_t)ceil_div(d.n, d.gram_tile_rows);
             d.gram_off = wd; wd += (int64_t)d.n_gram_tiles * rank * rank;
             d.rinv_off = wd; wd += rank * rank;
-            d.q_tile_rows = d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : kGenQRows;
+            // generic family: short row tiles for small matrices (their workgroups are latency bound,
+            // so parallelism has to come from the number of tiles)
+            const int gen_q_rows = d.n <= 1024 ? 16 : kGenQRows;
+            d.q_tile_rows = d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : gen_q_rows;
             d.n_q_tiles = (int32_t)ceil_div(d.n, d.q_tile_rows);
             d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * rank, 32);
             d.n_p_chunks = 1;
@@ -139,9 +142,13 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 if (!mf_q)
                     for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                         for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
-                // 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ... (16 per wave)
-                if (!mf_e)
-                    for (int64_t b0 = 0; b0 < d.nblk; b0 += 64) plan.err_items.push_back({l, (int32_t)(b0 / 64), 0, 0});
+                // 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ...: 16 per wave, or
+                // one per wave for small matrices (a: first block, b: blocks per wave)
+                if (!mf_e) {
+                    const int32_t per_wave = d.nblk <= 16384 ? 1 : 16;
+                    for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave)
+                        plan.err_items.push_back({l, (int32_t)b0, per_wave, 0});
+                }
             } else {
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;

@@ -64,7 +64,7 @@ struct Plan {
     // generic family
     std::vector<WorkItem> p_items;      // pass 1: (mat, first row)            4 rows per workgroup
     std::vector<WorkItem> q_items;      // pass 2: (mat, column tile, row tile)
-    std::vector<WorkItem> err_items;    // pass 3: (mat, first block / 64)
+    std::vector<WorkItem> err_items;    // pass 3: (mat, first block, blocks per wave)
     // octet family (one item per wave for p and err, per workgroup for q)
     std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk)
     std::vector<WorkItem> q_f_items;    // (mat, strip, row tile)
