@@ -259,7 +259,7 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
     // an all-reduce), unless the caller says otherwise
     if (!p_splits_ready) mfma_split_p_hat(dp, Phat, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    mfma_pass_q(dp, grads, codes, scales, ws, Qout, st);
+    mfma_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
     generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);

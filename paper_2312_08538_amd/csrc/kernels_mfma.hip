@@ -267,21 +267,45 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 }
 
 // ------------------------------------------------------------------ Q+ pass
+// Q+[k,c] = sum_i p[i,k] P^[i,c] with p = g + d q (d: step size of the row's block, q: integer code):
+//     Q+[k,c] = sum_i g[i,k] P^[i,c]  +  sum_i q[i,k] (d_i P^[i,c])
+// Both sums run on v_mfma_f32_32x32x16_bf16 with exact operands: g is bf16, q is a small integer,
+// P^ and the fp32 products d_i P^[i,c] are split into three bf16 parts.  Nothing is decoded or split
+// per element; the step sizes enter through 32 products per row (the workgroup's 128 columns are
+// one scale block).
+//
 // One workgroup per (128-column block, row tile); wave w owns columns 32w..32w+31 of the block.
-// Rows are walked in chunks of 64: octets are decoded to p (fp32) in the coalesced load layout and
-// written to an LDS tile; each lane then reads its column down 8 rows at a time (the contraction
-// runs over rows), splits p into three bf16 parts and feeds D[k][c] += p^T-split * P^-split.
-// Six products keep every term down to 2^-24 relative: (h,h) (h,m) (m,h) (h,l) (l,h) (m,m).
+// Rows are walked in chunks of 64.  The contraction runs over rows, so the matrix operand B[i][k]
+// needs, per lane, 8 rows of ONE column: the raw gradient rows and the codes (as bf16 integers) go
+// row-major into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16
+// (within 16 lanes: lane i supplies the address of 4 consecutive columns of row i / 4, chunk i % 4;
+// lane n receives column n of those 4 rows).  The splits of d_i P^ are made once per chunk by the
+// whole workgroup, stored row-major and read the same way; the splits of P^ come transposed from
+// the workspace as before.  fp32 sums of the matrix cores cover one chunk; chunks are added in fp64.
 constexpr int kQRows = 64;                  // rows per chunk
-constexpr int kPStride = 128 + 4;           // floats per row of the p tile in LDS
+constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
 constexpr int kBStride = kQRows + 8;        // bf16 per (split, c) row of the P^ tile in LDS
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// 8 consecutive rows of one column (two transposing reads of 4 rows each)
+__device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    union { s16x4 v; uint2 u; } lo, hi;
+    lo.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    hi.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * pitch));
+    return make_uint4(lo.u.x, lo.u.y, hi.u.x, hi.u.y);
+}
 
 __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                double *ws, float *Qout)
+                                                const float *__restrict__ Phat, double *ws, float *Qout)
 {
-    __shared__ __attribute__((aligned(16))) float sp[kQRows * kPStride];
-    __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];
+    __shared__ __attribute__((aligned(16))) uint16_t tg[kQRows * kTPitch];      // gradient rows, raw bf16
+    __shared__ __attribute__((aligned(16))) uint16_t tq[kQRows * kTPitch];      // codes as bf16 integers
+    __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];         // splits of P^, [split, c][row]
+    __shared__ __attribute__((aligned(16))) uint16_t sd[3 * kQRows * 32];       // splits of d_i P^, [split][row][c]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WorkItem it = dp.q_m_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -292,11 +316,15 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const uint16_t *g = grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
     const uint16_t *psT = reinterpret_cast<const uint16_t *>(ws + d.psT_off);
+    const float *ph = Phat + d.p_off;
     const int nblk_row = m >> 7;
 
+    // chunk loads held in registers until the previous chunk has been consumed
     uint4 rg[4], rb[3];
     uint32_t rcw[4];
-    float rs[4];
+    float4 rp0, rp1;
+    float rsc;
+    const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
     auto load_chunk = [&](int64_t i0) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -305,9 +333,8 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             if (row < row1) {
                 rg[s] = *reinterpret_cast<const uint4 *>(g + row * m + col0 + oct * 8);
                 rcw[s] = cw[(row * m + col0) / 8 + oct];
-                rs[s] = scales[d.scale_off + row * nblk_row + cb];
             } else {
-                rg[s] = make_uint4(0, 0, 0, 0); rcw[s] = 0; rs[s] = 0.0f;
+                rg[s] = make_uint4(0, 0, 0, 0); rcw[s] = 0;
             }
         }
 #pragma unroll
@@ -316,28 +343,48 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             const int64_t i = i0 + part * 8;
             rb[s] = (i < d.n_pad) ? *reinterpret_cast<const uint4 *>(psT + (int64_t)br * d.n_pad + i) : make_uint4(0, 0, 0, 0);
         }
+        const int64_t row = i0 + frow;
+        if (row < row1) {
+            const float4 *pp = reinterpret_cast<const float4 *>(ph + row * 32 + fcg * 8);
+            rp0 = pp[0];
+            rp1 = pp[1];
+            rsc = scales[d.scale_off + row * nblk_row + cb];
+        } else {
+            rp0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f); rp1 = rp0; rsc = 0.0f;
+        }
     };
     auto store_chunk = [&]() {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int idx = tid + 256 * s, rr = idx >> 4, oct = idx & 15;
-            const uint32_t w4[4] = {rg[s].x, rg[s].y, rg[s].z, rg[s].w};
-            const float step = rs[s] * inv_levels(4);
-            float p[8];
+            uint32_t qb[4];
 #pragma unroll
-            for (int i2 = 0; i2 < 4; ++i2) {
-                p[2 * i2] = __builtin_fmaf(step, (float)code_field(rcw[s], 2 * i2, 4), __uint_as_float(w4[i2] << 16));
-                p[2 * i2 + 1] = __builtin_fmaf(step, (float)code_field(rcw[s], 2 * i2 + 1, 4),
-                                               __uint_as_float(w4[i2] & 0xFFFF0000u));
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float lo = (float)code_field(rcw[s], 2 * e2, 4);
+                const float hi = (float)code_field(rcw[s], 2 * e2 + 1, 4);
+                qb[e2] = pack_hi16(lo, hi);              // small integers: exact in bf16
             }
-            float4 *dst = reinterpret_cast<float4 *>(sp + rr * kPStride + oct * 8);
-            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
-            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+            *reinterpret_cast<uint4 *>(tg + rr * kTPitch + oct * 8) = rg[s];
+            *reinterpret_cast<uint4 *>(tq + rr * kTPitch + oct * 8) = make_uint4(qb[0], qb[1], qb[2], qb[3]);
         }
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int idx = tid + 256 * s, br = idx >> 3, part = idx & 7;
             *reinterpret_cast<uint4 *>(sb + br * kBStride + part * 8) = rb[s];
+        }
+        {
+            const float dstep = rsc * inv_levels(4);
+            const float pv[8] = {rp0.x, rp0.y, rp0.z, rp0.w, rp1.x, rp1.y, rp1.z, rp1.w};
+            float hh[8], mm[8], ll[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) split3(dstep * pv[j], hh[j], mm[j], ll[j]);
+            uint16_t *o = sd + frow * 32 + fcg * 8;
+            *reinterpret_cast<uint4 *>(o) =
+                make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
+            *reinterpret_cast<uint4 *>(o + kQRows * 32) =
+                make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+            *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
+                make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
         }
     };
 
@@ -347,6 +394,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
     for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc64[v] = 0.0; }
     const int r32 = lane & 31, ig = lane >> 5;
+    // transposing reads: 16-lane group gq covers columns 16 (gq & 1) .. of the 32-wide operand and
+    // rows 8 (gq >> 1) ..; lane li of the group addresses row li / 4, columns 4 (li % 4) ..
+    const int gq = lane >> 4, li = lane & 15;
+    const int tr_row = 8 * (gq >> 1) + (li >> 2), tr_col = 16 * (gq & 1) + 4 * (li & 3);
+    const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
+    const int tr_d = tr_row * 32 + tr_col;                      // d P^ tile
 
     load_chunk(row0);
     for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
@@ -356,48 +409,42 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         if (i0 + kQRows < row1) load_chunk(i0 + kQRows);
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
-            Frag b0, b1, b2, ah, am, al;
-            b0.u = *reinterpret_cast<const uint4 *>(sb + (0 * 32 + r32) * kBStride + ks * 16 + ig * 8);
-            b1.u = *reinterpret_cast<const uint4 *>(sb + (1 * 32 + r32) * kBStride + ks * 16 + ig * 8);
-            b2.u = *reinterpret_cast<const uint4 *>(sb + (2 * 32 + r32) * kBStride + ks * 16 + ig * 8);
-            float h[8], mm[8], l[8];
+            Frag bg, bq, aP[3], aD[3];
+            bg.u = lds_read_tr16x8(tg + tr_t + ks * 16 * kTPitch, kTPitch);
+            bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float x = sp[(ks * 16 + ig * 8 + j) * kPStride + 32 * wave + r32];
-                split3(x, h[j], mm[j], l[j]);
+            for (int s = 0; s < 3; ++s) {
+                aP[s].u = *reinterpret_cast<const uint4 *>(sb + (s * 32 + r32) * kBStride + ks * 16 + ig * 8);
+                aD[s].u = lds_read_tr16x8(sd + s * kQRows * 32 + tr_d + ks * 16 * 32, 32);
             }
-            ah.u = make_uint4(pack_hi16(h[0], h[1]), pack_hi16(h[2], h[3]), pack_hi16(h[4], h[5]), pack_hi16(h[6], h[7]));
-            am.u = make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
-            al.u = make_uint4(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]), pack_hi16(l[4], l[5]), pack_hi16(l[6], l[7]));
-            acc = mfma(ah, b0, acc);
-            acc = mfma(ah, b1, acc);
-            acc = mfma(am, b0, acc);
-            acc = mfma(ah, b2, acc);
-            acc = mfma(al, b0, acc);
-            acc = mfma(am, b1, acc);
+            acc = mfma(aP[0], bg, acc);
+            acc = mfma(aD[0], bq, acc);
+            acc = mfma(aP[1], bg, acc);
+            acc = mfma(aD[1], bq, acc);
+            acc = mfma(aP[2], bg, acc);
+            acc = mfma(aD[2], bq, acc);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
     }
+    // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
+    const int kcol = col0 + 32 * wave + r32;
     if (d.n_q_tiles == 1) {
         // the only row tile of this matrix: Q+ and its operand splits are final
-        float *qo = Qout + d.q_off + (int64_t)(col0 + 32 * wave) * 32;
+        float *qo = Qout + d.q_off + (int64_t)kcol * 32;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int krow = 8 * (v >> 2) + 4 * ig + (v & 3);
+            const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
             const float x = (float)acc64[v];
-            qo[krow * 32 + r32] = x;
-            mfma_store_q_split(d, ws, col0 + 32 * wave + krow, r32, x);
+            qo[c] = x;
+            mfma_store_q_split(d, ws, kcol, c, x);
         }
         return;
     }
     // partial sums of this row tile, added in tile order by the reduction kernel
-    double *out = ws + d.qpart_off + ((int64_t)it.b * m + col0 + 32 * wave) * 32;
+    double *out = ws + d.qpart_off + ((int64_t)it.b * m + kcol) * 32;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int krow = 8 * (v >> 2) + 4 * ig + (v & 3);
-        out[krow * 32 + r32] = acc64[v];
-    }
+    for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
 }
 
 // ------------------------------------------------------------------ err pass
@@ -608,12 +655,12 @@ void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipSt
     hipLaunchKernelGGL(k_split_p_hat, dim3(dp.n_split_p), dim3(256), 0, st, dp, Phat, ws);
 }
 
-void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, double *ws,
-                 float *Qout, hipStream_t st)
+void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                 const float *Phat, double *ws, float *Qout, hipStream_t st)
 {
     if (dp.n_q_m <= 0) return;
     hipLaunchKernelGGL(k_q_mfma, dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
-                       scales, ws, Qout);
+                       scales, Phat, ws, Qout);
 }
 
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,

@@ -152,8 +152,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             } else {
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;
-                for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows)
-                    for (int32_t cc = 0; cc < d.n_p_chunks; ++cc) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
+                // neighbouring waves (one workgroup, one CU) take neighbouring row tiles of the SAME column
+                // chunk: they read the same rows of Q through the scalar cache at about the same time
+                for (int32_t cc = 0; cc < d.n_p_chunks; ++cc)
+                    for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                     for (int32_t st = 0; st < strips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
                 const int64_t rows_item = (int64_t)std::max(err_rows, rw);
