@@ -81,6 +81,44 @@ def test_cut_down_shapes_of_each_workload(env, name):
     _run_model(env, w, layout, 3, f"cut-{name}")
 
 
+def test_matrix_core_family_row_tiles_and_tails(env):
+    """Rank 32 / bf16 / 4-bit / block 128 (the matrix-core family) on shapes that take its other code
+    paths: more than one row tile of the Q+ pass (rows > 2048, partial sums and their reduction), a
+    Gram tile walked in two pieces (rows > 8192), a ragged last 128-row / 16-row tile, and a run of
+    column blocks that is not a whole 16."""
+    w = wl.WORKLOADS["large"]
+    layout = [(2200, 128), (8300, 128), (300, 2304), (45, 384)]
+    _run_model(env, w, layout, 2, "mfma-tiles")
+
+
+def test_staged_calls_equal_the_fused_step(env):
+    """conef_step and the four stage calls in sequence leave identical bits (the fused step reuses
+    operand copies that the staged calls rebuild)."""
+    R, B, U = env
+    import torch
+
+    for name, layout in [("large", [(300, 256), (2100, 128)]), ("translation", [(300, 512)]), ("cnn", [(64, 147), (128, 1152)])]:
+        w = wl.WORKLOADS[name]
+        Q0s = [wl.host_q0(w, l, shape=layout[l]) for l in range(len(layout))]
+        outs = []
+        for staged in (False, True):
+            gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+            b, ctx, st = gpu.buf, gpu.m.ctx, gpu.m.stream_handle()
+            for t in range(2):
+                gpu.set_grads([wl.host_gradient(w, t, l, shape=layout[l]) for l in range(len(layout))])
+                if staged:
+                    B.conef_step_p(ctx, b["grads"], b["codes"], b["scales"], b["Q"], b["P"], b["ws"], st)
+                    B.conef_orthonormalise(ctx, b["P"], b["ws"], st)
+                    B.conef_step_q(ctx, b["grads"], b["codes"], b["scales"], b["P"], b["Q"], b["ws"], st)
+                    B.conef_step_err(ctx, b["grads"], b["codes"], b["scales"], b["P"], b["Q"], b["ws"], t, st)
+                    torch.cuda.synchronize()
+                else:
+                    gpu.step(t)
+            outs.append([b[k].cpu().numpy().copy() for k in ("codes", "scales", "P", "Q")])
+        for x, y in zip(*outs):
+            assert np.array_equal(x.view(np.uint8), y.view(np.uint8)), name
+
+
 def test_cnn_full_model(env):
     """Configuration 'cnn' at full size: 21 matrices, 11.7 M elements, one grouped launch per pass."""
     w = wl.WORKLOADS["cnn"]
