@@ -98,38 +98,32 @@ def run_gpu(w, steps: int, warmup: int):
     return (t1 - t0) * 1e3 / steps, dict(zip(STAGES, stage_ms)), finite
 
 
-def run_oracle_sample(w):
-    """Times the oracle (as it stands) on a bounded sample of the workload: whole matrices in
-    layout order after the first (the first is the large embedding in the language-model
-    layouts), until about 60 M elements are covered."""
-    import numpy as np
-
+def run_oracle_sample(w, budget_s: float = 20.0):
+    """Times the oracle (as it stands) on the workload's matrices in layout order, one step from
+    zero error, until about `budget_s` seconds of CPU work are spent or the whole model is done.
+    To bound host-side generation, one gradient is drawn per distinct matrix shape and shared by
+    the matrices of that shape (every matrix still has its own state, Q and random draws)."""
     from oracle import conef_ref as R
     from paper_2312_08538_amd import workloads as wl
 
-    budget, picked, tot = 60e6, [], 0
-    order = list(range(1, len(w.layout))) + [0] if len(w.layout) > 1 else [0]
-    for l in order:
-        n, m = w.layout[l]
-        if picked and tot + n * m > budget:
-            continue
-        picked.append(l)
-        tot += n * m
-        if tot >= budget:
-            break
-    states, grads = [], []
-    for l in picked:
-        n, m = w.layout[l]
-        grads.append(wl.host_gradient(w, 0, l))
-        states.append(R.MatState.fresh(n, m, w.bits, w.block, wl.host_q0(w, l)))
     R.lib()
-    t0 = time.perf_counter()
-    for l, g, stt in zip(picked, grads, states):
-        R.step_matrix(g, stt, w.rank, w.bits, w.block, w.lib_seed, l, 0)
-    dt = time.perf_counter() - t0
+    by_shape = {}
+    spent, tot, used = 0.0, 0, 0
+    for l, (n, m) in enumerate(w.layout):
+        if (n, m) not in by_shape:
+            by_shape[(n, m)] = wl.host_gradient(w, 0, l)
+        stt = R.MatState.fresh(n, m, w.bits, w.block, wl.host_q0(w, l))
+        t0 = time.perf_counter()
+        R.step_matrix(by_shape[(n, m)], stt, w.rank, w.bits, w.block, w.lib_seed, l, 0)
+        spent += time.perf_counter() - t0
+        tot += n * m
+        used += 1
+        if spent >= budget_s:
+            break
     G = 4 if w.grad_dtype == 0 else 2
-    return tot * G / dt / 1e9, R.num_threads(), f"{len(picked)} whole matrices of the workload ({tot} elements, " \
-                                                 f"{100.0 * tot / w.elements:.1f} % of it), one step from zero error"
+    sample = (f"the first {used} of {len(w.layout)} matrices of the workload in layout order ({tot} elements, "
+              f"{100.0 * tot / w.elements:.1f} % of it), one step from zero error, {spent:.1f} s of oracle time")
+    return tot * G / spent / 1e9, R.num_threads(), sample
 
 
 def calibrate_copy(w):
@@ -150,6 +144,15 @@ def calibrate_copy(w):
     rd = 4 * (sum(-(-n * m // (32 // w.bits)) for n, m in w.layout) + sum(-(-n * m // w.block) for n, m in w.layout))
     print(f"calibration launch k_decode: reads {rd} bytes, writes {4 * w.elements} bytes", file=sys.stderr)
     model.close()
+    # and a plain device-to-device copy of 1 GiB (the runtime's copy kernel), src not cache resident
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    e.zero_()
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    print(f"calibration copy (runtime copy kernel): reads {src.numel() * 4} bytes, writes {src.numel() * 4} bytes",
+          file=sys.stderr)
 
 
 def load_traffic(workload: str, stage: str):
