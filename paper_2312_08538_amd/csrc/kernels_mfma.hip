@@ -118,8 +118,13 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const uint16_t *qsT = reinterpret_cast<const uint16_t *>(ws + d.qsT_off);
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
+    // scales of this lane's matrix-core row (row 32 wave + lane % 32 of the tile, clamped to the matrix)
+    const int64_t sc_lane_row = (row0 + 32 * wave + (lane & 31) < d.n) ? row0 + 32 * wave + (lane & 31) : d.n - 1;
+    const int64_t sc_row = d.scale_off + sc_lane_row * (m >> 7);
+    float blk_scale = 0.0f;
     struct StageRegs {
         uint4 g[4], q[3], c;
+        float sc;           // block scale of this lane's matrix-core row
     };
     auto load_stage = [&](StageRegs &r, int k0) {
 #pragma unroll
@@ -138,6 +143,9 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
             r.q[s] = *reinterpret_cast<const uint4 *>(qsT + (int64_t)qr * m + k0 + oct * 8);
         }
+        // loads return in issue order: the scale travels with the stage instead of being fetched
+        // when it is needed, where it would have to wait for the stages issued before it
+        r.sc = scales[sc_row + (k0 >> 7)];
     };
     auto store_stage = [&](const StageRegs &r) {
 #pragma unroll
@@ -162,7 +170,6 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const int r32 = lane & 31, kg = lane >> 5;
     const int my_row_in_tile = 32 * wave + r32;
     const int64_t my_row = row0 + my_row_in_tile;
-    const int nblk_row = m >> 7;
 
     auto compute_stage = [&](int k0) {
 #pragma unroll
@@ -190,8 +197,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         }
         if (((k0 + kStage) & 127) == 0) {
             // end of a scale block: fold the code part in with this row's step size
-            const int blk = k0 >> 7;
-            const float dstep = (my_row < d.n) ? scales[d.scale_off + my_row * nblk_row + blk] * inv_levels(4) : 0.0f;
+            const float dstep = (my_row < d.n) ? blk_scale * inv_levels(4) : 0.0f;
             const double dd = (double)dstep;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -209,6 +215,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     for (int k0 = 0; k0 < m; k0 += 2 * kStage) {
         __syncthreads();                 // everybody is done reading the previous stage
         store_stage(ra);
+        blk_scale = ra.sc;
         __syncthreads();
         if (k0 + 2 * kStage < m) load_stage(ra, k0 + 2 * kStage);
         compute_stage(k0);
