@@ -84,7 +84,6 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_apply = (int)pl.apply_items.size();
     d.n_qred = (int)pl.qred_items.size();
     d.n_elem = (int)pl.elem_items.size();
-    d.qd_off = (long long)pl.qd_off;
     d.q_elems = (long long)pl.q_elems;
     d.rank = pl.rank; d.rpad = pl.rpad; d.bits = pl.bits; d.block = pl.block; d.dtype = pl.dtype;
     d.seed_lo = (uint32_t)pl.seed; d.seed_hi = (uint32_t)(pl.seed >> 32);

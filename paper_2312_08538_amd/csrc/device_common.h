@@ -73,6 +73,18 @@ __device__ __forceinline__ uint32_t quantise_field(float x, float inv16, uint32_
     return ((mag ^ sgn) - sgn) & mask;      // -mag for negative x; -0.0f gives mag 0 -> field 0
 }
 
+// Workgroups are dealt to the eight XCDs (each with its own L2) in turn: workgroup b runs on XCD
+// b % 8.  This maps the grid onto work items so that every XCD takes a contiguous range of the
+// item table: workgroups that are resident together on an XCD then work on neighbouring items
+// and find the cache lines they share (code and scale lines that span several column blocks,
+// operand tables of their matrix) in that XCD's L2.
+__device__ __forceinline__ int xcd_contiguous_item(int b, int n_items)
+{
+    const int x = b & 7, j = b >> 3;
+    const int q = n_items >> 3, rem = n_items & 7;
+    return x * q + (x < rem ? x : rem) + j;
+}
+
 // Operand splits of Q+ for the matrix-core err pass: entry (k, c) of Q+ written as three bf16 parts
 // (x = hi + mid + lo by truncation) in tile order [column block of 128][split][k % 8][(k / 8) % 16][32].
 __device__ __forceinline__ void mfma_store_q_split(const MatDesc &d, double *ws, int k, int c, float x)

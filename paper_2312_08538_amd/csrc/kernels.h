@@ -21,7 +21,6 @@ struct DevicePlan {
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
-    long long qd_off = 0;           // doubles from the workspace start: fp64 copy of Q_state
     long long q_elems = 0;
 };
 
@@ -53,9 +52,8 @@ void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *cod
                     const float *Phat, double *ws, hipStream_t st);
 void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                       const float *Qn, uint64_t step, hipStream_t st);
-void octet_widen_q(const DevicePlan &dp, const float *Q, double *ws, hipStream_t st);
-void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, float *P,
-                  double *ws, hipStream_t st);
+void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                  const float *Q, float *P, double *ws, hipStream_t st);
 void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                   const float *Phat, double *ws, hipStream_t st);
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,

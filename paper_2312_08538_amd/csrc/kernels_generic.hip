@@ -241,11 +241,10 @@ void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, 
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Q, float *P, double *ws, hipStream_t st, Span span)
 {
-    octet_widen_q(dp, Q, ws, st);
     mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, true, false);
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, false, true);
-    octet_pass_p(dp, grads, codes, scales, P, ws, st);
+    octet_pass_p(dp, grads, codes, scales, Q, P, ws, st);
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
     if (dp.n_pred > 0) hipLaunchKernelGGL(k_p_reduce, dim3(dp.n_pred), dim3(256), 0, st, dp, (const double *)ws, P);

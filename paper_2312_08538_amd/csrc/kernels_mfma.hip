@@ -14,6 +14,8 @@
 // Operand layout of v_mfma_f32_32x32x16_bf16 (D = A*B, A 32x16, B 16x32, 64 lanes):
 //   lane l holds A[l%32][8*(l/32) + j], B[8*(l/32) + j][l%32], j = 0..7, and
 //   D[8*(v/4) + 4*(l/32) + v%4][l%32], v = 0..15.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -56,10 +58,11 @@ __device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
 }
 
 // ------------------------------------------------------------------ factor splits
-// src: rows x 32 fp32 (row-major).  dst: [3][32][rows_pad] bf16, transposed; rows >= `rows` are zero.
+// src: rows x 32 fp32 (row-major).  dst: bf16, [rows / 64 tiles][3 splits x 32 columns][64 rows]
+// (transposed within a tile); rows >= `rows` of the last tile are zero.
 // One workgroup per 64 source rows starting at r0.
 __device__ __forceinline__ void split_transposed_tile(const float *__restrict__ src, uint16_t *__restrict__ dst,
-                                                      int rows, int rows_pad, int r0)
+                                                      int rows, int r0)
 {
     __shared__ __attribute__((aligned(16))) uint16_t t[3][32][64 + 8];
     for (int e = threadIdx.x; e < 64 * 32; e += 256) {
@@ -73,14 +76,13 @@ __device__ __forceinline__ void split_transposed_tile(const float *__restrict__ 
         t[2][c][rr] = (uint16_t)(__float_as_uint(l) >> 16);
     }
     __syncthreads();
-    // 96 (split, column) rows of 64 entries = 128 bytes each; 8 threads of 16 bytes per row
+    // 96 (split, column) rows of 64 entries = 128 bytes each; 8 threads of 16 bytes per row.  The
+    // tile is stored as one contiguous 12 KB piece (tile-major table): its readers fetch it with
+    // consecutive 16-byte loads, spread evenly over the memory channels.
+    uint16_t *out = dst + (int64_t)(r0 >> 6) * kSplitTile;
     for (int e = threadIdx.x; e < 96 * 8; e += 256) {
         const int sc = e >> 3, part = e & 7;
-        const int col0 = r0 + part * 8;
-        if (col0 < rows_pad) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(&t[sc >> 5][sc & 31][part * 8]);
-            *reinterpret_cast<uint4 *>(dst + (int64_t)sc * rows_pad + col0) = v;
-        }
+        *reinterpret_cast<uint4 *>(out + e * 8) = *reinterpret_cast<const uint4 *>(&t[sc >> 5][sc & 31][part * 8]);
     }
 }
 
@@ -88,18 +90,23 @@ __global__ __launch_bounds__(256) void k_split_q_state(DevicePlan dp, const floa
 {
     const WorkItem it = dp.split_q_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
-    split_transposed_tile(Q + d.q_off, reinterpret_cast<uint16_t *>(ws + d.qsT_off), (int)d.m, (int)d.m, it.a * 64);
+    split_transposed_tile(Q + d.q_off, reinterpret_cast<uint16_t *>(ws + d.qsT_off), (int)d.m, it.a * 64);
 }
 
 // ------------------------------------------------------------------ P pass
 // One workgroup per 128 rows (wave w owns rows 32w..32w+31), walking the whole row in stages of
-// 64 columns.  Per stage the gradient tile, the code words and the three splits of Q^T go through
-// LDS (coalesced global loads, operand-shaped LDS reads).  D = Q^T-split (A, 32 c x 16 k) times
+// 64 columns.  Per stage the gradient tile and the three splits of Q^T go through LDS (coalesced
+// global loads, operand-shaped LDS reads).  The code words go through LDS in groups of four
+// stages: 256 columns of 4-bit codes are one 128-byte line per row, and a line that is fetched in
+// four pieces a stage apart has left the L2 in between (every workgroup streams through it).  D = Q^T-split (A, 32 c x 16 k) times
 // p^T (B, 16 k x 32 rows): a lane's accumulators all belong to ONE row, so the block step size is
 // a per-lane scalar.
 constexpr int kStage = 64;                  // columns per LDS stage
 constexpr int kGStride = kStage + 8;        // bf16 per gradient row in LDS (144 bytes)
-constexpr int kCStride = kStage / 8 + 4;    // code words per row in LDS (48 bytes)
+constexpr int kCodeGroup = 4 * kStage;      // columns per code group
+constexpr int kCStride = kCodeGroup / 8 + 4; // code words per row in LDS (144 bytes)
+constexpr int kScaleGroup = 32 * 128;       // columns per scale group: 32 scales are one 128-byte line per row
+constexpr int kSStride = 33;                // scales per row in LDS (+1: rows fall on distinct banks)
 
 __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
@@ -108,6 +115,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     __shared__ __attribute__((aligned(16))) uint16_t sg[kMfmaRows * kGStride];
     __shared__ __attribute__((aligned(16))) uint32_t sc[kMfmaRows * kCStride];
     __shared__ __attribute__((aligned(16))) uint16_t sq[96 * kGStride];
+    __shared__ float ss[kMfmaRows * kSStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WorkItem it = dp.p_m_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -118,14 +126,55 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const uint16_t *qsT = reinterpret_cast<const uint16_t *>(ws + d.qsT_off);
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
-    // scales of this lane's matrix-core row (row 32 wave + lane % 32 of the tile, clamped to the matrix)
-    const int64_t sc_lane_row = (row0 + 32 * wave + (lane & 31) < d.n) ? row0 + 32 * wave + (lane & 31) : d.n - 1;
-    const int64_t sc_row = d.scale_off + sc_lane_row * (m >> 7);
-    float blk_scale = 0.0f;
     struct StageRegs {
-        uint4 g[4], q[3], c;
-        float sc;           // block scale of this lane's matrix-core row
+        uint4 g[4], q[3];
     };
+    // The block scales go through LDS a group of 32 per row at a time, for the same reason as the
+    // code words.  The load is waited for on the spot, once per 4096 columns.
+    auto fetch_scales = [&](int k0) {
+        const int nblk_row = m >> 7, b0 = k0 >> 7, j = tid & 31;
+        const int blk = (b0 + j < nblk_row) ? b0 + j : nblk_row - 1;
+#pragma unroll 1
+        for (int s4 = 0; s4 < 16; s4 += 4) {        // four loads in flight at a time keep the register count down
+            float v[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int rr = (tid >> 5) + 8 * (s4 + s);
+                const int64_t row = (row0 + rr < d.n) ? row0 + rr : d.n - 1;
+                v[s] = scales[d.scale_off + row * nblk_row + blk];
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) ss[((tid >> 5) + 8 * (s4 + s)) * kSStride + j] = v[s];
+        }
+    };
+    // code words of a group: 128 rows x 128 bytes, 8 threads x 16 bytes per row.  A matrix whose
+    // width is an odd multiple of 128 ends with half a group: its missing half re-reads the first.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    struct CodeRegs {
+        u32x4 w0, w1, w2, w3;
+    };
+    const int c_part = tid & 7;
+    int64_t c_row[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int rr = (tid >> 3) + 32 * s;
+        c_row[s] = ((row0 + rr < d.n) ? row0 + rr : d.n - 1) * m;
+    }
+    auto load_codes = [&](CodeRegs &cg, int kg0) {
+        const int col = (kg0 + c_part * 32 < m) ? kg0 + c_part * 32 : kg0;
+        cg.w0 = *reinterpret_cast<const u32x4 *>(cw + ((c_row[0] + col) >> 3));
+        cg.w1 = *reinterpret_cast<const u32x4 *>(cw + ((c_row[1] + col) >> 3));
+        cg.w2 = *reinterpret_cast<const u32x4 *>(cw + ((c_row[2] + col) >> 3));
+        cg.w3 = *reinterpret_cast<const u32x4 *>(cw + ((c_row[3] + col) >> 3));
+    };
+    auto store_codes = [&](const CodeRegs &cg) {
+        uint32_t *dst = sc + (tid >> 3) * kCStride + c_part * 4;
+        *reinterpret_cast<u32x4 *>(dst) = cg.w0;
+        *reinterpret_cast<u32x4 *>(dst + 32 * kCStride) = cg.w1;
+        *reinterpret_cast<u32x4 *>(dst + 64 * kCStride) = cg.w2;
+        *reinterpret_cast<u32x4 *>(dst + 96 * kCStride) = cg.w3;
+    };
+
     auto load_stage = [&](StageRegs &r, int k0) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -133,19 +182,9 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             const int64_t row = row0 + rr;
             r.g[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
         }
-        {
-            const int rr = tid >> 1, half = tid & 1;
-            const int64_t row = row0 + rr;
-            r.c = (row < d.n) ? *reinterpret_cast<const uint4 *>(cw + (row * m + k0) / 8 + half * 4) : make_uint4(0, 0, 0, 0);
-        }
+        const uint16_t *qtile = qsT + (int64_t)(k0 >> 6) * kSplitTile + tid * 8;      // the stage's tile, contiguous
 #pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
-            r.q[s] = *reinterpret_cast<const uint4 *>(qsT + (int64_t)qr * m + k0 + oct * 8);
-        }
-        // loads return in issue order: the scale travels with the stage instead of being fetched
-        // when it is needed, where it would have to wait for the stages issued before it
-        r.sc = scales[sc_row + (k0 >> 7)];
+        for (int s = 0; s < 3; ++s) r.q[s] = *reinterpret_cast<const uint4 *>(qtile + 2048 * s);
     };
     auto store_stage = [&](const StageRegs &r) {
 #pragma unroll
@@ -153,7 +192,6 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
             *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
         }
-        *reinterpret_cast<uint4 *>(sc + (tid >> 1) * kCStride + (tid & 1) * 4) = r.c;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
@@ -176,7 +214,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         for (int ks = 0; ks < kStage / 16; ++ks) {
             Frag bg, bq, a0, a1, a2;
             bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
-            const uint32_t w = sc[my_row_in_tile * kCStride + ks * 2 + kg];
+            const uint32_t w = sc[my_row_in_tile * kCStride + ((k0 & (kCodeGroup - 1)) >> 3) + ks * 2 + kg];
             uint32_t qb[4];
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {
@@ -197,6 +235,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         }
         if (((k0 + kStage) & 127) == 0) {
             // end of a scale block: fold the code part in with this row's step size
+            const float blk_scale = ss[my_row_in_tile * kSStride + ((k0 >> 7) & 31)];
             const float dstep = (my_row < d.n) ? blk_scale * inv_levels(4) : 0.0f;
             const double dd = (double)dstep;
 #pragma unroll
@@ -210,12 +249,20 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 
     // m is a multiple of 128, so the number of stages is even: two stages per trip, one register set each
     StageRegs ra, rb;
+    CodeRegs cg;
+    load_codes(cg, 0);
     load_stage(ra, 0);
     load_stage(rb, kStage);
-    for (int k0 = 0; k0 < m; k0 += 2 * kStage) {
+    // two stages per trip, one register set each; two trips per code group
+    auto trip = [&](int k0, auto new_group) {
         __syncthreads();                 // everybody is done reading the previous stage
         store_stage(ra);
-        blk_scale = ra.sc;
+        if constexpr (decltype(new_group)::value) {
+            // the group's words have been in registers since the last group was stored
+            store_codes(cg);
+            load_codes(cg, (k0 + kCodeGroup < m) ? k0 + kCodeGroup : k0);      // the last group re-reads itself (unused)
+            if ((k0 & (kScaleGroup - 1)) == 0) fetch_scales(k0);
+        }
         __syncthreads();
         if (k0 + 2 * kStage < m) load_stage(ra, k0 + 2 * kStage);
         compute_stage(k0);
@@ -224,6 +271,10 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         __syncthreads();
         if (k0 + 3 * kStage < m) load_stage(rb, k0 + 3 * kStage);
         compute_stage(k0 + kStage);
+    };
+    for (int k0 = 0; k0 < m; k0 += kCodeGroup) {
+        trip(k0, std::true_type());
+        if (k0 + 2 * kStage < m) trip(k0 + 2 * kStage, std::false_type());
     }
     if (my_row < d.n) {
         float *out = P + d.p_off + my_row * 32;
@@ -253,7 +304,7 @@ __global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float 
             rm[((int64_t)2 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
         }
     }
-    split_transposed_tile(src, reinterpret_cast<uint16_t *>(ws + d.psT_off), (int)d.n, d.n_pad, r0);
+    split_transposed_tile(src, reinterpret_cast<uint16_t *>(ws + d.psT_off), (int)d.n, r0);
 }
 
 // Q+ (m x 32): splits for the err pass, in the order its matrix-core tiles read them:
@@ -314,7 +365,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];         // splits of P^, [split, c][row]
     __shared__ __attribute__((aligned(16))) uint16_t sd[3 * kQRows * 32];       // splits of d_i P^, [split][row][c]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const WorkItem it = dp.q_m_items[blockIdx.x];
+    const WorkItem it = dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
     const MatDesc d = dp.mats[it.mat];
     const int m = (int)d.m, cb = it.a;
     const int col0 = cb * 128;
@@ -326,62 +377,79 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const float *ph = Phat + d.p_off;
     const int nblk_row = m >> 7;
 
-    // chunk loads held in registers until the previous chunk has been consumed
-    uint4 rg[4], rb[3];
-    uint32_t rcw[4];
-    float4 rp0, rp1;
-    float rsc;
-    const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
-    auto load_chunk = [&](int64_t i0) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int idx = tid + 256 * s, rr = idx >> 4, oct = idx & 15;
-            const int64_t row = i0 + rr;
-            if (row < row1) {
-                rg[s] = *reinterpret_cast<const uint4 *>(g + row * m + col0 + oct * 8);
-                rcw[s] = cw[(row * m + col0) / 8 + oct];
-            } else {
-                rg[s] = make_uint4(0, 0, 0, 0); rcw[s] = 0;
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int idx = tid + 256 * s, br = idx >> 3, part = idx & 7;
-            const int64_t i = i0 + part * 8;
-            rb[s] = (i < d.n_pad) ? *reinterpret_cast<const uint4 *>(psT + (int64_t)br * d.n_pad + i) : make_uint4(0, 0, 0, 0);
-        }
-        const int64_t row = i0 + frow;
-        if (row < row1) {
-            const float4 *pp = reinterpret_cast<const float4 *>(ph + row * 32 + fcg * 8);
-            rp0 = pp[0];
-            rp1 = pp[1];
-            rsc = scales[d.scale_off + row * nblk_row + cb];
-        } else {
-            rp0 = make_float4(0.0f, 0.0f, 0.0f, 0.0f); rp1 = rp0; rsc = 0.0f;
-        }
+    // A chunk's loads are held in registers until its turn in LDS; two chunks are in flight.  Every
+    // load is unconditional (rows at or beyond the end of the tile re-read its last row and get zero
+    // factor operands instead): the waits on a chunk can then leave the younger chunk's loads pending.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    struct ChunkRegs {
+        u32x4 g0, g1, g2, g3, b0, b1, b2;
+        uint32_t cw0, cw1, cw2, cw3;
+        f32x4v p0, p1;
+        float sc;
     };
-    auto store_chunk = [&]() {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int idx = tid + 256 * s, rr = idx >> 4, oct = idx & 15;
-            uint32_t qb[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float lo = (float)code_field(rcw[s], 2 * e2, 4);
-                const float hi = (float)code_field(rcw[s], 2 * e2 + 1, 4);
-                qb[e2] = pack_hi16(lo, hi);              // small integers: exact in bf16
-            }
-            *reinterpret_cast<uint4 *>(tg + rr * kTPitch + oct * 8) = rg[s];
-            *reinterpret_cast<uint4 *>(tq + rr * kTPitch + oct * 8) = make_uint4(qb[0], qb[1], qb[2], qb[3]);
-        }
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int idx = tid + 256 * s, br = idx >> 3, part = idx & 7;
-            *reinterpret_cast<uint4 *>(sb + br * kBStride + part * 8) = rb[s];
+    const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
+    const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
+    const int brow = tid >> 3, bpart = tid & 7;     // P^ split roles: (split, c) rows brow + 32 s, 8 rows of the chunk
+    auto load_chunk = [&](ChunkRegs &r, int64_t i0) {
+        const int64_t last = row1 - 1;
+        {
+            const int64_t row = (i0 + frow < row1) ? i0 + frow : last;
+            const f32x4v *pp = reinterpret_cast<const f32x4v *>(ph + row * 32 + fcg * 8);
+            r.p0 = pp[0];
+            r.p1 = pp[1];
+            r.sc = scales[d.scale_off + row * nblk_row + cb];
         }
         {
-            const float dstep = rsc * inv_levels(4);
-            const float pv[8] = {rp0.x, rp0.y, rp0.z, rp0.w, rp1.x, rp1.y, rp1.z, rp1.w};
+            // the chunk's tile of the split table, contiguous (rows from n to n_pad are zero; a chunk
+            // beyond n_pad re-reads tile 0 and is masked when stored)
+            const int64_t tile = (i0 < d.n_pad) ? (i0 >> 6) : 0;
+            const uint16_t *src = psT + tile * kSplitTile + tid * 8;
+            r.b0 = *reinterpret_cast<const u32x4 *>(src);
+            r.b1 = *reinterpret_cast<const u32x4 *>(src + 2048);
+            r.b2 = *reinterpret_cast<const u32x4 *>(src + 4096);
+        }
+        int64_t e[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int64_t row = (i0 + grow + 16 * s < row1) ? i0 + grow + 16 * s : last;
+            e[s] = row * m + col0;
+        }
+        r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0] + goct * 8);
+        r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1] + goct * 8);
+        r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2] + goct * 8);
+        r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3] + goct * 8);
+        r.cw0 = cw[(e[0] >> 3) + goct];
+        r.cw1 = cw[(e[1] >> 3) + goct];
+        r.cw2 = cw[(e[2] >> 3) + goct];
+        r.cw3 = cw[(e[3] >> 3) + goct];
+    };
+    auto store_chunk = [&](const ChunkRegs &r, int64_t i0) {
+        const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
+        const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u32x4 qb;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float lo = (float)code_field(cs[s], 2 * e2, 4);
+                const float hi = (float)code_field(cs[s], 2 * e2 + 1, 4);
+                qb[e2] = pack_hi16(lo, hi);              // small integers: exact in bf16
+            }
+            *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
+            *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
+        }
+        {
+            const bool ok = i0 < d.n_pad;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(sb + brow * kBStride + bpart * 8) = ok ? r.b0 : z;
+            *reinterpret_cast<u32x4 *>(sb + (brow + 32) * kBStride + bpart * 8) = ok ? r.b1 : z;
+            *reinterpret_cast<u32x4 *>(sb + (brow + 64) * kBStride + bpart * 8) = ok ? r.b2 : z;
+        }
+        {
+            // rows at or beyond the end of the tile: zero operand, whatever the re-read row holds
+            const float dstep = (i0 + frow < row1) ? r.sc * inv_levels(4) : 0.0f;
+            const float pv[8] = {r.p0[0], r.p0[1], r.p0[2], r.p0[3], r.p1[0], r.p1[1], r.p1[2], r.p1[3]};
             float hh[8], mm[8], ll[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) split3(dstep * pv[j], hh[j], mm[j], ll[j]);
@@ -408,12 +476,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
     const int tr_d = tr_row * 32 + tr_col;                      // d P^ tile
 
-    load_chunk(row0);
-    for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
-        __syncthreads();
-        store_chunk();
-        __syncthreads();
-        if (i0 + kQRows < row1) load_chunk(i0 + kQRows);
+    auto compute_chunk = [&]() {
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
             Frag bg, bq, aP[3], aD[3];
@@ -433,6 +496,24 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
+    };
+
+    // Two chunks per trip, one register set each.  A tile with an odd number of chunks runs one
+    // chunk past its end: all of that chunk's factor operands are zero.
+    ChunkRegs ra, rb;
+    load_chunk(ra, row0);
+    load_chunk(rb, row0 + kQRows);
+    for (int64_t i0 = row0; i0 < row1; i0 += 2 * kQRows) {
+        __syncthreads();                // everybody is done reading the previous chunk
+        store_chunk(ra, i0);
+        __syncthreads();
+        load_chunk(ra, i0 + 2 * kQRows);
+        compute_chunk();
+        __syncthreads();
+        store_chunk(rb, i0 + kQRows);
+        __syncthreads();
+        load_chunk(rb, i0 + 3 * kQRows);
+        compute_chunk();
     }
     // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
     const int kcol = col0 + 32 * wave + r32;
@@ -507,7 +588,7 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][kErrTileElems];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const WorkItem it = dp.err_m_items[blockIdx.x];
+    const WorkItem it = dp.err_m_items[xcd_contiguous_item(blockIdx.x, dp.n_err_m)];
     const MatDesc d = dp.mats[it.mat];
     const int m = (int)d.m, m8 = m >> 3, nblk_row = m >> 7;
     const int64_t row0 = (int64_t)it.a + 16 * wave;

@@ -1,17 +1,17 @@
 // Octet kernel family: the streaming passes for matrices whose rows hold whole scale blocks
-// (cols % block == 0, block/8 a power of two <= 64) and rank <= 8.
+// (cols % block == 0, block/8 a power of two <= 64) and rank 2, 4 or 8.
 //
 // A lane owns an "octet": 8 consecutive elements of a row -- one 16-byte (bf16) or two 16-byte
 // (fp32) gradient loads, 16/32/64 bits of codes, one Philox call in the error pass.  `lr` lanes
 // (8..64, a power of two) cover a row segment; 64/lr rows share a wave.
 //
-//   P pass    one wave per 64-row x column-chunk item.  Octets are decoded in the coalesced load
-//             layout, p goes through a wave-private LDS tile and is read back with one lane per
-//             ROW, so the rank-r dot products run down the row inside a lane: Q (an fp64 copy,
-//             wave-uniform address, scalar loads) is an SGPR operand, and no cross-lane sum is
-//             needed.  fp64 accumulation: products of fp32 values are exact, one rounding at the end.
-//   Q+ pass   one workgroup per 512-column strip x row tile; a lane keeps 8 x r fp64 sums for its
-//             8 columns while the waves walk down the rows; P^ rows are per-lane broadcast loads.
+//   P pass    one wave per 64-row x column-chunk item on the fp64 matrix cores (rank padded to 16
+//             columns).  Octets are decoded in the coalesced load layout, p goes through a
+//             wave-private LDS tile and comes back in the operand layout; Q is read as an fp64 copy.
+//             Products of fp32 values are exact in fp64, the sum stays in fp64, one rounding at the end.
+//   Q+ pass   one wave per 64-column x row-tile item, same instruction with the roles of rows and
+//             columns exchanged; per-tile fp64 partial sums go to the workspace and are added in
+//             tile order by the reduction kernel.
 //   err pass  one wave per strip x row range, Q+ tile (8 x r) in registers, residual as the fp32
 //             fma chain, block max-norm by DPP, fixed-point stochastic rounding, pack, in place.
 //
@@ -22,6 +22,8 @@
 namespace conef {
 
 namespace {
+
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ octet load / decode
 template <bool BF16, int BITS>
@@ -56,6 +58,33 @@ __device__ __forceinline__ RawOctet<BF16, BITS> load_octet(const MatDesc &d, con
         }
         r.scale = scales[d.scale_off + (o >> d.lb_shift)];
     }
+    return r;
+}
+
+// The same without a condition: `o` must be an octet of the matrix (callers clamp).  Loads behind a
+// condition cost a branch each and make the waits on them conservative.
+template <bool BF16, int BITS>
+__device__ __forceinline__ RawOctet<BF16, BITS> load_octet_always(const MatDesc &d, const void *__restrict__ grads,
+                                                                  const uint32_t *codes, const float *scales, int64_t o)
+{
+    RawOctet<BF16, BITS> r;
+    r.g1 = make_uint4(0, 0, 0, 0); r.c1 = 0;
+    if (BF16) {
+        r.g0 = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(grads) + d.grad_off + o * 8);
+    } else {
+        const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(grads) + d.grad_off + o * 8);
+        r.g0 = gp[0];
+        r.g1 = gp[1];
+    }
+    if (BITS == 8) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + d.word_off + o * 2);
+        r.c0 = c.x; r.c1 = c.y;
+    } else if (BITS == 4) {
+        r.c0 = codes[d.word_off + o];
+    } else {
+        r.c0 = reinterpret_cast<const uint16_t *>(codes + d.word_off)[o];
+    }
+    r.scale = scales[d.scale_off + (o >> d.lb_shift)];
     return r;
 }
 
@@ -207,95 +236,123 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 }
 
 // ------------------------------------------------------------------ Q+ pass
-template <bool BF16, int BITS, int RP>
-__global__ __launch_bounds__(256) void k_q_octet(DevicePlan dp, const void *__restrict__ grads,
-                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                 const float *__restrict__ Phat, double *ws)
+// Q+ = p^T P^ on the fp64 matrix cores: D[k][c] += sum_i A[k][i] B[i][c] with A[k][i] = p[row i][column k]
+// and B[i][c] = P^[row i][c], four rows per instruction, fp64 sums throughout (no fp32 partial sums).
+// One wave per (64 columns, row tile), independent of the other waves.  Rows are walked 32 at a
+// time: octets are decoded in the coalesced load layout (8 lanes per row) into a wave-private LDS
+// tile (32 rows x 64 columns of p), read back one value per lane and instruction; the rows of P^
+// are converted from fp32.  Loads run one step ahead.  Partial sums per row tile go to the workspace.
+constexpr int kQTileCols = 64;
+constexpr int kQTilePitch = 80;     // floats per LDS tile row: rows 0..3 of a group fall on distinct banks
+constexpr int kQStepRows = 32;
+
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
+               const float *__restrict__ scales, const float *__restrict__ Phat, double *ws)
 {
-    __shared__ double red[64 * 8 * RP];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const WorkItem it = dp.q_f_items[blockIdx.x];
+    __shared__ __attribute__((aligned(16))) float tiles[4][kQStepRows * kQTilePitch];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_q_f) return;
+    float *T = tiles[wave];
+    const WorkItem it = dp.q_f_items[item];
     const MatDesc d = dp.mats[it.mat];
-    constexpr int r = RP;                 // this family is instantiated for the exact rank
-    const int lr = 1 << d.lr_shift, rw = 64 >> d.lr_shift;
-    const int sub = lane >> d.lr_shift, lc = lane & (lr - 1);
-    const int oc = it.a * lr + lc;
+    const int r = dp.rank;
+    const int col0 = it.a * kQTileCols;
     const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
     const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
+    const int lrow = lane >> 3, loct = lane & 7;      // load layout: 8 lanes per row, rows lrow + 8 s
+    const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
+    // columns at or beyond m (last strip) read the last octet of the row instead: they only feed
+    // rows of D that are not stored
+    const int64_t oct0 = ((col0 >> 3) + loct < d.m8) ? (col0 >> 3) + loct : d.m8 - 1;
 
-    double acc[8][RP];
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int c = 0; c < RP; ++c) acc[e][c] = 0.0;
+    const int mic = mi < r ? mi : r - 1;
 
-    int64_t row = row0 + wave * rw + sub;
-    bool valid = row < row1;
-    RawOctet<BF16, BITS> cur = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oc, valid);
-    float ph[RP];
-    load_factor_row<RP>(Phat, d.p_off + row * r, valid, ph);
-    for (int64_t r0 = row0 + wave * rw; r0 < row1; r0 += 4 * rw) {
-        const int64_t nrow = row + 4 * rw;
-        const bool nvalid = nrow < row1;
-        const RawOctet<BF16, BITS> nxt = load_octet<BF16, BITS>(d, grads, codes, scales, nrow * d.m8 + oc, nvalid);
-        float nph[RP];
-        load_factor_row<RP>(Phat, d.p_off + nrow * r, nvalid, nph);
+    f64x4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-        float p[8];
-        decode_octet<BF16, BITS>(cur, p);           // an invalid lane holds zeros: p = 0, ph = 0
-        double pd[RP];
+    constexpr int kLoads = kQStepRows / 8, kGroups = kQStepRows / 4;
+    struct Step {
+        RawOctet<BF16, BITS> o[kLoads];
+        float ph[kGroups];        // P^[i0 + 4 g + mk][mi]
+    };
+    auto load_step = [&](Step &st, int64_t i0) {
 #pragma unroll
-        for (int c = 0; c < RP; ++c) pd[c] = (double)ph[c];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const double pe = (double)p[e];
-#pragma unroll
-            for (int c = 0; c < RP; ++c) acc[e][c] = __builtin_fma(pe, pd[c], acc[e][c]);
+        for (int s = 0; s < kLoads; ++s) {
+            int64_t row = i0 + lrow + 8 * s;
+            row = row < row1 ? row : row1 - 1;
+            st.o[s] = load_octet_always<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oct0);
         }
-        cur = nxt;
+        // rows at or beyond row1 re-read the last row; their P^ operand is zero
 #pragma unroll
-        for (int c = 0; c < RP; ++c) ph[c] = nph[c];
-        row = nrow;
-        valid = nvalid;
-    }
-    // rows that shared the wave (lane groups above lr) hold sums for the same columns
-    for (int o = lr; o < 64; o <<= 1) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-#pragma unroll
-            for (int c = 0; c < RP; ++c) acc[e][c] += __shfl_xor(acc[e][c], o, 64);
-    }
-    // waves 0..3 are added in that order
-    for (int w2 = 0; w2 < 4; ++w2) {
-        if (wave == w2 && sub == 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-#pragma unroll
-                for (int c = 0; c < RP; ++c) {
-                    const int idx = (e * RP + c) * lr + lc;
-                    red[idx] = (w2 == 0) ? acc[e][c] : red[idx] + acc[e][c];
-                }
+        for (int g = 0; g < kGroups; ++g) {
+            const int64_t row = i0 + 4 * g + mk;
+            const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + mic];
+            st.ph[g] = (row < row1 && mi < r) ? v : 0.0f;
         }
-        __syncthreads();
+    };
+
+    Step cur;
+    load_step(cur, row0);
+    for (int64_t i0 = row0; i0 < row1; i0 += kQStepRows) {
+        // decode into the tile
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s) {
+            float p[8];
+            decode_octet<BF16, BITS>(cur.o[s], p);
+            float4 *dst = reinterpret_cast<float4 *>(T + (lrow + 8 * s) * kQTilePitch + loct * 8);
+            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
+            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+        }
+        float b[kGroups];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) b[g] = cur.ph[g];
+        load_step(cur, i0 + kQStepRows);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const double bg = (double)b[g];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const double a = (double)T[(4 * g + mk) * kQTilePitch + 16 * t + mi];
+                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bg, acc[t], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
     }
-    if (wave == 0 && sub == 0) {
-        double *out = ws + d.qpart_off + ((int64_t)it.b * d.m + (int64_t)oc * 8) * r;
+    // D[4 v + mk][mi]: column col0 + 16 t + 4 v + mk of the matrix, factor column mi
+    if (mi < r) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int c = 0; c < RP; ++c)
-                out[e * r + c] = red[(e * RP + c) * lr + lc];
+            for (int v = 0; v < 4; ++v) {
+                const int col = col0 + 16 * t + 4 * v + mk;
+                if (col < d.m) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + mi] = acc[t][v];
+            }
+        }
     }
 }
 
 // ------------------------------------------------------------------ P pass
+// P = p Q on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): products of fp32 values are exact in
+// fp64 and the sum is kept in fp64, as in a plain fp64 loop; the rank (<= 16) is padded to the
+// 16 columns of the instruction with zeros.
+//   operand layout: lane l holds A[l%16][l/16], B[l/16][l%16] and D[4v + l/16][l%16], v = 0..3.
+// One wave per (64 rows, column chunk).  Octets are decoded in the coalesced load layout into a
+// wave-private LDS tile (64 rows x 32 columns of p, fp32); A[i][kk] = p[row i][column 4j + kk] is
+// read back one value per lane (conflict-free), B[kk][c] = Q[column 4j + kk][c] is read from Q, eight
+// values per lane and sub-tile, loaded one sub-tile ahead.  Four waves per SIMD need <= 128 registers.
 constexpr int kSubCols = 32;        // columns per LDS sub-tile
 constexpr int kTileStride = 36;     // floats per LDS tile row: 32 columns + 4 of padding
 
-template <bool BF16, int BITS, int RP>
-__global__ __launch_bounds__(256) void k_p_octet(DevicePlan dp, const void *__restrict__ grads,
-                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                 const double *__restrict__ Qd, float *P, double *ws)
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
+               const float *__restrict__ scales, const float *__restrict__ Q, float *P, double *ws)
 {
     __shared__ float tiles[4][kPTileRows * kTileStride];
     const int lane = threadIdx.x & 63;
@@ -305,23 +362,46 @@ __global__ __launch_bounds__(256) void k_p_octet(DevicePlan dp, const void *__re
     float *T = tiles[wave];
     const WorkItem it = dp.p_f_items[item];
     const MatDesc d = dp.mats[it.mat];
-    constexpr int r = RP;
+    const int r = dp.rank;
     const int64_t row0 = it.a;
     const int c_begin = it.b * d.p_chunk_cols;
     const int c_end = (c_begin + d.p_chunk_cols < d.m) ? c_begin + d.p_chunk_cols : (int)d.m;
     const int lrow = lane >> 2, loct = lane & 3;      // load layout: 4 lanes per row, 16 rows per step
+    const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
 
-    double acc[RP];
+    f64x4 acc[4];
 #pragma unroll
-    for (int c = 0; c < RP; ++c) acc[c] = 0.0;
+    for (int t = 0; t < 4; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+    // B operand of a sub-tile: Q[col0 + 4 j + mk][mi], j = 0..7; zero for mi >= rank and for columns
+    // at or beyond the end of the chunk (the tile holds other data of the same rows there)
+    const int mic = mi < r ? mi : r - 1;
+    auto load_b = [&](float (&bq)[8], int col0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int col = col0 + 4 * j + mk;
+            const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + mic];
+            bq[j] = (col < c_end && mi < r) ? v : 0.0f;
+        }
+    };
+    // rows at or beyond n re-read the last row (their rows of D are not stored); octets at or beyond the
+    // end of the chunk re-read its last octet (their B operand is zero)
+    const int oct_end = c_end >> 3;
+    auto load_tile = [&](RawOctet<BF16, BITS> (&o)[4], int col0) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            int64_t row = row0 + s * 16 + lrow;
+            row = row < d.n ? row : d.n - 1;
+            int oc = (col0 >> 3) + loct;
+            oc = oc < oct_end ? oc : oct_end - 1;
+            o[s] = load_octet_always<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oc);
+        }
+    };
 
     RawOctet<BF16, BITS> cur[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int64_t row = row0 + s * 16 + lrow;
-        const int col = c_begin + loct * 8;
-        cur[s] = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + (col >> 3), row < d.n && col < c_end);
-    }
+    load_tile(cur, c_begin);
+    float bq[8], bn[8];
+    load_b(bq, c_begin);
     for (int col0 = c_begin; col0 < c_end; col0 += kSubCols) {
         // decode the loaded sub-tile into the wave's LDS tile (row-major, padded)
 #pragma unroll
@@ -333,60 +413,36 @@ __global__ __launch_bounds__(256) void k_p_octet(DevicePlan dp, const void *__re
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
         }
         // issue the loads of the next sub-tile
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int64_t row = row0 + s * 16 + lrow;
-            const int col = col0 + kSubCols + loct * 8;
-            cur[s] = load_octet<BF16, BITS>(d, grads, codes, scales, row * d.m8 + (col >> 3), row < d.n && col < c_end);
-        }
+        load_b(bn, col0 + kSubCols);
+        load_tile(cur, col0 + kSubCols);
         __builtin_amdgcn_wave_barrier();
-        // one lane per row: run down the row against the wave-uniform rows of Q
-        const int kmax = (c_end - col0 < kSubCols) ? c_end - col0 : kSubCols;          // multiple of 8
-        const double *qrow = Qd + d.q_off + (int64_t)col0 * r;
-        if (kmax == kSubCols) {
-            // full sub-tile: fixed trip count, so the scalar loads of Q can be batched ahead of their use
 #pragma unroll
-            for (int k4 = 0; k4 < kSubCols; k4 += 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(T + lane * kTileStride + k4);
-                const float pv[4] = {v.x, v.y, v.z, v.w};
+        for (int j = 0; j < 8; ++j) {
+            const double b = (double)bq[j];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const double pe = (double)pv[j];
-#pragma unroll
-                    for (int c = 0; c < RP; ++c) acc[c] = __builtin_fma(pe, qrow[(k4 + j) * r + c], acc[c]);
-                }
-            }
-        } else {
-            for (int k4 = 0; k4 < kmax; k4 += 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(T + lane * kTileStride + k4);
-                const float pv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const double pe = (double)pv[j];
-#pragma unroll
-                    for (int c = 0; c < RP; ++c) acc[c] = __builtin_fma(pe, qrow[(k4 + j) * r + c], acc[c]);
-                }
+            for (int t = 0; t < 4; ++t) {
+                const double a = (double)T[(16 * t + mi) * kTileStride + 4 * j + mk];
+                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[t], 0, 0, 0);
             }
         }
         __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bq[j] = bn[j];
     }
-    const int64_t row = row0 + lane;
-    if (row < d.n) {
-        if (d.n_p_chunks == 1) {
+    // D[4 v + mk][mi]: row 16 t + 4 v + mk of the tile, factor column mi
+    if (mi < r) {
 #pragma unroll
-            for (int c = 0; c < RP; ++c) P[d.p_off + row * r + c] = (float)acc[c];
-        } else {
-            double *out = ws + d.ppart_off + ((int64_t)it.b * d.n + row) * r;
+        for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int c = 0; c < RP; ++c) out[c] = acc[c];
+            for (int v = 0; v < 4; ++v) {
+                const int64_t row = row0 + 16 * t + 4 * v + mk;
+                if (row < d.n) {
+                    if (d.n_p_chunks == 1) P[d.p_off + row * r + mi] = (float)acc[t][v];
+                    else ws[d.ppart_off + ((int64_t)it.b * d.n + row) * r + mi] = acc[t][v];
+                }
+            }
         }
     }
-}
-
-__global__ __launch_bounds__(256) void k_widen(const float *__restrict__ in, double *__restrict__ out, long long n)
-{
-    const long long stride = (long long)gridDim.x * 256;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = (double)in[i];
 }
 
 }  // namespace
@@ -419,25 +475,34 @@ __global__ __launch_bounds__(256) void k_widen(const float *__restrict__ in, dou
         }                                                                            \
     } while (0)
 
-void octet_widen_q(const DevicePlan &dp, const float *Q, double *ws, hipStream_t st)
-{
-    if (dp.n_p_f <= 0) return;
-    hipLaunchKernelGGL(k_widen, dim3(512), dim3(256), 0, st, Q, ws + dp.qd_off, dp.q_elems);
-}
+#define CONEF_OCTET2_CASE(KERNEL, BF, B, GRID, ST, ...) \
+    case ((BF ? 1 : 0) << 8) | B: hipLaunchKernelGGL((KERNEL<BF, B>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;
 
-void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, float *P,
-                  double *ws, hipStream_t st)
+#define CONEF_OCTET2_DISPATCH(KERNEL, GRID, ST, ...)                     \
+    do {                                                                 \
+        switch ((dp.dtype << 8) | dp.bits) {                             \
+            CONEF_OCTET2_CASE(KERNEL, false, 2, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2_CASE(KERNEL, false, 4, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2_CASE(KERNEL, false, 8, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2_CASE(KERNEL, true, 2, GRID, ST, __VA_ARGS__)    \
+            CONEF_OCTET2_CASE(KERNEL, true, 4, GRID, ST, __VA_ARGS__)    \
+            CONEF_OCTET2_CASE(KERNEL, true, 8, GRID, ST, __VA_ARGS__)    \
+        default: break;                                                  \
+        }                                                                \
+    } while (0)
+
+void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
+                  const float *Q, float *P, double *ws, hipStream_t st)
 {
     if (dp.n_p_f <= 0) return;
-    const double *Qd = ws + dp.qd_off;
-    CONEF_OCTET_DISPATCH(k_p_octet, dim3((dp.n_p_f + 3) / 4), st, dp, grads, codes, scales, Qd, P, ws);
+    CONEF_OCTET2_DISPATCH(k_p_octet, dim3((dp.n_p_f + 3) / 4), st, dp, grads, codes, scales, Q, P, ws);
 }
 
 void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                   const float *Phat, double *ws, hipStream_t st)
 {
     if (dp.n_q_f <= 0) return;
-    CONEF_OCTET_DISPATCH(k_q_octet, dim3(dp.n_q_f), st, dp, grads, codes, scales, Phat, ws);
+    CONEF_OCTET2_DISPATCH(k_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, codes, scales, Phat, ws);
 }
 
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,

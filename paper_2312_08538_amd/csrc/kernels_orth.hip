@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     if constexpr (RP == 32) {
         // Matrix-core family: the operand splits of P^ (x = hi + mid + lo, three bf16 values by
         // truncation) that its Q+ and err passes read, written while the tile is at hand:
-        // row-major [3][n][32] and transposed [3][32][n_pad] (rows >= n zero).
+        // row-major [3][n][32] and transposed in tiles of 64 rows, [n_pad / 64][3 x 32][64] (rows >= n zero).
         if (write_splits && d.path == kPathMfma) {          // uniform
             __shared__ __attribute__((aligned(16))) uint16_t ts[3][32][64 + 8];
             uint16_t *rm = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.ps_off);
@@ -263,13 +263,10 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
                 ts[0][c][rr] = bh; ts[1][c][rr] = bm; ts[2][c][rr] = bl;
             }
             __syncthreads();
-            uint16_t *tr = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.psT_off);
+            uint16_t *tr = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.psT_off) + (row0 >> 6) * kSplitTile;
             for (int e = t; e < 96 * 8; e += 256) {
                 const int sc = e >> 3, part = e & 7;
-                const int64_t i0 = row0 + part * 8;
-                if (i0 < d.n_pad)
-                    *reinterpret_cast<uint4 *>(tr + (int64_t)sc * d.n_pad + i0) =
-                        *reinterpret_cast<const uint4 *>(&ts[sc >> 5][sc & 31][part * 8]);
+                *reinterpret_cast<uint4 *>(tr + e * 8) = *reinterpret_cast<const uint4 *>(&ts[sc >> 5][sc & 31][part * 8]);
             }
         }
     }

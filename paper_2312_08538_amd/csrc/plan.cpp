@@ -44,9 +44,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         // rows per wave item of the err pass: aim at >= ~4096 wave items over the model
         int err_rows = 128;
         while (err_rows > 8 && total_elems / ((int64_t)err_rows * 512) < 4096) err_rows >>= 1;
-        // rows per workgroup item of the Q+ pass (512 columns wide): aim at >= ~768 workgroups
+        // rows per wave item of the Q+ pass (64 columns wide): aim at >= ~4096 wave items
         int q_rows = 512;
-        while (q_rows > 32 && total_elems / ((int64_t)q_rows * 512) < 768) q_rows >>= 1;
+        while (q_rows > 64 && total_elems / ((int64_t)q_rows * 64) < 4096) q_rows >>= 1;
         // columns per wave item of the P pass (64 rows high): aim at >= ~2048 wave items
         int p_cols = 512;
         while (p_cols > 64 && total_elems / ((int64_t)kPTileRows * p_cols) < 2048) p_cols >>= 1;
@@ -78,7 +78,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
-            d.n_pad = (int32_t)round_up(d.n, 32);
+            d.n_pad = (int32_t)round_up(d.n, 64);
             if (d.path == kPathMfma) {
                 d.qsT_off = wd; wd += round_up(3 * 32 * d.m * 2 / 8, 32);
                 d.psT_off = wd; wd += round_up(3 * 32 * (int64_t)d.n_pad * 2 / 8, 32);
@@ -109,7 +109,6 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         }
         plan.grad_elems = (size_t)g; plan.code_words = (size_t)w; plan.n_scales = (size_t)s;
         plan.p_elems = (size_t)p; plan.q_elems = (size_t)q;
-        if (plan.any_octet) { plan.qd_off = (size_t)round_up(wd, 32); wd = (int64_t)plan.qd_off + q; }
         plan.ws_doubles = (size_t)round_up(wd, 32);
         plan.workspace_bytes = (size_t)round_up((int64_t)plan.ws_doubles * 8, 256);
 
@@ -153,11 +152,12 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;
                 // neighbouring waves (one workgroup, one CU) take neighbouring row tiles of the SAME column
-                // chunk: they read the same rows of Q through the scalar cache at about the same time
+                // chunk: they read the same rows of Q at about the same time
                 for (int32_t cc = 0; cc < d.n_p_chunks; ++cc)
                     for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
+                const int32_t qstrips = (int32_t)ceil_div(d.m, 64);
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
-                    for (int32_t st = 0; st < strips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
+                    for (int32_t st = 0; st < qstrips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
                 const int64_t rows_item = (int64_t)std::max(err_rows, rw);
                 for (int64_t r0 = 0; r0 < d.n; r0 += rows_item)
                     for (int32_t st = 0; st < strips; ++st)

@@ -17,6 +17,7 @@ constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (on
 
 enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
 constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
+constexpr int kSplitTile = 3 * 32 * 64;  // bf16 per tile of a transposed split table: 3 splits x 32 columns x 64 rows
 constexpr int kErrRows = 128;       // rows per workgroup item of the MFMA err pass (8 waves x 16)
 constexpr int kErrRun = 16;         // column blocks of 128 per item of the MFMA err pass (at most 16)
 
@@ -39,10 +40,10 @@ struct MatDesc {
     int32_t lr_shift;               // log2(lanes per row segment), 3..6
     int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
     int32_t m8;                     // m / 8
-    int32_t n_pad;                  // MFMA family: n rounded up to a multiple of 32
+    int32_t n_pad;                  // MFMA family: n rounded up to a multiple of 64
     // MFMA family: bf16 triple splits of the factors (x = hi + mid + lo), offsets in doubles
-    int64_t qsT_off;                // Q_state, transposed: [3][32][m]
-    int64_t psT_off;                // P^, transposed:      [3][32][n_pad]
+    int64_t qsT_off;                // Q_state, transposed in tiles of 64 rows: [m / 64][3 x 32][64]
+    int64_t psT_off;                // P^, transposed in tiles of 64 rows: [n_pad / 64][3 x 32][64]
     int64_t ps_off;                 // P^, row-major:       [3][n][32]
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
 };
@@ -57,7 +58,6 @@ struct Plan {
     uint64_t seed = 0;
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
-    size_t qd_off = 0;              // doubles: fp64 copy of Q_state (q_elems entries), 0 if unused
     bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;
     size_t ws_doubles = 0;
     size_t workspace_bytes = 0;
@@ -67,7 +67,7 @@ struct Plan {
     std::vector<WorkItem> err_items;    // pass 3: (mat, first block, blocks per wave)
     // octet family (one item per wave for p and err, per workgroup for q)
     std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk)
-    std::vector<WorkItem> q_f_items;    // (mat, strip, row tile)
+    std::vector<WorkItem> q_f_items;    // (mat, 64-column strip, row tile)
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
