@@ -64,6 +64,7 @@ void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                  const float *Q, float *P, double *ws, hipStream_t st, bool prep_only, bool main_only);
 
 void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st);
+void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st);
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Phat, double *ws, float *Qout, hipStream_t st);
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,

@@ -257,6 +257,8 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
     // the factors handed in may differ from those the orthonormalisation stage produced (e.g. after
     // an all-reduce), unless the caller says otherwise
     if (!p_splits_ready) mfma_split_p_hat(dp, Phat, ws, st);
+    // the matrix-core family reads the block scales of the incoming error state column block by column block
+    mfma_transpose_scales(dp, scales, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
@@ -276,6 +278,7 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
         // the factors handed in may differ from those the Q+ stage saw (e.g. after an all-reduce)
         mfma_split_p_hat(dp, Phat, ws, st);
         mfma_split_q_new(dp, Qn, ws, st);
+        mfma_transpose_scales(dp, scales, ws, st);      // the state may have changed since a Q+ stage ran
     }
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_err(dp, grads, codes, scales, ws, step, st);

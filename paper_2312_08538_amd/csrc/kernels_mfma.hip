@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 }
 
 // ------------------------------------------------------------------ splits of P^ and Q+
-// P^ (n x 32): transposed splits for the Q+ pass and row-major splits for the err pass.
+// P^ (n x 32): row-major operand splits for the err pass.
 __global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float *__restrict__ Phat, double *ws)
 {
     const WorkItem it = dp.split_p_items[blockIdx.x];
@@ -304,7 +304,34 @@ __global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float 
             rm[((int64_t)2 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
         }
     }
-    split_transposed_tile(src, reinterpret_cast<uint16_t *>(ws + d.psT_off), (int)d.n, r0);
+}
+
+// Column-block-major copy of the block scales of a matrix, scT[block of the row][row]: the Q+ and err
+// passes need, per 128-column block, the scales of consecutive rows, which are a row pitch apart
+// (a 128-byte line each) in the state's own row-major order.  One workgroup per 64 rows.
+__global__ __launch_bounds__(256) void k_transpose_scales(DevicePlan dp, const float *__restrict__ scales, double *ws)
+{
+    __shared__ float tile[64 * 33];
+    const WorkItem it = dp.split_p_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t row0 = (int64_t)it.a * 64;
+    const int nblk_row = (int)(d.m >> 7), tid = threadIdx.x;
+    const float *src = scales + d.scale_off;
+    float *dst = reinterpret_cast<float *>(ws + d.scT_off);
+    for (int b0 = 0; b0 < nblk_row; b0 += 32) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 5, j = idx & 31;
+            tile[rr * 33 + j] = (row0 + rr < d.n && b0 + j < nblk_row) ? src[(row0 + rr) * nblk_row + b0 + j] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int idx = tid + 256 * s, j = idx >> 6, rr = idx & 63;
+            if (row0 + rr < d.n && b0 + j < nblk_row) dst[(int64_t)(b0 + j) * d.n + row0 + rr] = tile[rr * 33 + j];
+        }
+        __syncthreads();
+    }
 }
 
 // Q+ (m x 32): splits for the err pass, in the order its matrix-core tiles read them:
@@ -337,12 +364,15 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 // needs, per lane, 8 rows of ONE column: the raw gradient rows and the codes (as bf16 integers) go
 // row-major into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16
 // (within 16 lanes: lane i supplies the address of 4 consecutive columns of row i / 4, chunk i % 4;
-// lane n receives column n of those 4 rows).  The splits of d_i P^ are made once per chunk by the
-// whole workgroup, stored row-major and read the same way; the splits of P^ come transposed from
-// the workspace as before.  fp32 sums of the matrix cores cover one chunk; chunks are added in fp64.
+// lane n receives column n of those 4 rows).  The splits of P^ and of d_i P^ are made once per chunk
+// by the whole workgroup from the fp32 rows of P^, stored row-major and read the same way: the only
+// factor data a chunk fetches are 8 KB of P^ and its 64 block scales (from the column-block-major
+// copy of the scales, 256 contiguous bytes).  Everything a workgroup loads passes through the L2,
+// whose bandwidth bounds this pass: tables of ready-made splits would cost more of it than the
+// splitting costs in arithmetic.  fp32 sums of the matrix cores cover one chunk; chunks are added
+// in fp64.
 constexpr int kQRows = 64;                  // rows per chunk
 constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
-constexpr int kBStride = kQRows + 8;        // bf16 per (split, c) row of the P^ tile in LDS
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
@@ -362,7 +392,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 {
     __shared__ __attribute__((aligned(16))) uint16_t tg[kQRows * kTPitch];      // gradient rows, raw bf16
     __shared__ __attribute__((aligned(16))) uint16_t tq[kQRows * kTPitch];      // codes as bf16 integers
-    __shared__ __attribute__((aligned(16))) uint16_t sb[96 * kBStride];         // splits of P^, [split, c][row]
+    __shared__ __attribute__((aligned(16))) uint16_t sb[3 * kQRows * 32];       // splits of P^, [split][row][c]
     __shared__ __attribute__((aligned(16))) uint16_t sd[3 * kQRows * 32];       // splits of d_i P^, [split][row][c]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WorkItem it = dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
@@ -373,9 +403,8 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
     const uint16_t *g = grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
-    const uint16_t *psT = reinterpret_cast<const uint16_t *>(ws + d.psT_off);
+    const float *scT = reinterpret_cast<const float *>(ws + d.scT_off) + (int64_t)cb * d.n;   // this block's scales, by row
     const float *ph = Phat + d.p_off;
-    const int nblk_row = m >> 7;
 
     // A chunk's loads are held in registers until its turn in LDS; two chunks are in flight.  Every
     // load is unconditional (rows at or beyond the end of the tile re-read its last row and get zero
@@ -383,14 +412,13 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef float f32x4v __attribute__((ext_vector_type(4)));
     struct ChunkRegs {
-        u32x4 g0, g1, g2, g3, b0, b1, b2;
+        u32x4 g0, g1, g2, g3;
         uint32_t cw0, cw1, cw2, cw3;
         f32x4v p0, p1;
         float sc;
     };
     const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
     const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
-    const int brow = tid >> 3, bpart = tid & 7;     // P^ split roles: (split, c) rows brow + 32 s, 8 rows of the chunk
     auto load_chunk = [&](ChunkRegs &r, int64_t i0) {
         const int64_t last = row1 - 1;
         {
@@ -398,16 +426,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             const f32x4v *pp = reinterpret_cast<const f32x4v *>(ph + row * 32 + fcg * 8);
             r.p0 = pp[0];
             r.p1 = pp[1];
-            r.sc = scales[d.scale_off + row * nblk_row + cb];
-        }
-        {
-            // the chunk's tile of the split table, contiguous (rows from n to n_pad are zero; a chunk
-            // beyond n_pad re-reads tile 0 and is masked when stored)
-            const int64_t tile = (i0 < d.n_pad) ? (i0 >> 6) : 0;
-            const uint16_t *src = psT + tile * kSplitTile + tid * 8;
-            r.b0 = *reinterpret_cast<const u32x4 *>(src);
-            r.b1 = *reinterpret_cast<const u32x4 *>(src + 2048);
-            r.b2 = *reinterpret_cast<const u32x4 *>(src + 4096);
+            r.sc = scT[row];
         }
         int64_t e[4];
 #pragma unroll
@@ -440,17 +459,25 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
         {
-            const bool ok = i0 < d.n_pad;
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            *reinterpret_cast<u32x4 *>(sb + brow * kBStride + bpart * 8) = ok ? r.b0 : z;
-            *reinterpret_cast<u32x4 *>(sb + (brow + 32) * kBStride + bpart * 8) = ok ? r.b1 : z;
-            *reinterpret_cast<u32x4 *>(sb + (brow + 64) * kBStride + bpart * 8) = ok ? r.b2 : z;
-        }
-        {
-            // rows at or beyond the end of the tile: zero operand, whatever the re-read row holds
-            const float dstep = (i0 + frow < row1) ? r.sc * inv_levels(4) : 0.0f;
-            const float pv[8] = {r.p0[0], r.p0[1], r.p0[2], r.p0[3], r.p1[0], r.p1[1], r.p1[2], r.p1[3]};
+            // rows at or beyond the end of the tile: zero operands, whatever the re-read row holds
+            const bool ok = i0 + frow < row1;
+            const float dstep = ok ? r.sc * inv_levels(4) : 0.0f;
+            float pv[8] = {r.p0[0], r.p0[1], r.p0[2], r.p0[3], r.p1[0], r.p1[1], r.p1[2], r.p1[3]};
             float hh[8], mm[8], ll[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pv[j] = ok ? pv[j] : 0.0f;
+                split3(pv[j], hh[j], mm[j], ll[j]);
+            }
+            {
+                uint16_t *o = sb + frow * 32 + fcg * 8;
+                *reinterpret_cast<uint4 *>(o) =
+                    make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
+                *reinterpret_cast<uint4 *>(o + kQRows * 32) =
+                    make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+                *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
+                    make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
+            }
 #pragma unroll
             for (int j = 0; j < 8; ++j) split3(dstep * pv[j], hh[j], mm[j], ll[j]);
             uint16_t *o = sd + frow * 32 + fcg * 8;
@@ -484,7 +511,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                aP[s].u = *reinterpret_cast<const uint4 *>(sb + (s * 32 + r32) * kBStride + ks * 16 + ig * 8);
+                aP[s].u = lds_read_tr16x8(sb + s * kQRows * 32 + tr_d + ks * 16 * 32, 32);
                 aD[s].u = lds_read_tr16x8(sd + s * kQRows * 32 + tr_d + ks * 16 * 32, 32);
             }
             acc = mfma(aP[0], bg, acc);
@@ -601,12 +628,16 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
     float *sc = scales + d.scale_off;
     const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
+    // incoming scales of the run's first block, by row; block b of the run is b * n further (below 2^32)
+    const float *scT_run = reinterpret_cast<const float *>(ws + d.scT_off) + (int64_t)it.b * d.n;
+    const uint32_t n32 = (uint32_t)d.n;
 
     // Rows of the tile that lie below the matrix are clamped to the matrix's last row for loading
     // (their results are never stored), so every load of the loop is unconditional.
     bool valid[4];
     int64_t grow[4];                 // element offset of the row start
     uint32_t orow[4], srow[4];       // octet / scale offset of the row start (both below 2^32)
+    uint32_t trow[4];                // row, for the column-block-major copy of the incoming scales
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int rr = 4 * kg + v;
@@ -615,6 +646,7 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
         grow[v] = row * m;
         orow[v] = (uint32_t)(row * m8);
         srow[v] = (uint32_t)(row * nblk_row);
+        trow[v] = (uint32_t)row;
     }
 
     // negated splits of this wave's rows of P^
@@ -634,7 +666,7 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
         for (int v = 0; v < 4; ++v) {
             in.g[v] = *reinterpret_cast<const uint4 *>(g + grow[v] + cb * 128 + cc * 8);
             in.cw[v] = cw[orow[v] + (uint32_t)(cb * 16 + cc)];
-            in.s[v] = sc[srow[v] + (uint32_t)cb];
+            in.s[v] = scT_run[(uint32_t)(cb - cb0) * n32 + trow[v]];
         }
     };
     // a block's splits of Q+: 1536 chunks of 16 bytes, three per thread
@@ -692,28 +724,42 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
             uint4 *dst = reinterpret_cast<uint4 *>(sB[(b + 1) & 1]) + tid;
             dst[0] = bq0; dst[512] = bq1; dst[1024] = bq2;
         }
-        // rounding phase, one octet (row 4 kg + v, columns 8 cc ..) at a time
+        // rounding phase.  First the max-norm of each of the lane's four row blocks (16 lanes = one
+        // 128-column block) ...
+        float amax[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float x[8];
             float a = 0.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                x[e] = acc[e][v];
-                a = fmaxf(a, fabsf(x[e]));
-            }
-            // 16 lanes = one 128-column block
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(acc[e][v]));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0xB1, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x4E, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
             a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
-            const float inv16 = (a > 0.0f) ? (7.0f / a) * 65536.0f : 0.0f;
+            amax[v] = a;
+            keep[v] = (cc == b) ? a : keep[v];
+        }
+        // ... then the four reciprocal step sizes s / a: all 16 lanes of a row group need all four, so
+        // lane i of every quad divides for row block i and the quad exchanges the results
+        const int qi = lane & 3;
+        const float asel = (qi == 0) ? amax[0] : (qi == 1) ? amax[1] : (qi == 2) ? amax[2] : amax[3];
+        const float isel = (asel > 0.0f) ? (7.0f / asel) * 65536.0f : 0.0f;
+        const float inv16v[4] = {
+            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x00, 0xF, 0xF, true)),
+            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x55, 0xF, 0xF, true)),
+            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xAA, 0xF, 0xF, true)),
+            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xFF, 0xF, 0xF, true))};
+        // ... then one octet (row 4 kg + v, columns 8 cc ..) at a time
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = acc[e][v];
             const uint32_t o = orow[v] + (uint32_t)(cb * 16 + cc);
             uint32_t rnd[4];
             philox4x32_10(o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
-            const uint32_t word = quantise_octet4(x, inv16, rnd);
+            const uint32_t word = quantise_octet4(x, inv16v[v], rnd);
             if (valid[v]) cw[o] = word;
-            keep[v] = (cc == b) ? a : keep[v];
         }
         __syncthreads();        // the next block's splits are in LDS; everybody is done with this block's
     }
@@ -741,6 +787,12 @@ void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipSt
 {
     if (dp.n_split_p <= 0) return;
     hipLaunchKernelGGL(k_split_p_hat, dim3(dp.n_split_p), dim3(256), 0, st, dp, Phat, ws);
+}
+
+void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st)
+{
+    if (dp.n_split_p <= 0) return;
+    hipLaunchKernelGGL(k_transpose_scales, dim3(dp.n_split_p), dim3(256), 0, st, dp, scales, ws);
 }
 
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,

@@ -112,21 +112,44 @@ __global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double 
     const MatDesc d = dp.mats[blockIdx.x];
     const int r = dp.rank;
     const int t = threadIdx.x;
-    for (int e = t; e < r * r; e += 256) {
-        const double *src = ws + d.gram_off + e;
+    // Ordered sum of the tiles.  A thread owns up to four entries and keeps their loads of eight
+    // tiles in flight together: with one entry at a time the sum over the tiles of a tall matrix
+    // is a long chain of dependent memory round trips.
+    {
+        constexpr int kE = (RP * RP + 255) / 256;
         const int64_t stride = (int64_t)r * r;
         const int T = d.n_gram_tiles;
-        double s = 0.0;
+        const double *src[kE];
+        bool live[kE];
+        double s[kE];
+#pragma unroll
+        for (int u = 0; u < kE; ++u) {
+            const int e = t + 256 * u;
+            live[u] = e < r * r;
+            src[u] = ws + d.gram_off + (live[u] ? e : 0);
+            s[u] = 0.0;
+        }
         int k = 0;
         for (; k + 8 <= T; k += 8) {
-            double v[8];
+            double v[kE][8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(k + u) * stride];
+            for (int u = 0; u < kE; ++u)
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += v[u];
+                for (int q = 0; q < 8; ++q) v[u][q] = src[u][(int64_t)(k + q) * stride];
+#pragma unroll
+            for (int u = 0; u < kE; ++u)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) s[u] += v[u][q];
         }
-        for (; k < T; ++k) s += src[(int64_t)k * stride];
-        G[(e / r) * RP + (e % r)] = s;
+        for (; k < T; ++k) {
+#pragma unroll
+            for (int u = 0; u < kE; ++u) s[u] += src[u][(int64_t)k * stride];
+        }
+#pragma unroll
+        for (int u = 0; u < kE; ++u) {
+            const int e = t + 256 * u;
+            if (live[u]) G[(e / r) * RP + (e % r)] = s[u];
+        }
     }
     __syncthreads();
     if (t >= 64) return;
@@ -241,32 +264,21 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     }
     if constexpr (RP == 32) {
         // Matrix-core family: the operand splits of P^ (x = hi + mid + lo, three bf16 values by
-        // truncation) that its Q+ and err passes read, written while the tile is at hand:
-        // row-major [3][n][32] and transposed in tiles of 64 rows, [n_pad / 64][3 x 32][64] (rows >= n zero).
+        // truncation) that its err pass reads, written while the tile is at hand: row-major [3][n][32].
         if (write_splits && d.path == kPathMfma) {          // uniform
-            __shared__ __attribute__((aligned(16))) uint16_t ts[3][32][64 + 8];
             uint16_t *rm = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.ps_off);
-            for (int e = t; e < 64 * 32; e += 256) {
+            for (int e = t; e < rows * 32; e += 256) {
                 const int rr = e >> 5, c = e & 31;
-                const float x = rr < rows ? tout[rr * kS + c] : 0.0f;
+                const float x = tout[rr * kS + c];
                 const uint32_t xb = __float_as_uint(x);
                 const float r1 = x - __uint_as_float(xb & 0xFFFF0000u);
                 const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
                 const float l = r1 - __uint_as_float(mb);
                 const uint16_t bh = (uint16_t)(xb >> 16), bm = (uint16_t)(mb >> 16), bl = (uint16_t)(__float_as_uint(l) >> 16);
-                if (rr < rows) {
-                    const int64_t row = row0 + rr;
-                    rm[((int64_t)0 * d.n + row) * 32 + c] = bh;
-                    rm[((int64_t)1 * d.n + row) * 32 + c] = bm;
-                    rm[((int64_t)2 * d.n + row) * 32 + c] = bl;
-                }
-                ts[0][c][rr] = bh; ts[1][c][rr] = bm; ts[2][c][rr] = bl;
-            }
-            __syncthreads();
-            uint16_t *tr = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.psT_off) + (row0 >> 6) * kSplitTile;
-            for (int e = t; e < 96 * 8; e += 256) {
-                const int sc = e >> 3, part = e & 7;
-                *reinterpret_cast<uint4 *>(tr + e * 8) = *reinterpret_cast<const uint4 *>(&ts[sc >> 5][sc & 31][part * 8]);
+                const int64_t row = row0 + rr;
+                rm[((int64_t)0 * d.n + row) * 32 + c] = bh;
+                rm[((int64_t)1 * d.n + row) * 32 + c] = bm;
+                rm[((int64_t)2 * d.n + row) * 32 + c] = bl;
             }
         }
     }

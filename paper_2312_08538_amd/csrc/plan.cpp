@@ -78,10 +78,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
-            d.n_pad = (int32_t)round_up(d.n, 64);
             if (d.path == kPathMfma) {
                 d.qsT_off = wd; wd += round_up(3 * 32 * d.m * 2 / 8, 32);
-                d.psT_off = wd; wd += round_up(3 * 32 * (int64_t)d.n_pad * 2 / 8, 32);
+                d.scT_off = wd; wd += round_up((d.m / 128) * d.n * 4 / 8 + 1, 32);
                 d.ps_off = wd;  wd += round_up(3 * 32 * d.n * 2 / 8, 32);
                 d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
             }

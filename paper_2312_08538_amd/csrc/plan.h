@@ -40,10 +40,9 @@ struct MatDesc {
     int32_t lr_shift;               // log2(lanes per row segment), 3..6
     int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
     int32_t m8;                     // m / 8
-    int32_t n_pad;                  // MFMA family: n rounded up to a multiple of 64
     // MFMA family: bf16 triple splits of the factors (x = hi + mid + lo), offsets in doubles
     int64_t qsT_off;                // Q_state, transposed in tiles of 64 rows: [m / 64][3 x 32][64]
-    int64_t psT_off;                // P^, transposed in tiles of 64 rows: [n_pad / 64][3 x 32][64]
+    int64_t scT_off;                // block scales, column-block-major: [m / 128][n] fp32
     int64_t ps_off;                 // P^, row-major:       [3][n][32]
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
 };
