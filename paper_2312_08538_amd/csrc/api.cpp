@@ -58,7 +58,6 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.p_m_items, &d.p_m_items))) return rc;
     if ((rc = upload(ctx, pl.q_m_items, &d.q_m_items))) return rc;
     if ((rc = upload(ctx, pl.err_m_items, &d.err_m_items))) return rc;
-    if ((rc = upload(ctx, pl.split_q_items, &d.split_q_items))) return rc;
     if ((rc = upload(ctx, pl.split_p_items, &d.split_p_items))) return rc;
     if ((rc = upload(ctx, pl.split_qn_items, &d.split_qn_items))) return rc;
     if ((rc = upload(ctx, pl.pred_items, &d.pred_items))) return rc;
@@ -76,7 +75,6 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_p_m = (int)pl.p_m_items.size();
     d.n_q_m = (int)pl.q_m_items.size();
     d.n_err_m = (int)pl.err_m_items.size();
-    d.n_split_q = (int)pl.split_q_items.size();
     d.n_split_p = (int)pl.split_p_items.size();
     d.n_split_qn = (int)pl.split_qn_items.size();
     d.n_pred = (int)pl.pred_items.size();

@@ -12,12 +12,12 @@ struct DevicePlan {
     const WorkItem *p_items = nullptr, *q_items = nullptr, *err_items = nullptr;          // generic family
     const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
-    const WorkItem *split_q_items = nullptr, *split_p_items = nullptr, *split_qn_items = nullptr;
+    const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
                    *elem_items = nullptr;
     int n_mats = 0;
     int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0;
-    int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_q = 0, n_split_p = 0, n_split_qn = 0;
+    int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_p = 0, n_split_qn = 0;
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
@@ -61,7 +61,7 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
 
 // MFMA family.  `prep_only` / `main_only` select the operand-split kernels or the pass itself.
 void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                 const float *Q, float *P, double *ws, hipStream_t st, bool prep_only, bool main_only);
+                 const float *Q, float *P, hipStream_t st);
 
 void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st);
 void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st);

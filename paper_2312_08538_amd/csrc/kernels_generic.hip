@@ -241,9 +241,8 @@ void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, 
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Q, float *P, double *ws, hipStream_t st, Span span)
 {
-    mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, true, false);
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    mfma_pass_p(dp, grads, codes, scales, Q, P, ws, st, false, true);
+    mfma_pass_p(dp, grads, codes, scales, Q, P, st);
     octet_pass_p(dp, grads, codes, scales, Q, P, ws, st);
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);

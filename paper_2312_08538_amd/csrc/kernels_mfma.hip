@@ -57,40 +57,16 @@ __device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
     l = r1 - m;
 }
 
-// ------------------------------------------------------------------ factor splits
-// src: rows x 32 fp32 (row-major).  dst: bf16, [rows / 64 tiles][3 splits x 32 columns][64 rows]
-// (transposed within a tile); rows >= `rows` of the last tile are zero.
-// One workgroup per 64 source rows starting at r0.
-__device__ __forceinline__ void split_transposed_tile(const float *__restrict__ src, uint16_t *__restrict__ dst,
-                                                      int rows, int r0)
-{
-    __shared__ __attribute__((aligned(16))) uint16_t t[3][32][64 + 8];
-    for (int e = threadIdx.x; e < 64 * 32; e += 256) {
-        const int rr = e >> 5, c = e & 31;
-        const int row = r0 + rr;
-        const float x = row < rows ? src[(int64_t)row * 32 + c] : 0.0f;
-        float h, m, l;
-        split3(x, h, m, l);
-        t[0][c][rr] = (uint16_t)(__float_as_uint(h) >> 16);
-        t[1][c][rr] = (uint16_t)(__float_as_uint(m) >> 16);
-        t[2][c][rr] = (uint16_t)(__float_as_uint(l) >> 16);
-    }
-    __syncthreads();
-    // 96 (split, column) rows of 64 entries = 128 bytes each; 8 threads of 16 bytes per row.  The
-    // tile is stored as one contiguous 12 KB piece (tile-major table): its readers fetch it with
-    // consecutive 16-byte loads, spread evenly over the memory channels.
-    uint16_t *out = dst + (int64_t)(r0 >> 6) * kSplitTile;
-    for (int e = threadIdx.x; e < 96 * 8; e += 256) {
-        const int sc = e >> 3, part = e & 7;
-        *reinterpret_cast<uint4 *>(out + e * 8) = *reinterpret_cast<const uint4 *>(&t[sc >> 5][sc & 31][part * 8]);
-    }
-}
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-__global__ __launch_bounds__(256) void k_split_q_state(DevicePlan dp, const float *__restrict__ Q, double *ws)
+// 8 consecutive rows of one column (two transposing reads of 4 rows each)
+__device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
 {
-    const WorkItem it = dp.split_q_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    split_transposed_tile(Q + d.q_off, reinterpret_cast<uint16_t *>(ws + d.qsT_off), (int)d.m, it.a * 64);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    union { s16x4 v; uint2 u; } lo, hi;
+    lo.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    hi.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * pitch));
+    return make_uint4(lo.u.x, lo.u.y, hi.u.x, hi.u.y);
 }
 
 // ------------------------------------------------------------------ P pass
@@ -110,11 +86,11 @@ constexpr int kSStride = 33;                // scales per row in LDS (+1: rows f
 
 __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                float *P, const double *ws)
+                                                const float *__restrict__ Q, float *P)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sg[kMfmaRows * kGStride];
     __shared__ __attribute__((aligned(16))) uint32_t sc[kMfmaRows * kCStride];
-    __shared__ __attribute__((aligned(16))) uint16_t sq[96 * kGStride];
+    __shared__ __attribute__((aligned(16))) uint16_t sq[3 * kStage * 32];      // splits of Q, [split][column of the stage][c]
     __shared__ float ss[kMfmaRows * kSStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WorkItem it = dp.p_m_items[blockIdx.x];
@@ -123,12 +99,15 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const int m = (int)d.m;
     const uint16_t *g = grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
-    const uint16_t *qsT = reinterpret_cast<const uint16_t *>(ws + d.qsT_off);
+    const float *qf = Q + d.q_off;
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
     struct StageRegs {
-        uint4 g[4], q[3];
+        uint4 g[4];
+        f32x4v q0, q1;      // 8 entries of one row of Q
     };
+    const int krow = tid >> 2, fcg = tid & 3;        // Q roles: row of Q (column of the stage), group of 8 c
     // The block scales go through LDS a group of 32 per row at a time, for the same reason as the
     // code words.  The load is waited for on the spot, once per 4096 columns.
     auto fetch_scales = [&](int k0) {
@@ -182,9 +161,10 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             const int64_t row = row0 + rr;
             r.g[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
         }
-        const uint16_t *qtile = qsT + (int64_t)(k0 >> 6) * kSplitTile + tid * 8;      // the stage's tile, contiguous
-#pragma unroll
-        for (int s = 0; s < 3; ++s) r.q[s] = *reinterpret_cast<const uint4 *>(qtile + 2048 * s);
+        // the stage's 64 rows of Q, 8 KB, contiguous
+        const f32x4v *qp = reinterpret_cast<const f32x4v *>(qf + (int64_t)(k0 + krow) * 32 + fcg * 8);
+        r.q0 = qp[0];
+        r.q1 = qp[1];
     };
     auto store_stage = [&](const StageRegs &r) {
 #pragma unroll
@@ -192,10 +172,19 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
             *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
         }
+        {
+            // operand splits of Q, row-major; the matrix cores read them through the transposing LDS load
+            const float qv[8] = {r.q0[0], r.q0[1], r.q0[2], r.q0[3], r.q1[0], r.q1[1], r.q1[2], r.q1[3]};
+            float hh[8], mm[8], ll[8];
 #pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int idx = tid + 256 * s, qr = idx >> 3, oct = idx & 7;
-            *reinterpret_cast<uint4 *>(sq + qr * kGStride + oct * 8) = r.q[s];
+            for (int j = 0; j < 8; ++j) split3(qv[j], hh[j], mm[j], ll[j]);
+            uint16_t *o = sq + krow * 32 + fcg * 8;
+            *reinterpret_cast<uint4 *>(o) =
+                make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
+            *reinterpret_cast<uint4 *>(o + kStage * 32) =
+                make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+            *reinterpret_cast<uint4 *>(o + 2 * kStage * 32) =
+                make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
         }
     };
 
@@ -208,6 +197,10 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const int r32 = lane & 31, kg = lane >> 5;
     const int my_row_in_tile = 32 * wave + r32;
     const int64_t my_row = row0 + my_row_in_tile;
+    // transposing reads of the Q splits: 16-lane group gq covers c = 16 (gq & 1) .. of the operand and
+    // columns 8 (gq >> 1) .. of the 16-column step; lane li of the group addresses column li / 4, c 4 (li % 4) ..
+    const int gq = lane >> 4, li = lane & 15;
+    const int tr_a = (8 * (gq >> 1) + (li >> 2)) * 32 + 16 * (gq & 1) + 4 * (li & 3);
 
     auto compute_stage = [&](int k0) {
 #pragma unroll
@@ -223,9 +216,9 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
                 qb[e2] = pack_hi16(lo, hi);          // small integers: exact in bf16
             }
             bq.u = make_uint4(qb[0], qb[1], qb[2], qb[3]);
-            a0.u = *reinterpret_cast<const uint4 *>(sq + (0 * 32 + r32) * kGStride + ks * 16 + kg * 8);
-            a1.u = *reinterpret_cast<const uint4 *>(sq + (1 * 32 + r32) * kGStride + ks * 16 + kg * 8);
-            a2.u = *reinterpret_cast<const uint4 *>(sq + (2 * 32 + r32) * kGStride + ks * 16 + kg * 8);
+            a0.u = lds_read_tr16x8(sq + 0 * kStage * 32 + tr_a + ks * 16 * 32, 32);
+            a1.u = lds_read_tr16x8(sq + 1 * kStage * 32 + tr_a + ks * 16 * 32, 32);
+            a2.u = lds_read_tr16x8(sq + 2 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             accP = mfma(a0, bg, accP);
             accS = mfma(a0, bq, accS);
             accP = mfma(a1, bg, accP);
@@ -373,18 +366,6 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 // in fp64.
 constexpr int kQRows = 64;                  // rows per chunk
 constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-// 8 consecutive rows of one column (two transposing reads of 4 rows each)
-__device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
-{
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    union { s16x4 v; uint2 u; } lo, hi;
-    lo.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    hi.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * pitch));
-    return make_uint4(lo.u.x, lo.u.y, hi.u.x, hi.u.y);
-}
 
 __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
@@ -773,14 +754,11 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
 }  // namespace
 
 void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                 const float *Q, float *P, double *ws, hipStream_t st, bool prep_only, bool main_only)
+                 const float *Q, float *P, hipStream_t st)
 {
     if (dp.n_p_m <= 0) return;
-    if (!main_only)
-        hipLaunchKernelGGL(k_split_q_state, dim3(dp.n_split_q), dim3(256), 0, st, dp, Q, ws);
-    if (!prep_only)
-        hipLaunchKernelGGL(k_p_mfma, dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
-                           codes, scales, P, (const double *)ws);
+    hipLaunchKernelGGL(k_p_mfma, dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       codes, scales, Q, P);
 }
 
 void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st)

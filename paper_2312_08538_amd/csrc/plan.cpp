@@ -79,7 +79,6 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
             if (d.path == kPathMfma) {
-                d.qsT_off = wd; wd += round_up(3 * 32 * d.m * 2 / 8, 32);
                 d.scT_off = wd; wd += round_up((d.m / 128) * d.n * 4 / 8 + 1, 32);
                 d.ps_off = wd;  wd += round_up(3 * 32 * d.n * 2 / 8, 32);
                 d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
@@ -118,7 +117,6 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             const bool mf_p = mf && (kMfmaPasses & 1), mf_q = mf && (kMfmaPasses & 2), mf_e = mf && (kMfmaPasses & 4);
             if (mf_p) {
                 for (int64_t r0 = 0; r0 < d.n; r0 += kMfmaRows) plan.p_m_items.push_back({l, (int32_t)r0, 0, 0});
-                for (int64_t k0 = 0; k0 < d.m; k0 += 64) plan.split_q_items.push_back({l, (int32_t)(k0 / 64), 0, 0});
             }
             if (mf_q) {
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)

@@ -17,7 +17,6 @@ constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (on
 
 enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
 constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
-constexpr int kSplitTile = 3 * 32 * 64;  // bf16 per tile of a transposed split table: 3 splits x 32 columns x 64 rows
 constexpr int kErrRows = 128;       // rows per workgroup item of the MFMA err pass (8 waves x 16)
 constexpr int kErrRun = 16;         // column blocks of 128 per item of the MFMA err pass (at most 16)
 
@@ -41,7 +40,6 @@ struct MatDesc {
     int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
     int32_t m8;                     // m / 8
     // MFMA family: bf16 triple splits of the factors (x = hi + mid + lo), offsets in doubles
-    int64_t qsT_off;                // Q_state, transposed in tiles of 64 rows: [m / 64][3 x 32][64]
     int64_t scT_off;                // block scales, column-block-major: [m / 128][n] fp32
     int64_t ps_off;                 // P^, row-major:       [3][n][32]
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
@@ -72,7 +70,6 @@ struct Plan {
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
     std::vector<WorkItem> q_m_items;    // (mat, column block of 128, row tile)
     std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
-    std::vector<WorkItem> split_q_items;   // split Q_state  (transposed):  (mat, first k / 64)
     std::vector<WorkItem> split_p_items;   // split P^ (both layouts):      (mat, first row / 64)
     std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
     // shared
