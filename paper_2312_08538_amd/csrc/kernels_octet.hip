@@ -1,14 +1,15 @@
 // Octet kernel family: the streaming passes for matrices whose rows hold whole scale blocks
-// (cols % block == 0, block/8 a power of two <= 64) and rank 2, 4 or 8.
+// (cols % block == 0, block a power of two from 64 to 512, cols % 64 == 0) and rank 2, 4 or 8.
 //
 // A lane owns an "octet": 8 consecutive elements of a row -- one 16-byte (bf16) or two 16-byte
 // (fp32) gradient loads, 16/32/64 bits of codes, one Philox call in the error pass.  `lr` lanes
 // (8..64, a power of two) cover a row segment; 64/lr rows share a wave.
 //
-//   P pass    one wave per 64-row x column-chunk item on the fp64 matrix cores (rank padded to 16
-//             columns).  Octets are decoded in the coalesced load layout, p goes through a
-//             wave-private LDS tile and comes back in the operand layout; Q is read as an fp64 copy.
-//             Products of fp32 values are exact in fp64, the sum stays in fp64, one rounding at the end.
+//   P pass    one workgroup per 64-row x column-chunk item on the fp64 matrix cores (rank padded to
+//             16 columns).  Octets are decoded in the coalesced load layout, p goes through a
+//             wave-private LDS tile and comes back in the operand layout; codes and scales are staged
+//             through LDS in whole 128-byte lines.  Products of fp32 values are exact in fp64, the
+//             sum stays in fp64, one rounding at the end.
 //   Q+ pass   one wave per 64-column x row-tile item, same instruction with the roles of rows and
 //             columns exchanged; per-tile fp64 partial sums go to the workspace and are added in
 //             tile order by the reduction kernel.
@@ -22,8 +23,6 @@
 namespace conef {
 
 namespace {
-
-typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------ octet load / decode
 template <bool BF16, int BITS>
@@ -236,8 +235,9 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 }
 
 // ------------------------------------------------------------------ Q+ pass
-// Q+ = p^T P^ on the fp64 matrix cores: D[k][c] += sum_i A[k][i] B[i][c] with A[k][i] = p[row i][column k]
-// and B[i][c] = P^[row i][c], four rows per instruction, fp64 sums throughout (no fp32 partial sums).
+// Q+ = p^T P^ on the fp64 matrix cores (v_mfma_f64_4x4x4_4b_f64, operand layout at the P pass below):
+// D[k][c] += sum_i A[k][i] B[i][c] with A[k][i] = p[row i][column k] and B[i][c] = P^[row i][c]; the four
+// blocks are four groups of four columns that share B; four rows per instruction, fp64 sums throughout.
 // One wave per (64 columns, row tile), independent of the other waves.  Rows are walked 32 at a
 // time: octets are decoded in the coalesced load layout (8 lanes per row) into a wave-private LDS
 // tile (32 rows x 64 columns of p), read back one value per lane and instruction; the rows of P^
@@ -246,7 +246,7 @@ constexpr int kQTileCols = 64;
 constexpr int kQTilePitch = 80;     // floats per LDS tile row: rows 0..3 of a group fall on distinct banks
 constexpr int kQStepRows = 32;
 
-template <bool BF16, int BITS>
+template <bool BF16, int BITS, int RH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
                const float *__restrict__ scales, const float *__restrict__ Phat, double *ws)
@@ -269,16 +269,18 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     // rows of D that are not stored
     const int64_t oct0 = ((col0 >> 3) + loct < d.m8) ? (col0 >> 3) + loct : d.m8 - 1;
 
-    const int mic = mi < r ? mi : r - 1;
+    const int mc = lane & 3;                          // factor column of this lane's B and D entries (+ 4 h)
 
-    f64x4 acc[4];
+    double acc[4][RH];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
 
     constexpr int kLoads = kQStepRows / 8, kGroups = kQStepRows / 4;
     struct Step {
         RawOctet<BF16, BITS> o[kLoads];
-        float ph[kGroups];        // P^[i0 + 4 g + mk][mi]
+        float ph[kGroups][RH];    // P^[i0 + 4 g + mk][mc + 4 h]
     };
     auto load_step = [&](Step &st, int64_t i0) {
 #pragma unroll
@@ -291,8 +293,12 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 #pragma unroll
         for (int g = 0; g < kGroups; ++g) {
             const int64_t row = i0 + 4 * g + mk;
-            const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + mic];
-            st.ph[g] = (row < row1 && mi < r) ? v : 0.0f;
+#pragma unroll
+            for (int h = 0; h < RH; ++h) {
+                const int c = mc + 4 * h;
+                const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + (c < r ? c : r - 1)];
+                st.ph[g][h] = (row < row1 && c < r) ? v : 0.0f;
+            }
         }
     };
 
@@ -308,139 +314,258 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
         }
-        float b[kGroups];
+        float b[kGroups][RH];
 #pragma unroll
-        for (int g = 0; g < kGroups; ++g) b[g] = cur.ph[g];
+        for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+            for (int h = 0; h < RH; ++h) b[g][h] = cur.ph[g][h];
         load_step(cur, i0 + kQStepRows);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int g = 0; g < kGroups; ++g) {
-            const double bg = (double)b[g];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const double a = (double)T[(4 * g + mk) * kQTilePitch + 16 * t + mi];
-                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bg, acc[t], 0, 0, 0);
+#pragma unroll
+                for (int h = 0; h < RH; ++h)
+                    acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, (double)b[g][h], acc[t][h], 0, 0, 0);
             }
         }
         __builtin_amdgcn_wave_barrier();
     }
-    // D[4 v + mk][mi]: column col0 + 16 t + 4 v + mk of the matrix, factor column mi
-    if (mi < r) {
+    // D of block (lane % 16) / 4, entry [lane / 16][lane % 4]: column 16 t + 4 ((lane % 16) / 4) + lane / 16 of the strip
+    const int dcol = 4 * (mi >> 2) + mk;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < 4; ++t) {
+        const int col = col0 + 16 * t + dcol;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int col = col0 + 16 * t + 4 * v + mk;
-                if (col < d.m) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + mi] = acc[t][v];
-            }
+        for (int h = 0; h < RH; ++h) {
+            const int c = mc + 4 * h;
+            if (col < d.m && c < r) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + c] = acc[t][h];
         }
     }
 }
 
 // ------------------------------------------------------------------ P pass
-// P = p Q on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): products of fp32 values are exact in
-// fp64 and the sum is kept in fp64, as in a plain fp64 loop; the rank (<= 16) is padded to the
-// 16 columns of the instruction with zeros.
-//   operand layout: lane l holds A[l%16][l/16], B[l/16][l%16] and D[4v + l/16][l%16], v = 0..3.
-// One wave per (64 rows, column chunk).  Octets are decoded in the coalesced load layout into a
-// wave-private LDS tile (64 rows x 32 columns of p, fp32); A[i][kk] = p[row i][column 4j + kk] is
+// P = p Q on the fp64 matrix cores: products of fp32 values are exact in fp64 and the sum is kept in
+// fp64, as in a plain fp64 loop.  v_mfma_f64_4x4x4_4b_f64 multiplies four independent 4x4 blocks:
+// block b (0..3) computes D_b[i][j] += sum_k A_b[i][k] B_b[k][j]; lane l holds A_b[i][k] for i = l % 4,
+// b = (l / 4) % 4, k = l / 16, B_b[k][j] for j = l % 4 (same b, k), and D_b[i][j] for i = l / 16,
+// b = (l % 16) / 4, j = l % 4.  Here the four blocks are four groups of four rows that share B
+// (four columns of p times four factor columns): one instruction covers 16 rows x 4 columns of p and
+// 4 factor columns; rank 8 takes two instructions (RH = 2 halves), ranks 2 and 4 one.  The
+// instruction runs at the rate of the fp64 vector ALU and is not overlapped with it (measured), so
+// its cost is that of r fp64 FMAs per element plus nothing for the sum across lanes.
+//
+// One workgroup per (64 rows, column chunk).  The chunk is walked in steps of 128 columns; in a step
+// wave w takes columns 32w..32w+31 (so the four waves read whole 128-byte lines of the gradient
+// between them, at the same time) and adds its products to accumulators of its own; the four sets
+// are added up in wave order when the chunk is done.  A wave decodes its 64 x 32 sub-tile in the
+// coalesced load layout into a wave-private LDS tile (fp32); A[i][kk] = p[row i][column 4j + kk] is
 // read back one value per lane (conflict-free), B[kk][c] = Q[column 4j + kk][c] is read from Q, eight
-// values per lane and sub-tile, loaded one sub-tile ahead.  Four waves per SIMD need <= 128 registers.
-constexpr int kSubCols = 32;        // columns per LDS sub-tile
+// values per lane and sub-tile; gradient and Q loads run one step ahead.
+//
+// Code words and block scales go through LDS a "group" at a time: the columns whose codes fill one
+// 128-byte line per row (1024 / bits columns).  Fetched 32 columns at a time, a line would be pulled
+// from memory again for every piece (the L2 does not hold it that long: every workgroup streams
+// through it).  The group after the current one waits in registers.
+constexpr int kSubCols = 32;        // columns per wave and step
+constexpr int kStepCols = 128;      // columns per workgroup and step
 constexpr int kTileStride = 36;     // floats per LDS tile row: 32 columns + 4 of padding
+constexpr int kCodePitch = 34;      // words per row of the code stage: 128 bytes + 8 of padding
+constexpr int kScalePitch = 9;      // floats per row of the scale stage: up to 8 blocks per group + 1
 
-template <bool BF16, int BITS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+template <bool BF16, int BITS, int RH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
                const float *__restrict__ scales, const float *__restrict__ Q, float *P, double *ws)
 {
-    __shared__ float tiles[4][kPTileRows * kTileStride];
-    const int lane = threadIdx.x & 63;
+    constexpr int kGroupCols = 1024 / BITS;                 // 512, 256, 128
+    constexpr int kGroupSteps = kGroupCols / kStepCols;     // 4, 2, 1
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(16))) float tiles[4][kPTileRows * kTileStride];
+    __shared__ __attribute__((aligned(16))) uint32_t cstage[kPTileRows * kCodePitch];
+    __shared__ float sstage[kPTileRows * kScalePitch];
+    const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
-    if (item >= dp.n_p_f) return;
     float *T = tiles[wave];
-    const WorkItem it = dp.p_f_items[item];
+    const WorkItem it = dp.p_f_items[xcd_contiguous_item(blockIdx.x, dp.n_p_f)];
     const MatDesc d = dp.mats[it.mat];
     const int r = dp.rank;
     const int64_t row0 = it.a;
     const int c_begin = it.b * d.p_chunk_cols;
     const int c_end = (c_begin + d.p_chunk_cols < d.m) ? c_begin + d.p_chunk_cols : (int)d.m;
-    const int lrow = lane >> 2, loct = lane & 3;      // load layout: 4 lanes per row, 16 rows per step
+    const int lrow = lane >> 2, loct = lane & 3;      // load layout: 4 lanes per row, 16 rows per load
     const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
+    const int lb = d.lb_shift + 3;                    // log2(block)
 
-    f64x4 acc[4];
+    const int mc = lane & 3;                          // factor column of this lane's B and D entries (+ 4 h)
+
+    double acc[4][RH];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
 
-    // B operand of a sub-tile: Q[col0 + 4 j + mk][mi], j = 0..7; zero for mi >= rank and for columns
-    // at or beyond the end of the chunk (the tile holds other data of the same rows there)
-    const int mic = mi < r ? mi : r - 1;
-    auto load_b = [&](float (&bq)[8], int col0) {
+    // ---- group staging: 64 rows x 128 bytes of codes (two 16-byte pieces per thread) and the scales
+    // of the group's blocks (up to 8 per row, two per thread).  Rows beyond the matrix re-read its last
+    // row, pieces beyond the row's end its first piece of the group (neither is used).
+    struct GroupRegs {
+        u32x4 c0, c1;
+        float s0, s1;
+    };
+    const int n_sc = (kGroupCols >> lb) > 0 ? (kGroupCols >> lb) : 1;       // blocks per group and row
+    auto load_group = [&](GroupRegs &gr, int gcol0) {
+        const uint8_t *cbase = reinterpret_cast<const uint8_t *>(codes + d.word_off);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 3, part = idx & 7;
+            const int64_t row = (row0 + rr < d.n) ? row0 + rr : d.n - 1;
+            const int col = (gcol0 + part * (kGroupCols / 8) < d.m) ? gcol0 + part * (kGroupCols / 8) : gcol0;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(cbase + ((row * d.m + col) * BITS >> 3));
+            if (s == 0) gr.c0 = v; else gr.c1 = v;
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 3, j = idx & 7;
+            const int64_t row = (row0 + rr < d.n) ? row0 + rr : d.n - 1;
+            int64_t blk = (row * d.m + gcol0) >> lb;
+            blk += (j < n_sc && gcol0 + (j << lb) < d.m) ? j : 0;
+            const float v = scales[d.scale_off + blk];
+            if (s == 0) gr.s0 = v; else gr.s1 = v;
+        }
+    };
+    auto store_group = [&](const GroupRegs &gr) {
+        {
+            const int rr = tid >> 3, part = tid & 7;
+            *reinterpret_cast<u32x4 *>(cstage + rr * kCodePitch + part * 4) = gr.c0;
+            *reinterpret_cast<u32x4 *>(cstage + (rr + 32) * kCodePitch + part * 4) = gr.c1;
+            sstage[rr * kScalePitch + part] = gr.s0;
+            sstage[(rr + 32) * kScalePitch + part] = gr.s1;
+        }
+    };
+
+    // B operand of a sub-tile: Q[col0 + 4 j + mk][mc + 4 h], j = 0..7; zero beyond the rank and for
+    // columns at or beyond the end of the chunk (the tile holds other data of the same rows there)
+    auto load_b = [&](float (&bq)[8][RH], int col0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int col = col0 + 4 * j + mk;
-            const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + mic];
-            bq[j] = (col < c_end && mi < r) ? v : 0.0f;
+#pragma unroll
+            for (int h = 0; h < RH; ++h) {
+                const int c = mc + 4 * h;
+                const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + (c < r ? c : r - 1)];
+                bq[j][h] = (col < c_end && c < r) ? v : 0.0f;
+            }
         }
     };
-    // rows at or beyond n re-read the last row (their rows of D are not stored); octets at or beyond the
-    // end of the chunk re-read its last octet (their B operand is zero)
+    // gradient octets of a sub-tile.  Rows at or beyond n re-read the last row (their rows of D are
+    // not stored); octets at or beyond the end of the chunk re-read its last octet (their B operand is zero)
+    struct GradRegs {
+        uint4 g0, g1;
+    };
     const int oct_end = c_end >> 3;
-    auto load_tile = [&](RawOctet<BF16, BITS> (&o)[4], int col0) {
+    auto load_grads = [&](GradRegs (&o)[4], int col0) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             int64_t row = row0 + s * 16 + lrow;
             row = row < d.n ? row : d.n - 1;
             int oc = (col0 >> 3) + loct;
             oc = oc < oct_end ? oc : oct_end - 1;
-            o[s] = load_octet_always<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oc);
+            const int64_t e = (row * d.m8 + oc) * 8;
+            if (BF16) {
+                o[s].g0 = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(grads) + d.grad_off + e);
+                o[s].g1 = make_uint4(0, 0, 0, 0);
+            } else {
+                const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(grads) + d.grad_off + e);
+                o[s].g0 = gp[0];
+                o[s].g1 = gp[1];
+            }
         }
     };
 
-    RawOctet<BF16, BITS> cur[4];
-    load_tile(cur, c_begin);
-    float bq[8], bn[8];
-    load_b(bq, c_begin);
-    for (int col0 = c_begin; col0 < c_end; col0 += kSubCols) {
+    const int n_steps = (c_end - c_begin + kStepCols - 1) / kStepCols;
+    GroupRegs gr;
+    GradRegs cur[4];
+    float bq[8][RH], bn[8][RH];
+    load_group(gr, c_begin);
+    load_grads(cur, c_begin + kSubCols * wave);
+    load_b(bq, c_begin + kSubCols * wave);
+    for (int step = 0; step < n_steps; ++step) {
+        const int col0 = c_begin + step * kStepCols + kSubCols * wave;       // this wave's sub-tile
+        const int gcol0 = c_begin + (step / kGroupSteps) * kGroupCols;        // its code group
+        if (step % kGroupSteps == 0) {
+            __syncthreads();            // every wave is done with the previous group's stage
+            store_group(gr);
+            const int gnext = gcol0 + kGroupCols;
+            load_group(gr, gnext < c_end ? gnext : gcol0);
+            __syncthreads();
+        }
         // decode the loaded sub-tile into the wave's LDS tile (row-major, padded)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
+            const int rr = s * 16 + lrow;
+            int oc = ((col0 - gcol0) >> 3) + loct;                       // octet of the group
+            oc = oc < (kGroupCols >> 3) ? oc : (kGroupCols >> 3) - 1;    // (columns beyond the chunk: unused)
+            RawOctet<BF16, BITS> o;
+            o.g0 = cur[s].g0; o.g1 = cur[s].g1; o.c1 = 0;
+            if (BITS == 8) {
+                const uint2 c = *reinterpret_cast<const uint2 *>(cstage + rr * kCodePitch + oc * 2);
+                o.c0 = c.x; o.c1 = c.y;
+            } else if (BITS == 4) {
+                o.c0 = cstage[rr * kCodePitch + oc];
+            } else {
+                o.c0 = reinterpret_cast<const uint16_t *>(cstage + rr * kCodePitch)[oc];
+            }
+            o.scale = sstage[rr * kScalePitch + ((oc << 3) >> lb)];
             float p[8];
-            decode_octet<BF16, BITS>(cur[s], p);
-            float4 *dst = reinterpret_cast<float4 *>(T + (s * 16 + lrow) * kTileStride + loct * 8);
+            decode_octet<BF16, BITS>(o, p);
+            float4 *dst = reinterpret_cast<float4 *>(T + rr * kTileStride + loct * 8);
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
         }
-        // issue the loads of the next sub-tile
-        load_b(bn, col0 + kSubCols);
-        load_tile(cur, col0 + kSubCols);
+        // issue the loads of this wave's next sub-tile
+        load_b(bn, col0 + kStepCols);
+        load_grads(cur, col0 + kStepCols);
         __builtin_amdgcn_wave_barrier();
+        if (col0 < c_end) {             // a ragged last step leaves the upper waves without columns
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const double b = (double)bq[j];
+            for (int j = 0; j < 8; ++j) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const double a = (double)T[(16 * t + mi) * kTileStride + 4 * j + mk];
-                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[t], 0, 0, 0);
+                for (int t = 0; t < 4; ++t) {
+                    const double a = (double)T[(16 * t + mi) * kTileStride + 4 * j + mk];
+#pragma unroll
+                    for (int h = 0; h < RH; ++h)
+                        acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, (double)bq[j][h], acc[t][h], 0, 0, 0);
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < 8; ++j) bq[j] = bn[j];
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int h = 0; h < RH; ++h) bq[j][h] = bn[j][h];
     }
-    // D[4 v + mk][mi]: row 16 t + 4 v + mk of the tile, factor column mi
-    if (mi < r) {
+    // ---- the four waves' sums, added in wave order.  D of block (lane % 16) / 4, entry [lane / 16][lane % 4]:
+    // row 16 t + 4 ((lane % 16) / 4) + lane / 16 of the tile, factor column lane % 4 + 4 h
+    __syncthreads();
+    double *red = reinterpret_cast<double *>(&tiles[0][0]);      // [wave][row][8], 16 KB of the 36 KB of tiles
+    const int drow = 4 * (mi >> 2) + mk;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int64_t row = row0 + 16 * t + 4 * v + mk;
-                if (row < d.n) {
-                    if (d.n_p_chunks == 1) P[d.p_off + row * r + mi] = (float)acc[t][v];
-                    else ws[d.ppart_off + ((int64_t)it.b * d.n + row) * r + mi] = acc[t][v];
-                }
-            }
+        for (int h = 0; h < RH; ++h) red[(wave * kPTileRows + 16 * t + drow) * 8 + mc + 4 * h] = acc[t][h];
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int idx = tid + 256 * s, rr = idx >> 3, c = idx & 7;
+        const int64_t row = row0 + rr;
+        if (c < r && row < d.n) {
+            double sum = red[rr * 8 + c];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) sum += red[(w * kPTileRows + rr) * 8 + c];
+            if (d.n_p_chunks == 1) P[d.p_off + row * r + c] = (float)sum;
+            else ws[d.ppart_off + ((int64_t)it.b * d.n + row) * r + c] = sum;
         }
     }
 }
@@ -475,8 +600,11 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
         }                                                                            \
     } while (0)
 
-#define CONEF_OCTET2_CASE(KERNEL, BF, B, GRID, ST, ...) \
-    case ((BF ? 1 : 0) << 8) | B: hipLaunchKernelGGL((KERNEL<BF, B>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;
+#define CONEF_OCTET2_CASE(KERNEL, BF, B, GRID, ST, ...)                                                         \
+    case ((BF ? 1 : 0) << 8) | B:                                                                              \
+        if (dp.rank > 4) hipLaunchKernelGGL((KERNEL<BF, B, 2>), GRID, dim3(256), 0, ST, __VA_ARGS__);          \
+        else hipLaunchKernelGGL((KERNEL<BF, B, 1>), GRID, dim3(256), 0, ST, __VA_ARGS__);                      \
+        break;
 
 #define CONEF_OCTET2_DISPATCH(KERNEL, GRID, ST, ...)                     \
     do {                                                                 \
@@ -495,7 +623,7 @@ void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes
                   const float *Q, float *P, double *ws, hipStream_t st)
 {
     if (dp.n_p_f <= 0) return;
-    CONEF_OCTET2_DISPATCH(k_p_octet, dim3((dp.n_p_f + 3) / 4), st, dp, grads, codes, scales, Q, P, ws);
+    CONEF_OCTET2_DISPATCH(k_p_octet, dim3(dp.n_p_f), st, dp, grads, codes, scales, Q, P, ws);
 }
 
 void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,

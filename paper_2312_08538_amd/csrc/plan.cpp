@@ -36,9 +36,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         plan.rpad = rank <= 4 ? 4 : rank <= 8 ? 8 : rank <= 16 ? 16 : 32;
         plan.mats.resize(n_mats);
 
-        // The octet family needs whole octets and whole scale blocks per row, a power-of-two
-        // number of lanes (8 elements each) per block, at most one wave wide, and rank 2, 4 or 8.
-        const bool block_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64;
+        // The octet family needs whole scale blocks per row, a power-of-two number of lanes (8 elements
+        // each) per block, at most one wave wide, and rank 2, 4 or 8.  Its P pass stages codes and scales
+        // in 128-byte lines: blocks of at least 64 elements and rows of a multiple of 64 columns.
+        const bool block_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64 && block >= 64;
         int64_t total_elems = 0;
         for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
         // rows per wave item of the err pass: aim at >= ~4096 wave items over the model
@@ -47,9 +48,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         // rows per wave item of the Q+ pass (64 columns wide): aim at >= ~4096 wave items
         int q_rows = 512;
         while (q_rows > 64 && total_elems / ((int64_t)q_rows * 64) < 4096) q_rows >>= 1;
-        // columns per wave item of the P pass (64 rows high): aim at >= ~2048 wave items
-        int p_cols = 512;
-        while (p_cols > 64 && total_elems / ((int64_t)kPTileRows * p_cols) < 2048) p_cols >>= 1;
+        // columns per workgroup item of the P pass (64 rows high): a multiple of every code group
+        // (1024 / bits columns) and of every block size of the family
+        const int p_cols = 512;
 
         int64_t g = 0, w = 0, s = 0, p = 0, q = 0, wd = 0;
         for (int l = 0; l < n_mats; ++l) {
@@ -62,7 +63,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             d.scale_off = s; s += round_up(d.nblk, kAlign);
             d.p_off = p;     p += round_up(d.n * rank, kAlign);
             d.q_off = q;     q += round_up(d.m * rank, kAlign);
-            d.path = (block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 8 == 0 && d.m % block == 0) ? kPathOctet
+            d.path = (block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 64 == 0 && d.m % block == 0) ? kPathOctet
                                                                                              : kPathGeneric;
             d.m8 = (int32_t)(d.m / 8);
             d.lb_shift = block_ok ? log2i(block / 8) : 0;
@@ -148,10 +149,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             } else {
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;
-                // neighbouring waves (one workgroup, one CU) take neighbouring row tiles of the SAME column
-                // chunk: they read the same rows of Q at about the same time
-                for (int32_t cc = 0; cc < d.n_p_chunks; ++cc)
-                    for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
+                // consecutive items are the column chunks of one row tile: they run side by side on one
+                // XCD and share the lines of block scales that span several chunks
+                for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows)
+                    for (int32_t cc = 0; cc < d.n_p_chunks; ++cc) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
                 const int32_t qstrips = (int32_t)ceil_div(d.m, 64);
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                     for (int32_t st = 0; st < qstrips; ++st) plan.q_f_items.push_back({l, st, rt, 0});

@@ -13,7 +13,7 @@ constexpr int kGramRows = 256;      // rows per LDS piece of the Gram kernel
 constexpr int kGenQRows = 128;      // rows per partial of Q+ in the generic pass 2
 constexpr int kGenQCols = 256;      // columns per workgroup in the generic pass 2
 constexpr int kFastMaxRank = 8;     // the octet family holds rank <= 8 in registers
-constexpr int kPTileRows = 64;      // rows per wave item of the fast P pass (one lane per row)
+constexpr int kPTileRows = 64;      // rows per workgroup item of the octet P pass
 
 enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
 constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
@@ -63,7 +63,7 @@ struct Plan {
     std::vector<WorkItem> q_items;      // pass 2: (mat, column tile, row tile)
     std::vector<WorkItem> err_items;    // pass 3: (mat, first block, blocks per wave)
     // octet family (one item per wave for p and err, per workgroup for q)
-    std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk)
+    std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk), one workgroup each
     std::vector<WorkItem> q_f_items;    // (mat, 64-column strip, row tile)
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
