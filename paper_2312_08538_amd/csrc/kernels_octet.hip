@@ -297,7 +297,7 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
             for (int h = 0; h < RH; ++h) {
                 const int c = mc + 4 * h;
                 const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + (c < r ? c : r - 1)];
-                st.ph[g][h] = (row < row1 && c < r) ? v : 0.0f;
+                st.ph[g][h] = v * ((row < row1 && c < r) ? 1.0f : 0.0f);       // a product, not a select (see the P pass)
             }
         }
     };
@@ -454,8 +454,10 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 #pragma unroll
             for (int h = 0; h < RH; ++h) {
                 const int c = mc + 4 * h;
+                // (masked by a product, not a select: a select lets the compiler move the load behind a
+                // branch on the condition, where it is waited for on the spot)
                 const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + (c < r ? c : r - 1)];
-                bq[j][h] = (col < c_end && c < r) ? v : 0.0f;
+                bq[j][h] = v * ((col < c_end && c < r) ? 1.0f : 0.0f);
             }
         }
     };
