@@ -103,10 +103,17 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
     typedef float f32x4v __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct StageRegs {
-        uint4 g[4];
+        u32x4 g[4];
         f32x4v q0, q1;      // 8 entries of one row of Q
     };
+    int64_t g_row[4];       // element offset of this thread's four gradient rows (rows (tid >> 3) + 32 s of the tile)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int rr = (tid >> 3) + 32 * s;
+        g_row[s] = ((row0 + rr < d.n) ? row0 + rr : d.n - 1) * m;
+    }
     const int krow = tid >> 2, fcg = tid & 3;        // Q roles: row of Q (column of the stage), group of 8 c
     // The block scales go through LDS a group of 32 per row at a time, for the same reason as the
     // code words.  The load is waited for on the spot, once per 4096 columns.
@@ -128,7 +135,6 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     };
     // code words of a group: 128 rows x 128 bytes, 8 threads x 16 bytes per row.  A matrix whose
     // width is an odd multiple of 128 ends with half a group: its missing half re-reads the first.
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct CodeRegs {
         u32x4 w0, w1, w2, w3;
     };
@@ -155,12 +161,10 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     };
 
     auto load_stage = [&](StageRegs &r, int k0) {
+        // rows beyond the matrix re-read its last row (their results are not stored): every load of the
+        // loop is unconditional, so the waits on a stage can leave the younger stage's loads pending
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
-            const int64_t row = row0 + rr;
-            r.g[s] = (row < d.n) ? *reinterpret_cast<const uint4 *>(g + row * m + k0 + oct * 8) : make_uint4(0, 0, 0, 0);
-        }
+        for (int s = 0; s < 4; ++s) r.g[s] = *reinterpret_cast<const u32x4 *>(g + g_row[s] + k0 + (tid & 7) * 8);
         // the stage's 64 rows of Q, 8 KB, contiguous
         const f32x4v *qp = reinterpret_cast<const f32x4v *>(qf + (int64_t)(k0 + krow) * 32 + fcg * 8);
         r.q0 = qp[0];
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
-            *reinterpret_cast<uint4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
+            *reinterpret_cast<u32x4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
         }
         {
             // operand splits of Q, row-major; the matrix cores read them through the transposing LDS load
@@ -254,20 +258,26 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             // the group's words have been in registers since the last group was stored
             store_codes(cg);
             load_codes(cg, (k0 + kCodeGroup < m) ? k0 + kCodeGroup : k0);      // the last group re-reads itself (unused)
-            if ((k0 & (kScaleGroup - 1)) == 0) fetch_scales(k0);
         }
         __syncthreads();
-        if (k0 + 2 * kStage < m) load_stage(ra, k0 + 2 * kStage);
+        load_stage(ra, (k0 + 2 * kStage < m) ? k0 + 2 * kStage : k0);      // past the end: a reload that is not used
         compute_stage(k0);
         __syncthreads();
         store_stage(rb);
         __syncthreads();
-        if (k0 + 3 * kStage < m) load_stage(rb, k0 + 3 * kStage);
+        load_stage(rb, (k0 + 3 * kStage < m) ? k0 + 3 * kStage : k0 + kStage);
         compute_stage(k0 + kStage);
     };
-    for (int k0 = 0; k0 < m; k0 += kCodeGroup) {
-        trip(k0, std::true_type());
-        if (k0 + 2 * kStage < m) trip(k0 + 2 * kStage, std::false_type());
+    // The scale fetch waits for its loads on the spot, once per 4096 columns, and stays out of the
+    // inner loop: inside it, it would make every wait of the loop a wait for all loads in flight.
+    for (int ks0 = 0; ks0 < m; ks0 += kScaleGroup) {
+        __syncthreads();                 // everybody is done with the previous group's scales
+        fetch_scales(ks0);
+        const int ks1 = (ks0 + kScaleGroup < m) ? ks0 + kScaleGroup : m;
+        for (int k0 = ks0; k0 < ks1; k0 += kCodeGroup) {
+            trip(k0, std::true_type());
+            if (k0 + 2 * kStage < m) trip(k0 + 2 * kStage, std::false_type());
+        }
     }
     if (my_row < d.n) {
         float *out = P + d.p_off + my_row * 32;
