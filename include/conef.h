@@ -116,6 +116,12 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
 int conef_set_timing(conef_ctx *ctx, int on);
 int conef_get_timing(conef_ctx *ctx, float ms[4]);
 
+/* Host-only self-check of a planned model (diagnostic; no passage of the paper): the work tables of
+ * each of the three passes cover every element of every matrix exactly once, every matrix has its
+ * reduction and orthonormalisation items, and the workspace regions are disjoint and inside
+ * workspace_bytes.  Returns CONEF_OK, or CONEF_ESTATE if the plan is inconsistent. */
+int conef_check_plan(const conef_ctx *ctx);
+
 void conef_destroy(conef_ctx *ctx);
 const char *conef_strerror(int code);
 

@@ -17,7 +17,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 
 EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_p",
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
-           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_destroy",
+           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_destroy",
            "conef_strerror"]
 
 
@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
     L.conef_decode_error.argtypes = [vp, vp, vp, vp, vp]
     L.conef_set_timing.argtypes = [vp, i32]
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    L.conef_check_plan.argtypes = [vp]
     L.conef_destroy.argtypes = [vp]
     L.conef_destroy.restype = None
     L.conef_strerror.argtypes = [i32]
@@ -99,6 +100,10 @@ def conef_sizes(ctx) -> dict:
     _check(lib().conef_sizes(ctx, *[ctypes.byref(x) for x in v]), "conef_sizes")
     keys = ["grad_elems", "code_words", "n_scales", "p_elems", "q_elems", "workspace_bytes"]
     return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+def conef_check_plan(ctx) -> None:
+    _check(lib().conef_check_plan(ctx), "conef_check_plan")
 
 
 def conef_offsets(ctx, mat: int) -> dict:

@@ -134,6 +134,12 @@ int conef_init(conef_ctx **out, const conef_mat *layout, int n_mats, int rank, i
     return CONEF_OK;
 }
 
+int conef_check_plan(const conef_ctx *ctx)
+{
+    if (!ctx) return CONEF_EINVAL;
+    return check_plan(ctx->plan) ? CONEF_OK : CONEF_ESTATE;
+}
+
 int conef_sizes(const conef_ctx *ctx, size_t *grad_elems, size_t *code_words, size_t *n_scales,
                 size_t *p_elems, size_t *q_elems, size_t *workspace_bytes)
 {

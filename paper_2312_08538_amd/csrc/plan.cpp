@@ -1,5 +1,8 @@
 #include "plan.h"
 
+#include <array>
+#include <utility>
+
 #include <algorithm>
 #include <new>
 
@@ -179,6 +182,108 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
         return kEnomem;
     }
     return kOk;
+}
+
+namespace {
+
+struct Cover {
+    std::vector<int64_t> area;                                   // per matrix
+    std::vector<std::array<int32_t, 4>> seen;                    // items, for the duplicate check
+    bool ok = true;
+    explicit Cover(size_t n) : area(n, 0) {}
+    // a rectangle [r0, r0 + rows) x [c0, c0 + cols), clipped to the matrix; must start inside it
+    void add(const Plan &plan, const WorkItem &it, int64_t r0, int64_t rows, int64_t c0, int64_t cols)
+    {
+        if (it.mat < 0 || it.mat >= (int)plan.mats.size()) { ok = false; return; }
+        const MatDesc &d = plan.mats[it.mat];
+        if (r0 < 0 || c0 < 0 || r0 >= d.n || c0 >= d.m || rows <= 0 || cols <= 0) { ok = false; return; }
+        area[it.mat] += std::min<int64_t>(rows, d.n - r0) * std::min<int64_t>(cols, d.m - c0);
+        seen.push_back({it.mat, it.a, it.b, it.c});
+    }
+    void add_elems(const Plan &plan, const WorkItem &it, int64_t e0, int64_t count)      // a run of the flat index
+    {
+        if (it.mat < 0 || it.mat >= (int)plan.mats.size()) { ok = false; return; }
+        const MatDesc &d = plan.mats[it.mat];
+        if (e0 < 0 || e0 >= d.N || count <= 0) { ok = false; return; }
+        area[it.mat] += std::min<int64_t>(count, d.N - e0);
+        seen.push_back({it.mat, it.a, it.b, it.c});
+    }
+    bool complete(const Plan &plan)
+    {
+        if (!ok) return false;
+        std::sort(seen.begin(), seen.end());
+        if (std::adjacent_find(seen.begin(), seen.end()) != seen.end()) return false;
+        for (size_t l = 0; l < plan.mats.size(); ++l)
+            if (area[l] != plan.mats[l].N) return false;
+        return true;
+    }
+};
+
+}  // namespace
+
+bool check_plan(const Plan &plan)
+{
+    const size_t nm = plan.mats.size();
+    // pass 1: P = p Q
+    {
+        Cover c(nm);
+        for (const WorkItem &it : plan.p_items) c.add(plan, it, it.a, 4, 0, INT64_MAX);
+        for (const WorkItem &it : plan.p_f_items)
+            c.add(plan, it, it.a, kPTileRows, (int64_t)it.b * plan.mats[it.mat].p_chunk_cols, plan.mats[it.mat].p_chunk_cols);
+        for (const WorkItem &it : plan.p_m_items) c.add(plan, it, it.a, kMfmaRows, 0, INT64_MAX);
+        if (!c.complete(plan)) return false;
+    }
+    // pass 2: Q+ = p^T P^
+    {
+        Cover c(nm);
+        for (const WorkItem &it : plan.q_items)
+            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * kGenQCols, kGenQCols);
+        for (const WorkItem &it : plan.q_f_items)
+            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 64, 64);
+        for (const WorkItem &it : plan.q_m_items)
+            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 128, 128);
+        if (!c.complete(plan)) return false;
+    }
+    // pass 3: residual, quantiser, pack
+    {
+        Cover c(nm);
+        for (const WorkItem &it : plan.err_items) c.add_elems(plan, it, (int64_t)it.a * plan.block, (int64_t)4 * it.b * plan.block);
+        for (const WorkItem &it : plan.err_f_items) {
+            const int64_t strip = (int64_t)8 << plan.mats[it.mat].lr_shift;
+            c.add(plan, it, it.b, it.c, (int64_t)it.a * strip, strip);
+        }
+        for (const WorkItem &it : plan.err_m_items) c.add(plan, it, it.a, kErrRows, (int64_t)it.b * 128, (int64_t)it.c * 128);
+        if (!c.complete(plan)) return false;
+    }
+    // per-matrix helpers, and the workspace map
+    std::vector<std::pair<int64_t, int64_t>> regions;            // [begin, end) in doubles
+    std::vector<int64_t> gram(nm, 0), apply(nm, 0), qred(nm, 0), pred(nm, 0);
+    for (const WorkItem &it : plan.gram_items) gram[it.mat] += 1;
+    for (const WorkItem &it : plan.apply_items) apply[it.mat] += 1;
+    for (const WorkItem &it : plan.qred_items) qred[it.mat] += 1;
+    for (const WorkItem &it : plan.pred_items) pred[it.mat] += 1;
+    for (size_t l = 0; l < nm; ++l) {
+        const MatDesc &d = plan.mats[l];
+        if (gram[l] != d.n_gram_tiles || apply[l] != (d.n + 63) / 64) return false;
+        const bool direct_q = d.path == kPathMfma && d.n_q_tiles == 1;
+        if (qred[l] != (direct_q ? 0 : (d.m * plan.rank + 255) / 256)) return false;
+        if (pred[l] != (d.n_p_chunks > 1 ? (d.n * plan.rank + 255) / 256 : 0)) return false;
+        regions.push_back({d.gram_off, d.gram_off + (int64_t)d.n_gram_tiles * plan.rank * plan.rank});
+        regions.push_back({d.rinv_off, d.rinv_off + (int64_t)plan.rank * plan.rank});
+        regions.push_back({d.qpart_off, d.qpart_off + (int64_t)d.n_q_tiles * d.m * plan.rank});
+        if (d.n_p_chunks > 1) regions.push_back({d.ppart_off, d.ppart_off + (int64_t)d.n_p_chunks * d.n * plan.rank});
+        if (d.path == kPathMfma) {
+            regions.push_back({d.scT_off, d.scT_off + ((d.m / 128) * d.n * 4 + 7) / 8});
+            regions.push_back({d.ps_off, d.ps_off + 3 * 32 * d.n * 2 / 8});
+            regions.push_back({d.qs_off, d.qs_off + 3 * 32 * d.m * 2 / 8});
+        }
+    }
+    std::sort(regions.begin(), regions.end());
+    for (size_t i = 0; i < regions.size(); ++i) {
+        if (regions[i].first < 0 || regions[i].second > (int64_t)plan.ws_doubles) return false;
+        if (i > 0 && regions[i].first < regions[i - 1].second) return false;
+    }
+    return true;
 }
 
 }  // namespace conef

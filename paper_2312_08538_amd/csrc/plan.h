@@ -70,7 +70,7 @@ struct Plan {
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
     std::vector<WorkItem> q_m_items;    // (mat, column block of 128, row tile)
     std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
-    std::vector<WorkItem> split_p_items;   // split P^ (both layouts):      (mat, first row / 64)
+    std::vector<WorkItem> split_p_items;   // split P^ / transpose the scales: (mat, first row / 64)
     std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
     // shared
     std::vector<WorkItem> pred_items;   // reduce partial P: (mat, first entry of n*r)
@@ -79,6 +79,12 @@ struct Plan {
     std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
     std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
 };
+
+// Checks that the work tables of each of the three passes cover every element of every matrix exactly
+// once (items inside their matrix, no item twice, covered areas adding up to rows x cols), that every
+// matrix has its reduction, Gram and apply items, and that the workspace regions do not overlap.
+// Returns true if so.
+bool check_plan(const Plan &plan);
 
 // Returns 0 or a negative CONEF_E* code.  `rows`/`cols` have n_mats entries.
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,

@@ -100,3 +100,37 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libconef.so"))
     with pytest.raises(RuntimeError):
         B.lib()
+
+
+PLAN_CASES = [
+    # (layout, rank, bits, block, dtype): every kernel family, ragged tiles, short last blocks
+    ([(256, 128)], 2, 8, 64, B.F32),
+    ([(64, 147), (64, 576), (512, 4608), (1000, 512)], 4, 4, 128, B.F32),
+    ([(32768, 1024), (1024, 4096), (4096, 1024), (77, 1024)], 8, 2, 256, B.BF16),
+    ([(50304, 2048), (2048, 8192), (8192, 2048), (2200, 128), (300, 2304), (45, 384)], 32, 4, 128, B.BF16),
+    ([(64, 147), (5, 3), (2, 67), (130, 2), (33, 129), (2, 1000), (257, 64)], 2, 4, 8, B.F32),
+    ([(96, 160), (40, 512), (300, 33)], 16, 4, 32, B.F32),
+    ([(640, 192), (65, 64), (129, 320)], 4, 8, 64, B.BF16),
+    ([(3000, 512), (100, 1536)], 8, 4, 512, B.F32),
+]
+
+
+@pytest.mark.parametrize("case", range(len(PLAN_CASES)))
+def test_work_tables_cover_every_matrix_exactly_once(case):
+    """The planner's work tables (which workgroup does which rows and columns in each of the three
+    passes, per kernel family), its reduction / orthonormalisation items and its workspace map."""
+    layout, rank, bits, block, dtype = PLAN_CASES[case]
+    ctx = B.conef_init(layout, rank, bits, block, dtype, 1)
+    try:
+        B.conef_check_plan(ctx)
+    finally:
+        B.conef_destroy(ctx)
+
+
+def test_full_workloads_plan_consistently():
+    for w in wl.WORKLOADS.values():
+        ctx = B.conef_init(list(w.layout), w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+        try:
+            B.conef_check_plan(ctx)
+        finally:
+            B.conef_destroy(ctx)
