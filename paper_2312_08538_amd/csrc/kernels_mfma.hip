@@ -494,7 +494,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
     const int tr_d = tr_row * 32 + tr_col;                      // d P^ tile
 
+    // Wave priority: the phases that issue loads and fill LDS run at a higher priority than the
+    // matrix-core phase, so that the workgroup that is feeding the memory pipeline is not held up by
+    // the other workgroup of the CU, which is computing (measured: 3 % for this pass; the same in the
+    // P pass costs 3 %, and there it is not done).
     auto compute_chunk = [&]() {
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
             Frag bg, bq, aP[3], aD[3];
@@ -514,6 +519,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
+        __builtin_amdgcn_s_setprio(2);
     };
 
     // Two chunks per trip, one register set each.  A tile with an odd number of chunks runs one
@@ -694,6 +700,7 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
         }
         load_in(in, cbn);
         // matrix-core phase: acc[t] -= P^ Q+^T over the rank, six split products
+        __builtin_amdgcn_s_setprio(2);
         const uint16_t *buf = sB[b & 1];
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -712,6 +719,7 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
         }
         {
             // the buffer written here was last read before the previous barrier
+            __builtin_amdgcn_s_setprio(0);
             uint4 *dst = reinterpret_cast<uint4 *>(sB[(b + 1) & 1]) + tid;
             dst[0] = bq0; dst[512] = bq1; dst[1024] = bq2;
         }
