@@ -189,22 +189,10 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
     for (int e = 0; e < 8; ++e) load_factor_row<RP>(Qn, d.q_off + ((int64_t)oc * 8 + e) * r, true, q[e]);
 
     const int row_end = it.b + it.c;
-    int row = it.b + sub;
-    bool valid = row < row_end;
-    RawOctet<BF16, BITS> cur = load_octet<BF16, BITS>(d, grads, codes, scales, (int64_t)row * d.m8 + oc, valid);
-    float ph[RP];
-    load_factor_row<RP>(Phat, d.p_off + (int64_t)row * r, valid, ph);
-
-    for (int r0 = it.b; r0 < row_end; r0 += rw) {
-        // prefetch the next row of this lane before working on the current one
-        const int nrow = row + rw;
-        const bool nvalid = nrow < row_end;
-        const RawOctet<BF16, BITS> nxt = load_octet<BF16, BITS>(d, grads, codes, scales, (int64_t)nrow * d.m8 + oc, nvalid);
-        float nph[RP];
-        load_factor_row<RP>(Phat, d.p_off + (int64_t)nrow * r, nvalid, nph);
-
+    // One row of this lane: decode, residual, block max-norm, rounding, store.
+    auto process = [&](const RawOctet<BF16, BITS> &oct, const float (&ph)[RP], int row, bool valid) {
         float x[8];
-        decode_octet<BF16, BITS>(cur, x);
+        decode_octet<BF16, BITS>(oct, x);
         float a = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -226,11 +214,26 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
             store_codes<BITS>(d, codes, o, f);
             if ((lc & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
         }
-        cur = nxt;
-#pragma unroll
-        for (int c = 0; c < RP; ++c) ph[c] = nph[c];
-        row = nrow;
-        valid = nvalid;
+    };
+    // Rows at or beyond the end of the item re-read its last row (nothing is stored for them), so the
+    // loads are unconditional.  The next row is loaded before the current one is worked on; two
+    // register sets take turns, so nothing is copied from one to the other.
+    auto load_row = [&](RawOctet<BF16, BITS> &oct, float (&ph)[RP], int row) {
+        const int rc = row < row_end ? row : row_end - 1;
+        oct = load_octet_always<BF16, BITS>(d, grads, codes, scales, (int64_t)rc * d.m8 + oc);
+        load_factor_row<RP>(Phat, d.p_off + (int64_t)rc * r, true, ph);
+    };
+    RawOctet<BF16, BITS> oa, ob;
+    float pa[RP], pb[RP];
+    int row = it.b + sub;
+    load_row(oa, pa, row);
+    for (int r0 = it.b; r0 < row_end; r0 += 2 * rw) {
+        load_row(ob, pb, row + rw);
+        process(oa, pa, row, row < row_end);
+        if (r0 + rw >= row_end) break;              // uniform
+        load_row(oa, pa, row + 2 * rw);
+        process(ob, pb, row + rw, row + rw < row_end);
+        row += 2 * rw;
     }
 }
 
