@@ -32,36 +32,9 @@ struct RawOctet {
     float scale;
 };
 
-template <bool BF16, int BITS>
-__device__ __forceinline__ RawOctet<BF16, BITS> load_octet(const MatDesc &d, const void *__restrict__ grads,
-                                                           const uint32_t *codes, const float *scales,
-                                                           int64_t o /* octet index in the matrix */, bool valid)
-{
-    RawOctet<BF16, BITS> r;
-    r.g0 = make_uint4(0, 0, 0, 0); r.g1 = make_uint4(0, 0, 0, 0); r.c0 = 0; r.c1 = 0; r.scale = 0.0f;
-    if (valid) {
-        if (BF16) {
-            r.g0 = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(grads) + d.grad_off + o * 8);
-        } else {
-            const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(grads) + d.grad_off + o * 8);
-            r.g0 = gp[0];
-            r.g1 = gp[1];
-        }
-        if (BITS == 8) {
-            const uint2 c = *reinterpret_cast<const uint2 *>(codes + d.word_off + o * 2);
-            r.c0 = c.x; r.c1 = c.y;
-        } else if (BITS == 4) {
-            r.c0 = codes[d.word_off + o];
-        } else {
-            r.c0 = reinterpret_cast<const uint16_t *>(codes + d.word_off)[o];
-        }
-        r.scale = scales[d.scale_off + (o >> d.lb_shift)];
-    }
-    return r;
-}
-
-// The same without a condition: `o` must be an octet of the matrix (callers clamp).  Loads behind a
-// condition cost a branch each and make the waits on them conservative.
+// Loads one octet with its code bits and block scale; `o` must be an octet of the matrix (callers
+// clamp and mask instead of loading behind a condition: a conditional load costs a branch and makes
+// the waits on it conservative).
 template <bool BF16, int BITS>
 __device__ __forceinline__ RawOctet<BF16, BITS> load_octet_always(const MatDesc &d, const void *__restrict__ grads,
                                                                   const uint32_t *codes, const float *scales, int64_t o)
