@@ -35,7 +35,7 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
 hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, bool write_splits, hipStream_t st,
                                  Span span = Span());
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, bool p_splits_ready, hipStream_t st,
+                         const float *Phat, float *Qout, double *ws, bool fused, hipStream_t st,
                          Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
                            const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
@@ -59,7 +59,7 @@ void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                     const float *Qn, uint64_t step, hipStream_t st);
 
-// MFMA family.  `prep_only` / `main_only` select the operand-split kernels or the pass itself.
+// MFMA family.
 void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Q, float *P, hipStream_t st);
 

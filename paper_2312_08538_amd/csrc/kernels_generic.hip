@@ -251,11 +251,9 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
 }
 
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, bool p_splits_ready, hipStream_t st, Span span)
+                         const float *Phat, float *Qout, double *ws, bool fused, hipStream_t st, Span span)
 {
-    // the factors handed in may differ from those the orthonormalisation stage produced (e.g. after
-    // an all-reduce), unless the caller says otherwise
-    if (!p_splits_ready) mfma_split_p_hat(dp, Phat, ws, st);
+    (void)fused;
     // the matrix-core family reads the block scales of the incoming error state column block by column block
     mfma_transpose_scales(dp, scales, ws, st);
     if (span.begin) (void)hipEventRecord(span.begin, st);
