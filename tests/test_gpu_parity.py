@@ -255,3 +255,41 @@ def test_runs_are_reproducible(env):
                      gpu.buf["P"].cpu().numpy().copy()))
     for a, b in zip(outs[0], outs[1]):
         assert np.array_equal(a, b)
+
+
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step(env):
+    """conef_step enqueues kernels only (no allocation, no memset, no synchronisation after the first
+    use of a context), so it can be captured in a HIP graph.  Every replay, with eager work and
+    synchronisations between the replays, must give the bits of the eager step on the same inputs."""
+    R, B, U = env
+    import torch
+
+    for name, layout in [("large", [(300, 256), (130, 384)]), ("translation", [(200, 512)]), ("cnn", [(64, 147), (128, 256)])]:
+        w = wl.WORKLOADS[name]
+        Q0s = [wl.host_q0(w, l, shape=layout[l]) for l in range(len(layout))]
+        grads = [[wl.host_gradient(w, t, l, shape=layout[l]) for l in range(len(layout))] for t in range(2)]
+        gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+        b = gpu.buf
+        # eager: step 0 (also uploads the work tables), then step 1; keep the inputs and result of step 1
+        gpu.set_grads(grads[0]); gpu.step(0)
+        before = {k: b[k].clone() for k in ("codes", "scales", "Q")}
+        gpu.set_grads(grads[1]); gpu.step(1)
+        want = {k: b[k].clone() for k in ("codes", "scales", "Q", "P")}
+        # capture step 1 on a side stream
+        s = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        for k in before:
+            b[k].copy_(before[k])
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=s):
+            gpu.m.step(b, 1)
+        for replay in range(3):
+            for k in before:
+                b[k].copy_(before[k])            # eager work between the replays
+            b["P"].zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for k in want:
+                assert torch.equal(b[k], want[k]), (name, replay, k)
+        gpu.m.close()
