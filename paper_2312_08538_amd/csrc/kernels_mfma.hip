@@ -388,42 +388,52 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const WorkItem it = dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
     const MatDesc d = dp.mats[it.mat];
-    const int m = (int)d.m, cb = it.a;
-    const int col0 = cb * 128;
+    const int m = (int)d.m;
+    // The item is a PAIR of neighbouring column blocks, A = 2 it.a and B = A + 1, worked on in turn
+    // chunk by chunk: the chunk's rows of P^ are fetched and split once for both (the splits of d_i P^
+    // differ, the step sizes are per block), and the two halves of the rows' code lines (128 columns
+    // of 4-bit codes are 64 bytes) are fetched close together in time.  A matrix with an odd number of
+    // blocks ends with a pair whose B does not exist: it re-reads A and is not written.
+    const int cbA = 2 * it.a, nblk_row = m >> 7;
+    const bool has_b = cbA + 1 < nblk_row;
+    const int cbB = has_b ? cbA + 1 : cbA;
     const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
     const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
     const uint16_t *g = grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
-    const float *scT = reinterpret_cast<const float *>(ws + d.scT_off) + (int64_t)cb * d.n;   // this block's scales, by row
+    const float *scT = reinterpret_cast<const float *>(ws + d.scT_off);       // [block][row]
     const float *ph = Phat + d.p_off;
 
-    // A chunk's loads are held in registers until its turn in LDS; two chunks are in flight.  Every
-    // load is unconditional (rows at or beyond the end of the tile re-read its last row and get zero
-    // factor operands instead): the waits on a chunk can then leave the younger chunk's loads pending.
+    // A block-chunk's loads are held in registers until its turn in LDS; two are in flight (block A and
+    // block B of a chunk, or B and the next chunk's A).  Every load is unconditional (rows at or beyond
+    // the end of the tile re-read its last row and get zero factor operands instead): the waits on one
+    // can then leave the younger one's loads pending.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef float f32x4v __attribute__((ext_vector_type(4)));
     struct ChunkRegs {
         u32x4 g0, g1, g2, g3;
         uint32_t cw0, cw1, cw2, cw3;
-        f32x4v p0, p1;
         float sc;
     };
     const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
     const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
-    auto load_chunk = [&](ChunkRegs &r, int64_t i0) {
+    auto load_factor = [&](f32x4v &p0, f32x4v &p1, int64_t i0) {
+        const int64_t row = (i0 + frow < row1) ? i0 + frow : row1 - 1;
+        const f32x4v *pp = reinterpret_cast<const f32x4v *>(ph + row * 32 + fcg * 8);
+        p0 = pp[0];
+        p1 = pp[1];
+    };
+    auto load_chunk = [&](ChunkRegs &r, int64_t i0, int cb) {
         const int64_t last = row1 - 1;
         {
             const int64_t row = (i0 + frow < row1) ? i0 + frow : last;
-            const f32x4v *pp = reinterpret_cast<const f32x4v *>(ph + row * 32 + fcg * 8);
-            r.p0 = pp[0];
-            r.p1 = pp[1];
-            r.sc = scT[row];
+            r.sc = scT[(int64_t)cb * d.n + row];
         }
         int64_t e[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int64_t row = (i0 + grow + 16 * s < row1) ? i0 + grow + 16 * s : last;
-            e[s] = row * m + col0;
+            e[s] = row * m + cb * 128;
         }
         r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0] + goct * 8);
         r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1] + goct * 8);
@@ -434,7 +444,20 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         r.cw2 = cw[(e[2] >> 3) + goct];
         r.cw3 = cw[(e[3] >> 3) + goct];
     };
-    auto store_chunk = [&](const ChunkRegs &r, int64_t i0) {
+    auto store_split = [&](uint16_t *o, const float (&x)[8]) {
+        float hh[8], mm[8], ll[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) split3(x[j], hh[j], mm[j], ll[j]);
+        *reinterpret_cast<uint4 *>(o) =
+            make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
+        *reinterpret_cast<uint4 *>(o + kQRows * 32) =
+            make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+        *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
+            make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
+    };
+    // pv: the thread's 8 entries of its row of P^ (zero for rows at or beyond the end of the tile,
+    // whatever the re-read row holds); with_p: also store the splits of P^ itself (first block of a chunk)
+    auto store_chunk = [&](const ChunkRegs &r, const float (&pv)[8], bool row_ok, bool with_p) {
         const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
         const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
 #pragma unroll
@@ -449,56 +472,32 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
-        {
-            // rows at or beyond the end of the tile: zero operands, whatever the re-read row holds
-            const bool ok = i0 + frow < row1;
-            const float dstep = ok ? r.sc * inv_levels(4) : 0.0f;
-            float pv[8] = {r.p0[0], r.p0[1], r.p0[2], r.p0[3], r.p1[0], r.p1[1], r.p1[2], r.p1[3]};
-            float hh[8], mm[8], ll[8];
+        if (with_p) store_split(sb + frow * 32 + fcg * 8, pv);
+        const float dstep = row_ok ? r.sc * inv_levels(4) : 0.0f;
+        float dp8[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                pv[j] = ok ? pv[j] : 0.0f;
-                split3(pv[j], hh[j], mm[j], ll[j]);
-            }
-            {
-                uint16_t *o = sb + frow * 32 + fcg * 8;
-                *reinterpret_cast<uint4 *>(o) =
-                    make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
-                *reinterpret_cast<uint4 *>(o + kQRows * 32) =
-                    make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
-                *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
-                    make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) split3(dstep * pv[j], hh[j], mm[j], ll[j]);
-            uint16_t *o = sd + frow * 32 + fcg * 8;
-            *reinterpret_cast<uint4 *>(o) =
-                make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
-            *reinterpret_cast<uint4 *>(o + kQRows * 32) =
-                make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
-            *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
-                make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
-        }
+        for (int j = 0; j < 8; ++j) dp8[j] = dstep * pv[j];
+        store_split(sd + frow * 32 + fcg * 8, dp8);
     };
 
     // the matrix cores accumulate one 64-row chunk in fp32; chunks are added up in fp64
     f32x16 acc;
-    double acc64[16];
+    double accA[16], accB[16];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; acc64[v] = 0.0; }
+    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; accA[v] = 0.0; accB[v] = 0.0; }
     const int r32 = lane & 31, ig = lane >> 5;
     // transposing reads: 16-lane group gq covers columns 16 (gq & 1) .. of the 32-wide operand and
     // rows 8 (gq >> 1) ..; lane li of the group addresses row li / 4, columns 4 (li % 4) ..
     const int gq = lane >> 4, li = lane & 15;
     const int tr_row = 8 * (gq >> 1) + (li >> 2), tr_col = 16 * (gq & 1) + 4 * (li & 3);
     const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
-    const int tr_d = tr_row * 32 + tr_col;                      // d P^ tile
+    const int tr_d = tr_row * 32 + tr_col;                      // P^ and d P^ tiles
 
     // Wave priority: the phases that issue loads and fill LDS run at a higher priority than the
     // matrix-core phase, so that the workgroup that is feeding the memory pipeline is not held up by
     // the other workgroup of the CU, which is computing (measured: 3 % for this pass; the same in the
     // P pass costs 3 %, and there it is not done).
-    auto compute_chunk = [&]() {
+    auto compute_chunk = [&](double (&acc64)[16]) {
         __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
@@ -522,41 +521,51 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         __builtin_amdgcn_s_setprio(2);
     };
 
-    // Two chunks per trip, one register set each.  A tile with an odd number of chunks runs one
-    // chunk past its end: all of that chunk's factor operands are zero.
+    // One chunk per trip: block A, then block B with the same rows of P^.
     ChunkRegs ra, rb;
-    load_chunk(ra, row0);
-    load_chunk(rb, row0 + kQRows);
-    for (int64_t i0 = row0; i0 < row1; i0 += 2 * kQRows) {
-        __syncthreads();                // everybody is done reading the previous chunk
-        store_chunk(ra, i0);
+    f32x4v np0, np1;                    // the next chunk's rows of P^
+    load_factor(np0, np1, row0);
+    load_chunk(ra, row0, cbA);
+    load_chunk(rb, row0, cbB);
+    for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
+        const bool row_ok = i0 + frow < row1;
+        float pv[8] = {np0[0], np0[1], np0[2], np0[3], np1[0], np1[1], np1[2], np1[3]};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pv[j] = row_ok ? pv[j] : 0.0f;
+        __syncthreads();                // everybody is done reading the previous block-chunk
+        store_chunk(ra, pv, row_ok, true);
         __syncthreads();
-        load_chunk(ra, i0 + 2 * kQRows);
-        compute_chunk();
+        load_factor(np0, np1, i0 + kQRows);
+        load_chunk(ra, i0 + kQRows, cbA);
+        compute_chunk(accA);
         __syncthreads();
-        store_chunk(rb, i0 + kQRows);
+        store_chunk(rb, pv, row_ok, false);
         __syncthreads();
-        load_chunk(rb, i0 + 3 * kQRows);
-        compute_chunk();
+        load_chunk(rb, i0 + kQRows, cbB);
+        compute_chunk(accB);
     }
     // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
-    const int kcol = col0 + 32 * wave + r32;
-    if (d.n_q_tiles == 1) {
-        // the only row tile of this matrix: Q+ and its operand splits are final
-        float *qo = Qout + d.q_off + (int64_t)kcol * 32;
+    auto write_block = [&](const double (&acc64)[16], int cb) {
+        const int kcol = cb * 128 + 32 * wave + r32;
+        if (d.n_q_tiles == 1) {
+            // the only row tile of this matrix: Q+ and its operand splits are final
+            float *qo = Qout + d.q_off + (int64_t)kcol * 32;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-            const float x = (float)acc64[v];
-            qo[c] = x;
-            mfma_store_q_split(d, ws, kcol, c, x);
+            for (int v = 0; v < 16; ++v) {
+                const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
+                const float x = (float)acc64[v];
+                qo[c] = x;
+                mfma_store_q_split(d, ws, kcol, c, x);
+            }
+        } else {
+            // partial sums of this row tile, added in tile order by the reduction kernel
+            double *out = ws + d.qpart_off + ((int64_t)it.b * m + kcol) * 32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
         }
-        return;
-    }
-    // partial sums of this row tile, added in tile order by the reduction kernel
-    double *out = ws + d.qpart_off + ((int64_t)it.b * m + kcol) * 32;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
+    };
+    write_block(accA, cbA);
+    if (has_b) write_block(accB, cbB);
 }
 
 // ------------------------------------------------------------------ err pass

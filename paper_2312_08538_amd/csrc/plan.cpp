@@ -123,8 +123,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 for (int64_t r0 = 0; r0 < d.n; r0 += kMfmaRows) plan.p_m_items.push_back({l, (int32_t)r0, 0, 0});
             }
             if (mf_q) {
+                // one item per pair of neighbouring column blocks (the last pair of an odd count has one)
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
-                    for (int32_t cb = 0; cb < (int32_t)(d.m / 128); ++cb) plan.q_m_items.push_back({l, cb, rt, 0});
+                    for (int32_t cp = 0; cp < (int32_t)((d.m / 128 + 1) / 2); ++cp) plan.q_m_items.push_back({l, cp, rt, 0});
             }
             if (mf_q || mf_e)
                 for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.split_p_items.push_back({l, (int32_t)(r0 / 64), 0, 0});
@@ -241,7 +242,7 @@ bool check_plan(const Plan &plan)
         for (const WorkItem &it : plan.q_f_items)
             c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 64, 64);
         for (const WorkItem &it : plan.q_m_items)
-            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 128, 128);
+            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 256, 256);
         if (!c.complete(plan)) return false;
     }
     // pass 3: residual, quantiser, pack

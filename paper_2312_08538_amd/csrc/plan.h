@@ -68,7 +68,7 @@ struct Plan {
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
-    std::vector<WorkItem> q_m_items;    // (mat, column block of 128, row tile)
+    std::vector<WorkItem> q_m_items;    // (mat, pair of column blocks of 128, row tile)
     std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
     std::vector<WorkItem> split_p_items;   // split P^ / transpose the scales: (mat, first row / 64)
     std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
