@@ -12,6 +12,7 @@
  *     layerwise fashion"):
  *         line 5   p = eta*g + e            (eta folded into g by the caller)
  *         line 6   Delta = Q(p)             gradient compressor: rank-r PowerSGD
+ *         lines 7-8  x+ = x - Delta         decompress and apply (one worker: the aggregate is Delta)
  *         line 9   e+ = C(p - Delta)        error compressor: stochastic quantiser
  *   - Section 4.2.1, eq. (3): C(e_i) = ||e|| * sign(e_i) * xi_i, xi_i in
  *     {l/s, (l+1)/s}, rounded up with probability |e_i|/||e|| * s - l, with the
@@ -27,7 +28,8 @@
  * Parity pins (tests/test_oracle_*.py): Philox known-answer vectors; exact
  * expectation of the quantiser by enumeration of all 2^16 draws; closed-form
  * variance; numpy QR / SVD / matmul for the low-rank part; exact recovery of
- * rank<=r inputs; brute force in Python integers/fp64 on tiny matrices.
+ * rank<=r inputs; brute force in Python integers/fp64 on tiny matrices; exact
+ * integer products and the identity p = Delta + residual for the update.
  * Absolute values of a multi-step run have no printed value in the paper to
  * compare with: "parity unpinned" for those, only invariants are checked.
  *
@@ -219,6 +221,33 @@ void ref_residual(const float *p, int64_t n, int64_t m, const float *Phat, const
             float acc = 0.0f;
             for (int c = 0; c < r; ++c) acc = fmaf(Phat[i * r + c], Qn[k * r + c], acc);
             x[i * m + k] = p[i * m + k] - acc;
+        }
+}
+
+/* Decompression and update, Algorithm 2 lines 7 and 8: the (aggregated) compressed gradient
+ * Delta = Phat*Qn^T is written out, or subtracted from the parameters, x <- x - Delta.  For one worker
+ * the aggregate of line 7 is the worker's own Delta.  Each entry of Delta is the same fp32 fma chain
+ * over c = 0..r-1 as in ref_residual (so p = Delta + residual holds entry by entry up to the one
+ * rounding of the subtraction); the update is one more fp32 subtraction.                              */
+void ref_decompress(int64_t n, int64_t m, const float *Phat, const float *Qn, int r, float *delta)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t k = 0; k < m; ++k) {
+            float acc = 0.0f;
+            for (int c = 0; c < r; ++c) acc = fmaf(Phat[i * r + c], Qn[k * r + c], acc);
+            delta[i * m + k] = acc;
+        }
+}
+
+void ref_apply_update(float *x, int64_t n, int64_t m, const float *Phat, const float *Qn, int r)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t k = 0; k < m; ++k) {
+            float acc = 0.0f;
+            for (int c = 0; c < r; ++c) acc = fmaf(Phat[i * r + c], Qn[k * r + c], acc);
+            x[i * m + k] = x[i * m + k] - acc;
         }
 }
 

@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
         L.ref_lowrank_Q.restype = None
         L.ref_residual.argtypes = [vp, i64, i64, vp, vp, i32, vp]
         L.ref_residual.restype = None
+        L.ref_decompress.argtypes = [i64, i64, vp, vp, i32, vp]
+        L.ref_decompress.restype = None
+        L.ref_apply_update.argtypes = [vp, i64, i64, vp, vp, i32]
+        L.ref_apply_update.restype = None
         L.ref_quantise.argtypes = [vp, i64, i32, i32, u64, u32, u64, vp, vp, vp]
         L.ref_quantise.restype = None
         L.ref_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, i32, u64, u32, u64,
@@ -189,6 +193,24 @@ def residual(p, Phat, Qn) -> np.ndarray:
     x = np.empty((n, m), np.float32)
     lib().ref_residual(_p(pa), n, m, _p(Pa), _p(Qa), Pa.shape[1], _p(x))
     return x
+
+
+def decompress(Phat, Qn) -> np.ndarray:
+    """Delta = Phat Qn^T (Algorithm 2 line 7 for one worker), each entry an fp32 fma chain over c."""
+    Pa, Qa = _c(Phat, np.float32), _c(Qn, np.float32)
+    n, m = Pa.shape[0], Qa.shape[0]
+    delta = np.empty((n, m), np.float32)
+    lib().ref_decompress(n, m, _p(Pa), _p(Qa), Pa.shape[1], _p(delta))
+    return delta
+
+
+def apply_update(x, Phat, Qn) -> np.ndarray:
+    """x - Phat Qn^T (Algorithm 2 line 8); returns a new array."""
+    xa = np.array(x, np.float32, order="C", copy=True)
+    Pa, Qa = _c(Phat, np.float32), _c(Qn, np.float32)
+    n, m = xa.shape
+    lib().ref_apply_update(_p(xa), n, m, _p(Pa), _p(Qa), Pa.shape[1])
+    return xa
 
 
 # ---------------------------------------------------------------- whole step
