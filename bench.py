@@ -98,6 +98,39 @@ def run_gpu(w, steps: int, warmup: int):
     return (t1 - t0) * 1e3 / steps, dict(zip(STAGES, stage_ms)), finite
 
 
+def run_update(w, reps: int = 10):
+    """Times the decompress-and-apply call that follows a step (Algorithm 2 lines 7-8, x <- x - P^ Q+^T)
+    on fp32 parameters of the workload's layout, with HIP events on the launch stream.  Not part of
+    `value`: the headline step is the compression path; this is reported beside it."""
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+    from paper_2312_08538_amd import workloads as wl
+
+    model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+    P = torch.randn(model.sizes["p_elems"], dtype=torch.float32, device="cuda:0")
+    Q = torch.randn(model.sizes["q_elems"], dtype=torch.float32, device="cuda:0") * 1e-3
+    x = torch.zeros(model.sizes["grad_elems"], dtype=torch.float32, device="cuda:0")
+    st = model.stream_handle()
+    for _ in range(2):
+        B.conef_apply_update(model.ctx, P, Q, x, st)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for e0, e1 in ev:                       # the library launches on torch's current stream, where these events go
+        e0.record()
+        B.conef_apply_update(model.ctx, P, Q, x, st)
+        e1.record()
+    torch.cuda.synchronize()
+    ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / reps
+    finite = bool(torch.isfinite(x).all())
+    model.close()
+    del P, Q, x
+    torch.cuda.empty_cache()
+    nbytes = 8 * w.elements + 4 * w.rank * sum(n + m for n, m in w.layout)       # read + write x, read the factors
+    return {"ms": round(ms, 4), "bytes": int(nbytes), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "finite": finite}
+
+
 def run_oracle_sample(w, budget_s: float = 20.0):
     """Times the oracle (as it stands) on the workload's matrices in layout order, one step from
     zero error, until about `budget_s` seconds of CPU work are spent or the whole model is done.
@@ -219,6 +252,7 @@ def main():
                      "traffic": load_traffic(w.name, dom)},
     }
     if not a.no_extra:
+        out["apply_update"] = run_update(w)
         extra = {}
         for name in ("cnn", "lm", "translation", "large"):
             if name == w.name:

@@ -106,6 +106,19 @@ int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, vo
 int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *err_scales,
                        float *e_out, void *hip_stream);
 
+/* Decompression and update, Algorithm 2 lines 7 and 8 (for one worker the aggregate of line 7 is the
+ * worker's own Delta; with several, pass the all-reduced factors):
+ *   conef_decompress    delta_out <- P^ Q+^T
+ *   conef_apply_update  params    <- params - P^ Q+^T
+ * Every entry of Delta is the fp32 fma chain over c = 0..r-1 that the err stage subtracts from p, so
+ * p = Delta + (argument of the error compressor) holds entry by entry up to one rounding.
+ * P_hat, Q_new         device, in      the factors conef_step / conef_step_q wrote (P_out, Q_out)
+ * delta_out / params   device, out / in-out   fp32, flat, laid out like an fp32 gradient buffer with the
+ *                      same element offsets (grad_off of conef_offsets); 16-byte aligned
+ * Asynchronous on hip_stream.  Errors: CONEF_EINVAL (null or misaligned pointer), CONEF_EHIP. */
+int conef_decompress(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *delta_out, void *hip_stream);
+int conef_apply_update(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *params, void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

@@ -17,7 +17,8 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 
 EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_p",
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
-           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_destroy",
+           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
+           "conef_apply_update", "conef_destroy",
            "conef_strerror"]
 
 
@@ -52,6 +53,8 @@ def lib() -> ctypes.CDLL:
     L.conef_set_timing.argtypes = [vp, i32]
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.conef_check_plan.argtypes = [vp]
+    L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
+    L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
     L.conef_destroy.argtypes = [vp]
     L.conef_destroy.restype = None
     L.conef_strerror.argtypes = [i32]
@@ -144,6 +147,14 @@ def conef_reset_error(ctx, err_codes, err_scales, stream=0):
 def conef_decode_error(ctx, err_codes, err_scales, e_out, stream=0):
     _check(lib().conef_decode_error(ctx, _ptr(err_codes), _ptr(err_scales), _ptr(e_out), stream),
            "conef_decode_error")
+
+
+def conef_decompress(ctx, P_hat, Q_new, delta_out, stream=0):
+    _check(lib().conef_decompress(ctx, _ptr(P_hat), _ptr(Q_new), _ptr(delta_out), stream), "conef_decompress")
+
+
+def conef_apply_update(ctx, P_hat, Q_new, params, stream=0):
+    _check(lib().conef_apply_update(ctx, _ptr(P_hat), _ptr(Q_new), _ptr(params), stream), "conef_apply_update")
 
 
 def conef_set_timing(ctx, on: bool):

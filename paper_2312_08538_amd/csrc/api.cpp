@@ -52,6 +52,7 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.p_items, &d.p_items))) return rc;
     if ((rc = upload(ctx, pl.q_items, &d.q_items))) return rc;
     if ((rc = upload(ctx, pl.err_items, &d.err_items))) return rc;
+    if ((rc = upload(ctx, pl.upd_items, &d.upd_items))) return rc;
     if ((rc = upload(ctx, pl.p_f_items, &d.p_f_items))) return rc;
     if ((rc = upload(ctx, pl.q_f_items, &d.q_f_items))) return rc;
     if ((rc = upload(ctx, pl.err_f_items, &d.err_f_items))) return rc;
@@ -69,6 +70,7 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_p = (int)pl.p_items.size();
     d.n_q = (int)pl.q_items.size();
     d.n_err = (int)pl.err_items.size();
+    d.n_upd = (int)pl.upd_items.size();
     d.n_p_f = (int)pl.p_f_items.size();
     d.n_q_f = (int)pl.q_f_items.size();
     d.n_err_f = (int)pl.err_f_items.size();
@@ -278,6 +280,27 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     return hip_rc(launch_decode(ctx->dev, err_codes, err_scales, e_out, static_cast<hipStream_t>(hip_stream)));
+}
+
+namespace {
+int update_impl(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *x, void *hip_stream, bool subtract)
+{
+    if (!ctx || !P_hat || !Q_new || !x) return CONEF_EINVAL;
+    if (misaligned(P_hat, 4) || misaligned(Q_new, 4) || misaligned(x, 16)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_update(ctx->dev, P_hat, Q_new, x, subtract, static_cast<hipStream_t>(hip_stream)));
+}
+}  // namespace
+
+int conef_decompress(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *delta_out, void *hip_stream)
+{
+    return update_impl(ctx, P_hat, Q_new, delta_out, hip_stream, false);
+}
+
+int conef_apply_update(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *params, void *hip_stream)
+{
+    return update_impl(ctx, P_hat, Q_new, params, hip_stream, true);
 }
 
 int conef_set_timing(conef_ctx *ctx, int on)

@@ -13,11 +13,13 @@ struct DevicePlan {
     const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
+    const WorkItem *upd_items = nullptr;                                                   // decompress / update
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
                    *elem_items = nullptr;
     int n_mats = 0;
     int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0;
     int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_p = 0, n_split_qn = 0;
+    int n_upd = 0;
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
@@ -40,6 +42,8 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
                            const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
                            hipStream_t st, Span span = Span());
+hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
+                         hipStream_t st);
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);
 hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,

@@ -285,6 +285,118 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ decompress / update
+// Delta = P^ Q+^T (Algorithm 2 line 7 for one worker) written out, or subtracted from the parameters
+// (line 8).  One workgroup per 64 x 128 tile: the tile's rows of P^ and of Q+ go through LDS
+// (transposed, so that a thread reads its 4 rows and 2 x 4 columns of one rank index with three 16-byte
+// reads), a thread holds a 4 x 8 block of sums, each the fp32 fma chain over c = 0..r-1 in that order
+// (the same chain the err pass subtracts from p).  Streaming: 4 (decompress) or 8 (update) bytes of
+// HBM traffic per element against r fused multiply-adds.
+#ifndef UPD_PREFETCH
+#define UPD_PREFETCH false
+#endif
+namespace {
+
+constexpr int kUpdAPitch = kUpdRows + 4, kUpdBPitch = kUpdCols + 4;
+
+template <bool SUBTRACT, bool PREFETCH>
+__global__ __launch_bounds__(256) void k_update(DevicePlan dp, const float *__restrict__ Phat,
+                                                const float *__restrict__ Qn, float *x)
+{
+    __shared__ __attribute__((aligned(16))) float sa[32 * kUpdAPitch];      // [c][row of the tile]
+    __shared__ __attribute__((aligned(16))) float sb[32 * kUpdBPitch];      // [c][column of the tile]
+    const WorkItem it = dp.upd_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank, tid = threadIdx.x;
+    const int64_t row0 = (int64_t)it.a * kUpdRows, col0 = (int64_t)it.b * kUpdCols;
+    const int rows = (int)((d.n - row0 < kUpdRows) ? d.n - row0 : kUpdRows);
+    const int cols = (int)((d.m - col0 < kUpdCols) ? d.m - col0 : kUpdCols);
+    // rows 4 ty .. 4 ty + 3 of the tile; columns 4 tx .. 4 tx + 3 and 64 + 4 tx .. 64 + 4 tx + 3: the 16 threads
+    // of a row group then touch 256 contiguous bytes of a row per access
+    const int tx = tid & 15, ty = tid >> 4;
+    float *base = x + d.grad_off;
+    const bool vec = (d.m & 3) == 0;                 // rows start on 16-byte boundaries
+    // the parameters of the thread's block are fetched before the sums are formed, not after
+    float4 xv[4][2];
+    if (SUBTRACT && PREFETCH && vec) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int rr = 4 * ty + i, cc = 64 * h + 4 * tx;
+                xv[i][h] = (rr < rows && cc < cols) ? *reinterpret_cast<const float4 *>(base + (row0 + rr) * d.m + col0 + cc)
+                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+    }
+    // the tile's rows of a factor are contiguous in memory; rows beyond the matrix are zero
+    {
+        const float *src = Phat + d.p_off + row0 * r;
+        for (int e = tid; e < kUpdRows * r; e += 256) {
+            const int rr = e / r, c = e - rr * r;
+            sa[c * kUpdAPitch + rr] = rr < rows ? src[e] : 0.0f;
+        }
+        const float *srq = Qn + d.q_off + col0 * r;
+        for (int e = tid; e < kUpdCols * r; e += 256) {
+            const int cc = e / r, c = e - cc * r;
+            sb[c * kUpdBPitch + cc] = cc < cols ? srq[e] : 0.0f;
+        }
+    }
+    __syncthreads();
+    float acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.0f;
+#pragma unroll 2
+    for (int c = 0; c < r; ++c) {
+        const float4 a4 = *reinterpret_cast<const float4 *>(sa + c * kUpdAPitch + 4 * ty);
+        const float4 b0 = *reinterpret_cast<const float4 *>(sb + c * kUpdBPitch + 4 * tx);
+        const float4 b1 = *reinterpret_cast<const float4 *>(sb + c * kUpdBPitch + 64 + 4 * tx);
+        const float a[4] = {a4.x, a4.y, a4.z, a4.w};
+        const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int rr = 4 * ty + i;
+        if (rr >= rows) continue;
+        float *prow = base + (row0 + rr) * d.m + col0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int cc = 64 * h + 4 * tx;          // first of this thread's 4 columns of half h
+            if (vec) {
+                if (cc < cols) {                     // cols is a multiple of 4 here
+                    float4 v = make_float4(acc[i][4 * h], acc[i][4 * h + 1], acc[i][4 * h + 2], acc[i][4 * h + 3]);
+                    if (SUBTRACT) {
+                        const float4 o = PREFETCH ? xv[i][h] : *reinterpret_cast<const float4 *>(prow + cc);
+                        v = make_float4(o.x - v.x, o.y - v.y, o.z - v.z, o.w - v.w);
+                    }
+                    *reinterpret_cast<float4 *>(prow + cc) = v;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (cc + j < cols) prow[cc + j] = SUBTRACT ? prow[cc + j] - acc[i][4 * h + j] : acc[i][4 * h + j];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
+                         hipStream_t st)
+{
+    if (dp.n_upd > 0) {
+        if (subtract) hipLaunchKernelGGL((k_update<true, UPD_PREFETCH>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+        else hipLaunchKernelGGL((k_update<false, false>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out, hipStream_t st)
 {
     hipLaunchKernelGGL(k_decode, dim3(dp.n_elem), dim3(256), 0, st, dp, codes, scales, e_out);

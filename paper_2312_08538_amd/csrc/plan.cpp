@@ -173,6 +173,9 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             if (!(mf_q && d.n_q_tiles == 1))
                 for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
+            for (int64_t r0 = 0; r0 < d.n; r0 += kUpdRows)
+                for (int64_t c0 = 0; c0 < d.m; c0 += kUpdCols)
+                    plan.upd_items.push_back({l, (int32_t)(r0 / kUpdRows), (int32_t)(c0 / kUpdCols), 0});
         }
         // A workgroup of the MFMA P pass walks a whole row range, so its duration grows with the
         // number of columns: longest first, so that the last workgroups to start are the short ones.
@@ -254,6 +257,13 @@ bool check_plan(const Plan &plan)
             c.add(plan, it, it.b, it.c, (int64_t)it.a * strip, strip);
         }
         for (const WorkItem &it : plan.err_m_items) c.add(plan, it, it.a, kErrRows, (int64_t)it.b * 128, (int64_t)it.c * 128);
+        if (!c.complete(plan)) return false;
+    }
+    // decompression / update
+    {
+        Cover c(nm);
+        for (const WorkItem &it : plan.upd_items)
+            c.add(plan, it, (int64_t)it.a * kUpdRows, kUpdRows, (int64_t)it.b * kUpdCols, kUpdCols);
         if (!c.complete(plan)) return false;
     }
     // per-matrix helpers, and the workspace map

@@ -17,6 +17,8 @@ constexpr int kPTileRows = 64;      // rows per workgroup item of the octet P pa
 
 enum Path { kPathGeneric = 0, kPathOctet = 1, kPathMfma = 2 };
 constexpr int kMfmaRows = 128;      // rows per workgroup item of the MFMA P pass
+constexpr int kUpdRows = 64;        // tile of the decompress / update kernel
+constexpr int kUpdCols = 128;
 constexpr int kErrRows = 128;       // rows per workgroup item of the MFMA err pass (8 waves x 16)
 constexpr int kErrRun = 16;         // column blocks of 128 per item of the MFMA err pass (at most 16)
 
@@ -78,6 +80,7 @@ struct Plan {
     std::vector<WorkItem> apply_items;  // (mat, first row)                    64 rows per workgroup
     std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
     std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
+    std::vector<WorkItem> upd_items;    // decompress / update: (mat, row tile of 64, column tile of 128)
 };
 
 // Checks that the work tables of each of the three passes cover every element of every matrix exactly

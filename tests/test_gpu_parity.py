@@ -293,3 +293,73 @@ def test_step_replayed_from_a_hip_graph_equals_the_eager_step(env):
             for k in want:
                 assert torch.equal(b[k], want[k]), (name, replay, k)
         gpu.m.close()
+
+
+@pytest.mark.parametrize("rank", [1, 4, 8, 32])
+def test_decompress_and_update_match_the_oracle_bit_for_bit(env, rank):
+    """Algorithm 2 lines 7-8 through the C ABI: Delta = P^ Q+^T and x <- x - Delta, every entry the
+    fp32 fma chain over the rank in the oracle's order, on tiles that are full, ragged in rows, ragged
+    in columns, narrower than a tile, and on a width that is not a multiple of 4 (scalar path)."""
+    R, B, U = env
+    import torch
+
+    layout = [(200, 384), (64, 128), (130, 147), (33, 129), (70, 1000), (257, 64)]
+    layout = [(n, m) for n, m in layout if min(n, m) >= rank]
+    rng = np.random.default_rng(100 + rank)
+    model = B.Model(layout, rank, 4, 128, B.F32, 7)
+    buf = model.alloc("cuda:0")
+    params = torch.zeros(model.sizes["grad_elems"], dtype=torch.float32, device="cuda:0")
+    delta = torch.full((model.sizes["grad_elems"],), 123.0, dtype=torch.float32, device="cuda:0")
+    Ps, Qs, xs = [], [], []
+    for l, (n, m) in enumerate(layout):
+        P = rng.standard_normal((n, rank)).astype(np.float32)
+        Q = rng.standard_normal((m, rank)).astype(np.float32)
+        x = rng.standard_normal((n, m)).astype(np.float32)
+        o = model.offsets[l]
+        buf["P"][o["p_off"]:o["p_off"] + P.size] = torch.from_numpy(P.ravel()).cuda()
+        buf["Q"][o["q_off"]:o["q_off"] + Q.size] = torch.from_numpy(Q.ravel()).cuda()
+        params[o["grad_off"]:o["grad_off"] + x.size] = torch.from_numpy(x.ravel()).cuda()
+        Ps.append(P); Qs.append(Q); xs.append(x)
+    st = model.stream_handle()
+    B.conef_decompress(model.ctx, buf["P"], buf["Q"], delta, st)
+    B.conef_apply_update(model.ctx, buf["P"], buf["Q"], params, st)
+    torch.cuda.synchronize()
+    end = 0
+    for l, (n, m) in enumerate(layout):
+        o = model.offsets[l]["grad_off"]
+        want_d = R.decompress(Ps[l], Qs[l])
+        want_x = R.apply_update(xs[l], Ps[l], Qs[l])
+        got_d = delta[o:o + n * m].cpu().numpy().reshape(n, m)
+        got_x = params[o:o + n * m].cpu().numpy().reshape(n, m)
+        assert np.array_equal(got_d.view(np.uint32), want_d.view(np.uint32)), (rank, l, "delta")
+        assert np.array_equal(got_x.view(np.uint32), want_x.view(np.uint32)), (rank, l, "update")
+        # the padding between matrices is never written
+        assert torch.all(delta[end:o] == 123.0)
+        end = o + n * m
+    model.close()
+
+
+def test_update_after_a_step_removes_what_the_error_keeps(env):
+    """One full step, then the update with the step's own factors on x = p: what is left of p is what
+    the error compressor was given, so x - Delta = decode(e+) up to the quantiser's step (line 9)."""
+    R, B, U = env
+    import torch
+
+    w = wl.WORKLOADS["cnn"]
+    layout = [(128, 256)]
+    g = wl.host_gradient(w, 0, 0, shape=layout[0])
+    Q0 = wl.host_q0(w, 0, shape=layout[0])
+    gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, [Q0])
+    gpu.set_grads([g]); gpu.step(0)                                # e_0 = 0, so p = g
+    b = gpu.buf
+    x = b["grads"].clone()
+    B.conef_apply_update(gpu.m.ctx, b["P"], b["Q"], x, gpu.m.stream_handle())
+    e = torch.zeros_like(x)
+    B.conef_decode_error(gpu.m.ctx, b["codes"], b["scales"], e, gpu.m.stream_handle())
+    torch.cuda.synchronize()
+    n, m = layout[0]
+    left = x[:n * m].cpu().numpy()
+    kept = e[:n * m].cpu().numpy()
+    scales = np.repeat(gpu.mat_scales(0), w.block)[:n * m]
+    assert np.all(np.abs(left - kept) <= scales / R.levels(w.bits) * (1 + 1e-6))      # at most one level apart
+    assert np.max(np.abs(left)) > 0
