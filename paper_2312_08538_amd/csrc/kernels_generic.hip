@@ -385,14 +385,101 @@ __global__ __launch_bounds__(256) void k_update(DevicePlan dp, const float *__re
     }
 }
 
+// The same on the fp32 matrix cores, for ranks that are a multiple of 4 and larger than 8 (where the
+// vector ALU, not the memory, bounds the kernel above).  v_mfma_f32_16x16x4_f32 accumulates its four
+// products one after the other, each fused, in ascending k: chained over k = 0..r-1 it gives the bits
+// of the sequential fp32 fma chain (checked against the chain on random operands: no difference in
+// any entry, where an unfused or a wider accumulation differs in about half of them).
+//   operand layout: lane l holds A[l%16][l/16], B[l/16][l%16] and D[4(l/16) + v][l%16], v = 0..3.
+// One workgroup per 64 x 128 tile, wave w rows 16w..16w+15.  Tile t (0..7) of the matrix cores takes
+// column 8 cc + t of every octet cc = l % 16, so after eight tiles lane (cc, kg = l / 16) holds rows
+// 4 kg + v, columns 8 cc .. 8 cc + 7: two 16-byte accesses per row.  The block of Q+ is staged in LDS
+// in the order the lanes read it ([cc][kg][t][q], c = 4 q + kg), 16-byte reads.
+typedef float upd_f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool SUBTRACT>
+__global__ __launch_bounds__(256) void k_update_mfma(DevicePlan dp, const float *__restrict__ Phat,
+                                                     const float *__restrict__ Qn, float *x)
+{
+    constexpr int kLanePitch = 64 + 4;              // floats per lane's piece: the 16 lanes of a read pass fall on all banks
+    __shared__ __attribute__((aligned(16))) float sbq[64 * kLanePitch];      // [cc][kg] x ([t][q] + padding)
+    const WorkItem it = dp.upd_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank, nq = r >> 2, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row0 = (int64_t)it.a * kUpdRows, col0 = (int64_t)it.b * kUpdCols;
+    const int rows = (int)((d.n - row0 < kUpdRows) ? d.n - row0 : kUpdRows);
+    const int cols = (int)((d.m - col0 < kUpdCols) ? d.m - col0 : kUpdCols);
+    const int cc = lane & 15, kg = lane >> 4;
+    {
+        const float *srq = Qn + d.q_off + col0 * r;       // the block's rows of Q+ are contiguous
+        for (int e = tid; e < kUpdCols * r; e += 256) {
+            const int col = e / r, c = e - col * r;
+            sbq[((col >> 3) * 4 + (c & 3)) * kLanePitch + (col & 7) * 8 + (c >> 2)] = col < cols ? srq[e] : 0.0f;
+        }
+    }
+    // A operand: P^[row 16 w + l % 16][4 q + l / 16], q = 0..r/4-1 (rows beyond the matrix: zero)
+    float a[8];
+    {
+        const int rr = 16 * wave + cc;
+        const float *pr = Phat + d.p_off + (row0 + (rr < rows ? rr : 0)) * r + kg;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] = (q < nq && rr < rows) ? pr[4 * q] : 0.0f;
+    }
+    __syncthreads();
+    upd_f32x4 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        acc[t] = upd_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        const float4 b0 = *reinterpret_cast<const float4 *>(sbq + (cc * 4 + kg) * kLanePitch + t * 8);
+        const float4 b1 = *reinterpret_cast<const float4 *>(sbq + (cc * 4 + kg) * kLanePitch + t * 8 + 4);
+        const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (q < nq) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], b[q], acc[t], 0, 0, 0);     // uniform
+    }
+    float *base = x + d.grad_off;
+    const bool vec = (d.m & 3) == 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int rr = 16 * wave + 4 * kg + v;
+        if (rr >= rows) continue;
+        float *prow = base + (row0 + rr) * d.m + col0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int c0 = 8 * cc + 4 * h;
+            const float dl[4] = {acc[4 * h][v], acc[4 * h + 1][v], acc[4 * h + 2][v], acc[4 * h + 3][v]};
+            if (vec) {
+                if (c0 < cols) {
+                    float4 o = make_float4(dl[0], dl[1], dl[2], dl[3]);
+                    if (SUBTRACT) {
+                        const float4 xo = *reinterpret_cast<const float4 *>(prow + c0);
+                        o = make_float4(xo.x - dl[0], xo.y - dl[1], xo.z - dl[2], xo.w - dl[3]);
+                    }
+                    *reinterpret_cast<float4 *>(prow + c0) = o;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (c0 + j < cols) prow[c0 + j] = SUBTRACT ? prow[c0 + j] - dl[j] : dl[j];
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st)
 {
     if (dp.n_upd > 0) {
-        if (subtract) hipLaunchKernelGGL((k_update<true, UPD_PREFETCH>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
-        else hipLaunchKernelGGL((k_update<false, false>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+        const bool cores = dp.rank > 8 && (dp.rank & 3) == 0;
+        if (cores) {
+            if (subtract) hipLaunchKernelGGL(k_update_mfma<true>, dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+            else hipLaunchKernelGGL(k_update_mfma<false>, dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+        } else {
+            if (subtract) hipLaunchKernelGGL((k_update<true, UPD_PREFETCH>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+            else hipLaunchKernelGGL((k_update<false, false>), dim3(dp.n_upd), dim3(256), 0, st, dp, Phat, Qn, x);
+        }
     }
     return hipGetLastError();
 }

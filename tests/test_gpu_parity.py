@@ -295,11 +295,12 @@ def test_step_replayed_from_a_hip_graph_equals_the_eager_step(env):
         gpu.m.close()
 
 
-@pytest.mark.parametrize("rank", [1, 4, 8, 32])
+@pytest.mark.parametrize("rank", [1, 4, 8, 12, 16, 30, 32])
 def test_decompress_and_update_match_the_oracle_bit_for_bit(env, rank):
     """Algorithm 2 lines 7-8 through the C ABI: Delta = P^ Q+^T and x <- x - Delta, every entry the
     fp32 fma chain over the rank in the oracle's order, on tiles that are full, ragged in rows, ragged
-    in columns, narrower than a tile, and on a width that is not a multiple of 4 (scalar path)."""
+    in columns, narrower than a tile, and on a width that is not a multiple of 4 (scalar path).  Ranks
+    above 8 that are a multiple of 4 run on the fp32 matrix cores, the others on the vector ALU."""
     R, B, U = env
     import torch
 
