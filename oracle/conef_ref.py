@@ -18,6 +18,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conef_ref.c")
+_SRC_SKETCH = os.path.join(_HERE, "sketch_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -26,9 +27,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_SKETCH))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -39,8 +41,7 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB):
-            build()
+        build()
         L = ctypes.CDLL(_LIB)
         vp, i64, i32, u64, u32 = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint64,
                                   ctypes.c_uint32)
@@ -73,6 +74,21 @@ def lib() -> ctypes.CDLL:
         L.ref_step_matrix.restype = None
         L.ref_step_matrix_efsgd.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, vp]
         L.ref_step_matrix_efsgd.restype = None
+        f32 = ctypes.c_float
+        L.ref_f16_to_f32.argtypes = [ctypes.c_uint16]
+        L.ref_f16_to_f32.restype = f32
+        L.ref_f32_to_f16.argtypes = [f32]
+        L.ref_f32_to_f16.restype = ctypes.c_uint16
+        L.ref_cs_hash.argtypes = [u64, u32, i64, i64, vp, vp]
+        L.ref_cs_hash.restype = None
+        L.ref_cs_decode.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+        L.ref_cs_decode.restype = None
+        L.ref_cs_form_p.argtypes = [vp, i32, vp, i32, i64, i64, vp, vp, f32, vp]
+        L.ref_cs_form_p.restype = None
+        L.ref_cs_update.argtypes = [vp, i64, i64, vp, vp, i64, f32, vp, i32]
+        L.ref_cs_update.restype = None
+        L.ref_cs_step_matrix.argtypes = [vp, i32, i64, i64, i32, i64, f32, u64, u32, vp, i32, vp, vp, vp, vp]
+        L.ref_cs_step_matrix.restype = None
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -256,4 +272,90 @@ def step_matrix_efsgd(g, e, Q):
     Qn = np.empty((m, r), np.float32)
     work = np.empty(n * m, np.float32)
     lib().ref_step_matrix_efsgd(_p(ga), n, m, r, _p(e), _p(Qa), _p(P), _p(Qn), _p(work))
+    return P, Qn
+
+
+# ---------------------------------------------------------------- count sketch (oracle/sketch_ref.c)
+TABLE_F32, TABLE_F16 = 0, 1
+
+
+def f32_to_f16(x: float) -> int:
+    return int(lib().ref_f32_to_f16(float(np.float32(x))))
+
+
+def f16_to_f32(h: int) -> float:
+    return float(lib().ref_f16_to_f32(int(h)))
+
+
+def table_array(table: np.ndarray):
+    """Returns (contiguous array, type tag).  fp16 tables travel as uint16 bit patterns."""
+    if table.dtype == np.float32:
+        return np.ascontiguousarray(table), TABLE_F32
+    if table.dtype == np.uint16:
+        return np.ascontiguousarray(table), TABLE_F16
+    raise TypeError("table must be float32 or uint16 (fp16 bits)")
+
+
+def cs_hash(seed: int, mat: int, n: int, w: int):
+    """Bucket (0..w-1) and sign (+1/-1) of every row of matrix `mat` (Section 4.2.2, row tensor trick)."""
+    bucket, sign = np.empty(n, np.int32), np.empty(n, np.int8)
+    lib().ref_cs_hash(seed, mat, n, w, _p(bucket), _p(sign))
+    return bucket, sign
+
+
+def cs_decode(table, bucket, sign, n: int) -> np.ndarray:
+    ta, tt = table_array(table)
+    m = ta.shape[1]
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    e = np.empty((n, m), np.float32)
+    lib().ref_cs_decode(_p(ta), tt, n, m, _p(b), _p(s), _p(e))
+    return e
+
+
+def cs_form_p(g, table, bucket, sign, beta: float) -> np.ndarray:
+    ga, dt = grad_array(g)
+    ta, tt = table_array(table)
+    n, m = g.shape
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    p = np.empty((n, m), np.float32)
+    lib().ref_cs_form_p(_p(ga), dt, _p(ta), tt, n, m, _p(b), _p(s), beta, _p(p))
+    return p
+
+
+def cs_update(x, bucket, sign, beta: float, table) -> None:
+    """table <- beta * table + sketch(x), in place (Algorithm 4 line 9 by linearity)."""
+    xa = _c(x, np.float32)
+    n, m = xa.shape
+    assert table.flags.c_contiguous and table.shape[1] == m
+    _, tt = table_array(table)
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    lib().ref_cs_update(_p(xa), n, m, _p(b), _p(s), table.shape[0], beta, _p(table), tt)
+
+
+@dataclass
+class SketchState:
+    """Per-matrix persistent state of ConEF-CS: the w x m table and the warm-started Q."""
+    n: int
+    m: int
+    table: np.ndarray
+    Q: np.ndarray
+
+    @staticmethod
+    def fresh(n: int, m: int, w: int, fp16: bool, Q0: np.ndarray) -> "SketchState":
+        return SketchState(n, m, np.zeros((w, m), np.uint16 if fp16 else np.float32),
+                           np.array(Q0, np.float32, order="C", copy=True))
+
+
+def cs_step_matrix(g, st: SketchState, rank: int, beta: float, seed: int, mat: int):
+    """Runs one partial-ConEF step with the count sketch on one matrix; updates `st`; returns (Phat, Qn)."""
+    ga, dt = grad_array(g)
+    n, m = st.n, st.m
+    assert ga.size == n * m and st.Q.shape == (m, rank) and st.table.flags.c_contiguous
+    _, tt = table_array(st.table)
+    P = np.empty((n, rank), np.float32)
+    Qn = np.empty((m, rank), np.float32)
+    work = np.empty(2 * n * m, np.float32)
+    lib().ref_cs_step_matrix(_p(ga), dt, n, m, rank, st.table.shape[0], beta, seed, mat,
+                             _p(st.table), tt, _p(st.Q), _p(P), _p(Qn), _p(work))
+    st.Q = Qn
     return P, Qn
