@@ -119,6 +119,49 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
 int conef_decompress(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *delta_out, void *hip_stream);
 int conef_apply_update(conef_ctx *ctx, const float *P_hat, const float *Q_new, float *params, void *hip_stream);
 
+/* ---- Count sketch as the error compressor (Section 4.2.2) with the partial update (Section 4.3,
+ * Algorithm 4).  A context made by conef_cs_init keeps, instead of codes and scales, one table per
+ * matrix: sketch_rows x cols entries (fp32 or fp16), row-major, at table_off of a flat table buffer.
+ * It is the v = 1 sketch recommended in Section 5.1 in its row form (Section 5.3, "tensor trick":
+ * a whole row of the rows x cols view is one entry of the sketched vector, so there is one hash
+ * per row): row i of matrix l has a bucket h(i) in [0, sketch_rows) and a sign s(i), and
+ *   estimate of the error   e[i, :] = s(i) * table[h(i), :]
+ *   Algorithm 4 line 5      p = fma(1 - beta, e, g)              (g already scaled by eta)
+ *   line 6                  P = p Q_state ; P^ = orthonormalise(P) ; Q+ = p^T P^   (as in conef_step)
+ *   line 9, by linearity    table[b, :] <- fma(beta, table[b, :], sum over rows i of bucket b,
+ *                                              ascending, of s(i) * (p - P^ Q+^T)[i, :])
+ * in fp32, rounded once to the table's type (nearest even).  beta = 0 is Algorithm 2 with the count
+ * sketch.  An all-zero table is e_0 = 0.
+ * Hash: one Philox4x32-10 call per row, counter (i, l, 0xFFFFFFFF, 0xFFFFFFFF), key (lo32(seed),
+ * hi32(seed)); bucket = floor(out[0] * sketch_rows / 2^32), sign = -1 if out[1] is odd.  It is fixed
+ * for the life of the context; conef_cs_hash returns it.
+ *   sketch_rows[n_mats]  table rows per matrix, 1 <= sketch_rows[l] <= rows[l]
+ *   beta                 share of the error kept back, 0 <= beta < 1
+ *   table_dtype          CONEF_TABLE_F32 or CONEF_TABLE_F16
+ * conef_sizes / conef_offsets give the gradient, P, Q and workspace sizes and offsets as before (its
+ * code and scale sizes are 0); conef_orthonormalise, conef_decompress, conef_apply_update, the timing
+ * calls and conef_check_plan work on either kind of context.  The quantiser's calls return
+ * CONEF_ESTATE on a count-sketch context and the conef_cs_* calls on a quantiser context.
+ * Pointers, alignment (16 bytes for grads, table, factors; 256 for the workspace), asynchrony and
+ * errors are as for conef_step; the table is updated in place. */
+enum { CONEF_TABLE_F32 = 0, CONEF_TABLE_F16 = 1 };
+int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
+                  float beta, int table_dtype, int grad_dtype, uint64_t seed);
+int conef_cs_sizes(const conef_ctx *ctx, size_t *table_elems);                 /* elements of the flat table buffer */
+int conef_cs_offsets(const conef_ctx *ctx, int mat, size_t *table_off, int64_t *sketch_rows);
+/* bucket_out[rows], sign_out[rows] (+1 / -1): host arrays owned by the caller. */
+int conef_cs_hash(const conef_ctx *ctx, int mat, int32_t *bucket_out, int8_t *sign_out);
+int conef_cs_step(conef_ctx *ctx, const void *grads, void *table, const float *Q_state, float *P_out,
+                  float *Q_out, void *workspace, void *hip_stream);
+int conef_cs_step_p(conef_ctx *ctx, const void *grads, const void *table, const float *Q_state,
+                    float *P_raw_out, void *workspace, void *hip_stream);        /* P = p * Q_state      */
+int conef_cs_step_q(conef_ctx *ctx, const void *grads, const void *table, const float *P_hat,
+                    float *Q_out, void *workspace, void *hip_stream);            /* Q+ = p^T * P^        */
+int conef_cs_step_err(conef_ctx *ctx, const void *grads, void *table, const float *P_hat,
+                      const float *Q_new, void *workspace, void *hip_stream);    /* table <- line 9      */
+/* e_out (fp32, laid out like an fp32 gradient buffer) <- the estimate of the error.  For tests and export. */
+int conef_cs_decode_error(conef_ctx *ctx, const void *table, float *e_out, void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

@@ -13,13 +13,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libconef.so")
 
 F32, BF16 = 0, 1
+TABLE_F32, TABLE_F16 = 0, 1
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
 
 EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_p",
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
            "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
            "conef_apply_update", "conef_destroy",
-           "conef_strerror"]
+           "conef_strerror",
+           "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
+           "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
 
 class conef_mat(ctypes.Structure):
@@ -55,6 +58,16 @@ def lib() -> ctypes.CDLL:
     L.conef_check_plan.argtypes = [vp]
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
     L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
+    L.conef_cs_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), ctypes.POINTER(ctypes.c_int64), i32, i32,
+                                ctypes.c_float, i32, i32, u64]
+    L.conef_cs_sizes.argtypes = [vp, szp]
+    L.conef_cs_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_cs_hash.argtypes = [vp, i32, vp, vp]
+    L.conef_cs_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.conef_cs_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.conef_cs_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.conef_cs_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.conef_cs_decode_error.argtypes = [vp, vp, vp, vp]
     L.conef_destroy.argtypes = [vp]
     L.conef_destroy.restype = None
     L.conef_strerror.argtypes = [i32]
@@ -157,6 +170,64 @@ def conef_apply_update(ctx, P_hat, Q_new, params, stream=0):
     _check(lib().conef_apply_update(ctx, _ptr(P_hat), _ptr(Q_new), _ptr(params), stream), "conef_apply_update")
 
 
+# count-sketch mode
+def conef_cs_init(layout: Sequence[Tuple[int, int]], sketch_rows: Sequence[int], rank: int, beta: float,
+                  table_dtype: int, grad_dtype: int, seed: int):
+    arr = (conef_mat * max(1, len(layout)))()
+    for i, (n, m) in enumerate(layout):
+        arr[i].rows, arr[i].cols = n, m
+    w = (ctypes.c_int64 * max(1, len(sketch_rows)))(*[int(x) for x in sketch_rows])
+    ctx = ctypes.c_void_p()
+    _check(lib().conef_cs_init(ctypes.byref(ctx), arr, w, len(layout), rank, beta, table_dtype, grad_dtype, seed),
+           "conef_cs_init")
+    return ctx
+
+
+def conef_cs_sizes(ctx) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_cs_sizes(ctx, ctypes.byref(v)), "conef_cs_sizes")
+    return {"table_elems": int(v.value)}
+
+
+def conef_cs_offsets(ctx, mat: int) -> dict:
+    off, w = ctypes.c_size_t(), ctypes.c_int64()
+    _check(lib().conef_cs_offsets(ctx, mat, ctypes.byref(off), ctypes.byref(w)), "conef_cs_offsets")
+    return {"table_off": int(off.value), "sketch_rows": int(w.value)}
+
+
+def conef_cs_hash(ctx, mat: int, rows: int):
+    """(bucket int32[rows], sign int8[rows]) of the rows of matrix `mat`."""
+    import numpy as np
+
+    bucket, sign = np.empty(rows, np.int32), np.empty(rows, np.int8)
+    _check(lib().conef_cs_hash(ctx, mat, bucket.ctypes.data, sign.ctypes.data), "conef_cs_hash")
+    return bucket, sign
+
+
+def conef_cs_step(ctx, grads, table, Q_state, P_out, Q_out, workspace, stream=0):
+    _check(lib().conef_cs_step(ctx, _ptr(grads), _ptr(table), _ptr(Q_state), _ptr(P_out), _ptr(Q_out),
+                               _ptr(workspace), stream), "conef_cs_step")
+
+
+def conef_cs_step_p(ctx, grads, table, Q_state, P_raw_out, workspace, stream=0):
+    _check(lib().conef_cs_step_p(ctx, _ptr(grads), _ptr(table), _ptr(Q_state), _ptr(P_raw_out), _ptr(workspace),
+                                 stream), "conef_cs_step_p")
+
+
+def conef_cs_step_q(ctx, grads, table, P_hat, Q_out, workspace, stream=0):
+    _check(lib().conef_cs_step_q(ctx, _ptr(grads), _ptr(table), _ptr(P_hat), _ptr(Q_out), _ptr(workspace), stream),
+           "conef_cs_step_q")
+
+
+def conef_cs_step_err(ctx, grads, table, P_hat, Q_new, workspace, stream=0):
+    _check(lib().conef_cs_step_err(ctx, _ptr(grads), _ptr(table), _ptr(P_hat), _ptr(Q_new), _ptr(workspace), stream),
+           "conef_cs_step_err")
+
+
+def conef_cs_decode_error(ctx, table, e_out, stream=0):
+    _check(lib().conef_cs_decode_error(ctx, _ptr(table), _ptr(e_out), stream), "conef_cs_decode_error")
+
+
 def conef_set_timing(ctx, on: bool):
     _check(lib().conef_set_timing(ctx, 1 if on else 0), "conef_set_timing")
 
@@ -217,3 +288,46 @@ class Model:
     def step(self, buf, step: int, Q_out=None):
         conef_step(self.ctx, buf["grads"], buf["codes"], buf["scales"], buf["Q"], buf["P"],
                    buf["Q"] if Q_out is None else Q_out, buf["ws"], step, self.stream_handle())
+
+
+class SketchModel:
+    """One count-sketch context plus its sizes and per-matrix offsets (see Model)."""
+
+    def __init__(self, layout, sketch_rows, rank, beta, table_dtype, grad_dtype, seed):
+        self.layout = [tuple(x) for x in layout]
+        self.sketch_rows = [int(x) for x in sketch_rows]
+        self.rank, self.beta, self.table_dtype, self.grad_dtype, self.seed = rank, beta, table_dtype, grad_dtype, seed
+        self.ctx = conef_cs_init(self.layout, self.sketch_rows, rank, beta, table_dtype, grad_dtype, seed)
+        self.sizes = conef_sizes(self.ctx)
+        self.sizes.update(conef_cs_sizes(self.ctx))
+        self.offsets = [dict(conef_offsets(self.ctx, l), **conef_cs_offsets(self.ctx, l))
+                        for l in range(len(self.layout))]
+
+    def close(self):
+        if self.ctx is not None:
+            conef_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def alloc(self, device="cuda:0"):
+        import torch
+
+        s = self.sizes
+        gdt = torch.float32 if self.grad_dtype == F32 else torch.bfloat16
+        tdt = torch.float32 if self.table_dtype == TABLE_F32 else torch.float16
+        return {
+            "grads": torch.zeros(s["grad_elems"], dtype=gdt, device=device),
+            "table": torch.zeros(s["table_elems"], dtype=tdt, device=device),
+            "Q": torch.zeros(s["q_elems"], dtype=torch.float32, device=device),
+            "P": torch.zeros(s["p_elems"], dtype=torch.float32, device=device),
+            "ws": torch.zeros(max(256, s["workspace_bytes"]), dtype=torch.uint8, device=device),
+        }
+
+    def step(self, buf, Q_out=None):
+        conef_cs_step(self.ctx, buf["grads"], buf["table"], buf["Q"], buf["P"],
+                      buf["Q"] if Q_out is None else Q_out, buf["ws"], Model.stream_handle())

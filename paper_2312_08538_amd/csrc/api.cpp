@@ -2,6 +2,8 @@
 // and the sequence of grouped launches that makes one step.
 #include <hip/hip_runtime.h>
 
+#include <climits>
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -66,6 +68,14 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.apply_items, &d.apply_items))) return rc;
     if ((rc = upload(ctx, pl.qred_items, &d.qred_items))) return rc;
     if ((rc = upload(ctx, pl.elem_items, &d.elem_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_err_items, &d.cs_err_items))) return rc;
+    if ((rc = upload(ctx, pl.row_hash, &d.row_hash))) return rc;
+    if ((rc = upload(ctx, pl.bucket_ptr, &d.bucket_ptr))) return rc;
+    if ((rc = upload(ctx, pl.bucket_rows, &d.bucket_rows))) return rc;
+    d.n_cs_err = (int)pl.cs_err_items.size();
+    d.table_dtype = pl.table_dtype;
+    d.beta = pl.beta;
+    d.omb = 1.0f - pl.beta;
     d.n_mats = (int)pl.mats.size();
     d.n_p = (int)pl.p_items.size();
     d.n_q = (int)pl.q_items.size();
@@ -136,6 +146,58 @@ int conef_init(conef_ctx **out, const conef_mat *layout, int n_mats, int rank, i
     return CONEF_OK;
 }
 
+int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
+                  float beta, int table_dtype, int grad_dtype, uint64_t seed)
+{
+    if (!out) return CONEF_EINVAL;
+    *out = nullptr;
+    if (!layout || !sketch_rows || n_mats < 1) return CONEF_EINVAL;
+    conef_ctx *ctx = new (std::nothrow) conef_ctx();
+    if (!ctx) return CONEF_ENOMEM;
+    int rc = CONEF_OK;
+    try {
+        std::vector<int64_t> rows(n_mats), cols(n_mats);
+        for (int l = 0; l < n_mats; ++l) { rows[l] = layout[l].rows; cols[l] = layout[l].cols; }
+        rc = make_sketch_plan(ctx->plan, rows.data(), cols.data(), sketch_rows, n_mats, rank, beta, table_dtype,
+                              grad_dtype, seed);
+    } catch (const std::bad_alloc &) {
+        rc = CONEF_ENOMEM;
+    }
+    if (rc != CONEF_OK) { delete ctx; return rc; }
+    *out = ctx;
+    return CONEF_OK;
+}
+
+int conef_cs_sizes(const conef_ctx *ctx, size_t *table_elems)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (table_elems) *table_elems = ctx->plan.table_elems;
+    return CONEF_OK;
+}
+
+int conef_cs_offsets(const conef_ctx *ctx, int mat, size_t *table_off, int64_t *sketch_rows)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (table_off) *table_off = (size_t)ctx->plan.mats[mat].table_off;
+    if (sketch_rows) *sketch_rows = ctx->plan.mats[mat].w;
+    return CONEF_OK;
+}
+
+int conef_cs_hash(const conef_ctx *ctx, int mat, int32_t *bucket_out, int8_t *sign_out)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size() || !bucket_out || !sign_out) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    const MatDesc &d = ctx->plan.mats[mat];
+    for (int64_t i = 0; i < d.n; ++i) {
+        const int32_t hv = ctx->plan.row_hash[(size_t)(d.hash_off + i)];
+        bucket_out[i] = hv & INT32_MAX;
+        sign_out[i] = hv < 0 ? -1 : 1;
+    }
+    return CONEF_OK;
+}
+
 int conef_check_plan(const conef_ctx *ctx)
 {
     if (!ctx) return CONEF_EINVAL;
@@ -172,6 +234,7 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
                  const float *Q_state, float *P_raw_out, void *workspace, void *hip_stream)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !Q_state || !P_raw_out || !workspace) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(Q_state, 16) ||
         misaligned(P_raw_out, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
@@ -216,6 +279,7 @@ int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, co
                 const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
         misaligned(Q_out, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
@@ -230,6 +294,7 @@ int step_err_impl(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
                   const float *Q_new, void *workspace, uint64_t step, void *hip_stream, bool splits_ready)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_new || !workspace) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(P_hat, 16) ||
         misaligned(Q_new, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
@@ -265,6 +330,7 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
 int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream)
 {
     if (!ctx || !err_codes || !err_scales) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
     if (misaligned(err_codes, 4) || misaligned(err_scales, 4)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
@@ -276,10 +342,77 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
                        void *hip_stream)
 {
     if (!ctx || !err_codes || !err_scales || !e_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
     if (misaligned(err_codes, 4) || misaligned(err_scales, 4) || misaligned(e_out, 4)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     return hip_rc(launch_decode(ctx->dev, err_codes, err_scales, e_out, static_cast<hipStream_t>(hip_stream)));
+}
+
+// ---------------------------------------------------------------- count-sketch mode
+int conef_cs_step_p(conef_ctx *ctx, const void *grads, const void *table, const float *Q_state, float *P_raw_out,
+                    void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !Q_state || !P_raw_out || !workspace) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(Q_state, 16) || misaligned(P_raw_out, 16) ||
+        misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_cs_pass_p(ctx->dev, grads, table, Q_state, P_raw_out, ws_doubles(ctx, workspace),
+                                   static_cast<hipStream_t>(hip_stream), stage_span(ctx, 0)));
+}
+
+int conef_cs_step_q(conef_ctx *ctx, const void *grads, const void *table, const float *P_hat, float *Q_out,
+                    void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(P_hat, 16) || misaligned(Q_out, 16) ||
+        misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_cs_pass_q(ctx->dev, grads, table, P_hat, Q_out, ws_doubles(ctx, workspace),
+                                   static_cast<hipStream_t>(hip_stream), stage_span(ctx, 2)));
+}
+
+int conef_cs_step_err(conef_ctx *ctx, const void *grads, void *table, const float *P_hat, const float *Q_new,
+                      void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !P_hat || !Q_new || !workspace) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(P_hat, 16) || misaligned(Q_new, 16) ||
+        misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_cs_pass_err(ctx->dev, grads, table, P_hat, Q_new, static_cast<hipStream_t>(hip_stream),
+                                     stage_span(ctx, 3)));
+}
+
+int conef_cs_step(conef_ctx *ctx, const void *grads, void *table, const float *Q_state, float *P_out, float *Q_out,
+                  void *workspace, void *hip_stream)
+{
+    int rc;
+    if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
+    if ((rc = conef_cs_step_p(ctx, grads, table, Q_state, P_out, workspace, hip_stream))) return rc;
+    /* exchange point 1: mean of P over the workers -- identity for one worker */
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = conef_cs_step_q(ctx, grads, table, P_out, Q_out, workspace, hip_stream))) return rc;
+    /* exchange point 2: mean of Q over the workers -- identity for one worker */
+    return conef_cs_step_err(ctx, grads, table, P_out, Q_out, workspace, hip_stream);
+}
+
+int conef_cs_decode_error(conef_ctx *ctx, const void *table, float *e_out, void *hip_stream)
+{
+    if (!ctx || !table || !e_out) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(table, 4) || misaligned(e_out, 4)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_cs_decode(ctx->dev, table, e_out, static_cast<hipStream_t>(hip_stream)));
 }
 
 namespace {

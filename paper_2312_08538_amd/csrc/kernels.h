@@ -14,6 +14,12 @@ struct DevicePlan {
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *upd_items = nullptr;                                                   // decompress / update
+    // count-sketch mode
+    const WorkItem *cs_err_items = nullptr;
+    const int32_t *row_hash = nullptr, *bucket_ptr = nullptr, *bucket_rows = nullptr;
+    int n_cs_err = 0;
+    int table_dtype = 0;            // 0 fp32, 1 fp16
+    float beta = 0.0f, omb = 1.0f;  // beta and fl32(1 - beta)
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
                    *elem_items = nullptr;
     int n_mats = 0;
@@ -44,6 +50,14 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
                            hipStream_t st, Span span = Span());
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
+// Count-sketch mode: the same three passes with a table as the error state.
+hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P,
+                            double *ws, hipStream_t st, Span span = Span());
+hipError_t launch_cs_pass_q(const DevicePlan &dp, const void *grads, const void *table, const float *Phat, float *Qout,
+                            double *ws, hipStream_t st, Span span = Span());
+hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *table, const float *Phat, const float *Qn,
+                              hipStream_t st, Span span = Span());
+hipError_t launch_cs_decode(const DevicePlan &dp, const void *table, float *e_out, hipStream_t st);
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);
 hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, size_t n_words, size_t n_scales,
@@ -54,6 +68,7 @@ void generic_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *cod
                     const float *Q, float *P, hipStream_t st);
 void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                     const float *Phat, double *ws, hipStream_t st);
+void generic_q_reduce(const DevicePlan &dp, double *ws, float *Qout, hipStream_t st);   // adds the row-tile partials of Q+
 void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                       const float *Qn, uint64_t step, hipStream_t st);
 void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,

@@ -229,6 +229,12 @@ void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *cod
         CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws);
 }
 
+void generic_q_reduce(const DevicePlan &dp, double *ws, float *Qout, hipStream_t st)
+{
+    if (dp.n_qred > 0)
+        hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, ws, Qout);
+}
+
 void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                       const float *Qn, uint64_t step, hipStream_t st)
 {
@@ -262,8 +268,7 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
     generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);
     // the reduction also writes the matrix-core family's operand splits of Q+
-    if (dp.n_qred > 0)
-        hipLaunchKernelGGL(k_q_reduce, dim3(dp.n_qred), dim3(256), 0, st, dp, (const double *)ws, ws, Qout);
+    generic_q_reduce(dp, ws, Qout, st);
     return hipGetLastError();
 }
 

@@ -1,6 +1,8 @@
 #include "plan.h"
 
 #include <array>
+#include <climits>
+#include <cstdint>
 #include <utility>
 
 #include <algorithm>
@@ -18,8 +20,90 @@ inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 inline int log2i(int64_t v) { int s = 0; while ((int64_t(1) << s) < v) ++s; return s; }
 }  // namespace
 
+namespace {
+int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
+                   int dtype, uint64_t seed, bool sketch);
+}
+
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,
               int block, int dtype, uint64_t seed)
+{
+    return make_plan_impl(plan, rows, cols, n_mats, rank, bits, block, dtype, seed, false);
+}
+
+void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative)
+{
+    // Philox4x32-10 (Salmon et al., SC'11), counter (row, matrix, ~0, ~0): the counter of a step no run reaches
+    uint32_t c0 = row, c1 = mat, c2 = 0xFFFFFFFFu, c3 = 0xFFFFFFFFu;
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    *bucket = (int32_t)(((uint64_t)c0 * (uint64_t)w) >> 32);
+    *negative = (c1 & 1u) != 0;
+}
+
+int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
+                     int rank, float beta, int table_dtype, int dtype, uint64_t seed)
+{
+    if (!sketch_rows || !(beta >= 0.0f && beta < 1.0f) || (table_dtype != 0 && table_dtype != 1)) return kEinval;
+    if (!rows || n_mats < 1) return kEinval;
+    for (int l = 0; l < n_mats; ++l)
+        if (sketch_rows[l] < 1 || sketch_rows[l] > rows[l]) return kEinval;
+    // the quantiser's parameters are not used in this mode; any valid pair will do
+    int rc = make_plan_impl(plan, rows, cols, n_mats, rank, 8, 4, dtype, seed, true);
+    if (rc != kOk) return rc;
+    try {
+        plan.sketch = true; plan.beta = beta; plan.table_dtype = table_dtype;
+        plan.code_words = 0; plan.n_scales = 0;
+        int64_t t = 0, h = 0, bp = 0;
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            d.w = sketch_rows[l];
+            d.table_off = t; t += round_up(d.w * d.m, kAlign);
+            d.hash_off = h;  h += d.n;
+            d.bptr_off = bp; bp += d.w + 1;
+        }
+        plan.table_elems = (size_t)t;
+        plan.row_hash.assign((size_t)h, 0);
+        plan.bucket_rows.assign((size_t)h, 0);
+        plan.bucket_ptr.assign((size_t)bp, 0);
+        for (int l = 0; l < n_mats; ++l) {
+            const MatDesc &d = plan.mats[l];
+            int32_t *ptr = plan.bucket_ptr.data() + d.bptr_off;
+            for (int64_t i = 0; i < d.n; ++i) {
+                int32_t b; bool neg;
+                sketch_hash(seed, (uint32_t)l, (uint32_t)i, d.w, &b, &neg);
+                plan.row_hash[(size_t)(d.hash_off + i)] = b | (neg ? INT32_MIN : 0);
+                ptr[b + 1] += 1;
+            }
+            for (int64_t b = 0; b < d.w; ++b) ptr[b + 1] += ptr[b];
+            // rows in ascending order within each bucket (a counting sort keeps the order of arrival)
+            std::vector<int32_t> fill(ptr, ptr + d.w);
+            for (int64_t i = 0; i < d.n; ++i) {
+                const int32_t hv = plan.row_hash[(size_t)(d.hash_off + i)];
+                const int32_t b = hv & INT32_MAX;
+                plan.bucket_rows[(size_t)(d.hash_off + fill[b]++)] = (int32_t)i | (hv & INT32_MIN);
+            }
+            // buckets per item: about 16 rows of the matrix each
+            const int64_t nb = std::max<int64_t>(1, std::min<int64_t>(64, 16 * d.w / d.n));
+            const int32_t nct = (int32_t)ceil_div(d.m, kCsCols);
+            for (int64_t b0 = 0; b0 < d.w; b0 += nb)
+                for (int32_t ct = 0; ct < nct; ++ct)
+                    plan.cs_err_items.push_back({l, (int32_t)b0, (int32_t)std::min<int64_t>(nb, d.w - b0), ct});
+        }
+    } catch (const std::bad_alloc &) {
+        return kEnomem;
+    }
+    return kOk;
+}
+
+namespace {
+int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
+                   int dtype, uint64_t seed, bool sketch)
 {
     if (!rows || !cols || n_mats < 1) return kEinval;
     if (rank < 1 || rank > kMaxRank) return kEinval;
@@ -66,7 +150,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
             d.scale_off = s; s += round_up(d.nblk, kAlign);
             d.p_off = p;     p += round_up(d.n * rank, kAlign);
             d.q_off = q;     q += round_up(d.m * rank, kAlign);
-            d.path = (block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 64 == 0 && d.m % block == 0) ? kPathOctet
+            d.path = (!sketch && block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 64 == 0 && d.m % block == 0) ? kPathOctet
                                                                                              : kPathGeneric;
             d.m8 = (int32_t)(d.m / 8);
             d.lb_shift = block_ok ? log2i(block / 8) : 0;
@@ -78,7 +162,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                 d.lr_shift = log2i(lr);
             }
             // MFMA family: dense rank-32 contractions on the matrix cores
-            if (rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0 && d.m <= (1 << 24)) d.path = kPathMfma;
+            if (!sketch && rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0 && d.m <= (1 << 24)) d.path = kPathMfma;
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
@@ -145,7 +229,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
                         for (int32_t ct = 0; ct < nct; ++ct) plan.q_items.push_back({l, ct, rt, 0});
                 // 4 waves per workgroup, each wave takes blocks b0+wave, b0+wave+4, ...: 16 per wave, or
                 // one per wave for small matrices (a: first block, b: blocks per wave)
-                if (!mf_e) {
+                if (!mf_e && !sketch) {
                     const int32_t per_wave = d.nblk <= 16384 ? 1 : 16;
                     for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave)
                         plan.err_items.push_back({l, (int32_t)b0, per_wave, 0});
@@ -187,6 +271,7 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
     }
     return kOk;
 }
+}  // namespace
 
 namespace {
 
@@ -248,6 +333,33 @@ bool check_plan(const Plan &plan)
             c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 256, 256);
         if (!c.complete(plan)) return false;
     }
+    // pass 3 of the count-sketch mode: every table entry once; bucket lists hold every row once, ascending
+    if (plan.sketch) {
+        std::vector<int64_t> area(nm, 0);
+        for (const WorkItem &it : plan.cs_err_items) {
+            if (it.mat < 0 || it.mat >= (int)nm) return false;
+            const MatDesc &d = plan.mats[it.mat];
+            if (it.a < 0 || it.b < 1 || it.a + it.b > d.w || it.c < 0 || (int64_t)it.c * kCsCols >= d.m) return false;
+            area[it.mat] += (int64_t)it.b * std::min<int64_t>(kCsCols, d.m - (int64_t)it.c * kCsCols);
+        }
+        for (size_t l = 0; l < nm; ++l) {
+            const MatDesc &d = plan.mats[l];
+            if (area[l] != d.w * d.m) return false;
+            const int32_t *ptr = plan.bucket_ptr.data() + d.bptr_off;
+            if (ptr[0] != 0 || ptr[d.w] != d.n) return false;
+            std::vector<char> seen(d.n, 0);
+            for (int64_t b = 0; b < d.w; ++b) {
+                if (ptr[b + 1] < ptr[b]) return false;
+                for (int32_t k = ptr[b]; k < ptr[b + 1]; ++k) {
+                    const int32_t hv = plan.bucket_rows[(size_t)(d.hash_off + k)], i = hv & INT32_MAX;
+                    if (i >= d.n || seen[i]) return false;
+                    if (k > ptr[b] && i <= (plan.bucket_rows[(size_t)(d.hash_off + k - 1)] & INT32_MAX)) return false;
+                    if (plan.row_hash[(size_t)(d.hash_off + i)] != ((int32_t)b | (hv & INT32_MIN))) return false;
+                    seen[i] = 1;
+                }
+            }
+        }
+    } else
     // pass 3: residual, quantiser, pack
     {
         Cover c(nm);

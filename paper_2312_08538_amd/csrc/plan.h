@@ -21,6 +21,7 @@ constexpr int kUpdRows = 64;        // tile of the decompress / update kernel
 constexpr int kUpdCols = 128;
 constexpr int kErrRows = 128;       // rows per workgroup item of the MFMA err pass (8 waves x 16)
 constexpr int kErrRun = 16;         // column blocks of 128 per item of the MFMA err pass (at most 16)
+constexpr int kCsCols = 256;        // columns per workgroup item of the count-sketch update pass
 
 // One matrix of the model as the kernels see it (device copy is an array of these).
 // Workspace offsets are in doubles from the start of the workspace.
@@ -45,6 +46,11 @@ struct MatDesc {
     int64_t scT_off;                // block scales, column-block-major: [m / 128][n] fp32
     int64_t ps_off;                 // P^, row-major:       [3][n][32]
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
+    // count-sketch error compressor (row sketch, one table row per bucket)
+    int64_t w;                      // table rows (buckets) of this matrix
+    int64_t table_off;              // element offset of the w x m table in the flat table buffer
+    int64_t hash_off;               // offset of the matrix's n entries in row_hash and bucket_rows
+    int64_t bptr_off;               // offset of its w + 1 entries in bucket_ptr
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -55,6 +61,15 @@ struct WorkItem {
 struct Plan {
     int rank = 0, bits = 0, block = 0, dtype = 0, rpad = 0;
     uint64_t seed = 0;
+    // count-sketch mode (the error state is a table instead of codes and scales)
+    bool sketch = false;
+    float beta = 0.0f;              // share of the error kept back (partial update)
+    int table_dtype = 0;            // 0 fp32, 1 fp16
+    size_t table_elems = 0;
+    std::vector<int32_t> row_hash;      // per row: bucket, bit 31 set for sign -1
+    std::vector<int32_t> bucket_ptr;    // per matrix w + 1 entries: rows of bucket b are bucket_rows[ptr[b] .. ptr[b+1])
+    std::vector<int32_t> bucket_rows;   // per matrix n entries: row index (bit 31: sign -1), ascending within a bucket
+    std::vector<WorkItem> cs_err_items; // sketch update: (mat, first bucket, buckets, column tile of kCsCols)
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
     bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;
@@ -92,5 +107,14 @@ bool check_plan(const Plan &plan);
 // Returns 0 or a negative CONEF_E* code.  `rows`/`cols` have n_mats entries.
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,
               int block, int dtype, uint64_t seed);
+
+// The same for the count-sketch error compressor: sketch_rows[l] buckets (1 .. rows[l]) for matrix l,
+// beta in [0, 1), table_dtype 0 (fp32) or 1 (fp16).  Also computes the hash of every row and the
+// bucket lists.
+int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
+                     int rank, float beta, int table_dtype, int dtype, uint64_t seed);
+
+// Bucket and sign of a row (Philox4x32-10 of (row, matrix) keyed by the seed).
+void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative);
 
 }  // namespace conef

@@ -134,3 +134,77 @@ def test_full_workloads_plan_consistently():
             B.conef_check_plan(ctx)
         finally:
             B.conef_destroy(ctx)
+
+
+# ------------------------------------------------------------------ count-sketch mode (host side)
+def test_sketch_init_rejects_bad_arguments():
+    lay = [(64, 64), (30, 20)]
+    bad = [
+        dict(sketch_rows=[0, 5]), dict(sketch_rows=[65, 5]), dict(sketch_rows=[8, 31]),   # 1 <= w <= rows
+        dict(beta=1.0), dict(beta=-0.01), dict(beta=float("nan")),
+        dict(table_dtype=2), dict(table_dtype=-1), dict(rank=0), dict(rank=21), dict(grad_dtype=5),
+    ]
+    for b in bad:
+        kw = dict(sketch_rows=[16, 30], rank=4, beta=0.9, table_dtype=B.TABLE_F16, grad_dtype=B.F32)
+        kw.update(b)
+        with pytest.raises(B.ConefError) as e:
+            B.conef_cs_init(lay, kw["sketch_rows"], kw["rank"], kw["beta"], kw["table_dtype"], kw["grad_dtype"], 0)
+        assert e.value.code == B.EINVAL, b
+    ctx = ctypes.c_void_p()
+    arr = (B.conef_mat * 1)()
+    arr[0].rows, arr[0].cols = 8, 8
+    assert B.lib().conef_cs_init(ctypes.byref(ctx), arr, None, 1, 2, 0.5, 0, 0, 0) == B.EINVAL     # null sketch_rows
+
+
+def test_sketch_and_quantiser_contexts_refuse_each_others_calls():
+    sk = B.conef_cs_init([(64, 64)], [16], 4, 0.5, B.TABLE_F32, B.F32, 0)
+    qc = B.conef_init([(64, 64)], 4, 4, 64, B.F32, 0)
+    L = B.lib()
+    assert L.conef_step(sk, 256, 256, 256, 256, 256, 256, 256, 0, 0) == B.ESTATE
+    assert L.conef_step_p(sk, 256, 256, 256, 256, 256, 256, 0) == B.ESTATE
+    assert L.conef_decode_error(sk, 256, 256, 256, 0) == B.ESTATE
+    assert L.conef_reset_error(sk, 256, 256, 0) == B.ESTATE
+    assert L.conef_cs_step(qc, 256, 256, 256, 256, 256, 256, 0) == B.ESTATE
+    assert L.conef_cs_step_err(qc, 256, 256, 256, 256, 256, 0) == B.ESTATE
+    assert L.conef_cs_decode_error(qc, 256, 256, 0) == B.ESTATE
+    assert L.conef_cs_sizes(qc, None) == B.ESTATE
+    assert L.conef_cs_step(sk, 256, 0, 256, 256, 256, 256, 0) == B.EINVAL              # null table
+    assert L.conef_cs_step(sk, 256, 264, 256, 256, 256, 256, 0) == B.EINVAL            # table not 16-byte aligned
+    assert L.conef_cs_offsets(sk, 1, None, None) == B.EINVAL
+    assert B.conef_sizes(sk)["code_words"] == 0 and B.conef_sizes(sk)["n_scales"] == 0
+    B.conef_destroy(sk)
+    B.conef_destroy(qc)
+
+
+SKETCH_PLAN_CASES = [
+    ([(37, 11), (64, 8), (300, 256)], [5, 64, 60], 4),
+    ([(64, 147), (128, 576), (20, 33)], [13, 26, 1], 3),
+    ([(2000, 520), (96, 1024)], [400, 96], 8),
+    ([(130, 300), (70, 2600)], [50, 7], 32),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SKETCH_PLAN_CASES)))
+def test_sketch_plan_tables_hash_and_bucket_lists(case, ref):
+    """Table offsets as documented; the library's hash is the oracle's; the bucket lists hold every row once
+    in ascending order and the update's work items cover every table entry once (the plan's self-check)."""
+    layout, ws, rank = SKETCH_PLAN_CASES[case]
+    m = B.SketchModel(layout, ws, rank, 0.9, B.TABLE_F16, B.BF16, 0xABCDEF0123)
+    B.conef_check_plan(m.ctx)
+    t = 0
+    for l, (n, mm) in enumerate(layout):
+        assert m.offsets[l]["table_off"] == t and m.offsets[l]["sketch_rows"] == ws[l]
+        t += (ws[l] * mm + 63) // 64 * 64
+        b, s = B.conef_cs_hash(m.ctx, l, n)
+        rb, rs = ref.cs_hash(0xABCDEF0123, l, n, ws[l])
+        assert np.array_equal(b, rb) and np.array_equal(s, rs)
+    assert m.sizes["table_elems"] == t
+    m.close()
+
+
+def test_sketch_plans_of_the_full_workloads_are_consistent():
+    for w in wl.WORKLOADS.values():
+        for keep in (0.2, 0.8):
+            m = B.SketchModel(w.layout, wl.sketch_rows(w.layout, keep), w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+            B.conef_check_plan(m.ctx)
+            m.close()
