@@ -69,6 +69,8 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.qred_items, &d.qred_items))) return rc;
     if ((rc = upload(ctx, pl.elem_items, &d.elem_items))) return rc;
     if ((rc = upload(ctx, pl.cs_err_items, &d.cs_err_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_err_f_items, &d.cs_err_f_items))) return rc;
+    d.n_cs_err_f = (int)pl.cs_err_f_items.size();
     if ((rc = upload(ctx, pl.row_hash, &d.row_hash))) return rc;
     if ((rc = upload(ctx, pl.bucket_ptr, &d.bucket_ptr))) return rc;
     if ((rc = upload(ctx, pl.bucket_rows, &d.bucket_rows))) return rc;

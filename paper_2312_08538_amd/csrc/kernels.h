@@ -15,9 +15,9 @@ struct DevicePlan {
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *upd_items = nullptr;                                                   // decompress / update
     // count-sketch mode
-    const WorkItem *cs_err_items = nullptr;
+    const WorkItem *cs_err_items = nullptr, *cs_err_f_items = nullptr;
     const int32_t *row_hash = nullptr, *bucket_ptr = nullptr, *bucket_rows = nullptr;
-    int n_cs_err = 0;
+    int n_cs_err = 0, n_cs_err_f = 0;
     int table_dtype = 0;            // 0 fp32, 1 fp16
     float beta = 0.0f, omb = 1.0f;  // beta and fl32(1 - beta)
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
@@ -68,6 +68,7 @@ void generic_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *cod
                     const float *Q, float *P, hipStream_t st);
 void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                     const float *Phat, double *ws, hipStream_t st);
+void generic_p_reduce(const DevicePlan &dp, double *ws, float *P, hipStream_t st);       // adds the column-chunk partials of P
 void generic_q_reduce(const DevicePlan &dp, double *ws, float *Qout, hipStream_t st);   // adds the row-tile partials of Q+
 void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                       const float *Qn, uint64_t step, hipStream_t st);

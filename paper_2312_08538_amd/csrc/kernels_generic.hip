@@ -229,6 +229,11 @@ void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *cod
         CONEF_DISPATCH_RP(k_pass_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, codes, scales, Phat, ws);
 }
 
+void generic_p_reduce(const DevicePlan &dp, double *ws, float *P, hipStream_t st)
+{
+    if (dp.n_pred > 0) hipLaunchKernelGGL(k_p_reduce, dim3(dp.n_pred), dim3(256), 0, st, dp, (const double *)ws, P);
+}
+
 void generic_q_reduce(const DevicePlan &dp, double *ws, float *Qout, hipStream_t st)
 {
     if (dp.n_qred > 0)
@@ -252,7 +257,7 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
     octet_pass_p(dp, grads, codes, scales, Q, P, ws, st);
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
-    if (dp.n_pred > 0) hipLaunchKernelGGL(k_p_reduce, dim3(dp.n_pred), dim3(256), 0, st, dp, (const double *)ws, P);
+    generic_p_reduce(dp, ws, P, st);
     return hipGetLastError();
 }
 

@@ -13,7 +13,8 @@
 // ascending order in fp32 and rounds once to the table's type (fp32 or fp16).  A bucket's rows all
 // read the same table row, so the pass fetches it once per bucket.
 //
-// This file holds the kernels that take any shape (one element per lane and access).
+// Two sets of kernels: one that takes any shape (one element per lane and access), and the octet path
+// for matrices whose rows hold whole octets (cols % 8 == 0), on the fp64 matrix cores.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -29,8 +30,12 @@ __device__ __forceinline__ float table_load(const void *table, int f16, int64_t 
 
 __device__ __forceinline__ void table_store(void *table, int f16, int64_t idx, float v)
 {
-    if (f16) reinterpret_cast<_Float16 *>(table)[idx] = (_Float16)v;       // round to nearest even
-    else reinterpret_cast<float *>(table)[idx] = v;
+    if (f16) {
+        asm volatile("" : "+v"(v));     // keeps the fp32 rounding of v apart from the conversion (no v_fma_mixlo_f16)
+        reinterpret_cast<_Float16 *>(table)[idx] = (_Float16)v;             // round to nearest even
+    } else {
+        reinterpret_cast<float *>(table)[idx] = v;
+    }
 }
 
 // (1 - beta) with the sign of the row folded in: fma(-(1 - beta), t, g) is fma(1 - beta, -t, g) exactly
@@ -155,6 +160,477 @@ __global__ __launch_bounds__(256) void k_cs_decode(DevicePlan dp, const void *ta
     }
 }
 
+// ================================================================== octet path (cols % 8 == 0)
+// A lane owns an octet: 8 consecutive elements of a row of the gradient (one or two 16-byte loads) and
+// the 8 table entries under them (row h(i) of the table, the same columns).  The P and Q+ passes are
+// the fp64 matrix-core passes of the quantiser's octet family with the decode replaced by
+// p = fma(+-(1 - beta), table entry, gradient): v_mfma_f64_4x4x4_4b_f64, four blocks that share B,
+// RH = rank / 4 (rounded up to 1, 2, 4, 8) instructions per A operand, fp64 sums, one rounding.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16, bool F16>
+struct SketchOctet {
+    u32x4 g0, g1;       // gradient bits (g1 only for fp32)
+    u32x4 t0, t1;       // table bits (t1 only for an fp32 table)
+};
+
+// `ge`, `te`: element offsets (multiples of 8) of the octet in the gradient buffer and in the table
+template <bool BF16, bool F16>
+__device__ __forceinline__ SketchOctet<BF16, F16> load_sketch_octet(const void *__restrict__ grads, const void *__restrict__ table,
+                                                                    int64_t ge, int64_t te)
+{
+    SketchOctet<BF16, F16> r;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    r.g1 = zero; r.t1 = zero;
+    if (BF16) {
+        r.g0 = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(grads) + ge);
+    } else {
+        const u32x4 *gp = reinterpret_cast<const u32x4 *>(reinterpret_cast<const float *>(grads) + ge);
+        r.g0 = gp[0]; r.g1 = gp[1];
+    }
+    if (F16) {
+        r.t0 = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(table) + te);
+    } else {
+        const u32x4 *tp = reinterpret_cast<const u32x4 *>(reinterpret_cast<const float *>(table) + te);
+        r.t0 = tp[0]; r.t1 = tp[1];
+    }
+    return r;
+}
+
+__device__ __forceinline__ float half_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
+
+template <bool BF16>
+__device__ __forceinline__ void widen_grad_octet(const u32x4 &g0, const u32x4 &g1, float g[8])
+{
+    if (BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            g[2 * i] = __uint_as_float(g0[i] << 16);
+            g[2 * i + 1] = __uint_as_float(g0[i] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { g[i] = __uint_as_float(g0[i]); g[4 + i] = __uint_as_float(g1[i]); }
+    }
+}
+
+template <bool F16>
+__device__ __forceinline__ void widen_table_octet(const u32x4 &t0, const u32x4 &t1, float t[8])
+{
+    if (F16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            t[2 * i] = half_bits_to_f32(t0[i] & 0xFFFFu);
+            t[2 * i + 1] = half_bits_to_f32(t0[i] >> 16);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { t[i] = __uint_as_float(t0[i]); t[4 + i] = __uint_as_float(t1[i]); }
+    }
+}
+
+// p = fma(somb, t, g) for the 8 elements of an octet (Algorithm 4 line 5 with the row's sign folded into somb)
+template <bool BF16, bool F16>
+__device__ __forceinline__ void form_p_octet(const SketchOctet<BF16, F16> &o, float somb, float p[8])
+{
+    float g[8], t[8];
+    widen_grad_octet<BF16>(o.g0, o.g1, g);
+    widen_table_octet<F16>(o.t0, o.t1, t);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_fmaf(somb, t[e], g[e]);
+}
+
+// ------------------------------------------------------------------ P pass
+// One workgroup per (64 rows, column chunk), walked in steps of 128 columns; wave w takes columns
+// 32 w .. 32 w + 31 of a step, forms its 64 x 32 sub-tile of p in the coalesced load layout, passes it
+// through a wave-private LDS tile into the operand layout (A[i][kk] = p[row i][column 4 j + kk]) and
+// multiplies by B[kk][c] = Q[column 4 j + kk][c]; loads run one step ahead; the four waves' sums are
+// added in wave order at the end.  A lane's four rows, hence their table rows and signs, are fixed.
+constexpr int kCsSubCols = 32, kCsStepCols = 128, kCsTileStride = 36;
+
+template <bool BF16, bool F16, int RH>
+__global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
+                                                    const float *__restrict__ Q, float *P, double *ws)
+{
+    __shared__ __attribute__((aligned(16))) float tiles[4][kPTileRows * kCsTileStride];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    float *T = tiles[wave];
+    const WorkItem it = dp.p_f_items[xcd_contiguous_item(blockIdx.x, dp.n_p_f)];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int64_t row0 = it.a;
+    const int c_begin = it.b * d.p_chunk_cols;
+    const int c_end = (c_begin + d.p_chunk_cols < d.m) ? c_begin + d.p_chunk_cols : (int)d.m;
+    const int lrow = lane >> 2, loct = lane & 3;      // load layout: 4 lanes per row, 16 rows per load
+    const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
+    const int mc = lane & 3;                          // factor column of this lane's B and D entries (+ 4 h)
+
+    double acc[4][RH];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
+
+    // the lane's four rows (rows at or beyond n re-read the last row: their rows of D are not stored)
+    int64_t grow[4], trow[4];
+    float somb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        int64_t row = row0 + s * 16 + lrow;
+        row = row < d.n ? row : d.n - 1;
+        const int32_t hv = dp.row_hash[d.hash_off + row];
+        grow[s] = d.grad_off + row * d.m;
+        trow[s] = d.table_off + (int64_t)(hv & INT32_MAX) * d.m;
+        somb[s] = hv < 0 ? -dp.omb : dp.omb;
+    }
+    const int oct_end = c_end >> 3;
+    auto load_tile = [&](SketchOctet<BF16, F16> (&o)[4], int col0) {
+        // octets at or beyond the end of the chunk re-read its last octet (their B operand is zero)
+        int oc = (col0 >> 3) + loct;
+        oc = oc < oct_end ? oc : oct_end - 1;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) o[s] = load_sketch_octet<BF16, F16>(grads, table, grow[s] + oc * 8, trow[s] + oc * 8);
+    };
+    // B operand of a sub-tile: Q[col0 + 4 j + mk][mc + 4 h], j = 0..7; zero beyond the rank and for columns
+    // at or beyond the end of the chunk (masked by a product: a select would let the load sink behind a branch)
+    auto load_b = [&](float (&bq)[8][RH], int col0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int col = col0 + 4 * j + mk;
+#pragma unroll
+            for (int h = 0; h < RH; ++h) {
+                const int c = mc + 4 * h;
+                const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + (c < r ? c : r - 1)];
+                bq[j][h] = v * ((col < c_end && c < r) ? 1.0f : 0.0f);
+            }
+        }
+    };
+
+    const int n_steps = (c_end - c_begin + kCsStepCols - 1) / kCsStepCols;
+    SketchOctet<BF16, F16> cur[4];
+    float bq[8][RH];
+    load_tile(cur, c_begin + kCsSubCols * wave);
+    load_b(bq, c_begin + kCsSubCols * wave);
+    for (int step = 0; step < n_steps; ++step) {
+        const int col0 = c_begin + step * kCsStepCols + kCsSubCols * wave;       // this wave's sub-tile
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float p[8];
+            form_p_octet<BF16, F16>(cur[s], somb[s], p);
+            float4 *dst = reinterpret_cast<float4 *>(T + (s * 16 + lrow) * kCsTileStride + loct * 8);
+            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
+            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+        }
+        double bd[8][RH];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int h = 0; h < RH; ++h) bd[j][h] = (double)bq[j][h];
+        // issue the loads of this wave's next sub-tile
+        load_b(bq, col0 + kCsStepCols);
+        load_tile(cur, col0 + kCsStepCols);
+        __builtin_amdgcn_wave_barrier();
+        if (col0 < c_end) {             // a ragged last step leaves the upper waves without columns
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const double a = (double)T[(16 * t + mi) * kCsTileStride + 4 * j + mk];
+#pragma unroll
+                    for (int h = 0; h < RH; ++h)
+                        acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, bd[j][h], acc[t][h], 0, 0, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    // the four waves' sums, added in wave order.  D of block (lane % 16) / 4, entry [lane / 16][lane % 4]:
+    // row 16 t + 4 ((lane % 16) / 4) + lane / 16 of the tile, factor column lane % 4 + 4 h
+    __syncthreads();
+    constexpr int RC = 4 * RH;
+    double *red = reinterpret_cast<double *>(&tiles[0][0]);      // [row][factor column] of one wave at a time
+    const int drow = 4 * (mi >> 2) + mk;
+    double sum[(kPTileRows * RC + 255) / 256];
+#pragma unroll
+    for (int u = 0; u < (kPTileRows * RC + 255) / 256; ++u) sum[u] = 0.0;
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int h = 0; h < RH; ++h) red[(16 * t + drow) * RC + mc + 4 * h] = acc[t][h];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < (kPTileRows * RC + 255) / 256; ++u) {
+            const int idx = tid + 256 * u;
+            if (idx < kPTileRows * RC) sum[u] += red[idx];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < (kPTileRows * RC + 255) / 256; ++u) {
+        const int idx = tid + 256 * u, rr = idx / RC, c = idx % RC;
+        const int64_t row = row0 + rr;
+        if (idx < kPTileRows * RC && c < r && row < d.n) {
+            if (d.n_p_chunks == 1) P[d.p_off + row * r + c] = (float)sum[u];
+            else ws[d.ppart_off + ((int64_t)it.b * d.n + row) * r + c] = sum[u];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ Q+ pass
+// One wave per (64 columns, row tile): D[k][c] += sum_i p[row i][column k] P^[row i][c], rows walked
+// 32 at a time through a wave-private LDS tile; loads run one step ahead, the hash of a row one step
+// ahead of its loads (the table row to read depends on it).  Partial sums per row tile go to the
+// workspace and are added in tile order by the reduction kernel.
+constexpr int kCsQTileCols = 64, kCsQTilePitch = 80, kCsQStepRows = 32;
+
+template <bool BF16, bool F16, int RH>
+__global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
+                                                    const float *__restrict__ Phat, double *ws)
+{
+    __shared__ __attribute__((aligned(16))) float tiles[4][kCsQStepRows * kCsQTilePitch];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_q_f) return;
+    float *T = tiles[wave];
+    const WorkItem it = dp.q_f_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int col0 = it.a * kCsQTileCols;
+    const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
+    const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
+    const int lrow = lane >> 3, loct = lane & 7;      // load layout: 8 lanes per row, rows lrow + 8 s
+    const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
+    const int mc = lane & 3;
+    // columns at or beyond m (last strip) read the last octet of the row instead: they only feed rows of D
+    // that are not stored
+    const int64_t oct0 = ((col0 >> 3) + loct < d.m8) ? (col0 >> 3) + loct : d.m8 - 1;
+
+    double acc[4][RH];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
+
+    constexpr int kLoads = kCsQStepRows / 8, kGroups = kCsQStepRows / 4;
+    struct Step {
+        SketchOctet<BF16, F16> o[kLoads];
+        float somb[kLoads];
+        float ph[kGroups][RH];    // P^[i0 + 4 g + mk][mc + 4 h]
+    };
+    int32_t hvn[kLoads];          // hash of the rows of the step after the one being loaded
+    auto load_hash = [&](int64_t i0) {
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s) {
+            int64_t row = i0 + lrow + 8 * s;
+            row = row < row1 ? row : row1 - 1;
+            hvn[s] = dp.row_hash[d.hash_off + row];
+        }
+    };
+    auto load_step = [&](Step &st, int64_t i0) {
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s) {
+            int64_t row = i0 + lrow + 8 * s;
+            row = row < row1 ? row : row1 - 1;         // rows at or beyond row1 re-read the last row; their P^ operand is zero
+            const int32_t hv = hvn[s];
+            st.somb[s] = hv < 0 ? -dp.omb : dp.omb;
+            st.o[s] = load_sketch_octet<BF16, F16>(grads, table, d.grad_off + (row * d.m8 + oct0) * 8,
+                                                   d.table_off + ((int64_t)(hv & INT32_MAX) * d.m8 + oct0) * 8);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            const int64_t row = i0 + 4 * g + mk;
+#pragma unroll
+            for (int h = 0; h < RH; ++h) {
+                const int c = mc + 4 * h;
+                const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + (c < r ? c : r - 1)];
+                st.ph[g][h] = v * ((row < row1 && c < r) ? 1.0f : 0.0f);
+            }
+        }
+        load_hash(i0 + kCsQStepRows);
+    };
+
+    Step cur;
+    load_hash(row0);
+    load_step(cur, row0);
+    for (int64_t i0 = row0; i0 < row1; i0 += kCsQStepRows) {
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s) {
+            float p[8];
+            form_p_octet<BF16, F16>(cur.o[s], cur.somb[s], p);
+            float4 *dst = reinterpret_cast<float4 *>(T + (lrow + 8 * s) * kCsQTilePitch + loct * 8);
+            dst[0] = make_float4(p[0], p[1], p[2], p[3]);
+            dst[1] = make_float4(p[4], p[5], p[6], p[7]);
+        }
+        double b[kGroups][RH];
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g)
+#pragma unroll
+            for (int h = 0; h < RH; ++h) b[g][h] = (double)cur.ph[g][h];
+        load_step(cur, i0 + kCsQStepRows);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const double a = (double)T[(4 * g + mk) * kCsQTilePitch + 16 * t + mi];
+#pragma unroll
+                for (int h = 0; h < RH; ++h)
+                    acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b[g][h], acc[t][h], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    // D of block (lane % 16) / 4, entry [lane / 16][lane % 4]: column 16 t + 4 ((lane % 16) / 4) + lane / 16 of the strip
+    const int dcol = 4 * (mi >> 2) + mk;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int col = col0 + 16 * t + dcol;
+#pragma unroll
+        for (int h = 0; h < RH; ++h) {
+            const int c = mc + 4 * h;
+            if (col < d.m && c < r) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + c] = acc[t][h];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ update pass
+// One wave per (run of buckets, column strip); a lane owns CPL consecutive columns and keeps their rows
+// of Q+ in registers (CPL * RP = 64 values).  The rows of the item's buckets form one list; the
+// gradient of the next row of the list is requested before the current row is worked on, and the
+// table row of the next bucket before the current bucket is.  Row index and P^ row are uniform over
+// the wave.
+template <bool BF16, bool F16, int CPL, int RP>
+__global__ __launch_bounds__(256) void k_cs_update_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
+                                                         const float *__restrict__ Phat, const float *__restrict__ Qn)
+{
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_cs_err_f) return;
+    const WorkItem it = dp.cs_err_f_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int64_t colw = (int64_t)it.c * (64 * CPL) + lane * CPL;
+    const bool active = colw < d.m;                   // cols % 8 == 0: a lane's CPL columns are all inside or all outside
+    const int64_t col = active ? colw : 0;            // inactive lanes read column 0 and store nothing
+
+    float q[CPL][RP];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j)
+#pragma unroll
+        for (int c = 0; c < RP; ++c) q[j][c] = Qn[d.q_off + (col + j) * r + (c < r ? c : r - 1)] * (c < r ? 1.0f : 0.0f);
+
+    constexpr int GW = BF16 ? (CPL / 2) : CPL;        // 32-bit words of CPL gradient elements
+    constexpr int TW = F16 ? (CPL / 2) : CPL;         // and of CPL table entries
+    struct Words { uint32_t w[8]; };
+    auto load_words = [&](const void *base, int64_t elem, int bytes_per, int nwords) {
+        Words o;
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(base) + elem * bytes_per);
+        if (nwords == 8) {
+            const u32x4 a = reinterpret_cast<const u32x4 *>(p)[0], b = reinterpret_cast<const u32x4 *>(p)[1];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { o.w[i] = a[i]; o.w[4 + i] = b[i]; }
+        } else if (nwords == 4) {
+            const u32x4 a = reinterpret_cast<const u32x4 *>(p)[0];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o.w[i] = a[i];
+        } else if (nwords == 2) {
+            const uint2 a = *reinterpret_cast<const uint2 *>(p);
+            o.w[0] = a.x; o.w[1] = a.y;
+        } else {
+            o.w[0] = p[0];
+        }
+        return o;
+    };
+    auto widen_g = [&](const Words &o, float (&g)[CPL]) {
+#pragma unroll
+        for (int j = 0; j < CPL; ++j)
+            g[j] = BF16 ? __uint_as_float((j & 1) ? (o.w[j >> 1] & 0xFFFF0000u) : (o.w[j >> 1] << 16)) : __uint_as_float(o.w[j]);
+    };
+    auto widen_t = [&](const Words &o, float (&t)[CPL]) {
+#pragma unroll
+        for (int j = 0; j < CPL; ++j)
+            t[j] = F16 ? half_bits_to_f32((j & 1) ? (o.w[j >> 1] >> 16) : (o.w[j >> 1] & 0xFFFFu)) : __uint_as_float(o.w[j]);
+    };
+
+    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
+    const int32_t *rows = dp.bucket_rows + d.hash_off;
+    const int b_end = it.a + it.b;
+    const int32_t e_end = ptr[b_end];
+    int32_t e = ptr[it.a];
+    // the first row of the list (if any) and the first table row
+    Words gn = load_words(grads, d.grad_off + (int64_t)(rows[e < e_end ? e : 0] & INT32_MAX) * d.m + col, BF16 ? 2 : 4, GW);
+    Words tn = load_words(table, d.table_off + (int64_t)it.a * d.m + col, F16 ? 2 : 4, TW);
+    for (int b = it.a; b < b_end; ++b) {
+        float s_old[CPL], acc[CPL];
+        widen_t(tn, s_old);
+        const int bn = b + 1 < b_end ? b + 1 : b;
+        tn = load_words(table, d.table_off + (int64_t)bn * d.m + col, F16 ? 2 : 4, TW);
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) acc[j] = 0.0f;
+        const int32_t e_stop = ptr[b + 1];
+        for (; e < e_stop; ++e) {
+            const int32_t hv = rows[e];
+            const int64_t i = hv & INT32_MAX;
+            float g[CPL];
+            widen_g(gn, g);
+            const int32_t en = e + 1 < e_end ? e + 1 : e;
+            gn = load_words(grads, d.grad_off + (int64_t)(rows[en] & INT32_MAX) * d.m + col, BF16 ? 2 : 4, GW);
+            const float somb = hv < 0 ? -dp.omb : dp.omb;
+            float ph[RP];
+#pragma unroll
+            for (int c = 0; c < RP; ++c) ph[c] = Phat[d.p_off + i * r + (c < r ? c : r - 1)];
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) {
+                const float pv = __builtin_fmaf(somb, s_old[j], g[j]);
+                float rec = 0.0f;
+#pragma unroll
+                for (int c = 0; c < RP; ++c)
+                    if (c < r) rec = __builtin_fmaf(ph[c], q[j][c], rec);
+                const float x = pv - rec;
+                acc[j] = hv < 0 ? acc[j] - x : acc[j] + x;
+            }
+        }
+        if (active) {
+            float out[CPL];
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) {
+                out[j] = __builtin_fmaf(dp.beta, s_old[j], acc[j]);
+                // The fp32 result is rounded to fp32 first and to fp16 afterwards.  Left to itself the
+                // compiler merges the two into v_fma_mixlo_f16, which rounds the exact sum once: a different
+                // fp16 value in a few per cent of the entries.  The empty statement keeps them apart.
+                if (F16) asm volatile("" : "+v"(out[j]));
+            }
+            const int64_t te = d.table_off + (int64_t)b * d.m + col;
+            if (F16) {
+                uint32_t w[CPL / 2];
+#pragma unroll
+                for (int j = 0; j < CPL / 2; ++j)
+                    w[j] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j]) |
+                           ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j + 1]) << 16);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(table) + te);
+                if (CPL == 8) { const u32x4 v = {w[0], w[1], w[2 % (CPL / 2)], w[3 % (CPL / 2)]}; *reinterpret_cast<u32x4 *>(dst) = v; }
+                else if (CPL == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1 % (CPL / 2)]);
+                else dst[0] = w[0];
+            } else {
+                float *dst = reinterpret_cast<float *>(table) + te;
+                if (CPL == 8) {
+                    reinterpret_cast<float4 *>(dst)[0] = make_float4(out[0], out[1], out[2 % CPL], out[3 % CPL]);
+                    reinterpret_cast<float4 *>(dst)[1] = make_float4(out[4 % CPL], out[5 % CPL], out[6 % CPL], out[7 % CPL]);
+                } else if (CPL == 4) {
+                    reinterpret_cast<float4 *>(dst)[0] = make_float4(out[0], out[1], out[2 % CPL], out[3 % CPL]);
+                } else {
+                    *reinterpret_cast<float2 *>(dst) = make_float2(out[0], out[1]);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 #define CONEF_CS_DISPATCH_RP(KERNEL, GRID, BLOCK, ST, ...)                                        \
@@ -167,13 +643,45 @@ __global__ __launch_bounds__(256) void k_cs_decode(DevicePlan dp, const void *ta
         }                                                                                         \
     } while (0)
 
+// octet path: gradient type x table type x RH (instructions per A operand: rank / 4 rounded up to 1, 2, 4, 8)
+#define CONEF_CS_OCTET_RH(KERNEL, BF, FH, GRID, ST, ...)                                                      \
+    do {                                                                                                      \
+        switch (dp.rpad) {                                                                                    \
+        case 4: hipLaunchKernelGGL((KERNEL<BF, FH, 1>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;          \
+        case 8: hipLaunchKernelGGL((KERNEL<BF, FH, 2>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;          \
+        case 16: hipLaunchKernelGGL((KERNEL<BF, FH, 4>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;         \
+        default: hipLaunchKernelGGL((KERNEL<BF, FH, 8>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;         \
+        }                                                                                                     \
+    } while (0)
+
+#define CONEF_CS_OCTET_DISPATCH(KERNEL, GRID, ST, ...)                                        \
+    do {                                                                                      \
+        const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;                              \
+        if (bf && fh) CONEF_CS_OCTET_RH(KERNEL, true, true, GRID, ST, __VA_ARGS__);           \
+        else if (bf) CONEF_CS_OCTET_RH(KERNEL, true, false, GRID, ST, __VA_ARGS__);           \
+        else if (fh) CONEF_CS_OCTET_RH(KERNEL, false, true, GRID, ST, __VA_ARGS__);           \
+        else CONEF_CS_OCTET_RH(KERNEL, false, false, GRID, ST, __VA_ARGS__);                  \
+    } while (0)
+
+// update pass: columns per lane x padded rank = 64 register values of Q+
+#define CONEF_CS_UPDATE_RP(BF, FH, GRID, ST, ...)                                                                       \
+    do {                                                                                                                \
+        switch (dp.rpad) {                                                                                              \
+        case 4: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 4>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
+        case 8: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 8>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
+        case 16: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 4, 16>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;    \
+        default: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 2, 32>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;    \
+        }                                                                                                               \
+    } while (0)
+
 hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P,
                             double *ws, hipStream_t st, Span span)
 {
-    (void)ws;
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    if (dp.n_p_f > 0) CONEF_CS_OCTET_DISPATCH(k_cs_p_octet, dim3(dp.n_p_f), st, dp, grads, table, Q, P, ws);
     if (dp.n_p > 0) CONEF_CS_DISPATCH_RP(k_cs_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, table, Q, P);
     if (span.end) (void)hipEventRecord(span.end, st);
+    generic_p_reduce(dp, ws, P, st);
     return hipGetLastError();
 }
 
@@ -181,6 +689,7 @@ hipError_t launch_cs_pass_q(const DevicePlan &dp, const void *grads, const void 
                             double *ws, hipStream_t st, Span span)
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    if (dp.n_q_f > 0) CONEF_CS_OCTET_DISPATCH(k_cs_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, table, Phat, ws);
     if (dp.n_q > 0) CONEF_CS_DISPATCH_RP(k_cs_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, table, Phat, ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     generic_q_reduce(dp, ws, Qout, st);
@@ -191,6 +700,14 @@ hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *tab
                               hipStream_t st, Span span)
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    if (dp.n_cs_err_f > 0) {
+        const dim3 grid((dp.n_cs_err_f + 3) / 4);
+        const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;
+        if (bf && fh) CONEF_CS_UPDATE_RP(true, true, grid, st, dp, grads, table, Phat, Qn);
+        else if (bf) CONEF_CS_UPDATE_RP(true, false, grid, st, dp, grads, table, Phat, Qn);
+        else if (fh) CONEF_CS_UPDATE_RP(false, true, grid, st, dp, grads, table, Phat, Qn);
+        else CONEF_CS_UPDATE_RP(false, false, grid, st, dp, grads, table, Phat, Qn);
+    }
     if (dp.n_cs_err > 0)
         CONEF_CS_DISPATCH_RP(k_cs_update_generic, dim3(dp.n_cs_err), dim3(kCsCols), st, dp, grads, table, Phat, Qn);
     if (span.end) (void)hipEventRecord(span.end, st);

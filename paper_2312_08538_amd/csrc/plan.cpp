@@ -88,12 +88,16 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
                 const int32_t b = hv & INT32_MAX;
                 plan.bucket_rows[(size_t)(d.hash_off + fill[b]++)] = (int32_t)i | (hv & INT32_MIN);
             }
-            // buckets per item: about 16 rows of the matrix each
+            // buckets per item: about 16 rows of the matrix each.  Octet path: one item per wave, a lane
+            // owns 8, 4 or 2 columns (its rows of Q+ stay in registers: 64 values)
+            const bool fast = d.path == kPathOctet;
             const int64_t nb = std::max<int64_t>(1, std::min<int64_t>(64, 16 * d.w / d.n));
-            const int32_t nct = (int32_t)ceil_div(d.m, kCsCols);
+            plan.mats[l].cs_cols = fast ? 64 * (plan.rpad <= 8 ? 8 : plan.rpad == 16 ? 4 : 2) : kCsCols;
+            const int32_t nct = (int32_t)ceil_div(d.m, plan.mats[l].cs_cols);
+            std::vector<WorkItem> &items = fast ? plan.cs_err_f_items : plan.cs_err_items;
             for (int64_t b0 = 0; b0 < d.w; b0 += nb)
                 for (int32_t ct = 0; ct < nct; ++ct)
-                    plan.cs_err_items.push_back({l, (int32_t)b0, (int32_t)std::min<int64_t>(nb, d.w - b0), ct});
+                    items.push_back({l, (int32_t)b0, (int32_t)std::min<int64_t>(nb, d.w - b0), ct});
         }
     } catch (const std::bad_alloc &) {
         return kEnomem;
@@ -152,9 +156,13 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             d.q_off = q;     q += round_up(d.m * rank, kAlign);
             d.path = (!sketch && block_ok && (rank == 2 || rank == 4 || rank == 8) && d.m % 64 == 0 && d.m % block == 0) ? kPathOctet
                                                                                              : kPathGeneric;
+            // count-sketch mode: the octet path needs whole octets per row only (16-byte aligned rows of
+            // the gradient and of the table), at any rank
+            const bool sketch_octet = sketch && d.m % 8 == 0;
             d.m8 = (int32_t)(d.m / 8);
             d.lb_shift = block_ok ? log2i(block / 8) : 0;
-            if (d.path == kPathOctet) {
+            if (sketch_octet) d.path = kPathOctet;
+            else if (d.path == kPathOctet) {
                 // lanes per row segment: the largest power of two <= 64 that divides m/8 and holds a block
                 int lr = 64;
                 while (lr > 8 && (d.m8 % lr) != 0) lr >>= 1;
@@ -245,7 +253,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                     for (int32_t st = 0; st < qstrips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
                 const int64_t rows_item = (int64_t)std::max(err_rows, rw);
-                for (int64_t r0 = 0; r0 < d.n; r0 += rows_item)
+                for (int64_t r0 = 0; r0 < d.n && !sketch; r0 += rows_item)
                     for (int32_t st = 0; st < strips; ++st)
                         plan.err_f_items.push_back({l, st, (int32_t)r0, (int32_t)std::min<int64_t>(rows_item, d.n - r0)});
                 if (d.n_p_chunks > 1)
@@ -336,12 +344,14 @@ bool check_plan(const Plan &plan)
     // pass 3 of the count-sketch mode: every table entry once; bucket lists hold every row once, ascending
     if (plan.sketch) {
         std::vector<int64_t> area(nm, 0);
-        for (const WorkItem &it : plan.cs_err_items) {
-            if (it.mat < 0 || it.mat >= (int)nm) return false;
-            const MatDesc &d = plan.mats[it.mat];
-            if (it.a < 0 || it.b < 1 || it.a + it.b > d.w || it.c < 0 || (int64_t)it.c * kCsCols >= d.m) return false;
-            area[it.mat] += (int64_t)it.b * std::min<int64_t>(kCsCols, d.m - (int64_t)it.c * kCsCols);
-        }
+        for (const std::vector<WorkItem> *tab : {&plan.cs_err_items, &plan.cs_err_f_items})
+            for (const WorkItem &it : *tab) {
+                if (it.mat < 0 || it.mat >= (int)nm) return false;
+                const MatDesc &d = plan.mats[it.mat];
+                if ((d.path == kPathOctet) != (tab == &plan.cs_err_f_items)) return false;
+                if (it.a < 0 || it.b < 1 || it.a + it.b > d.w || it.c < 0 || (int64_t)it.c * d.cs_cols >= d.m) return false;
+                area[it.mat] += (int64_t)it.b * std::min<int64_t>(d.cs_cols, d.m - (int64_t)it.c * d.cs_cols);
+            }
         for (size_t l = 0; l < nm; ++l) {
             const MatDesc &d = plan.mats[l];
             if (area[l] != d.w * d.m) return false;

@@ -51,6 +51,7 @@ struct MatDesc {
     int64_t table_off;              // element offset of the w x m table in the flat table buffer
     int64_t hash_off;               // offset of the matrix's n entries in row_hash and bucket_rows
     int64_t bptr_off;               // offset of its w + 1 entries in bucket_ptr
+    int32_t cs_cols;                // columns per item of the sketch update pass
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -69,7 +70,8 @@ struct Plan {
     std::vector<int32_t> row_hash;      // per row: bucket, bit 31 set for sign -1
     std::vector<int32_t> bucket_ptr;    // per matrix w + 1 entries: rows of bucket b are bucket_rows[ptr[b] .. ptr[b+1])
     std::vector<int32_t> bucket_rows;   // per matrix n entries: row index (bit 31: sign -1), ascending within a bucket
-    std::vector<WorkItem> cs_err_items; // sketch update: (mat, first bucket, buckets, column tile of kCsCols)
+    std::vector<WorkItem> cs_err_items; // sketch update: (mat, first bucket, buckets, column tile of cs_cols)
+    std::vector<WorkItem> cs_err_f_items;  // the same for matrices of the octet path, one item per wave
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
     bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;

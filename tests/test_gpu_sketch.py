@@ -5,9 +5,9 @@ the C ABI, against oracle/sketch_ref.c on the same seeded inputs.
     arithmetic in a fixed order, rounded once to the table's type);
   * estimate of the error: bit for bit;
   * P and Q+ stages: fp64 sums of exact products rounded once -> relative error <= 1e-6;
-  * whole steps, each from the oracle's state: factors to 1e-5; the table to 1e-5 of its largest entry
-    (fp32), or equal except for one unit in the last place on at most 2e-3 of its entries (fp16): the
-    factors the update sees may differ from the oracle's in their last bit.
+  * whole steps, each from the oracle's state: factors to 1e-5; a table entry to 2e-6 of the size of
+    the terms it is the sum of (fp32), plus one unit in the last place on at most 5e-3 of the entries
+    (fp16): the factors the update sees may differ from the oracle's in their last bit.
 """
 import numpy as np
 import pytest
@@ -84,6 +84,10 @@ LAYOUTS = [
     ([(200, 520), (96, 1024)], [40, 77], 8),
     ([(130, 300), (70, 260)], [50, 70], 32),
     ([(48, 96)], [48], 12),                                        # as many buckets as rows: some stay empty
+    ([(130, 304), (70, 264), (40, 2048)], [50, 70, 9], 32),        # whole octets per row: the matrix-core path at rank 32
+    ([(100, 136), (333, 640)], [30, 100], 16),
+    ([(1000, 1160), (64, 4608)], [200, 51], 4),                    # several row tiles and column chunks, ragged ends
+    ([(700, 72)], [1], 2),                                         # one bucket: a long list of rows
 ]
 
 
@@ -190,21 +194,29 @@ def test_steps_match_the_oracle(env, case, gdt, fp16, beta):
         model.step(buf)
         torch.cuda.synchronize()
         for l, ((n, m), stt) in enumerate(zip(layout, states)):
+            before = stt.table.copy()
             Ph, Qn = R.cs_step_matrix(grads[l], stt, rank, beta, seed, l)
             tag = f"case {case} mat {l} step {t}"
             assert U.rel_err(_get_factor(buf, "P", model.offsets[l]["p_off"], n, rank), Ph) <= 1e-5, tag
             assert U.rel_err(_get_factor(buf, "Q", model.offsets[l]["q_off"], m, rank), Qn) <= 1e-5, tag
+            # size of the terms a table entry is the sum of: beta |S| + sum over its bucket of |x| (a last-bit
+            # difference in a factor moves every term by ~1e-7 of its size, whatever the sum cancels to)
+            b, sg = R.cs_hash(seed, l, n, ws[l])
+            x = R.residual(R.cs_form_p(grads[l], before, b, sg, beta), Ph, Qn)
+            mag = np.zeros((ws[l], m), np.float32)
+            R.cs_update(np.abs(x), b, np.ones(n, np.int8), 0.0, mag)
+            bf = before.view(np.float16).astype(np.float32) if fp16 else before
+            mag = mag.astype(np.float64) + beta * np.abs(bf) + np.abs(Ph).max() * np.abs(Qn).max() * rank
             got = _get_table(model, buf, l)
             gf = got.view(np.float16).astype(np.float32) if fp16 else got
             wf = stt.table.view(np.float16).astype(np.float32) if fp16 else stt.table
-            scale = float(np.abs(wf).max())
             diff = np.abs(gf.astype(np.float64) - wf.astype(np.float64))
             if fp16:
                 # one unit in the last place of fp16 where the two roundings fall on different sides, rarely
-                assert np.all(diff <= np.abs(wf) * 2.0 ** -10 + 2.0 ** -24 + 1e-5 * scale), f"{tag}: table"
-                assert (got != stt.table).mean() <= 2e-3, f"{tag}: {(got != stt.table).mean()} of the table differs"
+                assert np.all(diff <= np.abs(wf) * 2.0 ** -10 + 2.0 ** -24 + 2e-6 * mag), f"{tag}: table"
+                assert (got != stt.table).mean() <= 5e-3, f"{tag}: {(got != stt.table).mean()} of the table differs"
             else:
-                assert diff.max() <= 1e-5 * scale, f"{tag}: table differs by {diff.max()} (scale {scale})"
+                assert np.all(diff <= 2e-6 * mag), f"{tag}: table differs by {diff.max()}"
 
 
 def test_quantiser_calls_refuse_a_sketch_context_and_back(env):
