@@ -499,24 +499,31 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
 }
 
 // ------------------------------------------------------------------ update pass
-// One wave per (run of buckets, column strip); a lane owns CPL consecutive columns and keeps their rows
-// of Q+ in registers (CPL * RP = 64 values).  The rows of the item's buckets form one list; the
-// gradient of the next row of the list is requested before the current row is worked on, and the
-// table row of the next bucket before the current bucket is.  Row index and P^ row are uniform over
-// the wave.
+// One workgroup of THREADS threads per (run of at most 256 buckets, tile of 512 columns); a thread owns
+// CPL = 512 / THREADS consecutive columns and keeps their rows of Q+ in registers (CPL * RP = 64 values,
+// zero beyond the rank).  The rows of the item's buckets form one list; it is walked 64 entries at a time: their row
+// indices and rows of P^ are staged in LDS by the whole workgroup (a thread then reads a row of P^ with
+// RP / 4 broadcast reads), and the gradient of the next entry is requested before the current one is
+// worked on, the table row of the next bucket before the current bucket is.
+constexpr int kCsChunk = 64;
+
+constexpr int kCsMaxBuckets = 256;
+
 template <bool BF16, bool F16, int CPL, int RP>
-__global__ __launch_bounds__(256) void k_cs_update_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
+__global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
                                                          const float *__restrict__ Phat, const float *__restrict__ Qn)
 {
-    const int lane = threadIdx.x & 63;
-    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
-    if (item >= dp.n_cs_err_f) return;
-    const WorkItem it = dp.cs_err_f_items[item];
+    constexpr int THREADS = 512 / CPL;
+    __shared__ int32_t s_ptr[kCsMaxBuckets + 1];
+    __shared__ int32_t s_row[kCsChunk];
+    __shared__ __attribute__((aligned(16))) float s_p[kCsChunk * RP];
+    const int tid = threadIdx.x;
+    const WorkItem it = dp.cs_err_f_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int r = dp.rank;
-    const int64_t colw = (int64_t)it.c * (64 * CPL) + lane * CPL;
-    const bool active = colw < d.m;                   // cols % 8 == 0: a lane's CPL columns are all inside or all outside
-    const int64_t col = active ? colw : 0;            // inactive lanes read column 0 and store nothing
+    const int64_t colw = (int64_t)it.c * 512 + tid * CPL;
+    const bool active = colw < d.m;                   // cols % 8 == 0: a thread's CPL columns are all inside or all outside
+    const int64_t col = active ? colw : 0;            // threads outside read column 0 and store nothing
 
     float q[CPL][RP];
 #pragma unroll
@@ -556,43 +563,63 @@ __global__ __launch_bounds__(256) void k_cs_update_octet(DevicePlan dp, const vo
         for (int j = 0; j < CPL; ++j)
             t[j] = F16 ? half_bits_to_f32((j & 1) ? (o.w[j >> 1] >> 16) : (o.w[j >> 1] & 0xFFFFu)) : __uint_as_float(o.w[j]);
     };
+    auto load_grad_row = [&](int32_t hv) {
+        return load_words(grads, d.grad_off + (int64_t)(hv & INT32_MAX) * d.m + col, BF16 ? 2 : 4, GW);
+    };
 
-    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
     const int32_t *rows = dp.bucket_rows + d.hash_off;
-    const int b_end = it.a + it.b;
-    const int32_t e_end = ptr[b_end];
-    int32_t e = ptr[it.a];
-    // the first row of the list (if any) and the first table row
-    Words gn = load_words(grads, d.grad_off + (int64_t)(rows[e < e_end ? e : 0] & INT32_MAX) * d.m + col, BF16 ? 2 : 4, GW);
+    for (int i = tid; i <= it.b; i += THREADS) s_ptr[i] = dp.bucket_ptr[d.bptr_off + it.a + i];     // at most 257 entries
+    __syncthreads();
+    const int32_t e0 = s_ptr[0], e1 = s_ptr[it.b];
+    // entries c0 .. c0 + 63 of the list (beyond its end: the last entry again, never used)
+    auto stage = [&](int32_t c0) {
+        if (tid < kCsChunk) s_row[tid] = rows[(c0 + tid < e1) ? c0 + tid : e1 - 1];
+        for (int idx = tid; idx < kCsChunk * RP; idx += THREADS) {
+            const int j = idx / RP, c = idx % RP;
+            const int32_t hv = rows[(c0 + j < e1) ? c0 + j : e1 - 1];
+            s_p[idx] = Phat[d.p_off + (int64_t)(hv & INT32_MAX) * r + (c < r ? c : r - 1)] * (c < r ? 1.0f : 0.0f);
+        }
+    };
+
+    int32_t e = e0;
     Words tn = load_words(table, d.table_off + (int64_t)it.a * d.m + col, F16 ? 2 : 4, TW);
-    for (int b = it.a; b < b_end; ++b) {
+    Words gn = tn;                                   // set when a chunk is staged
+    for (int bi = 0; bi < it.b; ++bi) {
+        const int b = it.a + bi;
         float s_old[CPL], acc[CPL];
         widen_t(tn, s_old);
-        const int bn = b + 1 < b_end ? b + 1 : b;
+        const int bn = bi + 1 < it.b ? b + 1 : b;
         tn = load_words(table, d.table_off + (int64_t)bn * d.m + col, F16 ? 2 : 4, TW);
 #pragma unroll
         for (int j = 0; j < CPL; ++j) acc[j] = 0.0f;
-        const int32_t e_stop = ptr[b + 1];
+        const int32_t e_stop = s_ptr[bi + 1];
         for (; e < e_stop; ++e) {
-            const int32_t hv = rows[e];
-            const int64_t i = hv & INT32_MAX;
+            const int j = (e - e0) & (kCsChunk - 1);          // uniform over the workgroup
+            if (j == 0) {
+                __syncthreads();                              // every thread is done with the previous chunk
+                stage(e);
+                __syncthreads();
+                gn = load_grad_row(s_row[0]);
+            }
+            const int32_t hv = s_row[j];
             float g[CPL];
             widen_g(gn, g);
-            const int32_t en = e + 1 < e_end ? e + 1 : e;
-            gn = load_words(grads, d.grad_off + (int64_t)(rows[en] & INT32_MAX) * d.m + col, BF16 ? 2 : 4, GW);
+            gn = load_grad_row(s_row[j + 1 < kCsChunk ? j + 1 : j]);
             const float somb = hv < 0 ? -dp.omb : dp.omb;
             float ph[RP];
 #pragma unroll
-            for (int c = 0; c < RP; ++c) ph[c] = Phat[d.p_off + i * r + (c < r ? c : r - 1)];
+            for (int c4 = 0; c4 < RP / 4; ++c4) {
+                const float4 v = reinterpret_cast<const float4 *>(s_p + j * RP)[c4];
+                ph[4 * c4] = v.x; ph[4 * c4 + 1] = v.y; ph[4 * c4 + 2] = v.z; ph[4 * c4 + 3] = v.w;
+            }
 #pragma unroll
-            for (int j = 0; j < CPL; ++j) {
-                const float pv = __builtin_fmaf(somb, s_old[j], g[j]);
+            for (int jj = 0; jj < CPL; ++jj) {
+                const float pv = __builtin_fmaf(somb, s_old[jj], g[jj]);
                 float rec = 0.0f;
 #pragma unroll
-                for (int c = 0; c < RP; ++c)
-                    if (c < r) rec = __builtin_fmaf(ph[c], q[j][c], rec);
+                for (int c = 0; c < RP; ++c) rec = __builtin_fmaf(ph[c], q[jj][c], rec);     // beyond the rank: + 0 * 0
                 const float x = pv - rec;
-                acc[j] = hv < 0 ? acc[j] - x : acc[j] + x;
+                acc[jj] = hv < 0 ? acc[jj] - x : acc[jj] + x;
             }
         }
         if (active) {
@@ -613,7 +640,7 @@ __global__ __launch_bounds__(256) void k_cs_update_octet(DevicePlan dp, const vo
                     w[j] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j]) |
                            ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j + 1]) << 16);
                 uint32_t *dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(table) + te);
-                if (CPL == 8) { const u32x4 v = {w[0], w[1], w[2 % (CPL / 2)], w[3 % (CPL / 2)]}; *reinterpret_cast<u32x4 *>(dst) = v; }
+                if (CPL == 8) { const u32x4 v = {w[0], w[1 % (CPL / 2)], w[2 % (CPL / 2)], w[3 % (CPL / 2)]}; *reinterpret_cast<u32x4 *>(dst) = v; }
                 else if (CPL == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1 % (CPL / 2)]);
                 else dst[0] = w[0];
             } else {
@@ -667,9 +694,9 @@ __global__ __launch_bounds__(256) void k_cs_update_octet(DevicePlan dp, const vo
 #define CONEF_CS_UPDATE_RP(BF, FH, GRID, ST, ...)                                                                       \
     do {                                                                                                                \
         switch (dp.rpad) {                                                                                              \
-        case 4: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 4>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
-        case 8: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 8>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
-        case 16: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 4, 16>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;    \
+        case 4: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 4>), GRID, dim3(64), 0, ST, __VA_ARGS__); break;       \
+        case 8: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 8, 8>), GRID, dim3(64), 0, ST, __VA_ARGS__); break;       \
+        case 16: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 4, 16>), GRID, dim3(128), 0, ST, __VA_ARGS__); break;    \
         default: hipLaunchKernelGGL((k_cs_update_octet<BF, FH, 2, 32>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;    \
         }                                                                                                               \
     } while (0)
@@ -701,7 +728,7 @@ hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *tab
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
     if (dp.n_cs_err_f > 0) {
-        const dim3 grid((dp.n_cs_err_f + 3) / 4);
+        const dim3 grid(dp.n_cs_err_f);
         const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;
         if (bf && fh) CONEF_CS_UPDATE_RP(true, true, grid, st, dp, grads, table, Phat, Qn);
         else if (bf) CONEF_CS_UPDATE_RP(true, false, grid, st, dp, grads, table, Phat, Qn);

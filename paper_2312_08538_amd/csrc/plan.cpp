@@ -68,6 +68,11 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
             d.bptr_off = bp; bp += d.w + 1;
         }
         plan.table_elems = (size_t)t;
+        // rows per item of the octet path's update pass: as many as leave about 4096 items, 32 to 256
+        int64_t total_elems = 0;
+        for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
+        int64_t cs_rows = 32;
+        while (cs_rows < 256 && total_elems / (cs_rows * 2 * 512) >= 4096) cs_rows *= 2;
         plan.row_hash.assign((size_t)h, 0);
         plan.bucket_rows.assign((size_t)h, 0);
         plan.bucket_ptr.assign((size_t)bp, 0);
@@ -88,11 +93,12 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
                 const int32_t b = hv & INT32_MAX;
                 plan.bucket_rows[(size_t)(d.hash_off + fill[b]++)] = (int32_t)i | (hv & INT32_MIN);
             }
-            // buckets per item: about 16 rows of the matrix each.  Octet path: one item per wave, a lane
-            // owns 8, 4 or 2 columns (its rows of Q+ stay in registers: 64 values)
+            // buckets per item: about 16 rows of the matrix each (at most 64 buckets); on the octet path, where
+            // a workgroup first loads 512 rows of Q+, `cs_rows` rows (at most 256 buckets)
             const bool fast = d.path == kPathOctet;
-            const int64_t nb = std::max<int64_t>(1, std::min<int64_t>(64, 16 * d.w / d.n));
-            plan.mats[l].cs_cols = fast ? 64 * (plan.rpad <= 8 ? 8 : plan.rpad == 16 ? 4 : 2) : kCsCols;
+            const int64_t nb = fast ? std::max<int64_t>(1, std::min<int64_t>(256, cs_rows * d.w / d.n))
+                                    : std::max<int64_t>(1, std::min<int64_t>(64, 16 * d.w / d.n));
+            plan.mats[l].cs_cols = fast ? 512 : kCsCols;
             const int32_t nct = (int32_t)ceil_div(d.m, plan.mats[l].cs_cols);
             std::vector<WorkItem> &items = fast ? plan.cs_err_f_items : plan.cs_err_items;
             for (int64_t b0 = 0; b0 < d.w; b0 += nb)

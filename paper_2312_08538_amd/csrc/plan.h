@@ -71,7 +71,7 @@ struct Plan {
     std::vector<int32_t> bucket_ptr;    // per matrix w + 1 entries: rows of bucket b are bucket_rows[ptr[b] .. ptr[b+1])
     std::vector<int32_t> bucket_rows;   // per matrix n entries: row index (bit 31: sign -1), ascending within a bucket
     std::vector<WorkItem> cs_err_items; // sketch update: (mat, first bucket, buckets, column tile of cs_cols)
-    std::vector<WorkItem> cs_err_f_items;  // the same for matrices of the octet path, one item per wave
+    std::vector<WorkItem> cs_err_f_items;  // the same for matrices of the octet path (wider tiles)
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
     bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;
