@@ -263,6 +263,9 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--count-sketch", action="store_true",
+                    help="time only the step with the count sketch as the error compressor (fp16 table, keep 0.2, "
+                         "beta 0.9) on --workload and print its line; for profiling that mode on its own")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
                          "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
@@ -280,6 +283,13 @@ def main():
     w = wl.WORKLOADS[a.workload]
     if a.calibrate_copy:
         calibrate_copy(w)
+    if a.count_sketch:
+        r = run_sketch(w, 0.2, 0.9, a.steps, a.warmup)
+        print(json.dumps({"metric": "ConEF-CS step throughput: gradient GB/s processed", "value": r["grad_GB/s"],
+                          "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+                          "config": {"workload": w.name, "rank": w.rank, "keep": 0.2, "beta": 0.9, "table": "f16"},
+                          **r}), flush=True)
+        return
     ms, stage_ms, finite = run_gpu(w, a.steps, a.warmup)
     if not finite:
         print("bench.py: non-finite factors after the timed run", file=sys.stderr)

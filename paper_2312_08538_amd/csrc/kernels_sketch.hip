@@ -167,6 +167,10 @@ __global__ __launch_bounds__(256) void k_cs_decode(DevicePlan dp, const void *ta
 // p = fma(+-(1 - beta), table entry, gradient): v_mfma_f64_4x4x4_4b_f64, four blocks that share B,
 // RH = rank / 4 (rounded up to 1, 2, 4, 8) instructions per A operand, fp64 sums, one rounding.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+// Ranks above 8 (RH = 4 or 8) use v_mfma_f64_16x16x4_f64 instead: D[i][c] += sum_k A[i][k] B[k][c] on 16 x 4 and
+// 4 x 16 operands, lane l holding A[l % 16][l / 16], B[l / 16][l % 16] and D[4 v + l / 16][l % 16] (v = 0..3).
+// Same rate per multiply-add, same A operands, but a lane holds RH / 4 B values per A instead of RH.
 
 template <bool BF16, bool F16>
 struct SketchOctet {
@@ -266,11 +270,17 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
     const int mi = lane & 15, mk = lane >> 4;         // matrix-core roles
     const int mc = lane & 3;                          // factor column of this lane's B and D entries (+ 4 h)
 
-    double acc[4][RH];
+    constexpr bool WIDE = RH >= 4;
+    constexpr int BN = WIDE ? RH / 4 : RH;            // B values per lane and A operand
+    double acc[4][WIDE ? 1 : RH];
+    f64x4 accw[4][WIDE ? BN : 1];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
-        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
+        for (int h = 0; h < (WIDE ? 1 : RH); ++h) acc[t][h] = 0.0;
+#pragma unroll
+        for (int h = 0; h < (WIDE ? BN : 1); ++h) accw[t][h] = f64x4{0.0, 0.0, 0.0, 0.0};
+    }
 
     // the lane's four rows (rows at or beyond n re-read the last row: their rows of D are not stored)
     int64_t grow[4], trow[4];
@@ -292,15 +302,16 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
 #pragma unroll
         for (int s = 0; s < 4; ++s) o[s] = load_sketch_octet<BF16, F16>(grads, table, grow[s] + oc * 8, trow[s] + oc * 8);
     };
-    // B operand of a sub-tile: Q[col0 + 4 j + mk][mc + 4 h], j = 0..7; zero beyond the rank and for columns
-    // at or beyond the end of the chunk (masked by a product: a select would let the load sink behind a branch)
-    auto load_b = [&](float (&bq)[8][RH], int col0) {
+    // B operand of a sub-tile: Q[col0 + 4 j + mk][mc + 4 h] (wide: [mi + 16 h]), j = 0..7; zero beyond the rank and
+    // for columns at or beyond the end of the chunk (masked by a product: a select would let the load sink
+    // behind a branch)
+    auto load_b = [&](float (&bq)[8][BN], int col0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int col = col0 + 4 * j + mk;
 #pragma unroll
-            for (int h = 0; h < RH; ++h) {
-                const int c = mc + 4 * h;
+            for (int h = 0; h < BN; ++h) {
+                const int c = WIDE ? mi + 16 * h : mc + 4 * h;
                 const float v = Q[d.q_off + (int64_t)(col < c_end ? col : c_end - 1) * r + (c < r ? c : r - 1)];
                 bq[j][h] = v * ((col < c_end && c < r) ? 1.0f : 0.0f);
             }
@@ -309,7 +320,7 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
 
     const int n_steps = (c_end - c_begin + kCsStepCols - 1) / kCsStepCols;
     SketchOctet<BF16, F16> cur[4];
-    float bq[8][RH];
+    float bq[8][BN];
     load_tile(cur, c_begin + kCsSubCols * wave);
     load_b(bq, c_begin + kCsSubCols * wave);
     for (int step = 0; step < n_steps; ++step) {
@@ -322,13 +333,9 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
         }
-        double bd[8][RH];
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int h = 0; h < RH; ++h) bd[j][h] = (double)bq[j][h];
         // issue the loads of this wave's next sub-tile
-        load_b(bq, col0 + kCsStepCols);
+        float bn[8][BN];
+        load_b(bn, col0 + kCsStepCols);
         load_tile(cur, col0 + kCsStepCols);
         __builtin_amdgcn_wave_barrier();
         if (col0 < c_end) {             // a ragged last step leaves the upper waves without columns
@@ -338,11 +345,17 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
                 for (int t = 0; t < 4; ++t) {
                     const double a = (double)T[(16 * t + mi) * kCsTileStride + 4 * j + mk];
 #pragma unroll
-                    for (int h = 0; h < RH; ++h)
-                        acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, bd[j][h], acc[t][h], 0, 0, 0);
+                    for (int h = 0; h < BN; ++h) {
+                        if (WIDE) accw[t][h] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)bq[j][h], accw[t][h], 0, 0, 0);
+                        else acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, (double)bq[j][h], acc[t][h], 0, 0, 0);
+                    }
                 }
             }
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int h = 0; h < BN; ++h) bq[j][h] = bn[j][h];
         __builtin_amdgcn_wave_barrier();
     }
     // the four waves' sums, added in wave order.  D of block (lane % 16) / 4, entry [lane / 16][lane % 4]:
@@ -357,9 +370,18 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
     for (int w = 0; w < 4; ++w) {
         if (wave == w) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < 4; ++t) {
+                if (WIDE) {
+                    // D[4 v + lane / 16][lane % 16]: row 16 t + 4 v + mk of the tile, factor column 16 h + mi
 #pragma unroll
-                for (int h = 0; h < RH; ++h) red[(16 * t + drow) * RC + mc + 4 * h] = acc[t][h];
+                    for (int h = 0; h < BN; ++h)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) red[(16 * t + 4 * v + mk) * RC + 16 * h + mi] = accw[t][h][v];
+                } else {
+#pragma unroll
+                    for (int h = 0; h < BN; ++h) red[(16 * t + drow) * RC + mc + 4 * h] = acc[t][h];
+                }
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -410,17 +432,23 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
     // that are not stored
     const int64_t oct0 = ((col0 >> 3) + loct < d.m8) ? (col0 >> 3) + loct : d.m8 - 1;
 
-    double acc[4][RH];
+    constexpr bool WIDE = RH >= 4;
+    constexpr int BN = WIDE ? RH / 4 : RH;            // B values per lane and A operand
+    double acc[4][WIDE ? 1 : RH];
+    f64x4 accw[4][WIDE ? BN : 1];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
-        for (int h = 0; h < RH; ++h) acc[t][h] = 0.0;
+        for (int h = 0; h < (WIDE ? 1 : RH); ++h) acc[t][h] = 0.0;
+#pragma unroll
+        for (int h = 0; h < (WIDE ? BN : 1); ++h) accw[t][h] = f64x4{0.0, 0.0, 0.0, 0.0};
+    }
 
     constexpr int kLoads = kCsQStepRows / 8, kGroups = kCsQStepRows / 4;
     struct Step {
         SketchOctet<BF16, F16> o[kLoads];
         float somb[kLoads];
-        float ph[kGroups][RH];    // P^[i0 + 4 g + mk][mc + 4 h]
+        float ph[kGroups][BN];    // P^[i0 + 4 g + mk][mc + 4 h] (wide: [mi + 16 h])
     };
     int32_t hvn[kLoads];          // hash of the rows of the step after the one being loaded
     auto load_hash = [&](int64_t i0) {
@@ -445,8 +473,8 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
         for (int g = 0; g < kGroups; ++g) {
             const int64_t row = i0 + 4 * g + mk;
 #pragma unroll
-            for (int h = 0; h < RH; ++h) {
-                const int c = mc + 4 * h;
+            for (int h = 0; h < BN; ++h) {
+                const int c = WIDE ? mi + 16 * h : mc + 4 * h;
                 const float v = Phat[d.p_off + (row < row1 ? row : row1 - 1) * r + (c < r ? c : r - 1)];
                 st.ph[g][h] = v * ((row < row1 && c < r) ? 1.0f : 0.0f);
             }
@@ -466,11 +494,11 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
         }
-        double b[kGroups][RH];
+        double b[kGroups][BN];
 #pragma unroll
         for (int g = 0; g < kGroups; ++g)
 #pragma unroll
-            for (int h = 0; h < RH; ++h) b[g][h] = (double)cur.ph[g][h];
+            for (int h = 0; h < BN; ++h) b[g][h] = (double)cur.ph[g][h];
         load_step(cur, i0 + kCsQStepRows);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -479,8 +507,10 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
             for (int t = 0; t < 4; ++t) {
                 const double a = (double)T[(4 * g + mk) * kCsQTilePitch + 16 * t + mi];
 #pragma unroll
-                for (int h = 0; h < RH; ++h)
-                    acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b[g][h], acc[t][h], 0, 0, 0);
+                for (int h = 0; h < BN; ++h) {
+                    if (WIDE) accw[t][h] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b[g][h], accw[t][h], 0, 0, 0);
+                    else acc[t][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b[g][h], acc[t][h], 0, 0, 0);
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -489,11 +519,22 @@ __global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *_
     const int dcol = 4 * (mi >> 2) + mk;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const int col = col0 + 16 * t + dcol;
+        if (WIDE) {
+            // D[4 v + lane / 16][lane % 16]: column 16 t + 4 v + mk of the strip, factor column 16 h + mi
 #pragma unroll
-        for (int h = 0; h < RH; ++h) {
-            const int c = mc + 4 * h;
-            if (col < d.m && c < r) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + c] = acc[t][h];
+            for (int h = 0; h < BN; ++h)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int col = col0 + 16 * t + 4 * v + mk, c = 16 * h + mi;
+                    if (col < d.m && c < r) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + c] = accw[t][h][v];
+                }
+        } else {
+            const int col = col0 + 16 * t + dcol;
+#pragma unroll
+            for (int h = 0; h < BN; ++h) {
+                const int c = mc + 4 * h;
+                if (col < d.m && c < r) ws[d.qpart_off + ((int64_t)it.b * d.m + col) * r + c] = acc[t][h];
+            }
         }
     }
 }
