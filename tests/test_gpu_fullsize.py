@@ -1,0 +1,206 @@
+"""Parity at the benchmark's full size: the `large` workload (1.31 G elements, rank 32, bf16 gradients),
+in the launch configuration `bench.py` times, checked on sampled outputs that the oracle can compute
+one by one from the inputs the library saw (downloaded from the device):
+
+  * sampled rows of the raw P of the step's first stage,
+  * the whole orthonormal factor of sampled matrices (orthonormal, same span as the raw P),
+  * sampled rows of Q+ (each needs one column of the gradient and of the error state),
+  * the new error state of sampled rows (quantiser) or sampled buckets (count sketch), computed by the
+    oracle from the library's own factors.
+
+Inputs are the benchmark's device-side generators; the step checked is the second one, so that the error
+state it decodes is not zero.
+"""
+import numpy as np
+import pytest
+
+from paper_2312_08538_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MATS = [0, 3, 4, 94]                  # 50304 x 2048, 2048 x 8192, 8192 x 2048, 2048 x 2048
+ROWS_PER_MAT = 3
+COLS_PER_MAT = 3
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import conef_ref as R
+    from paper_2312_08538_amd import binding as B
+    import parity_util as U
+
+    B.lib()
+    return R, B, U, torch
+
+
+def _rows(rng, n, k):
+    return sorted(set([0, n - 1] + [int(x) for x in rng.integers(0, n, k)]))
+
+
+def _grad_rows(torch, buf, off, m, rows):
+    """bf16 gradient rows as uint16 bit patterns, shape (len(rows), m)."""
+    idx = torch.tensor(rows, device=buf.device)
+    g = buf[off:].view(torch.int16)[: (max(rows) + 1) * m].view(-1, m)[idx]
+    return g.cpu().numpy().view(np.uint16)
+
+
+def _grad_col(torch, buf, off, n, m, k):
+    return buf[off:off + n * m].view(torch.int16).view(n, m)[:, k].cpu().numpy().view(np.uint16)
+
+
+def test_large_quantiser_step_on_sampled_outputs(env):
+    R, B, U, torch = env
+    w = wl.WORKLOADS["large"]
+    bits, block, rank, W = w.bits, w.block, w.rank, 32 // w.bits
+    model = B.Model(w.layout, rank, bits, block, w.grad_dtype, w.lib_seed)
+    buf = model.alloc()
+    st = model.stream_handle()
+    goffs = [o["grad_off"] for o in model.offsets]
+    wl.device_q0(w, buf["Q"], [o["q_off"] for o in model.offsets])
+    wl.device_fill_gradients(w, 0, buf["grads"], goffs)
+    print("[fullsize quantiser] step 0", flush=True)
+    model.step(buf, 0)
+    wl.device_fill_gradients(w, 1, buf["grads"], goffs)
+    torch.cuda.synchronize()
+    codes0, scales0, Q0 = buf["codes"].clone(), buf["scales"].clone(), buf["Q"].clone()
+    print("[fullsize quantiser] step 1, stage by stage", flush=True)
+    B.conef_step_p(model.ctx, buf["grads"], buf["codes"], buf["scales"], buf["Q"], buf["P"], buf["ws"], st)
+    torch.cuda.synchronize()
+    Praw = buf["P"].clone()
+    B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"], st)
+    B.conef_step_q(model.ctx, buf["grads"], buf["codes"], buf["scales"], buf["P"], buf["Q"], buf["ws"], st)
+    B.conef_step_err(model.ctx, buf["grads"], buf["codes"], buf["scales"], buf["P"], buf["Q"], buf["ws"], 1, st)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2024)
+    inv_s = np.float32(1.0 / R.levels(bits))
+    for l in MATS:
+        n, m = w.layout[l]
+        o = model.offsets[l]
+        Qs = Q0[o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+        Pr = Praw[o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+        Ph = buf["P"][o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+        Qn = buf["Q"][o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+        # the orthonormal factor: orthonormal columns, and the raw P lies in its span
+        G = Ph.astype(np.float64).T @ Ph.astype(np.float64)
+        assert np.abs(G - np.eye(rank)).max() <= 1e-5, f"mat {l}: P^ not orthonormal"
+        proj = Ph.astype(np.float64) @ (Ph.astype(np.float64).T @ Pr.astype(np.float64))
+        assert np.abs(proj - Pr).max() <= 1e-5 * np.abs(Pr).max(), f"mat {l}: raw P outside the span of P^"
+        rows = _rows(rng, n, ROWS_PER_MAT)
+        g_rows = _grad_rows(torch, buf["grads"], o["grad_off"], m, rows)
+        for gi, i in enumerate(rows):
+            wo, so = o["word_off"] + i * m // W, o["scale_off"] + i * m // block
+            c_old = codes0[wo:wo + m // W].cpu().numpy().view(np.uint32)
+            s_old = scales0[so:so + m // block].cpu().numpy()
+            p = R.form_p(g_rows[gi:gi + 1], c_old, s_old, bits, block)              # 1 x m, fp32
+            # raw P row
+            want = p.astype(np.float64) @ Qs.astype(np.float64)
+            assert np.abs(Pr[i] - want[0]).max() <= 2e-2 * np.abs(Pr).max(), f"mat {l} row {i}: raw P"
+            assert np.abs(Pr[i] - want[0]).max() <= 1e-5 * np.abs(Pr).max(), f"mat {l} row {i}: raw P (achieved level)"
+            # new error state of the row from the library's own factors
+            x = R.residual(p, Ph[i:i + 1], Qn)
+            draws = np.array([R.rand16(w.lib_seed, l, 1, i * m + k) for k in range(m)], np.uint16)
+            c_want, s_want = R.quantise(x, bits, block, draw=draws)
+            c_got = buf["codes"][wo:wo + m // W].cpu().numpy().view(np.uint32)
+            s_got = buf["scales"][so:so + m // block].cpu().numpy()
+            # the matrix-core family forms the residual from fp32-exact operand splits with fp32 accumulation:
+            # its value differs from the fma chain by ~1e-6 of the reconstruction's terms
+            rec = (np.abs(Ph[i:i + 1]).astype(np.float64) @ np.abs(Qn).astype(np.float64).T).ravel()
+            blk_rec = rec.reshape(-1, block).max(1)
+            assert np.all(np.abs(s_got - s_want) <= 1e-6 * np.maximum(s_want, blk_rec) + 1e-30), f"mat {l} row {i}: scales"
+            qg, qw = U.unpack(c_got, m, bits), U.unpack(c_want, m, bits)
+            bad = np.nonzero(qg != qw)[0]
+            assert bad.size <= max(2, int(2e-3 * m)), f"mat {l} row {i}: {bad.size} of {m} codes differ"
+            assert np.all(np.abs(qg[bad] - qw[bad]) == 1), f"mat {l} row {i}: a code differs by more than one level"
+        # sampled rows of Q+ (columns of p)
+        for k in _rows(rng, m, COLS_PER_MAT):
+            gk = wl.bf16_bits_to_f32(_grad_col(torch, buf["grads"], o["grad_off"], n, m, k))
+            j = np.arange(n, dtype=np.int64) * m + k
+            words = codes0[o["word_off"]:o["word_off"] + n * m // W][torch.from_numpy(j // W).cuda()].cpu().numpy().view(np.uint32)
+            f = (words >> (bits * (j % W)).astype(np.uint32)) & np.uint32((1 << bits) - 1)
+            q = np.where(f >= (1 << (bits - 1)), f.astype(np.int64) - (1 << bits), f.astype(np.int64))
+            sc = scales0[o["scale_off"]:o["scale_off"] + n * m // block][torch.from_numpy(j // block).cuda()].cpu().numpy()
+            d = sc * inv_s                                                  # fp32 product, as in the decode
+            pk = (d.astype(np.float64) * q + gk.astype(np.float64)).astype(np.float32)     # one rounding (the product is exact)
+            want = pk.astype(np.float64) @ Ph.astype(np.float64)
+            assert np.abs(Qn[k] - want).max() <= 1e-5 * np.abs(Qn).max(), f"mat {l} column {k}: Q+"
+    model.close()
+
+
+def test_large_count_sketch_step_on_sampled_outputs(env):
+    R, B, U, torch = env
+    w = wl.WORKLOADS["large"]
+    rank, beta, keep = w.rank, 0.9, 0.2
+    ws = wl.sketch_rows(w.layout, keep)
+    model = B.SketchModel(w.layout, ws, rank, beta, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+    buf = model.alloc()
+    st = B.Model.stream_handle()
+    goffs = [o["grad_off"] for o in model.offsets]
+    wl.device_q0(w, buf["Q"], [o["q_off"] for o in model.offsets])
+    wl.device_fill_gradients(w, 0, buf["grads"], goffs)
+    print("[fullsize sketch] step 0", flush=True)
+    model.step(buf)
+    wl.device_fill_gradients(w, 1, buf["grads"], goffs)
+    torch.cuda.synchronize()
+    table0, Q0 = buf["table"].clone(), buf["Q"].clone()
+    print("[fullsize sketch] step 1, stage by stage", flush=True)
+    B.conef_cs_step_p(model.ctx, buf["grads"], buf["table"], buf["Q"], buf["P"], buf["ws"], st)
+    torch.cuda.synchronize()
+    Praw = buf["P"].clone()
+    B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"], st)
+    B.conef_cs_step_q(model.ctx, buf["grads"], buf["table"], buf["P"], buf["Q"], buf["ws"], st)
+    B.conef_cs_step_err(model.ctx, buf["grads"], buf["table"], buf["P"], buf["Q"], buf["ws"], st)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4048)
+
+    def table_rows(t, off, m, rows):
+        idx = torch.tensor(rows, device=t.device)
+        return t[off:].view(torch.int16)[: (max(rows) + 1) * m].view(-1, m)[idx].cpu().numpy().view(np.uint16)
+
+    for l in MATS:
+        n, m = w.layout[l]
+        o = model.offsets[l]
+        bucket, sign = R.cs_hash(w.lib_seed, l, n, ws[l])
+        Qs = Q0[o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+        Pr = Praw[o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+        Ph = buf["P"][o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+        Qn = buf["Q"][o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+        G = Ph.astype(np.float64).T @ Ph.astype(np.float64)
+        assert np.abs(G - np.eye(rank)).max() <= 1e-5, f"mat {l}: P^ not orthonormal"
+        # raw P of sampled rows
+        rows = _rows(rng, n, ROWS_PER_MAT)
+        g_rows = _grad_rows(torch, buf["grads"], o["grad_off"], m, rows)
+        t_rows = table_rows(table0, o["table_off"], m, [int(bucket[i]) for i in rows])
+        for gi, i in enumerate(rows):
+            p = R.cs_form_p(g_rows[gi:gi + 1], t_rows[gi:gi + 1], np.zeros(1, np.int32), sign[i:i + 1], beta)
+            want = p.astype(np.float64) @ Qs.astype(np.float64)
+            assert np.abs(Pr[i] - want[0]).max() <= 1e-5 * np.abs(Pr).max(), f"mat {l} row {i}: raw P"
+        # Q+ of sampled columns
+        for k in _rows(rng, m, COLS_PER_MAT):
+            gk = wl.bf16_bits_to_f32(_grad_col(torch, buf["grads"], o["grad_off"], n, m, k))
+            tk = table0[o["table_off"]:o["table_off"] + ws[l] * m].view(ws[l], m)[:, k].float().cpu().numpy()
+            e = tk[bucket] * sign.astype(np.float32)
+            omb = np.float32(1.0) - np.float32(beta)
+            pk = (np.float64(omb) * e.astype(np.float64) + gk.astype(np.float64)).astype(np.float32)   # one rounding
+            want = pk.astype(np.float64) @ Ph.astype(np.float64)
+            assert np.abs(Qn[k] - want).max() <= 1e-5 * np.abs(Qn).max(), f"mat {l} column {k}: Q+"
+        # the new table row of sampled buckets from the library's own factors: bit for bit
+        counts = np.bincount(bucket, minlength=ws[l])
+        some = sorted(set([0, ws[l] - 1, int(np.argmax(counts))] + [int(x) for x in rng.integers(0, ws[l], 3)]))
+        for b in some:
+            members = np.nonzero(bucket == b)[0]                       # ascending rows
+            old = table_rows(table0, o["table_off"], m, [b])
+            new = old.copy()
+            if members.size:
+                gm = _grad_rows(torch, buf["grads"], o["grad_off"], m, [int(i) for i in members])
+                zero = np.zeros(members.size, np.int32)
+                p = R.cs_form_p(gm, old, zero, sign[members], beta)
+                x = R.residual(p, Ph[members], Qn)
+                R.cs_update(x, zero, sign[members], beta, new)
+            else:
+                R.cs_update(np.zeros((1, m), np.float32), np.zeros(1, np.int32), np.ones(1, np.int8), beta, new)
+            got = table_rows(buf["table"], o["table_off"], m, [b])
+            assert np.array_equal(got, new), f"mat {l} bucket {b} ({members.size} rows): {(got != new).sum()} entries differ"
+    model.close()
