@@ -14,6 +14,7 @@
  *         line 6   Delta = Q(p)             gradient compressor: rank-r PowerSGD
  *         lines 7-8  x+ = x - Delta         decompress and apply (one worker: the aggregate is Delta)
  *         line 9   e+ = C(p - Delta)        error compressor: stochastic quantiser
+ *   - Section 4.3, Algorithm 4 (partial ConEF): p = eta*g + (1-beta) e, e+ = C(beta e + p - Delta).
  *   - Section 4.2.1, eq. (3): C(e_i) = ||e|| * sign(e_i) * xi_i, xi_i in
  *     {l/s, (l+1)/s}, rounded up with probability |e_i|/||e|| * s - l, with the
  *     l2 norm replaced by the max-norm (Section 5.1, RQ1), taken per block.
@@ -131,6 +132,20 @@ void ref_form_p(const void *g, int dtype, const uint32_t *codes, const float *sc
     #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < N; ++j) {
         float d = step_size(scales[j / block], bits);
+        p[j] = fmaf(d, (float)ref_get_code(codes, j, bits), widen(g, dtype, j));
+    }
+}
+
+/* Algorithm 4 (partial ConEF) line 5 with the same decode: p_j = fma(omb * d_blk, q_j, g_j) with
+ * omb = fl32(1 - beta); the product omb * d_blk is rounded to fp32 first.  beta = 0 gives ref_form_p
+ * bit for bit (d * 1 = d).                                                                          */
+void ref_form_p_partial(const void *g, int dtype, const uint32_t *codes, const float *scales,
+                        int64_t N, int bits, int block, float beta, float *p)
+{
+    const float omb = 1.0f - beta;
+    #pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+        float d = step_size(scales[j / block], bits) * omb;
         p[j] = fmaf(d, (float)ref_get_code(codes, j, bits), widen(g, dtype, j));
     }
 }
@@ -311,6 +326,28 @@ void ref_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int r, int 
     ref_orthonormalise(P_out, n, r);
     ref_lowrank_Q(p, n, m, P_out, r, Q_out);
     /* all-reduce point 2 (mean of Q over workers): identity for one worker */
+    ref_residual(p, n, m, P_out, Q_out, r, x);
+    ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);
+}
+
+/* One step of partial ConEF (Section 4.3, Algorithm 4) with the quantiser as error compressor:
+ *   line 5   p = g + (1 - beta) e                 (ref_form_p_partial)
+ *   line 6   Delta = P^ Q+^T from p
+ *   line 9   e+ = C(beta e + p - Delta); beta e + p is g + e, formed as in ref_form_p (one fma), not
+ *            as the sum of two rounded parts.
+ * `work` holds 2*n*m floats.  beta = 0 is ref_step_matrix bit for bit.                              */
+void ref_step_matrix_partial(const void *g, int dtype, int64_t n, int64_t m, int r, int bits, int block,
+                             float beta, uint64_t seed, uint32_t mat, uint64_t step,
+                             uint32_t *codes, float *scales, const float *Q_state,
+                             float *P_out, float *Q_out, float *work)
+{
+    const int64_t N = n * m;
+    float *p = work, *x = work + N;
+    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);
+    ref_lowrank_P(p, n, m, Q_state, r, P_out);
+    ref_orthonormalise(P_out, n, r);
+    ref_lowrank_Q(p, n, m, P_out, r, Q_out);
+    ref_form_p(g, dtype, codes, scales, N, bits, block, p);          /* g + e */
     ref_residual(p, n, m, P_out, Q_out, r, x);
     ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);
 }

@@ -55,6 +55,11 @@ def lib() -> ctypes.CDLL:
         L.ref_decode.restype = None
         L.ref_form_p.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp]
         L.ref_form_p.restype = None
+        L.ref_form_p_partial.argtypes = [vp, i32, vp, vp, i64, i32, i32, ctypes.c_float, vp]
+        L.ref_form_p_partial.restype = None
+        L.ref_step_matrix_partial.argtypes = [vp, i32, i64, i64, i32, i32, i32, ctypes.c_float, u64, u32, u64,
+                                              vp, vp, vp, vp, vp, vp]
+        L.ref_step_matrix_partial.restype = None
         L.ref_lowrank_P.argtypes = [vp, i64, i64, vp, i32, vp]
         L.ref_lowrank_P.restype = None
         L.ref_orthonormalise.argtypes = [vp, i64, i32]
@@ -163,6 +168,16 @@ def form_p(g, codes, scales, bits: int, block: int) -> np.ndarray:
     return p.reshape(g.shape)
 
 
+def form_p_partial(g, codes, scales, bits: int, block: int, beta: float) -> np.ndarray:
+    """Algorithm 4 line 5: g + (1 - beta) decode(codes, scales)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    c, s = _c(codes, np.uint32), _c(scales, np.float32)
+    p = np.empty(N, np.float32)
+    lib().ref_form_p_partial(_p(ga), dt, _p(c), _p(s), N, bits, block, beta, _p(p))
+    return p.reshape(g.shape)
+
+
 def quantise(x, bits: int, block: int, seed: int = 0, mat: int = 0, step: int = 0, draw=None):
     """eq. (3) with block max-norm.  Returns (codes uint32[n_words], scales float32[n_blocks])."""
     xa = _c(x, np.float32).ravel()
@@ -257,6 +272,20 @@ def step_matrix(g, st: MatState, rank: int, bits: int, block: int, seed: int, ma
     work = np.empty(2 * n * m, np.float32)
     lib().ref_step_matrix(_p(ga), dt, n, m, rank, bits, block, seed, mat, step,
                           _p(st.codes), _p(st.scales), _p(st.Q), _p(P), _p(Qn), _p(work))
+    st.Q = Qn
+    return P, Qn
+
+
+def step_matrix_partial(g, st: MatState, rank: int, bits: int, block: int, beta: float, seed: int, mat: int, step: int):
+    """One partial-ConEF step (Algorithm 4) with the quantiser; updates `st`; returns (Phat, Qn)."""
+    ga, dt = grad_array(g)
+    n, m = st.n, st.m
+    assert ga.size == n * m and st.Q.shape == (m, rank)
+    P = np.empty((n, rank), np.float32)
+    Qn = np.empty((m, rank), np.float32)
+    work = np.empty(2 * n * m, np.float32)
+    lib().ref_step_matrix_partial(_p(ga), dt, n, m, rank, bits, block, beta, seed, mat, step,
+                                  _p(st.codes), _p(st.scales), _p(st.Q), _p(P), _p(Qn), _p(work))
     st.Q = Qn
     return P, Qn
 

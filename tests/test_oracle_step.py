@@ -157,3 +157,45 @@ def test_workload_shapes_one_small_matrix_each(ref, name):
         assert abs((x ** 2).sum() - (np2 - (Qn.astype(np.float64) ** 2).sum())) <= 1e-5 * np2
         q = ref.unpack_codes(st.codes, n * m, w.bits)
         assert np.abs(q).max() <= ref.levels(w.bits)
+
+
+# ------------------------------------------------------------------ partial ConEF with the quantiser (Algorithm 4)
+def test_partial_step_with_beta_zero_is_the_plain_step(ref):
+    rng = np.random.default_rng(61)
+    n, m, r, bits, block = 40, 96, 3, 4, 32
+    Q0 = rng.standard_normal((m, r)).astype(np.float32)
+    a = ref.MatState.fresh(n, m, bits, block, Q0)
+    b = ref.MatState.fresh(n, m, bits, block, Q0)
+    for t in range(3):
+        g = (rng.standard_normal((n, m)) * 0.1).astype(np.float32)
+        Pa, Qa = ref.step_matrix(g, a, r, bits, block, 9, 2, t)
+        Pb, Qb = ref.step_matrix_partial(g, b, r, bits, block, 0.0, 9, 2, t)
+        assert np.array_equal(Pa, Pb) and np.array_equal(Qa, Qb)
+        assert np.array_equal(a.codes, b.codes) and np.array_equal(a.scales, b.scales)
+
+
+@pytest.mark.parametrize("beta", [0.5, 0.9])
+def test_partial_step_follows_algorithm_4(ref, beta):
+    """p = g + (1 - beta) e feeds the compressor (factors against numpy in fp64); the error compressor sees
+    beta e + p - Delta = g + e - Delta: every decoded entry of the new state lies within one quantisation
+    step of it (the bound of stochastic rounding, eq. (3)); with p - Delta instead it would miss by ~beta |e|."""
+    rng = np.random.default_rng(62)
+    n, m, r, bits, block = 48, 64, 2, 8, 64
+    st = ref.MatState.fresh(n, m, bits, block, rng.standard_normal((m, r)).astype(np.float32))
+    for t in range(4):
+        g = (rng.standard_normal((n, m)) * 0.1).astype(np.float32)
+        e = ref.decode(st.codes, st.scales, n * m, bits, block).reshape(n, m).astype(np.float64)
+        Q = st.Q.astype(np.float64)
+        Ph, Qn = ref.step_matrix_partial(g, st, r, bits, block, beta, 5, 0, t)
+        p = g.astype(np.float64) + (1.0 - beta) * e
+        P64, Rr = np.linalg.qr(p @ Q)
+        P64 = P64 * np.sign(np.diag(Rr))
+        Q64 = p.T @ P64
+        assert np.abs(Ph - P64).max() < 2e-5 and np.abs(Qn - Q64).max() < 2e-5 * max(1.0, np.abs(Q64).max())
+        x = g.astype(np.float64) + e - P64 @ Q64.T
+        e_new = ref.decode(st.codes, st.scales, n * m, bits, block).reshape(n, m).astype(np.float64)
+        step = np.repeat(st.scales.astype(np.float64) / ref.levels(bits), block)[: n * m].reshape(n, m)
+        assert np.all(np.abs(e_new - x) <= step * (1 + 1e-4) + 1e-6)
+        if t > 0:
+            # the planted alternative (quantising p - Delta) is far outside that bound
+            assert np.abs(e_new - (p - P64 @ Q64.T)).max() > 10 * step.max()
