@@ -98,6 +98,14 @@ int conef_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float
                    const float *P_hat, const float *Q_new, void *workspace, uint64_t step,
                    void *hip_stream);                             /* err <- C(g + e - P^ Q+^T)      */
 
+/* Partial ConEF (Section 4.3, Algorithm 4): only the share (1 - beta) of the stored error is added to the
+ * gradient before compression, the rest stays in the error:
+ *   line 5   p  = g + (1 - beta) e          used by the P and Q+ stages (step size of a block times fl32(1 - beta))
+ *   line 9   e+ = C(beta e + p - Delta)     = C(g + e - Delta): the err stage forms g + e as before
+ * beta in [0, 1); 0 (the value after conef_init) is Algorithm 2.  Host-side setting, takes effect for the calls
+ * enqueued after it; also changes the beta of a count-sketch context.  Errors: CONEF_EINVAL. */
+int conef_set_beta(conef_ctx *ctx, float beta);
+
 /* e := 0 for the whole model (zero codes and scales), enqueued on the stream. */
 int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream);
 

@@ -20,7 +20,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
            "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
            "conef_apply_update", "conef_destroy",
-           "conef_strerror",
+           "conef_strerror", "conef_set_beta",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
@@ -56,6 +56,7 @@ def lib() -> ctypes.CDLL:
     L.conef_set_timing.argtypes = [vp, i32]
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.conef_check_plan.argtypes = [vp]
+    L.conef_set_beta.argtypes = [vp, ctypes.c_float]
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
     L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
     L.conef_cs_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), ctypes.POINTER(ctypes.c_int64), i32, i32,
@@ -116,6 +117,10 @@ def conef_sizes(ctx) -> dict:
     _check(lib().conef_sizes(ctx, *[ctypes.byref(x) for x in v]), "conef_sizes")
     keys = ["grad_elems", "code_words", "n_scales", "p_elems", "q_elems", "workspace_bytes"]
     return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+def conef_set_beta(ctx, beta: float) -> None:
+    _check(lib().conef_set_beta(ctx, beta), "conef_set_beta")
 
 
 def conef_check_plan(ctx) -> None:

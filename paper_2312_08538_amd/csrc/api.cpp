@@ -200,6 +200,16 @@ int conef_cs_hash(const conef_ctx *ctx, int mat, int32_t *bucket_out, int8_t *si
     return CONEF_OK;
 }
 
+int conef_set_beta(conef_ctx *ctx, float beta)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (!(beta >= 0.0f && beta < 1.0f)) return CONEF_EINVAL;
+    ctx->plan.beta = beta;
+    ctx->dev.beta = beta;
+    ctx->dev.omb = 1.0f - beta;
+    return CONEF_OK;
+}
+
 int conef_check_plan(const conef_ctx *ctx)
 {
     if (!ctx) return CONEF_EINVAL;

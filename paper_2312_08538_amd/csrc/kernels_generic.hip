@@ -11,14 +11,16 @@ namespace conef {
 
 namespace {
 
-// p_j = fma(d_blk, q_j, g_j): Algorithm 2 line 5 with the decode of eq. (3) fused in.
+// p_j = fma(omb * d_blk, q_j, g_j): Algorithm 2 line 5 with the decode of eq. (3) fused in.  omb is
+// 1 - beta of the partial update (Algorithm 4 line 5) in the P and Q+ passes and 1 in the err pass,
+// whose argument beta e + p - Delta is g + e - Delta; omb = 1 leaves the step size as it is.
 __device__ __forceinline__ float form_p(const MatDesc &d, const void *grads, const uint32_t *codes,
-                                        const float *scales, int dtype, int bits, int block, int64_t j)
+                                        const float *scales, int dtype, int bits, int block, int64_t j, float omb)
 {
     const int W = 32 / bits;
     const uint32_t w = codes[d.word_off + j / W];
     const int q = code_field(w, (int)(j % W), bits);
-    const float step = scales[d.scale_off + j / block] * inv_levels(bits);
+    const float step = scales[d.scale_off + j / block] * inv_levels(bits) * omb;
     return __builtin_fmaf(step, (float)q, load_grad(grads, dtype, d.grad_off + j));
 }
 
@@ -55,7 +57,7 @@ __global__ __launch_bounds__(256) void k_pass_p_generic(DevicePlan dp, const voi
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
     for (int64_t k = lane; k < d.m; k += 64) {
-        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, row * d.m + k);
+        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, row * d.m + k, dp.omb);
         const float *qrow = Q + d.q_off + k * r;
 #pragma unroll
         for (int c = 0; c < RP; ++c)
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, con
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
     for (int64_t i = row0; i < row1; ++i) {
-        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, i * d.m + k);
+        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, i * d.m + k, dp.omb);
         const float *prow = Phat + d.p_off + i * r;
 #pragma unroll
         for (int c = 0; c < RP; ++c)
@@ -122,7 +124,7 @@ __device__ __forceinline__ float residual_at(const DevicePlan &dp, const MatDesc
 {
     const int r = dp.rank;
     const int64_t i = j / d.m, k = j - i * d.m;
-    const float pv = form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, j);
+    const float pv = form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, j, 1.0f);
     const float *prow = Phat + d.p_off + i * r;
     const float *qrow = Qn + d.q_off + k * r;
     float acc = 0.0f;

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         if (((k0 + kStage) & 127) == 0) {
             // end of a scale block: fold the code part in with this row's step size
             const float blk_scale = ss[my_row_in_tile * kSStride + ((k0 >> 7) & 31)];
-            const float dstep = (my_row < d.n) ? blk_scale * inv_levels(4) : 0.0f;
+            const float dstep = (my_row < d.n) ? blk_scale * inv_levels(4) * dp.omb : 0.0f;      // omb: 1 - beta (Algorithm 4 line 5)
             const double dd = (double)dstep;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -473,7 +473,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
         if (with_p) store_split(sb + frow * 32 + fcg * 8, pv);
-        const float dstep = row_ok ? r.sc * inv_levels(4) : 0.0f;
+        const float dstep = row_ok ? r.sc * inv_levels(4) * dp.omb : 0.0f;        // omb: 1 - beta (Algorithm 4 line 5)
         float dp8[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) dp8[j] = dstep * pv[j];

@@ -60,8 +60,9 @@ __device__ __forceinline__ RawOctet<BF16, BITS> load_octet_always(const MatDesc 
     return r;
 }
 
+// omb: 1 - beta of the partial update in the P and Q+ passes (Algorithm 4 line 5), 1 in the err pass
 template <bool BF16, int BITS>
-__device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, float p[8])
+__device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, float omb, float p[8])
 {
     float g[8];
     if (BF16) {
@@ -76,7 +77,7 @@ __device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, floa
         g[3] = __uint_as_float(r.g0.w); g[4] = __uint_as_float(r.g1.x); g[5] = __uint_as_float(r.g1.y);
         g[6] = __uint_as_float(r.g1.z); g[7] = __uint_as_float(r.g1.w);
     }
-    const float step = r.scale * inv_levels(BITS);
+    const float step = r.scale * inv_levels(BITS) * omb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         int q;
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
     // One row of this lane: decode, residual, block max-norm, rounding, store.
     auto process = [&](const RawOctet<BF16, BITS> &oct, const float (&ph)[RP], int row, bool valid) {
         float x[8];
-        decode_octet<BF16, BITS>(oct, x);
+        decode_octet<BF16, BITS>(oct, 1.0f, x);
         float a = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -285,7 +286,7 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 #pragma unroll
         for (int s = 0; s < kLoads; ++s) {
             float p[8];
-            decode_octet<BF16, BITS>(cur.o[s], p);
+            decode_octet<BF16, BITS>(cur.o[s], dp.omb, p);
             float4 *dst = reinterpret_cast<float4 *>(T + (lrow + 8 * s) * kQTilePitch + loct * 8);
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
@@ -497,7 +498,7 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
             }
             o.scale = sstage[rr * kScalePitch + ((oc << 3) >> lb)];
             float p[8];
-            decode_octet<BF16, BITS>(o, p);
+            decode_octet<BF16, BITS>(o, dp.omb, p);
             float4 *dst = reinterpret_cast<float4 *>(T + rr * kTileStride + loct * 8);
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);

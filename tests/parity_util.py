@@ -67,16 +67,19 @@ def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step
 class OracleModel:
     """The oracle run over a list of matrices, keeping per-matrix state."""
 
-    def __init__(self, layout, rank, bits, block, seed, Q0s):
-        self.layout, self.rank, self.bits, self.block, self.seed = layout, rank, bits, block, seed
+    def __init__(self, layout, rank, bits, block, seed, Q0s, beta=0.0):
+        self.layout, self.rank, self.bits, self.block, self.seed, self.beta = layout, rank, bits, block, seed, beta
         self.states = [R.MatState.fresh(n, m, bits, block, Q0) for (n, m), Q0 in zip(layout, Q0s)]
 
     def step(self, grads, step):
         """grads: list of per-matrix arrays.  Returns per matrix (Phat, Qn, residual x)."""
         out = []
         for l, (g, st) in enumerate(zip(grads, self.states)):
-            p = R.form_p(g.reshape(st.n, st.m), st.codes, st.scales, self.bits, self.block)
-            Ph, Qn = R.step_matrix(g, st, self.rank, self.bits, self.block, self.seed, l, step)
+            p = R.form_p(g.reshape(st.n, st.m), st.codes, st.scales, self.bits, self.block)      # g + e
+            if self.beta == 0.0:
+                Ph, Qn = R.step_matrix(g, st, self.rank, self.bits, self.block, self.seed, l, step)
+            else:
+                Ph, Qn = R.step_matrix_partial(g, st, self.rank, self.bits, self.block, self.beta, self.seed, l, step)
             x = R.residual(p, Ph, Qn).ravel()
             out.append((Ph, Qn, x))
         return out
@@ -85,11 +88,13 @@ class OracleModel:
 class GpuModel:
     """The library run over the same list of matrices through the C ABI."""
 
-    def __init__(self, layout, rank, bits, block, dtype, seed, Q0s, device="cuda:0"):
+    def __init__(self, layout, rank, bits, block, dtype, seed, Q0s, device="cuda:0", beta=0.0):
         import torch
 
         self.torch = torch
         self.m = B.Model(layout, rank, bits, block, dtype, seed)
+        if beta != 0.0:
+            B.conef_set_beta(self.m.ctx, beta)
         self.buf = self.m.alloc(device)
         self.dtype = dtype
         for l, Q0 in enumerate(Q0s):

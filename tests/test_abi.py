@@ -208,3 +208,14 @@ def test_sketch_plans_of_the_full_workloads_are_consistent():
             m = B.SketchModel(w.layout, wl.sketch_rows(w.layout, keep), w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
             B.conef_check_plan(m.ctx)
             m.close()
+
+
+def test_set_beta_validates_its_argument():
+    ctx = B.conef_init([(64, 64)], 4, 4, 64, B.F32, 0)
+    L = B.lib()
+    for bad in (-0.1, 1.0, 1.5, float("nan")):
+        assert L.conef_set_beta(ctx, bad) == B.EINVAL
+    assert L.conef_set_beta(None, 0.5) == B.EINVAL
+    for good in (0.0, 0.5, 0.999):
+        assert L.conef_set_beta(ctx, good) == B.OK
+    B.conef_destroy(ctx)

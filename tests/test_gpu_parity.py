@@ -23,7 +23,7 @@ def env():
     return R, B, U
 
 
-def _run_model(env, w, layout, steps, what, grads_fn=None, q0_fn=None, resync=True, lockstep=None):
+def _run_model(env, w, layout, steps, what, grads_fn=None, q0_fn=None, resync=True, lockstep=None, beta=0.0):
     """Runs `steps` steps of a model on both sides, comparing after every step.
 
     The kernel families that accumulate the factors in fp64 reproduce the oracle bit for bit and
@@ -36,8 +36,8 @@ def _run_model(env, w, layout, steps, what, grads_fn=None, q0_fn=None, resync=Tr
     if lockstep is None:
         lockstep = (w.rank == 32 and w.grad_dtype == wl.BF16)
     Q0s = [(q0_fn(l) if q0_fn else wl.host_q0(w, l, shape=layout[l])) for l in range(len(layout))]
-    gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
-    ora = U.OracleModel(layout, w.rank, w.bits, w.block, w.lib_seed, Q0s)
+    gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s, beta=beta)
+    ora = U.OracleModel(layout, w.rank, w.bits, w.block, w.lib_seed, Q0s, beta=beta)
     total_excused = 0
     for t in range(steps):
         grads = [(grads_fn(t, l) if grads_fn else wl.host_gradient(w, t, l, shape=layout[l]))
@@ -364,3 +364,18 @@ def test_update_after_a_step_removes_what_the_error_keeps(env):
     scales = np.repeat(gpu.mat_scales(0), w.block)[:n * m]
     assert np.all(np.abs(left - kept) <= scales / R.levels(w.bits) * (1 + 1e-6))      # at most one level apart
     assert np.max(np.abs(left)) > 0
+
+
+@pytest.mark.parametrize("name,beta", [("tiny", 0.5), ("cnn", 0.9), ("lm", 0.85), ("translation", 0.9), ("large", 0.9)])
+def test_partial_update_matches_the_oracle(env, name, beta):
+    """Partial ConEF (Algorithm 4) with the quantiser: every kernel family on cut-down shapes of its workload
+    (and two odd shapes for the kernels that take any shape), four steps, same criteria as the plain step."""
+    w = wl.WORKLOADS[name]
+    if name == "tiny":
+        layout = [(256, 128), (37, 53)]
+    elif name == "large":
+        layout = [(300, 256), (160, 384), (130, 1024)]
+    else:
+        layout = [(min(n, 192), min(m, 1024)) for n, m in list(w.layout)[:3]] + [(45, 77)]
+    layout = [(n, m) for n, m in layout if min(n, m) >= w.rank]
+    _run_model(env, w, layout, 4, f"partial-{name}", beta=beta)
