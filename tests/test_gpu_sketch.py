@@ -235,3 +235,41 @@ def test_quantiser_calls_refuse_a_sketch_context_and_back(env):
     x = torch.zeros(sk.sizes["grad_elems"], dtype=torch.float32, device="cuda:0")
     B.conef_decompress(sk.ctx, sb["P"], sb["Q"], x)
     torch.cuda.synchronize()
+
+
+def test_sketch_step_is_reproducible_and_replays_from_a_hip_graph(env):
+    """After the first call on a context a count-sketch step only enqueues kernels, in a fixed summation
+    order: two runs give the same bits, and a captured step replayed three times (with eager work and
+    synchronisations in between) gives the bits of the eager step on the same inputs."""
+    R, B, U, torch = env
+    for layout, ws, rank, gdt, fp16 in [([(300, 256), (130, 384)], [60, 26], 32, wl.BF16, True),
+                                        ([(64, 147), (128, 576)], [13, 26], 4, wl.F32, True),
+                                        ([(200, 512)], [40], 8, wl.BF16, False)]:
+        rng = np.random.default_rng(77)
+        model = B.SketchModel(layout, ws, rank, 0.9, int(fp16), gdt, 31)
+        b = model.alloc()
+        for l, (n, m) in enumerate(layout):
+            _set_factor(torch, b, "Q", model.offsets[l]["q_off"], rng.standard_normal((m, rank)).astype(np.float32))
+        grads = [[_grad(rng, n, m, gdt) for n, m in layout] for _ in range(2)]
+        _to_dev_grads(torch, model, b, grads[0]); model.step(b)          # also uploads the work tables
+        before = {k: b[k].clone() for k in ("table", "Q")}
+        _to_dev_grads(torch, model, b, grads[1]); model.step(b)
+        torch.cuda.synchronize()
+        want = {k: b[k].clone() for k in ("table", "Q", "P")}
+        s = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        for k in before:
+            b[k].copy_(before[k])
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=s):
+            model.step(b)
+        for replay in range(3):
+            for k in before:
+                b[k].copy_(before[k])            # eager work between the replays
+            b["P"].zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for k in want:
+                assert torch.equal(b[k].view(torch.uint8), want[k].view(torch.uint8)), (layout, replay, k)
+        model.close()
