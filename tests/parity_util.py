@@ -32,21 +32,22 @@ def unpack(codes: np.ndarray, N: int, bits: int) -> np.ndarray:
     return np.where(f >= (1 << (bits - 1)), f - (1 << bits), f).astype(np.int32)
 
 
-def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what="", rec_oracle=None):
-    """Applies the boundary rule.  x_oracle: the oracle's residual (fp32, flat).  Returns the number
-    of excused mismatches.  rec_oracle (flat, sum_c |P^[i,c]| |Q+[k,c]|: the size of the terms of
-    the reconstruction) is given for the matrix-core family only: there the factors carry fp32
-    rounding, so the residual p - P^ Q+^T has an absolute error of ~1e-6 of those terms, and the
-    1e-6 window is taken relative to max(a, rec_block) instead of the block max-norm a."""
+def unpack_at(codes: np.ndarray, idx: np.ndarray, bits: int) -> np.ndarray:
+    """Signed fields of the elements `idx` only."""
+    W = 32 // bits
+    f = (codes[idx // W].astype(np.uint64) >> (bits * (idx % W)).astype(np.uint64)) & np.uint64((1 << bits) - 1)
+    f = f.astype(np.int64)
+    return np.where(f >= (1 << (bits - 1)), f - (1 << bits), f).astype(np.int32)
+
+
+def _excuse(bad, g_bad, w_bad, x_oracle, N, bits, block, seed, mat, step, what, rec_oracle, max_frac=1e-4, x_abs_tol=0.0):
+    """The boundary rule for the elements `bad` (codes g_bad on the GPU, w_bad in the oracle).  x_abs_tol: a
+    bound on the absolute difference of the two sides' residuals that comes from their factors differing
+    (whole steps on large matrices), added to the window."""
     s = R.levels(bits)
-    g = unpack(np.asarray(got_codes), N, bits)
-    w = unpack(np.asarray(want_codes), N, bits)
-    bad = np.nonzero(g != w)[0]
-    if bad.size == 0:
-        return 0
-    assert bad.size <= max(1, int(1e-4 * N)), f"{what}: {bad.size} of {N} codes differ"
-    for j in bad:
-        assert abs(int(g[j]) - int(w[j])) == 1, f"{what}: code {j} differs by more than one level"
+    assert bad.size <= max(1, int(max_frac * N)), f"{what}: {bad.size} of {N} codes differ"
+    for j, gj, wj in zip(bad, g_bad, w_bad):
+        assert abs(int(gj) - int(wj)) == 1, f"{what}: code {j} differs by more than one level"
         b0 = (j // block) * block
         xb = x_oracle[b0:min(N, b0 + block)]
         a = np.abs(xb).max()
@@ -57,11 +58,42 @@ def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step
         tol = 1e-6 * max(1.0, float(u))
         if rec_oracle is not None:
             tol *= max(1.0, float(np.abs(rec_oracle[b0:min(N, b0 + block)]).max()) / float(a))
+        tol += x_abs_tol * float(inv)
         near_draw = abs(f + xi - 1.0) <= tol          # rounded up exactly when fraction + draw / 2^16 >= 1
         near_grid = abs(float(u) - round(float(u))) <= tol
         assert near_draw or near_grid, (f"{what}: code {j} differs although the pre-rounding value is not near a "
                                         f"boundary (u={u}, f={f}, xi={xi})")
     return int(bad.size)
+
+
+def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what="", rec_oracle=None):
+    """Applies the boundary rule.  x_oracle: the oracle's residual (fp32, flat).  Returns the number
+    of excused mismatches.  rec_oracle (flat, sum_c |P^[i,c]| |Q+[k,c]|: the size of the terms of
+    the reconstruction) is given for the matrix-core family only: there the factors carry fp32
+    rounding, so the residual p - P^ Q+^T has an absolute error of ~1e-6 of those terms, and the
+    1e-6 window is taken relative to max(a, rec_block) instead of the block max-norm a."""
+    g = unpack(np.asarray(got_codes), N, bits)
+    w = unpack(np.asarray(want_codes), N, bits)
+    bad = np.nonzero(g != w)[0]
+    if bad.size == 0:
+        return 0
+    return _excuse(bad, g[bad], w[bad], x_oracle, N, bits, block, seed, mat, step, what, rec_oracle)
+
+
+def check_codes_sparse(got_codes, want_codes, x_of, N, bits, block, seed, mat, step, what="", rec_of=None, x_abs_tol=0.0):
+    """check_codes for large matrices: code words are compared packed, and only the fields of differing
+    words are unpacked; x_of() / rec_of() are called only if something differs."""
+    got_codes, want_codes = np.asarray(got_codes), np.asarray(want_codes)
+    diffw = np.nonzero(got_codes != want_codes)[0]
+    if diffw.size == 0:
+        return 0
+    W = 32 // bits
+    idx = (diffw[:, None].astype(np.int64) * W + np.arange(W, dtype=np.int64)[None, :]).ravel()
+    idx = idx[idx < N]
+    g, w = unpack_at(got_codes, idx, bits), unpack_at(want_codes, idx, bits)
+    sel = g != w
+    return _excuse(idx[sel], g[sel], w[sel], x_of(), N, bits, block, seed, mat, step, what,
+                   rec_of() if rec_of is not None else None, x_abs_tol=x_abs_tol)
 
 
 class OracleModel:

@@ -204,3 +204,67 @@ def test_large_count_sketch_step_on_sampled_outputs(env):
             got = table_rows(buf["table"], o["table_off"], m, [b])
             assert np.array_equal(got, new), f"mat {l} bucket {b} ({members.size} rows): {(got != new).sum()} entries differ"
     model.close()
+
+
+def test_large_whole_model_second_step_against_the_oracle(env):
+    """Every matrix of `large`, whole: the library's second step (fused call, the launch configuration of the
+    benchmark) against one oracle step started from the state the library itself held before that step
+    (downloaded), on the gradients the library read.  Factors, scales and every code of all 1.31 G elements
+    are compared with the criteria of the matrix-core family (see parity_util.compare_step)."""
+    R, B, U, torch = env
+    w = wl.WORKLOADS["large"]
+    bits, block, rank, W = w.bits, w.block, w.rank, 32 // w.bits
+    model = B.Model(w.layout, rank, bits, block, w.grad_dtype, w.lib_seed)
+    buf = model.alloc()
+    goffs = [o["grad_off"] for o in model.offsets]
+    wl.device_q0(w, buf["Q"], [o["q_off"] for o in model.offsets])
+    wl.device_fill_gradients(w, 0, buf["grads"], goffs)
+    print("[fullsize whole model] step 0", flush=True)
+    model.step(buf, 0)
+    wl.device_fill_gradients(w, 1, buf["grads"], goffs)
+    torch.cuda.synchronize()
+    codes0, scales0, Q0 = buf["codes"].cpu().numpy().view(np.uint32), buf["scales"].cpu().numpy(), buf["Q"].cpu().numpy()
+    print("[fullsize whole model] step 1", flush=True)
+    model.step(buf, 1)
+    torch.cuda.synchronize()
+    codes1, scales1 = buf["codes"].cpu().numpy().view(np.uint32), buf["scales"].cpu().numpy()
+    P1, Q1 = buf["P"].cpu().numpy(), buf["Q"].cpu().numpy()
+    excused = 0
+    for l, (n, m) in enumerate(w.layout):
+        o = model.offsets[l]
+        N = n * m
+        g = buf["grads"][o["grad_off"]:o["grad_off"] + N].view(torch.int16).cpu().numpy().view(np.uint16).reshape(n, m)
+        nw, nb = N // W, N // block
+        c0 = codes0[o["word_off"]:o["word_off"] + nw].copy()
+        s0 = scales0[o["scale_off"]:o["scale_off"] + nb].copy()
+        st = R.MatState(n, m, c0.copy(), s0.copy(), Q0[o["q_off"]:o["q_off"] + m * rank].reshape(m, rank).copy())
+        Ph, Qn = R.step_matrix(g, st, rank, bits, block, w.lib_seed, l, 1)
+        tag = f"large mat {l} ({n}x{m})"
+        eP = U.rel_err(P1[o["p_off"]:o["p_off"] + n * rank].reshape(n, rank), Ph)
+        eQ = U.rel_err(Q1[o["q_off"]:o["q_off"] + m * rank].reshape(m, rank), Qn)
+        assert eP <= 1e-5, f"{tag}: P rel err {eP}"
+        assert eQ <= 1e-5, f"{tag}: Q+ rel err {eQ}"
+        # The two sides' factors differ by eP, eQ (relative to the largest entry), so their residuals differ by
+        # at most sum_c |dP^[i,c]| |Q+[k,c]| + |P^[i,c]| |dQ+[k,c]|:
+        x_tol = float(eP * np.abs(Ph).max() * np.abs(Qn).sum(1).max() + eQ * np.abs(Qn).max() * np.abs(Ph).sum(1).max())
+
+        def rec_of():
+            return (np.abs(Ph).astype(np.float64) @ np.abs(Qn).astype(np.float64).T).astype(np.float32).ravel()
+
+        def x_of():
+            return R.residual(R.form_p(g, c0, s0, bits, block), Ph, Qn).ravel()
+
+        gs = scales1[o["scale_off"]:o["scale_off"] + nb]
+        dev = np.abs(gs - st.scales)
+        if dev.max() > 0:
+            blk_rec = rec_of().reshape(-1, block).max(1)
+            worst = float((dev / (1e-6 * np.maximum(st.scales, blk_rec) + x_tol)).max())
+            assert worst <= 1.0, f"{tag}: scales off by {worst} times the tolerance"
+        ex = U.check_codes_sparse(codes1[o["word_off"]:o["word_off"] + nw], st.codes, x_of, N, bits, block,
+                                  w.lib_seed, l, 1, tag, rec_of=rec_of, x_abs_tol=x_tol)
+        excused += ex
+        if l < 6 or ex:
+            print(f"[fullsize whole model] {tag}: eP {eP:.1e} eQ {eQ:.1e} max scale deviation {dev.max():.2e} "
+                  f"(x_tol {x_tol:.1e}), {ex} codes differ", flush=True)
+    print(f"[fullsize whole model] {excused} codes of {w.elements} excused as boundary cases", flush=True)
+    model.close()
