@@ -253,7 +253,8 @@ __device__ __forceinline__ void form_p_octet(const SketchOctet<BF16, F16> &o, fl
 constexpr int kCsSubCols = 32, kCsStepCols = 128, kCsTileStride = 36;
 
 template <bool BF16, bool F16, int RH>
-__global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RH >= 8 ? 2 : 3)))
+void k_cs_p_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
                                                     const float *__restrict__ Q, float *P, double *ws)
 {
     __shared__ __attribute__((aligned(16))) float tiles[4][kPTileRows * kCsTileStride];
@@ -410,7 +411,8 @@ __global__ __launch_bounds__(256) void k_cs_p_octet(DevicePlan dp, const void *_
 constexpr int kCsQTileCols = 64, kCsQTilePitch = 80, kCsQStepRows = 32;
 
 template <bool BF16, bool F16, int RH>
-__global__ __launch_bounds__(256) void k_cs_q_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RH >= 8 ? 2 : 3)))
+void k_cs_q_octet(DevicePlan dp, const void *__restrict__ grads, const void *__restrict__ table,
                                                     const float *__restrict__ Phat, double *ws)
 {
     __shared__ __attribute__((aligned(16))) float tiles[4][kCsQStepRows * kCsQTilePitch];
