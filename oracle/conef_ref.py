@@ -19,6 +19,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conef_ref.c")
 _SRC_SKETCH = os.path.join(_HERE, "sketch_ref.c")
+_SRC_RB = os.path.join(_HERE, "randblock_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -27,10 +28,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_SKETCH))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_SKETCH), os.path.getmtime(_SRC_RB))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -94,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.ref_cs_update.restype = None
         L.ref_cs_step_matrix.argtypes = [vp, i32, i64, i64, i32, i64, f32, u64, u32, vp, i32, vp, vp, vp, vp]
         L.ref_cs_step_matrix.restype = None
+        L.ref_rb_start.argtypes = [u64, u32, u64, i64, i64]
+        L.ref_rb_start.restype = i64
+        L.ref_rb_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, f32, u64, u32, u64, vp, vp, vp, vp]
+        L.ref_rb_step_matrix.restype = None
+        L.ref_cs_rb_step_matrix.argtypes = [vp, i32, i64, i64, i64, i64, f32, u64, u32, u64, vp, i32, vp, vp]
+        L.ref_cs_rb_step_matrix.restype = None
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -388,3 +395,31 @@ def cs_step_matrix(g, st: SketchState, rank: int, beta: float, seed: int, mat: i
                              _p(st.table), tt, _p(st.Q), _p(P), _p(Qn), _p(work))
     st.Q = Qn
     return P, Qn
+
+
+# ---------------------------------------------------------------- random-block gradient compressor (oracle/randblock_ref.c)
+def rb_start(seed: int, mat: int, step: int, N: int, k: int) -> int:
+    return int(lib().ref_rb_start(seed, mat, step, N, k))
+
+
+def rb_step_matrix(g, codes, scales, k: int, bits: int, block: int, beta: float, seed: int, mat: int, step: int):
+    """One step with the random-block compressor and the quantiser; codes/scales updated in place; returns Delta (k values)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    assert codes.dtype == np.uint32 and scales.dtype == np.float32 and codes.flags.c_contiguous and scales.flags.c_contiguous
+    delta = np.empty(k, np.float32)
+    work = np.empty(2 * N, np.float32)
+    lib().ref_rb_step_matrix(_p(ga), dt, N, k, bits, block, beta, seed, mat, step, _p(codes), _p(scales), _p(delta), _p(work))
+    return delta
+
+
+def cs_rb_step_matrix(g, table, k: int, beta: float, seed: int, mat: int, step: int):
+    """The same with the count sketch; `table` (w x m) updated in place; returns Delta."""
+    ga, dt = grad_array(g)
+    n, m = g.shape
+    _, tt = table_array(table)
+    assert table.flags.c_contiguous and table.shape[1] == m
+    delta = np.empty(k, np.float32)
+    work = np.empty(n * m, np.float32)
+    lib().ref_cs_rb_step_matrix(_p(ga), dt, n, m, k, table.shape[0], beta, seed, mat, step, _p(table), tt, _p(delta), _p(work))
+    return delta
