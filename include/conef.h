@@ -170,6 +170,29 @@ int conef_cs_step_err(conef_ctx *ctx, const void *grads, void *table, const floa
 /* e_out (fp32, laid out like an fp32 gradient buffer) <- the estimate of the error.  For tests and export. */
 int conef_cs_decode_error(conef_ctx *ctx, const void *table, float *e_out, void *hip_stream);
 
+/* ---- Unscaled random-block gradient compressor (Section 5.3) in place of the rank-r one, with either error
+ * compressor.  Per matrix and step a block of keep[l] consecutive coordinates of the flat row-major index is
+ * kept, the same on every worker that uses the same seed, so the kept values can be all-reduced as they are:
+ *   p     = g + (1 - beta) e                              (Algorithm 2 / 4 line 5; beta from conef_set_beta / conef_cs_init)
+ *   Delta = p on [start, start + keep), nothing elsewhere  (line 6; delta_out receives the keep values)
+ *   e+    = C(beta e + p - Delta)                          (line 9: g + e outside the block, beta e inside it; for the
+ *                                                          count sketch, table <- beta table + C(p - Delta))
+ * start = floor(r (rows cols - keep + 1) / 2^64), r = out[0] + 2^32 out[1] of the Philox4x32-10 call with counter
+ * (l, 0xFFFFFFFF, lo32(step), hi32(step)) and the context's key; conef_rb_start returns it (host).
+ * conef_rb_configure  host only; keep[n_mats] with 1 <= keep[l] <= rows*cols; may be called again to change them
+ * delta_out           device, out: flat fp32, matrix l at delta_off of conef_rb_offsets (multiples of 64), keep[l] values
+ * conef_rb_step is for quantiser contexts, conef_cs_rb_step for count-sketch contexts; CONEF_ESTATE on the other
+ * kind or before conef_rb_configure.  Pointers, alignment, asynchrony and errors as for conef_step; the error
+ * state is updated in place. */
+int conef_rb_configure(conef_ctx *ctx, const int64_t *keep);
+int conef_rb_sizes(const conef_ctx *ctx, size_t *delta_elems);
+int conef_rb_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *keep);
+int conef_rb_start(const conef_ctx *ctx, int mat, uint64_t step, int64_t *start);
+int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, float *delta_out,
+                  uint64_t step, void *hip_stream);
+int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
+                     void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

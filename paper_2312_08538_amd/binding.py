@@ -21,6 +21,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
            "conef_apply_update", "conef_destroy",
            "conef_strerror", "conef_set_beta",
+           "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
@@ -57,6 +58,12 @@ def lib() -> ctypes.CDLL:
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.conef_check_plan.argtypes = [vp]
     L.conef_set_beta.argtypes = [vp, ctypes.c_float]
+    L.conef_rb_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rb_sizes.argtypes = [vp, szp]
+    L.conef_rb_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rb_start.argtypes = [vp, i32, u64, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rb_step.argtypes = [vp, vp, vp, vp, vp, u64, vp]
+    L.conef_cs_rb_step.argtypes = [vp, vp, vp, vp, u64, vp]
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
     L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
     L.conef_cs_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), ctypes.POINTER(ctypes.c_int64), i32, i32,
@@ -117,6 +124,39 @@ def conef_sizes(ctx) -> dict:
     _check(lib().conef_sizes(ctx, *[ctypes.byref(x) for x in v]), "conef_sizes")
     keys = ["grad_elems", "code_words", "n_scales", "p_elems", "q_elems", "workspace_bytes"]
     return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+# random-block gradient compressor
+def conef_rb_configure(ctx, keep: Sequence[int]) -> None:
+    arr = (ctypes.c_int64 * max(1, len(keep)))(*[int(x) for x in keep])
+    _check(lib().conef_rb_configure(ctx, arr), "conef_rb_configure")
+
+
+def conef_rb_sizes(ctx) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_rb_sizes(ctx, ctypes.byref(v)), "conef_rb_sizes")
+    return {"delta_elems": int(v.value)}
+
+
+def conef_rb_offsets(ctx, mat: int) -> dict:
+    off, k = ctypes.c_size_t(), ctypes.c_int64()
+    _check(lib().conef_rb_offsets(ctx, mat, ctypes.byref(off), ctypes.byref(k)), "conef_rb_offsets")
+    return {"delta_off": int(off.value), "keep": int(k.value)}
+
+
+def conef_rb_start(ctx, mat: int, step: int) -> int:
+    v = ctypes.c_int64()
+    _check(lib().conef_rb_start(ctx, mat, step, ctypes.byref(v)), "conef_rb_start")
+    return int(v.value)
+
+
+def conef_rb_step(ctx, grads, err_codes, err_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_rb_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(delta_out), step, stream),
+           "conef_rb_step")
+
+
+def conef_cs_rb_step(ctx, grads, table, delta_out, step: int, stream=0):
+    _check(lib().conef_cs_rb_step(ctx, _ptr(grads), _ptr(table), _ptr(delta_out), step, stream), "conef_cs_rb_step")
 
 
 def conef_set_beta(ctx, beta: float) -> None:

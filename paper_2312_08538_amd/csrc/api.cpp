@@ -18,6 +18,7 @@ struct conef_ctx {
     Plan plan;
     DevicePlan dev;
     bool uploaded = false;
+    bool rb_uploaded = false;       // the random-block tables and per-matrix fields are on the device
     int device = -1;
     std::vector<void *> device_allocs;
     // stage timing: a ring of kTimingSlots event sets (8 events: begin/end of the 4 stages)
@@ -100,6 +101,23 @@ int ensure_uploaded(conef_ctx *ctx)
     d.rank = pl.rank; d.rpad = pl.rpad; d.bits = pl.bits; d.block = pl.block; d.dtype = pl.dtype;
     d.seed_lo = (uint32_t)pl.seed; d.seed_hi = (uint32_t)(pl.seed >> 32);
     ctx->uploaded = true;
+    return CONEF_OK;
+}
+
+// Uploads what conef_rb_configure made (after ensure_uploaded): the work tables and the descriptors again,
+// which now carry the per-matrix block sizes.
+int ensure_rb_uploaded(conef_ctx *ctx)
+{
+    if (ctx->rb_uploaded) return CONEF_OK;
+    const Plan &pl = ctx->plan;
+    DevicePlan &d = ctx->dev;
+    int rc;
+    if ((rc = upload(ctx, pl.mats, &d.mats))) return rc;
+    if ((rc = upload(ctx, pl.rb_items, &d.rb_items))) return rc;
+    if ((rc = upload(ctx, pl.rb_g_items, &d.rb_g_items))) return rc;
+    d.n_rb = (int)pl.rb_items.size();
+    d.n_rb_g = (int)pl.rb_g_items.size();
+    ctx->rb_uploaded = true;
     return CONEF_OK;
 }
 
@@ -359,6 +377,66 @@ int conef_decode_error(conef_ctx *ctx, const uint32_t *err_codes, const float *e
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     return hip_rc(launch_decode(ctx->dev, err_codes, err_scales, e_out, static_cast<hipStream_t>(hip_stream)));
+}
+
+// ---------------------------------------------------------------- random-block gradient compressor
+int conef_rb_configure(conef_ctx *ctx, const int64_t *keep)
+{
+    if (!ctx || !keep) return CONEF_EINVAL;
+    int rc = configure_random_block(ctx->plan, keep);
+    if (rc) return rc;
+    ctx->rb_uploaded = false;       // (the previous device copies stay allocated until the context is destroyed)
+    return CONEF_OK;
+}
+
+int conef_rb_sizes(const conef_ctx *ctx, size_t *delta_elems)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    if (delta_elems) *delta_elems = ctx->plan.rb_delta_elems;
+    return CONEF_OK;
+}
+
+int conef_rb_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *keep)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    if (delta_off) *delta_off = (size_t)ctx->plan.mats[mat].rb_delta_off;
+    if (keep) *keep = ctx->plan.mats[mat].rb_k;
+    return CONEF_OK;
+}
+
+int conef_rb_start(const conef_ctx *ctx, int mat, uint64_t step, int64_t *start)
+{
+    if (!ctx || !start || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    const MatDesc &d = ctx->plan.mats[mat];
+    *start = random_block_start(ctx->plan.seed, (uint32_t)mat, step, d.N, d.rb_k);
+    return CONEF_OK;
+}
+
+int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, float *delta_out,
+                  uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !delta_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch || ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(delta_out, 4))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !delta_out) return CONEF_EINVAL;
+    if (!ctx->plan.sketch || ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(delta_out, 4)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, static_cast<hipStream_t>(hip_stream)));
 }
 
 // ---------------------------------------------------------------- count-sketch mode

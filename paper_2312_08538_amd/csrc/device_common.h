@@ -55,6 +55,18 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// First coordinate of the block the random-block gradient compressor keeps of a matrix of N elements
+// (k of them) at a step: floor(r (N - k + 1) / 2^64) with r the first 64 bits of the Philox call with counter
+// (matrix, ~0, step), which no element draw uses (their second word is a matrix index).
+__device__ __forceinline__ int64_t random_block_start(uint32_t mat, uint32_t step_lo, uint32_t step_hi, uint32_t seed_lo,
+                                                      uint32_t seed_hi, int64_t N, int64_t k)
+{
+    uint32_t out[4];
+    philox4x32_10(mat, 0xFFFFFFFFu, step_lo, step_hi, seed_lo, seed_hi, out);
+    const uint64_t r = (uint64_t)out[0] | ((uint64_t)out[1] << 32);
+    return (int64_t)__umul64hi(r, (uint64_t)(N - k + 1));
+}
+
 // 16-bit draw of element j from the four output words of the call that covers j>>3.
 __device__ __forceinline__ uint32_t draw16(const uint32_t out[4], int j_low3)
 {

@@ -14,6 +14,9 @@ struct DevicePlan {
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *upd_items = nullptr;                                                   // decompress / update
+    // random-block gradient compressor
+    const WorkItem *rb_items = nullptr, *rb_g_items = nullptr;
+    int n_rb = 0, n_rb_g = 0;
     // count-sketch mode
     const WorkItem *cs_err_items = nullptr, *cs_err_f_items = nullptr;
     const int32_t *row_hash = nullptr, *bucket_ptr = nullptr, *bucket_rows = nullptr;
@@ -50,6 +53,14 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
                            hipStream_t st, Span span = Span());
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
+// Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
+hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
+                          uint64_t step, hipStream_t st);
+hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
+                             hipStream_t st);
+void octet_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta, uint64_t step,
+                   hipStream_t st);
+
 // Count-sketch mode: the same three passes with a table as the error state.
 hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P,
                             double *ws, hipStream_t st, Span span = Span());

@@ -174,6 +174,62 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
     }
 }
 
+// ---------------------------------------------------------------- random-block gradient compressor
+// Section 5.3, any layout: one wave per scale block, two sweeps as in the err pass.  The argument of the error
+// compressor is g + e outside the kept block [start, start + k) and beta e inside it; the kept values
+// p = g + (1 - beta) e go to the Delta buffer (first sweep only).
+__device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
+                                             const float *scales, int64_t j, int64_t start, float *delta, bool write)
+{
+    const int W = 32 / dp.bits;
+    const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
+    const float dstep = scales[d.scale_off + j / dp.block] * inv_levels(dp.bits);
+    const float g = load_grad(grads, dp.dtype, d.grad_off + j);
+    if (j >= start && j < start + d.rb_k) {
+        if (write) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
+        return dp.beta * (dstep * (float)q);
+    }
+    return __builtin_fmaf(dstep, (float)q, g);
+}
+
+__global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *grads, uint32_t *codes, float *scales,
+                                                    float *delta, uint32_t step_lo, uint32_t step_hi)
+{
+    const WorkItem it = dp.rb_g_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bits = dp.bits, W = 32 / bits, B = dp.block;
+    const float s_f = (float)((1 << (bits - 1)) - 1);
+    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    for (int t = 0; t < it.b; ++t) {
+        const int64_t blk = (int64_t)it.a + wave + 4 * t;
+        if (blk >= d.nblk) break;                                   // uniform per wave
+        const int64_t j0 = blk * B;
+        const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
+        float a = 0.0f;
+        for (int e = lane; e < cnt; e += 64)
+            a = fmaxf(a, fabsf(rb_argument(dp, d, grads, codes, scales, j0 + e, start, delta, true)));
+        a = wave_max(a);
+        const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
+        const int sweeps = (cnt + 63) / 64;
+        for (int sw = 0; sw < sweeps; ++sw) {
+            const int e = sw * 64 + lane;
+            uint32_t field = 0;
+            if (e < cnt && a > 0.0f) {
+                const int64_t j = j0 + e;
+                const float x = rb_argument(dp, d, grads, codes, scales, j, start, delta, false);
+                uint32_t out[4];
+                philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
+            }
+            // every lane of the wave has computed its argument before any word of the sweep is stored
+            for (int o = 1; o < W; o <<= 1) field |= __shfl_xor(field, o, 64);
+            if ((lane % W) == 0 && e < cnt) codes[d.word_off + (j0 + e) / W] = field;
+        }
+        if (lane == 0) scales[d.scale_off + blk] = a;
+    }
+}
+
 // Adds the column-chunk partial sums of P in chunk order and rounds once to fp32.
 __global__ __launch_bounds__(256) void k_p_reduce(DevicePlan dp, const double *ws, float *P)
 {
@@ -294,6 +350,16 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     octet_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     generic_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     if (span.end) (void)hipEventRecord(span.end, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
+                          uint64_t step, hipStream_t st)
+{
+    octet_rb_step(dp, grads, codes, scales, delta, step, st);
+    if (dp.n_rb_g > 0)
+        hipLaunchKernelGGL(k_rb_generic, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+                           (uint32_t)step, (uint32_t)(step >> 32));
     return hipGetLastError();
 }
 

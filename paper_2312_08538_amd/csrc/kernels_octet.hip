@@ -549,7 +549,93 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     }
 }
 
+// ------------------------------------------------------------------ random-block gradient compressor
+// Section 5.3: Delta keeps the k consecutive coordinates [start, start + k) of p = g + (1 - beta) e and nothing
+// else; the error compressor then takes beta e + p - Delta: g + e outside the block (the fma of the other
+// passes), beta e inside it.  One streaming pass: a wave walks runs of 64 octets (512 elements) of the flat
+// index; scale blocks of 8 * 2^j elements never straddle a run.  Decode, select, block max-norm by DPP,
+// stochastic rounding, pack, in place; the kept values go to the Delta buffer.
+template <bool BF16, int BITS>
+__global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
+                                                  float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi)
+{
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_rb) return;
+    const WorkItem it = dp.rb_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    const int64_t stop = start + d.rb_k;
+    const float s_f = (float)((1 << (BITS - 1)) - 1);
+    const uint32_t mask = (1u << BITS) - 1u;
+    RawOctet<BF16, BITS> cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, (int64_t)it.a * 64 + lane);
+    for (int rr = 0; rr < it.b; ++rr) {
+        const int64_t o = ((int64_t)it.a + rr) * 64 + lane;
+        const RawOctet<BF16, BITS> r = cur;
+        // the next run is requested before this one is worked on (the last one re-reads itself)
+        cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, o + (rr + 1 < it.b ? 64 : 0));
+        float g[8];
+        if (BF16) {
+            const uint32_t w[4] = {r.g0.x, r.g0.y, r.g0.z, r.g0.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                g[2 * i] = __uint_as_float(w[i] << 16);
+                g[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+        } else {
+            g[0] = __uint_as_float(r.g0.x); g[1] = __uint_as_float(r.g0.y); g[2] = __uint_as_float(r.g0.z);
+            g[3] = __uint_as_float(r.g0.w); g[4] = __uint_as_float(r.g1.x); g[5] = __uint_as_float(r.g1.y);
+            g[6] = __uint_as_float(r.g1.z); g[7] = __uint_as_float(r.g1.w);
+        }
+        const float dstep = r.scale * inv_levels(BITS);
+        const float dpart = dstep * dp.omb;
+        float x[8];
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int q;
+            if (BITS == 8) q = code_field(e < 4 ? r.c0 : r.c1, e & 3, 8);
+            else q = code_field(r.c0, e, BITS);
+            const float qf = (float)q;
+            const int64_t j = o * 8 + e;
+            if (j >= start && j < stop) {
+                delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
+                x[e] = dp.beta * (dstep * qf);
+            } else {
+                x[e] = __builtin_fmaf(dstep, qf, g[e]);
+            }
+            a = fmaxf(a, fabsf(x[e]));
+        }
+        a = block_max(a, d.lb_shift);
+        const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+        uint32_t f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16, draw16(rnd, e), mask);
+        store_codes<BITS>(d, codes, o, f);
+        if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
+    }
+}
+
 }  // namespace
+
+void octet_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta, uint64_t step,
+                   hipStream_t st)
+{
+    if (dp.n_rb <= 0) return;
+    const dim3 grid((dp.n_rb + 3) / 4);
+    const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+    switch ((dp.dtype << 8) | dp.bits) {
+    case (0 << 8) | 2: hipLaunchKernelGGL((k_rb_octet<false, 2>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    case (0 << 8) | 4: hipLaunchKernelGGL((k_rb_octet<false, 4>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    case (0 << 8) | 8: hipLaunchKernelGGL((k_rb_octet<false, 8>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    case (1 << 8) | 2: hipLaunchKernelGGL((k_rb_octet<true, 2>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    case (1 << 8) | 4: hipLaunchKernelGGL((k_rb_octet<true, 4>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    case (1 << 8) | 8: hipLaunchKernelGGL((k_rb_octet<true, 8>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+    default: break;
+    }
+}
 
 #define CONEF_OCTET_CASE(KERNEL, BF, B, R, GRID, ST, ...) \
     case ((BF ? 1 : 0) << 8) | (B << 4) | R: hipLaunchKernelGGL((KERNEL<BF, B, R>), GRID, dim3(256), 0, ST, __VA_ARGS__); break;

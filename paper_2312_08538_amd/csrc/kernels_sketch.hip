@@ -701,6 +701,115 @@ __global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, co
     }
 }
 
+// ------------------------------------------------------------------ random-block gradient compressor
+// Section 5.3 with the count sketch: Delta keeps p = g + (1 - beta) e on the coordinates [start, start + k) of the
+// flat index, and by linearity S <- beta S + C(p - Delta) with p - Delta equal to p outside the block and 0
+// inside.  Same walk of the bucket lists as the update pass above, without the factors.
+template <bool BF16, bool F16>
+__global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
+                                                    float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi)
+{
+    const int lane = threadIdx.x;
+    const WorkItem it = dp.cs_err_f_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t colw = (int64_t)it.c * 512 + lane * 8;
+    const bool active = colw < d.m;
+    const int64_t col = active ? colw : 0;
+    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    const int64_t stop = start + d.rb_k;
+    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
+    const int32_t *rows = dp.bucket_rows + d.hash_off;
+    const int b_end = it.a + it.b;
+    const int32_t e_end = ptr[b_end];
+    int32_t e = ptr[it.a];
+    // gradient octet of the next list entry and table octet of the next bucket, requested ahead
+    SketchOctet<BF16, F16> nxt = load_sketch_octet<BF16, F16>(grads, table,
+        d.grad_off + (int64_t)(rows[e < e_end ? e : 0] & INT32_MAX) * d.m + col, d.table_off + (int64_t)it.a * d.m + col);
+    for (int b = it.a; b < b_end; ++b) {
+        float s_old[8], acc[8];
+        widen_table_octet<F16>(nxt.t0, nxt.t1, s_old);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+        const int32_t e_stop = ptr[b + 1];
+        const int bn = b + 1 < b_end ? b + 1 : b;
+        if (e >= e_stop) {
+            // an empty bucket: only the table octet of the next one is needed
+            nxt = load_sketch_octet<BF16, F16>(grads, table, d.grad_off + (int64_t)(rows[e < e_end ? e : 0] & INT32_MAX) * d.m + col,
+                                               d.table_off + (int64_t)bn * d.m + col);
+        }
+        for (; e < e_stop; ++e) {
+            const int32_t hv = rows[e];
+            const int64_t i = hv & INT32_MAX;
+            float g[8];
+            widen_grad_octet<BF16>(nxt.g0, nxt.g1, g);
+            const int32_t en = e + 1 < e_end ? e + 1 : e;
+            // the table octet requested here is the next bucket's; it is consumed when this bucket is done
+            nxt = load_sketch_octet<BF16, F16>(grads, table, d.grad_off + (int64_t)(rows[en] & INT32_MAX) * d.m + col,
+                                               d.table_off + (int64_t)bn * d.m + col);
+            const float somb = hv < 0 ? -dp.omb : dp.omb;
+            const int64_t j0 = i * d.m + col;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float pv = __builtin_fmaf(somb, s_old[j], g[j]);
+                const bool inside = j0 + j >= start && j0 + j < stop;
+                if (inside && active) delta[d.rb_delta_off + (j0 + j - start)] = pv;
+                const float x = inside ? 0.0f : pv;
+                acc[j] = hv < 0 ? acc[j] - x : acc[j] + x;
+            }
+        }
+        if (active) {
+            float out[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                out[j] = __builtin_fmaf(dp.beta, s_old[j], acc[j]);
+                if (F16) asm volatile("" : "+v"(out[j]));       // fp32 rounding first, then the conversion (see the update pass)
+            }
+            const int64_t te = d.table_off + (int64_t)b * d.m + col;
+            if (F16) {
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    w[j] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j]) |
+                           ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)out[2 * j + 1]) << 16);
+                const u32x4 v = {w[0], w[1], w[2], w[3]};
+                *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(table) + te) = v;
+            } else {
+                float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(table) + te);
+                dst[0] = make_float4(out[0], out[1], out[2], out[3]);
+                dst[1] = make_float4(out[4], out[5], out[6], out[7]);
+            }
+        }
+    }
+}
+
+// The same for any shape: one thread per column of a 256-column tile.
+__global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const void *grads, void *table, float *delta,
+                                                           uint32_t step_lo, uint32_t step_hi)
+{
+    const WorkItem it = dp.cs_err_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t k = (int64_t)it.c * kCsCols + threadIdx.x;
+    if (k >= d.m) return;
+    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
+    const int32_t *rows = dp.bucket_rows + d.hash_off;
+    for (int b = it.a; b < it.a + it.b; ++b) {
+        const int64_t tidx = d.table_off + (int64_t)b * d.m + k;
+        const float s_old = table_load(table, dp.table_dtype, tidx);
+        float acc = 0.0f;
+        for (int32_t e = ptr[b]; e < ptr[b + 1]; ++e) {
+            const int32_t hv = rows[e];
+            const int64_t j = (int64_t)(hv & INT32_MAX) * d.m + k;
+            const float pv = __builtin_fmaf(signed_omb(dp, hv), s_old, load_grad(grads, dp.dtype, d.grad_off + j));
+            const bool inside = j >= start && j < start + d.rb_k;
+            if (inside) delta[d.rb_delta_off + (j - start)] = pv;
+            const float x = inside ? 0.0f : pv;
+            acc = hv < 0 ? acc - x : acc + x;
+        }
+        table_store(table, dp.table_dtype, tidx, __builtin_fmaf(dp.beta, s_old, acc));
+    }
+}
+
 }  // namespace
 
 #define CONEF_CS_DISPATCH_RP(KERNEL, GRID, BLOCK, ST, ...)                                        \
@@ -781,6 +890,23 @@ hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *tab
     if (dp.n_cs_err > 0)
         CONEF_CS_DISPATCH_RP(k_cs_update_generic, dim3(dp.n_cs_err), dim3(kCsCols), st, dp, grads, table, Phat, Qn);
     if (span.end) (void)hipEventRecord(span.end, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
+                             hipStream_t st)
+{
+    const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+    if (dp.n_cs_err_f > 0) {
+        const dim3 grid(dp.n_cs_err_f);
+        const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;
+        if (bf && fh) hipLaunchKernelGGL((k_cs_rb_octet<true, true>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
+        else if (bf) hipLaunchKernelGGL((k_cs_rb_octet<true, false>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
+        else if (fh) hipLaunchKernelGGL((k_cs_rb_octet<false, true>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
+        else hipLaunchKernelGGL((k_cs_rb_octet<false, false>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
+    }
+    if (dp.n_cs_err > 0)
+        hipLaunchKernelGGL(k_cs_rb_generic, dim3(dp.n_cs_err), dim3(kCsCols), 0, st, dp, grads, table, delta, lo, hi);
     return hipGetLastError();
 }
 

@@ -31,10 +31,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
     return make_plan_impl(plan, rows, cols, n_mats, rank, bits, block, dtype, seed, false);
 }
 
-void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative)
+namespace {
+// Philox4x32-10 (Salmon et al., SC'11) on the host, for the set-up values the library derives from the seed
+void host_philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint64_t seed, uint32_t out[4])
 {
-    // Philox4x32-10 (Salmon et al., SC'11), counter (row, matrix, ~0, ~0): the counter of a step no run reaches
-    uint32_t c0 = row, c1 = mat, c2 = 0xFFFFFFFFu, c3 = 0xFFFFFFFFu;
     uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     for (int round = 0; round < 10; ++round) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
@@ -42,8 +42,61 @@ void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *
         c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
         k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
     }
-    *bucket = (int32_t)(((uint64_t)c0 * (uint64_t)w) >> 32);
-    *negative = (c1 & 1u) != 0;
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+}  // namespace
+
+void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative)
+{
+    // counter (row, matrix, ~0, ~0): the counter of a step no run reaches
+    uint32_t out[4];
+    host_philox4x32_10(row, mat, 0xFFFFFFFFu, 0xFFFFFFFFu, seed, out);
+    *bucket = (int32_t)(((uint64_t)out[0] * (uint64_t)w) >> 32);
+    *negative = (out[1] & 1u) != 0;
+}
+
+int64_t random_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t k)
+{
+    // counter (matrix, ~0, step): no element draw uses it (their second word is a matrix index)
+    uint32_t out[4];
+    host_philox4x32_10(mat, 0xFFFFFFFFu, (uint32_t)step, (uint32_t)(step >> 32), seed, out);
+    const uint64_t r = (uint64_t)out[0] | ((uint64_t)out[1] << 32);
+    return (int64_t)(((unsigned __int128)r * (unsigned __int128)(uint64_t)(N - k + 1)) >> 64);
+}
+
+int configure_random_block(Plan &plan, const int64_t *keep)
+{
+    if (!keep) return kEinval;
+    const int n_mats = (int)plan.mats.size();
+    for (int l = 0; l < n_mats; ++l)
+        if (keep[l] < 1 || keep[l] > plan.mats[l].N) return kEinval;
+    try {
+        int64_t off = 0;
+        plan.rb_items.clear();
+        plan.rb_g_items.clear();
+        // the wave-per-run kernel needs whole blocks of 8 * 2^j elements (j <= 6) that fill the matrix
+        const bool block_ok = plan.block % 8 == 0 && is_pow2(plan.block / 8) && plan.block / 8 <= 64;
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            d.rb_k = keep[l];
+            d.rb_delta_off = off;
+            off += round_up(keep[l], kAlign);
+            if (plan.sketch) continue;              // the count-sketch mode walks its bucket lists
+            if (block_ok && d.N % 512 == 0) {
+                d.lb_shift = log2i(plan.block / 8);
+                const int64_t runs = d.N / 512, per_item = 8;
+                for (int64_t r0 = 0; r0 < runs; r0 += per_item)
+                    plan.rb_items.push_back({l, (int32_t)r0, (int32_t)std::min<int64_t>(per_item, runs - r0), 0});
+            } else {
+                const int32_t per_wave = d.nblk <= 16384 ? 1 : 16;
+                for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave) plan.rb_g_items.push_back({l, (int32_t)b0, per_wave, 0});
+            }
+        }
+        plan.rb_delta_elems = (size_t)off;
+    } catch (const std::bad_alloc &) {
+        return kEnomem;
+    }
+    return kOk;
 }
 
 int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,

@@ -52,6 +52,9 @@ struct MatDesc {
     int64_t hash_off;               // offset of the matrix's n entries in row_hash and bucket_rows
     int64_t bptr_off;               // offset of its w + 1 entries in bucket_ptr
     int32_t cs_cols;                // columns per item of the sketch update pass
+    // random-block gradient compressor
+    int64_t rb_k;                   // coordinates kept per step (0: not configured)
+    int64_t rb_delta_off;           // offset of the matrix's kept values in the flat Delta buffer
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -98,6 +101,10 @@ struct Plan {
     std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
     std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
     std::vector<WorkItem> upd_items;    // decompress / update: (mat, row tile of 64, column tile of 128)
+    // random-block gradient compressor with the quantiser (made by configure_random_block)
+    size_t rb_delta_elems = 0;
+    std::vector<WorkItem> rb_items;     // matrices of whole power-of-two blocks: (mat, first run of 512 elements, runs), one item per wave
+    std::vector<WorkItem> rb_g_items;   // any other matrix: (mat, first block, blocks per wave), 4 waves per item
 };
 
 // Checks that the work tables of each of the three passes cover every element of every matrix exactly
@@ -115,6 +122,13 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
 // bucket lists.
 int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
                      int rank, float beta, int table_dtype, int dtype, uint64_t seed);
+
+// Random-block gradient compressor: keep[l] coordinates of matrix l per step (1 .. rows * cols).  Sets the
+// per-matrix fields, the Delta layout and (for a quantiser plan) the work tables.  Returns 0 or a negative code.
+int configure_random_block(Plan &plan, const int64_t *keep);
+
+// First coordinate of the kept block of a matrix of N elements at `step` (Philox4x32-10 of (matrix, ~0, step)).
+int64_t random_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t k);
 
 // Bucket and sign of a row (Philox4x32-10 of (row, matrix) keyed by the seed).
 void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative);

@@ -96,6 +96,12 @@ def sketch_rows(layout, keep: float) -> List[int]:
     return [max(1, min(n, int(n * keep))) for n, _ in layout]
 
 
+def random_block_keep(layout, fraction: float) -> List[int]:
+    """Coordinates kept per matrix by the random-block gradient compressor: `fraction` of its elements, at
+    least one (Section 5.3 uses a tenth: "90 % communication efficiency")."""
+    return [max(1, int(n * m * fraction)) for n, m in layout]
+
+
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """fp32 -> bf16 bit patterns (uint16), round to nearest even (finite inputs)."""
     u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)

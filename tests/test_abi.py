@@ -219,3 +219,32 @@ def test_set_beta_validates_its_argument():
     for good in (0.0, 0.5, 0.999):
         assert L.conef_set_beta(ctx, good) == B.OK
     B.conef_destroy(ctx)
+
+
+# ------------------------------------------------------------------ random-block gradient compressor (host side)
+def test_random_block_layout_and_start_match_the_oracle(ref):
+    layout = [(64, 147), (512, 1024), (3, 5)]
+    keep = wl.random_block_keep(layout, 0.1)
+    assert keep == [940, 52428, 1]
+    for ctx in (B.conef_init(layout, 2, 4, 128, B.BF16, 0xC0FFEE123),
+                B.conef_cs_init(layout, [8, 100, 3], 2, 0.5, B.TABLE_F16, B.BF16, 0xC0FFEE123)):
+        L = B.lib()
+        assert L.conef_rb_sizes(ctx, None) == B.ESTATE                      # not configured yet
+        B.conef_rb_configure(ctx, keep)
+        off = 0
+        for l, (n, m) in enumerate(layout):
+            o = B.conef_rb_offsets(ctx, l)
+            assert (o["delta_off"], o["keep"]) == (off, keep[l])
+            off += (keep[l] + 63) // 64 * 64
+            for step in (0, 1, 7, 2 ** 33 + 1):
+                s = B.conef_rb_start(ctx, l, step)
+                assert s == ref.rb_start(0xC0FFEE123, l, step, n * m, keep[l])
+                assert 0 <= s <= n * m - keep[l]
+        assert B.conef_rb_sizes(ctx)["delta_elems"] == off
+        B.conef_check_plan(ctx)
+        for bad in ([0, 1, 1], [1, 1, 16]):
+            with pytest.raises(B.ConefError) as e:
+                B.conef_rb_configure(ctx, bad)
+            assert e.value.code == B.EINVAL
+        assert L.conef_rb_configure(ctx, None) == B.EINVAL
+        B.conef_destroy(ctx)
