@@ -186,6 +186,58 @@ def run_sketch(w, keep: float, beta: float, steps: int = 10, warmup: int = 3):
             "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "finite": finite}
 
 
+def run_random_block(w, fraction: float = 0.1, reps: int = 10):
+    """Times one step with the unscaled random-block gradient compressor (Section 5.3: a tenth of the coordinates
+    kept) in place of the rank-r one: with the workload's quantiser (beta = 0) and with the count sketch (fp16
+    table, keep 0.2, beta 0.9).  One streaming pass each; HIP events on the launch stream."""
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+    from paper_2312_08538_amd import workloads as wl
+
+    keep = wl.random_block_keep(w.layout, fraction)
+    G = 4 if w.grad_dtype == 0 else 2
+    out = {}
+    for kind in ("quantiser", "count_sketch"):
+        if kind == "quantiser":
+            model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(n * m * (w.bits / 8 + 4.0 / w.block) for n, m in w.layout)
+        else:
+            ws = wl.sketch_rows(w.layout, 0.2)
+            model = B.SketchModel(w.layout, ws, w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(a * m * 2 for a, (_, m) in zip(ws, w.layout))
+        B.conef_rb_configure(model.ctx, keep)
+        buf = model.alloc("cuda:0")
+        delta = torch.zeros(B.conef_rb_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
+        wl.device_fill_gradients(w, 0, buf["grads"], [o["grad_off"] for o in model.offsets])
+        st = B.Model.stream_handle()
+
+        def one(t):
+            if kind == "quantiser":
+                B.conef_rb_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
+            else:
+                B.conef_cs_rb_step(model.ctx, buf["grads"], buf["table"], delta, t, st)
+
+        for t in range(2):
+            one(t)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for t, (e0, e1) in enumerate(ev):
+            e0.record()
+            one(2 + t)
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / reps
+        nbytes = int(w.elements * G + 2 * state_bytes + 4 * sum(keep))      # gradient, state read + written, kept values
+        out[kind] = {"ms": round(ms, 4), "bytes": nbytes, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "finite": bool(torch.isfinite(delta).all())}
+        model.close()
+        del buf, delta
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_oracle_sample(w, budget_s: float = 20.0):
     """Times the oracle (as it stands) on the workload's matrices in layout order, one step from
     zero error, until about `budget_s` seconds of CPU work are spent or the whole model is done.
@@ -266,6 +318,9 @@ def main():
     ap.add_argument("--count-sketch", action="store_true",
                     help="time only the step with the count sketch as the error compressor (fp16 table, keep 0.2, "
                          "beta 0.9) on --workload and print its line; for profiling that mode on its own")
+    ap.add_argument("--random-block", action="store_true",
+                    help="time only the step with the random-block gradient compressor (a tenth of the coordinates "
+                         "kept; quantiser and count-sketch error compressors) on --workload and print its line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
                          "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
@@ -283,6 +338,12 @@ def main():
     w = wl.WORKLOADS[a.workload]
     if a.calibrate_copy:
         calibrate_copy(w)
+    if a.random_block:
+        r = run_random_block(w, 0.1, a.steps)
+        print(json.dumps({"metric": "random-block ConEF step throughput: gradient GB/s processed",
+                          "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+                          "steps": a.steps, "config": {"workload": w.name, "fraction": 0.1}, **r}), flush=True)
+        return
     if a.count_sketch:
         r = run_sketch(w, 0.2, 0.9, a.steps, a.warmup)
         print(json.dumps({"metric": "ConEF-CS step throughput: gradient GB/s processed", "value": r["grad_GB/s"],
@@ -333,6 +394,9 @@ def main():
         out["count_sketch"] = {"keep": 0.2, "beta": 0.9, "table": "f16",
                                "workloads": {name: run_sketch(wl.WORKLOADS[name], 0.2, 0.9)
                                              for name in ("cnn", "lm", "translation", "large")}}
+        # the unscaled random-block gradient compressor in place of the rank-r one (a tenth of the coordinates kept)
+        out["random_block"] = {"fraction": 0.1, "workloads": {name: run_random_block(wl.WORKLOADS[name])
+                                                              for name in ("cnn", "lm", "translation", "large")}}
     if not a.no_cpu_baseline:
         v, cores, sample = run_oracle_sample(w)
         out["cpu_baseline"] = {"value": round(v, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",

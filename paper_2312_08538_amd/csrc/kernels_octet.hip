@@ -568,12 +568,19 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
     const int64_t stop = start + d.rb_k;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     const uint32_t mask = (1u << BITS) - 1u;
-    RawOctet<BF16, BITS> cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, (int64_t)it.a * 64 + lane);
+    // The last run of a matrix may be short: octets at or beyond the end re-read the last octet and store
+    // nothing.  They make up whole scale blocks (the matrix is a whole number of blocks), so they do not
+    // enter the block maximum of a stored block.
+    const int64_t n_oct = d.N >> 3;
+    auto clamp = [&](int64_t o) { return o < n_oct ? o : n_oct - 1; };
+    RawOctet<BF16, BITS> cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, clamp((int64_t)it.a * 64 + lane));
     for (int rr = 0; rr < it.b; ++rr) {
-        const int64_t o = ((int64_t)it.a + rr) * 64 + lane;
+        const int64_t o_raw = ((int64_t)it.a + rr) * 64 + lane;
+        const bool valid = o_raw < n_oct;
+        const int64_t o = clamp(o_raw);
         const RawOctet<BF16, BITS> r = cur;
         // the next run is requested before this one is worked on (the last one re-reads itself)
-        cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, o + (rr + 1 < it.b ? 64 : 0));
+        cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, clamp(o_raw + (rr + 1 < it.b ? 64 : 0)));
         float g[8];
         if (BF16) {
             const uint32_t w[4] = {r.g0.x, r.g0.y, r.g0.z, r.g0.w};
@@ -599,7 +606,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             const float qf = (float)q;
             const int64_t j = o * 8 + e;
             if (j >= start && j < stop) {
-                delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
+                if (valid) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
                 x[e] = dp.beta * (dstep * qf);
             } else {
                 x[e] = __builtin_fmaf(dstep, qf, g[e]);
@@ -613,8 +620,10 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
         uint32_t f[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16, draw16(rnd, e), mask);
-        store_codes<BITS>(d, codes, o, f);
-        if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
+        if (valid) {
+            store_codes<BITS>(d, codes, o, f);
+            if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
+        }
     }
 }
 

@@ -74,7 +74,7 @@ int configure_random_block(Plan &plan, const int64_t *keep)
         int64_t off = 0;
         plan.rb_items.clear();
         plan.rb_g_items.clear();
-        // the wave-per-run kernel needs whole blocks of 8 * 2^j elements (j <= 6) that fill the matrix
+        // the wave-per-run kernel needs blocks of 8 * 2^j elements (j <= 6) that fill the matrix (no short last block)
         const bool block_ok = plan.block % 8 == 0 && is_pow2(plan.block / 8) && plan.block / 8 <= 64;
         for (int l = 0; l < n_mats; ++l) {
             MatDesc &d = plan.mats[l];
@@ -82,9 +82,9 @@ int configure_random_block(Plan &plan, const int64_t *keep)
             d.rb_delta_off = off;
             off += round_up(keep[l], kAlign);
             if (plan.sketch) continue;              // the count-sketch mode walks its bucket lists
-            if (block_ok && d.N % 512 == 0) {
+            if (block_ok && d.N % plan.block == 0) {
                 d.lb_shift = log2i(plan.block / 8);
-                const int64_t runs = d.N / 512, per_item = 8;
+                const int64_t runs = ceil_div(d.N, 512), per_item = 8;        // the last run may be short
                 for (int64_t r0 = 0; r0 < runs; r0 += per_item)
                     plan.rb_items.push_back({l, (int32_t)r0, (int32_t)std::min<int64_t>(per_item, runs - r0), 0});
             } else {

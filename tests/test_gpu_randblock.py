@@ -32,6 +32,7 @@ QUANTISER_CASES = [
     ([(96, 160), (33, 129)], 2, 8, 8, 0.5),
     ([(16, 64), (8, 8)], 2, 4, 200, 1.0),                          # the whole matrix is kept
     ([(300, 256), (160, 384)], 32, 4, 128, 0.001),                 # a block of a few coordinates
+    ([(77, 768), (5, 128), (129, 64)], 4, 4, 128, 0.1),            # whole blocks, short last runs of 512
 ]
 
 
