@@ -101,6 +101,10 @@ def lib() -> ctypes.CDLL:
         L.ref_rb_step_matrix.restype = None
         L.ref_cs_rb_step_matrix.argtypes = [vp, i32, i64, i64, i64, i64, f32, u64, u32, u64, vp, i32, vp, vp]
         L.ref_cs_rb_step_matrix.restype = None
+        L.ref_ss_step_matrix.argtypes = [vp, i32, i64, i32, i32, f32, u64, u32, u64, vp, vp, vp, vp]
+        L.ref_ss_step_matrix.restype = f32
+        L.ref_cs_ss_step_matrix.argtypes = [vp, i32, i64, i64, i64, f32, u64, u32, vp, i32, vp, vp]
+        L.ref_cs_ss_step_matrix.restype = f32
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -423,3 +427,28 @@ def cs_rb_step_matrix(g, table, k: int, beta: float, seed: int, mat: int, step: 
     work = np.empty(n * m, np.float32)
     lib().ref_cs_rb_step_matrix(_p(ga), dt, n, m, k, table.shape[0], beta, seed, mat, step, _p(table), tt, _p(delta), _p(work))
     return delta
+
+
+# ---------------------------------------------------------------- scaled-sign gradient compressor (oracle/randblock_ref.c)
+def ss_step_matrix(g, codes, scales, bits: int, block: int, beta: float, seed: int, mat: int, step: int):
+    """One step with the scaled-sign compressor and the quantiser; codes/scales updated in place.
+    Returns (sign words uint32[ceil(N/32)], c)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    assert codes.dtype == np.uint32 and scales.dtype == np.float32 and codes.flags.c_contiguous and scales.flags.c_contiguous
+    words = np.empty((N + 31) // 32, np.uint32)
+    work = np.empty(2 * N, np.float32)
+    c = lib().ref_ss_step_matrix(_p(ga), dt, N, bits, block, beta, seed, mat, step, _p(codes), _p(scales), _p(words), _p(work))
+    return words, np.float32(c)
+
+
+def cs_ss_step_matrix(g, table, beta: float, seed: int, mat: int):
+    """The same with the count sketch; `table` (w x m) updated in place.  Returns (sign words, c)."""
+    ga, dt = grad_array(g)
+    n, m = g.shape
+    _, tt = table_array(table)
+    assert table.flags.c_contiguous and table.shape[1] == m
+    words = np.empty((n * m + 31) // 32, np.uint32)
+    work = np.empty(n * m, np.float32)
+    c = lib().ref_cs_ss_step_matrix(_p(ga), dt, n, m, table.shape[0], beta, seed, mat, _p(table), tt, _p(words), _p(work))
+    return words, np.float32(c)

@@ -1,6 +1,7 @@
 /*
- * randblock_ref.c -- reference ("oracle") implementation of ConEF with the unscaled random-block
- * gradient compressor.
+ * randblock_ref.c -- reference ("oracle") implementation of ConEF with the two element-wise gradient
+ * compressors of the paper's experiments: unscaled random block (Section 5.3) and scaled sign (Section 5.1,
+ * at the end of this file).
  *
  * TEST INFRASTRUCTURE ONLY, like conef_ref.c and sketch_ref.c (whose routines it calls): shares no
  * code with the HIP path and is never called from it.
@@ -94,4 +95,59 @@ void ref_cs_rb_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int64
     ref_cs_update(p, n, m, bucket, sign, w, beta, table, tdtype);                /* line 9 by linearity */
     free(bucket);
     free(sign);
+}
+
+/* ------------------------------------------------------------------ */
+/* Scaled-sign gradient compressor (Section 5.1, RQ1): Q(p) = ||p||_1 / d * sign(p), per matrix (d = N).
+ * Readings: the sign of an entry is its IEEE sign bit (so +0 counts as positive: one bit per entry is
+ * sent, there is no code for 0); the l1 norm is accumulated in fp64 in index order and c = fl32(norm / N);
+ * the argument of the error compressor is beta e + p - Delta: with the quantiser (g + e) - Delta, the one
+ * fma of the other steps followed by one subtraction; with the count sketch p - Delta, sketched on top of
+ * beta S.  Outputs: the sign bits (bit j mod 32 of word j / 32, set for negative) and c.               */
+/* ------------------------------------------------------------------ */
+static float l1_scale(const float *p, int64_t N)
+{
+    double norm = 0.0;
+    for (int64_t j = 0; j < N; ++j) norm += fabs((double)p[j]);
+    return (float)(norm / (double)N);
+}
+
+float ref_ss_step_matrix(const void *g, int dtype, int64_t N, int bits, int block, float beta,
+                         uint64_t seed, uint32_t mat, uint64_t step, uint32_t *codes, float *scales,
+                         uint32_t *sign_words, float *work)
+{
+    float *p = work, *x = work + N;
+    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);       /* line 5 */
+    const float c = l1_scale(p, N);
+    ref_form_p(g, dtype, codes, scales, N, bits, block, x);                      /* g + e */
+    memset(sign_words, 0, sizeof(uint32_t) * (size_t)((N + 31) / 32));
+    for (int64_t j = 0; j < N; ++j) {
+        const int neg = signbit(p[j]) != 0;
+        if (neg) sign_words[j / 32] |= 1u << (j % 32);
+        x[j] = x[j] - (neg ? -c : c);                                            /* line 9 argument */
+    }
+    ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);
+    return c;
+}
+
+float ref_cs_ss_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int64_t w, float beta,
+                            uint64_t seed, uint32_t mat, void *table, int tdtype, uint32_t *sign_words, float *work)
+{
+    const int64_t N = n * m;
+    float *p = work;
+    int32_t *bucket = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int8_t *sign = (int8_t *)malloc((size_t)n);
+    ref_cs_hash(seed, mat, n, w, bucket, sign);
+    ref_cs_form_p(g, dtype, table, tdtype, n, m, bucket, sign, beta, p);
+    const float c = l1_scale(p, N);
+    memset(sign_words, 0, sizeof(uint32_t) * (size_t)((N + 31) / 32));
+    for (int64_t j = 0; j < N; ++j) {
+        const int neg = signbit(p[j]) != 0;
+        if (neg) sign_words[j / 32] |= 1u << (j % 32);
+        p[j] = p[j] - (neg ? -c : c);
+    }
+    ref_cs_update(p, n, m, bucket, sign, w, beta, table, tdtype);
+    free(bucket);
+    free(sign);
+    return c;
 }
