@@ -193,6 +193,27 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
                      void *hip_stream);
 
+/* ---- Scaled-sign gradient compressor (Section 5.1) in place of the rank-r one, with either error compressor:
+ *   p     = g + (1 - beta) e
+ *   Delta = c * sign(p),  c = fl32(||p||_1 / (rows cols)) per matrix       (line 6)
+ *   e+    = C(beta e + p - Delta)      quantiser: (g + e) - Delta; count sketch: table <- beta table + C(p - Delta)
+ * What a worker sends is one bit per entry and one scale per matrix:
+ *   sign_out   device, out: uint32 words, matrix l at sign_off of conef_ss_offsets (multiples of 64 words),
+ *              bit j mod 32 of word j / 32 set if entry j of p is negative (its IEEE sign bit; zeros count as
+ *              positive); conef_ss_sizes gives the length of the buffer
+ *   scale_out  device, out: n_mats floats, c of every matrix
+ * The l1 norm is a sum of fp64 partial sums taken in a fixed order (reproducible from run to run; it can differ
+ * from a sum in index order in the last bit of the fp64 value, hence, rarely, in the last bit of c).
+ * Two passes over the gradient and the error state, which is updated in place.  conef_ss_step is for
+ * quantiser contexts, conef_cs_ss_step for count-sketch contexts (CONEF_ESTATE on the other kind).
+ * Pointers, alignment, asynchrony and errors as for conef_step. */
+int conef_ss_sizes(const conef_ctx *ctx, size_t *sign_words);
+int conef_ss_offsets(const conef_ctx *ctx, int mat, size_t *sign_off);
+int conef_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *sign_out,
+                  float *scale_out, void *workspace, uint64_t step, void *hip_stream);
+int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *sign_out, float *scale_out,
+                     void *workspace, void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

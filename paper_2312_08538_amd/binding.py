@@ -21,6 +21,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
            "conef_apply_update", "conef_destroy",
            "conef_strerror", "conef_set_beta",
+           "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
@@ -58,6 +59,10 @@ def lib() -> ctypes.CDLL:
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.conef_check_plan.argtypes = [vp]
     L.conef_set_beta.argtypes = [vp, ctypes.c_float]
+    L.conef_ss_sizes.argtypes = [vp, szp]
+    L.conef_ss_offsets.argtypes = [vp, i32, szp]
+    L.conef_ss_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_cs_ss_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.conef_rb_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rb_sizes.argtypes = [vp, szp]
     L.conef_rb_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
@@ -124,6 +129,29 @@ def conef_sizes(ctx) -> dict:
     _check(lib().conef_sizes(ctx, *[ctypes.byref(x) for x in v]), "conef_sizes")
     keys = ["grad_elems", "code_words", "n_scales", "p_elems", "q_elems", "workspace_bytes"]
     return {k: int(x.value) for k, x in zip(keys, v)}
+
+
+# scaled-sign gradient compressor
+def conef_ss_sizes(ctx) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_ss_sizes(ctx, ctypes.byref(v)), "conef_ss_sizes")
+    return {"sign_words": int(v.value)}
+
+
+def conef_ss_offsets(ctx, mat: int) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_ss_offsets(ctx, mat, ctypes.byref(v)), "conef_ss_offsets")
+    return {"sign_off": int(v.value)}
+
+
+def conef_ss_step(ctx, grads, err_codes, err_scales, sign_out, scale_out, workspace, step: int, stream=0):
+    _check(lib().conef_ss_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(sign_out), _ptr(scale_out),
+                               _ptr(workspace), step, stream), "conef_ss_step")
+
+
+def conef_cs_ss_step(ctx, grads, table, sign_out, scale_out, workspace, stream=0):
+    _check(lib().conef_cs_ss_step(ctx, _ptr(grads), _ptr(table), _ptr(sign_out), _ptr(scale_out), _ptr(workspace), stream),
+           "conef_cs_ss_step")
 
 
 # random-block gradient compressor

@@ -69,6 +69,10 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.apply_items, &d.apply_items))) return rc;
     if ((rc = upload(ctx, pl.qred_items, &d.qred_items))) return rc;
     if ((rc = upload(ctx, pl.elem_items, &d.elem_items))) return rc;
+    if ((rc = upload(ctx, pl.rb_items, &d.rb_items))) return rc;
+    if ((rc = upload(ctx, pl.rb_g_items, &d.rb_g_items))) return rc;
+    d.n_rb = (int)pl.rb_items.size();
+    d.n_rb_g = (int)pl.rb_g_items.size();
     if ((rc = upload(ctx, pl.cs_err_items, &d.cs_err_items))) return rc;
     if ((rc = upload(ctx, pl.cs_err_f_items, &d.cs_err_f_items))) return rc;
     d.n_cs_err_f = (int)pl.cs_err_f_items.size();
@@ -104,19 +108,13 @@ int ensure_uploaded(conef_ctx *ctx)
     return CONEF_OK;
 }
 
-// Uploads what conef_rb_configure made (after ensure_uploaded): the work tables and the descriptors again,
-// which now carry the per-matrix block sizes.
+// Uploads what conef_rb_configure made (after ensure_uploaded): the descriptors again, which now carry the
+// per-matrix block sizes.
 int ensure_rb_uploaded(conef_ctx *ctx)
 {
     if (ctx->rb_uploaded) return CONEF_OK;
-    const Plan &pl = ctx->plan;
-    DevicePlan &d = ctx->dev;
     int rc;
-    if ((rc = upload(ctx, pl.mats, &d.mats))) return rc;
-    if ((rc = upload(ctx, pl.rb_items, &d.rb_items))) return rc;
-    if ((rc = upload(ctx, pl.rb_g_items, &d.rb_g_items))) return rc;
-    d.n_rb = (int)pl.rb_items.size();
-    d.n_rb_g = (int)pl.rb_g_items.size();
+    if ((rc = upload(ctx, ctx->plan.mats, &ctx->dev.mats))) return rc;
     ctx->rb_uploaded = true;
     return CONEF_OK;
 }
@@ -437,6 +435,49 @@ int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delt
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
     return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, static_cast<hipStream_t>(hip_stream)));
+}
+
+// ---------------------------------------------------------------- scaled-sign gradient compressor
+int conef_ss_sizes(const conef_ctx *ctx, size_t *sign_words)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (sign_words) *sign_words = ctx->plan.sign_words;
+    return CONEF_OK;
+}
+
+int conef_ss_offsets(const conef_ctx *ctx, int mat, size_t *sign_off)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (sign_off) *sign_off = (size_t)ctx->plan.mats[mat].sign_off;
+    return CONEF_OK;
+}
+
+int conef_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *sign_out,
+                  float *scale_out, void *workspace, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !sign_out || !scale_out || !workspace) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(sign_out, 4) ||
+        misaligned(scale_out, 4) || misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_ss_step(ctx->dev, grads, err_codes, err_scales, sign_out, scale_out, ws_doubles(ctx, workspace), step,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *sign_out, float *scale_out,
+                     void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !sign_out || !scale_out || !workspace) return CONEF_EINVAL;
+    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(sign_out, 4) || misaligned(scale_out, 4) ||
+        misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_cs_ss_step(ctx->dev, grads, table, sign_out, scale_out, ws_doubles(ctx, workspace),
+                                    static_cast<hipStream_t>(hip_stream)));
 }
 
 // ---------------------------------------------------------------- count-sketch mode

@@ -58,8 +58,15 @@ hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *cod
                           uint64_t step, hipStream_t st);
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
                              hipStream_t st);
-void octet_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta, uint64_t step,
-                   hipStream_t st);
+void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
+                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, hipStream_t st);
+// Scaled-sign gradient compressor: l1 norm pass, scale, sign bits + compression.
+hipError_t launch_ss_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *sign_words,
+                          float *c_scale, double *ws, uint64_t step, hipStream_t st);
+hipError_t launch_cs_ss_step(const DevicePlan &dp, const void *grads, void *table, uint32_t *sign_words, float *c_scale,
+                             double *ws, hipStream_t st);
+void launch_ss_scale(const DevicePlan &dp, const double *ws, float *c_scale, hipStream_t st);
+void launch_ss_clear(const DevicePlan &dp, uint32_t *sign_words, hipStream_t st);
 
 // Count-sketch mode: the same three passes with a table as the error state.
 hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P,

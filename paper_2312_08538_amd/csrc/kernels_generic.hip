@@ -178,37 +178,60 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
 // Section 5.3, any layout: one wave per scale block, two sweeps as in the err pass.  The argument of the error
 // compressor is g + e outside the kept block [start, start + k) and beta e inside it; the kept values
 // p = g + (1 - beta) e go to the Delta buffer (first sweep only).
+// Scaled sign (Section 5.1), Delta = c sign(p), c = ||p||_1 / N: MODE 1 adds up |p| in fp64 (one partial sum per
+// wave, blocks and elements in a fixed order), MODE 2 reads c, sets the sign bits of the negative entries (the
+// sign words of these matrices are cleared by the launcher first; bits are set with atomic ORs, whose result
+// does not depend on their order) and compresses (g + e) - Delta.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+
+template <int MODE>
 __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
-                                             const float *scales, int64_t j, int64_t start, float *delta, bool write)
+                                             const float *scales, int64_t j, int64_t start, float *delta, bool write,
+                                             float c, uint32_t *sign_words)
 {
     const int W = 32 / dp.bits;
     const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
     const float dstep = scales[d.scale_off + j / dp.block] * inv_levels(dp.bits);
     const float g = load_grad(grads, dp.dtype, d.grad_off + j);
-    if (j >= start && j < start + d.rb_k) {
-        if (write) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
-        return dp.beta * (dstep * (float)q);
+    if (MODE == kModeBlock) {
+        if (j >= start && j < start + d.rb_k) {
+            if (write) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
+            return dp.beta * (dstep * (float)q);
+        }
+        return __builtin_fmaf(dstep, (float)q, g);
     }
-    return __builtin_fmaf(dstep, (float)q, g);
+    const float pv = __builtin_fmaf(dstep * dp.omb, (float)q, g);
+    if (MODE == kModeNorm) return pv;
+    const bool neg = (__float_as_uint(pv) >> 31) != 0;
+    if (write && neg) atomicOr(sign_words + d.sign_off + j / 32, 1u << (j % 32));
+    return __builtin_fmaf(dstep, (float)q, g) - (neg ? -c : c);
 }
 
+template <int MODE>
 __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *grads, uint32_t *codes, float *scales,
-                                                    float *delta, uint32_t step_lo, uint32_t step_hi)
+                                                    float *delta, uint32_t step_lo, uint32_t step_hi,
+                                                    uint32_t *sign_words, const float *c_scale, double *ws)
 {
     const WorkItem it = dp.rb_g_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int bits = dp.bits, W = 32 / bits, B = dp.block;
     const float s_f = (float)((1 << (bits - 1)) - 1);
-    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
+    const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    double l1 = 0.0;
     for (int t = 0; t < it.b; ++t) {
         const int64_t blk = (int64_t)it.a + wave + 4 * t;
         if (blk >= d.nblk) break;                                   // uniform per wave
         const int64_t j0 = blk * B;
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
         float a = 0.0f;
-        for (int e = lane; e < cnt; e += 64)
-            a = fmaxf(a, fabsf(rb_argument(dp, d, grads, codes, scales, j0 + e, start, delta, true)));
+        for (int e = lane; e < cnt; e += 64) {
+            const float v = rb_argument<MODE>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words);
+            if (MODE == kModeNorm) l1 += (double)fabsf(v);
+            a = fmaxf(a, fabsf(v));
+        }
+        if (MODE == kModeNorm) continue;
         a = wave_max(a);
         const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
         const int sweeps = (cnt + 63) / 64;
@@ -217,7 +240,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             uint32_t field = 0;
             if (e < cnt && a > 0.0f) {
                 const int64_t j = j0 + e;
-                const float x = rb_argument(dp, d, grads, codes, scales, j, start, delta, false);
+                const float x = rb_argument<MODE>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
@@ -228,6 +251,40 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         }
         if (lane == 0) scales[d.scale_off + blk] = a;
     }
+    if (MODE == kModeNorm) {
+        l1 = wave_sum(l1);
+        if (lane == 0) ws[d.st_part_off + 4 * ((int)blockIdx.x - d.st_first) + wave] = l1;
+    }
+}
+
+// c = fl32(||p||_1 / N) of every matrix from the partial sums of the norm pass: thread t adds a contiguous share of
+// the matrix's partials in order, thread 0 the 256 shares in order.
+__global__ __launch_bounds__(256) void k_ss_scale(DevicePlan dp, const double *ws, float *c_scale)
+{
+    __shared__ double share[256];
+    const MatDesc d = dp.mats[blockIdx.x];
+    const int per = (d.st_slots + 255) / 256;
+    double s = 0.0;
+    for (int i = threadIdx.x * per; i < (int)(threadIdx.x + 1) * per && i < d.st_slots; ++i) s += ws[d.st_part_off + i];
+    share[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        for (int i = 0; i < 256; ++i) tot += share[i];
+        c_scale[blockIdx.x] = (float)(tot / (double)d.N);
+    }
+}
+
+// Clears the sign words of the matrices whose sign bits are set with atomic ORs (those off the octet paths).
+__global__ __launch_bounds__(256) void k_ss_clear(DevicePlan dp, uint32_t *sign_words)
+{
+    const WorkItem it = dp.elem_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    if (!d.st_atomic) return;
+    const int64_t n_words = (d.N + 31) / 32;
+    // an item covers 1024 elements = 32 words
+    const int64_t wd = ((int64_t)it.a << 5) + threadIdx.x;
+    if (threadIdx.x < 32 && wd < n_words) sign_words[d.sign_off + wd] = 0u;
 }
 
 // Adds the column-chunk partial sums of P in chunk order and rounds once to fp32.
@@ -356,10 +413,39 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
                           uint64_t step, hipStream_t st)
 {
-    octet_rb_step(dp, grads, codes, scales, delta, step, st);
+    octet_stream_step(dp, kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, st);
     if (dp.n_rb_g > 0)
-        hipLaunchKernelGGL(k_rb_generic, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
-                           (uint32_t)step, (uint32_t)(step >> 32));
+        hipLaunchKernelGGL(k_rb_generic<kModeBlock>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+                           (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr, (double *)nullptr);
+    return hipGetLastError();
+}
+
+void launch_ss_scale(const DevicePlan &dp, const double *ws, float *c_scale, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_ss_scale, dim3(dp.n_mats), dim3(256), 0, st, dp, ws, c_scale);
+}
+
+void launch_ss_clear(const DevicePlan &dp, uint32_t *sign_words, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_ss_clear, dim3(dp.n_elem), dim3(256), 0, st, dp, sign_words);
+}
+
+// Scaled sign with the quantiser: l1 norm (one pass), scale, then sign bits + compression of (g + e) - Delta.
+hipError_t launch_ss_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *sign_words,
+                          float *c_scale, double *ws, uint64_t step, hipStream_t st)
+{
+    const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+    octet_stream_step(dp, kModeNorm, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, st);
+    if (dp.n_rb_g > 0) {
+        hipLaunchKernelGGL(k_rb_generic<kModeNorm>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
+                           lo, hi, sign_words, (const float *)c_scale, ws);
+        launch_ss_clear(dp, sign_words, st);
+    }
+    launch_ss_scale(dp, ws, c_scale, st);
+    octet_stream_step(dp, kModeSign, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, st);
+    if (dp.n_rb_g > 0)
+        hipLaunchKernelGGL(k_rb_generic<kModeSign>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
+                           lo, hi, sign_words, (const float *)c_scale, ws);
     return hipGetLastError();
 }
 

@@ -549,23 +549,32 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     }
 }
 
-// ------------------------------------------------------------------ random-block gradient compressor
-// Section 5.3: Delta keeps the k consecutive coordinates [start, start + k) of p = g + (1 - beta) e and nothing
+// ------------------------------------------------------------------ element-wise gradient compressors
+// MODE 0, random block (Section 5.3): Delta keeps the k consecutive coordinates [start, start + k) of p = g + (1 - beta) e and nothing
 // else; the error compressor then takes beta e + p - Delta: g + e outside the block (the fma of the other
 // passes), beta e inside it.  One streaming pass: a wave walks runs of 64 octets (512 elements) of the flat
 // index; scale blocks of 8 * 2^j elements never straddle a run.  Decode, select, block max-norm by DPP,
 // stochastic rounding, pack, in place; the kept values go to the Delta buffer.
-template <bool BF16, int BITS>
+// Scaled sign (Section 5.1), Delta = c sign(p) with c = ||p||_1 / N per matrix, takes two passes of the same walk:
+// MODE 1 adds up |p| in fp64, one partial sum per wave in a fixed order (the scale kernel adds the partials in
+// item order); MODE 2 reads c, writes one sign byte per octet (bit e set if element e is negative) and
+// compresses (g + e) - Delta.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+
+template <bool BF16, int BITS, int MODE>
 __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
-                                                  float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi)
+                                                  float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi,
+                                                  uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws)
 {
     const int lane = threadIdx.x & 63;
     const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     if (item >= dp.n_rb) return;
     const WorkItem it = dp.rb_items[item];
     const MatDesc d = dp.mats[it.mat];
-    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
-    const int64_t stop = start + d.rb_k;
+    const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
+    const int64_t stop = MODE == kModeBlock ? start + d.rb_k : 0;
+    const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    double l1 = 0.0;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     const uint32_t mask = (1u << BITS) - 1u;
     // The last run of a matrix may be short: octets at or beyond the end re-read the last octet and store
@@ -598,6 +607,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
         const float dpart = dstep * dp.omb;
         float x[8];
         float a = 0.0f;
+        uint32_t neg_bits = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int q;
@@ -605,14 +615,28 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             else q = code_field(r.c0, e, BITS);
             const float qf = (float)q;
             const int64_t j = o * 8 + e;
-            if (j >= start && j < stop) {
-                if (valid) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
-                x[e] = dp.beta * (dstep * qf);
+            if (MODE == kModeBlock) {
+                if (j >= start && j < stop) {
+                    if (valid) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
+                    x[e] = dp.beta * (dstep * qf);
+                } else {
+                    x[e] = __builtin_fmaf(dstep, qf, g[e]);
+                }
             } else {
-                x[e] = __builtin_fmaf(dstep, qf, g[e]);
+                const float pv = __builtin_fmaf(dpart, qf, g[e]);
+                if (MODE == kModeNorm) {
+                    l1 += valid ? (double)fabsf(pv) : 0.0;
+                    x[e] = 0.0f;
+                } else {
+                    const bool neg = (__float_as_uint(pv) >> 31) != 0;
+                    neg_bits |= (neg ? 1u : 0u) << e;
+                    x[e] = __builtin_fmaf(dstep, qf, g[e]) - (neg ? -c : c);
+                }
             }
             a = fmaxf(a, fabsf(x[e]));
         }
+        if (MODE == kModeNorm) continue;
+        if (MODE == kModeSign && valid) reinterpret_cast<uint8_t *>(sign_words + d.sign_off)[o] = (uint8_t)neg_bits;
         a = block_max(a, d.lb_shift);
         const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
         uint32_t rnd[4];
@@ -625,25 +649,43 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
         }
     }
+    if (MODE == kModeNorm) {
+        l1 = wave_sum(l1);
+        if (lane == 0) ws[d.st_part_off + (item - d.st_first)] = l1;
+    }
 }
 
 }  // namespace
 
-void octet_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta, uint64_t step,
-                   hipStream_t st)
+// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign
+void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
+                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, hipStream_t st)
 {
     if (dp.n_rb <= 0) return;
     const dim3 grid((dp.n_rb + 3) / 4);
     const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+#define CONEF_STREAM_CASE(BF, B)                                                                                                   \
+    case ((BF ? 1 : 0) << 8) | B:                                                                                                  \
+        if (mode == kModeBlock)                                                                                                    \
+            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeBlock>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,   \
+                               sign_words, c_scale, ws);                                                                           \
+        else if (mode == kModeNorm)                                                                                                \
+            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeNorm>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,    \
+                               sign_words, c_scale, ws);                                                                           \
+        else                                                                                                                       \
+            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeSign>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,    \
+                               sign_words, c_scale, ws);                                                                           \
+        break;
     switch ((dp.dtype << 8) | dp.bits) {
-    case (0 << 8) | 2: hipLaunchKernelGGL((k_rb_octet<false, 2>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
-    case (0 << 8) | 4: hipLaunchKernelGGL((k_rb_octet<false, 4>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
-    case (0 << 8) | 8: hipLaunchKernelGGL((k_rb_octet<false, 8>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
-    case (1 << 8) | 2: hipLaunchKernelGGL((k_rb_octet<true, 2>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
-    case (1 << 8) | 4: hipLaunchKernelGGL((k_rb_octet<true, 4>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
-    case (1 << 8) | 8: hipLaunchKernelGGL((k_rb_octet<true, 8>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi); break;
+        CONEF_STREAM_CASE(false, 2)
+        CONEF_STREAM_CASE(false, 4)
+        CONEF_STREAM_CASE(false, 8)
+        CONEF_STREAM_CASE(true, 2)
+        CONEF_STREAM_CASE(true, 4)
+        CONEF_STREAM_CASE(true, 8)
     default: break;
     }
+#undef CONEF_STREAM_CASE
 }
 
 #define CONEF_OCTET_CASE(KERNEL, BF, B, R, GRID, ST, ...) \

@@ -705,9 +705,15 @@ __global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, co
 // Section 5.3 with the count sketch: Delta keeps p = g + (1 - beta) e on the coordinates [start, start + k) of the
 // flat index, and by linearity S <- beta S + C(p - Delta) with p - Delta equal to p outside the block and 0
 // inside.  Same walk of the bucket lists as the update pass above, without the factors.
-template <bool BF16, bool F16>
+// Scaled sign (Section 5.1), Delta = c sign(p) with c = ||p||_1 / N per matrix, takes two passes of the same walk:
+// MODE 1 adds up |p| in fp64 (one partial sum per wave; the scale kernel adds them in item order), MODE 2 reads
+// c, writes the sign bits (one byte per octet on this path) and sketches p - Delta on top of beta S.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+
+template <bool BF16, bool F16, int MODE>
 __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
-                                                    float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi)
+                                                    float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi,
+                                                    uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws)
 {
     const int lane = threadIdx.x;
     const WorkItem it = dp.cs_err_f_items[blockIdx.x];
@@ -715,8 +721,10 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
     const int64_t colw = (int64_t)it.c * 512 + lane * 8;
     const bool active = colw < d.m;
     const int64_t col = active ? colw : 0;
-    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
-    const int64_t stop = start + d.rb_k;
+    const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
+    const int64_t stop = MODE == kModeBlock ? start + d.rb_k : 0;
+    const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    double l1 = 0.0;
     const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
     const int32_t *rows = dp.bucket_rows + d.hash_off;
     const int b_end = it.a + it.b;
@@ -748,16 +756,28 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
                                                d.table_off + (int64_t)bn * d.m + col);
             const float somb = hv < 0 ? -dp.omb : dp.omb;
             const int64_t j0 = i * d.m + col;
+            uint32_t neg_bits = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float pv = __builtin_fmaf(somb, s_old[j], g[j]);
-                const bool inside = j0 + j >= start && j0 + j < stop;
-                if (inside && active) delta[d.rb_delta_off + (j0 + j - start)] = pv;
-                const float x = inside ? 0.0f : pv;
+                float x;
+                if (MODE == kModeBlock) {
+                    const bool inside = j0 + j >= start && j0 + j < stop;
+                    if (inside && active) delta[d.rb_delta_off + (j0 + j - start)] = pv;
+                    x = inside ? 0.0f : pv;
+                } else if (MODE == kModeNorm) {
+                    l1 += active ? (double)fabsf(pv) : 0.0;
+                    x = 0.0f;
+                } else {
+                    const bool neg = (__float_as_uint(pv) >> 31) != 0;
+                    neg_bits |= (neg ? 1u : 0u) << j;
+                    x = pv - (neg ? -c : c);
+                }
                 acc[j] = hv < 0 ? acc[j] - x : acc[j] + x;
             }
+            if (MODE == kModeSign && active) reinterpret_cast<uint8_t *>(sign_words + d.sign_off)[j0 >> 3] = (uint8_t)neg_bits;
         }
-        if (active) {
+        if (MODE != kModeNorm && active) {
             float out[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -780,20 +800,29 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
             }
         }
     }
+    if (MODE == kModeNorm) {
+        l1 = wave_sum(l1);
+        if (lane == 0) ws[d.st_part_off + ((int)blockIdx.x - d.st_first)] = l1;
+    }
 }
 
-// The same for any shape: one thread per column of a 256-column tile.
+// The same for any shape: one thread per column of a 256-column tile (sign bits by atomic OR into words the
+// launcher has cleared).
+template <int MODE>
 __global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const void *grads, void *table, float *delta,
-                                                           uint32_t step_lo, uint32_t step_hi)
+                                                           uint32_t step_lo, uint32_t step_hi, uint32_t *sign_words,
+                                                           const float *c_scale, double *ws)
 {
     const WorkItem it = dp.cs_err_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
     const int64_t k = (int64_t)it.c * kCsCols + threadIdx.x;
-    if (k >= d.m) return;
-    const int64_t start = random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k);
+    const bool active = k < d.m;
+    const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
+    const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    double l1 = 0.0;
     const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
     const int32_t *rows = dp.bucket_rows + d.hash_off;
-    for (int b = it.a; b < it.a + it.b; ++b) {
+    for (int b = it.a; b < it.a + it.b && active; ++b) {
         const int64_t tidx = d.table_off + (int64_t)b * d.m + k;
         const float s_old = table_load(table, dp.table_dtype, tidx);
         float acc = 0.0f;
@@ -801,12 +830,26 @@ __global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const 
             const int32_t hv = rows[e];
             const int64_t j = (int64_t)(hv & INT32_MAX) * d.m + k;
             const float pv = __builtin_fmaf(signed_omb(dp, hv), s_old, load_grad(grads, dp.dtype, d.grad_off + j));
-            const bool inside = j >= start && j < start + d.rb_k;
-            if (inside) delta[d.rb_delta_off + (j - start)] = pv;
-            const float x = inside ? 0.0f : pv;
+            float x;
+            if (MODE == kModeBlock) {
+                const bool inside = j >= start && j < start + d.rb_k;
+                if (inside) delta[d.rb_delta_off + (j - start)] = pv;
+                x = inside ? 0.0f : pv;
+            } else if (MODE == kModeNorm) {
+                l1 += (double)fabsf(pv);
+                x = 0.0f;
+            } else {
+                const bool neg = (__float_as_uint(pv) >> 31) != 0;
+                if (neg) atomicOr(sign_words + d.sign_off + j / 32, 1u << (j % 32));
+                x = pv - (neg ? -c : c);
+            }
             acc = hv < 0 ? acc - x : acc + x;
         }
-        table_store(table, dp.table_dtype, tidx, __builtin_fmaf(dp.beta, s_old, acc));
+        if (MODE != kModeNorm) table_store(table, dp.table_dtype, tidx, __builtin_fmaf(dp.beta, s_old, acc));
+    }
+    if (MODE == kModeNorm) {
+        l1 = wave_sum(l1);
+        if ((threadIdx.x & 63) == 0) ws[d.st_part_off + (kCsCols / 64) * ((int)blockIdx.x - d.st_first) + (threadIdx.x >> 6)] = l1;
     }
 }
 
@@ -893,20 +936,40 @@ hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *tab
     return hipGetLastError();
 }
 
-hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
-                             hipStream_t st)
+namespace {
+template <int MODE>
+void cs_stream_pass(const DevicePlan &dp, const void *grads, void *table, float *delta, uint32_t lo, uint32_t hi,
+                    uint32_t *sign_words, const float *c_scale, double *ws, hipStream_t st)
 {
-    const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
     if (dp.n_cs_err_f > 0) {
         const dim3 grid(dp.n_cs_err_f);
         const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;
-        if (bf && fh) hipLaunchKernelGGL((k_cs_rb_octet<true, true>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
-        else if (bf) hipLaunchKernelGGL((k_cs_rb_octet<true, false>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
-        else if (fh) hipLaunchKernelGGL((k_cs_rb_octet<false, true>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
-        else hipLaunchKernelGGL((k_cs_rb_octet<false, false>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi);
+        if (bf && fh) hipLaunchKernelGGL((k_cs_rb_octet<true, true, MODE>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi, sign_words, c_scale, ws);
+        else if (bf) hipLaunchKernelGGL((k_cs_rb_octet<true, false, MODE>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi, sign_words, c_scale, ws);
+        else if (fh) hipLaunchKernelGGL((k_cs_rb_octet<false, true, MODE>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi, sign_words, c_scale, ws);
+        else hipLaunchKernelGGL((k_cs_rb_octet<false, false, MODE>), grid, dim3(64), 0, st, dp, grads, table, delta, lo, hi, sign_words, c_scale, ws);
     }
     if (dp.n_cs_err > 0)
-        hipLaunchKernelGGL(k_cs_rb_generic, dim3(dp.n_cs_err), dim3(kCsCols), 0, st, dp, grads, table, delta, lo, hi);
+        hipLaunchKernelGGL(k_cs_rb_generic<MODE>, dim3(dp.n_cs_err), dim3(kCsCols), 0, st, dp, grads, table, delta, lo, hi,
+                           sign_words, c_scale, ws);
+}
+}  // namespace
+
+hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
+                             hipStream_t st)
+{
+    cs_stream_pass<kModeBlock>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
+    return hipGetLastError();
+}
+
+// Scaled sign with the count sketch: l1 norm (one pass), scale, then sign bits + sketch of p - Delta.
+hipError_t launch_cs_ss_step(const DevicePlan &dp, const void *grads, void *table, uint32_t *sign_words, float *c_scale,
+                             double *ws, hipStream_t st)
+{
+    cs_stream_pass<kModeNorm>(dp, grads, table, nullptr, 0, 0, sign_words, c_scale, ws, st);
+    if (dp.n_cs_err > 0) launch_ss_clear(dp, sign_words, st);
+    launch_ss_scale(dp, ws, c_scale, st);
+    cs_stream_pass<kModeSign>(dp, grads, table, nullptr, 0, 0, sign_words, c_scale, ws, st);
     return hipGetLastError();
 }
 

@@ -72,25 +72,11 @@ int configure_random_block(Plan &plan, const int64_t *keep)
         if (keep[l] < 1 || keep[l] > plan.mats[l].N) return kEinval;
     try {
         int64_t off = 0;
-        plan.rb_items.clear();
-        plan.rb_g_items.clear();
-        // the wave-per-run kernel needs blocks of 8 * 2^j elements (j <= 6) that fill the matrix (no short last block)
-        const bool block_ok = plan.block % 8 == 0 && is_pow2(plan.block / 8) && plan.block / 8 <= 64;
         for (int l = 0; l < n_mats; ++l) {
             MatDesc &d = plan.mats[l];
             d.rb_k = keep[l];
             d.rb_delta_off = off;
             off += round_up(keep[l], kAlign);
-            if (plan.sketch) continue;              // the count-sketch mode walks its bucket lists
-            if (block_ok && d.N % plan.block == 0) {
-                d.lb_shift = log2i(plan.block / 8);
-                const int64_t runs = ceil_div(d.N, 512), per_item = 8;        // the last run may be short
-                for (int64_t r0 = 0; r0 < runs; r0 += per_item)
-                    plan.rb_items.push_back({l, (int32_t)r0, (int32_t)std::min<int64_t>(per_item, runs - r0), 0});
-            } else {
-                const int32_t per_wave = d.nblk <= 16384 ? 1 : 16;
-                for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave) plan.rb_g_items.push_back({l, (int32_t)b0, per_wave, 0});
-            }
         }
         plan.rb_delta_elems = (size_t)off;
     } catch (const std::bad_alloc &) {
@@ -154,10 +140,22 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
             plan.mats[l].cs_cols = fast ? 512 : kCsCols;
             const int32_t nct = (int32_t)ceil_div(d.m, plan.mats[l].cs_cols);
             std::vector<WorkItem> &items = fast ? plan.cs_err_f_items : plan.cs_err_items;
+            plan.mats[l].st_first = (int32_t)items.size();
             for (int64_t b0 = 0; b0 < d.w; b0 += nb)
                 for (int32_t ct = 0; ct < nct; ++ct)
                     items.push_back({l, (int32_t)b0, (int32_t)std::min<int64_t>(nb, d.w - b0), ct});
+            // element-wise gradient compressors walk the same items: one partial l1 sum per wave (octet path: one
+            // wave per item, else four)
+            plan.mats[l].st_slots = (int32_t)(items.size() - plan.mats[l].st_first) * (fast ? 1 : kCsCols / 64);
+            plan.mats[l].st_atomic = fast ? 0 : 1;
         }
+        int64_t wd = (int64_t)plan.ws_doubles;
+        for (int l = 0; l < n_mats; ++l) {
+            plan.mats[l].st_part_off = wd;
+            wd += plan.mats[l].st_slots;
+        }
+        plan.ws_doubles = (size_t)round_up(wd, 32);
+        plan.workspace_bytes = (size_t)round_up((int64_t)plan.ws_doubles * 8, 256);
     } catch (const std::bad_alloc &) {
         return kEnomem;
     }
@@ -260,6 +258,31 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                 }
             }
         }
+        // Stream tables of the element-wise gradient compressors (random block, scaled sign) for the quantiser:
+        // the wave-per-run kernel needs blocks of 8 * 2^j elements (j <= 6) that fill the matrix (no short last block)
+        int64_t sw = 0;
+        const bool stream_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64;
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            d.sign_off = sw; sw += round_up(ceil_div(d.N, 32), kAlign);
+            if (sketch) continue;                   // the count-sketch mode walks its bucket lists
+            if (stream_ok && d.N % block == 0) {
+                d.lb_shift = log2i(block / 8);
+                const int64_t runs = ceil_div(d.N, 512), per_item = 8;        // the last run may be short
+                d.st_first = (int32_t)plan.rb_items.size();
+                for (int64_t r0 = 0; r0 < runs; r0 += per_item)
+                    plan.rb_items.push_back({l, (int32_t)r0, (int32_t)std::min<int64_t>(per_item, runs - r0), 0});
+                d.st_slots = (int32_t)plan.rb_items.size() - d.st_first;      // one wave per item
+            } else {
+                const int32_t per_wave = d.nblk <= 16384 ? 1 : 16;
+                d.st_first = (int32_t)plan.rb_g_items.size();
+                for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave) plan.rb_g_items.push_back({l, (int32_t)b0, per_wave, 0});
+                d.st_slots = 4 * ((int32_t)plan.rb_g_items.size() - d.st_first);   // four waves per item
+                d.st_atomic = 1;
+            }
+            d.st_part_off = wd; wd += d.st_slots;
+        }
+        plan.sign_words = (size_t)sw;
         plan.grad_elems = (size_t)g; plan.code_words = (size_t)w; plan.n_scales = (size_t)s;
         plan.p_elems = (size_t)p; plan.q_elems = (size_t)q;
         plan.ws_doubles = (size_t)round_up(wd, 32);
@@ -463,6 +486,7 @@ bool check_plan(const Plan &plan)
         regions.push_back({d.gram_off, d.gram_off + (int64_t)d.n_gram_tiles * plan.rank * plan.rank});
         regions.push_back({d.rinv_off, d.rinv_off + (int64_t)plan.rank * plan.rank});
         regions.push_back({d.qpart_off, d.qpart_off + (int64_t)d.n_q_tiles * d.m * plan.rank});
+        if (d.st_slots > 0) regions.push_back({d.st_part_off, d.st_part_off + d.st_slots});
         if (d.n_p_chunks > 1) regions.push_back({d.ppart_off, d.ppart_off + (int64_t)d.n_p_chunks * d.n * plan.rank});
         if (d.path == kPathMfma) {
             regions.push_back({d.scT_off, d.scT_off + ((d.m / 128) * d.n * 4 + 7) / 8});

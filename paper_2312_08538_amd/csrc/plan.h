@@ -55,6 +55,11 @@ struct MatDesc {
     // random-block gradient compressor
     int64_t rb_k;                   // coordinates kept per step (0: not configured)
     int64_t rb_delta_off;           // offset of the matrix's kept values in the flat Delta buffer
+    // element-wise gradient compressors (random block, scaled sign): the matrix's items in its stream table
+    int32_t st_first, st_slots;     // index of its first item; partial-sum slots (one per wave that works on it)
+    int32_t st_atomic;              // its sign bits are set with atomic ORs (kernels for any shape): cleared first
+    int64_t st_part_off;            // workspace offset (doubles) of its partial l1 sums
+    int64_t sign_off;               // offset (words) of its sign bits in the flat sign buffer
 };
 
 // One unit of work of a grouped launch: matrix index and kernel-specific coordinates.
@@ -101,8 +106,9 @@ struct Plan {
     std::vector<WorkItem> qred_items;   // reduce partial Q+: (mat, first entry of m*r)
     std::vector<WorkItem> elem_items;   // element-wise helpers: (mat, first element / 1024)
     std::vector<WorkItem> upd_items;    // decompress / update: (mat, row tile of 64, column tile of 128)
-    // random-block gradient compressor with the quantiser (made by configure_random_block)
-    size_t rb_delta_elems = 0;
+    // element-wise gradient compressors with the quantiser: stream tables (made with the plan)
+    size_t sign_words = 0;
+    size_t rb_delta_elems = 0;      // set by configure_random_block
     std::vector<WorkItem> rb_items;     // matrices of whole power-of-two blocks: (mat, first run of 512 elements, runs), one item per wave
     std::vector<WorkItem> rb_g_items;   // any other matrix: (mat, first block, blocks per wave), 4 waves per item
 };
