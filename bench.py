@@ -238,6 +238,58 @@ def run_random_block(w, fraction: float = 0.1, reps: int = 10):
     return out
 
 
+def run_scaled_sign(w, reps: int = 10):
+    """Times one step with the scaled-sign gradient compressor (Section 5.1) in place of the rank-r one, with the
+    workload's quantiser (beta = 0) and with the count sketch (fp16 table, keep 0.2, beta 0.9): two passes over
+    the gradient and the error state.  HIP events on the launch stream."""
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+    from paper_2312_08538_amd import workloads as wl
+
+    G = 4 if w.grad_dtype == 0 else 2
+    out = {}
+    for kind in ("quantiser", "count_sketch"):
+        if kind == "quantiser":
+            model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(n * m * (w.bits / 8 + 4.0 / w.block) for n, m in w.layout)
+        else:
+            ws = wl.sketch_rows(w.layout, 0.2)
+            model = B.SketchModel(w.layout, ws, w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(a * m * 2 for a, (_, m) in zip(ws, w.layout))
+        buf = model.alloc("cuda:0")
+        signs = torch.zeros(B.conef_ss_sizes(model.ctx)["sign_words"], dtype=torch.int32, device="cuda:0")
+        cs = torch.zeros(len(w.layout), dtype=torch.float32, device="cuda:0")
+        wl.device_fill_gradients(w, 0, buf["grads"], [o["grad_off"] for o in model.offsets])
+        st = B.Model.stream_handle()
+
+        def one(t):
+            if kind == "quantiser":
+                B.conef_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], signs, cs, buf["ws"], t, st)
+            else:
+                B.conef_cs_ss_step(model.ctx, buf["grads"], buf["table"], signs, cs, buf["ws"], st)
+
+        for t in range(2):
+            one(t)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for t, (e0, e1) in enumerate(ev):
+            e0.record()
+            one(2 + t)
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / reps
+        # gradient and state read twice, state written once, one sign bit per entry written
+        nbytes = int(2 * w.elements * G + 3 * state_bytes + w.elements / 8)
+        out[kind] = {"ms": round(ms, 4), "bytes": nbytes, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "finite": bool(torch.isfinite(cs).all())}
+        model.close()
+        del buf, signs
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_oracle_sample(w, budget_s: float = 20.0):
     """Times the oracle (as it stands) on the workload's matrices in layout order, one step from
     zero error, until about `budget_s` seconds of CPU work are spent or the whole model is done.
@@ -321,6 +373,9 @@ def main():
     ap.add_argument("--random-block", action="store_true",
                     help="time only the step with the random-block gradient compressor (a tenth of the coordinates "
                          "kept; quantiser and count-sketch error compressors) on --workload and print its line")
+    ap.add_argument("--scaled-sign", action="store_true",
+                    help="time only the step with the scaled-sign gradient compressor (quantiser and count-sketch error "
+                         "compressors) on --workload and print its line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
                          "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
@@ -338,6 +393,12 @@ def main():
     w = wl.WORKLOADS[a.workload]
     if a.calibrate_copy:
         calibrate_copy(w)
+    if a.scaled_sign:
+        r = run_scaled_sign(w, a.steps)
+        print(json.dumps({"metric": "scaled-sign ConEF step throughput: gradient GB/s processed",
+                          "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+                          "steps": a.steps, "config": {"workload": w.name}, **r}), flush=True)
+        return
     if a.random_block:
         r = run_random_block(w, 0.1, a.steps)
         print(json.dumps({"metric": "random-block ConEF step throughput: gradient GB/s processed",
@@ -397,6 +458,8 @@ def main():
         # the unscaled random-block gradient compressor in place of the rank-r one (a tenth of the coordinates kept)
         out["random_block"] = {"fraction": 0.1, "workloads": {name: run_random_block(wl.WORKLOADS[name])
                                                               for name in ("cnn", "lm", "translation", "large")}}
+        out["scaled_sign"] = {"workloads": {name: run_scaled_sign(wl.WORKLOADS[name])
+                                            for name in ("cnn", "lm", "translation", "large")}}
     if not a.no_cpu_baseline:
         v, cores, sample = run_oracle_sample(w)
         out["cpu_baseline"] = {"value": round(v, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
