@@ -273,3 +273,28 @@ def test_sketch_step_is_reproducible_and_replays_from_a_hip_graph(env):
             for k in want:
                 assert torch.equal(b[k].view(torch.uint8), want[k].view(torch.uint8)), (layout, replay, k)
         model.close()
+
+
+def test_set_beta_on_a_sketch_context_equals_a_context_made_with_that_beta(env):
+    R, B, U, torch = env
+    layout, ws, rank = [(200, 520), (64, 147)], [40, 13], 4
+    rng = np.random.default_rng(99)
+    grads = [_grad(rng, n, m, wl.F32) for n, m in layout]
+    tables = [_random_table(rng, w, m, True) for w, (_, m) in zip(ws, layout)]
+    Qs = [rng.standard_normal((m, rank)).astype(np.float32) for _, m in layout]
+    results = []
+    for make in ("init", "set"):
+        model = B.SketchModel(layout, ws, rank, 0.9 if make == "init" else 0.25, 1, wl.F32, 7)
+        if make == "set":
+            B.conef_set_beta(model.ctx, 0.9)
+        buf = model.alloc()
+        _to_dev_grads(torch, model, buf, grads)
+        for l in range(len(layout)):
+            _set_table(torch, model, buf, l, tables[l])
+            _set_factor(torch, buf, "Q", model.offsets[l]["q_off"], Qs[l])
+        model.step(buf)
+        torch.cuda.synchronize()
+        results.append({k: buf[k].clone() for k in ("table", "Q", "P")})
+        model.close()
+    for k in results[0]:
+        assert torch.equal(results[0][k].view(torch.uint8), results[1][k].view(torch.uint8)), k
