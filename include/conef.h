@@ -200,7 +200,8 @@ int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delt
  * What a worker sends is one bit per entry and one scale per matrix:
  *   sign_out   device, out: uint32 words, matrix l at sign_off of conef_ss_offsets (multiples of 64 words),
  *              bit j mod 32 of word j / 32 set if entry j of p is negative (its IEEE sign bit; zeros count as
- *              positive); conef_ss_sizes gives the length of the buffer
+ *              positive); bits of a matrix's last word beyond its last entry are unspecified; conef_ss_sizes gives
+ *              the length of the buffer
  *   scale_out  device, out: n_mats floats, c of every matrix
  * The l1 norm is a sum of fp64 partial sums taken in a fixed order (reproducible from run to run; it can differ
  * from a sum in index order in the last bit of the fp64 value, hence, rarely, in the last bit of c).
