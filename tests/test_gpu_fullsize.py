@@ -1,6 +1,7 @@
-"""Parity at the benchmark's full size: the `large` workload (1.31 G elements, rank 32, bf16 gradients),
-in the launch configuration `bench.py` times, checked on sampled outputs that the oracle can compute
-one by one from the inputs the library saw (downloaded from the device):
+"""Parity at full size, in the launch configuration `bench.py` times: the `large` workload (1.31 G elements,
+rank 32, bf16 gradients) checked on sampled outputs that the oracle can compute one by one from the inputs
+the library saw (downloaded from the device), and whole models (`large`, `translation`, `lm`) against one
+oracle step per matrix.  Sampled:
 
   * sampled rows of the raw P of the step's first stage,
   * the whole orthonormal factor of sampled matrices (orthonormal, same span as the raw P),
@@ -206,13 +207,15 @@ def test_large_count_sketch_step_on_sampled_outputs(env):
     model.close()
 
 
-def test_large_whole_model_second_step_against_the_oracle(env):
-    """Every matrix of `large`, whole: the library's second step (fused call, the launch configuration of the
+@pytest.mark.parametrize("name", ["lm", "translation", "large"])
+def test_whole_model_second_step_against_the_oracle(env, name):
+    """Every matrix of the workload, whole (`large`: 1.31 G elements; `translation`, `lm`: the other kernel
+    families at their full sizes): the library's second step (fused call, the launch configuration of the
     benchmark) against one oracle step started from the state the library itself held before that step
-    (downloaded), on the gradients the library read.  Factors, scales and every code of all 1.31 G elements
-    are compared with the criteria of the matrix-core family (see parity_util.compare_step)."""
+    (downloaded), on the gradients the library read.  Factors, scales and every code are compared with the
+    criteria of parity_util.compare_step."""
     R, B, U, torch = env
-    w = wl.WORKLOADS["large"]
+    w = wl.WORKLOADS[name]
     bits, block, rank, W = w.bits, w.block, w.rank, 32 // w.bits
     model = B.Model(w.layout, rank, bits, block, w.grad_dtype, w.lib_seed)
     buf = model.alloc()
@@ -233,13 +236,14 @@ def test_large_whole_model_second_step_against_the_oracle(env):
     for l, (n, m) in enumerate(w.layout):
         o = model.offsets[l]
         N = n * m
-        g = buf["grads"][o["grad_off"]:o["grad_off"] + N].view(torch.int16).cpu().numpy().view(np.uint16).reshape(n, m)
-        nw, nb = N // W, N // block
+        gd = buf["grads"][o["grad_off"]:o["grad_off"] + N]
+        g = (gd.view(torch.int16).cpu().numpy().view(np.uint16) if w.grad_dtype == wl.BF16 else gd.cpu().numpy()).reshape(n, m)
+        nw, nb = -(-N // W), -(-N // block)
         c0 = codes0[o["word_off"]:o["word_off"] + nw].copy()
         s0 = scales0[o["scale_off"]:o["scale_off"] + nb].copy()
         st = R.MatState(n, m, c0.copy(), s0.copy(), Q0[o["q_off"]:o["q_off"] + m * rank].reshape(m, rank).copy())
         Ph, Qn = R.step_matrix(g, st, rank, bits, block, w.lib_seed, l, 1)
-        tag = f"large mat {l} ({n}x{m})"
+        tag = f"{name} mat {l} ({n}x{m})"
         eP = U.rel_err(P1[o["p_off"]:o["p_off"] + n * rank].reshape(n, rank), Ph)
         eQ = U.rel_err(Q1[o["q_off"]:o["q_off"] + m * rank].reshape(m, rank), Qn)
         assert eP <= 1e-5, f"{tag}: P rel err {eP}"
@@ -257,7 +261,8 @@ def test_large_whole_model_second_step_against_the_oracle(env):
         gs = scales1[o["scale_off"]:o["scale_off"] + nb]
         dev = np.abs(gs - st.scales)
         if dev.max() > 0:
-            blk_rec = rec_of().reshape(-1, block).max(1)
+            rec = rec_of()
+            blk_rec = np.concatenate([rec, np.zeros((-N) % block, np.float32)]).reshape(-1, block).max(1)
             worst = float((dev / (1e-6 * np.maximum(st.scales, blk_rec) + x_tol)).max())
             assert worst <= 1.0, f"{tag}: scales off by {worst} times the tolerance"
         ex = U.check_codes_sparse(codes1[o["word_off"]:o["word_off"] + nw], st.codes, x_of, N, bits, block,
@@ -266,7 +271,7 @@ def test_large_whole_model_second_step_against_the_oracle(env):
         if l < 6 or ex:
             print(f"[fullsize whole model] {tag}: eP {eP:.1e} eQ {eQ:.1e} max scale deviation {dev.max():.2e} "
                   f"(x_tol {x_tol:.1e}), {ex} codes differ", flush=True)
-    print(f"[fullsize whole model] {excused} codes of {w.elements} excused as boundary cases", flush=True)
+    print(f"[fullsize whole model] {name}: {excused} codes of {w.elements} excused as boundary cases", flush=True)
     model.close()
 
 
