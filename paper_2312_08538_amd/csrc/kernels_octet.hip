@@ -219,12 +219,14 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 // time: octets are decoded in the coalesced load layout (8 lanes per row) into a wave-private LDS
 // tile (32 rows x 64 columns of p), read back one value per lane and instruction; the rows of P^
 // are converted from fp32.  Loads run one step ahead.  Partial sums per row tile go to the workspace.
+// Occupancy target (measured): four waves per SIMD with bf16 gradients (a few spilled registers cost less
+// than the fourth wave brings), three with fp32 gradients, whose octets take twice the registers.
 constexpr int kQTileCols = 64;
 constexpr int kQTilePitch = 80;     // floats per LDS tile row: rows 0..3 of a group fall on distinct banks
 constexpr int kQStepRows = 32;
 
 template <bool BF16, int BITS, int RH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BF16 ? 4 : 3, BF16 ? 4 : 3)))
 void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
                const float *__restrict__ scales, const float *__restrict__ Phat, double *ws)
 {
