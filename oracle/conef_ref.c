@@ -10,10 +10,10 @@
  * compression", arXiv 2312.08538):
  *   - Algorithm 2 (ConEF), per worker and per layer (Section 5, "applied in a
  *     layerwise fashion"):
- *         line 5   p = eta*g + e            (eta folded into g by the caller)
- *         line 6   Delta = Q(p)             gradient compressor: rank-r PowerSGD
- *         lines 7-8  x+ = x - Delta         decompress and apply (one worker: the aggregate is Delta)
- *         line 9   e+ = C(p - Delta)        error compressor: stochastic quantiser
+ *         accumulate   p = eta*g + e            (eta folded into g by the caller)
+ *         compress     Delta = Q(p)             gradient compressor: rank-r PowerSGD
+ *         update       x+ = x - Delta           decompress and apply (one worker: the aggregate is Delta)
+ *         error        e+ = C(p - Delta)        error compressor: stochastic quantiser
  *   - Section 4.3, Algorithm 4 (partial ConEF): p = eta*g + (1-beta) e, e+ = C(beta e + p - Delta).
  *   - Section 4.2.1, eq. (3): C(e_i) = ||e|| * sign(e_i) * xi_i, xi_i in
  *     {l/s, (l+1)/s}, rounded up with probability |e_i|/||e|| * s - l, with the
@@ -125,7 +125,7 @@ void ref_decode(const uint32_t *codes, const float *scales, int64_t N, int bits,
     }
 }
 
-/* Algorithm 2 line 5 with the decode fused: p_j = fma(d_blk, q_j, g_j), one rounding. */
+/* The accumulation step of Algorithm 2 (p = eta*g + e) with the decode fused: p_j = fma(d_blk, q_j, g_j), one rounding. */
 void ref_form_p(const void *g, int dtype, const uint32_t *codes, const float *scales,
                 int64_t N, int bits, int block, float *p)
 {
@@ -136,7 +136,7 @@ void ref_form_p(const void *g, int dtype, const uint32_t *codes, const float *sc
     }
 }
 
-/* Algorithm 4 (partial ConEF) line 5 with the same decode: p_j = fma(omb * d_blk, q_j, g_j) with
+/* The accumulation step of Algorithm 4 (partial ConEF), p = g + (1 - beta) e, with the same decode: p_j = fma(omb * d_blk, q_j, g_j) with
  * omb = fl32(1 - beta); the product omb * d_blk is rounded to fp32 first.  beta = 0 gives ref_form_p
  * bit for bit (d * 1 = d).                                                                          */
 void ref_form_p_partial(const void *g, int dtype, const uint32_t *codes, const float *scales,
@@ -225,7 +225,7 @@ void ref_lowrank_Q(const float *p, int64_t n, int64_t m, const float *Phat, int 
     }
 }
 
-/* Argument of the error compressor, Algorithm 2 line 9: x = p - Phat*Qn^T,
+/* Argument of the error compressor in the error step of Algorithm 2: x = p - Phat*Qn^T,
  * fp32, the rank-r sum taken as an fma chain over c = 0..r-1.            */
 void ref_residual(const float *p, int64_t n, int64_t m, const float *Phat, const float *Qn,
                   int r, float *x)
@@ -239,9 +239,9 @@ void ref_residual(const float *p, int64_t n, int64_t m, const float *Phat, const
         }
 }
 
-/* Decompression and update, Algorithm 2 lines 7 and 8: the (aggregated) compressed gradient
+/* Decompression and update (the aggregation and update steps of Algorithm 2): the (aggregated) compressed gradient
  * Delta = Phat*Qn^T is written out, or subtracted from the parameters, x <- x - Delta.  For one worker
- * the aggregate of line 7 is the worker's own Delta.  Each entry of Delta is the same fp32 fma chain
+ * the aggregate is the worker's own Delta.  Each entry of Delta is the same fp32 fma chain
  * over c = 0..r-1 as in ref_residual (so p = Delta + residual holds entry by entry up to the one
  * rounding of the subtraction); the update is one more fp32 subtraction.                              */
 void ref_decompress(int64_t n, int64_t m, const float *Phat, const float *Qn, int r, float *delta)
@@ -311,7 +311,7 @@ void ref_quantise(const float *x, int64_t N, int bits, int block,
  * receives the orthonormal factor, Q_out the new right factor (may alias
  * Q_state).  `work` holds 2*n*m floats (p and x).  identity_ec != 0 skips
  * the quantiser and stores x itself in `e_full` (that is Algorithm 1,
- * EFSGD, line 9) -- used only by tests.                                   */
+ * EFSGD, its error step) -- used only by tests.                                   */
 /* ------------------------------------------------------------------ */
 void ref_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int r, int bits, int block,
                      uint64_t seed, uint32_t mat, uint64_t step,
@@ -331,9 +331,9 @@ void ref_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int r, int 
 }
 
 /* One step of partial ConEF (Section 4.3, Algorithm 4) with the quantiser as error compressor:
- *   line 5   p = g + (1 - beta) e                 (ref_form_p_partial)
- *   line 6   Delta = P^ Q+^T from p
- *   line 9   e+ = C(beta e + p - Delta); beta e + p is g + e, formed as in ref_form_p (one fma), not
+ *   accumulate   p = g + (1 - beta) e                 (ref_form_p_partial)
+ *   compress     Delta = P^ Q+^T from p
+ *   error        e+ = C(beta e + p - Delta); beta e + p is g + e, formed as in ref_form_p (one fma), not
  *            as the sum of two rounded parts.
  * `work` holds 2*n*m floats.  beta = 0 is ref_step_matrix bit for bit.                              */
 void ref_step_matrix_partial(const void *g, int dtype, int64_t n, int64_t m, int r, int bits, int block,

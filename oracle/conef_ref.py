@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
 bench.py's cpu_baseline leg.  The product package never imports this module.
 
 Every function takes and returns numpy arrays; the arithmetic is all in the C
-file (Algorithm 2 lines 5, 6, 9; eq. (3) with the block max-norm; the rank-r
+file (Algorithm 2: accumulate, compress, error; eq. (3) with the block max-norm; the rank-r
 factorisation of Section 5.2).
 """
 from __future__ import annotations
@@ -180,7 +180,7 @@ def form_p(g, codes, scales, bits: int, block: int) -> np.ndarray:
 
 
 def form_p_partial(g, codes, scales, bits: int, block: int, beta: float) -> np.ndarray:
-    """Algorithm 4 line 5: g + (1 - beta) decode(codes, scales)."""
+    """The accumulation step of Algorithm 4: g + (1 - beta) decode(codes, scales)."""
     ga, dt = grad_array(g)
     N = ga.size
     c, s = _c(codes, np.uint32), _c(scales, np.float32)
@@ -238,7 +238,7 @@ def residual(p, Phat, Qn) -> np.ndarray:
 
 
 def decompress(Phat, Qn) -> np.ndarray:
-    """Delta = Phat Qn^T (Algorithm 2 line 7 for one worker), each entry an fp32 fma chain over c."""
+    """Delta = Phat Qn^T (the aggregated compressed gradient of Algorithm 2, for one worker), each entry an fp32 fma chain over c."""
     Pa, Qa = _c(Phat, np.float32), _c(Qn, np.float32)
     n, m = Pa.shape[0], Qa.shape[0]
     delta = np.empty((n, m), np.float32)
@@ -247,7 +247,7 @@ def decompress(Phat, Qn) -> np.ndarray:
 
 
 def apply_update(x, Phat, Qn) -> np.ndarray:
-    """x - Phat Qn^T (Algorithm 2 line 8); returns a new array."""
+    """x - Phat Qn^T (the update step of Algorithm 2); returns a new array."""
     xa = np.array(x, np.float32, order="C", copy=True)
     Pa, Qa = _c(Phat, np.float32), _c(Qn, np.float32)
     n, m = xa.shape
@@ -363,7 +363,7 @@ def cs_form_p(g, table, bucket, sign, beta: float) -> np.ndarray:
 
 
 def cs_update(x, bucket, sign, beta: float, table) -> None:
-    """table <- beta * table + sketch(x), in place (Algorithm 4 line 9 by linearity)."""
+    """table <- beta * table + sketch(x), in place (the error step of Algorithm 4, by linearity)."""
     xa = _c(x, np.float32)
     n, m = xa.shape
     assert table.flags.c_contiguous and table.shape[1] == m

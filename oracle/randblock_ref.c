@@ -11,9 +11,9 @@
  *     coordinates chosen uniformly at random and drops the rest; with the same seed on every worker
  *     the blocks coincide, so the kept values can be all-reduced.  Nothing is rescaled.
  *   - Algorithm 2 / Algorithm 4 around it, per worker and per layer (Section 5, "layerwise"):
- *         line 5   p = eta*g + (1 - beta) e
- *         line 6   Delta = p on the block, 0 elsewhere
- *         line 9   e+ = C(beta e + p - Delta)
+ *         accumulate   p = eta*g + (1 - beta) e
+ *         compress     Delta = p on the block, 0 elsewhere
+ *         error        e+ = C(beta e + p - Delta)
  *     with either error compressor: the block-wise quantiser of Section 4.2.1 or the count sketch of
  *     Section 4.2.2.
  *
@@ -70,12 +70,12 @@ void ref_rb_step_matrix(const void *g, int dtype, int64_t N, int64_t k, int bits
 {
     float *p = work, *x = work + N;
     const int64_t start = ref_rb_start(seed, mat, step, N, k);
-    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);       /* line 5 */
-    for (int64_t j = 0; j < k; ++j) delta[j] = p[start + j];                     /* line 6 */
+    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);       /* accumulate */
+    for (int64_t j = 0; j < k; ++j) delta[j] = p[start + j];                     /* compress */
     ref_form_p(g, dtype, codes, scales, N, bits, block, x);                      /* g + e: beta e + p outside the block */
     ref_decode(codes, scales, N, bits, block, p);                                /* e */
     for (int64_t j = start; j < start + k; ++j) x[j] = beta * p[j];              /* inside: beta e */
-    ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);       /* line 9 */
+    ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);       /* error */
 }
 
 /* The same with the count sketch (row sketch of an n x m matrix, w buckets) as error compressor.
@@ -90,9 +90,9 @@ void ref_cs_rb_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int64
     int8_t *sign = (int8_t *)malloc((size_t)n);
     ref_cs_hash(seed, mat, n, w, bucket, sign);
     const int64_t start = ref_rb_start(seed, mat, step, N, k);
-    ref_cs_form_p(g, dtype, table, tdtype, n, m, bucket, sign, beta, p);         /* line 5 */
-    for (int64_t j = 0; j < k; ++j) { delta[j] = p[start + j]; p[start + j] = 0.0f; }    /* line 6; p - Delta */
-    ref_cs_update(p, n, m, bucket, sign, w, beta, table, tdtype);                /* line 9 by linearity */
+    ref_cs_form_p(g, dtype, table, tdtype, n, m, bucket, sign, beta, p);         /* accumulate */
+    for (int64_t j = 0; j < k; ++j) { delta[j] = p[start + j]; p[start + j] = 0.0f; }    /* compress; p - Delta */
+    ref_cs_update(p, n, m, bucket, sign, w, beta, table, tdtype);                /* error, by linearity */
     free(bucket);
     free(sign);
 }
@@ -117,14 +117,14 @@ float ref_ss_step_matrix(const void *g, int dtype, int64_t N, int bits, int bloc
                          uint32_t *sign_words, float *work)
 {
     float *p = work, *x = work + N;
-    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);       /* line 5 */
+    ref_form_p_partial(g, dtype, codes, scales, N, bits, block, beta, p);       /* accumulate */
     const float c = l1_scale(p, N);
     ref_form_p(g, dtype, codes, scales, N, bits, block, x);                      /* g + e */
     memset(sign_words, 0, sizeof(uint32_t) * (size_t)((N + 31) / 32));
     for (int64_t j = 0; j < N; ++j) {
         const int neg = signbit(p[j]) != 0;
         if (neg) sign_words[j / 32] |= 1u << (j % 32);
-        x[j] = x[j] - (neg ? -c : c);                                            /* line 9 argument */
+        x[j] = x[j] - (neg ? -c : c);                                            /* argument of the error step */
     }
     ref_quantise(x, N, bits, block, seed, mat, step, NULL, codes, scales);
     return c;

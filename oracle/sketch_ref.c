@@ -15,11 +15,11 @@
  *     one entry of the sketched vector: n hashes instead of nm, and the table is w x m with
  *     S[h(i), :] += s(i) e[i, :]  (row variant).
  *   - Section 4.3, Algorithm 4 (partial ConEF), per worker and per layer:
- *         line 5   p  = eta*g + (1 - beta) e        (eta folded into g by the caller)
- *         line 6   Delta = Q(p)                      rank-r compressor of conef_ref.c
- *         line 9   e+ = C(beta e + p - Delta)
+ *         accumulate   p  = eta*g + (1 - beta) e        (eta folded into g by the caller)
+ *         compress     Delta = Q(p)                      rank-r compressor of conef_ref.c
+ *         error        e+ = C(beta e + p - Delta)
  *     and, by the linearity of the sketch (Section 4.2.2, and the remark after Algorithm 4),
- *     line 9 is taken without decoding e:  S+ = beta S + C(p - Delta).  beta = 0 is Algorithm 2.
+ *     the error step is taken without decoding e:  S+ = beta S + C(p - Delta).  beta = 0 is Algorithm 2.
  *   - Section 5.2: the table may be kept in fp16 ("mixed precision trick").
  *
  * Readings where the paper is silent:
@@ -130,7 +130,7 @@ void ref_cs_decode(const void *table, int tdtype, int64_t n, int64_t m, const in
         }
 }
 
-/* Algorithm 4 line 5: p = g + (1 - beta) e, one fused multiply-add per entry; omb = fl32(1 - beta). */
+/* The accumulation step of Algorithm 4: p = g + (1 - beta) e, one fused multiply-add per entry; omb = fl32(1 - beta). */
 void ref_cs_form_p(const void *g, int dtype, const void *table, int tdtype, int64_t n, int64_t m,
                    const int32_t *bucket, const int8_t *sign, float beta, float *p)
 {
@@ -143,7 +143,7 @@ void ref_cs_form_p(const void *g, int dtype, const void *table, int tdtype, int6
         }
 }
 
-/* Algorithm 4 line 9 through the linearity of the sketch: S+ = beta S + C(x), x = p - Delta.
+/* The error step of Algorithm 4 through the linearity of the sketch: S+ = beta S + C(x), x = p - Delta.
  * C(x)[b, k] is the sum of s(i) x[i, k] over the rows i of bucket b, added in ascending row order
  * from 0; then one fused multiply-add with the old entry and one rounding to the table's type.    */
 void ref_cs_update(const float *x, int64_t n, int64_t m, const int32_t *bucket, const int8_t *sign,
@@ -163,7 +163,7 @@ void ref_cs_update(const float *x, int64_t n, int64_t m, const int32_t *bucket, 
     free(acc);
 }
 
-/* One full step for one matrix (Algorithm 4 lines 5, 6, 9).  `table` is updated in place; P_out
+/* One full step for one matrix (Algorithm 4: accumulate, compress, error).  `table` is updated in place; P_out
  * receives the orthonormal factor, Q_out the new right factor (may alias Q_state).  `work` holds
  * 2*n*m floats (p, then x = p - Delta).                                                          */
 void ref_cs_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int r, int64_t w, float beta,
