@@ -107,11 +107,13 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
             d.bptr_off = bp; bp += d.w + 1;
         }
         plan.table_elems = (size_t)t;
-        // rows per item of the octet path's update pass: as many as leave about 4096 items, 32 to 256
+        // rows per item of the octet path's update pass: as many as leave about 2048 items, 32 to 256 (an item
+        // first loads its 512 rows of Q+; measured on 124 M to 1.3 G elements: 4096 and 1024 items are both slower)
         int64_t total_elems = 0;
         for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
+        const int64_t min_items = 2048;
         int64_t cs_rows = 32;
-        while (cs_rows < 256 && total_elems / (cs_rows * 2 * 512) >= 4096) cs_rows *= 2;
+        while (cs_rows < 256 && total_elems / (cs_rows * 2 * 512) >= min_items) cs_rows *= 2;
         plan.row_hash.assign((size_t)h, 0);
         plan.bucket_rows.assign((size_t)h, 0);
         plan.bucket_ptr.assign((size_t)bp, 0);
