@@ -192,9 +192,10 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
         const bool block_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64 && block >= 64;
         int64_t total_elems = 0;
         for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
-        // rows per wave item of the err pass: aim at >= ~4096 wave items over the model
+        // rows per wave item of the err pass: aim at >= ~8192 wave items over the model (measured on 124 M and
+        // 210 M elements: half and twice as many rows per item are both slower)
         int err_rows = 128;
-        while (err_rows > 8 && total_elems / ((int64_t)err_rows * 512) < 4096) err_rows >>= 1;
+        while (err_rows > 8 && total_elems / ((int64_t)err_rows * 512) < 8192) err_rows >>= 1;
         // rows per wave item of the Q+ pass (64 columns wide): aim at >= ~4096 wave items
         int q_rows = 512;
         while (q_rows > 64 && total_elems / ((int64_t)q_rows * 64) < 4096) q_rows >>= 1;
