@@ -20,6 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conef_ref.c")
 _SRC_SKETCH = os.path.join(_HERE, "sketch_ref.c")
 _SRC_RB = os.path.join(_HERE, "randblock_ref.c")
+_SRC_I = os.path.join(_HERE, "iconef_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -28,10 +29,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_SKETCH), os.path.getmtime(_SRC_RB))
+    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -105,6 +106,12 @@ def lib() -> ctypes.CDLL:
         L.ref_ss_step_matrix.restype = f32
         L.ref_cs_ss_step_matrix.argtypes = [vp, i32, i64, i64, i64, f32, u64, u32, vp, i32, vp, vp]
         L.ref_cs_ss_step_matrix.restype = f32
+        L.ref_i_form_p.argtypes = [vp, i32, vp, vp, vp, vp, i64, i32, i32, vp, vp]
+        L.ref_i_form_p.restype = None
+        L.ref_i_rb_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
+        L.ref_i_rb_step_matrix.restype = None
+        L.ref_i_ss_step_matrix.argtypes = [vp, i32, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
+        L.ref_i_ss_step_matrix.restype = f32
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -451,4 +458,44 @@ def cs_ss_step_matrix(g, table, beta: float, seed: int, mat: int):
     words = np.empty((n * m + 31) // 32, np.uint32)
     work = np.empty(n * m, np.float32)
     c = lib().ref_cs_ss_step_matrix(_p(ga), dt, n, m, table.shape[0], beta, seed, mat, _p(table), tt, _p(words), _p(work))
+    return words, np.float32(c)
+
+
+# ---------------------------------------------------------------- iConEF version 1 (oracle/iconef_ref.c)
+def _check_state(*arrays):
+    for a in arrays:
+        assert a.flags.c_contiguous and a.dtype in (np.uint32, np.float32)
+
+
+def i_form_p(g, codes, scales, codes2, scales2, bits: int, block: int) -> np.ndarray:
+    """p = g + e~ + q (Algorithm 3, accumulation), flat fp32."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales, codes2, scales2)
+    tmp, p = np.empty(N, np.float32), np.empty(N, np.float32)
+    lib().ref_i_form_p(_p(ga), dt, _p(codes), _p(scales), _p(codes2), _p(scales2), N, bits, block, _p(tmp), _p(p))
+    return p
+
+
+def i_rb_step_matrix(g, codes, scales, codes2, scales2, k: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """One iConEF-v1 step with the random-block compressor; both vectors updated in place; returns Delta (k values)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales, codes2, scales2)
+    delta = np.empty(k, np.float32)
+    work = np.empty(2 * N, np.float32)
+    lib().ref_i_rb_step_matrix(_p(ga), dt, N, k, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
+                               _p(scales2), _p(delta), _p(work))
+    return delta
+
+
+def i_ss_step_matrix(g, codes, scales, codes2, scales2, bits: int, block: int, seed: int, mat: int, step: int):
+    """One iConEF-v1 step with the scaled-sign compressor; both vectors updated in place; returns (sign words, c)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales, codes2, scales2)
+    words = np.empty((N + 31) // 32, np.uint32)
+    work = np.empty(2 * N, np.float32)
+    c = lib().ref_i_ss_step_matrix(_p(ga), dt, N, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
+                                   _p(scales2), _p(words), _p(work))
     return words, np.float32(c)
