@@ -215,6 +215,27 @@ int conef_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
 int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *sign_out, float *scale_out,
                      void *workspace, void *hip_stream);
 
+/* ---- Improved contractive error feedback, version 1 (Section 3.2, Algorithm 3) with the quantiser as both error
+ * compressors and an element-wise gradient compressor.  A worker keeps two compressed vectors of the same layout,
+ * e~ (err_codes, err_scales) and q (err2_codes, err2_scales), both zero at the start:
+ *   p     = g + e~ + q                   (Algorithm 3 line 5; p_j = fma(d2, c2_j, fma(d1, c1_j, g_j)))
+ *   Delta = Q(p)                         (line 6: the random block of conef_rb_step / the scaled sign of conef_ss_step)
+ *   e~+   = C(p - Delta)                 (line 10; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign)
+ *   q+    = C(p - Delta - e~+)           (line 14; the decoded e~+ is rounded to fp32, then subtracted)
+ * The second quantisation draws its own random numbers: element j uses the 16-bit draw it has in conef_step, taken
+ * from the Philox call whose matrix word is l + 2^31.  q+ holds what the first rounding left, so its block scales
+ * are at most one quantisation step of e~+: the stored pair is about s = 2^(bits-1) - 1 times closer to p - Delta
+ * than e~+ alone, for twice the state.  Algorithm 3 has no partial update: CONEF_ESTATE unless the context's beta is 0,
+ * on a count-sketch context, and for conef_i_rb_step before conef_rb_configure.
+ *   err2_codes, err2_scales   device, in/out: laid out like err_codes / err_scales (same offsets and sizes); must
+ *                             not be the same buffers (CONEF_EINVAL)
+ * Every other argument, alignment, asynchrony and errors as for conef_rb_step / conef_ss_step. */
+int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
+int conef_i_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, uint32_t *sign_out, float *scale_out, void *workspace, uint64_t step,
+                    void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

@@ -23,6 +23,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_strerror", "conef_set_beta",
            "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
+           "conef_i_rb_step", "conef_i_ss_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.conef_rb_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rb_start.argtypes = [vp, i32, u64, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rb_step.argtypes = [vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i_rb_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i_ss_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_cs_rb_step.argtypes = [vp, vp, vp, vp, u64, vp]
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
     L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
@@ -185,6 +188,18 @@ def conef_rb_step(ctx, grads, err_codes, err_scales, delta_out, step: int, strea
 
 def conef_cs_rb_step(ctx, grads, table, delta_out, step: int, stream=0):
     _check(lib().conef_cs_rb_step(ctx, _ptr(grads), _ptr(table), _ptr(delta_out), step, stream), "conef_cs_rb_step")
+
+
+# improved contractive error feedback, version 1 (two compressed error vectors)
+def conef_i_rb_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_i_rb_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
+                                 _ptr(delta_out), step, stream), "conef_i_rb_step")
+
+
+def conef_i_ss_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, sign_out, scale_out, workspace, step: int,
+                    stream=0):
+    _check(lib().conef_i_ss_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
+                                 _ptr(sign_out), _ptr(scale_out), _ptr(workspace), step, stream), "conef_i_ss_step")
 
 
 def conef_set_beta(ctx, beta: float) -> None:

@@ -423,7 +423,23 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, static_cast<hipStream_t>(hip_stream)));
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, float *delta_out, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !delta_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch || ctx->plan.rb_delta_elems == 0 || ctx->plan.beta != 0.0f) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
+        misaligned(err2_scales, 4) || misaligned(delta_out, 4) || err_codes == err2_codes || err_scales == err2_scales)
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales,
+                                 static_cast<hipStream_t>(hip_stream)));
 }
 
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
@@ -463,7 +479,23 @@ int conef_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     return hip_rc(launch_ss_step(ctx->dev, grads, err_codes, err_scales, sign_out, scale_out, ws_doubles(ctx, workspace), step,
-                                 static_cast<hipStream_t>(hip_stream)));
+                                 nullptr, nullptr, static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_i_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, uint32_t *sign_out, float *scale_out, void *workspace, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !sign_out || !scale_out || !workspace)
+        return CONEF_EINVAL;
+    if (ctx->plan.sketch || ctx->plan.beta != 0.0f) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
+        misaligned(err2_scales, 4) || misaligned(sign_out, 4) || misaligned(scale_out, 4) || misaligned(workspace, 256) ||
+        err_codes == err2_codes || err_scales == err2_scales)
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    return hip_rc(launch_ss_step(ctx->dev, grads, err_codes, err_scales, sign_out, scale_out, ws_doubles(ctx, workspace), step,
+                                 err2_codes, err2_scales, static_cast<hipStream_t>(hip_stream)));
 }
 
 int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *sign_out, float *scale_out,

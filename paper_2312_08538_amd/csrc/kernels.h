@@ -54,15 +54,17 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
 // Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
+// codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, hipStream_t st);
+                          uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st);
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
                              hipStream_t st);
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
-                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, hipStream_t st);
+                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
+                       float *scales2, hipStream_t st);
 // Scaled-sign gradient compressor: l1 norm pass, scale, sign bits + compression.
 hipError_t launch_ss_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *sign_words,
-                          float *c_scale, double *ws, uint64_t step, hipStream_t st);
+                          float *c_scale, double *ws, uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st);
 hipError_t launch_cs_ss_step(const DevicePlan &dp, const void *grads, void *table, uint32_t *sign_words, float *c_scale,
                              double *ws, hipStream_t st);
 void launch_ss_scale(const DevicePlan &dp, const double *ws, float *c_scale, hipStream_t st);

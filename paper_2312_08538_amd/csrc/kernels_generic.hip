@@ -4,6 +4,8 @@
 //
 // All reductions run in a fixed order (no floating-point atomics), so results are
 // reproducible from run to run.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -182,17 +184,38 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
 // wave, blocks and elements in a fixed order), MODE 2 reads c, sets the sign bits of the negative entries (the
 // sign words of these matrices are cleared by the launcher first; bits are set with atomic ORs, whose result
 // does not depend on their order) and compresses (g + e) - Delta.
+// TWO: improved contractive error feedback, version 1 (Algorithm 3, no beta), with a second compressed vector
+// (codes2, scales2) of the same layout: p = g + e~ + q, e~+ = C(p - Delta), q+ = C(p - Delta - e~+) with random
+// numbers of its own (matrix word of the Philox counter + 2^31).  The second block maximum needs the first
+// rounding of the whole block, so the block is swept three times: maximum, maximum of what the rounding leaves,
+// and both roundings again with the stores.
 constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
 
-template <int MODE>
+template <int MODE, bool TWO>
 __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
                                              const float *scales, int64_t j, int64_t start, float *delta, bool write,
-                                             float c, uint32_t *sign_words)
+                                             float c, uint32_t *sign_words, const uint32_t *codes2, const float *scales2)
 {
     const int W = 32 / dp.bits;
     const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
     const float dstep = scales[d.scale_off + j / dp.block] * inv_levels(dp.bits);
     const float g = load_grad(grads, dp.dtype, d.grad_off + j);
+    if (TWO) {
+        const int q2 = code_field(codes2[d.word_off + j / W], (int)(j % W), dp.bits);
+        const float dstep2 = scales2[d.scale_off + j / dp.block] * inv_levels(dp.bits);
+        const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, (float)q, g));
+        if (MODE == kModeBlock) {
+            if (j >= start && j < start + d.rb_k) {
+                if (write) delta[d.rb_delta_off + (j - start)] = pv;
+                return 0.0f;
+            }
+            return pv;
+        }
+        if (MODE == kModeNorm) return pv;
+        const bool neg = (__float_as_uint(pv) >> 31) != 0;
+        if (write && neg) atomicOr(sign_words + d.sign_off + j / 32, 1u << (j % 32));
+        return pv - (neg ? -c : c);
+    }
     if (MODE == kModeBlock) {
         if (j >= start && j < start + d.rb_k) {
             if (write) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
@@ -207,10 +230,11 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
     return __builtin_fmaf(dstep, (float)q, g) - (neg ? -c : c);
 }
 
-template <int MODE>
+template <int MODE, bool TWO>
 __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *grads, uint32_t *codes, float *scales,
                                                     float *delta, uint32_t step_lo, uint32_t step_hi,
-                                                    uint32_t *sign_words, const float *c_scale, double *ws)
+                                                    uint32_t *sign_words, const float *c_scale, double *ws,
+                                                    uint32_t *codes2, float *scales2)
 {
     const WorkItem it = dp.rb_g_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -227,7 +251,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
         float a = 0.0f;
         for (int e = lane; e < cnt; e += 64) {
-            const float v = rb_argument<MODE>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words);
+            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2);
             if (MODE == kModeNorm) l1 += (double)fabsf(v);
             a = fmaxf(a, fabsf(v));
         }
@@ -235,12 +259,58 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         a = wave_max(a);
         const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
         const int sweeps = (cnt + 63) / 64;
+        if (TWO) {
+            const uint32_t mask = (1u << bits) - 1u;
+            const float dnew = a * inv_levels(bits);
+            // argument of the second rounding: x minus the decoded first rounding of x
+            auto second_argument = [&](int64_t j, uint32_t &f1) {
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2);
+                uint32_t out[4];
+                philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                f1 = quantise_field(x, inv16, draw16(out, (int)(j & 7)), mask);
+                const int qn = (int)(f1 << (32 - bits)) >> (32 - bits);
+                return x - dnew * (float)qn;
+            };
+            float a2 = 0.0f;
+            for (int e = lane; e < cnt; e += 64) {
+                uint32_t f1;
+                a2 = fmaxf(a2, fabsf(second_argument(j0 + e, f1)));
+            }
+            a2 = wave_max(a2);
+            const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
+            for (int sw = 0; sw < sweeps; ++sw) {
+                const int e = sw * 64 + lane;
+                uint32_t field = 0, field2 = 0;
+                if (e < cnt) {
+                    const int64_t j = j0 + e;
+                    uint32_t f1, out[4];
+                    const float y = second_argument(j, f1);
+                    philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                    field = f1 << (bits * (e % W));
+                    field2 = quantise_field(y, inv16_2, draw16(out, (int)(j & 7)), mask) << (bits * (e % W));
+                }
+                // every lane of the wave has read its old codes before any word of the sweep is stored
+                for (int o = 1; o < W; o <<= 1) {
+                    field |= __shfl_xor(field, o, 64);
+                    field2 |= __shfl_xor(field2, o, 64);
+                }
+                if ((lane % W) == 0 && e < cnt) {
+                    codes[d.word_off + (j0 + e) / W] = field;
+                    codes2[d.word_off + (j0 + e) / W] = field2;
+                }
+            }
+            if (lane == 0) {
+                scales[d.scale_off + blk] = a;
+                scales2[d.scale_off + blk] = a2;
+            }
+            continue;
+        }
         for (int sw = 0; sw < sweeps; ++sw) {
             const int e = sw * 64 + lane;
             uint32_t field = 0;
             if (e < cnt && a > 0.0f) {
                 const int64_t j = j0 + e;
-                const float x = rb_argument<MODE>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
@@ -410,13 +480,21 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     return hipGetLastError();
 }
 
+// codes2 / scales2: the second error vector of Algorithm 3, or null (here and in launch_ss_step)
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, hipStream_t st)
+                          uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st)
 {
-    octet_stream_step(dp, kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, st);
-    if (dp.n_rb_g > 0)
-        hipLaunchKernelGGL(k_rb_generic<kModeBlock>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
-                           (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr, (double *)nullptr);
+    octet_stream_step(dp, kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, codes2, scales2, st);
+    if (dp.n_rb_g > 0) {
+        if (codes2)
+            hipLaunchKernelGGL((k_rb_generic<kModeBlock, true>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+                               (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr,
+                               (double *)nullptr, codes2, scales2);
+        else
+            hipLaunchKernelGGL((k_rb_generic<kModeBlock, false>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+                               (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr,
+                               (double *)nullptr, codes2, scales2);
+    }
     return hipGetLastError();
 }
 
@@ -432,20 +510,26 @@ void launch_ss_clear(const DevicePlan &dp, uint32_t *sign_words, hipStream_t st)
 
 // Scaled sign with the quantiser: l1 norm (one pass), scale, then sign bits + compression of (g + e) - Delta.
 hipError_t launch_ss_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *sign_words,
-                          float *c_scale, double *ws, uint64_t step, hipStream_t st)
+                          float *c_scale, double *ws, uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st)
 {
     const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
-    octet_stream_step(dp, kModeNorm, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, st);
+    auto generic = [&](auto mode) {
+        constexpr int M = decltype(mode)::value;
+        if (codes2)
+            hipLaunchKernelGGL((k_rb_generic<M, true>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
+                               lo, hi, sign_words, (const float *)c_scale, ws, codes2, scales2);
+        else
+            hipLaunchKernelGGL((k_rb_generic<M, false>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
+                               lo, hi, sign_words, (const float *)c_scale, ws, codes2, scales2);
+    };
+    octet_stream_step(dp, kModeNorm, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, codes2, scales2, st);
     if (dp.n_rb_g > 0) {
-        hipLaunchKernelGGL(k_rb_generic<kModeNorm>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
-                           lo, hi, sign_words, (const float *)c_scale, ws);
+        generic(std::integral_constant<int, kModeNorm>{});
         launch_ss_clear(dp, sign_words, st);
     }
     launch_ss_scale(dp, ws, c_scale, st);
-    octet_stream_step(dp, kModeSign, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, st);
-    if (dp.n_rb_g > 0)
-        hipLaunchKernelGGL(k_rb_generic<kModeSign>, dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, (float *)nullptr,
-                           lo, hi, sign_words, (const float *)c_scale, ws);
+    octet_stream_step(dp, kModeSign, grads, codes, scales, nullptr, step, sign_words, c_scale, ws, codes2, scales2, st);
+    if (dp.n_rb_g > 0) generic(std::integral_constant<int, kModeSign>{});
     return hipGetLastError();
 }
 

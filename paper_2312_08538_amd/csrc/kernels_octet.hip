@@ -60,6 +60,31 @@ __device__ __forceinline__ RawOctet<BF16, BITS> load_octet_always(const MatDesc 
     return r;
 }
 
+// Code bits and block scale of octet `o` of a second compressed vector laid out like the first
+// (the second error vector of Algorithm 3).
+template <int BITS>
+struct RawCodes {
+    uint32_t c0, c1;
+    float scale;
+};
+
+template <int BITS>
+__device__ __forceinline__ RawCodes<BITS> load_codes_always(const MatDesc &d, const uint32_t *codes, const float *scales, int64_t o)
+{
+    RawCodes<BITS> r;
+    r.c1 = 0;
+    if (BITS == 8) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + d.word_off + o * 2);
+        r.c0 = c.x; r.c1 = c.y;
+    } else if (BITS == 4) {
+        r.c0 = codes[d.word_off + o];
+    } else {
+        r.c0 = reinterpret_cast<const uint16_t *>(codes + d.word_off)[o];
+    }
+    r.scale = scales[d.scale_off + (o >> d.lb_shift)];
+    return r;
+}
+
 // omb: 1 - beta of the partial update in the P and Q+ passes (Algorithm 4 line 5), 1 in the err pass
 template <bool BF16, int BITS>
 __device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, float omb, float p[8])
@@ -561,12 +586,18 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 // MODE 1 adds up |p| in fp64, one partial sum per wave in a fixed order (the scale kernel adds the partials in
 // item order); MODE 2 reads c, writes one sign byte per octet (bit e set if element e is negative) and
 // compresses (g + e) - Delta.
+// TWO: improved contractive error feedback, version 1 (Algorithm 3, no beta): a second compressed vector q of the
+// same layout (codes2, scales2) is added in the accumulation, p = g + e~ + q; the first vector becomes
+// e~+ = C(p - Delta) as before and the second q+ = C(p - Delta - e~+): the decoded e~+ (rounded to fp32) is
+// subtracted, the block maximum taken again and the difference rounded with random numbers of its own (matrix
+// word of the Philox counter + 2^31), all in registers.
 constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
 
-template <bool BF16, int BITS, int MODE>
+template <bool BF16, int BITS, int MODE, bool TWO>
 __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
                                                   float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi,
-                                                  uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws)
+                                                  uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws,
+                                                  uint32_t *codes2, float *scales2)
 {
     const int lane = threadIdx.x & 63;
     const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -585,13 +616,17 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
     const int64_t n_oct = d.N >> 3;
     auto clamp = [&](int64_t o) { return o < n_oct ? o : n_oct - 1; };
     RawOctet<BF16, BITS> cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, clamp((int64_t)it.a * 64 + lane));
+    RawCodes<BITS> cur2 = {0u, 0u, 0.0f};
+    if (TWO) cur2 = load_codes_always<BITS>(d, codes2, scales2, clamp((int64_t)it.a * 64 + lane));
     for (int rr = 0; rr < it.b; ++rr) {
         const int64_t o_raw = ((int64_t)it.a + rr) * 64 + lane;
         const bool valid = o_raw < n_oct;
         const int64_t o = clamp(o_raw);
         const RawOctet<BF16, BITS> r = cur;
+        const RawCodes<BITS> r2 = cur2;
         // the next run is requested before this one is worked on (the last one re-reads itself)
         cur = load_octet_always<BF16, BITS>(d, grads, codes, scales, clamp(o_raw + (rr + 1 < it.b ? 64 : 0)));
+        if (TWO) cur2 = load_codes_always<BITS>(d, codes2, scales2, clamp(o_raw + (rr + 1 < it.b ? 64 : 0)));
         float g[8];
         if (BF16) {
             const uint32_t w[4] = {r.g0.x, r.g0.y, r.g0.z, r.g0.w};
@@ -606,7 +641,8 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             g[6] = __uint_as_float(r.g1.z); g[7] = __uint_as_float(r.g1.w);
         }
         const float dstep = r.scale * inv_levels(BITS);
-        const float dpart = dstep * dp.omb;
+        const float dpart = TWO ? dstep : dstep * dp.omb;
+        const float dstep2 = r2.scale * inv_levels(BITS);
         float x[8];
         float a = 0.0f;
         uint32_t neg_bits = 0;
@@ -617,7 +653,25 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             else q = code_field(r.c0, e, BITS);
             const float qf = (float)q;
             const int64_t j = o * 8 + e;
-            if (MODE == kModeBlock) {
+            if (TWO) {
+                int q2;
+                if (BITS == 8) q2 = code_field(e < 4 ? r2.c0 : r2.c1, e & 3, 8);
+                else q2 = code_field(r2.c0, e, BITS);
+                // p = g + e~ + q; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign
+                const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, qf, g[e]));
+                if (MODE == kModeBlock) {
+                    const bool kept = j >= start && j < stop;
+                    if (kept && valid) delta[d.rb_delta_off + (j - start)] = pv;
+                    x[e] = kept ? 0.0f : pv;
+                } else if (MODE == kModeNorm) {
+                    l1 += valid ? (double)fabsf(pv) : 0.0;
+                    x[e] = 0.0f;
+                } else {
+                    const bool neg = (__float_as_uint(pv) >> 31) != 0;
+                    neg_bits |= (neg ? 1u : 0u) << e;
+                    x[e] = pv - (neg ? -c : c);
+                }
+            } else if (MODE == kModeBlock) {
                 if (j >= start && j < stop) {
                     if (valid) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
                     x[e] = dp.beta * (dstep * qf);
@@ -650,6 +704,26 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             store_codes<BITS>(d, codes, o, f);
             if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
         }
+        if (TWO) {
+            // q+ = C(x - e~+): what the first rounding left, one level finer
+            const float dnew = a * inv_levels(BITS);
+            float a2 = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int qn = (int)(f[e] << (32 - BITS)) >> (32 - BITS);
+                x[e] = x[e] - dnew * (float)qn;
+                a2 = fmaxf(a2, fabsf(x[e]));
+            }
+            a2 = block_max(a2, d.lb_shift);
+            const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
+            philox4x32_10((uint32_t)o, (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16_2, draw16(rnd, e), mask);
+            if (valid) {
+                store_codes<BITS>(d, codes2, o, f);
+                if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales2[d.scale_off + (o >> d.lb_shift)] = a2;
+            }
+        }
     }
     if (MODE == kModeNorm) {
         l1 = wave_sum(l1);
@@ -659,24 +733,29 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
 
 }  // namespace
 
-// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign
+// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign; codes2 / scales2: the second error
+// vector of Algorithm 3, or null for plain contractive error feedback
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
-                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, hipStream_t st)
+                       uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
+                       float *scales2, hipStream_t st)
 {
     if (dp.n_rb <= 0) return;
     const dim3 grid((dp.n_rb + 3) / 4);
     const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+    const bool two = codes2 != nullptr;
+#define CONEF_STREAM_LAUNCH(BF, B, M, T)                                                                                           \
+    hipLaunchKernelGGL((k_rb_octet<BF, B, M, T>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi, sign_words,     \
+                       c_scale, ws, codes2, scales2)
+#define CONEF_STREAM_MODE(BF, B, M)                                                                                                \
+    do {                                                                                                                           \
+        if (two) CONEF_STREAM_LAUNCH(BF, B, M, true);                                                                              \
+        else CONEF_STREAM_LAUNCH(BF, B, M, false);                                                                                 \
+    } while (0)
 #define CONEF_STREAM_CASE(BF, B)                                                                                                   \
     case ((BF ? 1 : 0) << 8) | B:                                                                                                  \
-        if (mode == kModeBlock)                                                                                                    \
-            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeBlock>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,   \
-                               sign_words, c_scale, ws);                                                                           \
-        else if (mode == kModeNorm)                                                                                                \
-            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeNorm>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,    \
-                               sign_words, c_scale, ws);                                                                           \
-        else                                                                                                                       \
-            hipLaunchKernelGGL((k_rb_octet<BF, B, kModeSign>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi,    \
-                               sign_words, c_scale, ws);                                                                           \
+        if (mode == kModeBlock) CONEF_STREAM_MODE(BF, B, kModeBlock);                                                              \
+        else if (mode == kModeNorm) CONEF_STREAM_MODE(BF, B, kModeNorm);                                                           \
+        else CONEF_STREAM_MODE(BF, B, kModeSign);                                                                                  \
         break;
     switch ((dp.dtype << 8) | dp.bits) {
         CONEF_STREAM_CASE(false, 2)
@@ -687,6 +766,8 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
         CONEF_STREAM_CASE(true, 8)
     default: break;
     }
+#undef CONEF_STREAM_LAUNCH
+#undef CONEF_STREAM_MODE
 #undef CONEF_STREAM_CASE
 }
 
