@@ -1,0 +1,116 @@
+"""Parity at full size of the steps with an element-wise gradient compressor, in the launch configuration `bench.py`
+times: every matrix of the `large` workload (1.31 G elements, bf16 gradients, 4-bit codes, blocks of 128), whole.
+The library's second step (so that the state it decodes is not zero) is compared with one oracle step per matrix
+started from the state the library itself held before that step (downloaded), on the gradients the library read:
+kept values, sign words, codes and scales of one or two error vectors, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2312_08538_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import conef_ref as R
+    from paper_2312_08538_amd import binding as B
+
+    B.lib()
+    return R, B, torch
+
+
+@pytest.mark.parametrize("which", ["random_block", "scaled_sign", "iconef_random_block", "iconef_scaled_sign"])
+def test_large_whole_model_stream_step_against_the_oracle(env, which):
+    R, B, torch = env
+    w = wl.WORKLOADS["large"]
+    bits, block, W, seed = w.bits, w.block, 32 // w.bits, w.lib_seed
+    two, block_mode = which.startswith("iconef"), which.endswith("random_block")
+    keep = wl.random_block_keep(w.layout, 0.1)
+    model = B.Model(w.layout, w.rank, bits, block, w.grad_dtype, seed)
+    B.conef_rb_configure(model.ctx, keep)
+    buf = model.alloc()
+    codes2 = torch.zeros_like(buf["codes"]) if two else None
+    scales2 = torch.zeros_like(buf["scales"]) if two else None
+    delta = torch.zeros(B.conef_rb_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
+    signs = torch.zeros(B.conef_ss_sizes(model.ctx)["sign_words"], dtype=torch.int32, device="cuda:0")
+    cs = torch.zeros(len(w.layout), dtype=torch.float32, device="cuda:0")
+    goffs = [o["grad_off"] for o in model.offsets]
+    st = model.stream_handle()
+
+    def launch(t):
+        print(f"[fullsize stream {which}] step {t}: launching", flush=True)
+        if which == "random_block":
+            B.conef_rb_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
+        elif which == "scaled_sign":
+            B.conef_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], signs, cs, buf["ws"], t, st)
+        elif which == "iconef_random_block":
+            B.conef_i_rb_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
+        else:
+            B.conef_i_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, signs, cs, buf["ws"], t, st)
+        torch.cuda.synchronize()
+
+    def download():
+        out = [buf["codes"].cpu().numpy().view(np.uint32), buf["scales"].cpu().numpy()]
+        if two:
+            out += [codes2.cpu().numpy().view(np.uint32), scales2.cpu().numpy()]
+        return out
+
+    wl.device_fill_gradients(w, 0, buf["grads"], goffs)
+    launch(0)
+    before = download()
+    wl.device_fill_gradients(w, 1, buf["grads"], goffs)
+    launch(1)
+    after = download()
+    delta_h = delta.cpu().numpy()
+    signs_h = signs.cpu().numpy().view(np.uint32)
+    cs_h = cs.cpu().numpy()
+    if two:
+        assert np.any(before[2] != 0) and before[3].max() > 0          # the second vector was live when step 1 read it
+    scale_mismatch = 0
+    for l, (n, m) in enumerate(w.layout):
+        o = model.offsets[l]
+        N = n * m
+        nw, nb = -(-N // W), -(-N // block)
+        g = buf["grads"][o["grad_off"]:o["grad_off"] + N].view(torch.int16).cpu().numpy().view(np.uint16).reshape(n, m)
+        state = []
+        for i, arr in enumerate(before):
+            off, cnt = (o["word_off"], nw) if i % 2 == 0 else (o["scale_off"], nb)
+            state.append(arr[off:off + cnt].copy())
+        tag = f"{which} mat {l} ({n}x{m})"
+        words = c = want_delta = None
+        if which == "random_block":
+            want_delta = R.rb_step_matrix(g, state[0], state[1], keep[l], bits, block, 0.0, seed, l, 1)
+        elif which == "scaled_sign":
+            words, c = R.ss_step_matrix(g, state[0], state[1], bits, block, 0.0, seed, l, 1)
+        elif which == "iconef_random_block":
+            want_delta = R.i_rb_step_matrix(g, *state, keep[l], bits, block, seed, l, 1)
+        else:
+            words, c = R.i_ss_step_matrix(g, *state, bits, block, seed, l, 1)
+        if block_mode:
+            ro = B.conef_rb_offsets(model.ctx, l)
+            got = delta_h[ro["delta_off"]:ro["delta_off"] + keep[l]]
+            assert np.array_equal(got.view(np.uint32), want_delta.view(np.uint32)), f"{tag}: kept values"
+        else:
+            assert abs(float(cs_h[l]) - float(c)) <= float(np.spacing(np.float32(c))), f"{tag}: scale {cs_h[l]} vs {c}"
+            if np.float32(cs_h[l]) != np.float32(c):
+                scale_mismatch += 1         # a last-bit difference of c changes every argument: nothing more to compare
+                continue
+            so = B.conef_ss_offsets(model.ctx, l)["sign_off"]
+            assert N % 32 == 0
+            assert np.array_equal(signs_h[so:so + words.size], words), f"{tag}: sign bits"
+        for i, (arr, want) in enumerate(zip(after, state)):
+            off, cnt = (o["word_off"], nw) if i % 2 == 0 else (o["scale_off"], nb)
+            got = arr[off:off + cnt]
+            name = ("codes", "scales", "second codes", "second scales")[i]
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), \
+                f"{tag}: {name} differ in {(got.view(np.uint32) != want.view(np.uint32)).sum()} of {cnt}"
+        if l < 3:
+            print(f"[fullsize stream {which}] {tag}: equal", flush=True)
+    print(f"[fullsize stream {which}] all {len(w.layout)} matrices compared; scale differed in its last bit for "
+          f"{scale_mismatch}", flush=True)
+    assert scale_mismatch <= len(w.layout) // 10
+    model.close()
