@@ -21,6 +21,7 @@ _SRC = os.path.join(_HERE, "conef_ref.c")
 _SRC_SKETCH = os.path.join(_HERE, "sketch_ref.c")
 _SRC_RB = os.path.join(_HERE, "randblock_ref.c")
 _SRC_I = os.path.join(_HERE, "iconef_ref.c")
+_SRC_RK = os.path.join(_HERE, "randk_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -29,10 +30,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I))
+    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -112,6 +113,16 @@ def lib() -> ctypes.CDLL:
         L.ref_i_rb_step_matrix.restype = None
         L.ref_i_ss_step_matrix.argtypes = [vp, i32, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
         L.ref_i_ss_step_matrix.restype = f32
+        L.ref_rk_count.argtypes = [i64, i64]
+        L.ref_rk_count.restype = i64
+        L.ref_rk_indices.argtypes = [u64, u32, u64, i64, i64, vp]
+        L.ref_rk_indices.restype = None
+        L.ref_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, f32, u64, u32, u64, vp, vp, vp, vp]
+        L.ref_rk_step_matrix.restype = None
+        L.ref_cs_rk_step_matrix.argtypes = [vp, i32, i64, i64, i64, i64, f32, u64, u32, u64, vp, i32, vp, vp]
+        L.ref_cs_rk_step_matrix.restype = None
+        L.ref_i_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
+        L.ref_i_rk_step_matrix.restype = None
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -499,3 +510,50 @@ def i_ss_step_matrix(g, codes, scales, codes2, scales2, bits: int, block: int, s
     c = lib().ref_i_ss_step_matrix(_p(ga), dt, N, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
                                    _p(scales2), _p(words), _p(work))
     return words, np.float32(c)
+
+
+# ---------------------------------------------------------------- random-k gradient compressor, stratified (oracle/randk_ref.c)
+def rk_count(N: int, G: int) -> int:
+    return int(lib().ref_rk_count(N, G))
+
+
+def rk_indices(seed: int, mat: int, step: int, N: int, G: int) -> np.ndarray:
+    """Kept coordinate of every stratum (int64, ascending)."""
+    idx = np.empty(rk_count(N, G), np.int64)
+    lib().ref_rk_indices(seed, mat, step, N, G, _p(idx))
+    return idx
+
+
+def rk_step_matrix(g, codes, scales, G: int, bits: int, block: int, beta: float, seed: int, mat: int, step: int):
+    """One step with the random-k compressor and the quantiser; codes/scales updated in place; returns Delta (k values)."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales)
+    delta = np.empty(rk_count(N, G), np.float32)
+    work = np.empty(2 * N, np.float32)
+    lib().ref_rk_step_matrix(_p(ga), dt, N, G, bits, block, beta, seed, mat, step, _p(codes), _p(scales), _p(delta), _p(work))
+    return delta
+
+
+def cs_rk_step_matrix(g, table, G: int, beta: float, seed: int, mat: int, step: int):
+    """The same with the count sketch; `table` (w x m) updated in place; returns Delta."""
+    ga, dt = grad_array(g)
+    n, m = g.shape
+    _, tt = table_array(table)
+    assert table.flags.c_contiguous and table.shape[1] == m
+    delta = np.empty(rk_count(n * m, G), np.float32)
+    work = np.empty(n * m, np.float32)
+    lib().ref_cs_rk_step_matrix(_p(ga), dt, n, m, G, table.shape[0], beta, seed, mat, step, _p(table), tt, _p(delta), _p(work))
+    return delta
+
+
+def i_rk_step_matrix(g, codes, scales, codes2, scales2, G: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """One iConEF-v1 step with the random-k compressor; both vectors updated in place; returns Delta."""
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales, codes2, scales2)
+    delta = np.empty(rk_count(N, G), np.float32)
+    work = np.empty(2 * N, np.float32)
+    lib().ref_i_rk_step_matrix(_p(ga), dt, N, G, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
+                               _p(scales2), _p(delta), _p(work))
+    return delta
