@@ -193,6 +193,35 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
                      void *hip_stream);
 
+/* ---- Random-k gradient compressor (the compressor of the paper's iConEF experiment in the appendix, which names it
+ * and its rate only) in place of the rank-r one, unscaled like the random block, with either error compressor and
+ * with improved contractive error feedback.  Reading built here, "stratified": the flat row-major index range of
+ * matrix l is cut into strata of group[l] consecutive coordinates (the last one may be shorter) and one coordinate of
+ * every stratum is kept, drawn uniformly within its stratum and independently of the others, the same on every
+ * worker that uses the same seed.  Every coordinate is kept with probability 1 / group[l], exactly
+ * keep = ceil(rows cols / group[l]) values are sent (in stratum order, so they can be all-reduced as they are), and
+ * E||p - Delta||^2 = (1 - 1/group) ||p||^2 as for a uniformly drawn subset; two coordinates of one stratum are never
+ * kept together.
+ *   kept coordinate of stratum i = i group + floor(u_i len_i / 2^32), len_i = min(group, rows cols - i group),
+ *   u_i = word i mod 4 of the Philox4x32-10 call with counter (floor(i / 4), l + 2^30, lo32(step), hi32(step)) and
+ *   the context's key; conef_rk_index returns it (host).
+ *   p, Delta, e+ as for conef_rb_step with "the kept coordinates" in place of the block; conef_i_rk_step: the two
+ *   error vectors of conef_i_rb_step.
+ * conef_rk_configure  host only; group[n_mats] with 1 <= group[l] <= rows*cols, and rows*cols < 2^32 for every
+ *                     matrix (CONEF_EINVAL otherwise); may be called again
+ * delta_out           device, out: flat fp32, matrix l at delta_off of conef_rk_offsets (multiples of 64), keep values
+ * conef_rk_step and conef_i_rk_step are for quantiser contexts, conef_cs_rk_step for count-sketch contexts;
+ * CONEF_ESTATE on the other kind or before conef_rk_configure (and for conef_i_rk_step unless beta is 0).
+ * Pointers, alignment, asynchrony and errors as for conef_step; the error state is updated in place. */
+int conef_rk_configure(conef_ctx *ctx, const int64_t *group);
+int conef_rk_sizes(const conef_ctx *ctx, size_t *delta_elems);
+int conef_rk_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *keep);
+int conef_rk_index(const conef_ctx *ctx, int mat, uint64_t step, int64_t stratum, int64_t *index);
+int conef_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, float *delta_out,
+                  uint64_t step, void *hip_stream);
+int conef_cs_rk_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
+                     void *hip_stream);
+
 /* ---- Scaled-sign gradient compressor (Section 5.1) in place of the rank-r one, with either error compressor:
  *   p     = g + (1 - beta) e
  *   Delta = c * sign(p),  c = fl32(||p||_1 / (rows cols)) per matrix       (line 6)
@@ -219,7 +248,8 @@ int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *s
  * compressors and an element-wise gradient compressor.  A worker keeps two compressed vectors of the same layout,
  * e~ (err_codes, err_scales) and q (err2_codes, err2_scales), both zero at the start:
  *   p     = g + e~ + q                   (Algorithm 3 line 5; p_j = fma(d2, c2_j, fma(d1, c1_j, g_j)))
- *   Delta = Q(p)                         (line 6: the random block of conef_rb_step / the scaled sign of conef_ss_step)
+ *   Delta = Q(p)                         (line 6: the random block of conef_rb_step, the scaled sign of conef_ss_step
+ *                                        or the random-k of conef_rk_step)
  *   e~+   = C(p - Delta)                 (line 10; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign)
  *   q+    = C(p - Delta - e~+)           (line 14; the decoded e~+ is rounded to fp32, then subtracted)
  * The second quantisation draws its own random numbers: element j uses the 16-bit draw it has in conef_step, taken
@@ -235,6 +265,8 @@ int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
 int conef_i_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                     float *err2_scales, uint32_t *sign_out, float *scale_out, void *workspace, uint64_t step,
                     void *hip_stream);
+int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
 
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small

@@ -23,7 +23,8 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_strerror", "conef_set_beta",
            "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
-           "conef_i_rb_step", "conef_i_ss_step",
+           "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step",
+           "conef_rk_configure", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
@@ -70,6 +71,13 @@ def lib() -> ctypes.CDLL:
     L.conef_rb_start.argtypes = [vp, i32, u64, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rb_step.argtypes = [vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_rb_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i_rk_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_rk_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rk_sizes.argtypes = [vp, szp]
+    L.conef_rk_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rk_index.argtypes = [vp, i32, u64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rk_step.argtypes = [vp, vp, vp, vp, vp, u64, vp]
+    L.conef_cs_rk_step.argtypes = [vp, vp, vp, vp, u64, vp]
     L.conef_i_ss_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_cs_rb_step.argtypes = [vp, vp, vp, vp, u64, vp]
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
@@ -200,6 +208,44 @@ def conef_i_ss_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, 
                     stream=0):
     _check(lib().conef_i_ss_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
                                  _ptr(sign_out), _ptr(scale_out), _ptr(workspace), step, stream), "conef_i_ss_step")
+
+
+def conef_i_rk_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_i_rk_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
+                                 _ptr(delta_out), step, stream), "conef_i_rk_step")
+
+
+# random-k gradient compressor (stratified: one coordinate kept per stratum of group[l] consecutive ones)
+def conef_rk_configure(ctx, group: Sequence[int]) -> None:
+    arr = (ctypes.c_int64 * max(1, len(group)))(*[int(x) for x in group])
+    _check(lib().conef_rk_configure(ctx, arr), "conef_rk_configure")
+
+
+def conef_rk_sizes(ctx) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_rk_sizes(ctx, ctypes.byref(v)), "conef_rk_sizes")
+    return {"delta_elems": int(v.value)}
+
+
+def conef_rk_offsets(ctx, mat: int) -> dict:
+    off, keep = ctypes.c_size_t(), ctypes.c_int64()
+    _check(lib().conef_rk_offsets(ctx, mat, ctypes.byref(off), ctypes.byref(keep)), "conef_rk_offsets")
+    return {"delta_off": int(off.value), "keep": int(keep.value)}
+
+
+def conef_rk_index(ctx, mat: int, step: int, stratum: int) -> int:
+    v = ctypes.c_int64()
+    _check(lib().conef_rk_index(ctx, mat, step, stratum, ctypes.byref(v)), "conef_rk_index")
+    return int(v.value)
+
+
+def conef_rk_step(ctx, grads, err_codes, err_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_rk_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(delta_out), step, stream),
+           "conef_rk_step")
+
+
+def conef_cs_rk_step(ctx, grads, table, delta_out, step: int, stream=0):
+    _check(lib().conef_cs_rk_step(ctx, _ptr(grads), _ptr(table), _ptr(delta_out), step, stream), "conef_cs_rk_step")
 
 
 def conef_set_beta(ctx, beta: float) -> None:

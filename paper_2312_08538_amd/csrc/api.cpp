@@ -423,7 +423,7 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, false,
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -438,7 +438,7 @@ int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, false,
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -450,7 +450,85 @@ int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delt
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, static_cast<hipStream_t>(hip_stream)));
+    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, false, static_cast<hipStream_t>(hip_stream)));
+}
+
+// ---------------------------------------------------------------- random-k gradient compressor (stratified)
+int conef_rk_configure(conef_ctx *ctx, const int64_t *group)
+{
+    if (!ctx || !group) return CONEF_EINVAL;
+    int rc = configure_random_k(ctx->plan, group);
+    if (rc) return rc;
+    ctx->rb_uploaded = false;       // the descriptors are uploaded again before the next step
+    return CONEF_OK;
+}
+
+int conef_rk_sizes(const conef_ctx *ctx, size_t *delta_elems)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    if (delta_elems) *delta_elems = ctx->plan.rk_delta_elems;
+    return CONEF_OK;
+}
+
+int conef_rk_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *keep)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    const MatDesc &d = ctx->plan.mats[mat];
+    if (delta_off) *delta_off = (size_t)d.rk_delta_off;
+    if (keep) *keep = (d.N + d.rk_g - 1) / d.rk_g;
+    return CONEF_OK;
+}
+
+int conef_rk_index(const conef_ctx *ctx, int mat, uint64_t step, int64_t stratum, int64_t *index)
+{
+    if (!ctx || !index || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    const MatDesc &d = ctx->plan.mats[mat];
+    if (stratum < 0 || stratum >= (d.N + d.rk_g - 1) / d.rk_g) return CONEF_EINVAL;
+    *index = random_k_index(ctx->plan.seed, (uint32_t)mat, step, d.N, d.rk_g, stratum);
+    return CONEF_OK;
+}
+
+int conef_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, float *delta_out,
+                  uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !delta_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch || ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(delta_out, 4))
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, true,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, float *delta_out, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !delta_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch || ctx->plan.rk_delta_elems == 0 || ctx->plan.beta != 0.0f) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
+        misaligned(err2_scales, 4) || misaligned(delta_out, 4) || err_codes == err2_codes || err_scales == err2_scales)
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, true,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_cs_rk_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !table || !delta_out) return CONEF_EINVAL;
+    if (!ctx->plan.sketch || ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(delta_out, 4)) return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, true, static_cast<hipStream_t>(hip_stream)));
 }
 
 // ---------------------------------------------------------------- scaled-sign gradient compressor

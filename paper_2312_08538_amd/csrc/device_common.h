@@ -67,6 +67,58 @@ __device__ __forceinline__ int64_t random_block_start(uint32_t mat, uint32_t ste
     return (int64_t)__umul64hi(r, (uint64_t)(N - k + 1));
 }
 
+// Random-k gradient compressor, stratified: the flat index range of a matrix is cut into strata of g consecutive
+// coordinates (the last one may be shorter) and one coordinate of every stratum is kept:
+//   stratum i keeps  i g + floor(u_i len_i / 2^32),  len_i = min(g, N - i g),
+//   u_i = word i % 4 of the Philox call with counter (i / 4, matrix + 2^30, step), which no other draw uses.
+// N < 2^32.  strata_kept_octet looks at the 8 consecutive coordinates j0 .. j0 + 7 (all below N): bit e of the
+// result is set if j0 + e is kept; the kept ones belong to consecutive strata, the first of which is *first.
+__device__ __forceinline__ uint32_t stratum_of(uint32_t j, uint32_t g, uint64_t magic)
+{
+    return g == 1 ? j : (uint32_t)__umul64hi((uint64_t)j, magic);
+}
+
+__device__ __forceinline__ uint32_t strata_kept_octet(uint32_t j0, uint32_t N, uint32_t g, uint64_t magic, uint32_t mat,
+                                                      uint32_t step_lo, uint32_t step_hi, uint32_t seed_lo, uint32_t seed_hi,
+                                                      uint32_t *first)
+{
+    const uint32_t ia = stratum_of(j0, g, magic), ib = stratum_of(j0 + 7u, g, magic);
+    uint32_t bits = 0, first_i = 0, cached = 0xFFFFFFFFu;
+    uint32_t out[4] = {0u, 0u, 0u, 0u};
+    for (uint32_t i = ia; i <= ib; ++i) {
+        if ((i >> 2) != cached) {
+            cached = i >> 2;
+            philox4x32_10(cached, mat + 0x40000000u, step_lo, step_hi, seed_lo, seed_hi, out);
+        }
+        const uint32_t w = i & 3u;
+        const uint32_t u = w == 0 ? out[0] : (w == 1 ? out[1] : (w == 2 ? out[2] : out[3]));
+        const uint32_t base = i * g;
+        const uint32_t len = N - base < g ? N - base : g;
+        const uint32_t rel = base + __umulhi(u, len) - j0;       // wraps to a large value if the kept one lies before j0
+        if (rel < 8u) {
+            if (bits == 0) first_i = i;
+            bits |= 1u << rel;
+        }
+    }
+    *first = first_i;
+    return bits;
+}
+
+// The same question for one coordinate j: is it the kept one of its stratum (*stratum)?
+__device__ __forceinline__ bool strata_kept(uint32_t j, uint32_t N, uint32_t g, uint64_t magic, uint32_t mat, uint32_t step_lo,
+                                            uint32_t step_hi, uint32_t seed_lo, uint32_t seed_hi, uint32_t *stratum)
+{
+    const uint32_t i = stratum_of(j, g, magic);
+    uint32_t out[4];
+    philox4x32_10(i >> 2, mat + 0x40000000u, step_lo, step_hi, seed_lo, seed_hi, out);
+    const uint32_t w = i & 3u;
+    const uint32_t u = w == 0 ? out[0] : (w == 1 ? out[1] : (w == 2 ? out[2] : out[3]));
+    const uint32_t base = i * g;
+    const uint32_t len = N - base < g ? N - base : g;
+    *stratum = i;
+    return j == base + __umulhi(u, len);
+}
+
 // 16-bit draw of element j from the four output words of the call that covers j>>3.
 __device__ __forceinline__ uint32_t draw16(const uint32_t out[4], int j_low3)
 {

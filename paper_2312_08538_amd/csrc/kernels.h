@@ -54,11 +54,12 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
 // Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
-// codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null
+// codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null;
+// strata: the random-k gradient compressor (one coordinate per stratum) instead of the random block
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st);
+                          uint64_t step, uint32_t *codes2, float *scales2, bool strata, hipStream_t st);
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
-                             hipStream_t st);
+                             bool strata, hipStream_t st);
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
                        uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
                        float *scales2, hipStream_t st);

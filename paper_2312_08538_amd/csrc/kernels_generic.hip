@@ -189,12 +189,34 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
 // numbers of its own (matrix word of the Philox counter + 2^31).  The second block maximum needs the first
 // rounding of the whole block, so the block is swept three times: maximum, maximum of what the rounding leaves,
 // and both roundings again with the stores.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+// MODE 3, random-k (stratified, see strata_kept): as MODE 0 with the kept coordinates scattered.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
+
+// Is coordinate j kept by the gradient compressor at this step, and where in the Delta buffer does its value go?
+template <int MODE>
+__device__ __forceinline__ bool rb_kept(const DevicePlan &dp, const MatDesc &d, int mat, int64_t j, int64_t start,
+                                        uint32_t step_lo, uint32_t step_hi, int64_t *slot)
+{
+    if (MODE == kModeBlock) {
+        *slot = d.rb_delta_off + (j - start);
+        return j >= start && j < start + d.rb_k;
+    }
+    if (MODE == kModeStrata) {
+        uint32_t i;
+        const bool kept = strata_kept((uint32_t)j, (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)mat, step_lo, step_hi, dp.seed_lo,
+                                      dp.seed_hi, &i);
+        *slot = d.rk_delta_off + i;
+        return kept;
+    }
+    *slot = 0;
+    return false;
+}
 
 template <int MODE, bool TWO>
 __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
                                              const float *scales, int64_t j, int64_t start, float *delta, bool write,
-                                             float c, uint32_t *sign_words, const uint32_t *codes2, const float *scales2)
+                                             float c, uint32_t *sign_words, const uint32_t *codes2, const float *scales2,
+                                             int mat, uint32_t step_lo, uint32_t step_hi)
 {
     const int W = 32 / dp.bits;
     const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
@@ -204,9 +226,10 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
         const int q2 = code_field(codes2[d.word_off + j / W], (int)(j % W), dp.bits);
         const float dstep2 = scales2[d.scale_off + j / dp.block] * inv_levels(dp.bits);
         const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, (float)q, g));
-        if (MODE == kModeBlock) {
-            if (j >= start && j < start + d.rb_k) {
-                if (write) delta[d.rb_delta_off + (j - start)] = pv;
+        if (MODE == kModeBlock || MODE == kModeStrata) {
+            int64_t slot;
+            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+                if (write) delta[slot] = pv;
                 return 0.0f;
             }
             return pv;
@@ -216,9 +239,10 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
         if (write && neg) atomicOr(sign_words + d.sign_off + j / 32, 1u << (j % 32));
         return pv - (neg ? -c : c);
     }
-    if (MODE == kModeBlock) {
-        if (j >= start && j < start + d.rb_k) {
-            if (write) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
+    if (MODE == kModeBlock || MODE == kModeStrata) {
+        int64_t slot;
+        if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+            if (write) delta[slot] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
             return dp.beta * (dstep * (float)q);
         }
         return __builtin_fmaf(dstep, (float)q, g);
@@ -251,7 +275,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
         float a = 0.0f;
         for (int e = lane; e < cnt; e += 64) {
-            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2);
+            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
             if (MODE == kModeNorm) l1 += (double)fabsf(v);
             a = fmaxf(a, fabsf(v));
         }
@@ -264,7 +288,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             const float dnew = a * inv_levels(bits);
             // argument of the second rounding: x minus the decoded first rounding of x
             auto second_argument = [&](int64_t j, uint32_t &f1) {
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 f1 = quantise_field(x, inv16, draw16(out, (int)(j & 7)), mask);
@@ -310,7 +334,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             uint32_t field = 0;
             if (e < cnt && a > 0.0f) {
                 const int64_t j = j0 + e;
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
@@ -480,20 +504,27 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     return hipGetLastError();
 }
 
-// codes2 / scales2: the second error vector of Algorithm 3, or null (here and in launch_ss_step)
+// codes2 / scales2: the second error vector of Algorithm 3, or null (here and in launch_ss_step); strata: the
+// random-k compressor instead of the random block
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, uint32_t *codes2, float *scales2, hipStream_t st)
+                          uint64_t step, uint32_t *codes2, float *scales2, bool strata, hipStream_t st)
 {
-    octet_stream_step(dp, kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, codes2, scales2, st);
-    if (dp.n_rb_g > 0) {
+    octet_stream_step(dp, strata ? kModeStrata : kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, codes2,
+                      scales2, st);
+    auto generic = [&](auto mode) {
+        constexpr int M = decltype(mode)::value;
         if (codes2)
-            hipLaunchKernelGGL((k_rb_generic<kModeBlock, true>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+            hipLaunchKernelGGL((k_rb_generic<M, true>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
                                (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr,
                                (double *)nullptr, codes2, scales2);
         else
-            hipLaunchKernelGGL((k_rb_generic<kModeBlock, false>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
+            hipLaunchKernelGGL((k_rb_generic<M, false>), dim3(dp.n_rb_g), dim3(256), 0, st, dp, grads, codes, scales, delta,
                                (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (const float *)nullptr,
                                (double *)nullptr, codes2, scales2);
+    };
+    if (dp.n_rb_g > 0) {
+        if (strata) generic(std::integral_constant<int, kModeStrata>{});
+        else generic(std::integral_constant<int, kModeBlock>{});
     }
     return hipGetLastError();
 }

@@ -591,7 +591,9 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 // e~+ = C(p - Delta) as before and the second q+ = C(p - Delta - e~+): the decoded e~+ (rounded to fp32) is
 // subtracted, the block maximum taken again and the difference rounded with random numbers of its own (matrix
 // word of the Philox counter + 2^31), all in registers.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+// MODE 3, random-k (stratified: one coordinate kept per stratum of rk_g consecutive ones, see strata_kept_octet):
+// as MODE 0 with the kept coordinates scattered; the kept values go to the Delta buffer in stratum order.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
 
 template <bool BF16, int BITS, int MODE, bool TWO>
 __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
@@ -646,6 +648,10 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
         float x[8];
         float a = 0.0f;
         uint32_t neg_bits = 0;
+        uint32_t kbits = 0, kfirst = 0;
+        if (MODE == kModeStrata)
+            kbits = strata_kept_octet((uint32_t)(o * 8), (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)it.mat, step_lo, step_hi,
+                                      dp.seed_lo, dp.seed_hi, &kfirst);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             int q;
@@ -653,15 +659,24 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             else q = code_field(r.c0, e, BITS);
             const float qf = (float)q;
             const int64_t j = o * 8 + e;
+            // kept by the gradient compressor?  and where its value goes
+            bool kept = false;
+            int64_t slot = 0;
+            if (MODE == kModeBlock) {
+                kept = j >= start && j < stop;
+                slot = d.rb_delta_off + (j - start);
+            } else if (MODE == kModeStrata) {
+                kept = ((kbits >> e) & 1u) != 0;
+                slot = d.rk_delta_off + kfirst + __popc(kbits & ((1u << e) - 1u));
+            }
             if (TWO) {
                 int q2;
                 if (BITS == 8) q2 = code_field(e < 4 ? r2.c0 : r2.c1, e & 3, 8);
                 else q2 = code_field(r2.c0, e, BITS);
                 // p = g + e~ + q; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign
                 const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, qf, g[e]));
-                if (MODE == kModeBlock) {
-                    const bool kept = j >= start && j < stop;
-                    if (kept && valid) delta[d.rb_delta_off + (j - start)] = pv;
+                if (MODE == kModeBlock || MODE == kModeStrata) {
+                    if (kept && valid) delta[slot] = pv;
                     x[e] = kept ? 0.0f : pv;
                 } else if (MODE == kModeNorm) {
                     l1 += valid ? (double)fabsf(pv) : 0.0;
@@ -671,9 +686,9 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
                     neg_bits |= (neg ? 1u : 0u) << e;
                     x[e] = pv - (neg ? -c : c);
                 }
-            } else if (MODE == kModeBlock) {
-                if (j >= start && j < stop) {
-                    if (valid) delta[d.rb_delta_off + (j - start)] = __builtin_fmaf(dpart, qf, g[e]);
+            } else if (MODE == kModeBlock || MODE == kModeStrata) {
+                if (kept) {
+                    if (valid) delta[slot] = __builtin_fmaf(dpart, qf, g[e]);
                     x[e] = dp.beta * (dstep * qf);
                 } else {
                     x[e] = __builtin_fmaf(dstep, qf, g[e]);
@@ -733,7 +748,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
 
 }  // namespace
 
-// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign; codes2 / scales2: the second error
+// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign, 3 random-k; codes2 / scales2: the second error
 // vector of Algorithm 3, or null for plain contractive error feedback
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
                        uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
@@ -754,6 +769,7 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
 #define CONEF_STREAM_CASE(BF, B)                                                                                                   \
     case ((BF ? 1 : 0) << 8) | B:                                                                                                  \
         if (mode == kModeBlock) CONEF_STREAM_MODE(BF, B, kModeBlock);                                                              \
+        else if (mode == kModeStrata) CONEF_STREAM_MODE(BF, B, kModeStrata);                                                       \
         else if (mode == kModeNorm) CONEF_STREAM_MODE(BF, B, kModeNorm);                                                           \
         else CONEF_STREAM_MODE(BF, B, kModeSign);                                                                                  \
         break;

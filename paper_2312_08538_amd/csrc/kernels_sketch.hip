@@ -708,7 +708,8 @@ __global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, co
 // Scaled sign (Section 5.1), Delta = c sign(p) with c = ||p||_1 / N per matrix, takes two passes of the same walk:
 // MODE 1 adds up |p| in fp64 (one partial sum per wave; the scale kernel adds them in item order), MODE 2 reads
 // c, writes the sign bits (one byte per octet on this path) and sketches p - Delta on top of beta S.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2;
+// MODE 3, random-k (stratified, see strata_kept_octet): as MODE 0 with the kept coordinates scattered.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
 
 template <bool BF16, bool F16, int MODE>
 __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
@@ -757,6 +758,10 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
             const float somb = hv < 0 ? -dp.omb : dp.omb;
             const int64_t j0 = i * d.m + col;
             uint32_t neg_bits = 0;
+            uint32_t kbits = 0, kfirst = 0;
+            if (MODE == kModeStrata)
+                kbits = strata_kept_octet((uint32_t)j0, (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)it.mat, step_lo, step_hi,
+                                          dp.seed_lo, dp.seed_hi, &kfirst);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float pv = __builtin_fmaf(somb, s_old[j], g[j]);
@@ -764,6 +769,10 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
                 if (MODE == kModeBlock) {
                     const bool inside = j0 + j >= start && j0 + j < stop;
                     if (inside && active) delta[d.rb_delta_off + (j0 + j - start)] = pv;
+                    x = inside ? 0.0f : pv;
+                } else if (MODE == kModeStrata) {
+                    const bool inside = ((kbits >> j) & 1u) != 0;
+                    if (inside && active) delta[d.rk_delta_off + kfirst + __popc(kbits & ((1u << j) - 1u))] = pv;
                     x = inside ? 0.0f : pv;
                 } else if (MODE == kModeNorm) {
                     l1 += active ? (double)fabsf(pv) : 0.0;
@@ -834,6 +843,12 @@ __global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const 
             if (MODE == kModeBlock) {
                 const bool inside = j >= start && j < start + d.rb_k;
                 if (inside) delta[d.rb_delta_off + (j - start)] = pv;
+                x = inside ? 0.0f : pv;
+            } else if (MODE == kModeStrata) {
+                uint32_t si;
+                const bool inside = strata_kept((uint32_t)j, (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)it.mat, step_lo, step_hi,
+                                                dp.seed_lo, dp.seed_hi, &si);
+                if (inside) delta[d.rk_delta_off + si] = pv;
                 x = inside ? 0.0f : pv;
             } else if (MODE == kModeNorm) {
                 l1 += (double)fabsf(pv);
@@ -956,9 +971,12 @@ void cs_stream_pass(const DevicePlan &dp, const void *grads, void *table, float 
 }  // namespace
 
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
-                             hipStream_t st)
+                             bool strata, hipStream_t st)
 {
-    cs_stream_pass<kModeBlock>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
+    if (strata)
+        cs_stream_pass<kModeStrata>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
+    else
+        cs_stream_pass<kModeBlock>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
     return hipGetLastError();
 }
 

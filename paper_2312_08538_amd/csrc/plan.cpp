@@ -85,6 +85,39 @@ int configure_random_block(Plan &plan, const int64_t *keep)
     return kOk;
 }
 
+int64_t random_k_index(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t G, int64_t i)
+{
+    // counter (stratum / 4, matrix + 2^30, step): four strata per call, word i % 4
+    uint32_t out[4];
+    host_philox4x32_10((uint32_t)(i >> 2), mat + 0x40000000u, (uint32_t)step, (uint32_t)(step >> 32), seed, out);
+    const int64_t len = (N - i * G < G) ? N - i * G : G;
+    return i * G + (int64_t)(((uint64_t)out[i & 3] * (uint64_t)len) >> 32);
+}
+
+int configure_random_k(Plan &plan, const int64_t *group)
+{
+    if (!group) return kEinval;
+    const int n_mats = (int)plan.mats.size();
+    if (n_mats >= (1 << 30)) return kEinval;
+    for (int l = 0; l < n_mats; ++l)
+        if (group[l] < 1 || group[l] > plan.mats[l].N || plan.mats[l].N >= ((int64_t)1 << 32)) return kEinval;
+    int64_t off = 0;
+    for (int l = 0; l < n_mats; ++l) {
+        MatDesc &d = plan.mats[l];
+        d.rk_g = (uint32_t)group[l];
+        d.rk_pad = 0;
+        // j / g = mulhi64(j, magic) for every j < 2^32: magic = 2^64 / g for a power of two (a shift), else
+        // floor(2^64 / g) + 1, whose excess j (g - 2^64 mod g) / (g 2^64) < 2^-32 < 1 / g never reaches the next integer
+        if (d.rk_g == 1) d.rk_magic = 0;
+        else if ((d.rk_g & (d.rk_g - 1)) == 0) d.rk_magic = ((uint64_t)1 << 63) / (d.rk_g >> 1);
+        else d.rk_magic = ~(uint64_t)0 / d.rk_g + 1;
+        d.rk_delta_off = off;
+        off += round_up((d.N + group[l] - 1) / group[l], kAlign);
+    }
+    plan.rk_delta_elems = (size_t)off;
+    return kOk;
+}
+
 int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
                      int rank, float beta, int table_dtype, int dtype, uint64_t seed)
 {
@@ -406,6 +439,19 @@ struct Cover {
 bool check_plan(const Plan &plan)
 {
     const size_t nm = plan.mats.size();
+    // random-k: the multiply-high division by the stratum length, on the coordinates around every kind of boundary
+    if (plan.rk_delta_elems != 0)
+        for (const MatDesc &d : plan.mats) {
+            if (d.rk_g < 1 || d.rk_g > d.N || d.N >= ((int64_t)1 << 32)) return false;
+            if (d.rk_g == 1) continue;
+            const uint64_t g = d.rk_g, last = (uint64_t)d.N - 1;
+            const uint64_t probes[] = {0, 1, g - 1, g, g + 1, 2 * g - 1, 2 * g, last / 2, last / g * g - 1, last / g * g, last - 1, last,
+                                       0xFFFFFFFFull / g * g - 1, 0xFFFFFFFFull / g * g, 0xFFFFFFFEull, 0xFFFFFFFFull};
+            for (uint64_t j : probes) {
+                j &= 0xFFFFFFFFull;
+                if ((uint64_t)(((unsigned __int128)j * d.rk_magic) >> 64) != j / g) return false;
+            }
+        }
     // pass 1: P = p Q
     {
         Cover c(nm);

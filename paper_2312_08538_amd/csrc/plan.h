@@ -55,6 +55,11 @@ struct MatDesc {
     // random-block gradient compressor
     int64_t rb_k;                   // coordinates kept per step (0: not configured)
     int64_t rb_delta_off;           // offset of the matrix's kept values in the flat Delta buffer
+    // random-k gradient compressor (stratified: one coordinate kept per stratum of rk_g consecutive ones)
+    uint32_t rk_g;                  // stratum length (0: not configured)
+    uint32_t rk_pad;
+    uint64_t rk_magic;              // floor(2^64 / rk_g) + 1: j / rk_g = mulhi64(j, rk_magic) for j < 2^32 (unused for rk_g = 1)
+    int64_t rk_delta_off;           // offset of the matrix's kept values (one per stratum) in the flat Delta buffer
     // element-wise gradient compressors (random block, scaled sign): the matrix's items in its stream table
     int32_t st_first, st_slots;     // index of its first item; partial-sum slots (one per wave that works on it)
     int32_t st_atomic;              // its sign bits are set with atomic ORs (kernels for any shape): cleared first
@@ -109,6 +114,7 @@ struct Plan {
     // element-wise gradient compressors with the quantiser: stream tables (made with the plan)
     size_t sign_words = 0;
     size_t rb_delta_elems = 0;      // set by configure_random_block
+    size_t rk_delta_elems = 0;      // set by configure_random_k
     std::vector<WorkItem> rb_items;     // matrices of whole power-of-two blocks: (mat, first run of 512 elements, runs), one item per wave
     std::vector<WorkItem> rb_g_items;   // any other matrix: (mat, first block, blocks per wave), 4 waves per item
 };
@@ -132,6 +138,10 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
 // Random-block gradient compressor: keep[l] coordinates of matrix l per step (1 .. rows * cols).  Sets the
 // per-matrix fields, the Delta layout and (for a quantiser plan) the work tables.  Returns 0 or a negative code.
 int configure_random_block(Plan &plan, const int64_t *keep);
+// Random-k, stratified: group[l] = stratum length of matrix l, 1 <= group[l] <= rows*cols < 2^32.
+int configure_random_k(Plan &plan, const int64_t *group);
+// Kept coordinate of stratum i of a matrix of N coordinates with strata of G (host; the kernels compute the same).
+int64_t random_k_index(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t G, int64_t i);
 
 // First coordinate of the kept block of a matrix of N elements at `step` (Philox4x32-10 of (matrix, ~0, step)).
 int64_t random_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t k);

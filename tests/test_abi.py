@@ -248,3 +248,41 @@ def test_random_block_layout_and_start_match_the_oracle(ref):
             assert e.value.code == B.EINVAL
         assert L.conef_rb_configure(ctx, None) == B.EINVAL
         B.conef_destroy(ctx)
+
+
+def test_random_k_layout_and_kept_coordinates_match_the_oracle(ref):
+    layout = [(64, 147), (512, 1024), (3, 5)]
+    group = [10, 16, 4]
+    for ctx in (B.conef_init(layout, 2, 4, 128, B.BF16, 0xC0FFEE123),
+                B.conef_cs_init(layout, [8, 100, 3], 2, 0.5, B.TABLE_F16, B.BF16, 0xC0FFEE123)):
+        L = B.lib()
+        assert L.conef_rk_sizes(ctx, None) == B.ESTATE                      # not configured yet
+        B.conef_rk_configure(ctx, group)
+        off = 0
+        for l, (n, m) in enumerate(layout):
+            N, G = n * m, group[l]
+            keep = -(-N // G)
+            o = B.conef_rk_offsets(ctx, l)
+            assert (o["delta_off"], o["keep"]) == (off, keep) and keep == ref.rk_count(N, G)
+            off += (keep + 63) // 64 * 64
+            for step in (0, 7, 2 ** 33 + 1):
+                want = ref.rk_indices(0xC0FFEE123, l, step, N, G)
+                for i in (0, 1, keep // 2, keep - 1):
+                    assert B.conef_rk_index(ctx, l, step, i) == want[i]
+            with pytest.raises(B.ConefError) as e:
+                B.conef_rk_index(ctx, l, 0, keep)
+            assert e.value.code == B.EINVAL
+        assert B.conef_rk_sizes(ctx)["delta_elems"] == off
+        B.conef_check_plan(ctx)
+        for bad in ([0, 1, 1], [1, 1, 16], [-3, 1, 1]):
+            with pytest.raises(B.ConefError) as e:
+                B.conef_rk_configure(ctx, bad)
+            assert e.value.code == B.EINVAL
+        assert L.conef_rk_configure(ctx, None) == B.EINVAL
+        B.conef_destroy(ctx)
+    # a matrix of 2^32 coordinates or more is refused (the kernels index a matrix with 32 bits here)
+    ctx = B.conef_init([(65536, 65536)], 2, 4, 128, B.BF16, 1)
+    with pytest.raises(B.ConefError) as e:
+        B.conef_rk_configure(ctx, [10])
+    assert e.value.code == B.EINVAL
+    B.conef_destroy(ctx)
