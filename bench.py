@@ -299,6 +299,67 @@ def run_scaled_sign(w, reps: int = 10):
     return out
 
 
+def run_random_k(w, group: int = 10, reps: int = 10):
+    """Times one step with the random-k gradient compressor (stratified: one coordinate kept of every `group`
+    consecutive ones) in place of the rank-r one: with the workload's quantiser (beta = 0), with the count sketch (fp16
+    table, keep 0.2, beta 0.9) and with iConEF-v1 (the quantiser twice).  One streaming pass each; HIP events on the
+    launch stream."""
+    import torch
+
+    from paper_2312_08538_amd import binding as B
+    from paper_2312_08538_amd import workloads as wl
+
+    G = 4 if w.grad_dtype == 0 else 2
+    kept = sum(-(-(n * m) // group) for n, m in w.layout)
+    out = {}
+    for kind in ("quantiser", "count_sketch", "iconef_v1"):
+        if kind == "count_sketch":
+            ws = wl.sketch_rows(w.layout, 0.2)
+            model = B.SketchModel(w.layout, ws, w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(a * m * 2 for a, (_, m) in zip(ws, w.layout))
+        else:
+            model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+            state_bytes = sum(n * m * (w.bits / 8 + 4.0 / w.block) for n, m in w.layout) * (2 if kind == "iconef_v1" else 1)
+        B.conef_rk_configure(model.ctx, [group] * len(w.layout))
+        buf = model.alloc("cuda:0")
+        delta = torch.zeros(B.conef_rk_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
+        if kind == "iconef_v1":
+            codes2, scales2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+        wl.device_fill_gradients(w, 0, buf["grads"], [o["grad_off"] for o in model.offsets])
+        st = B.Model.stream_handle()
+
+        def one(t):
+            if kind == "quantiser":
+                B.conef_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
+            elif kind == "count_sketch":
+                B.conef_cs_rk_step(model.ctx, buf["grads"], buf["table"], delta, t, st)
+            else:
+                B.conef_i_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
+
+        for t in range(2):
+            one(t)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for t, (e0, e1) in enumerate(ev):
+            e0.record()
+            one(2 + t)
+            e1.record()
+            if kind == "count_sketch" and t % 8 == 7:
+                buf["table"].zero_()        # outside the timed spans; see run_scaled_sign
+        torch.cuda.synchronize()
+        ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / reps
+        nbytes = int(w.elements * G + 2 * state_bytes + 4 * kept)       # gradient, state read + written, kept values
+        out[kind] = {"ms": round(ms, 4), "bytes": nbytes, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "finite": bool(torch.isfinite(delta).all())}
+        model.close()
+        del buf, delta
+        if kind == "iconef_v1":
+            del codes2, scales2
+        torch.cuda.empty_cache()
+    return out
+
+
 def run_iconef(w, fraction: float = 0.1, reps: int = 10):
     """Times one step of improved contractive error feedback, version 1 (Algorithm 3: two compressed error vectors, the
     workload's quantiser twice) with the random-block (a tenth kept) and the scaled-sign gradient compressors.  HIP
@@ -439,6 +500,9 @@ def main():
     ap.add_argument("--scaled-sign", action="store_true",
                     help="time only the step with the scaled-sign gradient compressor (quantiser and count-sketch error "
                          "compressors) on --workload and print its line")
+    ap.add_argument("--random-k", action="store_true",
+                    help="time only the step with the random-k gradient compressor (stratified, one coordinate of every "
+                         "ten kept; quantiser, count sketch and iConEF-v1) on --workload and print its line")
     ap.add_argument("--iconef", action="store_true",
                     help="time only the iConEF-v1 step (two compressed error vectors, the quantiser twice) with the "
                          "random-block and scaled-sign gradient compressors on --workload and print its line")
@@ -464,6 +528,12 @@ def main():
         print(json.dumps({"metric": "scaled-sign ConEF step throughput: gradient GB/s processed",
                           "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
                           "steps": a.steps, "config": {"workload": w.name}, **r}), flush=True)
+        return
+    if a.random_k:
+        r = run_random_k(w, 10, a.steps)
+        print(json.dumps({"metric": "random-k ConEF step throughput: gradient GB/s processed",
+                          "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+                          "steps": a.steps, "config": {"workload": w.name, "group": 10}, **r}), flush=True)
         return
     if a.iconef:
         r = run_iconef(w, 0.1, a.steps)
@@ -532,6 +602,8 @@ def main():
                                                               for name in ("cnn", "lm", "translation", "large")}}
         out["scaled_sign"] = {"workloads": {name: run_scaled_sign(wl.WORKLOADS[name])
                                             for name in ("cnn", "lm", "translation", "large")}}
+        out["random_k"] = {"group": 10, "workloads": {name: run_random_k(wl.WORKLOADS[name])
+                                                      for name in ("cnn", "lm", "translation", "large")}}
         # improved contractive error feedback, version 1: a second compressed vector, the quantiser twice
         out["iconef_v1"] = {"fraction": 0.1, "workloads": {name: run_iconef(wl.WORKLOADS[name])
                                                            for name in ("cnn", "lm", "translation", "large")}}

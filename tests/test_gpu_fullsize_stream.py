@@ -2,7 +2,8 @@
 times: every matrix of the `large` workload (1.31 G elements, bf16 gradients, 4-bit codes, blocks of 128), whole.
 The library's second step (so that the state it decodes is not zero) is compared with one oracle step per matrix
 started from the state the library itself held before that step (downloaded), on the gradients the library read:
-kept values, sign words, codes and scales of one or two error vectors, bit for bit."""
+kept values (random block, random-k), sign words and scale (scaled sign), codes and scales of one or two error
+vectors, bit for bit."""
 import numpy as np
 import pytest
 
@@ -23,19 +24,23 @@ def env():
     return R, B, torch
 
 
-@pytest.mark.parametrize("which", ["random_block", "scaled_sign", "iconef_random_block", "iconef_scaled_sign"])
+@pytest.mark.parametrize("which", ["random_block", "scaled_sign", "random_k", "iconef_random_block", "iconef_scaled_sign",
+                                   "iconef_random_k"])
 def test_large_whole_model_stream_step_against_the_oracle(env, which):
     R, B, torch = env
     w = wl.WORKLOADS["large"]
     bits, block, W, seed = w.bits, w.block, 32 // w.bits, w.lib_seed
-    two, block_mode = which.startswith("iconef"), which.endswith("random_block")
+    two, block_mode, strata = which.startswith("iconef"), which.endswith("random_block"), which.endswith("random_k")
     keep = wl.random_block_keep(w.layout, 0.1)
+    group = [10] * len(w.layout)
     model = B.Model(w.layout, w.rank, bits, block, w.grad_dtype, seed)
     B.conef_rb_configure(model.ctx, keep)
+    B.conef_rk_configure(model.ctx, group)
     buf = model.alloc()
     codes2 = torch.zeros_like(buf["codes"]) if two else None
     scales2 = torch.zeros_like(buf["scales"]) if two else None
-    delta = torch.zeros(B.conef_rb_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
+    delta = torch.zeros(max(B.conef_rb_sizes(model.ctx)["delta_elems"], B.conef_rk_sizes(model.ctx)["delta_elems"]),
+                        dtype=torch.float32, device="cuda:0")
     signs = torch.zeros(B.conef_ss_sizes(model.ctx)["sign_words"], dtype=torch.int32, device="cuda:0")
     cs = torch.zeros(len(w.layout), dtype=torch.float32, device="cuda:0")
     goffs = [o["grad_off"] for o in model.offsets]
@@ -49,6 +54,10 @@ def test_large_whole_model_stream_step_against_the_oracle(env, which):
             B.conef_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], signs, cs, buf["ws"], t, st)
         elif which == "iconef_random_block":
             B.conef_i_rb_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
+        elif which == "random_k":
+            B.conef_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
+        elif which == "iconef_random_k":
+            B.conef_i_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
         else:
             B.conef_i_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, signs, cs, buf["ws"], t, st)
         torch.cuda.synchronize()
@@ -88,11 +97,16 @@ def test_large_whole_model_stream_step_against_the_oracle(env, which):
             words, c = R.ss_step_matrix(g, state[0], state[1], bits, block, 0.0, seed, l, 1)
         elif which == "iconef_random_block":
             want_delta = R.i_rb_step_matrix(g, *state, keep[l], bits, block, seed, l, 1)
+        elif which == "random_k":
+            want_delta = R.rk_step_matrix(g, state[0], state[1], group[l], bits, block, 0.0, seed, l, 1)
+        elif which == "iconef_random_k":
+            want_delta = R.i_rk_step_matrix(g, *state, group[l], bits, block, seed, l, 1)
         else:
             words, c = R.i_ss_step_matrix(g, *state, bits, block, seed, l, 1)
-        if block_mode:
-            ro = B.conef_rb_offsets(model.ctx, l)
-            got = delta_h[ro["delta_off"]:ro["delta_off"] + keep[l]]
+        if block_mode or strata:
+            ro = B.conef_rk_offsets(model.ctx, l) if strata else B.conef_rb_offsets(model.ctx, l)
+            assert ro["keep"] == want_delta.size
+            got = delta_h[ro["delta_off"]:ro["delta_off"] + want_delta.size]
             assert np.array_equal(got.view(np.uint32), want_delta.view(np.uint32)), f"{tag}: kept values"
         else:
             assert abs(float(cs_h[l]) - float(c)) <= float(np.spacing(np.float32(c))), f"{tag}: scale {cs_h[l]} vs {c}"
