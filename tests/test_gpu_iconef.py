@@ -176,3 +176,77 @@ def test_iconef_calls_reject_what_algorithm_3_does_not_define(env):
     assert np.isfinite(qb["scales"].cpu().numpy()).all() and np.isfinite(s2.cpu().numpy()).all()
     qm.close()
     sk.close()
+
+
+@pytest.mark.parametrize("which", ["scaled_sign", "iconef_scaled_sign", "iconef_random_block", "random_k", "iconef_random_k"])
+def test_stream_steps_replayed_from_a_hip_graph_equal_the_eager_steps(env, which):
+    """The steps with an element-wise gradient compressor enqueue kernels only (the sign words that are set with
+    atomic ORs are cleared by a kernel, not a memset), so they can be captured in a HIP graph.  Every replay, with
+    eager work and synchronisations between the replays, must give the bits of the eager step."""
+    R, B, S, torch = env
+    layout, bits, block = [(64, 147), (128, 512), (37, 53)], 4, 128        # both kernel families
+    model = B.Model(layout, 4, bits, block, wl.F32, 77)
+    B.conef_rb_configure(model.ctx, wl.random_block_keep(layout, 0.1))
+    B.conef_rk_configure(model.ctx, [10, 10, 7])
+    buf = model.alloc()
+    codes2, scales2 = _second_buffers(torch, buf)
+    delta = torch.zeros(max(B.conef_rb_sizes(model.ctx)["delta_elems"], B.conef_rk_sizes(model.ctx)["delta_elems"]),
+                        dtype=torch.float32, device="cuda:0")
+    signs = torch.zeros(B.conef_ss_sizes(model.ctx)["sign_words"], dtype=torch.int32, device="cuda:0")
+    cs = torch.zeros(len(layout), dtype=torch.float32, device="cuda:0")
+    rng = np.random.default_rng(3)
+
+    def launch(t, stream):
+        a = (model.ctx, buf["grads"], buf["codes"], buf["scales"])
+        if which == "scaled_sign":
+            B.conef_ss_step(*a, signs, cs, buf["ws"], t, stream)
+        elif which == "iconef_scaled_sign":
+            B.conef_i_ss_step(*a, codes2, scales2, signs, cs, buf["ws"], t, stream)
+        elif which == "iconef_random_block":
+            B.conef_i_rb_step(*a, codes2, scales2, delta, t, stream)
+        elif which == "random_k":
+            B.conef_rk_step(*a, delta, t, stream)
+        else:
+            B.conef_i_rk_step(*a, codes2, scales2, delta, t, stream)
+
+    state = {"codes": buf["codes"], "scales": buf["scales"], "codes2": codes2, "scales2": scales2}
+    outs = dict(state, delta=delta, signs=signs, cs=cs)
+    S._to_dev_grads(torch, model, buf, [S._grad(rng, n, m, wl.F32) for n, m in layout])
+    launch(0, model.stream_handle())                 # also uploads the work tables
+    torch.cuda.synchronize()
+    before = {k: v.clone() for k, v in state.items()}
+    S._to_dev_grads(torch, model, buf, [S._grad(rng, n, m, wl.F32) for n, m in layout])
+    delta.fill_(float("nan"))                        # what the step does not write stays NaN
+    launch(1, model.stream_handle())
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in outs.items()}
+    s = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    for k in before:
+        state[k].copy_(before[k])
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=s):
+        launch(1, s.cuda_stream)
+    for replay in range(3):
+        for k in before:
+            state[k].copy_(before[k])                # eager work between the replays
+        delta.fill_(float("nan"))
+        signs.fill_(-1)
+        cs.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            if k == "delta":
+                if "sign" in which:
+                    continue                         # not written by these steps
+                kept = ~torch.isnan(want[k])
+                assert torch.equal(outs[k][kept], want[k][kept]), (which, replay, k)
+            elif k == "signs" and "sign" in which:
+                # bits beyond a matrix's last entry and the padding between matrices are unspecified
+                for l, (n, m) in enumerate(layout):
+                    so, full = B.conef_ss_offsets(model.ctx, l)["sign_off"], (n * m) // 32
+                    assert torch.equal(outs[k][so:so + full], want[k][so:so + full]), (which, replay, k, l)
+            elif k != "signs":
+                assert torch.equal(outs[k], want[k]), (which, replay, k)
+    model.close()
