@@ -112,25 +112,39 @@ __device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, floa
     }
 }
 
+// Fixed-point stochastic rounding of an octet (quantise_field on each of its 8 values) straight into packed
+// BITS-wide two's-complement fields: 8-bit codes give two words (elements 0..3, 4..7), 4- and 2-bit codes the low
+// 32 / 16 bits of w[0].  Magnitudes and sign bits are gathered field by field and the negation is done on the
+// whole word: with s the sign bit of a field, ((mag ^ (s - (s >> (BITS-1)))) + (s >> (BITS-1))) ^ s is
+// 2^BITS - mag for a negative field with mag >= 1 and 0 for mag = 0; no carry leaves a field.
 template <int BITS>
-__device__ __forceinline__ void store_codes(const MatDesc &d, uint32_t *codes, int64_t o, const uint32_t f[8])
+__device__ __forceinline__ void quantise_octet(const float x[8], float inv16, const uint32_t rnd[4], uint32_t w[2])
 {
-    if (BITS == 8) {
-        uint2 c;
-        c.x = f[0] | (f[1] << 8) | (f[2] << 16) | (f[3] << 24);
-        c.y = f[4] | (f[5] << 8) | (f[6] << 16) | (f[7] << 24);
-        *reinterpret_cast<uint2 *>(codes + d.word_off + o * 2) = c;
-    } else if (BITS == 4) {
-        uint32_t c = 0;
+    constexpr int kPerWord = BITS == 8 ? 4 : 8;
+    constexpr uint32_t kSignBits = BITS == 8 ? 0x80808080u : (BITS == 4 ? 0x88888888u : 0x0000AAAAu);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) c |= f[e] << (4 * e);
-        codes[d.word_off + o] = c;
-    } else {
-        uint32_t c = 0;
+    for (int h = 0; h < 8 / kPerWord; ++h) {
+        uint32_t mags = 0, sg = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) c |= f[e] << (2 * e);
-        reinterpret_cast<uint16_t *>(codes + d.word_off)[o] = (uint16_t)c;
+        for (int k = kPerWord - 1; k >= 0; --k) {
+            const int e = h * kPerWord + k;
+            const uint32_t U = (uint32_t)(fabsf(x[e]) * inv16);
+            mags = (mags << BITS) | ((U + draw16(rnd, e)) >> 16);
+            sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(x[e]), 32 - BITS);     // (sg << BITS) | top BITS bits of x
+        }
+        sg &= kSignBits;
+        const uint32_t s1 = sg >> (BITS - 1), sm = sg - s1;
+        w[h] = ((mags ^ sm) + s1) ^ sg;
     }
+    if (BITS != 8) w[1] = 0;
+}
+
+template <int BITS>
+__device__ __forceinline__ void store_code_words(const MatDesc &d, uint32_t *codes, int64_t o, const uint32_t w[2])
+{
+    if (BITS == 8) *reinterpret_cast<uint2 *>(codes + d.word_off + o * 2) = make_uint2(w[0], w[1]);
+    else if (BITS == 4) codes[d.word_off + o] = w[0];
+    else reinterpret_cast<uint16_t *>(codes + d.word_off)[o] = (uint16_t)w[0];
 }
 
 // max over the 2^lb_shift lanes of a scale block (aligned group of lanes)
@@ -181,7 +195,6 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
     const int sub = lane >> d.lr_shift, lc = lane & (lr - 1);
     const int oc = it.a * lr + lc;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
-    const uint32_t mask = (1u << BITS) - 1u;
 
     float q[8][RP];
 #pragma unroll
@@ -206,11 +219,10 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
         const int64_t o = (int64_t)row * d.m8 + oc;
         uint32_t rnd[4];
         philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
-        uint32_t f[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16, draw16(rnd, e), mask);
+        uint32_t w[2];
+        quantise_octet<BITS>(x, inv16, rnd, w);
         if (valid) {
-            store_codes<BITS>(d, codes, o, f);
+            store_code_words<BITS>(d, codes, o, w);
             if ((lc & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
         }
     };
@@ -601,6 +613,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
                                                   uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws,
                                                   uint32_t *codes2, float *scales2)
 {
+    constexpr bool SPARSE = MODE == kModeBlock || MODE == kModeStrata;      // Delta keeps a few coordinates as they are
     const int lane = threadIdx.x & 63;
     const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     if (item >= dp.n_rb) return;
@@ -611,7 +624,6 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
     double l1 = 0.0;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
-    const uint32_t mask = (1u << BITS) - 1u;
     // The last run of a matrix may be short: octets at or beyond the end re-read the last octet and store
     // nothing.  They make up whole scale blocks (the matrix is a whole number of blocks), so they do not
     // enter the block maximum of a stored block.
@@ -645,78 +657,78 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
         const float dstep = r.scale * inv_levels(BITS);
         const float dpart = TWO ? dstep : dstep * dp.omb;
         const float dstep2 = r2.scale * inv_levels(BITS);
-        float x[8];
-        float a = 0.0f;
-        uint32_t neg_bits = 0;
-        uint32_t kbits = 0, kfirst = 0;
-        if (MODE == kModeStrata)
+        auto code_of = [&](int e) {
+            return (float)(BITS == 8 ? code_field(e < 4 ? r.c0 : r.c1, e & 3, 8) : code_field(r.c0, e, BITS));
+        };
+        // Which of the octet's coordinates does the gradient compressor keep as they are (bit e of kbits), and where
+        // does the first of them go in the Delta buffer (the others follow it)?  Most octets of a random block keep none.
+        uint32_t kbits = 0;
+        int64_t kslot = 0;
+        if (MODE == kModeBlock) {
+            const int64_t lo = start - o * 8, hi = stop - o * 8;       // the block in the octet's own coordinates
+            if (hi > 0 && lo < 8) {
+                const int l8 = lo > 0 ? (int)lo : 0, h8 = hi < 8 ? (int)hi : 8;
+                kbits = ((1u << h8) - 1u) & ~((1u << l8) - 1u);
+                kslot = d.rb_delta_off + (l8 - lo);
+            }
+        } else if (MODE == kModeStrata) {
+            uint32_t kfirst;
             kbits = strata_kept_octet((uint32_t)(o * 8), (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)it.mat, step_lo, step_hi,
                                       dp.seed_lo, dp.seed_hi, &kfirst);
+            kslot = d.rk_delta_off + kfirst;
+        }
+        // x: the argument of the error compressor.  First as if nothing were kept: g + e (= beta e + p), or p = g + e~ + q
+        float x[8];
+        uint32_t neg_bits = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            int q;
-            if (BITS == 8) q = code_field(e < 4 ? r.c0 : r.c1, e & 3, 8);
-            else q = code_field(r.c0, e, BITS);
-            const float qf = (float)q;
-            const int64_t j = o * 8 + e;
-            // kept by the gradient compressor?  and where its value goes
-            bool kept = false;
-            int64_t slot = 0;
-            if (MODE == kModeBlock) {
-                kept = j >= start && j < stop;
-                slot = d.rb_delta_off + (j - start);
-            } else if (MODE == kModeStrata) {
-                kept = ((kbits >> e) & 1u) != 0;
-                slot = d.rk_delta_off + kfirst + __popc(kbits & ((1u << e) - 1u));
-            }
+            const float qf = code_of(e);
+            float ge = __builtin_fmaf(dstep, qf, g[e]);
+            float pv = TWO ? ge : __builtin_fmaf(dpart, qf, g[e]);        // p = g + (1 - beta) e
             if (TWO) {
-                int q2;
-                if (BITS == 8) q2 = code_field(e < 4 ? r2.c0 : r2.c1, e & 3, 8);
-                else q2 = code_field(r2.c0, e, BITS);
-                // p = g + e~ + q; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign
-                const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, qf, g[e]));
-                if (MODE == kModeBlock || MODE == kModeStrata) {
-                    if (kept && valid) delta[slot] = pv;
-                    x[e] = kept ? 0.0f : pv;
-                } else if (MODE == kModeNorm) {
-                    l1 += valid ? (double)fabsf(pv) : 0.0;
-                    x[e] = 0.0f;
-                } else {
-                    const bool neg = (__float_as_uint(pv) >> 31) != 0;
-                    neg_bits |= (neg ? 1u : 0u) << e;
-                    x[e] = pv - (neg ? -c : c);
-                }
-            } else if (MODE == kModeBlock || MODE == kModeStrata) {
-                if (kept) {
-                    if (valid) delta[slot] = __builtin_fmaf(dpart, qf, g[e]);
-                    x[e] = dp.beta * (dstep * qf);
-                } else {
-                    x[e] = __builtin_fmaf(dstep, qf, g[e]);
-                }
-            } else {
-                const float pv = __builtin_fmaf(dpart, qf, g[e]);
-                if (MODE == kModeNorm) {
-                    l1 += valid ? (double)fabsf(pv) : 0.0;
-                    x[e] = 0.0f;
-                } else {
-                    const bool neg = (__float_as_uint(pv) >> 31) != 0;
-                    neg_bits |= (neg ? 1u : 0u) << e;
-                    x[e] = __builtin_fmaf(dstep, qf, g[e]) - (neg ? -c : c);
-                }
+                const int q2 = BITS == 8 ? code_field(e < 4 ? r2.c0 : r2.c1, e & 3, 8) : code_field(r2.c0, e, BITS);
+                pv = ge = __builtin_fmaf(dstep2, (float)q2, ge);
             }
-            a = fmaxf(a, fabsf(x[e]));
+            if (MODE == kModeNorm) {
+                l1 += valid ? (double)fabsf(pv) : 0.0;
+                x[e] = 0.0f;
+            } else if (MODE == kModeSign) {
+                const bool neg = (__float_as_uint(pv) >> 31) != 0;
+                neg_bits |= (neg ? 1u : 0u) << e;
+                x[e] = ge - (neg ? -c : c);
+            } else {
+                x[e] = ge;
+            }
         }
         if (MODE == kModeNorm) continue;
+        // ... then the kept coordinates: Delta = p there, and beta e (plain) or nothing (two vectors) is left
+        if (SPARSE && kbits != 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if ((kbits >> e) & 1u) {
+                    const int64_t slot = kslot + __popc(kbits & ((1u << e) - 1u));
+                    if (TWO) {
+                        if (valid) delta[slot] = x[e];
+                        x[e] = 0.0f;
+                    } else {
+                        const float qf = code_of(e);
+                        if (valid) delta[slot] = __builtin_fmaf(dpart, qf, g[e]);
+                        x[e] = dp.beta * (dstep * qf);
+                    }
+                }
+            }
+        }
         if (MODE == kModeSign && valid) reinterpret_cast<uint8_t *>(sign_words + d.sign_off)[o] = (uint8_t)neg_bits;
+        float a = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(x[e]));
         a = block_max(a, d.lb_shift);
         const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
-        uint32_t rnd[4];
+        uint32_t rnd[4], w[2];
         philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
-        uint32_t f[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16, draw16(rnd, e), mask);
+        quantise_octet<BITS>(x, inv16, rnd, w);
         if (valid) {
-            store_codes<BITS>(d, codes, o, f);
+            store_code_words<BITS>(d, codes, o, w);
             if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
         }
         if (TWO) {
@@ -725,17 +737,16 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             float a2 = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int qn = (int)(f[e] << (32 - BITS)) >> (32 - BITS);
+                const int qn = BITS == 8 ? code_field(w[e >> 2], e & 3, 8) : code_field(w[0], e, BITS);
                 x[e] = x[e] - dnew * (float)qn;
                 a2 = fmaxf(a2, fabsf(x[e]));
             }
             a2 = block_max(a2, d.lb_shift);
             const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
             philox4x32_10((uint32_t)o, (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = quantise_field(x[e], inv16_2, draw16(rnd, e), mask);
+            quantise_octet<BITS>(x, inv16_2, rnd, w);
             if (valid) {
-                store_codes<BITS>(d, codes2, o, f);
+                store_code_words<BITS>(d, codes2, o, w);
                 if ((lane & ((1 << d.lb_shift) - 1)) == 0) scales2[d.scale_off + (o >> d.lb_shift)] = a2;
             }
         }
