@@ -123,6 +123,10 @@ def lib() -> ctypes.CDLL:
         L.ref_cs_rk_step_matrix.restype = None
         L.ref_i_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
         L.ref_i_rk_step_matrix.restype = None
+        L.ref_i_error.argtypes = [vp, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp]
+        L.ref_i_error.restype = None
+        L.ref_i_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ref_i_step_matrix.restype = None
         L.ref_num_threads.argtypes = []
         L.ref_num_threads.restype = i32
         _lib = L
@@ -557,3 +561,25 @@ def i_rk_step_matrix(g, codes, scales, codes2, scales2, G: int, bits: int, block
     lib().ref_i_rk_step_matrix(_p(ga), dt, N, G, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
                                _p(scales2), _p(delta), _p(work))
     return delta
+
+
+def i_error(x, codes, scales, codes2, scales2, bits: int, block: int, seed: int, mat: int, step: int) -> None:
+    """The two error steps of Algorithm 3 on x = p - Delta (flat fp32, left unchanged): both vectors replaced."""
+    xa = np.ascontiguousarray(x, np.float32).ravel().copy()
+    _check_state(codes, scales, codes2, scales2)
+    tmp = np.empty(xa.size, np.float32)
+    lib().ref_i_error(_p(xa), xa.size, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2), _p(scales2), _p(tmp))
+
+
+def i_step_matrix(g, codes, scales, codes2, scales2, Q, rank: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """One iConEF-v1 step with the rank-r compressor; both vectors updated in place; returns (P^, Q+)."""
+    ga, dt = grad_array(g)
+    n, m = g.shape
+    _check_state(codes, scales, codes2, scales2)
+    Qs = np.ascontiguousarray(Q, np.float32)
+    assert Qs.shape == (m, rank)
+    P_out, Q_out = np.empty((n, rank), np.float32), np.empty((m, rank), np.float32)
+    work = np.empty(3 * n * m, np.float32)
+    lib().ref_i_step_matrix(_p(ga), dt, n, m, rank, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
+                            _p(scales2), _p(Qs), _p(P_out), _p(Q_out), _p(work))
+    return P_out, Q_out

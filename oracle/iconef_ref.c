@@ -1,8 +1,8 @@
 /*
  * iconef_ref.c -- reference ("oracle") implementation of improved contractive error feedback, version 1
  * (Algorithm 3 of arXiv 2312.08538, Section 3.2), with the block-wise stochastic quantiser of Section 4.2.1
- * as both error compressors and an element-wise gradient compressor (unscaled random block, Section 5.3, or
- * scaled sign, Section 5.1).
+ * as both error compressors, around an element-wise gradient compressor (unscaled random block, Section 5.3, or
+ * scaled sign, Section 5.1) and, at the end of this file, around the rank-r compressor of Section 5.2.
  *
  * TEST INFRASTRUCTURE ONLY, like the other files here (whose routines it calls): shares no code with the
  * HIP path and is never called from it.
@@ -29,7 +29,10 @@
  * plain step (already pinned); p uses both vectors (exact integer data); p - Delta = e~+ + q+ + r with
  * |r_j| at most one step of the second quantiser, which is at most 1/s of the first one's; data the first
  * quantiser holds exactly leaves q+ = 0; the second vector is the pinned quantiser applied to the rounding
- * error of the first, with its own random numbers; the mean of e~+ + q+ over seeds is p - Delta.
+ * error of the first, with its own random numbers; the mean of e~+ + q+ over seeds is p - Delta.  Rank-r: from
+ * zero state the plain step; P^ orthonormal and spanning p Q, Q+ = p^T P^ with the p that holds both vectors (and
+ * not with one left out); p - P^ Q+^T held by the pair to one second-level step; the error steps are the pinned
+ * ones applied to the residual.
  */
 #include <math.h>
 #include <stdint.h>
@@ -94,4 +97,29 @@ float ref_i_ss_step_matrix(const void *g, int dtype, int64_t N, int bits, int bl
     }
     ref_i_error(p, N, bits, block, seed, mat, step, codes, scales, codes2, scales2, tmp);
     return c;
+}
+
+/* ------------------------------------------------------------------ */
+/* iConEF version 1 around the rank-r gradient compressor of Section 5.2 (the compressor of Algorithm 2's
+ * experiments): Delta = P^ Q+^T from one power-iteration step on p = g + e~ + q, then the two error steps on
+ * p - Delta.  The factorisation is that of the plain step (conef_ref.c), applied to the p of Algorithm 3.
+ * `work` holds 3*n*m floats.                                                                               */
+/* ------------------------------------------------------------------ */
+void ref_lowrank_P(const float *p, int64_t n, int64_t m, const float *Q, int r, float *P);
+void ref_orthonormalise(float *P, int64_t n, int r);
+void ref_lowrank_Q(const float *p, int64_t n, int64_t m, const float *Phat, int r, float *Qn);
+void ref_residual(const float *p, int64_t n, int64_t m, const float *Phat, const float *Qn, int r, float *x);
+
+void ref_i_step_matrix(const void *g, int dtype, int64_t n, int64_t m, int r, int bits, int block, uint64_t seed,
+                       uint32_t mat, uint64_t step, uint32_t *codes, float *scales, uint32_t *codes2, float *scales2,
+                       const float *Q_state, float *P_out, float *Q_out, float *work)
+{
+    const int64_t N = n * m;
+    float *tmp = work, *p = work + N, *x = work + 2 * N;
+    ref_i_form_p(g, dtype, codes, scales, codes2, scales2, N, bits, block, tmp, p);             /* accumulate */
+    ref_lowrank_P(p, n, m, Q_state, r, P_out);                                                  /* compress ... */
+    ref_orthonormalise(P_out, n, r);
+    ref_lowrank_Q(p, n, m, P_out, r, Q_out);
+    ref_residual(p, n, m, P_out, Q_out, r, x);                                                  /* p - Delta */
+    ref_i_error(x, N, bits, block, seed, mat, step, codes, scales, codes2, scales2, tmp);       /* both error steps */
 }

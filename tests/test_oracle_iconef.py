@@ -186,3 +186,62 @@ def test_scaled_sign_uses_the_sum_of_both_vectors():
         assert np.all(np.abs(x - e) <= step2 * (1 + 1e-5) + 1e-6 * np.abs(x).max())
         if t > 0:
             assert np.any(c2 != 0)          # the second vector is live state that the next accumulation used
+
+
+# ---------------------------------------------------------------- around the rank-r compressor
+def test_rank_r_first_step_from_zero_state_is_the_plain_step():
+    rng = np.random.default_rng(20)
+    n, m, rank, bits, block, seed = 48, 96, 4, 4, 32, 55
+    g = rng.standard_normal((n, m)).astype(np.float32)
+    Q0 = rng.standard_normal((m, rank)).astype(np.float32)
+    c1, s1, c2, s2 = fresh(n * m, bits, block)
+    Ph, Qn = R.i_step_matrix(g, c1, s1, c2, s2, Q0, rank, bits, block, seed, 2, 9)
+    st = R.MatState.fresh(n, m, bits, block, Q0)
+    Ph0, Qn0 = R.step_matrix(g, st, rank, bits, block, seed, 2, 9)
+    assert np.array_equal(Ph, Ph0) and np.array_equal(Qn, Qn0)
+    assert np.array_equal(c1, st.codes) and np.array_equal(s1, st.scales)
+    assert np.any(c2 != 0)
+
+
+def test_rank_r_factors_come_from_the_sum_of_both_vectors_and_the_pair_holds_the_residual():
+    rng = np.random.default_rng(21)
+    n, m, rank, bits, block, seed = 40, 64, 2, 8, 64, 56
+    s = R.levels(bits)
+    c1, s1, c2, s2 = fresh(n * m, bits, block)
+    Q = rng.standard_normal((m, rank)).astype(np.float32)
+    for t in range(4):
+        g = rng.standard_normal((n, m)).astype(np.float32)
+        p = R.i_form_p(g, c1, s1, c2, s2, bits, block).astype(np.float64).reshape(n, m)
+        e_first = R.decode(c1, s1, n * m, bits, block).astype(np.float64).reshape(n, m)
+        Ph, Qn = R.i_step_matrix(g, c1, s1, c2, s2, Q, rank, bits, block, seed, 0, t)
+        Ph64, Qn64 = Ph.astype(np.float64), Qn.astype(np.float64)
+        # P^ is an orthonormal basis of the columns of p Q, and Q+ = p^T P^, with the p that holds BOTH vectors
+        assert np.abs(Ph64.T @ Ph64 - np.eye(rank)).max() < 1e-5
+        raw = p @ Q.astype(np.float64)
+        assert np.abs(raw - Ph64 @ (Ph64.T @ raw)).max() < 1e-4 * np.abs(raw).max()
+        assert np.abs(Qn64 - p.T @ Ph64).max() < 1e-5 * np.abs(Qn64).max()
+        if t > 1:       # with the second vector left out of p, Q+ would be visibly different
+            p_wrong = g.astype(np.float64) + e_first
+            assert np.abs(Qn64 - p_wrong.T @ Ph64).max() > 1e-4 * np.abs(Qn64).max()
+        x = (p - Ph64 @ Qn64.T).ravel()
+        e = R.decode(c1, s1, n * m, bits, block).astype(np.float64) + R.decode(c2, s2, n * m, bits, block).astype(np.float64)
+        step2 = (s2.astype(np.float64) / s)[np.arange(n * m) // block]
+        assert np.all(np.abs(x - e) <= step2 * (1 + 1e-4) + 1e-5 * np.abs(x).max())
+        Q = Qn
+
+
+def test_rank_r_error_steps_are_the_pinned_ones_on_the_residual():
+    rng = np.random.default_rng(22)
+    n, m, rank, bits, block, seed = 33, 50, 3, 4, 25 * 4, 57
+    g = rng.standard_normal((n, m)).astype(np.float32)
+    Q = rng.standard_normal((m, rank)).astype(np.float32)
+    c1, s1, c2, s2 = fresh(n * m, bits, block)
+    R.i_step_matrix(g, c1, s1, c2, s2, Q, rank, bits, block, seed, 1, 0)           # some state in both vectors
+    a = [v.copy() for v in (c1, s1, c2, s2)]
+    g = rng.standard_normal((n, m)).astype(np.float32)
+    p = R.i_form_p(g, *a, bits, block).reshape(n, m)
+    Ph, Qn = R.i_step_matrix(g, c1, s1, c2, s2, Q, rank, bits, block, seed, 1, 1)
+    x = R.residual(p, Ph, Qn)
+    R.i_error(x, *a, bits, block, seed, 1, 1)
+    for got, want in zip((c1, s1, c2, s2), a):
+        assert np.array_equal(got, want)
