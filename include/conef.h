@@ -268,6 +268,25 @@ int conef_i_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
 int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                     float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
 
+/* ---- The same (Algorithm 3, version 1, the quantiser twice) around the rank-r compressor of conef_step:
+ *   p = g + e~ + q,  Delta = P^ Q+^T (one power-iteration step on p),  e~+ = C(p - Delta),  q+ = C(p - Delta - e~+),
+ * with the arithmetic stated above.  The accumulation is split in two: conef_i_accumulate adds the first vector to
+ * the gradient IN PLACE (g_j <- fma(d1, c1_j, g_j)), and the passes of the step then decode the second vector on top
+ * of that sum.  Hence:
+ *   grads   device, IN/OUT: fp32 gradients; on return they hold g + e~ (the input of the factorisation)
+ * and the calls are for contexts with fp32 gradients, the quantiser and beta = 0 (CONEF_ESTATE otherwise; a bf16
+ * gradient buffer cannot take the sum, and the bf16 matrix-core kernel family has no two-vector form).
+ * conef_i_step = conef_i_accumulate(grads, e~) -> conef_step_p(grads, q) -> conef_orthonormalise ->
+ * conef_step_q(grads, q) -> conef_i_step_err; the two exchange points of conef_step fall between the same calls.
+ * conef_i_step_err: grads as left by conef_i_accumulate; err2_* in: q, out: q+; err_* out: e~+ (not read).
+ * Every other argument, alignment, asynchrony and errors as for conef_step and its stage calls. */
+int conef_i_accumulate(conef_ctx *ctx, float *grads, const uint32_t *err_codes, const float *err_scales, void *hip_stream);
+int conef_i_step_err(conef_ctx *ctx, const float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                     float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream);
+int conef_i_step(conef_ctx *ctx, float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                 float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
+                 void *hip_stream);
+
 /* Stage timing.  After conef_set_timing(ctx, 1) every stage records a pair of HIP events on the
  * caller's stream around its main kernel (p: the P = pQ pass; orthonormalise: its three small
  * kernels; q: the Q+ pass without its final reduction; err: the residual + quantise pass).  Up to

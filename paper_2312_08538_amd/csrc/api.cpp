@@ -355,6 +355,56 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     return step_err_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, step, hip_stream, true);
 }
 
+// ---------------------------------------------------------------- iConEF version 1 around the rank-r compressor
+namespace {
+// Algorithm 3 has no partial update, the accumulation adds into an fp32 gradient buffer, and the passes that follow
+// must belong to the kernel families that take fp32 gradients (all but the bf16 matrix-core family).
+int i_lowrank_state(const conef_ctx *ctx)
+{
+    if (ctx->plan.sketch || ctx->plan.beta != 0.0f || ctx->plan.dtype != 0) return CONEF_ESTATE;
+    return CONEF_OK;
+}
+}  // namespace
+
+int conef_i_accumulate(conef_ctx *ctx, float *grads, const uint32_t *err_codes, const float *err_scales, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales) return CONEF_EINVAL;
+    int rc = i_lowrank_state(ctx);
+    if (rc) return rc;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4)) return CONEF_EINVAL;
+    if ((rc = ensure_uploaded(ctx))) return rc;
+    return hip_rc(launch_i_accumulate(ctx->dev, grads, err_codes, err_scales, static_cast<hipStream_t>(hip_stream)));
+}
+
+int conef_i_step_err(conef_ctx *ctx, const float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                     float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream)
+{
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !P_hat || !Q_new) return CONEF_EINVAL;
+    int rc = i_lowrank_state(ctx);
+    if (rc) return rc;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
+        misaligned(err2_scales, 4) || misaligned(P_hat, 16) || misaligned(Q_new, 16) || err_codes == err2_codes ||
+        err_scales == err2_scales)
+        return CONEF_EINVAL;
+    if ((rc = ensure_uploaded(ctx))) return rc;
+    return hip_rc(launch_pass_err_two(ctx->dev, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, step,
+                                      static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
+}
+
+int conef_i_step(conef_ctx *ctx, float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                 float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
+                 void *hip_stream)
+{
+    if (!ctx || !err2_codes || !err2_scales) return CONEF_EINVAL;
+    int rc;
+    if (ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
+    if ((rc = conef_i_accumulate(ctx, grads, err_codes, err_scales, hip_stream))) return rc;                     // g + e~
+    if ((rc = conef_step_p(ctx, grads, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream))) return rc;   // ... + q
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = step_q_impl(ctx, grads, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true))) return rc;
+    return conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, step, hip_stream);
+}
+
 int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream)
 {
     if (!ctx || !err_codes || !err_scales) return CONEF_EINVAL;

@@ -54,6 +54,13 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
 // Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
+// Improved contractive error feedback around the rank-r compressor (fp32 gradients, no matrix of the bf16 matrix-core
+// family): g <- g + e~ in place, and the err pass that decodes the second vector and writes both.
+hipError_t launch_i_accumulate(const DevicePlan &dp, float *grads, const uint32_t *codes, const float *scales, hipStream_t st);
+hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
+                               float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span);
+void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
+                        float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st);
 // codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null;
 // strata: the random-k gradient compressor (one coordinate per stratum) instead of the random block
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,

@@ -136,10 +136,14 @@ __device__ __forceinline__ float residual_at(const DevicePlan &dp, const MatDesc
     return pv - acc;
 }
 
-template <int RP>
+// TWO (improved contractive error feedback, version 1): the vector decoded here (codes, scales) is the second one,
+// the first having been added to the gradient by k_i_accumulate; the rounded residual goes to codes_first /
+// scales_first, what that rounding leaves, rounded again, back to codes / scales.  Three sweeps as in k_rb_generic.
+template <int RP, bool TWO>
 __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const void *grads, uint32_t *codes,
                                                           float *scales, const float *Phat, const float *Qn,
-                                                          uint32_t step_lo, uint32_t step_hi)
+                                                          uint32_t step_lo, uint32_t step_hi, uint32_t *codes_first,
+                                                          float *scales_first)
 {
     const WorkItem it = dp.err_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
@@ -158,6 +162,52 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
         // the old scale of this block is read by nobody else; codes are overwritten word by word below
         const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
         const int sweeps = (cnt + 63) / 64;
+        if (TWO) {
+            const uint32_t mask = (1u << bits) - 1u;
+            const float dnew = a * inv_levels(bits);
+            // argument of the second rounding: the residual minus its decoded first rounding
+            auto second_argument = [&](int64_t j, uint32_t &f1) {
+                const float x = residual_at<RP>(dp, d, grads, codes, scales, Phat, Qn, j);
+                uint32_t out[4];
+                philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                f1 = quantise_field(x, inv16, draw16(out, (int)(j & 7)), mask);
+                const int qn = (int)(f1 << (32 - bits)) >> (32 - bits);
+                return x - dnew * (float)qn;
+            };
+            float a2 = 0.0f;
+            for (int e = lane; e < cnt; e += 64) {
+                uint32_t f1;
+                a2 = fmaxf(a2, fabsf(second_argument(j0 + e, f1)));
+            }
+            a2 = wave_max(a2);
+            const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
+            for (int sw = 0; sw < sweeps; ++sw) {
+                const int e = sw * 64 + lane;
+                uint32_t field = 0, field2 = 0;
+                if (e < cnt) {
+                    const int64_t j = j0 + e;
+                    uint32_t f1, out[4];
+                    const float y = second_argument(j, f1);
+                    philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
+                    field = f1 << (bits * (e % W));
+                    field2 = quantise_field(y, inv16_2, draw16(out, (int)(j & 7)), mask) << (bits * (e % W));
+                }
+                // every lane of the wave has read its old codes before any word of the sweep is stored
+                for (int o = 1; o < W; o <<= 1) {
+                    field |= __shfl_xor(field, o, 64);
+                    field2 |= __shfl_xor(field2, o, 64);
+                }
+                if ((lane % W) == 0 && e < cnt) {
+                    codes_first[d.word_off + (j0 + e) / W] = field;
+                    codes[d.word_off + (j0 + e) / W] = field2;
+                }
+            }
+            if (lane == 0) {
+                scales_first[d.scale_off + blk] = a;
+                scales[d.scale_off + blk] = a2;
+            }
+            continue;
+        }
         for (int sw = 0; sw < sweeps; ++sw) {
             const int e = sw * 64 + lane;
             uint32_t field = 0;
@@ -173,6 +223,33 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
             if ((lane % W) == 0 && e < cnt) codes[d.word_off + (j0 + e) / W] = field;
         }
         if (lane == 0) scales[d.scale_off + blk] = a;
+    }
+}
+
+// ---------------------------------------------------------------- accumulation of a compressed vector
+// g <- g + e~ in place on fp32 gradients, one fused multiply-add per entry (the first half of Algorithm 3's
+// accumulation when the rank-r compressor follows: its passes then decode the second vector on top of this sum).
+// A thread takes 4 consecutive entries: they share a code word and a scale block.
+__global__ __launch_bounds__(256) void k_i_accumulate(DevicePlan dp, float *grads, const uint32_t *codes, const float *scales)
+{
+    const WorkItem it = dp.elem_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t j = ((int64_t)it.a << 10) + 4 * (int)threadIdx.x;
+    if (j >= d.N) return;
+    const int bits = dp.bits, W = 32 / bits;
+    const uint32_t w = codes[d.word_off + j / W];
+    const float dstep = scales[d.scale_off + j / dp.block] * inv_levels(bits);
+    const int f0 = (int)(j % W);
+    float *gp = grads + d.grad_off + j;
+    if (j + 4 <= d.N) {
+        float4 v = *reinterpret_cast<float4 *>(gp);
+        v.x = __builtin_fmaf(dstep, (float)code_field(w, f0, bits), v.x);
+        v.y = __builtin_fmaf(dstep, (float)code_field(w, f0 + 1, bits), v.y);
+        v.z = __builtin_fmaf(dstep, (float)code_field(w, f0 + 2, bits), v.z);
+        v.w = __builtin_fmaf(dstep, (float)code_field(w, f0 + 3, bits), v.w);
+        *reinterpret_cast<float4 *>(gp) = v;
+    } else {
+        for (int e = 0; j + e < d.N; ++e) gp[e] = __builtin_fmaf(dstep, (float)code_field(w, f0 + e, bits), gp[e]);
     }
 }
 
@@ -452,9 +529,39 @@ void generic_q_reduce(const DevicePlan &dp, double *ws, float *Qout, hipStream_t
 void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                       const float *Qn, uint64_t step, hipStream_t st)
 {
-    if (dp.n_err > 0)
-        CONEF_DISPATCH_RP(k_pass_err_generic, dim3(dp.n_err), dim3(256), st, dp, grads, codes, scales, Phat, Qn,
-                          (uint32_t)step, (uint32_t)(step >> 32));
+    if (dp.n_err <= 0) return;
+    switch (dp.rpad) {
+    case 4: hipLaunchKernelGGL((k_pass_err_generic<4, false>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr); break;
+    case 8: hipLaunchKernelGGL((k_pass_err_generic<8, false>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr); break;
+    case 16: hipLaunchKernelGGL((k_pass_err_generic<16, false>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr); break;
+    default: hipLaunchKernelGGL((k_pass_err_generic<32, false>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr); break;
+    }
+}
+
+// The err pass of improved contractive error feedback around the rank-r compressor: codes2 / scales2 is decoded
+// (the first vector is already in the gradient) and receives the second vector, codes / scales the first.
+hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
+                               float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
+{
+    if (span.begin) (void)hipEventRecord(span.begin, st);
+    octet_pass_err_two(dp, grads, codes, scales, codes2, scales2, Phat, Qn, step, st);
+    if (dp.n_err > 0) {
+        const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+        switch (dp.rpad) {
+        case 4: hipLaunchKernelGGL((k_pass_err_generic<4, true>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes2, scales2, Phat, Qn, lo, hi, codes, scales); break;
+        case 8: hipLaunchKernelGGL((k_pass_err_generic<8, true>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes2, scales2, Phat, Qn, lo, hi, codes, scales); break;
+        case 16: hipLaunchKernelGGL((k_pass_err_generic<16, true>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes2, scales2, Phat, Qn, lo, hi, codes, scales); break;
+        default: hipLaunchKernelGGL((k_pass_err_generic<32, true>), dim3(dp.n_err), dim3(256), 0, st, dp, grads, codes2, scales2, Phat, Qn, lo, hi, codes, scales); break;
+        }
+    }
+    if (span.end) (void)hipEventRecord(span.end, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_i_accumulate(const DevicePlan &dp, float *grads, const uint32_t *codes, const float *scales, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_i_accumulate, dim3(dp.n_elem), dim3(256), 0, st, dp, grads, codes, scales);
+    return hipGetLastError();
 }
 
 // A stage's span brackets its main pass kernels (both families), not the small reductions after them.

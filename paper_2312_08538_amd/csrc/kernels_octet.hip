@@ -180,10 +180,15 @@ __device__ __forceinline__ void load_factor_row(const float *__restrict__ F, int
 }
 
 // ------------------------------------------------------------------ err pass
-template <bool BF16, int BITS, int RP>
+// TWO (improved contractive error feedback, version 1, around this compressor): the first error vector has been
+// added to the gradient by the accumulation pass, so the vector decoded here (codes, scales) is the second one;
+// the rounded residual goes to codes_first / scales_first and what that rounding leaves, rounded again with random
+// numbers of its own, back to codes / scales (see k_rb_octet).
+template <bool BF16, int BITS, int RP, bool TWO = false>
 __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes,
                                                    float *scales, const float *__restrict__ Phat,
-                                                   const float *__restrict__ Qn, uint32_t step_lo, uint32_t step_hi)
+                                                   const float *__restrict__ Qn, uint32_t step_lo, uint32_t step_hi,
+                                                   uint32_t *codes_first = nullptr, float *scales_first = nullptr)
 {
     const int lane = threadIdx.x & 63;
     const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -222,8 +227,26 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
         uint32_t w[2];
         quantise_octet<BITS>(x, inv16, rnd, w);
         if (valid) {
-            store_code_words<BITS>(d, codes, o, w);
-            if ((lc & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a;
+            store_code_words<BITS>(d, TWO ? codes_first : codes, o, w);
+            if ((lc & ((1 << d.lb_shift) - 1)) == 0) (TWO ? scales_first : scales)[d.scale_off + (o >> d.lb_shift)] = a;
+        }
+        if (TWO) {
+            const float dnew = a * inv_levels(BITS);
+            float a2 = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int qn = BITS == 8 ? code_field(w[e >> 2], e & 3, 8) : code_field(w[0], e, BITS);
+                x[e] = x[e] - dnew * (float)qn;
+                a2 = fmaxf(a2, fabsf(x[e]));
+            }
+            a2 = block_max(a2, d.lb_shift);
+            const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
+            philox4x32_10((uint32_t)o, (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+            quantise_octet<BITS>(x, inv16_2, rnd, w);
+            if (valid) {
+                store_code_words<BITS>(d, codes, o, w);
+                if ((lc & ((1 << d.lb_shift) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a2;
+            }
         }
     };
     // Rows at or beyond the end of the item re-read its last row (nothing is stored for them), so the
@@ -864,7 +887,28 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
 {
     if (dp.n_err_f <= 0) return;
     CONEF_OCTET_DISPATCH(k_err_octet, dim3((dp.n_err_f + 3) / 4), st, dp, grads, codes, scales, Phat, Qn,
-                         (uint32_t)step, (uint32_t)(step >> 32));
+                         (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr);
+}
+
+// The err pass of improved contractive error feedback (fp32 gradients only): codes2 / scales2 is decoded and
+// receives the second vector, codes / scales the first.
+void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
+                        float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st)
+{
+    if (dp.n_err_f <= 0) return;
+    const dim3 grid((dp.n_err_f + 3) / 4);
+#define CONEF_ERR_TWO_CASE(B, R)                                                                                        \
+    case (B << 4) | R:                                                                                                  \
+        hipLaunchKernelGGL((k_err_octet<false, B, R, true>), grid, dim3(256), 0, st, dp, grads, codes2, scales2, Phat,  \
+                           Qn, (uint32_t)step, (uint32_t)(step >> 32), codes, scales);                                  \
+        break;
+    switch ((dp.bits << 4) | dp.rank) {
+        CONEF_ERR_TWO_CASE(2, 2) CONEF_ERR_TWO_CASE(2, 4) CONEF_ERR_TWO_CASE(2, 8)
+        CONEF_ERR_TWO_CASE(4, 2) CONEF_ERR_TWO_CASE(4, 4) CONEF_ERR_TWO_CASE(4, 8)
+        CONEF_ERR_TWO_CASE(8, 2) CONEF_ERR_TWO_CASE(8, 4) CONEF_ERR_TWO_CASE(8, 8)
+    default: break;
+    }
+#undef CONEF_ERR_TWO_CASE
 }
 
 }  // namespace conef

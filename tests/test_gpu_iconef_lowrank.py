@@ -1,0 +1,156 @@
+"""GPU parity tests of improved contractive error feedback, version 1 (Algorithm 3, the quantiser twice) around the
+rank-r compressor: the library through the C ABI against oracle/iconef_ref.c, free-running over several steps on
+fp32 gradients, in both kernel families that take them (whole blocks with rank 2/4/8, and any shape).
+
+Per step and matrix: the gradient buffer after the call is g + e~ bit for bit; the factors agree with the oracle's
+step from the same state to 1e-5; and both new vectors are, bit for bit, the oracle's two error steps applied to the
+residual formed from the library's own factors (the fp32 fma chain is the same on both sides, so nothing is left to
+tolerance there).  The oracle then continues from the library's state."""
+import numpy as np
+import pytest
+
+from paper_2312_08538_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from oracle import conef_ref as R
+    from paper_2312_08538_amd import binding as B
+    import parity_util as U
+
+    B.lib()
+    return R, B, U, torch
+
+
+CASES = [
+    # (layout, rank, bits, block)
+    ([(128, 256), (64, 512), (300, 128)], 4, 4, 128),          # whole blocks, rank 4: the lane-per-octet kernels
+    ([(64, 147), (37, 53), (130, 129)], 4, 4, 128),            # odd shapes: the kernels for any layout
+    ([(96, 512), (200, 1024)], 8, 2, 256),
+    ([(100, 192), (33, 64)], 2, 8, 64),
+    ([(70, 200), (256, 384)], 12, 4, 200),                     # a rank outside 2/4/8 and an odd block length
+    ([(500, 768), (64, 147)], 8, 8, 128),                      # both families in one model
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_iconef_with_the_rank_r_compressor(env, case):
+    R, B, U, torch = env
+    layout, rank, bits, block = CASES[case]
+    seed, W = 3100 + case, 32 // bits
+    model = B.Model(layout, rank, bits, block, wl.F32, seed)
+    buf = model.alloc()
+    codes2, scales2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+    rng = np.random.default_rng([case, 31])
+    state = []
+    for l, (n, m) in enumerate(layout):
+        N = n * m
+        Q0 = rng.standard_normal((m, rank)).astype(np.float32)
+        state.append([np.zeros(R.n_words(N, bits), np.uint32), np.zeros(R.n_blocks(N, block), np.float32),
+                      np.zeros(R.n_words(N, bits), np.uint32), np.zeros(R.n_blocks(N, block), np.float32), Q0])
+        o = model.offsets[l]
+        buf["Q"][o["q_off"]:o["q_off"] + Q0.size] = torch.from_numpy(Q0.ravel()).to("cuda:0")
+    second_live = False
+    for t in range(4):
+        grads = [(rng.standard_normal((n, m)) * 10.0 ** rng.integers(-2, 1)).astype(np.float32) for n, m in layout]
+        for l, g in enumerate(grads):
+            o = model.offsets[l]["grad_off"]
+            buf["grads"][o:o + g.size] = torch.from_numpy(g.ravel()).to("cuda:0")
+        print(f"[iconef rank-r case {case}] step {t}: launching", flush=True)
+        B.conef_i_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, buf["Q"], buf["P"], buf["Q"],
+                       buf["ws"], t, model.stream_handle())
+        torch.cuda.synchronize()
+        for l, (n, m) in enumerate(layout):
+            N, o = n * m, model.offsets[l]
+            c1, s1, c2, s2, Q = state[l]
+            tag = f"case {case} mat {l} step {t}"
+            # the gradient buffer now holds g + e~
+            got_g = buf["grads"][o["grad_off"]:o["grad_off"] + N].cpu().numpy()
+            want_g = R.form_p(grads[l], c1, s1, bits, block).ravel()
+            assert np.array_equal(got_g.view(np.uint32), want_g.view(np.uint32)), f"{tag}: accumulated gradient"
+            P_gpu = buf["P"][o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+            Q_gpu = buf["Q"][o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+            # the oracle's two error steps on the residual from the library's own factors: bit for bit
+            p = R.i_form_p(grads[l], c1, s1, c2, s2, bits, block).reshape(n, m)
+            own = [c1.copy(), s1.copy(), c2.copy(), s2.copy()]
+            R.i_error(R.residual(p, P_gpu, Q_gpu), *own, bits, block, seed, l, t)
+            # the oracle's whole step from the same state: factors to 1e-5
+            Ph, Qn = R.i_step_matrix(grads[l], c1, s1, c2, s2, Q, rank, bits, block, seed, l, t)
+            assert U.rel_err(P_gpu, Ph) <= 1e-5, f"{tag}: P^ {U.rel_err(P_gpu, Ph)}"
+            assert U.rel_err(Q_gpu, Qn) <= 1e-5, f"{tag}: Q+ {U.rel_err(Q_gpu, Qn)}"
+            got = [buf["codes"][o["word_off"]:o["word_off"] + c1.size].cpu().numpy().view(np.uint32),
+                   buf["scales"][o["scale_off"]:o["scale_off"] + s1.size].cpu().numpy(),
+                   codes2[o["word_off"]:o["word_off"] + c2.size].cpu().numpy().view(np.uint32),
+                   scales2[o["scale_off"]:o["scale_off"] + s2.size].cpu().numpy()]
+            for name, g_, w_ in zip(("first codes", "first scales", "second codes", "second scales"), got, own):
+                assert np.array_equal(g_.view(np.uint32), w_.view(np.uint32)), \
+                    f"{tag}: {name} differ in {(g_.view(np.uint32) != w_.view(np.uint32)).sum()} of {w_.size}"
+            second_live = second_live or bool(np.any(got[2] != 0))
+            # the oracle goes on from the library's state
+            state[l] = [got[0].copy(), got[1].copy(), got[2].copy(), got[3].copy(), Q_gpu.copy()]
+    assert second_live
+    model.close()
+
+
+def test_staged_calls_give_the_fused_step(env):
+    R, B, U, torch = env
+    layout, rank, bits, block = [(128, 256), (64, 147)], 4, 4, 128
+    rng = np.random.default_rng(5)
+    outs = []
+    for staged in (False, True):
+        model = B.Model(layout, rank, bits, block, wl.F32, 9)
+        buf = model.alloc()
+        c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+        r2 = np.random.default_rng(6)
+        buf["Q"].copy_(torch.from_numpy(r2.standard_normal(buf["Q"].numel()).astype(np.float32)).to("cuda:0"))
+        for t in range(3):
+            buf["grads"].copy_(torch.from_numpy(r2.standard_normal(buf["grads"].numel()).astype(np.float32)).to("cuda:0"))
+            a = (model.ctx, buf["grads"], buf["codes"], buf["scales"])
+            if staged:
+                B.conef_i_accumulate(*a)
+                B.conef_step_p(model.ctx, buf["grads"], c2, s2, buf["Q"], buf["P"], buf["ws"])
+                B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"])
+                B.conef_step_q(model.ctx, buf["grads"], c2, s2, buf["P"], buf["Q"], buf["ws"])
+                B.conef_i_step_err(*a, c2, s2, buf["P"], buf["Q"], t)
+            else:
+                B.conef_i_step(*a, c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], t)
+        torch.cuda.synchronize()
+        outs.append([x.clone() for x in (buf["codes"], buf["scales"], c2, s2, buf["Q"], buf["P"])])
+        model.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_rank_r_iconef_calls_reject_what_they_cannot_serve(env):
+    R, B, U, torch = env
+    for make, code in ((lambda: B.Model([(64, 64)], 4, 4, 64, wl.BF16, 1), B.ESTATE),):
+        m = make()
+        buf = m.alloc()
+        c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+        with pytest.raises(B.ConefError) as e:      # bf16 gradients cannot take the sum
+            B.conef_i_step(m.ctx, buf["grads"], buf["codes"], buf["scales"], c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], 0)
+        assert e.value.code == code
+        m.close()
+    m = B.Model([(64, 64)], 4, 4, 64, wl.F32, 1)
+    buf = m.alloc()
+    c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+    B.conef_set_beta(m.ctx, 0.5)
+    with pytest.raises(B.ConefError) as e:          # Algorithm 3 has no partial update
+        B.conef_i_step(m.ctx, buf["grads"], buf["codes"], buf["scales"], c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], 0)
+    assert e.value.code == B.ESTATE
+    B.conef_set_beta(m.ctx, 0.0)
+    with pytest.raises(B.ConefError) as e:          # the two vectors in one buffer
+        B.conef_i_step(m.ctx, buf["grads"], buf["codes"], buf["scales"], buf["codes"], s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], 0)
+    assert e.value.code == B.EINVAL
+    m.close()
+    sk = B.SketchModel([(64, 64)], [16], 4, 0.0, 0, wl.F32, 1)
+    sb = sk.alloc()
+    with pytest.raises(B.ConefError) as e:
+        B.conef_i_accumulate(sk.ctx, sb["grads"], sb["table"], sb["table"])
+    assert e.value.code == B.ESTATE
+    sk.close()
