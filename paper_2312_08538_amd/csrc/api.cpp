@@ -395,8 +395,15 @@ int conef_i_step(conef_ctx *ctx, float *grads, uint32_t *err_codes, float *err_s
                  float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
                  void *hip_stream)
 {
-    if (!ctx || !err2_codes || !err2_scales) return CONEF_EINVAL;
-    int rc;
+    // everything is checked before the first pass is enqueued: the accumulation changes the gradient buffer
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !Q_state || !P_out || !Q_out || !workspace)
+        return CONEF_EINVAL;
+    int rc = i_lowrank_state(ctx);
+    if (rc) return rc;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
+        misaligned(err2_scales, 4) || misaligned(Q_state, 16) || misaligned(P_out, 16) || misaligned(Q_out, 16) ||
+        misaligned(workspace, 256) || err_codes == err2_codes || err_scales == err2_scales)
+        return CONEF_EINVAL;
     if (ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_i_accumulate(ctx, grads, err_codes, err_scales, hip_stream))) return rc;                     // g + e~
     if ((rc = conef_step_p(ctx, grads, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream))) return rc;   // ... + q

@@ -286,3 +286,52 @@ def test_random_k_layout_and_kept_coordinates_match_the_oracle(ref):
         B.conef_rk_configure(ctx, [10])
     assert e.value.code == B.EINVAL
     B.conef_destroy(ctx)
+
+
+def test_element_wise_and_iconef_calls_validate_their_arguments_before_any_launch():
+    """Every check below returns before the library touches the GPU, so it runs here."""
+    L = B.lib()
+    q = B.conef_init([(64, 64)], 4, 4, 128, B.F32, 0)
+    qb = B.conef_init([(64, 64)], 4, 4, 128, B.BF16, 0)
+    sk = B.conef_cs_init([(64, 64)], [16], 4, 0.0, B.TABLE_F32, B.F32, 0)
+    A = 256                                                    # any aligned non-null address
+    # not configured yet
+    assert L.conef_rb_step(q, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_rk_step(q, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_i_rb_step(q, A, A, A, 512, 512, A, 0, 0) == B.ESTATE
+    assert L.conef_i_rk_step(q, A, A, A, 512, 512, A, 0, 0) == B.ESTATE
+    assert L.conef_cs_rk_step(sk, A, A, A, 0, 0) == B.ESTATE
+    for ctx in (q, qb, sk):
+        B.conef_rb_configure(ctx, [100])
+        B.conef_rk_configure(ctx, [10])
+    # the wrong kind of context
+    assert L.conef_rb_step(sk, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_rk_step(sk, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_ss_step(sk, A, A, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_i_ss_step(sk, A, A, A, 512, 512, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_cs_rb_step(q, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_cs_rk_step(q, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_cs_ss_step(q, A, A, A, A, A, 0) == B.ESTATE
+    assert L.conef_i_step(sk, A, A, A, 512, 512, A, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_i_step(qb, A, A, A, 512, 512, A, A, A, A, 0, 0) == B.ESTATE          # bf16 gradients
+    assert L.conef_i_accumulate(qb, A, A, A, 0) == B.ESTATE
+    # null and misaligned pointers, the two vectors in one buffer
+    assert L.conef_rk_step(q, 0, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_rk_step(q, 260, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_rk_step(q, A, A, A, 258, 0, 0) == B.EINVAL
+    assert L.conef_i_rb_step(q, A, A, A, 0, 512, A, 0, 0) == B.EINVAL
+    assert L.conef_i_rb_step(q, A, A, A, A, 512, A, 0, 0) == B.EINVAL                   # codes twice
+    assert L.conef_i_rk_step(q, A, A, A, 512, A, A, 0, 0) == B.EINVAL                   # scales twice
+    assert L.conef_i_ss_step(q, A, A, A, 512, 512, A, A, 128, 0, 0) == B.EINVAL         # workspace not 256-byte aligned
+    assert L.conef_i_step(q, A, A, A, A, 512, A, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_i_step(q, A, A, A, 512, 512, A, A, A, 128, 0, 0) == B.EINVAL
+    assert L.conef_i_step_err(q, A, A, A, 512, 512, 0, A, 0, 0) == B.EINVAL
+    assert L.conef_i_accumulate(q, 260, A, A, 0) == B.EINVAL
+    # Algorithm 3 has no partial update
+    B.conef_set_beta(q, 0.25)
+    assert L.conef_i_rb_step(q, A, A, A, 512, 512, A, 0, 0) == B.ESTATE
+    assert L.conef_i_ss_step(q, A, A, A, 512, 512, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_i_rk_step(q, A, A, A, 512, 512, A, 0, 0) == B.ESTATE
+    assert L.conef_i_step(q, A, A, A, 512, 512, A, A, A, A, 0, 0) == B.ESTATE
+    for ctx in (q, qb, sk):
+        B.conef_destroy(ctx)
