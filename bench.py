@@ -415,20 +415,19 @@ def run_iconef(w, fraction: float = 0.1, reps: int = 10):
 
 
 def run_iconef_lowrank(w, reps: int = 10):
-    """Times one iConEF-v1 step around the rank-r compressor (fp32 gradients; the accumulation pass, the three passes of
-    the plain step and the second rounding in the err pass).  The step adds the first error vector into the gradient
-    buffer, so the gradients are generated again before every step, outside the timed spans."""
+    """Times one iConEF-v1 step around the rank-r compressor (the three passes of the plain step, each decoding both
+    error vectors, and the second rounding in the err pass); for the workloads outside the bf16 matrix-core family."""
     import torch
 
     from paper_2312_08538_amd import binding as B
     from paper_2312_08538_amd import workloads as wl
 
-    assert w.grad_dtype == 0
+    G = 4 if w.grad_dtype == 0 else 2
     model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
     buf = model.alloc("cuda:0")
     codes2, scales2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
-    goffs = [o["grad_off"] for o in model.offsets]
     wl.device_q0(w, buf["Q"], [o["q_off"] for o in model.offsets])
+    wl.device_fill_gradients(w, 0, buf["grads"], [o["grad_off"] for o in model.offsets])
     st = B.Model.stream_handle()
 
     def one(t):
@@ -436,21 +435,17 @@ def run_iconef_lowrank(w, reps: int = 10):
                        buf["ws"], t, st)
 
     for t in range(2):
-        wl.device_fill_gradients(w, t, buf["grads"], goffs)
         one(t)
     torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for t, (e0, e1) in enumerate(ev):
-        wl.device_fill_gradients(w, 2 + t, buf["grads"], goffs)
         e0.record()
         one(2 + t)
         e1.record()
     torch.cuda.synchronize()
     ms = sum(e0.elapsed_time(e1) for e0, e1 in ev) / reps
     state = sum(n * m * (w.bits / 8 + 4.0 / w.block) for n, m in w.layout)          # one of the two vectors
-    # accumulation: gradient read and written, first vector read; P and Q+ passes: gradient and second vector read;
-    # err pass: the same read, both vectors written
-    nbytes = int(w.elements * 4 * 5 + state * 6)
+    nbytes = int(w.elements * G * 3 + state * 8)        # three passes read the gradient and both vectors; the last writes both
     out = {"ms_per_step": round(ms, 4), "bytes": nbytes, "model_hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
            "finite": bool(torch.isfinite(buf["Q"]).all() and torch.isfinite(scales2).all())}
     model.close()
@@ -552,8 +547,8 @@ def main():
                     help="time only the iConEF-v1 step (two compressed error vectors, the quantiser twice) with the "
                          "random-block and scaled-sign gradient compressors on --workload and print its line")
     ap.add_argument("--iconef-rank-r", action="store_true",
-                    help="time only the iConEF-v1 step around the rank-r compressor on --workload (one with fp32 "
-                         "gradients: cnn, lm) and print its line")
+                    help="time only the iConEF-v1 step around the rank-r compressor on --workload (cnn, lm or "
+                         "translation: the bf16 matrix-core kernel family has no two-vector form) and print its line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
                          "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
@@ -578,8 +573,8 @@ def main():
                           "steps": a.steps, "config": {"workload": w.name}, **r}), flush=True)
         return
     if a.iconef_rank_r:
-        if w.grad_dtype != 0:
-            print("bench.py: --iconef-rank-r needs a workload with fp32 gradients (cnn, lm)", file=sys.stderr)
+        if w.name == "large":
+            print("bench.py: --iconef-rank-r needs cnn, lm or translation (no two-vector form at rank 32 / bf16)", file=sys.stderr)
             sys.exit(2)
         r = run_iconef_lowrank(w, a.steps)
         print(json.dumps({"metric": "iConEF-v1 rank-r step throughput: gradient GB/s processed",
@@ -664,8 +659,9 @@ def main():
         # improved contractive error feedback, version 1: a second compressed vector, the quantiser twice
         out["iconef_v1"] = {"fraction": 0.1, "workloads": {name: run_iconef(wl.WORKLOADS[name])
                                                            for name in ("cnn", "lm", "translation", "large")}}
-        # ... and around the rank-r compressor (the workloads with fp32 gradients)
-        out["iconef_v1_rank_r"] = {"workloads": {name: run_iconef_lowrank(wl.WORKLOADS[name]) for name in ("cnn", "lm")}}
+        # ... and around the rank-r compressor (the workloads outside the bf16 matrix-core family)
+        out["iconef_v1_rank_r"] = {"workloads": {name: run_iconef_lowrank(wl.WORKLOADS[name])
+                                                 for name in ("cnn", "lm", "translation")}}
     if not a.no_cpu_baseline:
         v, cores, sample = run_oracle_sample(w)
         out["cpu_baseline"] = {"value": round(v, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",

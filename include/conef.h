@@ -270,20 +270,24 @@ int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
 
 /* ---- The same (Algorithm 3, version 1, the quantiser twice) around the rank-r compressor of conef_step:
  *   p = g + e~ + q,  Delta = P^ Q+^T (one power-iteration step on p),  e~+ = C(p - Delta),  q+ = C(p - Delta - e~+),
- * with the arithmetic stated above.  The accumulation is split in two: conef_i_accumulate adds the first vector to
- * the gradient IN PLACE (g_j <- fma(d1, c1_j, g_j)), and the passes of the step then decode the second vector on top
- * of that sum.  Hence:
- *   grads   device, IN/OUT: fp32 gradients; on return they hold g + e~ (the input of the factorisation)
- * and the calls are for contexts with fp32 gradients, the quantiser and beta = 0 (CONEF_ESTATE otherwise; a bf16
- * gradient buffer cannot take the sum, and the bf16 matrix-core kernel family has no two-vector form).
- * conef_i_step = conef_i_accumulate(grads, e~) -> conef_step_p(grads, q) -> conef_orthonormalise ->
- * conef_step_q(grads, q) -> conef_i_step_err; the two exchange points of conef_step fall between the same calls.
- * conef_i_step_err: grads as left by conef_i_accumulate; err2_* in: q, out: q+; err_* out: e~+ (not read).
+ * with the arithmetic stated above (p_j = fma(d2, c2_j, fma(d1, c1_j, g_j))).  The stage calls mirror those of
+ * conef_step, each decoding both vectors; conef_orthonormalise is shared:
+ *   conef_i_step = conef_i_step_p -> conef_orthonormalise -> conef_i_step_q -> conef_i_step_err,
+ * with the two exchange points of conef_step between the same calls.  conef_i_step_err replaces both vectors in place.
+ * For quantiser contexts with beta = 0 whose matrices all belong to the kernel families for ranks 2/4/8 or for any
+ * shape: CONEF_ESTATE on a count-sketch context, for beta > 0, and when the plan holds a matrix of the bf16
+ * matrix-core family (rank 32, bf16 gradients, 4-bit codes, blocks of 128, columns a multiple of 128), which has no
+ * two-vector form.  CONEF_EINVAL if the two vectors share a buffer.
  * Every other argument, alignment, asynchrony and errors as for conef_step and its stage calls. */
-int conef_i_accumulate(conef_ctx *ctx, float *grads, const uint32_t *err_codes, const float *err_scales, void *hip_stream);
-int conef_i_step_err(conef_ctx *ctx, const float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+int conef_i_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                   const uint32_t *err2_codes, const float *err2_scales, const float *Q_state, float *P_raw_out,
+                   void *workspace, void *hip_stream);
+int conef_i_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                   const uint32_t *err2_codes, const float *err2_scales, const float *P_hat, float *Q_out, void *workspace,
+                   void *hip_stream);
+int conef_i_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                      float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream);
-int conef_i_step(conef_ctx *ctx, float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                  float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
                  void *hip_stream);
 

@@ -23,7 +23,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_strerror", "conef_set_beta",
            "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
-           "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step", "conef_i_accumulate", "conef_i_step_err", "conef_i_step",
+           "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step", "conef_i_step_p", "conef_i_step_q", "conef_i_step_err", "conef_i_step",
            "conef_rk_configure", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
@@ -72,7 +72,8 @@ def lib() -> ctypes.CDLL:
     L.conef_rb_step.argtypes = [vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_rb_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_rk_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
-    L.conef_i_accumulate.argtypes = [vp, vp, vp, vp, vp]
+    L.conef_i_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.conef_i_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.conef_i_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_rk_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
@@ -218,8 +219,14 @@ def conef_i_rk_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, 
                                  _ptr(delta_out), step, stream), "conef_i_rk_step")
 
 
-def conef_i_accumulate(ctx, grads, err_codes, err_scales, stream=0):
-    _check(lib().conef_i_accumulate(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), stream), "conef_i_accumulate")
+def conef_i_step_p(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_raw_out, workspace, stream=0):
+    _check(lib().conef_i_step_p(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
+                                _ptr(Q_state), _ptr(P_raw_out), _ptr(workspace), stream), "conef_i_step_p")
+
+
+def conef_i_step_q(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_out, workspace, stream=0):
+    _check(lib().conef_i_step_q(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
+                                _ptr(P_hat), _ptr(Q_out), _ptr(workspace), stream), "conef_i_step_q")
 
 
 def conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, step: int, stream=0):

@@ -357,58 +357,95 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
 
 // ---------------------------------------------------------------- iConEF version 1 around the rank-r compressor
 namespace {
-// Algorithm 3 has no partial update, the accumulation adds into an fp32 gradient buffer, and the passes that follow
-// must belong to the kernel families that take fp32 gradients (all but the bf16 matrix-core family).
+// Algorithm 3 has no partial update, and the bf16 matrix-core kernel family has no two-vector form.
 int i_lowrank_state(const conef_ctx *ctx)
 {
-    if (ctx->plan.sketch || ctx->plan.beta != 0.0f || ctx->plan.dtype != 0) return CONEF_ESTATE;
+    if (ctx->plan.sketch || ctx->plan.beta != 0.0f || !ctx->plan.p_m_items.empty()) return CONEF_ESTATE;
     return CONEF_OK;
+}
+
+bool i_bad_state_pointers(const void *grads, const uint32_t *c1, const float *s1, const uint32_t *c2, const float *s2)
+{
+    return misaligned(grads, 16) || misaligned(c1, 16) || misaligned(s1, 4) || misaligned(c2, 16) || misaligned(s2, 4) ||
+           c1 == c2 || s1 == s2;
+}
+
+// the plan with the first error vector in it
+struct PlanWithFirst {
+    DevicePlan dp;
+    PlanWithFirst(const conef_ctx *ctx, const uint32_t *c1, const float *s1) : dp(ctx->dev)
+    {
+        dp.i_codes = c1;
+        dp.i_scales = s1;
+    }
+};
+
+int i_step_p_impl(conef_ctx *ctx, const void *grads, const uint32_t *c1, const float *s1, const uint32_t *c2, const float *s2,
+                  const float *Q_state, float *P_raw_out, void *workspace, void *hip_stream)
+{
+    if (!ctx || !grads || !c1 || !s1 || !c2 || !s2 || !Q_state || !P_raw_out || !workspace) return CONEF_EINVAL;
+    int rc = i_lowrank_state(ctx);
+    if (rc) return rc;
+    if (i_bad_state_pointers(grads, c1, s1, c2, s2) || misaligned(Q_state, 16) || misaligned(P_raw_out, 16) ||
+        misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    if ((rc = ensure_uploaded(ctx))) return rc;
+    return hip_rc(launch_pass_p(PlanWithFirst(ctx, c1, s1).dp, grads, c2, s2, Q_state, P_raw_out, ws_doubles(ctx, workspace),
+                                static_cast<hipStream_t>(hip_stream), stage_span(ctx, 0)));
+}
+
+int i_step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *c1, const float *s1, const uint32_t *c2, const float *s2,
+                  const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused)
+{
+    if (!ctx || !grads || !c1 || !s1 || !c2 || !s2 || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
+    int rc = i_lowrank_state(ctx);
+    if (rc) return rc;
+    if (i_bad_state_pointers(grads, c1, s1, c2, s2) || misaligned(P_hat, 16) || misaligned(Q_out, 16) || misaligned(workspace, 256))
+        return CONEF_EINVAL;
+    if ((rc = ensure_uploaded(ctx))) return rc;
+    return hip_rc(launch_pass_q(PlanWithFirst(ctx, c1, s1).dp, grads, c2, s2, P_hat, Q_out, ws_doubles(ctx, workspace), fused,
+                                static_cast<hipStream_t>(hip_stream), stage_span(ctx, 2)));
 }
 }  // namespace
 
-int conef_i_accumulate(conef_ctx *ctx, float *grads, const uint32_t *err_codes, const float *err_scales, void *hip_stream)
+int conef_i_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                   const uint32_t *err2_codes, const float *err2_scales, const float *Q_state, float *P_raw_out,
+                   void *workspace, void *hip_stream)
 {
-    if (!ctx || !grads || !err_codes || !err_scales) return CONEF_EINVAL;
-    int rc = i_lowrank_state(ctx);
-    if (rc) return rc;
-    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4)) return CONEF_EINVAL;
-    if ((rc = ensure_uploaded(ctx))) return rc;
-    return hip_rc(launch_i_accumulate(ctx->dev, grads, err_codes, err_scales, static_cast<hipStream_t>(hip_stream)));
+    return i_step_p_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_raw_out, workspace, hip_stream);
 }
 
-int conef_i_step_err(conef_ctx *ctx, const float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+int conef_i_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
+                   const uint32_t *err2_codes, const float *err2_scales, const float *P_hat, float *Q_out, void *workspace,
+                   void *hip_stream)
+{
+    return i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_out, workspace, hip_stream, false);
+}
+
+int conef_i_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                      float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !P_hat || !Q_new) return CONEF_EINVAL;
     int rc = i_lowrank_state(ctx);
     if (rc) return rc;
-    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
-        misaligned(err2_scales, 4) || misaligned(P_hat, 16) || misaligned(Q_new, 16) || err_codes == err2_codes ||
-        err_scales == err2_scales)
+    if (i_bad_state_pointers(grads, err_codes, err_scales, err2_codes, err2_scales) || misaligned(P_hat, 16) || misaligned(Q_new, 16))
         return CONEF_EINVAL;
     if ((rc = ensure_uploaded(ctx))) return rc;
-    return hip_rc(launch_pass_err_two(ctx->dev, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, step,
-                                      static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
+    return hip_rc(launch_pass_err_two(PlanWithFirst(ctx, err_codes, err_scales).dp, grads, err_codes, err_scales, err2_codes,
+                                      err2_scales, P_hat, Q_new, step, static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
 }
 
-int conef_i_step(conef_ctx *ctx, float *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                  float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
                  void *hip_stream)
 {
-    // everything is checked before the first pass is enqueued: the accumulation changes the gradient buffer
-    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !Q_state || !P_out || !Q_out || !workspace)
-        return CONEF_EINVAL;
-    int rc = i_lowrank_state(ctx);
-    if (rc) return rc;
-    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(err2_codes, 16) ||
-        misaligned(err2_scales, 4) || misaligned(Q_state, 16) || misaligned(P_out, 16) || misaligned(Q_out, 16) ||
-        misaligned(workspace, 256) || err_codes == err2_codes || err_scales == err2_scales)
-        return CONEF_EINVAL;
-    if (ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
-    if ((rc = conef_i_accumulate(ctx, grads, err_codes, err_scales, hip_stream))) return rc;                     // g + e~
-    if ((rc = conef_step_p(ctx, grads, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream))) return rc;   // ... + q
+    int rc;
+    if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
+    if ((rc = i_step_p_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream)))
+        return rc;
     if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
-    if ((rc = step_q_impl(ctx, grads, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true))) return rc;
+    if ((rc = i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true)))
+        return rc;
     return conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, step, hip_stream);
 }
 

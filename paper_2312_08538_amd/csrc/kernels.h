@@ -33,6 +33,11 @@ struct DevicePlan {
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
     uint32_t seed_lo = 0, seed_hi = 0;
     long long q_elems = 0;
+    // Improved contractive error feedback around the rank-r compressor: the FIRST error vector, laid out like the
+    // codes / scales arguments of the pass kernels (which then hold the second one): p = g + first + second.  Null in
+    // every other call; set in a copy of the plan by the launchers of the two-vector passes.
+    const uint32_t *i_codes = nullptr;
+    const float *i_scales = nullptr;
 };
 
 // Optional pair of events recorded immediately before and after a stage's main kernel.
@@ -54,9 +59,9 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
 // Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
-// Improved contractive error feedback around the rank-r compressor (fp32 gradients, no matrix of the bf16 matrix-core
-// family): g <- g + e~ in place, and the err pass that decodes the second vector and writes both.
-hipError_t launch_i_accumulate(const DevicePlan &dp, float *grads, const uint32_t *codes, const float *scales, hipStream_t st);
+// Improved contractive error feedback around the rank-r compressor (no matrix of the bf16 matrix-core family): the P
+// and Q+ passes are launch_pass_p / launch_pass_q on a plan that carries the first vector (i_codes, i_scales) with the
+// second vector as their codes / scales; the err pass decodes both vectors and writes both.
 hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                                float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span);
 void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,

@@ -26,6 +26,18 @@ __device__ __forceinline__ float form_p(const MatDesc &d, const void *grads, con
     return __builtin_fmaf(step, (float)q, load_grad(grads, dtype, d.grad_off + j));
 }
 
+// The same with the plan's first error vector, if there is one (Algorithm 3: p = g + e~ + q, the first vector in the
+// inner fused multiply-add, the codes / scales arguments in the outer one; no partial update there).
+__device__ __forceinline__ float form_p(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
+                                        const float *scales, int64_t j, float omb)
+{
+    if (!dp.i_codes) return form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, j, omb);
+    const int W = 32 / dp.bits;
+    const float inner = form_p(d, grads, dp.i_codes, dp.i_scales, dp.dtype, dp.bits, dp.block, j, 1.0f);
+    const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
+    return __builtin_fmaf(scales[d.scale_off + j / dp.block] * inv_levels(dp.bits), (float)q, inner);
+}
+
 // Sum of T values src[0], src[stride], ... added in index order; loads are issued 8 at a time so
 // the chain of additions, not the memory latency, sets the pace.
 __device__ __forceinline__ double ordered_sum(const double *src, int T, int64_t stride)
@@ -59,7 +71,7 @@ __global__ __launch_bounds__(256) void k_pass_p_generic(DevicePlan dp, const voi
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
     for (int64_t k = lane; k < d.m; k += 64) {
-        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, row * d.m + k, dp.omb);
+        const double pv = (double)form_p(dp, d, grads, codes, scales, row * d.m + k, dp.omb);
         const float *qrow = Q + d.q_off + k * r;
 #pragma unroll
         for (int c = 0; c < RP; ++c)
@@ -92,7 +104,7 @@ __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, con
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
     for (int64_t i = row0; i < row1; ++i) {
-        const double pv = (double)form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, i * d.m + k, dp.omb);
+        const double pv = (double)form_p(dp, d, grads, codes, scales, i * d.m + k, dp.omb);
         const float *prow = Phat + d.p_off + i * r;
 #pragma unroll
         for (int c = 0; c < RP; ++c)
@@ -126,7 +138,7 @@ __device__ __forceinline__ float residual_at(const DevicePlan &dp, const MatDesc
 {
     const int r = dp.rank;
     const int64_t i = j / d.m, k = j - i * d.m;
-    const float pv = form_p(d, grads, codes, scales, dp.dtype, dp.bits, dp.block, j, 1.0f);
+    const float pv = form_p(dp, d, grads, codes, scales, j, 1.0f);
     const float *prow = Phat + d.p_off + i * r;
     const float *qrow = Qn + d.q_off + k * r;
     float acc = 0.0f;
@@ -136,9 +148,9 @@ __device__ __forceinline__ float residual_at(const DevicePlan &dp, const MatDesc
     return pv - acc;
 }
 
-// TWO (improved contractive error feedback, version 1): the vector decoded here (codes, scales) is the second one,
-// the first having been added to the gradient by k_i_accumulate; the rounded residual goes to codes_first /
-// scales_first, what that rounding leaves, rounded again, back to codes / scales.  Three sweeps as in k_rb_generic.
+// TWO (improved contractive error feedback, version 1): p = g + e~ + q with the first vector in the plan
+// (dp.i_codes = codes_first) and the second in codes / scales; the rounded residual goes back to the first vector,
+// what that rounding leaves, rounded again, to the second.  Three sweeps as in k_rb_generic.
 template <int RP, bool TWO>
 __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const void *grads, uint32_t *codes,
                                                           float *scales, const float *Phat, const float *Qn,
@@ -223,33 +235,6 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
             if ((lane % W) == 0 && e < cnt) codes[d.word_off + (j0 + e) / W] = field;
         }
         if (lane == 0) scales[d.scale_off + blk] = a;
-    }
-}
-
-// ---------------------------------------------------------------- accumulation of a compressed vector
-// g <- g + e~ in place on fp32 gradients, one fused multiply-add per entry (the first half of Algorithm 3's
-// accumulation when the rank-r compressor follows: its passes then decode the second vector on top of this sum).
-// A thread takes 4 consecutive entries: they share a code word and a scale block.
-__global__ __launch_bounds__(256) void k_i_accumulate(DevicePlan dp, float *grads, const uint32_t *codes, const float *scales)
-{
-    const WorkItem it = dp.elem_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    const int64_t j = ((int64_t)it.a << 10) + 4 * (int)threadIdx.x;
-    if (j >= d.N) return;
-    const int bits = dp.bits, W = 32 / bits;
-    const uint32_t w = codes[d.word_off + j / W];
-    const float dstep = scales[d.scale_off + j / dp.block] * inv_levels(bits);
-    const int f0 = (int)(j % W);
-    float *gp = grads + d.grad_off + j;
-    if (j + 4 <= d.N) {
-        float4 v = *reinterpret_cast<float4 *>(gp);
-        v.x = __builtin_fmaf(dstep, (float)code_field(w, f0, bits), v.x);
-        v.y = __builtin_fmaf(dstep, (float)code_field(w, f0 + 1, bits), v.y);
-        v.z = __builtin_fmaf(dstep, (float)code_field(w, f0 + 2, bits), v.z);
-        v.w = __builtin_fmaf(dstep, (float)code_field(w, f0 + 3, bits), v.w);
-        *reinterpret_cast<float4 *>(gp) = v;
-    } else {
-        for (int e = 0; j + e < d.N; ++e) gp[e] = __builtin_fmaf(dstep, (float)code_field(w, f0 + e, bits), gp[e]);
     }
 }
 
@@ -538,8 +523,8 @@ void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, 
     }
 }
 
-// The err pass of improved contractive error feedback around the rank-r compressor: codes2 / scales2 is decoded
-// (the first vector is already in the gradient) and receives the second vector, codes / scales the first.
+// The err pass of improved contractive error feedback around the rank-r compressor: codes / scales hold the first
+// vector (also dp.i_codes / dp.i_scales), codes2 / scales2 the second; both are decoded and both replaced.
 hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                                float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
 {
@@ -555,12 +540,6 @@ hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t
         }
     }
     if (span.end) (void)hipEventRecord(span.end, st);
-    return hipGetLastError();
-}
-
-hipError_t launch_i_accumulate(const DevicePlan &dp, float *grads, const uint32_t *codes, const float *scales, hipStream_t st)
-{
-    hipLaunchKernelGGL(k_i_accumulate, dim3(dp.n_elem), dim3(256), 0, st, dp, grads, codes, scales);
     return hipGetLastError();
 }
 

@@ -85,6 +85,18 @@ __device__ __forceinline__ RawCodes<BITS> load_codes_always(const MatDesc &d, co
     return r;
 }
 
+// p <- p + second vector (the outer fused multiply-add of Algorithm 3's accumulation)
+template <int BITS>
+__device__ __forceinline__ void add_codes(const RawCodes<BITS> &r, float p[8])
+{
+    const float step = r.scale * inv_levels(BITS);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int q = BITS == 8 ? code_field(e < 4 ? r.c0 : r.c1, e & 3, 8) : code_field(r.c0, e, BITS);
+        p[e] = __builtin_fmaf(step, (float)q, p[e]);
+    }
+}
+
 // omb: 1 - beta of the partial update in the P and Q+ passes (Algorithm 4 line 5), 1 in the err pass
 template <bool BF16, int BITS>
 __device__ __forceinline__ void decode_octet(const RawOctet<BF16, BITS> &r, float omb, float p[8])
@@ -180,10 +192,10 @@ __device__ __forceinline__ void load_factor_row(const float *__restrict__ F, int
 }
 
 // ------------------------------------------------------------------ err pass
-// TWO (improved contractive error feedback, version 1, around this compressor): the first error vector has been
-// added to the gradient by the accumulation pass, so the vector decoded here (codes, scales) is the second one;
-// the rounded residual goes to codes_first / scales_first and what that rounding leaves, rounded again with random
-// numbers of its own, back to codes / scales (see k_rb_octet).
+// TWO (improved contractive error feedback, version 1, around this compressor): p = g + e~ + q with the first
+// vector in codes_first / scales_first and the second in codes / scales; the rounded residual goes back to the
+// first vector and what that rounding leaves, rounded again with random numbers of its own, to the second
+// (see k_rb_octet).  Both are read by the lane that overwrites them, before it does.
 template <bool BF16, int BITS, int RP, bool TWO = false>
 __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes,
                                                    float *scales, const float *__restrict__ Phat,
@@ -207,9 +219,10 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 
     const int row_end = it.b + it.c;
     // One row of this lane: decode, residual, block max-norm, rounding, store.
-    auto process = [&](const RawOctet<BF16, BITS> &oct, const float (&ph)[RP], int row, bool valid) {
+    auto process = [&](const RawOctet<BF16, BITS> &oct, const RawCodes<BITS> &oct2, const float (&ph)[RP], int row, bool valid) {
         float x[8];
         decode_octet<BF16, BITS>(oct, 1.0f, x);
+        if (TWO) add_codes<BITS>(oct2, x);
         float a = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -252,21 +265,24 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
     // Rows at or beyond the end of the item re-read its last row (nothing is stored for them), so the
     // loads are unconditional.  The next row is loaded before the current one is worked on; two
     // register sets take turns, so nothing is copied from one to the other.
-    auto load_row = [&](RawOctet<BF16, BITS> &oct, float (&ph)[RP], int row) {
+    auto load_row = [&](RawOctet<BF16, BITS> &oct, RawCodes<BITS> &oct2, float (&ph)[RP], int row) {
         const int rc = row < row_end ? row : row_end - 1;
-        oct = load_octet_always<BF16, BITS>(d, grads, codes, scales, (int64_t)rc * d.m8 + oc);
+        // (gradient with the first vector; in the plain step that is the only one)
+        oct = load_octet_always<BF16, BITS>(d, grads, TWO ? codes_first : codes, TWO ? scales_first : scales, (int64_t)rc * d.m8 + oc);
+        if (TWO) oct2 = load_codes_always<BITS>(d, codes, scales, (int64_t)rc * d.m8 + oc);
         load_factor_row<RP>(Phat, d.p_off + (int64_t)rc * r, true, ph);
     };
     RawOctet<BF16, BITS> oa, ob;
+    RawCodes<BITS> oa2 = {0u, 0u, 0.0f}, ob2 = {0u, 0u, 0.0f};
     float pa[RP], pb[RP];
     int row = it.b + sub;
-    load_row(oa, pa, row);
+    load_row(oa, oa2, pa, row);
     for (int r0 = it.b; r0 < row_end; r0 += 2 * rw) {
-        load_row(ob, pb, row + rw);
-        process(oa, pa, row, row < row_end);
+        load_row(ob, ob2, pb, row + rw);
+        process(oa, oa2, pa, row, row < row_end);
         if (r0 + rw >= row_end) break;              // uniform
-        load_row(oa, pa, row + 2 * rw);
-        process(ob, pb, row + rw, row + rw < row_end);
+        load_row(oa, oa2, pa, row + 2 * rw);
+        process(ob, ob2, pb, row + rw, row + rw < row_end);
         row += 2 * rw;
     }
 }
@@ -285,8 +301,9 @@ constexpr int kQTileCols = 64;
 constexpr int kQTilePitch = 80;     // floats per LDS tile row: rows 0..3 of a group fall on distinct banks
 constexpr int kQStepRows = 32;
 
-template <bool BF16, int BITS, int RH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BF16 ? 4 : 3, BF16 ? 4 : 3)))
+// TWO: p = g + e~ + q with the plan's first error vector (dp.i_codes) decoded under the codes / scales arguments.
+template <bool BF16, int BITS, int RH, bool TWO = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((BF16 ? 4 : 3) - (TWO ? 1 : 0), (BF16 ? 4 : 3) - (TWO ? 1 : 0))))
 void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
                const float *__restrict__ scales, const float *__restrict__ Phat, double *ws)
 {
@@ -319,6 +336,7 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     constexpr int kLoads = kQStepRows / 8, kGroups = kQStepRows / 4;
     struct Step {
         RawOctet<BF16, BITS> o[kLoads];
+        RawCodes<BITS> o2[TWO ? kLoads : 1];
         float ph[kGroups][RH];    // P^[i0 + 4 g + mk][mc + 4 h]
     };
     auto load_step = [&](Step &st, int64_t i0) {
@@ -326,7 +344,8 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
         for (int s = 0; s < kLoads; ++s) {
             int64_t row = i0 + lrow + 8 * s;
             row = row < row1 ? row : row1 - 1;
-            st.o[s] = load_octet_always<BF16, BITS>(d, grads, codes, scales, row * d.m8 + oct0);
+            st.o[s] = load_octet_always<BF16, BITS>(d, grads, TWO ? dp.i_codes : codes, TWO ? dp.i_scales : scales, row * d.m8 + oct0);
+            if (TWO) st.o2[s] = load_codes_always<BITS>(d, codes, scales, row * d.m8 + oct0);
         }
         // rows at or beyond row1 re-read the last row; their P^ operand is zero
 #pragma unroll
@@ -349,6 +368,7 @@ void k_q_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
         for (int s = 0; s < kLoads; ++s) {
             float p[8];
             decode_octet<BF16, BITS>(cur.o[s], dp.omb, p);
+            if (TWO) add_codes<BITS>(cur.o2[s], p);
             float4 *dst = reinterpret_cast<float4 *>(T + (lrow + 8 * s) * kQTilePitch + loct * 8);
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
@@ -414,8 +434,10 @@ constexpr int kTileStride = 36;     // floats per LDS tile row: 32 columns + 4 o
 constexpr int kCodePitch = 34;      // words per row of the code stage: 128 bytes + 8 of padding
 constexpr int kScalePitch = 9;      // floats per row of the scale stage: up to 8 blocks per group + 1
 
-template <bool BF16, int BITS, int RH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+// TWO: p = g + e~ + q; the plan's first error vector (dp.i_codes) is staged beside the codes / scales arguments.
+// (the second stage costs LDS: two workgroups per CU instead of three)
+template <bool BF16, int BITS, int RH, bool TWO = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TWO ? 2 : 3, TWO ? 2 : 3)))
 void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__restrict__ codes,
                const float *__restrict__ scales, const float *__restrict__ Q, float *P, double *ws)
 {
@@ -425,6 +447,8 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     __shared__ __attribute__((aligned(16))) float tiles[4][kPTileRows * kTileStride];
     __shared__ __attribute__((aligned(16))) uint32_t cstage[kPTileRows * kCodePitch];
     __shared__ float sstage[kPTileRows * kScalePitch];
+    __shared__ __attribute__((aligned(16))) uint32_t cstage1[TWO ? kPTileRows * kCodePitch : 4];     // first vector
+    __shared__ float sstage1[TWO ? kPTileRows * kScalePitch : 1];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     float *T = tiles[wave];
@@ -454,7 +478,7 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
         float s0, s1;
     };
     const int n_sc = (kGroupCols >> lb) > 0 ? (kGroupCols >> lb) : 1;       // blocks per group and row
-    auto load_group = [&](GroupRegs &gr, int gcol0) {
+    auto load_group = [&](GroupRegs &gr, int gcol0, const uint32_t *codes, const float *scales) {
         const uint8_t *cbase = reinterpret_cast<const uint8_t *>(codes + d.word_off);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -474,7 +498,7 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
             if (s == 0) gr.s0 = v; else gr.s1 = v;
         }
     };
-    auto store_group = [&](const GroupRegs &gr) {
+    auto store_group = [&](const GroupRegs &gr, uint32_t *cstage, float *sstage) {
         {
             const int rr = tid >> 3, part = tid & 7;
             *reinterpret_cast<u32x4 *>(cstage + rr * kCodePitch + part * 4) = gr.c0;
@@ -526,10 +550,11 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
     };
 
     const int n_steps = (c_end - c_begin + kStepCols - 1) / kStepCols;
-    GroupRegs gr;
+    GroupRegs gr, gr1;
     GradRegs cur[4];
     float bq[8][RH], bn[8][RH];
-    load_group(gr, c_begin);
+    load_group(gr, c_begin, codes, scales);
+    if (TWO) load_group(gr1, c_begin, dp.i_codes, dp.i_scales);
     load_grads(cur, c_begin + kSubCols * wave);
     load_b(bq, c_begin + kSubCols * wave);
     for (int step = 0; step < n_steps; ++step) {
@@ -537,9 +562,11 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
         const int gcol0 = c_begin + (step / kGroupSteps) * kGroupCols;        // its code group
         if (step % kGroupSteps == 0) {
             __syncthreads();            // every wave is done with the previous group's stage
-            store_group(gr);
+            store_group(gr, cstage, sstage);
+            if (TWO) store_group(gr1, cstage1, sstage1);
             const int gnext = gcol0 + kGroupCols;
-            load_group(gr, gnext < c_end ? gnext : gcol0);
+            load_group(gr, gnext < c_end ? gnext : gcol0, codes, scales);
+            if (TWO) load_group(gr1, gnext < c_end ? gnext : gcol0, dp.i_codes, dp.i_scales);
             __syncthreads();
         }
         // decode the loaded sub-tile into the wave's LDS tile (row-major, padded)
@@ -548,19 +575,27 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
             const int rr = s * 16 + lrow;
             int oc = ((col0 - gcol0) >> 3) + loct;                       // octet of the group
             oc = oc < (kGroupCols >> 3) ? oc : (kGroupCols >> 3) - 1;    // (columns beyond the chunk: unused)
+            // code bits and block scale of the octet from a stage
+            auto staged = [&](const uint32_t *cs, const float *ss) {
+                RawCodes<BITS> k;
+                k.c1 = 0;
+                if (BITS == 8) {
+                    const uint2 c = *reinterpret_cast<const uint2 *>(cs + rr * kCodePitch + oc * 2);
+                    k.c0 = c.x; k.c1 = c.y;
+                } else if (BITS == 4) {
+                    k.c0 = cs[rr * kCodePitch + oc];
+                } else {
+                    k.c0 = reinterpret_cast<const uint16_t *>(cs + rr * kCodePitch)[oc];
+                }
+                k.scale = ss[rr * kScalePitch + ((oc << 3) >> lb)];
+                return k;
+            };
+            const RawCodes<BITS> k0 = TWO ? staged(cstage1, sstage1) : staged(cstage, sstage);
             RawOctet<BF16, BITS> o;
-            o.g0 = cur[s].g0; o.g1 = cur[s].g1; o.c1 = 0;
-            if (BITS == 8) {
-                const uint2 c = *reinterpret_cast<const uint2 *>(cstage + rr * kCodePitch + oc * 2);
-                o.c0 = c.x; o.c1 = c.y;
-            } else if (BITS == 4) {
-                o.c0 = cstage[rr * kCodePitch + oc];
-            } else {
-                o.c0 = reinterpret_cast<const uint16_t *>(cstage + rr * kCodePitch)[oc];
-            }
-            o.scale = sstage[rr * kScalePitch + ((oc << 3) >> lb)];
+            o.g0 = cur[s].g0; o.g1 = cur[s].g1; o.c0 = k0.c0; o.c1 = k0.c1; o.scale = k0.scale;
             float p[8];
             decode_octet<BF16, BITS>(o, dp.omb, p);
+            if (TWO) add_codes<BITS>(staged(cstage, sstage), p);
             float4 *dst = reinterpret_cast<float4 *>(T + rr * kTileStride + loct * 8);
             dst[0] = make_float4(p[0], p[1], p[2], p[3]);
             dst[1] = make_float4(p[4], p[5], p[6], p[7]);
@@ -868,18 +903,40 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
         }                                                                \
     } while (0)
 
+// the two-vector instances (a plan that carries a first error vector, see DevicePlan::i_codes)
+#define CONEF_OCTET2T_CASE(KERNEL, BF, B, GRID, ST, ...)                                                           \
+    case ((BF ? 1 : 0) << 8) | B:                                                                                  \
+        if (dp.rank > 4) hipLaunchKernelGGL((KERNEL<BF, B, 2, true>), GRID, dim3(256), 0, ST, __VA_ARGS__);        \
+        else hipLaunchKernelGGL((KERNEL<BF, B, 1, true>), GRID, dim3(256), 0, ST, __VA_ARGS__);                    \
+        break;
+
+#define CONEF_OCTET2T_DISPATCH(KERNEL, GRID, ST, ...)                     \
+    do {                                                                  \
+        switch ((dp.dtype << 8) | dp.bits) {                              \
+            CONEF_OCTET2T_CASE(KERNEL, false, 2, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2T_CASE(KERNEL, false, 4, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2T_CASE(KERNEL, false, 8, GRID, ST, __VA_ARGS__)   \
+            CONEF_OCTET2T_CASE(KERNEL, true, 2, GRID, ST, __VA_ARGS__)    \
+            CONEF_OCTET2T_CASE(KERNEL, true, 4, GRID, ST, __VA_ARGS__)    \
+            CONEF_OCTET2T_CASE(KERNEL, true, 8, GRID, ST, __VA_ARGS__)    \
+        default: break;                                                   \
+        }                                                                 \
+    } while (0)
+
 void octet_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                   const float *Q, float *P, double *ws, hipStream_t st)
 {
     if (dp.n_p_f <= 0) return;
-    CONEF_OCTET2_DISPATCH(k_p_octet, dim3(dp.n_p_f), st, dp, grads, codes, scales, Q, P, ws);
+    if (dp.i_codes) CONEF_OCTET2T_DISPATCH(k_p_octet, dim3(dp.n_p_f), st, dp, grads, codes, scales, Q, P, ws);
+    else CONEF_OCTET2_DISPATCH(k_p_octet, dim3(dp.n_p_f), st, dp, grads, codes, scales, Q, P, ws);
 }
 
 void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                   const float *Phat, double *ws, hipStream_t st)
 {
     if (dp.n_q_f <= 0) return;
-    CONEF_OCTET2_DISPATCH(k_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, codes, scales, Phat, ws);
+    if (dp.i_codes) CONEF_OCTET2T_DISPATCH(k_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, codes, scales, Phat, ws);
+    else CONEF_OCTET2_DISPATCH(k_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, codes, scales, Phat, ws);
 }
 
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
@@ -890,24 +947,28 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
                          (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr);
 }
 
-// The err pass of improved contractive error feedback (fp32 gradients only): codes2 / scales2 is decoded and
-// receives the second vector, codes / scales the first.
+// The err pass of improved contractive error feedback: codes / scales hold the first vector, codes2 / scales2 the
+// second; both are decoded and both replaced.
 void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                         float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st)
 {
     if (dp.n_err_f <= 0) return;
     const dim3 grid((dp.n_err_f + 3) / 4);
-#define CONEF_ERR_TWO_CASE(B, R)                                                                                        \
-    case (B << 4) | R:                                                                                                  \
-        hipLaunchKernelGGL((k_err_octet<false, B, R, true>), grid, dim3(256), 0, st, dp, grads, codes2, scales2, Phat,  \
+#define CONEF_ERR_TWO_CASE(BF, B, R)                                                                                    \
+    case ((BF ? 1 : 0) << 8) | (B << 4) | R:                                                                            \
+        hipLaunchKernelGGL((k_err_octet<BF, B, R, true>), grid, dim3(256), 0, st, dp, grads, codes2, scales2, Phat,     \
                            Qn, (uint32_t)step, (uint32_t)(step >> 32), codes, scales);                                  \
         break;
-    switch ((dp.bits << 4) | dp.rank) {
-        CONEF_ERR_TWO_CASE(2, 2) CONEF_ERR_TWO_CASE(2, 4) CONEF_ERR_TWO_CASE(2, 8)
-        CONEF_ERR_TWO_CASE(4, 2) CONEF_ERR_TWO_CASE(4, 4) CONEF_ERR_TWO_CASE(4, 8)
-        CONEF_ERR_TWO_CASE(8, 2) CONEF_ERR_TWO_CASE(8, 4) CONEF_ERR_TWO_CASE(8, 8)
+#define CONEF_ERR_TWO_DTYPE(BF)                                                                   \
+    CONEF_ERR_TWO_CASE(BF, 2, 2) CONEF_ERR_TWO_CASE(BF, 2, 4) CONEF_ERR_TWO_CASE(BF, 2, 8)        \
+    CONEF_ERR_TWO_CASE(BF, 4, 2) CONEF_ERR_TWO_CASE(BF, 4, 4) CONEF_ERR_TWO_CASE(BF, 4, 8)        \
+    CONEF_ERR_TWO_CASE(BF, 8, 2) CONEF_ERR_TWO_CASE(BF, 8, 4) CONEF_ERR_TWO_CASE(BF, 8, 8)
+    switch ((dp.dtype << 8) | (dp.bits << 4) | dp.rank) {
+        CONEF_ERR_TWO_DTYPE(false)
+        CONEF_ERR_TWO_DTYPE(true)
     default: break;
     }
+#undef CONEF_ERR_TWO_DTYPE
 #undef CONEF_ERR_TWO_CASE
 }
 
