@@ -258,7 +258,8 @@ int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *s
  * than e~+ alone, for twice the state.  Algorithm 3 has no partial update: CONEF_ESTATE unless the context's beta is 0,
  * on a count-sketch context, and for conef_i_rb_step before conef_rb_configure.
  *   err2_codes, err2_scales   device, in/out: laid out like err_codes / err_scales (same offsets and sizes); must
- *                             not be the same buffers (CONEF_EINVAL)
+ *                             not be the same buffers (CONEF_EINVAL); conef_reset_error and conef_decode_error
+ *                             serve either vector (pass its buffers)
  * Every other argument, alignment, asynchrony and errors as for conef_rb_step / conef_ss_step. */
 int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                     float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
