@@ -1,4 +1,6 @@
-"""ctypes face of the CPU oracle (oracle/conef_ref.c).
+"""ctypes face of the CPU oracle: oracle/conef_ref.c (the step of Algorithm 2), sketch_ref.c (count sketch, partial
+update), randblock_ref.c (random block, scaled sign), iconef_ref.c (Algorithm 3, version 1) and randk_ref.c (random-k),
+built into one shared library with gcc.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
 bench.py's cpu_baseline leg.  The product package never imports this module.
