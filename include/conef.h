@@ -3,7 +3,10 @@
  * contractive error feedback (ConEF, arXiv 2312.08538, Algorithm 2) with a rank-r
  * PowerSGD-style gradient compressor (Section 5.2) and the block-wise stochastic
  * quantiser of Section 4.2.1, eq. (3) (max-norm variant, Section 5.1) as the error
- * compressor.
+ * compressor; further down, the other compressors of the paper: the count sketch as the
+ * error compressor with the partial update of Algorithm 4 (conef_cs_*), the element-wise
+ * gradient compressors random block, random-k and scaled sign (conef_rb_*, conef_rk_*,
+ * conef_ss_*), and improved contractive error feedback, Algorithm 3 (conef_i_*).
  *
  * Conventions
  *   - Every function returns CONEF_OK (0) or a negative CONEF_E* code; nothing throws,
@@ -22,6 +25,9 @@
  *     line 1), so zero-filled buffers are a valid initial state.
  *   - Random draws: Philox4x32-10, counter (j>>3, l, lo32(step), hi32(step)), key
  *     (lo32(seed), hi32(seed)); element j uses 16 bits: half (j&1) of output word (j&7)>>1.
+ *     Other draws use counters of their own, stated with the calls: (l, 2^32-1, step) the random
+ *     block's start, (i>>2, l + 2^30, step) the random-k strata, (j>>3, l + 2^31, step) the second
+ *     rounding of Algorithm 3, (i, l, 2^32-1, 2^32-1) the sketch's row hash.
  *   - Calls on one context must not overlap in time (they share the workspace).
  */
 #ifndef CONEF_H
