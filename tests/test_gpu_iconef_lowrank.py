@@ -153,11 +153,13 @@ def test_rank_r_iconef_calls_reject_what_they_cannot_serve(env):
     sk.close()
 
 
-def test_lm_whole_model_second_step_against_the_oracle(env):
-    """Every matrix of the `lm` workload (123.5 M fp32 elements, rank 4: the launch configuration `bench.py` times for
-    this step), whole: the library's second step against the oracle started from the state the library held before it."""
+@pytest.mark.parametrize("name", ["lm", "translation"])
+def test_whole_model_second_step_against_the_oracle(env, name):
+    """Every matrix of the `lm` (123.5 M fp32 elements, rank 4) and `translation` (209.7 M bf16 elements, rank 8, 2-bit
+    codes) workloads, whole, in the launch configuration `bench.py` times for this step: the library's second step
+    against the oracle started from the state the library held before it."""
     R, B, U, torch = env
-    w = wl.WORKLOADS["lm"]
+    w = wl.WORKLOADS[name]
     bits, block, rank, seed, W = w.bits, w.block, w.rank, w.lib_seed, 32 // w.bits
     model = B.Model(w.layout, rank, bits, block, w.grad_dtype, seed)
     buf = model.alloc()
@@ -166,7 +168,7 @@ def test_lm_whole_model_second_step_against_the_oracle(env):
     wl.device_q0(w, buf["Q"], [o["q_off"] for o in model.offsets])
 
     def step(t):
-        print(f"[iconef rank-r lm] step {t}: launching", flush=True)
+        print(f"[iconef rank-r {name}] step {t}: launching", flush=True)
         B.conef_i_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, buf["Q"], buf["P"], buf["Q"],
                        buf["ws"], t, model.stream_handle())
         torch.cuda.synchronize()
@@ -179,7 +181,8 @@ def test_lm_whole_model_second_step_against_the_oracle(env):
     step(0)
     before, Q0 = download(), buf["Q"].cpu().numpy()
     wl.device_fill_gradients(w, 1, buf["grads"], goffs)
-    g_all = buf["grads"].cpu().numpy()
+    g_dev = buf["grads"].view(torch.int16) if w.grad_dtype == wl.BF16 else buf["grads"]
+    g_all = g_dev.cpu().numpy().view(np.uint16 if w.grad_dtype == wl.BF16 else np.float32)
     step(1)
     after, P1, Q1 = download(), buf["P"].cpu().numpy(), buf["Q"].cpu().numpy()
     assert np.any(before[2] != 0)
@@ -193,12 +196,12 @@ def test_lm_whole_model_second_step_against_the_oracle(env):
         own = [a.copy() for a in st]
         R.i_error(R.residual(R.i_form_p(g, *st, bits, block).reshape(n, m), P_gpu, Q_gpu), *own, bits, block, seed, l, 1)
         Ph, Qn = R.i_step_matrix(g, *st, Q0[o["q_off"]:o["q_off"] + m * rank].reshape(m, rank), rank, bits, block, seed, l, 1)
-        tag = f"lm mat {l} ({n}x{m})"
+        tag = f"{name} mat {l} ({n}x{m})"
         assert U.rel_err(P_gpu, Ph) <= 1e-5 and U.rel_err(Q_gpu, Qn) <= 1e-5, f"{tag}: factors"
-        for i, name in enumerate(("first codes", "first scales", "second codes", "second scales")):
+        for i, what in enumerate(("first codes", "first scales", "second codes", "second scales")):
             off, cnt = (o["word_off"], nw) if i % 2 == 0 else (o["scale_off"], nb)
             got = after[i][off:off + cnt]
             assert np.array_equal(got.view(np.uint32), own[i].view(np.uint32)), \
-                f"{tag}: {name} differ in {(got.view(np.uint32) != own[i].view(np.uint32)).sum()} of {cnt}"
-    print(f"[iconef rank-r lm] all {len(w.layout)} matrices: both error vectors bit for bit", flush=True)
+                f"{tag}: {what} differ in {(got.view(np.uint32) != own[i].view(np.uint32)).sum()} of {cnt}"
+    print(f"[iconef rank-r {name}] all {len(w.layout)} matrices: both error vectors bit for bit", flush=True)
     model.close()
