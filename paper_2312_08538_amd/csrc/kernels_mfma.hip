@@ -597,25 +597,61 @@ struct ErrIn {
 };
 
 // Fixed-point stochastic rounding of an octet into a word of eight 4-bit two's-complement fields.
-// Magnitudes (0..7) and sign bits are gathered nibble by nibble; the negation is done on the whole
-// word: for a negative field ((mag ^ 7) + 1) ^ 8 = 16 - mag for mag = 1..7 and 0 for mag = 0,
-// without carries between fields.
+// U + draw is below 2^19 for finite input, so byte 2 of the sum is the magnitude (0..7) and nothing
+// else: byte permutes gather the eight magnitudes (even elements into the low nibbles of a word's
+// bytes, odd ones into the high nibbles).  Sign bits are gathered nibble by nibble; the negation is
+// done on the whole word: for a negative field ((mag ^ 7) + 1) ^ 8 = 16 - mag for mag = 1..7 and 0
+// for mag = 0, without carries between fields.
 __device__ __forceinline__ uint32_t quantise_octet4(const float x[8], float inv16, const uint32_t rnd[4])
 {
-    uint32_t mags = 0, sg = 0;
+    uint32_t t[8], sg = 0;
 #pragma unroll
     for (int e = 7; e >= 0; --e) {
         const uint32_t U = (uint32_t)(fabsf(x[e]) * inv16);
         const uint32_t r16 = (e & 1) ? (rnd[e >> 1] >> 16) : (rnd[e >> 1] & 0xFFFFu);
-        mags = (mags << 4) | ((U + r16) >> 16);
+        t[e] = U + r16;
         sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(x[e]), 28);      // (sg << 4) | top nibble of x
     }
+    // __builtin_amdgcn_perm(hi, lo, sel): result byte i is byte sel_i of {hi, lo} (0..3 lo, 4..7 hi, 12: zero)
+    const uint32_t ev = __builtin_amdgcn_perm(t[2], t[0], 0x0C0C0602u) | __builtin_amdgcn_perm(t[6], t[4], 0x06020C0Cu);
+    const uint32_t od = __builtin_amdgcn_perm(t[3], t[1], 0x0C0C0602u) | __builtin_amdgcn_perm(t[7], t[5], 0x06020C0Cu);
+    const uint32_t mags = (od << 4) | ev;
     sg &= 0x88888888u;
     const uint32_t s1 = sg >> 3, s7 = sg - s1;
     return ((mags ^ s7) + s1) ^ sg;
 }
 
-__global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
+// the value of lane (lane ^ 1) / (lane ^ 2) of the quad, and of the lanes 4 and 8 further on in the row of 16
+__device__ __forceinline__ uint32_t dpp_quad_xor1(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0xB1, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t dpp_quad_xor2(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x4E, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t dpp_row_ror4(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x124, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t dpp_row_ror8(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x128, 0xF, 0xF, true); }
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// signed 4-bit field in the low nibble of byte `byte` of w, divided by 16 (exact), as fp32: the
+// conversion instruction reads the nibble through its byte selector, so no shift or mask is spent
+template <int byte>
+__device__ __forceinline__ float nibble_over_16(uint32_t w)
+{
+    float r;
+    if constexpr (byte == 0) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
+    else if constexpr (byte == 1) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(r) : "v"(w));
+    else if constexpr (byte == 2) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
+    else asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
+    return r;
+}
+
+// the eight fields of a code word, each divided by 16
+__device__ __forceinline__ void fields_over_16(uint32_t w, float q[8])
+{
+    const uint32_t w4 = w >> 4;
+    q[0] = nibble_over_16<0>(w); q[1] = nibble_over_16<0>(w4);
+    q[2] = nibble_over_16<1>(w); q[3] = nibble_over_16<1>(w4);
+    q[4] = nibble_over_16<2>(w); q[5] = nibble_over_16<2>(w4);
+    q[6] = nibble_over_16<3>(w); q[7] = nibble_over_16<3>(w4);
+}
+
+__global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][kErrTileElems];
@@ -624,35 +660,36 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
     const WorkItem it = dp.err_m_items[xcd_contiguous_item(blockIdx.x, dp.n_err_m)];
     const MatDesc d = dp.mats[it.mat];
     const int m = (int)d.m, m8 = m >> 3, nblk_row = m >> 7;
-    const int64_t row0 = (int64_t)it.a + 16 * wave;
+    const int64_t tile_row0 = it.a;                  // first row of the workgroup's tile: inside the matrix
+    const int64_t row0 = tile_row0 + 16 * wave;
     const int cb0 = it.b, nb = it.c;
     const int cc = lane & 15, kg = lane >> 4;
     // rows of this wave that exist; a wave below the matrix still fills LDS and joins the barriers
     const int rows_left = (int)((d.n - row0 < 16) ? (d.n - row0 > 0 ? d.n - row0 : 0) : 16);
-    const uint16_t *g = grads + d.grad_off;
-    uint32_t *cw = codes + d.word_off;
-    float *sc = scales + d.scale_off;
     const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
-    // incoming scales of the run's first block, by row; block b of the run is b * n further (below 2^32)
-    const float *scT_run = reinterpret_cast<const float *>(ws + d.scT_off) + (int64_t)it.b * d.n;
-    const uint32_t n32 = (uint32_t)d.n;
 
-    // Rows of the tile that lie below the matrix are clamped to the matrix's last row for loading
-    // (their results are never stored), so every load of the loop is unconditional.
+    // Addresses are a scalar base (the tile's first row, the block in turn) plus a 32-bit lane offset
+    // that stays the same for the whole run.  Rows of the tile that lie below the matrix are clamped
+    // to its last row for loading (their results are never stored), so every load of the loop is
+    // unconditional.
+    const uint16_t *g_tile = grads + d.grad_off + tile_row0 * m;                       // + cb * 128 elements
+    uint32_t *cw_tile = codes + d.word_off + tile_row0 * m8;                            // + cb * 16 words
+    // incoming scales, column-block-major copy [block][row]: + cb * n
+    const float *scT_tile = reinterpret_cast<const float *>(ws + d.scT_off) + tile_row0;
     bool valid[4];
-    int64_t grow[4];                 // element offset of the row start
-    uint32_t orow[4], srow[4];       // octet / scale offset of the row start (both below 2^32)
-    uint32_t trow[4];                // row, for the column-block-major copy of the incoming scales
+    uint32_t goff[4], ooff[4], toff[4];     // byte offsets of the lane's gradient octet, code word and scale from the bases
+    uint32_t octet0[4];                     // octet index (within the matrix) of the lane's octet in column block 0
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int rr = 4 * kg + v;
         valid[v] = rr < rows_left;
         const int64_t row = (row0 + rr < d.n) ? row0 + rr : d.n - 1;
-        grow[v] = row * m;
-        orow[v] = (uint32_t)(row * m8);
-        srow[v] = (uint32_t)(row * nblk_row);
-        trow[v] = (uint32_t)row;
+        const uint32_t rel = (uint32_t)(row - tile_row0);               // 0 .. 127
+        goff[v] = (rel * (uint32_t)m + (uint32_t)cc * 8u) * 2u;
+        ooff[v] = (rel * (uint32_t)m8 + (uint32_t)cc) * 4u;
+        toff[v] = rel * 4u;
+        octet0[v] = (uint32_t)(row * m8) + (uint32_t)cc;
     }
 
     // negated splits of this wave's rows of P^
@@ -668,43 +705,69 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
     }
 
     auto load_in = [&](ErrIn &in, int cb) {
+        const char *gb = reinterpret_cast<const char *>(g_tile + cb * 128);
+        const char *cb_w = reinterpret_cast<const char *>(cw_tile + cb * 16);
+        const char *sb = reinterpret_cast<const char *>(scT_tile + (int64_t)cb * d.n);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            in.g[v] = *reinterpret_cast<const uint4 *>(g + grow[v] + cb * 128 + cc * 8);
-            in.cw[v] = cw[orow[v] + (uint32_t)(cb * 16 + cc)];
-            in.s[v] = scT_run[(uint32_t)(cb - cb0) * n32 + trow[v]];
+            in.g[v] = *reinterpret_cast<const uint4 *>(gb + goff[v]);
+            in.cw[v] = *reinterpret_cast<const uint32_t *>(cb_w + ooff[v]);
+            in.s[v] = *reinterpret_cast<const float *>(sb + toff[v]);
         }
     };
-    // a block's splits of Q+: 1536 chunks of 16 bytes, three per thread
-    const uint4 *qsrc = reinterpret_cast<const uint4 *>(Qs) + tid;
-    constexpr int kChunks = kErrTileElems / 8;      // 16-byte chunks per block
+    // a block's splits of Q+: 1536 chunks of 16 bytes, three per thread (scalar base + lane offset again)
+    constexpr int kBlockBytes = kErrTileElems * 2;
+    uint32_t qoff = (uint32_t)tid * 16u;
+    auto load_q_splits = [&](int cb, uint4 &b0, uint4 &b1, uint4 &b2) {
+        const char *qb = reinterpret_cast<const char *>(Qs) + (int64_t)cb * kBlockBytes;
+        b0 = *reinterpret_cast<const uint4 *>(qb + qoff);
+        b1 = *reinterpret_cast<const uint4 *>(qb + 8192 + qoff);
+        b2 = *reinterpret_cast<const uint4 *>(qb + 16384 + qoff);
+    };
 
     ErrIn in;
     load_in(in, cb0);
     {
-        const uint4 *src = qsrc + (int64_t)cb0 * kChunks;
         uint4 *dst = reinterpret_cast<uint4 *>(sB[0]) + tid;
-        const uint4 b0 = src[0], b1 = src[512], b2 = src[1024];
+        uint4 b0, b1, b2;
+        load_q_splits(cb0, b0, b1, b2);
         dst[0] = b0; dst[512] = b1; dst[1024] = b2;
     }
     __syncthreads();
 
+    // The block max-norms are reduced "transposed": the 16 lanes of a row group hold four maxima each
+    // (one per row 4 kg + v); two exchange steps inside the quad leave every lane with ONE row's
+    // maximum over its quad (lane qi of a quad ends up with row vq below), two rotations by 4 and 8
+    // lanes finish it.  The lane then divides for its row only, and the quad exchanges the quotients.
+    const int qi = lane & 3, quad = cc >> 2;
+    const bool odd1 = (qi & 1) != 0, odd2 = (qi & 2) != 0;
+    const int vq = 2 * (qi & 1) + (qi >> 1);        // the row (of the lane's four) whose maximum the lane ends up with
+    const bool valid_q = (4 * kg + vq) < rows_left;
+    // the outgoing scales: block 4 j + quad of the run, row 4 kg + vq, j = 0..3
     float keep[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int b = 0; b < nb; ++b) {
         const int cb = cb0 + b;
         const int cbn = (b + 1 < nb) ? cb + 1 : cb;      // the last trip reloads its own block (unused)
-        const uint4 *bsrc = qsrc + (int64_t)cbn * kChunks;
-        const uint4 bq0 = bsrc[0], bq1 = bsrc[512], bq2 = bsrc[1024];
+        // keeps the lane offsets as they are (scalar base + 32-bit lane offset addressing): without it the
+        // compiler turns every address into a 64-bit per-lane pointer that it advances with vector adds
+#pragma unroll
+        for (int v = 0; v < 4; ++v) asm volatile("" : "+v"(goff[v]), "+v"(ooff[v]), "+v"(toff[v]));
+        asm volatile("" : "+v"(qoff));
+        uint4 bq0, bq1, bq2;
+        load_q_splits(cbn, bq0, bq1, bq2);
         // decode p into the accumulators: acc[t][v] = p[row 4 kg + v][column 8 cc + t]
         f32x4 acc[8];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const uint32_t w4[4] = {in.g[v].x, in.g[v].y, in.g[v].z, in.g[v].w};
-            const float step = in.s[v] * inv_levels(4);
+            // 16 d with d = scale * fl(1/7): the fields come divided by 16, and the product with a power of two is exact
+            const float step16 = (in.s[v] * inv_levels(4)) * 16.0f;
+            float q16[8];
+            fields_over_16(in.cw[v], q16);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
-                acc[e][v] = __builtin_fmaf(step, (float)code_field(in.cw[v], e, 4), gv);
+                acc[e][v] = __builtin_fmaf(step16, q16[e], gv);
             }
         }
         load_in(in, cbn);
@@ -733,48 +796,58 @@ __global__ __launch_bounds__(512) void k_err_mfma(DevicePlan dp, const uint16_t 
             dst[0] = bq0; dst[512] = bq1; dst[1024] = bq2;
         }
         // rounding phase.  First the max-norm of each of the lane's four row blocks (16 lanes = one
-        // 128-column block) ...
-        float amax[4];
+        // 128-column block): non-negative floats order like their bit patterns, so the cross-lane
+        // steps are integer maxima (one instruction each with the lane permutation folded in)
+        uint32_t am[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             float a = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(acc[e][v]));
-            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0xB1, 0xF, 0xF, true)));
-            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x4E, 0xF, 0xF, true)));
-            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x141, 0xF, 0xF, true)));
-            a = fmaxf(a, __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x140, 0xF, 0xF, true)));
-            amax[v] = a;
-            keep[v] = (cc == b) ? a : keep[v];
+            am[v] = __float_as_uint(a);
         }
-        // ... then the four reciprocal step sizes s / a: all 16 lanes of a row group need all four, so
-        // lane i of every quad divides for row block i and the quad exchanges the results
-        const int qi = lane & 3;
-        const float asel = (qi == 0) ? amax[0] : (qi == 1) ? amax[1] : (qi == 2) ? amax[2] : amax[3];
-        const float isel = (asel > 0.0f) ? (7.0f / asel) * 65536.0f : 0.0f;
+        const uint32_t r0 = umax(odd1 ? am[2] : am[0], dpp_quad_xor1(odd1 ? am[0] : am[2]));
+        const uint32_t r1 = umax(odd1 ? am[3] : am[1], dpp_quad_xor1(odd1 ? am[1] : am[3]));
+        uint32_t mx = umax(odd2 ? r1 : r0, dpp_quad_xor2(odd2 ? r0 : r1));
+        mx = umax(mx, dpp_row_ror4(mx));
+        mx = umax(mx, dpp_row_ror8(mx));
+        const float amax = __uint_as_float(mx);       // max-norm of block cb of row 4 kg + vq
+        {
+            const bool mine = quad == (b & 3);
+            const int j = b >> 2;
+            keep[0] = (mine && j == 0) ? amax : keep[0];
+            keep[1] = (mine && j == 1) ? amax : keep[1];
+            keep[2] = (mine && j == 2) ? amax : keep[2];
+            keep[3] = (mine && j == 3) ? amax : keep[3];
+        }
+        // ... then the reciprocal step size s / a of the lane's row, exchanged inside the quad
+        // (lane 0 of a quad holds row 0, lane 2 row 1, lane 1 row 2, lane 3 row 3)
+        const float isel = (amax > 0.0f) ? (7.0f / amax) * 65536.0f : 0.0f;
         const float inv16v[4] = {
             __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x00, 0xF, 0xF, true)),
-            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x55, 0xF, 0xF, true)),
             __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xAA, 0xF, 0xF, true)),
+            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x55, 0xF, 0xF, true)),
             __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xFF, 0xF, 0xF, true))};
         // ... then one octet (row 4 kg + v, columns 8 cc ..) at a time
+        char *cw_out = reinterpret_cast<char *>(cw_tile + cb * 16);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             float x[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = acc[e][v];
-            const uint32_t o = orow[v] + (uint32_t)(cb * 16 + cc);
+            const uint32_t o = octet0[v] + (uint32_t)(cb * 16);
             uint32_t rnd[4];
             philox4x32_10(o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
             const uint32_t word = quantise_octet4(x, inv16v[v], rnd);
-            if (valid[v]) cw[o] = word;
+            if (valid[v]) *reinterpret_cast<uint32_t *>(cw_out + ooff[v]) = word;
         }
         __syncthreads();        // the next block's splits are in LDS; everybody is done with this block's
     }
-    if (cc < nb) {
+    if (valid_q) {
+        float *sc_row = scales + d.scale_off + (row0 + 4 * kg + vq) * nblk_row + cb0;
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (valid[v]) sc[srow[v] + (uint32_t)(cb0 + cc)] = keep[v];
+        for (int j = 0; j < 4; ++j)
+            if (4 * j + quad < nb) sc_row[4 * j + quad] = keep[j];
     }
 }
 
