@@ -274,17 +274,14 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
 }
 
 namespace {
-// fused: the call is part of conef_step, so the stage that follows works on exactly what this one
-// leaves behind (the operand splits of P^ written by the orthonormalisation are still valid for
-// the Q+ stage, which then need not make them again)
-int orthonormalise_impl(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream, bool fused)
+int orthonormalise_impl(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
 {
     if (!ctx || !P_inout || !workspace) return CONEF_EINVAL;
     if (misaligned(P_inout, 16) || misaligned(workspace, 256)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), fused, st, stage_span(ctx, 1)));
+    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st, stage_span(ctx, 1)));
 }
 
 int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
@@ -293,7 +290,7 @@ int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, co
 
 int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
 {
-    return orthonormalise_impl(ctx, P_inout, workspace, hip_stream, false);
+    return orthonormalise_impl(ctx, P_inout, workspace, hip_stream);
 }
 
 int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
@@ -348,7 +345,7 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_out, workspace, hip_stream))) return rc;
     /* exchange point 1: mean of P over the workers -- identity for one worker */
-    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
     if ((rc = step_q_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream, true))) return rc;
     /* exchange point 2: mean of Q over the workers -- identity for one worker; the operand splits
        of P^ and Q+ made by the Q+ stage are therefore still valid for the err stage */
@@ -443,7 +440,7 @@ int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = i_step_p_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream)))
         return rc;
-    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
     if ((rc = i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true)))
         return rc;
     return conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, step, hip_stream);
@@ -734,7 +731,7 @@ int conef_cs_step(conef_ctx *ctx, const void *grads, void *table, const float *Q
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_cs_step_p(ctx, grads, table, Q_state, P_out, workspace, hip_stream))) return rc;
     /* exchange point 1: mean of P over the workers -- identity for one worker */
-    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, true))) return rc;
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
     if ((rc = conef_cs_step_q(ctx, grads, table, P_out, Q_out, workspace, hip_stream))) return rc;
     /* exchange point 2: mean of Q over the workers -- identity for one worker */
     return conef_cs_step_err(ctx, grads, table, P_out, Q_out, workspace, hip_stream);

@@ -48,7 +48,7 @@ struct Span {
 // Each launcher enqueues on `st` and returns hipGetLastError().  `ws` is the caller's workspace.
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Q, float *P, double *ws, hipStream_t st, Span span = Span());
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, bool write_splits, hipStream_t st,
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st,
                                  Span span = Span());
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Phat, float *Qout, double *ws, bool fused, hipStream_t st,
@@ -116,12 +116,11 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
 void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Q, float *P, hipStream_t st);
 
-void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st);
 void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st);
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Phat, double *ws, float *Qout, hipStream_t st);
-void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,
-                   uint64_t step, hipStream_t st);
+void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                   const double *ws, uint64_t step, hipStream_t st);
 void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st);
 
 }  // namespace conef

@@ -578,12 +578,11 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 {
     if (!splits_ready) {
         // the factors handed in may differ from those the Q+ stage saw (e.g. after an all-reduce)
-        mfma_split_p_hat(dp, Phat, ws, st);
         mfma_split_q_new(dp, Qn, ws, st);
         mfma_transpose_scales(dp, scales, ws, st);      // the state may have changed since a Q+ stage ran
     }
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    mfma_pass_err(dp, grads, codes, scales, ws, step, st);
+    mfma_pass_err(dp, grads, codes, scales, Phat, ws, step, st);
     octet_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     generic_pass_err(dp, grads, codes, scales, Phat, Qn, step, st);
     if (span.end) (void)hipEventRecord(span.end, st);

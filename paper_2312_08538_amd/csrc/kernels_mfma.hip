@@ -289,26 +289,6 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 }
 
 // ------------------------------------------------------------------ splits of P^ and Q+
-// P^ (n x 32): row-major operand splits for the err pass.
-__global__ __launch_bounds__(256) void k_split_p_hat(DevicePlan dp, const float *__restrict__ Phat, double *ws)
-{
-    const WorkItem it = dp.split_p_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    const float *src = Phat + d.p_off;
-    const int r0 = it.a * 64;
-    uint16_t *rm = reinterpret_cast<uint16_t *>(ws + d.ps_off);            // [3][n][32]
-    for (int e = threadIdx.x; e < 64 * 32; e += 256) {
-        const int row = r0 + (e >> 5), c = e & 31;
-        if (row < d.n) {
-            float h, m, l;
-            split3(src[(int64_t)row * 32 + c], h, m, l);
-            rm[((int64_t)0 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(h) >> 16);
-            rm[((int64_t)1 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(m) >> 16);
-            rm[((int64_t)2 * d.n + row) * 32 + c] = (uint16_t)(__float_as_uint(l) >> 16);
-        }
-    }
-}
-
 // Column-block-major copy of the block scales of a matrix, scT[block of the row][row]: the Q+ and err
 // passes need, per 128-column block, the scales of consecutive rows, which are a row pitch apart
 // (a 128-byte line each) in the state's own row-major order.  One workgroup per 64 rows.
@@ -652,7 +632,8 @@ __device__ __forceinline__ void fields_over_16(uint32_t w, float q[8])
 }
 
 __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
-                                                  float *scales, const double *ws, uint32_t step_lo, uint32_t step_hi)
+                                                  float *scales, const float *__restrict__ Phat, const double *ws,
+                                                  uint32_t step_lo, uint32_t step_hi)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][kErrTileElems];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -666,7 +647,6 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
     const int cc = lane & 15, kg = lane >> 4;
     // rows of this wave that exist; a wave below the matrix still fills LDS and joins the barriers
     const int rows_left = (int)((d.n - row0 < 16) ? (d.n - row0 > 0 ? d.n - row0 : 0) : 16);
-    const uint16_t *Ps = reinterpret_cast<const uint16_t *>(ws + d.ps_off);
     const uint16_t *Qs = reinterpret_cast<const uint16_t *>(ws + d.qs_off);
 
     // Addresses are a scalar base (the tile's first row, the block in turn) plus a 32-bit lane offset
@@ -692,15 +672,22 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
         octet0[v] = (uint32_t)(row * m8) + (uint32_t)cc;
     }
 
-    // negated splits of this wave's rows of P^
+    // negated splits of this wave's rows of P^ (x = hi + mid + lo in bf16 by truncation, so -x = -hi - mid - lo)
     Frag A[3];
     {
         const int64_t arow = (row0 + cc < d.n) ? row0 + cc : d.n - 1;
+        const float4 *pr = reinterpret_cast<const float4 *>(Phat + d.p_off + arow * 32 + kg * 8);
+        const float4 p0 = pr[0], p1 = pr[1];
+        const float x[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        float hh[8], mm[8], ll[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) split3(x[j], hh[j], mm[j], ll[j]);
+        A[0].u = make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
+        A[1].u = make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
+        A[2].u = make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
-            uint4 a = *reinterpret_cast<const uint4 *>(Ps + ((int64_t)s * d.n + arow) * 32 + kg * 8);
-            a.x ^= 0x80008000u; a.y ^= 0x80008000u; a.z ^= 0x80008000u; a.w ^= 0x80008000u;
-            A[s].u = a;
+            A[s].u.x ^= 0x80008000u; A[s].u.y ^= 0x80008000u; A[s].u.z ^= 0x80008000u; A[s].u.w ^= 0x80008000u;
         }
     }
 
@@ -861,12 +848,6 @@ void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                        codes, scales, Q, P);
 }
 
-void mfma_split_p_hat(const DevicePlan &dp, const float *Phat, double *ws, hipStream_t st)
-{
-    if (dp.n_split_p <= 0) return;
-    hipLaunchKernelGGL(k_split_p_hat, dim3(dp.n_split_p), dim3(256), 0, st, dp, Phat, ws);
-}
-
 void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st)
 {
     if (dp.n_split_p <= 0) return;
@@ -881,12 +862,12 @@ void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                        scales, Phat, ws, Qout);
 }
 
-void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const double *ws,
-                   uint64_t step, hipStream_t st)
+void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                   const double *ws, uint64_t step, hipStream_t st)
 {
     if (dp.n_err_m <= 0) return;
     hipLaunchKernelGGL(k_err_mfma, dim3(dp.n_err_m), dim3(512), 0, st, dp,
-                       reinterpret_cast<const uint16_t *>(grads), codes, scales, ws, (uint32_t)step, (uint32_t)(step >> 32));
+                       reinterpret_cast<const uint16_t *>(grads), codes, scales, Phat, ws, (uint32_t)step, (uint32_t)(step >> 32));
 }
 
 void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st)

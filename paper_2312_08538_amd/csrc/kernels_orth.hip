@@ -1,10 +1,12 @@
 // Orthonormalisation of all left factors of a model: P^ = thin-QR factor of P with positive
 // diagonal of R, by Cholesky-QR in fp64:  G = P^T P,  G = R^T R,  P^ = P R^-1.  In exact arithmetic
-// this is the matrix Gram-Schmidt produces.  Three grouped launches:
+// this is the matrix Gram-Schmidt produces.  Four grouped launches:
 //   k_gram_partial      fp64 Gram matrices of row tiles (4 x 4 register blocks per thread),
-//   k_cholesky_inverse  per matrix: ordered sum of the tiles, then factorisation and inversion of
-//                       the triangle inside one wave (a lane owns a column; rows are broadcast
-//                       with v_readlane, no LDS traffic and no barriers in the O(r^3) part),
+//   k_gram_reduce       the tiles of a matrix added up: 16 interleaved partial sums per entry, each
+//                       in tile order, then those in order,
+//   k_cholesky_inverse  per matrix: factorisation and inversion of the triangle inside one wave (a
+//                       lane owns a column; rows are broadcast with v_readlane, no LDS traffic and
+//                       no barriers in the O(r^3) part),
 //   k_apply_rinv        P^ = P R^-1 on 64-row tiles staged through LDS.
 // All sums run in a fixed order.
 #include "device_common.h"
@@ -100,59 +102,54 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
     }
 }
 
+// ---------------------------------------------------------------- sum of the partial Gram matrices
+// One workgroup per (matrix, 16 entries of the r x r matrix): thread (entry, part) adds the tiles
+// part, part + 16, ... in that order, then the 16 parts are added in order.  (One thread per entry
+// walking all tiles is a chain of dependent memory round trips, hundreds long for a tall matrix.)
+template <int RP>
+__global__ __launch_bounds__(256) void k_gram_reduce(DevicePlan dp, double *ws)
+{
+    constexpr int kSlices = (RP * RP + 15) / 16;
+    __shared__ double red[16][16];
+    const MatDesc d = dp.mats[blockIdx.x / kSlices];
+    const int r = dp.rank, t = threadIdx.x;
+    const int e = (int)(blockIdx.x % kSlices) * 16 + (t & 15), part = t >> 4;
+    const bool live = e < r * r;
+    const int64_t stride = (int64_t)r * r;
+    const double *src = ws + d.gram_off + (live ? e : 0);
+    const int T = d.n_gram_tiles;
+    double s = 0.0;
+    int k = part;
+    for (; k + 48 < T; k += 64) {
+        const double v0 = src[(int64_t)k * stride], v1 = src[(int64_t)(k + 16) * stride];
+        const double v2 = src[(int64_t)(k + 32) * stride], v3 = src[(int64_t)(k + 48) * stride];
+        s = ((s + v0) + v1) + v2;
+        s += v3;
+    }
+    for (; k < T; k += 16) s += src[(int64_t)k * stride];
+    red[part][t & 15] = s;
+    __syncthreads();
+    if (t < 16 && live) {
+        double a = red[0][t];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) a += red[q][t];
+        ws[d.gsum_off + e] = a;
+    }
+}
+
 // ---------------------------------------------------------------- Cholesky factor and its inverse
-// One workgroup per matrix.  All threads add up the partial Gram matrices (tile order) into LDS;
-// then wave 0 factors G = R^T R and inverts R with lane j holding column j in registers.
+// One wave per matrix factors G = R^T R and inverts R with lane j holding column j in registers.
 // A column whose squared norm after projection is not above 1e-12 of its squared norm is linearly
 // dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.
 template <int RP>
-__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws)
+__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws)
 {
     __shared__ double G[RP * RP];
     const MatDesc d = dp.mats[blockIdx.x];
     const int r = dp.rank;
     const int t = threadIdx.x;
-    // Ordered sum of the tiles.  A thread owns up to four entries and keeps their loads of eight
-    // tiles in flight together: with one entry at a time the sum over the tiles of a tall matrix
-    // is a long chain of dependent memory round trips.
-    {
-        constexpr int kE = (RP * RP + 255) / 256;
-        const int64_t stride = (int64_t)r * r;
-        const int T = d.n_gram_tiles;
-        const double *src[kE];
-        bool live[kE];
-        double s[kE];
-#pragma unroll
-        for (int u = 0; u < kE; ++u) {
-            const int e = t + 256 * u;
-            live[u] = e < r * r;
-            src[u] = ws + d.gram_off + (live[u] ? e : 0);
-            s[u] = 0.0;
-        }
-        int k = 0;
-        for (; k + 8 <= T; k += 8) {
-            double v[kE][8];
-#pragma unroll
-            for (int u = 0; u < kE; ++u)
-#pragma unroll
-                for (int q = 0; q < 8; ++q) v[u][q] = src[u][(int64_t)(k + q) * stride];
-#pragma unroll
-            for (int u = 0; u < kE; ++u)
-#pragma unroll
-                for (int q = 0; q < 8; ++q) s[u] += v[u][q];
-        }
-        for (; k < T; ++k) {
-#pragma unroll
-            for (int u = 0; u < kE; ++u) s[u] += src[u][(int64_t)k * stride];
-        }
-#pragma unroll
-        for (int u = 0; u < kE; ++u) {
-            const int e = t + 256 * u;
-            if (live[u]) G[(e / r) * RP + (e % r)] = s[u];
-        }
-    }
+    for (int e = t; e < r * r; e += 64) G[(e / r) * RP + (e % r)] = ws[d.gsum_off + e];
     __syncthreads();
-    if (t >= 64) return;
     const int j = t;                                   // this lane's column (lanes >= r idle along)
     double col[RP];
 #pragma unroll
@@ -224,7 +221,7 @@ __device__ __forceinline__ void apply_columns(const double (&in)[RP], const doub
 }
 
 template <int RP>
-__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws, bool write_splits)
+__global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, const double *ws)
 {
     constexpr int kS = RP + 1;
     __shared__ float tin[64 * kS];
@@ -262,47 +259,33 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     } else {
         for (int e = t; e < rows * r; e += 256) base[e] = tout[(e / r) * kS + (e % r)];
     }
-    if constexpr (RP == 32) {
-        // Matrix-core family: the operand splits of P^ (x = hi + mid + lo, three bf16 values by
-        // truncation) that its err pass reads, written while the tile is at hand: row-major [3][n][32].
-        if (write_splits && d.path == kPathMfma) {          // uniform
-            uint16_t *rm = reinterpret_cast<uint16_t *>(const_cast<double *>(ws) + d.ps_off);
-            for (int e = t; e < rows * 32; e += 256) {
-                const int rr = e >> 5, c = e & 31;
-                const float x = tout[rr * kS + c];
-                const uint32_t xb = __float_as_uint(x);
-                const float r1 = x - __uint_as_float(xb & 0xFFFF0000u);
-                const uint32_t mb = __float_as_uint(r1) & 0xFFFF0000u;
-                const float l = r1 - __uint_as_float(mb);
-                const uint16_t bh = (uint16_t)(xb >> 16), bm = (uint16_t)(mb >> 16), bl = (uint16_t)(__float_as_uint(l) >> 16);
-                const int64_t row = row0 + rr;
-                rm[((int64_t)0 * d.n + row) * 32 + c] = bh;
-                rm[((int64_t)1 * d.n + row) * 32 + c] = bm;
-                rm[((int64_t)2 * d.n + row) * 32 + c] = bl;
-            }
-        }
-    }
 }
 
 }  // namespace
 
-#define CONEF_ORTH_DISPATCH(KERNEL, GRID, ST, ...)                                                \
+#define CONEF_ORTH_DISPATCH(KERNEL, GRID, THREADS, ST, ...)                                       \
     do {                                                                                          \
         switch (dp.rpad) {                                                                        \
-        case 4: hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;        \
-        case 8: hipLaunchKernelGGL(KERNEL<8>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;        \
-        case 16: hipLaunchKernelGGL(KERNEL<16>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
-        default: hipLaunchKernelGGL(KERNEL<32>, GRID, dim3(256), 0, ST, __VA_ARGS__); break;      \
+        case 4: hipLaunchKernelGGL(KERNEL<4>, GRID, dim3(THREADS), 0, ST, __VA_ARGS__); break;    \
+        case 8: hipLaunchKernelGGL(KERNEL<8>, GRID, dim3(THREADS), 0, ST, __VA_ARGS__); break;    \
+        case 16: hipLaunchKernelGGL(KERNEL<16>, GRID, dim3(THREADS), 0, ST, __VA_ARGS__); break;  \
+        default: hipLaunchKernelGGL(KERNEL<32>, GRID, dim3(THREADS), 0, ST, __VA_ARGS__); break;  \
         }                                                                                         \
     } while (0)
 
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, bool write_splits, hipStream_t st, Span span)
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
 {
-    // the span covers all three kernels of this stage
+    // the span covers all kernels of this stage
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), st, dp, (const float *)P, ws);
-    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats), st, dp, ws);
-    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), st, dp, P, (const double *)ws, write_splits && dp.n_split_p > 0);
+    CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), 256, st, dp, (const float *)P, ws);
+    switch (dp.rpad) {
+    case 4: hipLaunchKernelGGL(k_gram_reduce<4>, dim3(dp.n_mats), dim3(256), 0, st, dp, ws); break;
+    case 8: hipLaunchKernelGGL(k_gram_reduce<8>, dim3(dp.n_mats * 4), dim3(256), 0, st, dp, ws); break;
+    case 16: hipLaunchKernelGGL(k_gram_reduce<16>, dim3(dp.n_mats * 16), dim3(256), 0, st, dp, ws); break;
+    default: hipLaunchKernelGGL(k_gram_reduce<32>, dim3(dp.n_mats * 64), dim3(256), 0, st, dp, ws); break;
+    }
+    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats), 64, st, dp, ws);
+    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), 256, st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }

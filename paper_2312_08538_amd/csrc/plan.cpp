@@ -269,13 +269,13 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             else plan.any_generic = true;
             if (d.path == kPathMfma) {
                 d.scT_off = wd; wd += round_up((d.m / 128) * d.n * 4 / 8 + 1, 32);
-                d.ps_off = wd;  wd += round_up(3 * 32 * d.n * 2 / 8, 32);
                 d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
             }
 
             d.gram_tile_rows = d.n > 8192 ? 2 * kGramRows : kGramRows;
             d.n_gram_tiles = (int32_t)ceil_div(d.n, d.gram_tile_rows);
             d.gram_off = wd; wd += (int64_t)d.n_gram_tiles * rank * rank;
+            d.gsum_off = wd; wd += rank * rank;
             d.rinv_off = wd; wd += rank * rank;
             // generic family: short row tiles for small matrices (their workgroups are latency bound,
             // so parallelism has to come from the number of tiles)
@@ -533,13 +533,13 @@ bool check_plan(const Plan &plan)
         if (qred[l] != (direct_q ? 0 : (d.m * plan.rank + 255) / 256)) return false;
         if (pred[l] != (d.n_p_chunks > 1 ? (d.n * plan.rank + 255) / 256 : 0)) return false;
         regions.push_back({d.gram_off, d.gram_off + (int64_t)d.n_gram_tiles * plan.rank * plan.rank});
+        regions.push_back({d.gsum_off, d.gsum_off + (int64_t)plan.rank * plan.rank});
         regions.push_back({d.rinv_off, d.rinv_off + (int64_t)plan.rank * plan.rank});
         regions.push_back({d.qpart_off, d.qpart_off + (int64_t)d.n_q_tiles * d.m * plan.rank});
         if (d.st_slots > 0) regions.push_back({d.st_part_off, d.st_part_off + d.st_slots});
         if (d.n_p_chunks > 1) regions.push_back({d.ppart_off, d.ppart_off + (int64_t)d.n_p_chunks * d.n * plan.rank});
         if (d.path == kPathMfma) {
             regions.push_back({d.scT_off, d.scT_off + ((d.m / 128) * d.n * 4 + 7) / 8});
-            regions.push_back({d.ps_off, d.ps_off + 3 * 32 * d.n * 2 / 8});
             regions.push_back({d.qs_off, d.qs_off + 3 * 32 * d.m * 2 / 8});
         }
     }

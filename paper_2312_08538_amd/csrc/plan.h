@@ -30,6 +30,7 @@ struct MatDesc {
     int64_t grad_off, word_off, scale_off, p_off, q_off;   // element offsets in the flat buffers
     int64_t nblk;                   // number of scale blocks
     int64_t gram_off;               // partial Gram matrices, [n_gram_tiles][r*r]
+    int64_t gsum_off;               // r*r Gram matrix (the partial ones added up in a fixed order)
     int64_t rinv_off;               // r*r inverse triangular factor
     int64_t qpart_off;              // partial sums of Q+, [n_q_tiles][m*r]
     int64_t ppart_off;              // partial sums of P, [n_p_chunks][n*r] (only if n_p_chunks > 1)
@@ -42,9 +43,8 @@ struct MatDesc {
     int32_t lr_shift;               // log2(lanes per row segment), 3..6
     int32_t lb_shift;               // log2(lanes per scale block) = log2(block/8)
     int32_t m8;                     // m / 8
-    // MFMA family: bf16 triple splits of the factors (x = hi + mid + lo), offsets in doubles
+    // MFMA family: workspace offsets in doubles; bf16 triple split of Q+ (x = hi + mid + lo)
     int64_t scT_off;                // block scales, column-block-major: [m / 128][n] fp32
-    int64_t ps_off;                 // P^, row-major:       [3][n][32]
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
     // count-sketch error compressor (row sketch, one table row per bucket)
     int64_t w;                      // table rows (buckets) of this matrix
@@ -102,7 +102,7 @@ struct Plan {
     std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
     std::vector<WorkItem> q_m_items;    // (mat, pair of column blocks of 128, row tile)
     std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
-    std::vector<WorkItem> split_p_items;   // split P^ / transpose the scales: (mat, first row / 64)
+    std::vector<WorkItem> split_p_items;   // transpose the scales: (mat, first row / 64)
     std::vector<WorkItem> split_qn_items;  // split Q+ (row-major):         (mat, first k / 64)
     // shared
     std::vector<WorkItem> pred_items;   // reduce partial P: (mat, first entry of n*r)
