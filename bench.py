@@ -81,21 +81,36 @@ def run_gpu(w, steps: int, warmup: int):
     for t in range(warmup):
         maybe_reset(t)
         one_step(t)
+    # The timed region: exactly `steps` steps, bracketed by synchronisation; one event pair per step on the
+    # launch stream (torch's current stream, the one the library is given) for the median and the minimum.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
-    B.conef_set_timing(model.ctx, True)
     t0 = time.perf_counter()
-    for t in range(warmup, warmup + steps):
+    for i, t in enumerate(range(warmup, warmup + steps)):
+        maybe_reset(t)
+        ev[i][0].record()
+        one_step(t)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    stats = {"median_ms": round(per_step[len(per_step) // 2] if len(per_step) % 2 else
+                                0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2]), 4),
+             "min_ms": round(per_step[0], 4), "max_ms": round(per_step[-1], 4)}
+    # Stage durations: the same steps again with the library's stage events on (the events sit between the
+    # kernels of a step, so these steps are kept out of the timed region above).
+    B.conef_set_timing(model.ctx, True)
+    for t in range(warmup + steps, warmup + 2 * steps):
         maybe_reset(t)
         one_step(t)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     stage_ms = B.conef_get_timing(model.ctx)
     B.conef_set_timing(model.ctx, False)
     finite = bool(torch.isfinite(buf["P"]).all()) and bool(torch.isfinite(buf["Q"]).all())
     model.close()
     del buf, gsets
     torch.cuda.empty_cache()
-    return (t1 - t0) * 1e3 / steps, dict(zip(STAGES, stage_ms)), finite
+    return (t1 - t0) * 1e3 / steps, dict(zip(STAGES, stage_ms)), finite, stats
 
 
 def run_update(w, reps: int = 10):
@@ -606,7 +621,7 @@ def main():
                           "config": {"workload": w.name, "rank": w.rank, "keep": 0.2, "beta": 0.9, "table": "f16"},
                           **r}), flush=True)
         return
-    ms, stage_ms, finite = run_gpu(w, a.steps, a.warmup)
+    ms, stage_ms, finite, stats = run_gpu(w, a.steps, a.warmup)
     if not finite:
         print("bench.py: non-finite factors after the timed run", file=sys.stderr)
         sys.exit(1)
@@ -617,7 +632,7 @@ def main():
     out = {
         "metric": "ConEF step throughput: gradient GB/s processed",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms, 4), "step_ms": stats, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.grad_dtype == 0 else "bf16->f32",
         "data": "synthetic",
         "config": {"workload": w.name, "matrices": len(w.layout), "elements": w.elements,
@@ -639,10 +654,10 @@ def main():
             if name == w.name:
                 continue
             ww = wl.WORKLOADS[name]
-            ms2, st2, _ = run_gpu(ww, 10, 3)
+            ms2, st2, _, stats2 = run_gpu(ww, 10, 3)
             extra[name] = {"ms_per_step": round(ms2, 4), "grad_GB/s": round(ww.grad_bytes / (ms2 * 1e-3) / 1e9, 2),
                            "model_hbm_frac": round(ww.model_bytes() / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                           "stage_ms": {k: round(v, 4) for k, v in st2.items()}}
+                           "step_ms": stats2, "stage_ms": {k: round(v, 4) for k, v in st2.items()}}
         out["other_workloads"] = extra
         # the count sketch as the error compressor (fp16 table with a fifth of the rows: 90 % of an fp32 error
         # vector saved, beta = 0.9, the setting of Section 5.2), beside the step, not inside `value`

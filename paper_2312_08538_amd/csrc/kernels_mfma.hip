@@ -5,7 +5,7 @@
 //   - a factor entry x (fp32) is written as hi + mid + lo, three bf16 values obtained by
 //     truncation (each remainder is exact), so hi + mid + lo == x to 24 bits;
 //   - in the P pass the other operand is exact in bf16 by construction: the gradient is bf16,
-//     and the 4-bit codes are small integers; the block step size d multiplies the code part
+//     and the 4-bit codes are small integers (fed as sixteenths, with 16 d); the block step size d multiplies the code part
 //     once per 128-column block, on the accumulators:
 //         P[i,c] = sum_k g[i,k] Q[k,c] + sum_blocks d[i,blk] * sum_{k in blk} q[i,k] Q[k,c]
 //     All products are exact; sums are fp32 inside the matrix core.
@@ -67,6 +67,29 @@ __device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
     lo.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
     hi.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * pitch));
     return make_uint4(lo.u.x, lo.u.y, hi.u.x, hi.u.y);
+}
+
+// signed 4-bit field in the low nibble of byte `byte` of w, divided by 16 (exact), as fp32: the
+// conversion instruction reads the nibble through its byte selector, so no shift or mask is spent
+template <int byte>
+__device__ __forceinline__ float nibble_over_16(uint32_t w)
+{
+    float r;
+    if constexpr (byte == 0) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
+    else if constexpr (byte == 1) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(r) : "v"(w));
+    else if constexpr (byte == 2) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
+    else asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
+    return r;
+}
+
+// the eight fields of a code word, each divided by 16
+__device__ __forceinline__ void fields_over_16(uint32_t w, float q[8])
+{
+    const uint32_t w4 = w >> 4;
+    q[0] = nibble_over_16<0>(w); q[1] = nibble_over_16<0>(w4);
+    q[2] = nibble_over_16<1>(w); q[3] = nibble_over_16<1>(w4);
+    q[4] = nibble_over_16<2>(w); q[5] = nibble_over_16<2>(w4);
+    q[6] = nibble_over_16<3>(w); q[7] = nibble_over_16<3>(w4);
 }
 
 // ------------------------------------------------------------------ P pass
@@ -212,14 +235,10 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             Frag bg, bq, a0, a1, a2;
             bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
             const uint32_t w = sc[my_row_in_tile * kCStride + ((k0 & (kCodeGroup - 1)) >> 3) + ks * 2 + kg];
-            uint32_t qb[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float lo = (float)code_field(w, 2 * e2, 4);
-                const float hi = (float)code_field(w, 2 * e2 + 1, 4);
-                qb[e2] = pack_hi16(lo, hi);          // small integers: exact in bf16
-            }
-            bq.u = make_uint4(qb[0], qb[1], qb[2], qb[3]);
+            float q16[8];
+            fields_over_16(w, q16);                  // sixteenths of small integers: exact in bf16
+            bq.u = make_uint4(pack_hi16(q16[0], q16[1]), pack_hi16(q16[2], q16[3]), pack_hi16(q16[4], q16[5]),
+                              pack_hi16(q16[6], q16[7]));
             a0.u = lds_read_tr16x8(sq + 0 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a1.u = lds_read_tr16x8(sq + 1 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a2.u = lds_read_tr16x8(sq + 2 * kStage * 32 + tr_a + ks * 16 * 32, 32);
@@ -233,7 +252,8 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         if (((k0 + kStage) & 127) == 0) {
             // end of a scale block: fold the code part in with this row's step size
             const float blk_scale = ss[my_row_in_tile * kSStride + ((k0 >> 7) & 31)];
-            const float dstep = (my_row < d.n) ? blk_scale * inv_levels(4) * dp.omb : 0.0f;      // omb: 1 - beta (Algorithm 4 line 5)
+            // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
+            const float dstep = (my_row < d.n) ? (blk_scale * inv_levels(4) * dp.omb) * 16.0f : 0.0f;
             const double dd = (double)dstep;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -442,18 +462,17 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
+            float q16[8];
+            fields_over_16(cs[s], q16);                  // sixteenths of small integers: exact in bf16
             u32x4 qb;
 #pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float lo = (float)code_field(cs[s], 2 * e2, 4);
-                const float hi = (float)code_field(cs[s], 2 * e2 + 1, 4);
-                qb[e2] = pack_hi16(lo, hi);              // small integers: exact in bf16
-            }
+            for (int e2 = 0; e2 < 4; ++e2) qb[e2] = pack_hi16(q16[2 * e2], q16[2 * e2 + 1]);
             *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
         if (with_p) store_split(sb + frow * 32 + fcg * 8, pv);
-        const float dstep = row_ok ? r.sc * inv_levels(4) * dp.omb : 0.0f;        // omb: 1 - beta (Algorithm 4 line 5)
+        // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
+        const float dstep = row_ok ? (r.sc * inv_levels(4) * dp.omb) * 16.0f : 0.0f;
         float dp8[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) dp8[j] = dstep * pv[j];
@@ -607,29 +626,6 @@ __device__ __forceinline__ uint32_t dpp_quad_xor2(uint32_t a) { return __builtin
 __device__ __forceinline__ uint32_t dpp_row_ror4(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x124, 0xF, 0xF, true); }
 __device__ __forceinline__ uint32_t dpp_row_ror8(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x128, 0xF, 0xF, true); }
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
-
-// signed 4-bit field in the low nibble of byte `byte` of w, divided by 16 (exact), as fp32: the
-// conversion instruction reads the nibble through its byte selector, so no shift or mask is spent
-template <int byte>
-__device__ __forceinline__ float nibble_over_16(uint32_t w)
-{
-    float r;
-    if constexpr (byte == 0) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
-    else if constexpr (byte == 1) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(r) : "v"(w));
-    else if constexpr (byte == 2) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
-    else asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
-    return r;
-}
-
-// the eight fields of a code word, each divided by 16
-__device__ __forceinline__ void fields_over_16(uint32_t w, float q[8])
-{
-    const uint32_t w4 = w >> 4;
-    q[0] = nibble_over_16<0>(w); q[1] = nibble_over_16<0>(w4);
-    q[2] = nibble_over_16<1>(w); q[3] = nibble_over_16<1>(w4);
-    q[4] = nibble_over_16<2>(w); q[5] = nibble_over_16<2>(w4);
-    q[6] = nibble_over_16<3>(w); q[7] = nibble_over_16<3>(w4);
-}
 
 __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const float *__restrict__ Phat, const double *ws,
