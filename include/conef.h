@@ -44,7 +44,7 @@ typedef struct conef_ctx conef_ctx;                 /* opaque; host memory owned
 typedef struct { int64_t rows, cols; } conef_mat;   /* one layout entry */
 
 enum { CONEF_F32 = 0, CONEF_BF16 = 1 };             /* gradient element type; P, Q, scales are fp32 */
-enum { CONEF_OK = 0, CONEF_EINVAL = -1, CONEF_ENOMEM = -2, CONEF_EHIP = -3, CONEF_ESTATE = -4 };
+enum { CONEF_OK = 0, CONEF_EINVAL = -1, CONEF_ENOMEM = -2, CONEF_EHIP = -3, CONEF_ESTATE = -4, CONEF_ETOOBIG = -5 };
 
 /* Plans a model.  Host only: no device is touched until the first call that launches.
  *   layout[n_mats]  matrices in model order (each rows, cols >= 1, rows*cols < 2^35)
@@ -88,6 +88,25 @@ int conef_offsets(const conef_ctx *ctx, int mat, size_t *grad_off, size_t *word_
 int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
                const float *Q_state, float *P_out, float *Q_out, void *workspace,
                uint64_t step, void *hip_stream);
+
+/* conef_step for callers that cannot allocate device memory or be handed a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace of the step (partial Gram
+ * matrices, partial sums of Q+, operand copies: everything conef_sizes() counts in workspace_bytes) is a
+ * static device array of CONEF_STATIC_WORKSPACE_BYTES inside the library, one copy per GPU, held until the
+ * process ends; its address on the current device is looked up on the first call there.  The call itself
+ * allocates nothing, frees nothing and does not synchronise; inputs and outputs are the caller's, as in
+ * conef_step, and so are the results (same kernels, same order: bit-identical).
+ *   - The context's work tables must already be on the device: any earlier call on the context that enqueues
+ *     work (conef_reset_error, a step, a stage) uploads them; CONEF_ESTATE otherwise, and on a count-sketch
+ *     context, and if the current device is not the one the tables were uploaded to.
+ *   - CONEF_ETOOBIG if the model's workspace_bytes exceed CONEF_STATIC_WORKSPACE_BYTES (host-only check).
+ *   - Every call on a GPU shares that GPU's array, which keeps the last call's contents; nothing in it has to
+ *     start at zero (every region is written before it is read within a step).  Calls that overlap in time on
+ *     one GPU (two streams, two contexts, two threads) race on it: run them one after the other.
+ * Errors otherwise as conef_step. */
+#define CONEF_STATIC_WORKSPACE_BYTES (32u << 20)
+int conef_step_static(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+                      const float *Q_state, float *P_out, float *Q_out, uint64_t step, void *hip_stream);
 
 /* The same step in its four stages, for callers that all-reduce P and Q between them
  * (the two exchange points of an all-reducable compressor, Section 2 "How gradients are

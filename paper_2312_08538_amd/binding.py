@@ -14,9 +14,10 @@ LIB_PATH = os.path.join(_HERE, "libconef.so")
 
 F32, BF16 = 0, 1
 TABLE_F32, TABLE_F16 = 0, 1
-OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4
+OK, EINVAL, ENOMEM, EHIP, ESTATE, ETOOBIG = 0, -1, -2, -3, -4, -5
+STATIC_WORKSPACE_BYTES = 32 << 20
 
-EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_p",
+EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_static", "conef_step_p",
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
            "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
            "conef_apply_update", "conef_destroy",
@@ -51,6 +52,7 @@ def lib() -> ctypes.CDLL:
     L.conef_sizes.argtypes = [vp, szp, szp, szp, szp, szp, szp]
     L.conef_offsets.argtypes = [vp, i32, szp, szp, szp, szp, szp]
     L.conef_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_step_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.conef_orthonormalise.argtypes = [vp, vp, vp, vp]
     L.conef_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
@@ -291,6 +293,11 @@ def conef_offsets(ctx, mat: int) -> dict:
 def conef_step(ctx, grads, err_codes, err_scales, Q_state, P_out, Q_out, workspace, step: int, stream=0):
     _check(lib().conef_step(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(Q_state), _ptr(P_out),
                             _ptr(Q_out), _ptr(workspace), step, stream), "conef_step")
+
+
+def conef_step_static(ctx, grads, err_codes, err_scales, Q_state, P_out, Q_out, step: int, stream=0):
+    _check(lib().conef_step_static(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(Q_state), _ptr(P_out),
+                                   _ptr(Q_out), step, stream), "conef_step_static")
 
 
 def conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_raw_out, workspace, stream=0):

@@ -5,6 +5,7 @@
 #include <climits>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -350,6 +351,50 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     /* exchange point 2: mean of Q over the workers -- identity for one worker; the operand splits
        of P^ and Q+ made by the Q+ stage are therefore still valid for the err stage */
     return step_err_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, step, hip_stream, true);
+}
+
+// ---------------------------------------------------------------- the step without allocation or workspace argument
+}  // extern "C"
+
+// The workspace of conef_step_static: one copy per GPU, part of the loaded code object.  In host code this name
+// is a stand-in, not a device address; the address on a device comes from hipGetSymbolAddress (below).
+static __device__ __align__(256) unsigned char scratch[CONEF_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (which must be `device`), looked up once per device.
+int static_scratch(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return CONEF_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CONEF_EHIP;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return CONEF_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int conef_step_static(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales,
+                      const float *Q_state, float *P_out, float *Q_out, uint64_t step, void *hip_stream)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (ctx->plan.workspace_bytes > (size_t)CONEF_STATIC_WORKSPACE_BYTES) return CONEF_ETOOBIG;
+    if (ctx->plan.sketch || !ctx->uploaded) return CONEF_ESTATE;      // the upload allocates: it is not done here
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return CONEF_EHIP;
+    if (device != ctx->device) return CONEF_ESTATE;
+    void *ws = nullptr;
+    int rc = static_scratch(device, &ws);
+    if (rc) return rc;
+    return conef_step(ctx, grads, err_codes, err_scales, Q_state, P_out, Q_out, ws, step, hip_stream);
 }
 
 // ---------------------------------------------------------------- iConEF version 1 around the rank-r compressor
@@ -826,6 +871,7 @@ const char *conef_strerror(int code)
     case CONEF_ENOMEM: return "out of host memory";
     case CONEF_EHIP: return "a HIP runtime call failed";
     case CONEF_ESTATE: return "call not valid in the current state";
+    case CONEF_ETOOBIG: return "the model's workspace exceeds the static workspace of conef_step_static";
     default: return "unknown error code";
     }
 }

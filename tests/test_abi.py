@@ -127,6 +127,23 @@ def test_work_tables_cover_every_matrix_exactly_once(case):
         B.conef_destroy(ctx)
 
 
+def test_static_workspace_step_checks_the_size_on_the_host():
+    """conef_step_static refuses a model whose workspace exceeds the library's static array before it looks at
+    a pointer or at the device (so the check runs without a GPU), and a context with nothing uploaded yet."""
+    w = wl.WORKLOADS["large"]
+    big = B.conef_init(list(w.layout), w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
+    assert B.conef_sizes(big)["workspace_bytes"] > B.STATIC_WORKSPACE_BYTES
+    fake = ctypes.c_void_p(0x1000)
+    assert B.lib().conef_step_static(big, fake, fake, fake, fake, fake, fake, 0, None) == B.ETOOBIG
+    B.conef_destroy(big)
+    small = B.conef_init([(64, 64)], 4, 4, 64, B.F32, 0)
+    assert B.conef_sizes(small)["workspace_bytes"] <= B.STATIC_WORKSPACE_BYTES
+    assert B.lib().conef_step_static(small, fake, fake, fake, fake, fake, fake, 0, None) == B.ESTATE
+    assert B.lib().conef_step_static(None, fake, fake, fake, fake, fake, fake, 0, None) == B.EINVAL
+    assert b"static workspace" in B.lib().conef_strerror(B.ETOOBIG)
+    B.conef_destroy(small)
+
+
 def test_full_workloads_plan_consistently():
     for w in wl.WORKLOADS.values():
         ctx = B.conef_init(list(w.layout), w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
