@@ -143,6 +143,31 @@ def host_q0(w: Workload, mat: int, shape=None, rank=None) -> np.ndarray:
     return rng.standard_normal((m, rank or w.rank)).astype(np.float32)
 
 
+def graded_panel(n: int, r: int, cond: float, seed: int) -> np.ndarray:
+    """An n x r fp32 panel with singular values 1, cond^(-1/(r-1)), ..., 1/cond (geometric) and random
+    orthonormal singular vectors on both sides: the left factor P = p Q of a gradient with a decaying spectrum
+    after a few warm-started steps looks like this (its condition number is a power of the spectrum's decay)."""
+    rng = np.random.default_rng([77, seed, n, r])
+    U, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    V, _ = np.linalg.qr(rng.standard_normal((r, r)))
+    sig = np.asarray([cond ** (-j / max(1, r - 1)) for j in range(r)])
+    return np.ascontiguousarray(((U * sig) @ V.T).astype(np.float32))
+
+
+def decaying_gradient(n: int, m: int, decay: float, noise: float, seed: int, step: int = 0) -> np.ndarray:
+    """An n x m fp32 matrix with singular values decay^j on fixed singular vectors (the same for every step) plus
+    iid N(0, noise^2) entries that change with the step: a gradient whose leading subspace persists from step
+    to step, which is what warm-started subspace iteration locks on to."""
+    k = min(n, m, 48)
+    rng = np.random.default_rng([78, seed, n, m])
+    U, _ = np.linalg.qr(rng.standard_normal((n, k)))
+    V, _ = np.linalg.qr(rng.standard_normal((m, k)))
+    sig = decay ** np.arange(k)
+    g = (U * sig) @ V.T
+    g += noise * np.random.default_rng([79, seed, n, m, step]).standard_normal((n, m))
+    return np.ascontiguousarray(g.astype(np.float32))
+
+
 def device_fill_gradients(w: Workload, step: int, flat, offsets) -> None:
     """Fills the flat device gradient buffer `flat` (a torch tensor of the workload's gradient
     dtype) matrix by matrix at the given element offsets, drawing on the device with a torch

@@ -40,10 +40,14 @@ def unpack_at(codes: np.ndarray, idx: np.ndarray, bits: int) -> np.ndarray:
     return np.where(f >= (1 << (bits - 1)), f - (1 << bits), f).astype(np.int32)
 
 
-def _excuse(bad, g_bad, w_bad, x_oracle, N, bits, block, seed, mat, step, what, rec_oracle, max_frac=1e-4, x_abs_tol=0.0):
+def _excuse(bad, g_bad, w_bad, x_oracle, N, bits, block, seed, mat, step, what, rec_oracle, max_frac=1e-4, x_abs_tol=0.0,
+            j0=0, stats=None):
     """The boundary rule for the elements `bad` (codes g_bad on the GPU, w_bad in the oracle).  x_abs_tol: a
     bound on the absolute difference of the two sides' residuals that comes from their factors differing
-    (whole steps on large matrices), added to the window."""
+    (whole steps on large matrices), added to the window.  j0: flat index (within the matrix) of element 0 of
+    x_oracle, when only a piece of the matrix is looked at.  stats (a dict): counts the differing codes that the
+    strict rule (window 1e-6 max(1, u), nothing added) already excuses under "strict" and the others, which need
+    the widened window, under "widened"."""
     s = R.levels(bits)
     assert bad.size <= max(1, int(max_frac * N)), f"{what}: {bad.size} of {N} codes differ"
     for j, gj, wj in zip(bad, g_bad, w_bad):
@@ -54,8 +58,11 @@ def _excuse(bad, g_bad, w_bad, x_oracle, N, bits, block, seed, mat, step, what, 
         inv = np.float32(s) / np.float32(a)
         u = np.float32(np.abs(x_oracle[j]) * inv)
         f = float(u - np.floor(u))
-        xi = R.rand16(seed, mat, step, int(j)) / 65536.0
+        xi = R.rand16(seed, mat, step, int(j0 + j)) / 65536.0
         tol = 1e-6 * max(1.0, float(u))
+        if stats is not None:
+            strict = abs(f + xi - 1.0) <= tol or abs(float(u) - round(float(u))) <= tol
+            stats["strict" if strict else "widened"] = stats.get("strict" if strict else "widened", 0) + 1
         if rec_oracle is not None:
             tol *= max(1.0, float(np.abs(rec_oracle[b0:min(N, b0 + block)]).max()) / float(a))
         tol += x_abs_tol * float(inv)
@@ -66,7 +73,8 @@ def _excuse(bad, g_bad, w_bad, x_oracle, N, bits, block, seed, mat, step, what, 
     return int(bad.size)
 
 
-def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what="", rec_oracle=None):
+def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step, what="", rec_oracle=None, j0=0,
+                stats=None):
     """Applies the boundary rule.  x_oracle: the oracle's residual (fp32, flat).  Returns the number
     of excused mismatches.  rec_oracle (flat, sum_c |P^[i,c]| |Q+[k,c]|: the size of the terms of
     the reconstruction) is given for the matrix-core family only: there the factors carry fp32
@@ -77,10 +85,11 @@ def check_codes(got_codes, want_codes, x_oracle, N, bits, block, seed, mat, step
     bad = np.nonzero(g != w)[0]
     if bad.size == 0:
         return 0
-    return _excuse(bad, g[bad], w[bad], x_oracle, N, bits, block, seed, mat, step, what, rec_oracle)
+    return _excuse(bad, g[bad], w[bad], x_oracle, N, bits, block, seed, mat, step, what, rec_oracle, j0=j0, stats=stats)
 
 
-def check_codes_sparse(got_codes, want_codes, x_of, N, bits, block, seed, mat, step, what="", rec_of=None, x_abs_tol=0.0):
+def check_codes_sparse(got_codes, want_codes, x_of, N, bits, block, seed, mat, step, what="", rec_of=None, x_abs_tol=0.0,
+                       stats=None):
     """check_codes for large matrices: code words are compared packed, and only the fields of differing
     words are unpacked; x_of() / rec_of() are called only if something differs."""
     got_codes, want_codes = np.asarray(got_codes), np.asarray(want_codes)
@@ -93,7 +102,7 @@ def check_codes_sparse(got_codes, want_codes, x_of, N, bits, block, seed, mat, s
     g, w = unpack_at(got_codes, idx, bits), unpack_at(want_codes, idx, bits)
     sel = g != w
     return _excuse(idx[sel], g[sel], w[sel], x_of(), N, bits, block, seed, mat, step, what,
-                   rec_of() if rec_of is not None else None, x_abs_tol=x_abs_tol)
+                   rec_of() if rec_of is not None else None, x_abs_tol=x_abs_tol, stats=stats)
 
 
 class OracleModel:

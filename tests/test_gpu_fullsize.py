@@ -111,10 +111,11 @@ def test_large_quantiser_step_on_sampled_outputs(env):
             rec = (np.abs(Ph[i:i + 1]).astype(np.float64) @ np.abs(Qn).astype(np.float64).T).ravel()
             blk_rec = rec.reshape(-1, block).max(1)
             assert np.all(np.abs(s_got - s_want) <= 1e-6 * np.maximum(s_want, blk_rec) + 1e-30), f"mat {l} row {i}: scales"
-            qg, qw = U.unpack(c_got, m, bits), U.unpack(c_want, m, bits)
-            bad = np.nonzero(qg != qw)[0]
-            assert bad.size <= max(2, int(2e-3 * m)), f"mat {l} row {i}: {bad.size} of {m} codes differ"
-            assert np.all(np.abs(qg[bad] - qw[bad]) == 1), f"mat {l} row {i}: a code differs by more than one level"
+            # every differing code excused one by one by the boundary rule (at most 1e-4 of the row, i.e. one code;
+            # the factors are the library's own on both sides, so nothing is added for them)
+            sampled_stats = {}
+            U.check_codes(c_got, c_want, x.ravel(), m, bits, block, w.lib_seed, l, 1, f"mat {l} row {i}",
+                          rec_oracle=rec.astype(np.float32), j0=i * m, stats=sampled_stats)
         # sampled rows of Q+ (columns of p)
         for k in _rows(rng, m, COLS_PER_MAT):
             gk = wl.bf16_bits_to_f32(_grad_col(torch, buf["grads"], o["grad_off"], n, m, k))
@@ -233,6 +234,9 @@ def test_whole_model_second_step_against_the_oracle(env, name):
     codes1, scales1 = buf["codes"].cpu().numpy().view(np.uint32), buf["scales"].cpu().numpy()
     P1, Q1 = buf["P"].cpu().numpy(), buf["Q"].cpu().numpy()
     excused = 0
+    # how far the criteria as stated (scales within 1e-6 of the scale itself; a differing code within 1e-6 max(1, u)
+    # of a boundary) are from holding without the allowances below
+    strict = {"blocks": 0, "scale_misses": 0, "worst_scale_rel": 0.0, "codes": {}}
     for l, (n, m) in enumerate(w.layout):
         o = model.offsets[l]
         N = n * m
@@ -260,18 +264,35 @@ def test_whole_model_second_step_against_the_oracle(env, name):
 
         gs = scales1[o["scale_off"]:o["scale_off"] + nb]
         dev = np.abs(gs - st.scales)
+        strict["blocks"] += nb
+        rel = dev / np.maximum(st.scales, np.float32(1e-30))
+        strict["scale_misses"] += int((rel > 1e-6).sum())
+        strict["worst_scale_rel"] = max(strict["worst_scale_rel"], float(rel.max()))
         if dev.max() > 0:
             rec = rec_of()
             blk_rec = np.concatenate([rec, np.zeros((-N) % block, np.float32)]).reshape(-1, block).max(1)
             worst = float((dev / (1e-6 * np.maximum(st.scales, blk_rec) + x_tol)).max())
             assert worst <= 1.0, f"{tag}: scales off by {worst} times the tolerance"
         ex = U.check_codes_sparse(codes1[o["word_off"]:o["word_off"] + nw], st.codes, x_of, N, bits, block,
-                                  w.lib_seed, l, 1, tag, rec_of=rec_of, x_abs_tol=x_tol)
+                                  w.lib_seed, l, 1, tag, rec_of=rec_of, x_abs_tol=x_tol, stats=strict["codes"])
         excused += ex
         if l < 6 or ex:
             print(f"[fullsize whole model] {tag}: eP {eP:.1e} eQ {eQ:.1e} max scale deviation {dev.max():.2e} "
                   f"(x_tol {x_tol:.1e}), {ex} codes differ", flush=True)
     print(f"[fullsize whole model] {name}: {excused} codes of {w.elements} excused as boundary cases", flush=True)
+    n_strict, n_wide = strict["codes"].get("strict", 0), strict["codes"].get("widened", 0)
+    print(f"[fullsize whole model] {name}: against the criteria as stated: {strict['scale_misses']} of {strict['blocks']} scales "
+          f"off by more than 1e-6 of the scale (worst {strict['worst_scale_rel']:.2e}); of the {excused} differing codes "
+          f"{n_strict} lie within 1e-6 max(1, u) of a boundary, {n_wide} need the widened window", flush=True)
+    assert n_strict + n_wide == excused
+    # The allowances are bounded quantities, not open windows.  Measured on `large` (bf16 matrix cores): all 271
+    # differing codes of 1.31e9 lie inside the window as stated, none needs the widened one; 97 of 10.2e6 scales
+    # (1e-5 of them) miss 1e-6 relative to the scale itself, the worst by a factor 8.  The other families meet
+    # the criteria as stated, exactly.
+    assert strict["scale_misses"] <= 1e-4 * strict["blocks"] and strict["worst_scale_rel"] <= 2e-5
+    assert n_wide <= 1e-7 * w.elements
+    if name != "large":
+        assert strict["scale_misses"] == 0 and n_wide == 0
     model.close()
 
 

@@ -240,6 +240,180 @@ def test_zero_gradient_and_dependent_columns(env):
     assert np.max(np.abs(G[np.ix_(live, live)] - np.eye(live.sum()))) <= 1e-5
 
 
+@pytest.mark.parametrize("cond", [1e2, 1e4, 1e5])
+@pytest.mark.parametrize("name,rank", [("lm", 4), ("translation", 8), ("large", 32)])
+def test_orthonormalise_ill_conditioned_panels(env, name, rank, cond):
+    """The orthonormalisation stage on panels with graded singular values (condition 1e2, 1e4, 1e5: what the left
+    factor of a gradient with a decaying spectrum looks like after warm-started steps), for the three padded
+    ranks of the kernels, on panels that span one Gram tile, several, and a ragged last one: orthonormal to 1e-5
+    and within 1e-4 of the oracle's twice-projected Gram-Schmidt.  (The Gram matrix, the Cholesky factor and the
+    triangular solve are fp64: the loss of orthogonality is cond^2 2^-53, 1e-6 at 1e5.)"""
+    R, B, U = env
+    import torch
+
+    w = wl.WORKLOADS[name]
+    layout = [(300, 256), (1000, 128), (5000, 128), (64, 256)]
+    model = B.Model(layout, rank, w.bits, w.block, w.grad_dtype, 3)
+    buf = model.alloc()
+    panels = [wl.graded_panel(n, rank, cond, l) for l, (n, _) in enumerate(layout)]
+    for l, P in enumerate(panels):
+        o = model.offsets[l]["p_off"]
+        buf["P"][o:o + P.size] = torch.from_numpy(P.ravel()).cuda()
+    B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"], model.stream_handle())
+    torch.cuda.synchronize()
+    for l, (P, (n, _)) in enumerate(zip(panels, layout)):
+        o = model.offsets[l]["p_off"]
+        got = buf["P"][o:o + n * rank].cpu().numpy().reshape(n, rank)
+        want = R.orthonormalise(P)
+        assert np.all(np.isfinite(got))
+        G = got.astype(np.float64).T @ got.astype(np.float64)
+        orth = float(np.abs(G - np.eye(rank)).max())
+        err = U.rel_err(got, want)
+        print(f"[orth cond {cond:.0e} rank {rank}] panel {n} x {rank}: |P^T P - I| {orth:.1e}, against the oracle {err:.1e}", flush=True)
+        assert orth <= 1e-5, (name, n, cond, orth)
+        assert err <= 1e-4, (name, n, cond, err)
+    model.close()
+
+
+@pytest.mark.parametrize("name,layout", [("translation", [(512, 1024), (256, 512)]), ("lm", [(384, 768), (768, 256)])])
+def test_warm_started_steps_on_a_decaying_spectrum(env, name, layout):
+    """Four free-running steps on gradients whose leading singular values decay geometrically (factor 0.5 per
+    index) over a persistent subspace plus small noise: after the first step the warm-started Q is aligned with
+    that subspace and P = p Q has a condition number of several thousand, the case the orthonormalisation has to
+    survive.  The octet family accumulates the factors in fp64: factors within the stated tolerances of the
+    oracle's at every step, P^ orthonormal."""
+    R, B, U = env
+    w = wl.WORKLOADS[name]
+    Q0s = [wl.host_q0(w, l, shape=layout[l]) for l in range(len(layout))]
+    gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+    ora = U.OracleModel(layout, w.rank, w.bits, w.block, w.lib_seed, Q0s)
+    worst_cond = 0.0
+    for t in range(4):
+        grads = []
+        for l, (n, m) in enumerate(layout):
+            g = 1e-3 * wl.decaying_gradient(n, m, 0.5, 1e-5, l, t)
+            grads.append(wl.f32_to_bf16_bits(g) if w.grad_dtype == wl.BF16 else g)
+        gpu.set_grads(grads)
+        gpu.step(t)
+        for l, st in enumerate(ora.states):             # condition of the panel the oracle orthonormalises at this step
+            p = R.form_p(grads[l].reshape(st.n, st.m), st.codes, st.scales, w.bits, w.block)
+            sv = np.linalg.svd(R.lowrank_P(p, st.Q).astype(np.float64), compute_uv=False)
+            worst_cond = max(worst_cond, float(sv[0] / sv[-1]))
+        out = ora.step(grads, t)
+        for l, (Ph, Qn, x) in enumerate(out):
+            eP, eQ = U.rel_err(gpu.mat_P(l), Ph), U.rel_err(gpu.mat_Q(l), Qn)
+            G = gpu.mat_P(l).astype(np.float64).T @ gpu.mat_P(l).astype(np.float64)
+            print(f"[decaying spectrum {name}] step {t} mat {l}: eP {eP:.1e} eQ {eQ:.1e} |G - I| {np.abs(G - np.eye(w.rank)).max():.1e}", flush=True)
+            assert eP <= PQ_TOL[w.grad_dtype] and eQ <= PQ_TOL[w.grad_dtype], (name, t, l, eP, eQ)
+            assert np.abs(G - np.eye(w.rank)).max() <= 1e-5
+        for l, st in enumerate(ora.states):             # the next step starts from the oracle's state on both sides
+            gpu.set_state(l, st.codes, st.scales)
+            gpu.set_Q(l, st.Q)
+    print(f"[decaying spectrum {name}] largest condition number of a panel P: {worst_cond:.1e}", flush=True)
+    assert worst_cond >= 1e2
+    gpu.m.close()
+
+
+def _free_running(env, layout, grads_of, what, codes_at_step_0=True):
+    """Ten steps of the bf16 matrix-core family left to itself (error and Q carried over on each side, nothing
+    reset).  Returns per step the largest factor error over the matrices and whether any code differs."""
+    R, B, U = env
+    w = wl.WORKLOADS["large"]
+    Q0s = [wl.host_q0(w, l, shape=layout[l]) for l in range(len(layout))]
+    gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+    ora = U.OracleModel(layout, w.rank, w.bits, w.block, w.lib_seed, Q0s)
+    errs, differ, deltas = [], [], []
+    for t in range(10):
+        grads = [grads_of(t, l) for l in range(len(layout))]
+        gpu.set_grads(grads)
+        gpu.step(t)
+        out = ora.step(grads, t)
+        if t == 0 and codes_at_step_0:
+            U.compare_step(gpu, out, ora, t, PQ_TOL[w.grad_dtype], what, fp32_factors=True)
+        e = max(max(U.rel_err(gpu.mat_P(l), Ph), U.rel_err(gpu.mat_Q(l), Qn)) for l, (Ph, Qn, x) in enumerate(out))
+        d = any(not np.array_equal(gpu.mat_codes(l), ora.states[l].codes) for l in range(len(layout)))
+        # the compressed gradient itself, Delta = P^ Q+^T (what a worker sends), relative to its own size
+        dd = 0.0
+        for l, (Ph, Qn, x) in enumerate(out):
+            want = Ph.astype(np.float64) @ Qn.astype(np.float64).T
+            got = gpu.mat_P(l).astype(np.float64) @ gpu.mat_Q(l).astype(np.float64).T
+            dd = max(dd, float(np.linalg.norm(got - want) / np.linalg.norm(want)))
+        print(f"[{what}] step {t}: factor error {e:.1e}, Delta error {dd:.1e}, codes {'differ' if d else 'equal'}", flush=True)
+        errs.append(e)
+        differ.append(d)
+        deltas.append(dd)
+    gpu.m.close()
+    return errs, differ, deltas
+
+
+def test_matrix_core_family_ten_free_running_steps_on_a_decaying_spectrum(env):
+    """Gradients with a geometrically decaying spectrum over a persistent subspace (0.85 per index, 48 components)
+    plus noise, in bf16, ten free-running steps.  What a worker sends, Delta = P^ Q+^T, stays within 2e-2 of the
+    oracle's (Frobenius norm) at every step.  The factors themselves are compared on the first step only: their
+    trailing columns belong to singular values at the level of the quantisation noise of the error feedback,
+    which differs between the two runs as soon as one code does, so column-wise they drift apart while the
+    product does not.  Codes are not compared: the residual of such a gradient is a thousand times smaller than
+    the reconstruction it is the remainder of, so the two sides' fp32 evaluations of p - P^ Q+^T (an fma chain;
+    matrix-core sums) differ by ~1e-4 of a quantisation step instead of ~1e-7, neither being the more exact."""
+    layout = [(512, 1024), (300, 256), (256, 2048)]
+    errs, _, deltas = _free_running(env, layout,
+                                    lambda t, l: wl.f32_to_bf16_bits(wl.decaying_gradient(layout[l][0], layout[l][1], 0.85, 1e-6, l, t)),
+                                    "free-running mfma, decaying spectrum", codes_at_step_0=False)
+    assert errs[0] <= 2e-2, errs
+    assert max(deltas) <= 2e-2, deltas
+
+
+def test_matrix_core_family_ten_free_running_steps_on_gapless_gradients(env):
+    """The benchmark's iid Student-t gradients have no spectral gap, and there the warm-started iteration carries
+    any difference forward, amplified about three times per step (the oracle does the same against a copy of itself
+    with ONE code changed by one level: its own tests show that).  Left to itself the library
+    stays within 2e-2 of the oracle (within 1e-5, in fact) for as long as all codes are equal; the first
+    excused boundary case (a code one level off) is such a one-code change, after which the factors of the
+    two runs are no longer comparable step by step, which is why the other tests compare in lock-step."""
+    w = wl.WORKLOADS["large"]
+    layout = [(512, 1024), (300, 256), (256, 2048)]
+    errs, differ, _ = _free_running(env, layout, lambda t, l: wl.host_gradient(w, t, l, shape=layout[l]),
+                                    "free-running mfma, gapless")
+    first = differ.index(True) if True in differ else len(differ)
+    assert first >= 1
+    assert all(e <= 1e-5 for e in errs[:first]), errs
+    assert errs[0] <= 2e-2 and all(e <= 2e-2 for e in errs[:first + 1]), errs
+
+
+@pytest.mark.parametrize("name,layout", [("tiny", [(256, 128)]), ("cnn", [(64, 147), (128, 1152)]), ("large", [(300, 256), (130, 384)])])
+def test_a_run_resumed_in_a_fresh_context_continues_bit_for_bit(env, name, layout):
+    """Checkpoint and resume through the C ABI: a worker's state is (codes, scales, Q), the step counter and the
+    seed.  Ten steps on one context equal five steps, a download of the state, a NEW context and new device
+    buffers loaded from the download, and five more steps: codes, scales and both factors bit for bit."""
+    R, B, U = env
+    w = wl.WORKLOADS[name]
+    Q0s = [wl.host_q0(w, l, shape=layout[l]) for l in range(len(layout))]
+    grads = [[wl.host_gradient(w, t, l, shape=layout[l]) for l in range(len(layout))] for t in range(10)]
+    one = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+    for t in range(10):
+        one.set_grads(grads[t])
+        one.step(t)
+    first = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+    for t in range(5):
+        first.set_grads(grads[t])
+        first.step(t)
+    saved = {k: first.buf[k].cpu().numpy().copy() for k in ("codes", "scales", "Q")}
+    first.m.close()
+    del first
+    second = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s)
+    import torch
+
+    for k, v in saved.items():
+        second.buf[k].copy_(torch.from_numpy(v))
+    for t in range(5, 10):
+        second.set_grads(grads[t])
+        second.step(t)
+    for k in ("codes", "scales", "Q", "P"):
+        assert torch.equal(one.buf[k], second.buf[k]), (name, k)
+    one.m.close()
+    second.m.close()
+
+
 def test_runs_are_reproducible(env):
     """Fixed-order reductions: two runs from the same state give identical bits."""
     R, B, U = env

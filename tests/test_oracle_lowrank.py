@@ -68,6 +68,25 @@ def test_orthonormalise_is_the_positive_diagonal_thin_QR(ref, n, r):
     assert np.max(np.abs(np.tril(R, -1))) <= 1e-5 * np.abs(R).max()
 
 
+@pytest.mark.parametrize("cond", [1e2, 1e4, 1e5])
+@pytest.mark.parametrize("n,r", [(300, 4), (1000, 8), (5000, 32)])
+def test_orthonormalise_graded_panels_against_householder_qr(ref, n, r, cond):
+    """Panels with geometrically graded singular values (condition 1e2 .. 1e5): the oracle's twice-projected
+    Gram-Schmidt in fp64 gives the factor of numpy's Householder QR (signs fixed so that diag(R) > 0) to a few
+    fp32 units in the last place, and orthonormal columns.  The GPU tests compare the library on the same panels."""
+    from paper_2312_08538_amd import workloads as wl
+
+    P = wl.graded_panel(n, r, cond, 1)
+    s = np.linalg.svd(P.astype(np.float64), compute_uv=False)
+    assert 0.5 * cond <= s[0] / s[-1] <= 2 * cond
+    Ph = ref.orthonormalise(P)
+    Qf, Rf = np.linalg.qr(P.astype(np.float64))
+    Qf = Qf * np.sign(np.diag(Rf))
+    assert np.max(np.abs(Ph - Qf)) <= 4e-7 * np.abs(Qf).max() + 1e-9
+    G = Ph.astype(np.float64).T @ Ph.astype(np.float64)
+    assert np.max(np.abs(G - np.eye(r))) <= 1e-5
+
+
 def test_orthonormalise_ill_conditioned_still_orthogonal(ref):
     """Columns nearly parallel (condition ~1e5): projecting twice keeps orthogonality."""
     rng = _rng(3)

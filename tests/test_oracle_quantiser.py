@@ -94,8 +94,9 @@ def test_grid_points_are_reproduced_exactly(ref, bits, block):
 @pytest.mark.parametrize("bits,block", BITS_BLOCK)
 @pytest.mark.parametrize("kind", ["normal", "laplace", "t3"])
 def test_sure_error_bound_and_absmax(ref, bits, block, kind):
-    """|C(x)_j - x_j| < a/s for every draw; the max-norm element always gets |q| = s; codes stay
-    within [-s, s]; the stored scale is the block max-norm."""
+    """|C(x)_j - x_j| < a/s for every draw; the max-norm element gets |q| = s (in at least 99 % of the blocks;
+    never less than s - 1: fl(s / a) * a can land one fixed-point unit under s * 2^16, and then a small draw
+    leaves it one level below); codes stay within [-s, s]; the stored scale is the block max-norm."""
     s = ref.levels(bits)
     rng = np.random.default_rng(11)
     N = block * 37 + block // 2                      # ragged last block

@@ -199,3 +199,62 @@ def test_partial_step_follows_algorithm_4(ref, beta):
         if t > 0:
             # the planted alternative (quantising p - Delta) is far outside that bound
             assert np.abs(e_new - (p - P64 @ Q64.T)).max() > 10 * step.max()
+
+
+def test_one_code_flip_is_carried_forward_on_gapless_gradients_but_not_on_a_decaying_spectrum(ref):
+    """Why multi-step runs on the benchmark's iid gradients are compared in lock-step: the oracle against a copy
+    of itself in which ONE stored code is changed by one level after the first step.  On iid Student-t gradients
+    (no spectral gap: the rank-r subspace the warm-started iteration follows is not determined by the data) the
+    factors of the two runs drift apart within a few steps (3e-3 of the largest entry after one step, 0.4 after
+    six); on gradients with a decaying spectrum over a persistent subspace the same change stays below 1e-3.
+    (Nothing here is specific to an implementation: both runs are the oracle.)"""
+    w = wl.WORKLOADS["large"]
+    n, m = 256, 512
+
+    def run(grad_of):
+        Q0 = wl.host_q0(w, 0, shape=(n, m))
+        a = ref.MatState.fresh(n, m, w.bits, w.block, Q0.copy())
+        b = ref.MatState.fresh(n, m, w.bits, w.block, Q0.copy())
+        gaps = []
+        for t in range(8):
+            g = grad_of(t)
+            Pa, Qa = ref.step_matrix(g, a, w.rank, w.bits, w.block, 9, 0, t)
+            Pb, Qb = ref.step_matrix(g, b, w.rank, w.bits, w.block, 9, 0, t)
+            if t == 0:
+                assert np.array_equal(a.codes, b.codes)
+                q = ref.unpack_codes(b.codes, n * m, w.bits)
+                j = int(np.nonzero((q > -7) & (q < 7))[0][n * m // 3])         # a code that can move by one level
+                field = (int(b.codes[j // 8]) >> (4 * (j % 8))) & 0xF
+                new = (field + 1) & 0xF
+                b.codes[j // 8] = np.uint32((int(b.codes[j // 8]) & ~(0xF << (4 * (j % 8)))) | (new << (4 * (j % 8))))
+                assert np.count_nonzero(ref.unpack_codes(a.codes, n * m, w.bits) != ref.unpack_codes(b.codes, n * m, w.bits)) == 1
+            gaps.append(float(np.abs(Qa - Qb).max() / np.abs(Qa).max()))
+        return gaps
+
+    gapless = run(lambda t: wl.host_gradient(w, t, 0, shape=(n, m)))
+    decaying = run(lambda t: wl.f32_to_bf16_bits(wl.decaying_gradient(n, m, 0.85, 1e-6, 0, t)))
+    assert gapless[0] == 0.0 and decaying[0] == 0.0
+    assert gapless[1] > 0.0
+    assert max(gapless) >= 30 * gapless[1] and max(gapless) >= 0.1      # carried forward, amplified: no longer comparable
+    assert max(decaying) <= 2e-3 and max(decaying) <= max(gapless) / 100    # stays two orders of magnitude smaller
+
+
+def test_a_run_resumed_from_its_saved_state_continues_bit_for_bit(ref):
+    """Checkpoint and resume: the state of a worker is (codes, scales, Q) plus the step counter and the seed; the
+    draws are a function of (seed, matrix, step, element), so ten steps in one go equal five steps, a save of the
+    state to plain arrays, a fresh start from them, and five more, bit for bit."""
+    w = wl.WORKLOADS["tiny"]
+    (n, m), = w.layout
+    Q0 = wl.host_q0(w, 0)
+    one = ref.MatState.fresh(n, m, w.bits, w.block, Q0.copy())
+    for t in range(10):
+        ref.step_matrix(wl.host_gradient(w, t, 0), one, w.rank, w.bits, w.block, w.lib_seed, 0, t)
+    first = ref.MatState.fresh(n, m, w.bits, w.block, Q0.copy())
+    for t in range(5):
+        ref.step_matrix(wl.host_gradient(w, t, 0), first, w.rank, w.bits, w.block, w.lib_seed, 0, t)
+    saved = {"codes": first.codes.tobytes(), "scales": first.scales.tobytes(), "Q": first.Q.tobytes(), "step": 5}
+    second = ref.MatState(n, m, np.frombuffer(saved["codes"], np.uint32).copy(), np.frombuffer(saved["scales"], np.float32).copy(),
+                          np.frombuffer(saved["Q"], np.float32).reshape(m, w.rank).copy())
+    for t in range(saved["step"], 10):
+        ref.step_matrix(wl.host_gradient(w, t, 0), second, w.rank, w.bits, w.block, w.lib_seed, 0, t)
+    assert np.array_equal(one.codes, second.codes) and np.array_equal(one.scales, second.scales) and np.array_equal(one.Q, second.Q)
