@@ -116,7 +116,9 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     __shared__ __attribute__((aligned(16))) uint16_t sq[3 * kStage * 32];      // splits of Q, [split][column of the stage][c]
     __shared__ float ss[kMfmaRows * kSStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const WorkItem it = dp.p_m_items[blockIdx.x];
+    // the table holds one list per XCD (workgroup b runs on XCD b % 8), each inside an address range of its own
+    const WorkItem it = dp.p_m_items[(blockIdx.x & 7) * (dp.n_p_m >> 3) + (blockIdx.x >> 3)];
+    if (it.mat < 0) return;                          // padding of a shorter list
     const MatDesc d = dp.mats[it.mat];
     const int64_t row0 = it.a;
     const int m = (int)d.m;

@@ -99,7 +99,7 @@ struct Plan {
     std::vector<WorkItem> q_f_items;    // (mat, 64-column strip, row tile)
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
-    std::vector<WorkItem> p_m_items;    // (mat, first row)                    128 rows per workgroup
+    std::vector<WorkItem> p_m_items;    // (mat, first row), 128 rows per workgroup; eight lists of one length, one per XCD (mat = -1: padding)
     std::vector<WorkItem> q_m_items;    // (mat, pair of column blocks of 128, row tile)
     std::vector<WorkItem> err_m_items;  // (mat, first row, first column block of 128, blocks)   128 rows per workgroup
     std::vector<WorkItem> split_p_items;   // transpose the scales: (mat, first row / 64)
