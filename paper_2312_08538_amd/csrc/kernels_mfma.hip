@@ -370,9 +370,13 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 // row-major into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16
 // (within 16 lanes: lane i supplies the address of 4 consecutive columns of row i / 4, chunk i % 4;
 // lane n receives column n of those 4 rows).  The splits of P^ and of d_i P^ are made once per chunk
-// by the whole workgroup from the fp32 rows of P^, stored row-major and read the same way: the only
-// factor data a chunk fetches are 8 KB of P^ and its 64 block scales (from the column-block-major
-// copy of the scales, 256 contiguous bytes).  Everything a workgroup loads passes through the L2,
+// by the whole workgroup from the fp32 entries of P^: a thread takes 8 rows of one column, which is
+// what one lane of a matrix-core operand holds, so the splits are stored in operand order (one
+// 16-byte store each) and read back with one 16-byte load per operand.  The only factor data a chunk
+// fetches are 8 KB of P^ and its 64 block scales (from the column-block-major copy of the scales).
+// What a wave can get out of the LDS is bounded by the number of its LDS instructions (one comes back
+// every ~17 ns, whatever its width), so operands that need no transposing read come as one
+// instruction, not two.  Everything a workgroup loads passes through the L2,
 // whose bandwidth bounds this pass: tables of ready-made splits would cost more of it than the
 // splitting costs in arithmetic.  fp32 sums of the matrix cores cover one chunk; chunks are added
 // in fp64.
@@ -415,21 +419,26 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     struct ChunkRegs {
         u32x4 g0, g1, g2, g3;
         uint32_t cw0, cw1, cw2, cw3;
-        float sc;
+        float sc[8];
     };
-    const int frow = tid >> 2, fcg = tid & 3;       // factor roles: row of the chunk, group of 8 c
+    // factor roles: column fc of P^ and the 8 rows 8 frg .. 8 frg + 7 of the chunk: exactly what one lane of a
+    // matrix-core operand holds (lane = 32 (frg % 2) + fc of the operand of rows 16 (frg / 2) ..), so the splits
+    // go to LDS in operand order with one 16-byte store each and come back with one 16-byte load
+    const int fc = tid & 31, frg = tid >> 5;
     const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
-    auto load_factor = [&](f32x4v &p0, f32x4v &p1, int64_t i0) {
-        const int64_t row = (i0 + frow < row1) ? i0 + frow : row1 - 1;
-        const f32x4v *pp = reinterpret_cast<const f32x4v *>(ph + row * 32 + fcg * 8);
-        p0 = pp[0];
-        p1 = pp[1];
+    auto load_factor = [&](float (&pf)[8], int64_t i0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : row1 - 1;
+            pf[j] = ph[row * 32 + fc];
+        }
     };
     auto load_chunk = [&](ChunkRegs &r, int64_t i0, int cb) {
         const int64_t last = row1 - 1;
-        {
-            const int64_t row = (i0 + frow < row1) ? i0 + frow : last;
-            r.sc = scT[(int64_t)cb * d.n + row];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
+            r.sc[j] = scT[(int64_t)cb * d.n + row];
         }
         int64_t e[4];
 #pragma unroll
@@ -446,20 +455,22 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         r.cw2 = cw[(e[2] >> 3) + goct];
         r.cw3 = cw[(e[3] >> 3) + goct];
     };
+    // splits of 8 rows of one column, in operand order: [split][16 rows][lane] x 8 bf16
     auto store_split = [&](uint16_t *o, const float (&x)[8]) {
         float hh[8], mm[8], ll[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) split3(x[j], hh[j], mm[j], ll[j]);
-        *reinterpret_cast<uint4 *>(o) =
+        uint16_t *dst = o + ((frg >> 1) * 64 + (frg & 1) * 32 + fc) * 8;
+        *reinterpret_cast<uint4 *>(dst) =
             make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
-        *reinterpret_cast<uint4 *>(o + kQRows * 32) =
+        *reinterpret_cast<uint4 *>(dst + kQRows * 32) =
             make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
-        *reinterpret_cast<uint4 *>(o + 2 * kQRows * 32) =
+        *reinterpret_cast<uint4 *>(dst + 2 * kQRows * 32) =
             make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
     };
-    // pv: the thread's 8 entries of its row of P^ (zero for rows at or beyond the end of the tile,
+    // pv: the thread's 8 entries of its column of P^ (zero for rows at or beyond the end of the tile,
     // whatever the re-read row holds); with_p: also store the splits of P^ itself (first block of a chunk)
-    auto store_chunk = [&](const ChunkRegs &r, const float (&pv)[8], bool row_ok, bool with_p) {
+    auto store_chunk = [&](const ChunkRegs &r, const float (&pv)[8], bool with_p) {
         const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
         const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
 #pragma unroll
@@ -472,13 +483,15 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
-        if (with_p) store_split(sb + frow * 32 + fcg * 8, pv);
-        // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
-        const float dstep = row_ok ? (r.sc * inv_levels(4) * dp.omb) * 16.0f : 0.0f;
+        if (with_p) store_split(sb, pv);
         float dp8[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dp8[j] = dstep * pv[j];
-        store_split(sd + frow * 32 + fcg * 8, dp8);
+        for (int j = 0; j < 8; ++j) {
+            // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
+            const float dstep = (r.sc[j] * inv_levels(4) * dp.omb) * 16.0f;
+            dp8[j] = dstep * pv[j];                      // pv is zero for rows beyond the tile
+        }
+        store_split(sd, dp8);
     };
 
     // the matrix cores accumulate one 64-row chunk in fp32; chunks are added up in fp64
@@ -492,7 +505,6 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int gq = lane >> 4, li = lane & 15;
     const int tr_row = 8 * (gq >> 1) + (li >> 2), tr_col = 16 * (gq & 1) + 4 * (li & 3);
     const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
-    const int tr_d = tr_row * 32 + tr_col;                      // P^ and d P^ tiles
 
     // Wave priority: the phases that issue loads and fill LDS run at a higher priority than the
     // matrix-core phase, so that the workgroup that is feeding the memory pipeline is not held up by
@@ -507,8 +519,8 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                aP[s].u = lds_read_tr16x8(sb + s * kQRows * 32 + tr_d + ks * 16 * 32, 32);
-                aD[s].u = lds_read_tr16x8(sd + s * kQRows * 32 + tr_d + ks * 16 * 32, 32);
+                aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
+                aD[s].u = *reinterpret_cast<const uint4 *>(sd + s * kQRows * 32 + (ks * 64 + lane) * 8);
             }
             acc = mfma(aP[0], bg, acc);
             acc = mfma(aD[0], bq, acc);
@@ -524,23 +536,22 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 
     // One chunk per trip: block A, then block B with the same rows of P^.
     ChunkRegs ra, rb;
-    f32x4v np0, np1;                    // the next chunk's rows of P^
-    load_factor(np0, np1, row0);
+    float np[8];                        // the next chunk's entries of P^
+    load_factor(np, row0);
     load_chunk(ra, row0, cbA);
     load_chunk(rb, row0, cbB);
     for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
-        const bool row_ok = i0 + frow < row1;
-        float pv[8] = {np0[0], np0[1], np0[2], np0[3], np1[0], np1[1], np1[2], np1[3]};
+        float pv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pv[j] = row_ok ? pv[j] : 0.0f;
+        for (int j = 0; j < 8; ++j) pv[j] = (i0 + 8 * frg + j < row1) ? np[j] : 0.0f;
         __syncthreads();                // everybody is done reading the previous block-chunk
-        store_chunk(ra, pv, row_ok, true);
+        store_chunk(ra, pv, true);
         __syncthreads();
-        load_factor(np0, np1, i0 + kQRows);
+        load_factor(np, i0 + kQRows);
         load_chunk(ra, i0 + kQRows, cbA);
         compute_chunk(accA);
         __syncthreads();
-        store_chunk(rb, pv, row_ok, false);
+        store_chunk(rb, pv, false);
         __syncthreads();
         load_chunk(rb, i0 + kQRows, cbB);
         compute_chunk(accB);
