@@ -431,7 +431,7 @@ def run_iconef(w, fraction: float = 0.1, reps: int = 10):
 
 def run_iconef_lowrank(w, reps: int = 10):
     """Times one iConEF-v1 step around the rank-r compressor (the three passes of the plain step, each decoding both
-    error vectors, and the second rounding in the err pass); for the workloads outside the bf16 matrix-core family."""
+    error vectors, and the second rounding in the err pass)."""
     import torch
 
     from paper_2312_08538_amd import binding as B
@@ -562,8 +562,7 @@ def main():
                     help="time only the iConEF-v1 step (two compressed error vectors, the quantiser twice) with the "
                          "random-block and scaled-sign gradient compressors on --workload and print its line")
     ap.add_argument("--iconef-rank-r", action="store_true",
-                    help="time only the iConEF-v1 step around the rank-r compressor on --workload (cnn, lm or "
-                         "translation: the bf16 matrix-core kernel family has no two-vector form) and print its line")
+                    help="time only the iConEF-v1 step around the rank-r compressor on --workload and print its line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming kernel of known size (k_decode: reads the codes and "
                          "scales, writes 4 bytes per element) for scaling rocprofv3 byte counters")
@@ -588,9 +587,6 @@ def main():
                           "steps": a.steps, "config": {"workload": w.name}, **r}), flush=True)
         return
     if a.iconef_rank_r:
-        if w.name == "large":
-            print("bench.py: --iconef-rank-r needs cnn, lm or translation (no two-vector form at rank 32 / bf16)", file=sys.stderr)
-            sys.exit(2)
         r = run_iconef_lowrank(w, a.steps)
         print(json.dumps({"metric": "iConEF-v1 rank-r step throughput: gradient GB/s processed",
                           "value": round(w.grad_bytes / (r["ms_per_step"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
@@ -674,9 +670,9 @@ def main():
         # improved contractive error feedback, version 1: a second compressed vector, the quantiser twice
         out["iconef_v1"] = {"fraction": 0.1, "workloads": {name: run_iconef(wl.WORKLOADS[name])
                                                            for name in ("cnn", "lm", "translation", "large")}}
-        # ... and around the rank-r compressor (the workloads outside the bf16 matrix-core family)
+        # ... and around the rank-r compressor
         out["iconef_v1_rank_r"] = {"workloads": {name: run_iconef_lowrank(wl.WORKLOADS[name])
-                                                 for name in ("cnn", "lm", "translation")}}
+                                                 for name in ("cnn", "lm", "translation", "large")}}
     if not a.no_cpu_baseline:
         v, cores, sample = run_oracle_sample(w)
         out["cpu_baseline"] = {"value": round(v, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",

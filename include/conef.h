@@ -300,10 +300,9 @@ int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
  * conef_step, each decoding both vectors; conef_orthonormalise is shared:
  *   conef_i_step = conef_i_step_p -> conef_orthonormalise -> conef_i_step_q -> conef_i_step_err,
  * with the two exchange points of conef_step between the same calls.  conef_i_step_err replaces both vectors in place.
- * For quantiser contexts with beta = 0 whose matrices all belong to the kernel families for ranks 2/4/8 or for any
- * shape: CONEF_ESTATE on a count-sketch context, for beta > 0, and when the plan holds a matrix of the bf16
- * matrix-core family (rank 32, bf16 gradients, 4-bit codes, blocks of 128, columns a multiple of 128), which has no
- * two-vector form.  CONEF_EINVAL if the two vectors share a buffer.
+ * For quantiser contexts with beta = 0 (Algorithm 3 has no partial update): CONEF_ESTATE on a count-sketch context
+ * and for beta > 0.  CONEF_EINVAL if the two vectors share a buffer.  conef_i_step_err takes the workspace of the
+ * other stage calls (contents as conef_step_err expects them: nothing kept from an earlier call is relied upon).
  * Every other argument, alignment, asynchrony and errors as for conef_step and its stage calls. */
 int conef_i_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
                    const uint32_t *err2_codes, const float *err2_scales, const float *Q_state, float *P_raw_out,
@@ -312,7 +311,8 @@ int conef_i_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes,
                    const uint32_t *err2_codes, const float *err2_scales, const float *P_hat, float *Q_out, void *workspace,
                    void *hip_stream);
 int conef_i_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
-                     float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream);
+                     float *err2_scales, const float *P_hat, const float *Q_new, void *workspace, uint64_t step,
+                     void *hip_stream);
 int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                  float *err2_scales, const float *Q_state, float *P_out, float *Q_out, void *workspace, uint64_t step,
                  void *hip_stream);

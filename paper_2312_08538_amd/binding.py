@@ -76,7 +76,7 @@ def lib() -> ctypes.CDLL:
     L.conef_i_rk_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_step_p.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.conef_i_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-    L.conef_i_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_rk_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rk_sizes.argtypes = [vp, szp]
@@ -231,9 +231,9 @@ def conef_i_step_q(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P
                                 _ptr(P_hat), _ptr(Q_out), _ptr(workspace), stream), "conef_i_step_q")
 
 
-def conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, step: int, stream=0):
+def conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, workspace, step: int, stream=0):
     _check(lib().conef_i_step_err(ctx, _ptr(grads), _ptr(err_codes), _ptr(err_scales), _ptr(err2_codes), _ptr(err2_scales),
-                                  _ptr(P_hat), _ptr(Q_new), step, stream), "conef_i_step_err")
+                                  _ptr(P_hat), _ptr(Q_new), _ptr(workspace), step, stream), "conef_i_step_err")
 
 
 def conef_i_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_out, Q_out, workspace, step: int,

@@ -399,10 +399,10 @@ int conef_step_static(conef_ctx *ctx, const void *grads, uint32_t *err_codes, fl
 
 // ---------------------------------------------------------------- iConEF version 1 around the rank-r compressor
 namespace {
-// Algorithm 3 has no partial update, and the bf16 matrix-core kernel family has no two-vector form.
+// Algorithm 3 has no partial update.
 int i_lowrank_state(const conef_ctx *ctx)
 {
-    if (ctx->plan.sketch || ctx->plan.beta != 0.0f || !ctx->plan.p_m_items.empty()) return CONEF_ESTATE;
+    if (ctx->plan.sketch || ctx->plan.beta != 0.0f) return CONEF_ESTATE;
     return CONEF_OK;
 }
 
@@ -464,17 +464,30 @@ int conef_i_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes,
     return i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_out, workspace, hip_stream, false);
 }
 
-int conef_i_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
-                     float *err2_scales, const float *P_hat, const float *Q_new, uint64_t step, void *hip_stream)
+namespace {
+int i_step_err_impl(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                    float *err2_scales, const float *P_hat, const float *Q_new, void *workspace, uint64_t step, void *hip_stream,
+                    bool splits_ready)
 {
-    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !P_hat || !Q_new) return CONEF_EINVAL;
+    if (!ctx || !grads || !err_codes || !err_scales || !err2_codes || !err2_scales || !P_hat || !Q_new || !workspace)
+        return CONEF_EINVAL;
     int rc = i_lowrank_state(ctx);
     if (rc) return rc;
-    if (i_bad_state_pointers(grads, err_codes, err_scales, err2_codes, err2_scales) || misaligned(P_hat, 16) || misaligned(Q_new, 16))
+    if (i_bad_state_pointers(grads, err_codes, err_scales, err2_codes, err2_scales) || misaligned(P_hat, 16) ||
+        misaligned(Q_new, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
     if ((rc = ensure_uploaded(ctx))) return rc;
     return hip_rc(launch_pass_err_two(PlanWithFirst(ctx, err_codes, err_scales).dp, grads, err_codes, err_scales, err2_codes,
-                                      err2_scales, P_hat, Q_new, step, static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
+                                      err2_scales, P_hat, Q_new, step, ws_doubles(ctx, workspace), splits_ready,
+                                      static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
+}
+}  // namespace
+
+int conef_i_step_err(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
+                     float *err2_scales, const float *P_hat, const float *Q_new, void *workspace, uint64_t step, void *hip_stream)
+{
+    return i_step_err_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_hat, Q_new, workspace, step, hip_stream,
+                           false);
 }
 
 int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
@@ -488,7 +501,8 @@ int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *
     if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
     if ((rc = i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true)))
         return rc;
-    return conef_i_step_err(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, step, hip_stream);
+    return i_step_err_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, step, hip_stream,
+                           true);
 }
 
 int conef_reset_error(conef_ctx *ctx, uint32_t *err_codes, float *err_scales, void *hip_stream)

@@ -59,11 +59,12 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
 hipError_t launch_update(const DevicePlan &dp, const float *Phat, const float *Qn, float *x, bool subtract,
                          hipStream_t st);
 // Random-block gradient compressor: one streaming pass (decode + add, keep the block, compress the rest).
-// Improved contractive error feedback around the rank-r compressor (no matrix of the bf16 matrix-core family): the P
-// and Q+ passes are launch_pass_p / launch_pass_q on a plan that carries the first vector (i_codes, i_scales) with the
-// second vector as their codes / scales; the err pass decodes both vectors and writes both.
+// Improved contractive error feedback around the rank-r compressor: the P and Q+ passes are launch_pass_p /
+// launch_pass_q on a plan that carries the first vector (i_codes, i_scales) with the second vector as their codes /
+// scales; the err pass decodes both vectors and writes both (splits_ready as in launch_pass_err).
 hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
-                               float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span);
+                               float *scales2, const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
+                               hipStream_t st, Span span);
 void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                         float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st);
 // codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null;
@@ -116,9 +117,11 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
 void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Q, float *P, hipStream_t st);
 
-void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st);
+void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, bool second, hipStream_t st);
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Phat, double *ws, float *Qout, hipStream_t st);
+void mfma_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2, float *scales2,
+                       const float *Phat, const double *ws, uint64_t step, hipStream_t st);
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                    const double *ws, uint64_t step, hipStream_t st);
 void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st);

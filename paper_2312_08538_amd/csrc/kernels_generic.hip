@@ -526,9 +526,16 @@ void generic_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, 
 // The err pass of improved contractive error feedback around the rank-r compressor: codes / scales hold the first
 // vector (also dp.i_codes / dp.i_scales), codes2 / scales2 the second; both are decoded and both replaced.
 hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
-                               float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st, Span span)
+                               float *scales2, const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,
+                               hipStream_t st, Span span)
 {
+    if (!splits_ready) {
+        mfma_split_q_new(dp, Qn, ws, st);
+        mfma_transpose_scales(dp, scales2, ws, false, st);
+        mfma_transpose_scales(dp, scales, ws, true, st);
+    }
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_pass_err_two(dp, grads, codes, scales, codes2, scales2, Phat, ws, step, st);
     octet_pass_err_two(dp, grads, codes, scales, codes2, scales2, Phat, Qn, step, st);
     if (dp.n_err > 0) {
         const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
@@ -561,7 +568,8 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
 {
     (void)fused;
     // the matrix-core family reads the block scales of the incoming error state column block by column block
-    mfma_transpose_scales(dp, scales, ws, st);
+    mfma_transpose_scales(dp, scales, ws, false, st);
+    if (dp.i_codes) mfma_transpose_scales(dp, dp.i_scales, ws, true, st);     // the first vector of Algorithm 3
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
@@ -579,7 +587,7 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     if (!splits_ready) {
         // the factors handed in may differ from those the Q+ stage saw (e.g. after an all-reduce)
         mfma_split_q_new(dp, Qn, ws, st);
-        mfma_transpose_scales(dp, scales, ws, st);      // the state may have changed since a Q+ stage ran
+        mfma_transpose_scales(dp, scales, ws, false, st);      // the state may have changed since a Q+ stage ran
     }
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_err(dp, grads, codes, scales, Phat, ws, step, st);

@@ -107,6 +107,9 @@ constexpr int kCStride = kCodeGroup / 8 + 4; // code words per row in LDS (144 b
 constexpr int kScaleGroup = 32 * 128;       // columns per scale group: 32 scales are one 128-byte line per row
 constexpr int kSStride = 33;                // scales per row in LDS (+1: rows fall on distinct banks)
 
+// GRAD = false, ACCUM = true: the contribution of a compressed vector alone (no gradient) added to a P that an
+// earlier launch has written: P = (g + second) Q, then P += first Q, for the two error vectors of Algorithm 3.
+template <bool GRAD, bool ACCUM>
 __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
                                                 const float *__restrict__ Q, float *P)
@@ -127,8 +130,8 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     const float *qf = Q + d.q_off;
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
-    typedef float f32x4v __attribute__((ext_vector_type(4)));
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
     struct StageRegs {
         u32x4 g[4];
         f32x4v q0, q1;      // 8 entries of one row of Q
@@ -188,18 +191,22 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     auto load_stage = [&](StageRegs &r, int k0) {
         // rows beyond the matrix re-read its last row (their results are not stored): every load of the
         // loop is unconditional, so the waits on a stage can leave the younger stage's loads pending
+        if (GRAD) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) r.g[s] = *reinterpret_cast<const u32x4 *>(g + g_row[s] + k0 + (tid & 7) * 8);
+            for (int s = 0; s < 4; ++s) r.g[s] = *reinterpret_cast<const u32x4 *>(g + g_row[s] + k0 + (tid & 7) * 8);
+        }
         // the stage's 64 rows of Q, 8 KB, contiguous
         const f32x4v *qp = reinterpret_cast<const f32x4v *>(qf + (int64_t)(k0 + krow) * 32 + fcg * 8);
         r.q0 = qp[0];
         r.q1 = qp[1];
     };
     auto store_stage = [&](const StageRegs &r) {
+        if (GRAD) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
-            *reinterpret_cast<u32x4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
+            for (int s = 0; s < 4; ++s) {
+                const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
+                *reinterpret_cast<u32x4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
+            }
         }
         {
             // operand splits of Q, row-major; the matrix cores read them through the transposing LDS load
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
         for (int ks = 0; ks < kStage / 16; ++ks) {
             Frag bg, bq, a0, a1, a2;
-            bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
+            if (GRAD) bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
             const uint32_t w = sc[my_row_in_tile * kCStride + ((k0 & (kCodeGroup - 1)) >> 3) + ks * 2 + kg];
             float q16[8];
             fields_over_16(w, q16);                  // sixteenths of small integers: exact in bf16
@@ -244,11 +251,11 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
             a0.u = lds_read_tr16x8(sq + 0 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a1.u = lds_read_tr16x8(sq + 1 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a2.u = lds_read_tr16x8(sq + 2 * kStage * 32 + tr_a + ks * 16 * 32, 32);
-            accP = mfma(a0, bg, accP);
+            if (GRAD) accP = mfma(a0, bg, accP);
             accS = mfma(a0, bq, accS);
-            accP = mfma(a1, bg, accP);
+            if (GRAD) accP = mfma(a1, bg, accP);
             accS = mfma(a1, bq, accS);
-            accP = mfma(a2, bg, accP);
+            if (GRAD) accP = mfma(a2, bg, accP);
             accS = mfma(a2, bq, accS);
         }
         if (((k0 + kStage) & 127) == 0) {
@@ -304,9 +311,15 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     if (my_row < d.n) {
         float *out = P + d.p_off + my_row * 32;
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4)
-            *reinterpret_cast<float4 *>(out + 8 * g4 + 4 * kg) =
-                make_float4((float)acc64[4 * g4], (float)acc64[4 * g4 + 1], (float)acc64[4 * g4 + 2], (float)acc64[4 * g4 + 3]);
+        for (int g4 = 0; g4 < 4; ++g4) {
+            float4 *o4 = reinterpret_cast<float4 *>(out + 8 * g4 + 4 * kg);
+            if (ACCUM) {
+                const float4 old = *o4;
+                acc64[4 * g4] += (double)old.x; acc64[4 * g4 + 1] += (double)old.y;
+                acc64[4 * g4 + 2] += (double)old.z; acc64[4 * g4 + 3] += (double)old.w;
+            }
+            *o4 = make_float4((float)acc64[4 * g4], (float)acc64[4 * g4 + 1], (float)acc64[4 * g4 + 2], (float)acc64[4 * g4 + 3]);
+        }
     }
 }
 
@@ -314,7 +327,8 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 // Column-block-major copy of the block scales of a matrix, scT[block of the row][row]: the Q+ and err
 // passes need, per 128-column block, the scales of consecutive rows, which are a row pitch apart
 // (a 128-byte line each) in the state's own row-major order.  One workgroup per 64 rows.
-__global__ __launch_bounds__(256) void k_transpose_scales(DevicePlan dp, const float *__restrict__ scales, double *ws)
+// (second: into the region kept for the other error vector of Algorithm 3)
+__global__ __launch_bounds__(256) void k_transpose_scales(DevicePlan dp, const float *__restrict__ scales, double *ws, int second)
 {
     __shared__ float tile[64 * 33];
     const WorkItem it = dp.split_p_items[blockIdx.x];
@@ -322,7 +336,7 @@ __global__ __launch_bounds__(256) void k_transpose_scales(DevicePlan dp, const f
     const int64_t row0 = (int64_t)it.a * 64;
     const int nblk_row = (int)(d.m >> 7), tid = threadIdx.x;
     const float *src = scales + d.scale_off;
-    float *dst = reinterpret_cast<float *>(ws + d.scT_off);
+    float *dst = reinterpret_cast<float *>(ws + (second ? d.scT2_off : d.scT_off));
     for (int b0 = 0; b0 < nblk_row; b0 += 32) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -383,6 +397,10 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 constexpr int kQRows = 64;                  // rows per chunk
 constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
 
+// GRAD = false, ACCUM = true: the contribution of a compressed vector alone (no gradient; its scales in the second
+// column-block-major region) added to what an earlier launch has left: Q+ = (g + second)^T P^, then
+// Q+ += first^T P^, for the two error vectors of Algorithm 3.
+template <bool GRAD, bool ACCUM>
 __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
                                                 const float *__restrict__ Phat, double *ws, float *Qout)
@@ -407,7 +425,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
     const uint16_t *g = grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
-    const float *scT = reinterpret_cast<const float *>(ws + d.scT_off);       // [block][row]
+    const float *scT = reinterpret_cast<const float *>(ws + (GRAD ? d.scT_off : d.scT2_off));       // [block][row]
     const float *ph = Phat + d.p_off;
 
     // A block-chunk's loads are held in registers until its turn in LDS; two are in flight (block A and
@@ -415,7 +433,6 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     // the end of the tile re-read its last row and get zero factor operands instead): the waits on one
     // can then leave the younger one's loads pending.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    typedef float f32x4v __attribute__((ext_vector_type(4)));
     struct ChunkRegs {
         u32x4 g0, g1, g2, g3;
         uint32_t cw0, cw1, cw2, cw3;
@@ -446,10 +463,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             const int64_t row = (i0 + grow + 16 * s < row1) ? i0 + grow + 16 * s : last;
             e[s] = row * m + cb * 128;
         }
-        r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0] + goct * 8);
-        r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1] + goct * 8);
-        r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2] + goct * 8);
-        r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3] + goct * 8);
+        if (GRAD) {
+            r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0] + goct * 8);
+            r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1] + goct * 8);
+            r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2] + goct * 8);
+            r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3] + goct * 8);
+        }
         r.cw0 = cw[(e[0] >> 3) + goct];
         r.cw1 = cw[(e[1] >> 3) + goct];
         r.cw2 = cw[(e[2] >> 3) + goct];
@@ -480,10 +499,10 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             u32x4 qb;
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) qb[e2] = pack_hi16(q16[2 * e2], q16[2 * e2 + 1]);
-            *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
+            if (GRAD) *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
             *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
         }
-        if (with_p) store_split(sb, pv);
+        if (GRAD && with_p) store_split(sb, pv);
         float dp8[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -515,18 +534,18 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
             Frag bg, bq, aP[3], aD[3];
-            bg.u = lds_read_tr16x8(tg + tr_t + ks * 16 * kTPitch, kTPitch);
+            if (GRAD) bg.u = lds_read_tr16x8(tg + tr_t + ks * 16 * kTPitch, kTPitch);
             bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
-                aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
+                if (GRAD) aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
                 aD[s].u = *reinterpret_cast<const uint4 *>(sd + s * kQRows * 32 + (ks * 64 + lane) * 8);
             }
-            acc = mfma(aP[0], bg, acc);
+            if (GRAD) acc = mfma(aP[0], bg, acc);
             acc = mfma(aD[0], bq, acc);
-            acc = mfma(aP[1], bg, acc);
+            if (GRAD) acc = mfma(aP[1], bg, acc);
             acc = mfma(aD[1], bq, acc);
-            acc = mfma(aP[2], bg, acc);
+            if (GRAD) acc = mfma(aP[2], bg, acc);
             acc = mfma(aD[2], bq, acc);
         }
 #pragma unroll
@@ -565,7 +584,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-                const float x = (float)acc64[v];
+                const float x = (float)(ACCUM ? acc64[v] + (double)qo[c] : acc64[v]);
                 qo[c] = x;
                 mfma_store_q_split(d, ws, kcol, c, x);
             }
@@ -573,7 +592,10 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             // partial sums of this row tile, added in tile order by the reduction kernel
             double *out = ws + d.qpart_off + ((int64_t)it.b * m + kcol) * 32;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
+            for (int v = 0; v < 16; ++v) {
+                const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
+                out[c] = ACCUM ? out[c] + acc64[v] : acc64[v];
+            }
         }
     };
     write_block(accA, cbA);
@@ -602,10 +624,13 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 // cc of the run) and stored once per run, 64 contiguous bytes per row.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+template <bool TWO>
 struct ErrIn {
     uint4 g[4];
     uint32_t cw[4];
     float s[4];
+    uint32_t cw1[TWO ? 4 : 1];      // the first error vector of Algorithm 3
+    float s1[TWO ? 4 : 1];
 };
 
 // Fixed-point stochastic rounding of an octet into a word of eight 4-bit two's-complement fields.
@@ -640,9 +665,15 @@ __device__ __forceinline__ uint32_t dpp_row_ror4(uint32_t a) { return __builtin_
 __device__ __forceinline__ uint32_t dpp_row_ror8(uint32_t a) { return __builtin_amdgcn_update_dpp(0, a, 0x128, 0xF, 0xF, true); }
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 
-__global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
+// TWO (Algorithm 3, both error steps): p = g + e~ + q with the first vector in codes_first / scales_first and the
+// second in codes / scales (their scales column-block-major in the second and the first workspace region); the
+// residual is rounded into the first vector, what that rounding leaves is rounded again (draws of the stream
+// mat | 2^31) into the second.
+template <bool TWO>
+__global__ __launch_bounds__(512, TWO ? 2 : 4) void k_err_mfma(DevicePlan dp, const uint16_t *__restrict__ grads, uint32_t *codes,
                                                   float *scales, const float *__restrict__ Phat, const double *ws,
-                                                  uint32_t step_lo, uint32_t step_hi)
+                                                  uint32_t step_lo, uint32_t step_hi, uint32_t *codes_first,
+                                                  float *scales_first)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sB[2][kErrTileElems];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -666,6 +697,8 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
     uint32_t *cw_tile = codes + d.word_off + tile_row0 * m8;                            // + cb * 16 words
     // incoming scales, column-block-major copy [block][row]: + cb * n
     const float *scT_tile = reinterpret_cast<const float *>(ws + d.scT_off) + tile_row0;
+    uint32_t *cw1_tile = TWO ? codes_first + d.word_off + tile_row0 * m8 : nullptr;
+    const float *scT1_tile = TWO ? reinterpret_cast<const float *>(ws + d.scT2_off) + tile_row0 : nullptr;
     bool valid[4];
     uint32_t goff[4], ooff[4], toff[4];     // byte offsets of the lane's gradient octet, code word and scale from the bases
     uint32_t octet0[4];                     // octet index (within the matrix) of the lane's octet in column block 0
@@ -700,7 +733,7 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
         }
     }
 
-    auto load_in = [&](ErrIn &in, int cb) {
+    auto load_in = [&](ErrIn<TWO> &in, int cb) {
         const char *gb = reinterpret_cast<const char *>(g_tile + cb * 128);
         const char *cb_w = reinterpret_cast<const char *>(cw_tile + cb * 16);
         const char *sb = reinterpret_cast<const char *>(scT_tile + (int64_t)cb * d.n);
@@ -709,6 +742,15 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
             in.g[v] = *reinterpret_cast<const uint4 *>(gb + goff[v]);
             in.cw[v] = *reinterpret_cast<const uint32_t *>(cb_w + ooff[v]);
             in.s[v] = *reinterpret_cast<const float *>(sb + toff[v]);
+        }
+        if (TWO) {
+            const char *cb_w1 = reinterpret_cast<const char *>(cw1_tile + cb * 16);
+            const char *sb1 = reinterpret_cast<const char *>(scT1_tile + (int64_t)cb * d.n);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                in.cw1[TWO ? v : 0] = *reinterpret_cast<const uint32_t *>(cb_w1 + ooff[v]);
+                in.s1[TWO ? v : 0] = *reinterpret_cast<const float *>(sb1 + toff[v]);
+            }
         }
     };
     // a block's splits of Q+: 1536 chunks of 16 bytes, three per thread (scalar base + lane offset again)
@@ -721,7 +763,7 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
         b2 = *reinterpret_cast<const uint4 *>(qb + 16384 + qoff);
     };
 
-    ErrIn in;
+    ErrIn<TWO> in;
     load_in(in, cb0);
     {
         uint4 *dst = reinterpret_cast<uint4 *>(sB[0]) + tid;
@@ -741,6 +783,39 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
     const bool valid_q = (4 * kg + vq) < rows_left;
     // the outgoing scales: block 4 j + quad of the run, row 4 kg + vq, j = 0..3
     float keep[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float keep2[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    // max-norm of a block of each of the lane's four rows (v of f(v, e) = |value| source): the lane ends up with row vq's
+    auto block_max = [&](const f32x4 (&val)[8]) {
+        uint32_t am[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float a = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(val[e][v]));
+            am[v] = __float_as_uint(a);
+        }
+        const uint32_t r0 = umax(odd1 ? am[2] : am[0], dpp_quad_xor1(odd1 ? am[0] : am[2]));
+        const uint32_t r1 = umax(odd1 ? am[3] : am[1], dpp_quad_xor1(odd1 ? am[1] : am[3]));
+        uint32_t mx = umax(odd2 ? r1 : r0, dpp_quad_xor2(odd2 ? r0 : r1));
+        mx = umax(mx, dpp_row_ror4(mx));
+        mx = umax(mx, dpp_row_ror8(mx));
+        return __uint_as_float(mx);
+    };
+    // the quad's four values in row order (lane 0 of a quad holds row 0, lane 2 row 1, lane 1 row 2, lane 3 row 3)
+    auto quad_rows = [&](float x, float (&out)[4]) {
+        out[0] = __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x00, 0xF, 0xF, true));
+        out[1] = __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xAA, 0xF, 0xF, true));
+        out[2] = __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0x55, 0xF, 0xF, true));
+        out[3] = __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), 0xFF, 0xF, 0xF, true));
+    };
+    auto keep_scale = [&](float (&k)[4], float amax, int b) {
+        const bool mine = quad == (b & 3);
+        const int j = b >> 2;
+        k[0] = (mine && j == 0) ? amax : k[0];
+        k[1] = (mine && j == 1) ? amax : k[1];
+        k[2] = (mine && j == 2) ? amax : k[2];
+        k[3] = (mine && j == 3) ? amax : k[3];
+    };
     for (int b = 0; b < nb; ++b) {
         const int cb = cb0 + b;
         const int cbn = (b + 1 < nb) ? cb + 1 : cb;      // the last trip reloads its own block (unused)
@@ -760,6 +835,18 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
             const float step16 = (in.s[v] * inv_levels(4)) * 16.0f;
             float q16[8];
             fields_over_16(in.cw[v], q16);
+            if (TWO) {
+                // the first vector in the inner fused multiply-add, the second in the outer one
+                const float step16_1 = (in.s1[TWO ? v : 0] * inv_levels(4)) * 16.0f;
+                float q16_1[8];
+                fields_over_16(in.cw1[TWO ? v : 0], q16_1);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
+                    acc[e][v] = __builtin_fmaf(step16, q16[e], __builtin_fmaf(step16_1, q16_1[e], gv));
+                }
+                continue;
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float gv = (e & 1) ? __uint_as_float(w4[e >> 1] & 0xFFFF0000u) : __uint_as_float(w4[e >> 1] << 16);
@@ -794,36 +881,40 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
         // rounding phase.  First the max-norm of each of the lane's four row blocks (16 lanes = one
         // 128-column block): non-negative floats order like their bit patterns, so the cross-lane
         // steps are integer maxima (one instruction each with the lane permutation folded in)
-        uint32_t am[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float a = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(acc[e][v]));
-            am[v] = __float_as_uint(a);
-        }
-        const uint32_t r0 = umax(odd1 ? am[2] : am[0], dpp_quad_xor1(odd1 ? am[0] : am[2]));
-        const uint32_t r1 = umax(odd1 ? am[3] : am[1], dpp_quad_xor1(odd1 ? am[1] : am[3]));
-        uint32_t mx = umax(odd2 ? r1 : r0, dpp_quad_xor2(odd2 ? r0 : r1));
-        mx = umax(mx, dpp_row_ror4(mx));
-        mx = umax(mx, dpp_row_ror8(mx));
-        const float amax = __uint_as_float(mx);       // max-norm of block cb of row 4 kg + vq
-        {
-            const bool mine = quad == (b & 3);
-            const int j = b >> 2;
-            keep[0] = (mine && j == 0) ? amax : keep[0];
-            keep[1] = (mine && j == 1) ? amax : keep[1];
-            keep[2] = (mine && j == 2) ? amax : keep[2];
-            keep[3] = (mine && j == 3) ? amax : keep[3];
-        }
+        const float amax = block_max(acc);            // max-norm of block cb of row 4 kg + vq
         // ... then the reciprocal step size s / a of the lane's row, exchanged inside the quad
-        // (lane 0 of a quad holds row 0, lane 2 row 1, lane 1 row 2, lane 3 row 3)
         const float isel = (amax > 0.0f) ? (7.0f / amax) * 65536.0f : 0.0f;
-        const float inv16v[4] = {
-            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x00, 0xF, 0xF, true)),
-            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xAA, 0xF, 0xF, true)),
-            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0x55, 0xF, 0xF, true)),
-            __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(isel), 0xFF, 0xF, 0xF, true))};
+        float inv16v[4];
+        quad_rows(isel, inv16v);
+        if (TWO) {
+            // both roundings of Algorithm 3.  The first goes to the first vector; its decoded value (16 d_new times
+            // the field over 16: the same product) is taken off the residual with a multiplication and a
+            // subtraction, and what is left is rounded into the second vector.
+            keep_scale(keep2, amax, b);
+            float dnew16[4];
+            quad_rows((amax * inv_levels(4)) * 16.0f, dnew16);
+            char *cw1_out = reinterpret_cast<char *>(cw1_tile + cb * 16);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float x[8], q16[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = acc[e][v];
+                const uint32_t o = octet0[v] + (uint32_t)(cb * 16);
+                uint32_t rnd[4];
+                philox4x32_10(o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+                const uint32_t word = quantise_octet4(x, inv16v[v], rnd);
+                if (valid[v]) *reinterpret_cast<uint32_t *>(cw1_out + ooff[v]) = word;
+                fields_over_16(word, q16);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e][v] = x[e] - dnew16[v] * q16[e];
+            }
+            const float amax2 = block_max(acc);
+            keep_scale(keep, amax2, b);
+            const float isel2 = (amax2 > 0.0f) ? (7.0f / amax2) * 65536.0f : 0.0f;
+            quad_rows(isel2, inv16v);
+        } else {
+            keep_scale(keep, amax, b);
+        }
         // ... then one octet (row 4 kg + v, columns 8 cc ..) at a time
         char *cw_out = reinterpret_cast<char *>(cw_tile + cb * 16);
 #pragma unroll
@@ -833,7 +924,7 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
             for (int e = 0; e < 8; ++e) x[e] = acc[e][v];
             const uint32_t o = octet0[v] + (uint32_t)(cb * 16);
             uint32_t rnd[4];
-            philox4x32_10(o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+            philox4x32_10(o, TWO ? ((uint32_t)it.mat | 0x80000000u) : (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
             const uint32_t word = quantise_octet4(x, inv16v[v], rnd);
             if (valid[v]) *reinterpret_cast<uint32_t *>(cw_out + ooff[v]) = word;
         }
@@ -844,6 +935,12 @@ __global__ __launch_bounds__(512, 4) void k_err_mfma(DevicePlan dp, const uint16
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (4 * j + quad < nb) sc_row[4 * j + quad] = keep[j];
+        if (TWO) {
+            float *sc1_row = scales_first + d.scale_off + (row0 + 4 * kg + vq) * nblk_row + cb0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (4 * j + quad < nb) sc1_row[4 * j + quad] = keep2[j];
+        }
     }
 }
 
@@ -853,30 +950,48 @@ void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                  const float *Q, float *P, hipStream_t st)
 {
     if (dp.n_p_m <= 0) return;
-    hipLaunchKernelGGL(k_p_mfma, dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+    hipLaunchKernelGGL((k_p_mfma<true, false>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
                        codes, scales, Q, P);
+    // Algorithm 3: the other error vector's share, added to what the launch above has written
+    if (dp.i_codes)
+        hipLaunchKernelGGL((k_p_mfma<false, true>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                           dp.i_codes, dp.i_scales, Q, P);
 }
 
-void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, hipStream_t st)
+void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, bool second, hipStream_t st)
 {
     if (dp.n_split_p <= 0) return;
-    hipLaunchKernelGGL(k_transpose_scales, dim3(dp.n_split_p), dim3(256), 0, st, dp, scales, ws);
+    hipLaunchKernelGGL(k_transpose_scales, dim3(dp.n_split_p), dim3(256), 0, st, dp, scales, ws, second ? 1 : 0);
 }
 
 void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                  const float *Phat, double *ws, float *Qout, hipStream_t st)
 {
     if (dp.n_q_m <= 0) return;
-    hipLaunchKernelGGL(k_q_mfma, dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
+    hipLaunchKernelGGL((k_q_mfma<true, false>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
                        scales, Phat, ws, Qout);
+    // Algorithm 3: the other error vector's share (its scales transposed into the second region by the caller)
+    if (dp.i_codes)
+        hipLaunchKernelGGL((k_q_mfma<false, true>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                           dp.i_codes, dp.i_scales, Phat, ws, Qout);
 }
 
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                    const double *ws, uint64_t step, hipStream_t st)
 {
     if (dp.n_err_m <= 0) return;
-    hipLaunchKernelGGL(k_err_mfma, dim3(dp.n_err_m), dim3(512), 0, st, dp,
-                       reinterpret_cast<const uint16_t *>(grads), codes, scales, Phat, ws, (uint32_t)step, (uint32_t)(step >> 32));
+    hipLaunchKernelGGL(k_err_mfma<false>, dim3(dp.n_err_m), dim3(512), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
+                       scales, Phat, ws, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr);
+}
+
+// Both error steps of Algorithm 3: codes / scales hold the first vector, codes2 / scales2 the second; the caller has
+// put the column-block-major copies of scales2 and scales into the first and the second workspace region.
+void mfma_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2, float *scales2,
+                       const float *Phat, const double *ws, uint64_t step, hipStream_t st)
+{
+    if (dp.n_err_m <= 0) return;
+    hipLaunchKernelGGL(k_err_mfma<true>, dim3(dp.n_err_m), dim3(512), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes2,
+                       scales2, Phat, ws, (uint32_t)step, (uint32_t)(step >> 32), codes, scales);
 }
 
 void mfma_split_q_new(const DevicePlan &dp, const float *Qn, double *ws, hipStream_t st)

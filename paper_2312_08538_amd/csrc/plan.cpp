@@ -269,6 +269,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             else plan.any_generic = true;
             if (d.path == kPathMfma) {
                 d.scT_off = wd; wd += round_up((d.m / 128) * d.n * 4 / 8 + 1, 32);
+                d.scT2_off = wd; wd += round_up((d.m / 128) * d.n * 4 / 8 + 1, 32);
                 d.qs_off = wd;  wd += round_up(3 * 32 * d.m * 2 / 8, 32);
             }
 
@@ -585,6 +586,7 @@ bool check_plan(const Plan &plan)
         if (d.n_p_chunks > 1) regions.push_back({d.ppart_off, d.ppart_off + (int64_t)d.n_p_chunks * d.n * plan.rank});
         if (d.path == kPathMfma) {
             regions.push_back({d.scT_off, d.scT_off + ((d.m / 128) * d.n * 4 + 7) / 8});
+            regions.push_back({d.scT2_off, d.scT2_off + ((d.m / 128) * d.n * 4 + 7) / 8});
             regions.push_back({d.qs_off, d.qs_off + 3 * 32 * d.m * 2 / 8});
         }
     }

@@ -45,6 +45,7 @@ struct MatDesc {
     int32_t m8;                     // m / 8
     // MFMA family: workspace offsets in doubles; bf16 triple split of Q+ (x = hi + mid + lo)
     int64_t scT_off;                // block scales, column-block-major: [m / 128][n] fp32
+    int64_t scT2_off;               // the same for the other error vector of Algorithm 3
     int64_t qs_off;                 // Q+, tile order:      [m/128][3][8][16][32]
     // count-sketch error compressor (row sketch, one table row per bucket)
     int64_t w;                      // table rows (buckets) of this matrix

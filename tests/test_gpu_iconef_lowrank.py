@@ -1,6 +1,7 @@
 """GPU parity tests of improved contractive error feedback, version 1 (Algorithm 3, the quantiser twice) around the
 rank-r compressor: the library through the C ABI against oracle/iconef_ref.c, free-running over several steps, in
-both kernel families that have a two-vector form (whole blocks with rank 2/4/8, and any shape), both gradient types.
+the kernel families for whole blocks with rank 2/4/8 and for any shape, both gradient types; the bf16 matrix-core
+family (rank 32) has a test of its own below, with the criteria of the plain step's matrix-core tests.
 
 Per step and matrix: the gradient buffer is left as it was; the factors agree with the oracle's step from the same
 state to 1e-5; and both new vectors are, bit for bit, the oracle's two error steps applied to the
@@ -114,7 +115,7 @@ def test_staged_calls_give_the_fused_step(env):
                 B.conef_i_step_p(*a, c2, s2, buf["Q"], buf["P"], buf["ws"])
                 B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"])
                 B.conef_i_step_q(*a, c2, s2, buf["P"], buf["Q"], buf["ws"])
-                B.conef_i_step_err(*a, c2, s2, buf["P"], buf["Q"], t)
+                B.conef_i_step_err(*a, c2, s2, buf["P"], buf["Q"], buf["ws"], t)
             else:
                 B.conef_i_step(*a, c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], t)
         torch.cuda.synchronize()
@@ -124,15 +125,118 @@ def test_staged_calls_give_the_fused_step(env):
         assert torch.equal(a, b)
 
 
+MFMA_LAYOUTS = [
+    [(300, 256), (2200, 128), (45, 384)],           # ragged 128-row and 16-row tiles, more than one row tile of the Q+ pass
+    [(421, 1536), (128, 2304)],                     # runs of column blocks that are not a whole 16, an odd number of blocks
+]
+
+
+@pytest.mark.parametrize("case", range(len(MFMA_LAYOUTS)))
+def test_iconef_with_the_rank_r_compressor_on_the_matrix_cores(env, case):
+    """The bf16 matrix-core family (rank 32, bf16 gradients, 4-bit codes, blocks of 128).  Its factors are fp32 sums of
+    exact bf16 products, so, as for the plain step, nothing is bit for bit: per step and matrix the factors agree with
+    the oracle's step from the same state; the first vector is the oracle's quantisation of the residual formed from
+    the library's own factors, scales to 1e-6 (of the larger of the scale and the terms of the reconstruction) and
+    codes under the boundary rule; the second vector is judged the same way against the oracle's quantisation (random
+    stream mat | 2^31) of that residual minus the LIBRARY's decoded first vector, so that a first code excused at a
+    boundary does not count again (the block's largest element leaves a difference of the size of its own rounding
+    error there, so the windows of the second vector are relative to the first vector's magnitudes).  The oracle then
+    continues from the library's state."""
+    R, B, U, torch = env
+    import test_gpu_sketch as S
+
+    layout, rank, bits, block = MFMA_LAYOUTS[case], 32, 4, 128
+    seed = 4100 + case
+    model = B.Model(layout, rank, bits, block, wl.BF16, seed)
+    buf = model.alloc()
+    codes2, scales2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+    rng = np.random.default_rng([case, 41])
+    state = []
+    for l, (n, m) in enumerate(layout):
+        N = n * m
+        Q0 = rng.standard_normal((m, rank)).astype(np.float32)
+        state.append([np.zeros(R.n_words(N, bits), np.uint32), np.zeros(R.n_blocks(N, block), np.float32),
+                      np.zeros(R.n_words(N, bits), np.uint32), np.zeros(R.n_blocks(N, block), np.float32), Q0])
+        o = model.offsets[l]
+        buf["Q"][o["q_off"]:o["q_off"] + Q0.size] = torch.from_numpy(Q0.ravel()).to("cuda:0")
+    excused, second_live = 0, False
+    for t in range(3):
+        grads = [S._grad(rng, n, m, wl.BF16) for n, m in layout]
+        S._to_dev_grads(torch, model, buf, grads)
+        g_before = buf["grads"].clone()
+        print(f"[iconef rank-32 case {case}] step {t}: launching", flush=True)
+        B.conef_i_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, buf["Q"], buf["P"], buf["Q"],
+                       buf["ws"], t, model.stream_handle())
+        torch.cuda.synchronize()
+        for l, (n, m) in enumerate(layout):
+            N, o = n * m, model.offsets[l]
+            c1, s1, c2, s2, Q = state[l]
+            tag = f"rank-32 case {case} mat {l} step {t}"
+            P_gpu = buf["P"][o["p_off"]:o["p_off"] + n * rank].cpu().numpy().reshape(n, rank)
+            Q_gpu = buf["Q"][o["q_off"]:o["q_off"] + m * rank].cpu().numpy().reshape(m, rank)
+            got = [buf["codes"][o["word_off"]:o["word_off"] + c1.size].cpu().numpy().view(np.uint32),
+                   buf["scales"][o["scale_off"]:o["scale_off"] + s1.size].cpu().numpy(),
+                   codes2[o["word_off"]:o["word_off"] + c2.size].cpu().numpy().view(np.uint32),
+                   scales2[o["scale_off"]:o["scale_off"] + s2.size].cpu().numpy()]
+            Ph, Qn = R.i_step_matrix(grads[l], c1.copy(), s1.copy(), c2.copy(), s2.copy(), Q, rank, bits, block, seed, l, t)
+            assert U.rel_err(P_gpu, Ph) <= 1e-4, f"{tag}: P^ {U.rel_err(P_gpu, Ph)}"
+            assert U.rel_err(Q_gpu, Qn) <= 1e-4, f"{tag}: Q+ {U.rel_err(Q_gpu, Qn)}"
+            p = R.i_form_p(grads[l], c1, s1, c2, s2, bits, block).reshape(n, m)
+            x = R.residual(p, P_gpu, Q_gpu).ravel()
+            rec = (np.abs(P_gpu).astype(np.float64) @ np.abs(Q_gpu).astype(np.float64).T).astype(np.float32).ravel()
+            blk_rec = rec.reshape(-1, block).max(1)
+            # first error step
+            w1, ws1 = R.quantise(x, bits, block, seed, l, t)
+            assert np.all(np.abs(got[1] - ws1) <= 1e-6 * np.maximum(ws1, blk_rec)), f"{tag}: first scales"
+            excused += U.check_codes(got[0], w1, x, N, bits, block, seed, l, t, tag + " first", rec_oracle=rec)
+            # second error step, from the library's own first vector
+            x2 = x - R.decode(got[0], got[1], N, bits, block).ravel()
+            w2, ws2 = R.quantise(x2, bits, block, seed, l | 0x80000000, t)
+            # ... whose argument is a difference of terms as large as the residual itself (about 7 of its own levels):
+            # the 1e-6 windows are taken relative to the largest term, here the first vector's block max-norm
+            terms = np.maximum(rec, np.abs(x))
+            assert np.all(np.abs(got[3] - ws2) <= 1e-6 * np.maximum(ws2, terms.reshape(-1, block).max(1))), f"{tag}: second scales"
+            excused += U.check_codes(got[2], w2, x2, N, bits, block, seed, l | 0x80000000, t, tag + " second", rec_oracle=terms)
+            second_live = second_live or bool(np.any(got[2] != 0))
+            state[l] = [got[0].copy(), got[1].copy(), got[2].copy(), got[3].copy(), Q_gpu.copy()]
+        assert torch.equal(buf["grads"], g_before)
+    assert second_live
+    print(f"[iconef rank-32 case {case}] excused codes: {excused}", flush=True)
+    model.close()
+
+
+def test_staged_calls_give_the_fused_step_on_the_matrix_cores(env):
+    R, B, U, torch = env
+    layout = [(300, 256), (2100, 128)]
+    outs = []
+    for staged in (False, True):
+        model = B.Model(layout, 32, 4, 128, wl.BF16, 9)
+        buf = model.alloc()
+        c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+        r2 = np.random.default_rng(6)
+        buf["Q"].copy_(torch.from_numpy(r2.standard_normal(buf["Q"].numel()).astype(np.float32)).to("cuda:0"))
+        for t in range(3):
+            g = torch.from_numpy(r2.standard_normal(buf["grads"].numel()).astype(np.float32)).to("cuda:0")
+            buf["grads"].copy_(g.to(buf["grads"].dtype))
+            a = (model.ctx, buf["grads"], buf["codes"], buf["scales"])
+            if staged:
+                B.conef_i_step_p(*a, c2, s2, buf["Q"], buf["P"], buf["ws"])
+                B.conef_orthonormalise(model.ctx, buf["P"], buf["ws"])
+                B.conef_i_step_q(*a, c2, s2, buf["P"], buf["Q"], buf["ws"])
+                buf["ws"].zero_()           # the err stage call relies on nothing left in the workspace
+                B.conef_i_step_err(*a, c2, s2, buf["P"], buf["Q"], buf["ws"], t)
+            else:
+                B.conef_i_step(*a, c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], t)
+        torch.cuda.synchronize()
+        outs.append([x.clone() for x in (buf["codes"], buf["scales"], c2, s2, buf["Q"], buf["P"])])
+        assert bool(torch.any(c2 != 0))
+        model.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def test_rank_r_iconef_calls_reject_what_they_cannot_serve(env):
     R, B, U, torch = env
-    m = B.Model([(256, 256)], 32, 4, 128, wl.BF16, 1)       # the bf16 matrix-core family has no two-vector form
-    buf = m.alloc()
-    c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
-    with pytest.raises(B.ConefError) as e:
-        B.conef_i_step(m.ctx, buf["grads"], buf["codes"], buf["scales"], c2, s2, buf["Q"], buf["P"], buf["Q"], buf["ws"], 0)
-    assert e.value.code == B.ESTATE
-    m.close()
     m = B.Model([(64, 64)], 4, 4, 64, wl.F32, 1)
     buf = m.alloc()
     c2, s2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
