@@ -1,6 +1,6 @@
 """ctypes face of the CPU oracle: oracle/conef_ref.c (the step of Algorithm 2), sketch_ref.c (count sketch, partial
-update), randblock_ref.c (random block, scaled sign), iconef_ref.c (Algorithm 3, version 1) and randk_ref.c (random-k),
-built into one shared library with gcc.
+update), randblock_ref.c (random block, scaled sign), iconef_ref.c (Algorithm 3, version 1), randk_ref.c (random-k) and
+iconef2_ref.c (Algorithm 3, version 2), built into one shared library with gcc.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
 bench.py's cpu_baseline leg.  The product package never imports this module.
@@ -24,6 +24,7 @@ _SRC_SKETCH = os.path.join(_HERE, "sketch_ref.c")
 _SRC_RB = os.path.join(_HERE, "randblock_ref.c")
 _SRC_I = os.path.join(_HERE, "iconef_ref.c")
 _SRC_RK = os.path.join(_HERE, "randk_ref.c")
+_SRC_I2 = os.path.join(_HERE, "iconef2_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -32,10 +33,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK))
+    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -125,6 +126,12 @@ def lib() -> ctypes.CDLL:
         L.ref_cs_rk_step_matrix.restype = None
         L.ref_i_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
         L.ref_i_rk_step_matrix.restype = None
+        L.ref_i2_start.argtypes = [u64, u32, u64, i64, i64]
+        L.ref_i2_start.restype = i64
+        L.ref_i2_rb_step_matrix.argtypes = [vp, i32, i64, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp]
+        L.ref_i2_rb_step_matrix.restype = None
+        L.ref_i2_rk_step_matrix.argtypes = [vp, i32, i64, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp]
+        L.ref_i2_rk_step_matrix.restype = None
         L.ref_i_error.argtypes = [vp, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp]
         L.ref_i_error.restype = None
         L.ref_i_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -563,6 +570,35 @@ def i_rk_step_matrix(g, codes, scales, codes2, scales2, G: int, bits: int, block
     lib().ref_i_rk_step_matrix(_p(ga), dt, N, G, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
                                _p(scales2), _p(delta), _p(work))
     return delta
+
+
+# ---------------------------------------------------------------- iConEF version 2 (oracle/iconef2_ref.c)
+def i2_start(seed: int, mat: int, step: int, N: int, ke: int) -> int:
+    """First coordinate of the block the first error compressor keeps when it runs at `step` (step taken mod 2^64)."""
+    return int(lib().ref_i2_start(seed, mat, step % (1 << 64), N, ke))
+
+
+def _i2_step(fn, g, e_vals, codes, scales, arg, n_delta: int, bits: int, block: int, seed: int, mat: int, step: int):
+    ga, dt = grad_array(g)
+    N = ga.size
+    _check_state(codes, scales)
+    assert e_vals.dtype == np.float32 and e_vals.flags.c_contiguous and 0 <= e_vals.size <= N
+    delta = np.empty(n_delta, np.float32)
+    work = np.empty(N, np.float32)
+    fn(_p(ga), dt, N, arg, e_vals.size, bits, block, seed, mat, step, _p(e_vals), _p(codes), _p(scales), _p(delta), _p(work))
+    return delta
+
+
+def i2_rb_step_matrix(g, e_vals, codes, scales, k: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """One iConEF-v2 step, random block of k as gradient compressor, random block of e_vals.size as first error
+    compressor; e_vals, codes, scales updated in place; returns Delta (k values)."""
+    return _i2_step(lib().ref_i2_rb_step_matrix, g, e_vals, codes, scales, k, k, bits, block, seed, mat, step)
+
+
+def i2_rk_step_matrix(g, e_vals, codes, scales, G: int, bits: int, block: int, seed: int, mat: int, step: int):
+    """The same with the stratified random-k gradient compressor (strata of G); returns Delta."""
+    return _i2_step(lib().ref_i2_rk_step_matrix, g, e_vals, codes, scales, G, rk_count(np.asarray(g).size, G), bits, block,
+                    seed, mat, step)
 
 
 def i_error(x, codes, scales, codes2, scales2, bits: int, block: int, seed: int, mat: int, step: int) -> None:
