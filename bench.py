@@ -317,8 +317,9 @@ def run_scaled_sign(w, reps: int = 10):
 def run_random_k(w, group: int = 10, reps: int = 10):
     """Times one step with the random-k gradient compressor (stratified: one coordinate kept of every `group`
     consecutive ones) in place of the rank-r one: with the workload's quantiser (beta = 0), with the count sketch (fp16
-    table, keep 0.2, beta 0.9) and with iConEF-v1 (the quantiser twice).  One streaming pass each; HIP events on the
-    launch stream."""
+    table, keep 0.2, beta 0.9), with iConEF-v1 (the quantiser twice) and with iConEF-v2 (first error vector: a random block
+    of 5 % of every matrix kept in fp32, as large as the appendix experiment's; second: the quantiser).  One streaming pass
+    each; HIP events on the launch stream."""
     import torch
 
     from paper_2312_08538_amd import binding as B
@@ -327,7 +328,7 @@ def run_random_k(w, group: int = 10, reps: int = 10):
     G = 4 if w.grad_dtype == 0 else 2
     kept = sum(-(-(n * m) // group) for n, m in w.layout)
     out = {}
-    for kind in ("quantiser", "count_sketch", "iconef_v1"):
+    for kind in ("quantiser", "count_sketch", "iconef_v1", "iconef_v2"):
         if kind == "count_sketch":
             ws = wl.sketch_rows(w.layout, 0.2)
             model = B.SketchModel(w.layout, ws, w.rank, 0.9, B.TABLE_F16, w.grad_dtype, w.lib_seed)
@@ -340,6 +341,11 @@ def run_random_k(w, group: int = 10, reps: int = 10):
         delta = torch.zeros(B.conef_rk_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
         if kind == "iconef_v1":
             codes2, scales2 = torch.zeros_like(buf["codes"]), torch.zeros_like(buf["scales"])
+        if kind == "iconef_v2":
+            keep_e = [max(1, (n * m) // 20) for n, m in w.layout]
+            B.conef_i2_configure(model.ctx, keep_e)
+            e_bufs = [torch.zeros(B.conef_i2_sizes(model.ctx)["e_elems"], dtype=torch.float32, device="cuda:0") for _ in range(2)]
+            state_bytes += 4 * sum(keep_e)
         wl.device_fill_gradients(w, 0, buf["grads"], [o["grad_off"] for o in model.offsets])
         st = B.Model.stream_handle()
 
@@ -348,8 +354,11 @@ def run_random_k(w, group: int = 10, reps: int = 10):
                 B.conef_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
             elif kind == "count_sketch":
                 B.conef_cs_rk_step(model.ctx, buf["grads"], buf["table"], delta, t, st)
-            else:
+            elif kind == "iconef_v1":
                 B.conef_i_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
+            else:
+                B.conef_i2_rk_step(model.ctx, buf["grads"], e_bufs[t % 2], e_bufs[(t + 1) % 2], buf["codes"], buf["scales"],
+                                   delta, t, st)
 
         for t in range(2):
             one(t)
@@ -371,6 +380,8 @@ def run_random_k(w, group: int = 10, reps: int = 10):
         del buf, delta
         if kind == "iconef_v1":
             del codes2, scales2
+        if kind == "iconef_v2":
+            del e_bufs
         torch.cuda.empty_cache()
     return out
 
@@ -557,7 +568,7 @@ def main():
                          "compressors) on --workload and print its line")
     ap.add_argument("--random-k", action="store_true",
                     help="time only the step with the random-k gradient compressor (stratified, one coordinate of every "
-                         "ten kept; quantiser, count sketch and iConEF-v1) on --workload and print its line")
+                         "ten kept; quantiser, count sketch, iConEF-v1 and iConEF-v2) on --workload and print its line")
     ap.add_argument("--iconef", action="store_true",
                     help="time only the iConEF-v1 step (two compressed error vectors, the quantiser twice) with the "
                          "random-block and scaled-sign gradient compressors on --workload and print its line")

@@ -294,6 +294,40 @@ int conef_i_ss_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
 int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *err_scales, uint32_t *err2_codes,
                     float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
 
+/* ---- Improved contractive error feedback, version 2 (Algorithm 3 of Section 3.2 with its "else" branch), around the
+ * random-block and random-k gradient compressors: the FIRST error compressor is a contractive compressor of the
+ * gradient compressor's class (Assumption 4), the second is the error compressor C.  Per matrix, with
+ * x = p - Delta:
+ *   p     = eta*g + e~ + q
+ *   Delta = the gradient compressor's kept coordinates of p (conef_rb_step / conef_rk_step)
+ *   e~+   = Q(x): the keep_e[l] consecutive coordinates [s, s + keep_e[l]) of x as they are (fp32), nothing else;
+ *           s = floor(r (N - keep_e + 1) / 2^64), r = the first 64 bits of the Philox4x32-10 call with counter
+ *           (l, 2^32 - 2, lo32(step), hi32(step)) and the context's key (conef_i2_start returns it, host)
+ *   q+    = C(x - e~+): the quantiser of conef_step (random numbers of matrix word l), 0 on both kept sets
+ * (the appendix experiment picks the coordinates of e~+ by magnitude instead; that selection is not built).
+ * e~ is stored as its kept values only: the accumulation at `step` adds them back on the block drawn at step - 1
+ * (mod 2^64), p_j = fma(d, c_j, g_j) + e~_i there (one fp32 addition) and fma(d, c_j, g_j) elsewhere.  The state is
+ * keep_e fp32 values plus one compressed vector per matrix.
+ *   conef_i2_configure  host only; keep_e[n_mats] with 0 <= keep_e[l] <= rows*cols (CONEF_EINVAL otherwise; 0: the step
+ *                       is conef_rb_step / conef_rk_step); may be called again
+ *   conef_i2_sizes      e_elems = length of the flat buffer of first error vectors (at least 64)
+ *   conef_i2_offsets    matrix l's values start at e_off (a multiple of 64) and are keep_e many
+ *   e_in                device, in: the first error vectors left by the previous step (all zero before the first)
+ *   e_out               device, out: the new ones; another buffer than e_in (CONEF_EINVAL), since the two blocks of a
+ *                       matrix overlap in general: the caller swaps the two from step to step
+ *   err_codes, err_scales   device, in/out: q, as for conef_rb_step;  delta_out: as for conef_rb_step / conef_rk_step
+ * For quantiser contexts with beta = 0 after conef_i2_configure and conef_rb_configure (conef_i2_rb_step) or
+ * conef_rk_configure (conef_i2_rk_step): CONEF_ESTATE otherwise.  Alignment (e_in, e_out: 4 bytes), asynchrony and
+ * errors as for conef_rb_step. */
+int conef_i2_configure(conef_ctx *ctx, const int64_t *keep_e);
+int conef_i2_sizes(const conef_ctx *ctx, size_t *e_elems);
+int conef_i2_offsets(const conef_ctx *ctx, int mat, size_t *e_off, int64_t *keep_e);
+int conef_i2_start(const conef_ctx *ctx, int mat, uint64_t step, int64_t *start);
+int conef_i2_rb_step(conef_ctx *ctx, const void *grads, const float *e_in, float *e_out, uint32_t *err_codes, float *err_scales,
+                     float *delta_out, uint64_t step, void *hip_stream);
+int conef_i2_rk_step(conef_ctx *ctx, const void *grads, const float *e_in, float *e_out, uint32_t *err_codes, float *err_scales,
+                     float *delta_out, uint64_t step, void *hip_stream);
+
 /* ---- The same (Algorithm 3, version 1, the quantiser twice) around the rank-r compressor of conef_step:
  *   p = g + e~ + q,  Delta = P^ Q+^T (one power-iteration step on p),  e~+ = C(p - Delta),  q+ = C(p - Delta - e~+),
  * with the arithmetic stated above (p_j = fma(d2, c2_j, fma(d1, c1_j, g_j))).  The stage calls mirror those of

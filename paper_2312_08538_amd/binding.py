@@ -25,6 +25,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
            "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step", "conef_i_step_p", "conef_i_step_q", "conef_i_step_err", "conef_i_step",
+           "conef_i2_configure", "conef_i2_sizes", "conef_i2_offsets", "conef_i2_start", "conef_i2_rb_step", "conef_i2_rk_step",
            "conef_rk_configure", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
            "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
@@ -78,6 +79,12 @@ def lib() -> ctypes.CDLL:
     L.conef_i_step_q.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.conef_i_step_err.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i2_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_i2_sizes.argtypes = [vp, szp]
+    L.conef_i2_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_i2_start.argtypes = [vp, i32, u64, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_i2_rb_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
+    L.conef_i2_rk_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_rk_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rk_sizes.argtypes = [vp, szp]
     L.conef_rk_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
@@ -273,6 +280,40 @@ def conef_rk_step(ctx, grads, err_codes, err_scales, delta_out, step: int, strea
 
 def conef_cs_rk_step(ctx, grads, table, delta_out, step: int, stream=0):
     _check(lib().conef_cs_rk_step(ctx, _ptr(grads), _ptr(table), _ptr(delta_out), step, stream), "conef_cs_rk_step")
+
+
+# improved contractive error feedback, version 2: the first error vector is a random block kept as it is
+def conef_i2_configure(ctx, keep_e: Sequence[int]) -> None:
+    arr = (ctypes.c_int64 * max(1, len(keep_e)))(*[int(x) for x in keep_e])
+    _check(lib().conef_i2_configure(ctx, arr), "conef_i2_configure")
+
+
+def conef_i2_sizes(ctx) -> dict:
+    v = ctypes.c_size_t()
+    _check(lib().conef_i2_sizes(ctx, ctypes.byref(v)), "conef_i2_sizes")
+    return {"e_elems": int(v.value)}
+
+
+def conef_i2_offsets(ctx, mat: int) -> dict:
+    off, keep = ctypes.c_size_t(), ctypes.c_int64()
+    _check(lib().conef_i2_offsets(ctx, mat, ctypes.byref(off), ctypes.byref(keep)), "conef_i2_offsets")
+    return {"e_off": int(off.value), "keep_e": int(keep.value)}
+
+
+def conef_i2_start(ctx, mat: int, step: int) -> int:
+    v = ctypes.c_int64()
+    _check(lib().conef_i2_start(ctx, mat, step % (1 << 64), ctypes.byref(v)), "conef_i2_start")
+    return int(v.value)
+
+
+def conef_i2_rb_step(ctx, grads, e_in, e_out, err_codes, err_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_i2_rb_step(ctx, _ptr(grads), _ptr(e_in), _ptr(e_out), _ptr(err_codes), _ptr(err_scales), _ptr(delta_out),
+                                  step, stream), "conef_i2_rb_step")
+
+
+def conef_i2_rk_step(ctx, grads, e_in, e_out, err_codes, err_scales, delta_out, step: int, stream=0):
+    _check(lib().conef_i2_rk_step(ctx, _ptr(grads), _ptr(e_in), _ptr(e_out), _ptr(err_codes), _ptr(err_scales), _ptr(delta_out),
+                                  step, stream), "conef_i2_rk_step")
 
 
 def conef_set_beta(ctx, beta: float) -> None:

@@ -670,6 +670,77 @@ int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+// ---------------------------------------------------------------- iConEF version 2 around the element-wise compressors
+int conef_i2_configure(conef_ctx *ctx, const int64_t *keep_e)
+{
+    if (!ctx || !keep_e) return CONEF_EINVAL;
+    if (ctx->plan.sketch) return CONEF_ESTATE;
+    int rc = configure_i2(ctx->plan, keep_e);
+    if (rc) return rc;
+    ctx->rb_uploaded = false;       // the descriptors are uploaded again before the next step
+    return CONEF_OK;
+}
+
+int conef_i2_sizes(const conef_ctx *ctx, size_t *e_elems)
+{
+    if (!ctx) return CONEF_EINVAL;
+    if (!ctx->plan.i2_configured) return CONEF_ESTATE;
+    if (e_elems) *e_elems = ctx->plan.i2_elems;
+    return CONEF_OK;
+}
+
+int conef_i2_offsets(const conef_ctx *ctx, int mat, size_t *e_off, int64_t *keep_e)
+{
+    if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (!ctx->plan.i2_configured) return CONEF_ESTATE;
+    if (e_off) *e_off = (size_t)ctx->plan.mats[mat].i2_off;
+    if (keep_e) *keep_e = ctx->plan.mats[mat].i2_k;
+    return CONEF_OK;
+}
+
+int conef_i2_start(const conef_ctx *ctx, int mat, uint64_t step, int64_t *start)
+{
+    if (!ctx || !start || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    if (!ctx->plan.i2_configured) return CONEF_ESTATE;
+    const MatDesc &d = ctx->plan.mats[mat];
+    *start = i2_block_start(ctx->plan.seed, (uint32_t)mat, step, d.N, d.i2_k);
+    return CONEF_OK;
+}
+
+namespace {
+int i2_step_impl(conef_ctx *ctx, const void *grads, const float *e_in, float *e_out, uint32_t *err_codes, float *err_scales,
+                 float *delta_out, uint64_t step, void *hip_stream, bool strata)
+{
+    if (!ctx || !grads || !e_in || !e_out || !err_codes || !err_scales || !delta_out) return CONEF_EINVAL;
+    if (ctx->plan.sketch || !ctx->plan.i2_configured || ctx->plan.beta != 0.0f ||
+        (strata ? ctx->plan.rk_delta_elems : ctx->plan.rb_delta_elems) == 0)
+        return CONEF_ESTATE;
+    if (misaligned(grads, 16) || misaligned(err_codes, 16) || misaligned(err_scales, 4) || misaligned(delta_out, 4) ||
+        misaligned(e_in, 4) || misaligned(e_out, 4) || e_in == e_out)
+        return CONEF_EINVAL;
+    int rc = ensure_uploaded(ctx);
+    if (rc) return rc;
+    if ((rc = ensure_rb_uploaded(ctx))) return rc;
+    DevicePlan dp = ctx->dev;
+    dp.i2_in = e_in;
+    dp.i2_out = e_out;
+    return hip_rc(launch_rb_step(dp, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, strata,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+}  // namespace
+
+int conef_i2_rb_step(conef_ctx *ctx, const void *grads, const float *e_in, float *e_out, uint32_t *err_codes, float *err_scales,
+                     float *delta_out, uint64_t step, void *hip_stream)
+{
+    return i2_step_impl(ctx, grads, e_in, e_out, err_codes, err_scales, delta_out, step, hip_stream, false);
+}
+
+int conef_i2_rk_step(conef_ctx *ctx, const void *grads, const float *e_in, float *e_out, uint32_t *err_codes, float *err_scales,
+                     float *delta_out, uint64_t step, void *hip_stream)
+{
+    return i2_step_impl(ctx, grads, e_in, e_out, err_codes, err_scales, delta_out, step, hip_stream, true);
+}
+
 int conef_cs_rk_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
 {
     if (!ctx || !grads || !table || !delta_out) return CONEF_EINVAL;

@@ -67,6 +67,17 @@ __device__ __forceinline__ int64_t random_block_start(uint32_t mat, uint32_t ste
     return (int64_t)__umul64hi(r, (uint64_t)(N - k + 1));
 }
 
+// The same for the block that the first error compressor of Algorithm 3, version 2, keeps (ke coordinates): counter
+// (matrix, ~0 - 1, step), which neither the gradient compressor's block nor an element draw uses.
+__device__ __forceinline__ int64_t i2_block_start(uint32_t mat, uint32_t step_lo, uint32_t step_hi, uint32_t seed_lo,
+                                                  uint32_t seed_hi, int64_t N, int64_t ke)
+{
+    uint32_t out[4];
+    philox4x32_10(mat, 0xFFFFFFFEu, step_lo, step_hi, seed_lo, seed_hi, out);
+    const uint64_t r = (uint64_t)out[0] | ((uint64_t)out[1] << 32);
+    return (int64_t)__umul64hi(r, (uint64_t)(N - ke + 1));
+}
+
 // Random-k gradient compressor, stratified: the flat index range of a matrix is cut into strata of g consecutive
 // coordinates (the last one may be shorter) and one coordinate of every stratum is kept:
 //   stratum i keeps  i g + floor(u_i len_i / 2^32),  len_i = min(g, N - i g),

@@ -38,6 +38,10 @@ struct DevicePlan {
     // every other call; set in a copy of the plan by the launchers of the two-vector passes.
     const uint32_t *i_codes = nullptr;
     const float *i_scales = nullptr;
+    // Algorithm 3, version 2, around an element-wise gradient compressor: the first error vector (a random block of
+    // every matrix, MatDesc::i2_k values at i2_off) as it comes in and where the new one goes (another buffer)
+    const float *i2_in = nullptr;
+    float *i2_out = nullptr;
 };
 
 // Optional pair of events recorded immediately before and after a stage's main kernel.

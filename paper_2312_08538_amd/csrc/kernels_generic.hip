@@ -278,7 +278,7 @@ template <int MODE, bool TWO>
 __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
                                              const float *scales, int64_t j, int64_t start, float *delta, bool write,
                                              float c, uint32_t *sign_words, const uint32_t *codes2, const float *scales2,
-                                             int mat, uint32_t step_lo, uint32_t step_hi)
+                                             int mat, uint32_t step_lo, uint32_t step_hi, int64_t e_from, int64_t e_to)
 {
     const int W = 32 / dp.bits;
     const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
@@ -303,6 +303,25 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
     }
     if (MODE == kModeBlock || MODE == kModeStrata) {
         int64_t slot;
+        if (dp.i2_out) {
+            // Algorithm 3, version 2: p = g + q, + e~ on the block e~ was taken from; Delta = p on the kept coordinates;
+            // e~+ = p - Delta on the new block; the quantiser gets what is left
+            float pv = __builtin_fmaf(dstep, (float)q, g);
+            if (j >= e_from && j < e_from + d.i2_k) pv = pv + dp.i2_in[d.i2_off + (j - e_from)];
+            const bool mine = j >= e_to && j < e_to + d.i2_k;
+            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+                if (write) {
+                    delta[slot] = pv;
+                    if (mine) dp.i2_out[d.i2_off + (j - e_to)] = 0.0f;
+                }
+                return 0.0f;
+            }
+            if (mine) {
+                if (write) dp.i2_out[d.i2_off + (j - e_to)] = pv;
+                return 0.0f;
+            }
+            return pv;
+        }
         if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
             if (write) delta[slot] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
             return dp.beta * (dstep * (float)q);
@@ -329,6 +348,13 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
     const float s_f = (float)((1 << (bits - 1)) - 1);
     const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    // Algorithm 3, version 2: the block the incoming first error vector was taken from (drawn one step ago) and the new one's
+    int64_t e_from = 0, e_to = 0;
+    if ((MODE == kModeBlock || MODE == kModeStrata) && !TWO && dp.i2_out) {
+        const uint64_t prev = (((uint64_t)step_hi << 32) | step_lo) - 1;
+        e_from = i2_block_start((uint32_t)it.mat, (uint32_t)prev, (uint32_t)(prev >> 32), dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
+        e_to = i2_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
+    }
     double l1 = 0.0;
     for (int t = 0; t < it.b; ++t) {
         const int64_t blk = (int64_t)it.a + wave + 4 * t;
@@ -337,7 +363,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
         float a = 0.0f;
         for (int e = lane; e < cnt; e += 64) {
-            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
+            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
             if (MODE == kModeNorm) l1 += (double)fabsf(v);
             a = fmaxf(a, fabsf(v));
         }
@@ -350,7 +376,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             const float dnew = a * inv_levels(bits);
             // argument of the second rounding: x minus the decoded first rounding of x
             auto second_argument = [&](int64_t j, uint32_t &f1) {
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 f1 = quantise_field(x, inv16, draw16(out, (int)(j & 7)), mask);
@@ -396,7 +422,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             uint32_t field = 0;
             if (e < cnt && a > 0.0f) {
                 const int64_t j = j0 + e;
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));

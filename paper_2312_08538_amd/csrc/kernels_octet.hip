@@ -665,7 +665,11 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 // as MODE 0 with the kept coordinates scattered; the kept values go to the Delta buffer in stratum order.
 constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
 
-template <bool BF16, int BITS, int MODE, bool TWO>
+// V2: improved contractive error feedback, version 2 (Algorithm 3, no beta), for MODE 0 and 3: the first error vector
+// is a random block of every matrix kept as it is (i2_k values, dp.i2_in; taken from the block drawn one step ago), the
+// compressed vector is q: p = g + q, + e~ on that block; Delta = p on the kept coordinates; e~+ = p - Delta on the block
+// drawn now (to dp.i2_out, another buffer: other waves still read the old one); q+ = C(p - Delta - e~+).
+template <bool BF16, int BITS, int MODE, bool TWO, bool V2>
 __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
                                                   float *__restrict__ delta, uint32_t step_lo, uint32_t step_hi,
                                                   uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws,
@@ -680,6 +684,12 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
     const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
     const int64_t stop = MODE == kModeBlock ? start + d.rb_k : 0;
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    int64_t e_from = 0, e_to = 0;
+    if (V2) {
+        const uint64_t prev = (((uint64_t)step_hi << 32) | step_lo) - 1;
+        e_from = i2_block_start((uint32_t)it.mat, (uint32_t)prev, (uint32_t)(prev >> 32), dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
+        e_to = i2_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
+    }
     double l1 = 0.0;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     // The last run of a matrix may be short: octets at or beyond the end re-read the last octet and store
@@ -759,19 +769,43 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
             }
         }
         if (MODE == kModeNorm) continue;
+        if (V2) {
+            // + e~ where it was taken from
+            const int64_t lo = e_from - o * 8, hi = lo + d.i2_k;
+            if (hi > 0 && lo < 8) {
+                const float *src = dp.i2_in + d.i2_off - lo;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e >= lo && e < hi) x[e] = x[e] + src[e];
+            }
+        }
         // ... then the kept coordinates: Delta = p there, and beta e (plain) or nothing (two vectors) is left
         if (SPARSE && kbits != 0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if ((kbits >> e) & 1u) {
                     const int64_t slot = kslot + __popc(kbits & ((1u << e) - 1u));
-                    if (TWO) {
+                    if (TWO || V2) {
                         if (valid) delta[slot] = x[e];
                         x[e] = 0.0f;
                     } else {
                         const float qf = code_of(e);
                         if (valid) delta[slot] = __builtin_fmaf(dpart, qf, g[e]);
                         x[e] = dp.beta * (dstep * qf);
+                    }
+                }
+            }
+        }
+        if (V2) {
+            // e~+: what is left on the block drawn now, as it is (0 where Delta has taken it)
+            const int64_t lo = e_to - o * 8, hi = lo + d.i2_k;
+            if (hi > 0 && lo < 8) {
+                float *dst = dp.i2_out + d.i2_off - lo;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (e >= lo && e < hi) {
+                        if (valid) dst[e] = x[e];
+                        x[e] = 0.0f;
                     }
                 }
             }
@@ -826,19 +860,24 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
     if (dp.n_rb <= 0) return;
     const dim3 grid((dp.n_rb + 3) / 4);
     const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
-    const bool two = codes2 != nullptr;
-#define CONEF_STREAM_LAUNCH(BF, B, M, T)                                                                                           \
-    hipLaunchKernelGGL((k_rb_octet<BF, B, M, T>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi, sign_words,     \
+    const bool two = codes2 != nullptr, v2 = dp.i2_out != nullptr;
+#define CONEF_STREAM_LAUNCH(BF, B, M, T, V)                                                                                        \
+    hipLaunchKernelGGL((k_rb_octet<BF, B, M, T, V>), grid, dim3(256), 0, st, dp, grads, codes, scales, delta, lo, hi, sign_words,  \
                        c_scale, ws, codes2, scales2)
 #define CONEF_STREAM_MODE(BF, B, M)                                                                                                \
     do {                                                                                                                           \
-        if (two) CONEF_STREAM_LAUNCH(BF, B, M, true);                                                                              \
-        else CONEF_STREAM_LAUNCH(BF, B, M, false);                                                                                 \
+        if (two) CONEF_STREAM_LAUNCH(BF, B, M, true, false);                                                                       \
+        else CONEF_STREAM_LAUNCH(BF, B, M, false, false);                                                                          \
+    } while (0)
+#define CONEF_STREAM_MODE_V2(BF, B, M)                                                                                             \
+    do {                                                                                                                           \
+        if (v2 && !two) CONEF_STREAM_LAUNCH(BF, B, M, false, true);                                                                \
+        else CONEF_STREAM_MODE(BF, B, M);                                                                                          \
     } while (0)
 #define CONEF_STREAM_CASE(BF, B)                                                                                                   \
     case ((BF ? 1 : 0) << 8) | B:                                                                                                  \
-        if (mode == kModeBlock) CONEF_STREAM_MODE(BF, B, kModeBlock);                                                              \
-        else if (mode == kModeStrata) CONEF_STREAM_MODE(BF, B, kModeStrata);                                                       \
+        if (mode == kModeBlock) CONEF_STREAM_MODE_V2(BF, B, kModeBlock);                                                           \
+        else if (mode == kModeStrata) CONEF_STREAM_MODE_V2(BF, B, kModeStrata);                                                    \
         else if (mode == kModeNorm) CONEF_STREAM_MODE(BF, B, kModeNorm);                                                           \
         else CONEF_STREAM_MODE(BF, B, kModeSign);                                                                                  \
         break;
@@ -853,6 +892,7 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
     }
 #undef CONEF_STREAM_LAUNCH
 #undef CONEF_STREAM_MODE
+#undef CONEF_STREAM_MODE_V2
 #undef CONEF_STREAM_CASE
 }
 

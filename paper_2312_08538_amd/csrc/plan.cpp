@@ -85,6 +85,33 @@ int configure_random_block(Plan &plan, const int64_t *keep)
     return kOk;
 }
 
+int64_t i2_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t ke)
+{
+    // counter (matrix, ~0 - 1, step): neither the gradient compressor's block nor an element draw uses it
+    uint32_t out[4];
+    host_philox4x32_10(mat, 0xFFFFFFFEu, (uint32_t)step, (uint32_t)(step >> 32), seed, out);
+    const uint64_t r = (uint64_t)out[0] | ((uint64_t)out[1] << 32);
+    return (int64_t)(((unsigned __int128)r * (unsigned __int128)(uint64_t)(N - ke + 1)) >> 64);
+}
+
+int configure_i2(Plan &plan, const int64_t *keep_e)
+{
+    if (!keep_e) return kEinval;
+    const int n_mats = (int)plan.mats.size();
+    for (int l = 0; l < n_mats; ++l)
+        if (keep_e[l] < 0 || keep_e[l] > plan.mats[l].N) return kEinval;
+    int64_t off = 0;
+    for (int l = 0; l < n_mats; ++l) {
+        MatDesc &d = plan.mats[l];
+        d.i2_k = keep_e[l];
+        d.i2_off = off;
+        off += round_up(keep_e[l], kAlign);
+    }
+    plan.i2_elems = (size_t)(off > 0 ? off : kAlign);
+    plan.i2_configured = true;
+    return kOk;
+}
+
 int64_t random_k_index(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t G, int64_t i)
 {
     // counter (stratum / 4, matrix + 2^30, step): four strata per call, word i % 4

@@ -61,6 +61,9 @@ struct MatDesc {
     uint32_t rk_pad;
     uint64_t rk_magic;              // floor(2^64 / rk_g) + 1: j / rk_g = mulhi64(j, rk_magic) for j < 2^32 (unused for rk_g = 1)
     int64_t rk_delta_off;           // offset of the matrix's kept values (one per stratum) in the flat Delta buffer
+    // Algorithm 3, version 2: the first error vector is a random block of the matrix, kept as it is
+    int64_t i2_k;                   // coordinates it keeps (0: none)
+    int64_t i2_off;                 // offset of the matrix's kept values in the flat buffer of first error vectors
     // element-wise gradient compressors (random block, scaled sign): the matrix's items in its stream table
     int32_t st_first, st_slots;     // index of its first item; partial-sum slots (one per wave that works on it)
     int32_t st_atomic;              // its sign bits are set with atomic ORs (kernels for any shape): cleared first
@@ -116,6 +119,8 @@ struct Plan {
     size_t sign_words = 0;
     size_t rb_delta_elems = 0;      // set by configure_random_block
     size_t rk_delta_elems = 0;      // set by configure_random_k
+    size_t i2_elems = 0;            // set by configure_i2 (never 0 once configured)
+    bool i2_configured = false;
     std::vector<WorkItem> rb_items;     // matrices of whole power-of-two blocks: (mat, first run of 512 elements, runs), one item per wave
     std::vector<WorkItem> rb_g_items;   // any other matrix: (mat, first block, blocks per wave), 4 waves per item
 };
@@ -146,6 +151,9 @@ int64_t random_k_index(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, in
 
 // First coordinate of the kept block of a matrix of N elements at `step` (Philox4x32-10 of (matrix, ~0, step)).
 int64_t random_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t k);
+// Algorithm 3, version 2: sizes of the first error vectors (keep_e[l] in 0 .. N_l) and where each one's block starts
+int configure_i2(Plan &plan, const int64_t *keep_e);
+int64_t i2_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t ke);
 
 // Bucket and sign of a row (Philox4x32-10 of (row, matrix) keyed by the seed).
 void sketch_hash(uint64_t seed, uint32_t mat, uint32_t row, int64_t w, int32_t *bucket, bool *negative);

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_function():
     header = open(os.path.join(ROOT, "include", "conef.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(conef_[a-z_]+)\s*\(", header)))
+    declared = sorted(set(re.findall(r"\b(conef_[a-z0-9_]+)\s*\(", header)))
     assert declared, "no declarations found"
     L = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
@@ -302,6 +302,49 @@ def test_random_k_layout_and_kept_coordinates_match_the_oracle(ref):
     with pytest.raises(B.ConefError) as e:
         B.conef_rk_configure(ctx, [10])
     assert e.value.code == B.EINVAL
+    B.conef_destroy(ctx)
+
+
+def test_first_error_vector_layout_and_start_match_the_oracle(ref):
+    """Algorithm 3, version 2: sizes, offsets and block starts of the first error vectors (host side)."""
+    layout = [(64, 147), (512, 1024), (3, 5)]
+    keep_e = [470, 0, 15]
+    seed = 0xC0FFEE123
+    ctx = B.conef_init(layout, 2, 4, 128, B.BF16, seed)
+    L = B.lib()
+    assert L.conef_i2_sizes(ctx, None) == B.ESTATE                          # not configured yet
+    assert L.conef_i2_rb_step(ctx, 512, 512, 1024, 512, 512, 512, 0, 0) == B.ESTATE
+    B.conef_i2_configure(ctx, keep_e)
+    off = 0
+    for l, (n, m) in enumerate(layout):
+        o = B.conef_i2_offsets(ctx, l)
+        assert (o["e_off"], o["keep_e"]) == (off, keep_e[l])
+        off += (keep_e[l] + 63) // 64 * 64
+        for step in (0, 1, 7, 2 ** 33 + 1, 2 ** 64 - 1):
+            s = B.conef_i2_start(ctx, l, step)
+            assert s == ref.i2_start(seed, l, step, n * m, keep_e[l]) and 0 <= s <= n * m - keep_e[l]
+    assert B.conef_i2_sizes(ctx)["e_elems"] == off
+    B.conef_check_plan(ctx)
+    for bad in ([-1, 1, 1], [1, 1, 16]):
+        with pytest.raises(B.ConefError) as e:
+            B.conef_i2_configure(ctx, bad)
+        assert e.value.code == B.EINVAL
+    assert L.conef_i2_configure(ctx, None) == B.EINVAL
+    # null, misaligned and doubled buffers (after the gradient compressor is configured, before any launch)
+    B.conef_rb_configure(ctx, [10, 10, 1])
+    A = 512
+    assert L.conef_i2_rb_step(ctx, A, 0, 1024, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_i2_rb_step(ctx, A, A, A, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_i2_rb_step(ctx, A, 514, 1024, A, A, A, 0, 0) == B.EINVAL
+    assert L.conef_i2_rk_step(ctx, A, A, 1024, A, A, A, 0, 0) == B.ESTATE     # random-k not configured
+    B.conef_destroy(ctx)
+    sk = B.conef_cs_init(layout, [8, 100, 3], 2, 0.5, B.TABLE_F16, B.BF16, seed)
+    assert L.conef_i2_configure(sk, (ctypes.c_int64 * 3)(1, 1, 1)) == B.ESTATE
+    B.conef_destroy(sk)
+    # all zero: the buffer is still a valid allocation
+    ctx = B.conef_init([(8, 8)], 2, 4, 8, B.F32, 1)
+    B.conef_i2_configure(ctx, [0])
+    assert B.conef_i2_sizes(ctx)["e_elems"] == 64
     B.conef_destroy(ctx)
 
 
