@@ -13,7 +13,10 @@
  *     aborts or synchronises the stream.  conef_strerror() names a code.
  *   - "device" pointers are HIP device memory owned by the caller (allocated, kept alive
  *     until the stream has drained, and freed by the caller).  The library owns only the
- *     context and the small device-side tables it uploads on first use.
+ *     context and the small device-side tables it uploads on first use: the first call that
+ *     launches on a context allocates them and copies them with a blocking hipMemcpy (the
+ *     first one after a conef_*_configure call copies the descriptors again); no other call
+ *     allocates or blocks.
  *   - A model is a list of matrices ("layerwise" application, Section 5); matrix l is
  *     rows x cols, row-major.  All per-matrix data live in flat buffers at the element
  *     offsets reported by conef_offsets(); conef_sizes() gives the buffer lengths.

@@ -32,15 +32,26 @@ struct conef_ctx {
 
 namespace {
 
+// Copies a host table to the device.  *dev_out is assigned only when the copy has succeeded; a table that is already
+// on the device (refresh: same length, e.g. the descriptors after a compressor has been configured) is overwritten
+// in its allocation.  Synchronous (hipMalloc + hipMemcpy): done on a context's first call, never later.
 template <typename T>
-int upload(conef_ctx *ctx, const std::vector<T> &host, const T **dev_out)
+int upload(conef_ctx *ctx, const std::vector<T> &host, const T **dev_out, bool refresh = false)
 {
-    *dev_out = nullptr;
-    if (host.empty()) return CONEF_OK;
+    if (host.empty()) {
+        *dev_out = nullptr;
+        return CONEF_OK;
+    }
+    const size_t bytes = host.size() * sizeof(T);
+    if (refresh && *dev_out)
+        return hipMemcpy(const_cast<T *>(*dev_out), host.data(), bytes, hipMemcpyHostToDevice) == hipSuccess ? CONEF_OK : CONEF_EHIP;
     void *p = nullptr;
-    if (hipMalloc(&p, host.size() * sizeof(T)) != hipSuccess) return CONEF_EHIP;
+    if (hipMalloc(&p, bytes) != hipSuccess) return CONEF_EHIP;
+    if (hipMemcpy(p, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(p);
+        return CONEF_EHIP;
+    }
     ctx->device_allocs.push_back(p);
-    if (hipMemcpy(p, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return CONEF_EHIP;
     *dev_out = static_cast<const T *>(p);
     return CONEF_OK;
 }
@@ -60,6 +71,7 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.p_f_items, &d.p_f_items))) return rc;
     if ((rc = upload(ctx, pl.q_f_items, &d.q_f_items))) return rc;
     if ((rc = upload(ctx, pl.err_f_items, &d.err_f_items))) return rc;
+    if ((rc = upload(ctx, pl.err_t_items, &d.err_t_items))) return rc;
     if ((rc = upload(ctx, pl.p_m_items, &d.p_m_items))) return rc;
     if ((rc = upload(ctx, pl.q_m_items, &d.q_m_items))) return rc;
     if ((rc = upload(ctx, pl.err_m_items, &d.err_m_items))) return rc;
@@ -92,6 +104,7 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_p_f = (int)pl.p_f_items.size();
     d.n_q_f = (int)pl.q_f_items.size();
     d.n_err_f = (int)pl.err_f_items.size();
+    d.n_err_t = (int)pl.err_t_items.size();
     d.n_p_m = (int)pl.p_m_items.size();
     d.n_q_m = (int)pl.q_m_items.size();
     d.n_err_m = (int)pl.err_m_items.size();
@@ -115,7 +128,7 @@ int ensure_rb_uploaded(conef_ctx *ctx)
 {
     if (ctx->rb_uploaded) return CONEF_OK;
     int rc;
-    if ((rc = upload(ctx, ctx->plan.mats, &ctx->dev.mats))) return rc;
+    if ((rc = upload(ctx, ctx->plan.mats, &ctx->dev.mats, true))) return rc;
     ctx->rb_uploaded = true;
     return CONEF_OK;
 }

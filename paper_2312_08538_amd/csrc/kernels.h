@@ -11,6 +11,7 @@ struct DevicePlan {
     const MatDesc *mats = nullptr;
     const WorkItem *p_items = nullptr, *q_items = nullptr, *err_items = nullptr;          // generic family
     const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
+    const WorkItem *err_t_items = nullptr;      // octet family, err pass with the residual on the fp32 matrix cores
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *upd_items = nullptr;                                                   // decompress / update
@@ -26,7 +27,7 @@ struct DevicePlan {
     const WorkItem *pred_items = nullptr, *gram_items = nullptr, *apply_items = nullptr, *qred_items = nullptr,
                    *elem_items = nullptr;
     int n_mats = 0;
-    int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0;
+    int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0, n_err_t = 0;
     int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_p = 0, n_split_qn = 0;
     int n_upd = 0;
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;

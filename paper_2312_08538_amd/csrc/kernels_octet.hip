@@ -15,6 +15,7 @@
 //             tile order by the reduction kernel.
 //   err pass  one wave per strip x row range, Q+ tile (8 x r) in registers, residual as the fp32
 //             fma chain, block max-norm by DPP, fixed-point stochastic rounding, pack, in place.
+//             Ranks 4 and 8 with blocks up to 256: the same chain on the fp32 matrix cores (k_err_tile).
 //
 // All sums are combined in a fixed order: results do not depend on scheduling.
 #include "device_common.h"
@@ -284,6 +285,156 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
         load_row(oa, oa2, pa, row + 2 * rw);
         process(ob, ob2, pb, row + rw, row + rw < row_end);
         row += 2 * rw;
+    }
+}
+
+// ------------------------------------------------------------------ err pass, residual on the fp32 matrix cores
+// For rank 4 and 8, blocks of at most 256 elements and columns a multiple of 128 (of 256 for blocks of 256).  In the
+// kernel above the fp32 fma chain over the rank is most of the vector work (8 of ~33 instructions per element at rank 8,
+// where the vector ALU and not the memory sets the pace).  v_mfma_f32_16x16x4_f32 adds its four products one after the
+// other, each fused, in ascending k (see the update kernel of the kernels for any shape): started from 0 and chained
+// over the rank it gives the bits of that chain, so the results stay those of the kernel above bit for bit.
+//   operand layout: lane l holds A[l%16][l/16], B[l/16][l%16] and D[4(l/16) + v][l%16], v = 0..3.
+// One wave per item: a strip of 128 columns (WIDE: 256, two tiles side by side, one scale block of 256) and a range
+// of rows, 16 rows per trip.  Tile t (0..7) of the matrix cores takes column 8 cc + t of every octet cc = l % 16, so
+// after eight tiles lane (cc, kg = l / 16) holds rows 4 kg + v, columns 8 cc .. 8 cc + 7: the octets it loads.  The
+// strip's rows of Q+ stay in registers in operand order for the whole item; a trip loads 16 rows of P^ (one or two
+// floats per lane).  A scale block is 2^lb_shift <= 16 lanes of one DPP row (WIDE: the row's 16 lanes, both tiles).
+typedef float tile_f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16, int BITS, int RP, bool WIDE, bool TWO>
+__global__ __launch_bounds__(256) void k_err_tile(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
+                                                  const float *__restrict__ Phat, const float *__restrict__ Qn,
+                                                  uint32_t step_lo, uint32_t step_hi, uint32_t *codes_first, float *scales_first)
+{
+    constexpr int NT = WIDE ? 2 : 1, NQ = RP / 4;
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_err_t) return;
+    const WorkItem it = dp.err_t_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int cc = lane & 15, kg = lane >> 4;
+    const int oc0 = it.a * 16 * NT + cc;                    // the lane's octet column in tile 0 (tile 1: + 16)
+    const int row_end = it.b + it.c;
+    const float s_f = (float)((1 << (BITS - 1)) - 1);
+    const int lb = WIDE ? 4 : d.lb_shift;                   // lanes of one DPP row that share a scale block
+
+    // B operand: Q+[column 8 (oc0 + 16 h) + t][4 q + kg]
+    float bq[NT][8][NQ];
+#pragma unroll
+    for (int h = 0; h < NT; ++h)
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) bq[h][t][q] = Qn[d.q_off + ((int64_t)(oc0 + 16 * h) * 8 + t) * RP + 4 * q + kg];
+
+    struct TripIn {
+        RawOctet<BF16, BITS> o[NT][4];
+        RawCodes<BITS> o2[TWO ? NT : 1][TWO ? 4 : 1];
+        float a[NQ];
+    };
+    // Rows at or beyond the end of the item re-read its last row (nothing is stored for them): unconditional loads.
+    auto load_trip = [&](TripIn &in, int r0) {
+        const int ar = r0 + cc < row_end ? r0 + cc : row_end - 1;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) in.a[q] = Phat[d.p_off + (int64_t)ar * RP + 4 * q + kg];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = r0 + 4 * kg + v < row_end ? r0 + 4 * kg + v : row_end - 1;
+#pragma unroll
+            for (int h = 0; h < NT; ++h) {
+                const int64_t o = (int64_t)row * d.m8 + oc0 + 16 * h;
+                in.o[h][v] = load_octet_always<BF16, BITS>(d, grads, TWO ? codes_first : codes, TWO ? scales_first : scales, o);
+                if (TWO) in.o2[TWO ? h : 0][TWO ? v : 0] = load_codes_always<BITS>(d, codes, scales, o);
+            }
+        }
+    };
+    auto process = [&](const TripIn &in, int r0) {
+        tile_f32x4 acc[NT][8];
+#pragma unroll
+        for (int h = 0; h < NT; ++h)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                acc[h][t] = tile_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) acc[h][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.a[q], bq[h][t][q], acc[h][t], 0, 0, 0);
+            }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = r0 + 4 * kg + v;
+            const bool valid = row < row_end;
+            const int rowc = valid ? row : row_end - 1;
+            float x[NT][8];
+            float a = 0.0f;
+#pragma unroll
+            for (int h = 0; h < NT; ++h) {
+                decode_octet<BF16, BITS>(in.o[h][v], 1.0f, x[h]);
+                if (TWO) add_codes<BITS>(in.o2[TWO ? h : 0][TWO ? v : 0], x[h]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    x[h][e] = x[h][e] - acc[h][e][v];
+                    a = fmaxf(a, fabsf(x[h][e]));
+                }
+            }
+            a = block_max(a, lb);
+            const float inv16 = (a > 0.0f) ? (s_f / a) * 65536.0f : 0.0f;
+            const float dnew = a * inv_levels(BITS);
+            float a2 = 0.0f;
+            uint32_t w[NT][2];
+#pragma unroll
+            for (int h = 0; h < NT; ++h) {
+                const int64_t o = (int64_t)rowc * d.m8 + oc0 + 16 * h;
+                uint32_t rnd[4];
+                philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+                quantise_octet<BITS>(x[h], inv16, rnd, w[h]);
+                if (valid) {
+                    store_code_words<BITS>(d, TWO ? codes_first : codes, o, w[h]);
+                    if (h == 0 && (cc & ((1 << lb) - 1)) == 0) (TWO ? scales_first : scales)[d.scale_off + (o >> d.lb_shift)] = a;
+                }
+                if (TWO) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int qn = BITS == 8 ? code_field(w[h][e >> 2], e & 3, 8) : code_field(w[h][0], e, BITS);
+                        x[h][e] = x[h][e] - dnew * (float)qn;
+                        a2 = fmaxf(a2, fabsf(x[h][e]));
+                    }
+                }
+            }
+            if (TWO) {
+                a2 = block_max(a2, lb);
+                const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
+#pragma unroll
+                for (int h = 0; h < NT; ++h) {
+                    const int64_t o = (int64_t)rowc * d.m8 + oc0 + 16 * h;
+                    uint32_t rnd[4];
+                    philox4x32_10((uint32_t)o, (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
+                    quantise_octet<BITS>(x[h], inv16_2, rnd, w[h]);
+                    if (valid) {
+                        store_code_words<BITS>(d, codes, o, w[h]);
+                        if (h == 0 && (cc & ((1 << lb) - 1)) == 0) scales[d.scale_off + (o >> d.lb_shift)] = a2;
+                    }
+                }
+            }
+        }
+    };
+    if (WIDE) {
+        // two tiles of inputs and accumulators leave no room for a second set: the other waves of the SIMD cover the loads
+        for (int r0 = it.b; r0 < row_end; r0 += 16) {
+            TripIn t;
+            load_trip(t, r0);
+            process(t, r0);
+        }
+        return;
+    }
+    // the next trip is loaded before the current one is worked on; two register sets take turns
+    TripIn ta, tb;
+    load_trip(ta, it.b);
+    for (int r0 = it.b; r0 < row_end; r0 += 32) {
+        load_trip(tb, r0 + 16);
+        process(ta, r0);
+        if (r0 + 16 >= row_end) break;              // uniform
+        load_trip(ta, r0 + 32);
+        process(tb, r0 + 16);
     }
 }
 
@@ -979,9 +1130,39 @@ void octet_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes
     else CONEF_OCTET2_DISPATCH(k_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, codes, scales, Phat, ws);
 }
 
+// The strip kernel for the plan's err_t_items (rank 4 or 8; `first`: the first vector of Algorithm 3, or null)
+template <bool TWO>
+static void launch_err_tile(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
+                            const float *Qn, uint64_t step, uint32_t *codes_first, float *scales_first, hipStream_t st)
+{
+    if (dp.n_err_t <= 0) return;
+    const dim3 grid((dp.n_err_t + 3) / 4);
+    const uint32_t lo = (uint32_t)step, hi = (uint32_t)(step >> 32);
+#define CONEF_ERR_TILE_CASE(BF, B, R)                                                                                             \
+    case ((BF ? 1 : 0) << 8) | (B << 4) | R:                                                                                      \
+        if (dp.block == 256)                                                                                                      \
+            hipLaunchKernelGGL((k_err_tile<BF, B, R, true, TWO>), grid, dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn, lo, \
+                               hi, codes_first, scales_first);                                                                    \
+        else                                                                                                                      \
+            hipLaunchKernelGGL((k_err_tile<BF, B, R, false, TWO>), grid, dim3(256), 0, st, dp, grads, codes, scales, Phat, Qn,    \
+                               lo, hi, codes_first, scales_first);                                                                \
+        break;
+#define CONEF_ERR_TILE_DTYPE(BF)                                                                    \
+    CONEF_ERR_TILE_CASE(BF, 2, 4) CONEF_ERR_TILE_CASE(BF, 2, 8) CONEF_ERR_TILE_CASE(BF, 4, 4)       \
+    CONEF_ERR_TILE_CASE(BF, 4, 8) CONEF_ERR_TILE_CASE(BF, 8, 4) CONEF_ERR_TILE_CASE(BF, 8, 8)
+    switch ((dp.dtype << 8) | (dp.bits << 4) | dp.rank) {
+        CONEF_ERR_TILE_DTYPE(false)
+        CONEF_ERR_TILE_DTYPE(true)
+    default: break;
+    }
+#undef CONEF_ERR_TILE_CASE
+#undef CONEF_ERR_TILE_DTYPE
+}
+
 void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,
                     const float *Qn, uint64_t step, hipStream_t st)
 {
+    launch_err_tile<false>(dp, grads, codes, scales, Phat, Qn, step, nullptr, nullptr, st);
     if (dp.n_err_f <= 0) return;
     CONEF_OCTET_DISPATCH(k_err_octet, dim3((dp.n_err_f + 3) / 4), st, dp, grads, codes, scales, Phat, Qn,
                          (uint32_t)step, (uint32_t)(step >> 32), (uint32_t *)nullptr, (float *)nullptr);
@@ -992,6 +1173,7 @@ void octet_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, fl
 void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                         float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st)
 {
+    launch_err_tile<true>(dp, grads, codes2, scales2, Phat, Qn, step, codes, scales, st);
     if (dp.n_err_f <= 0) return;
     const dim3 grid((dp.n_err_f + 3) / 4);
 #define CONEF_ERR_TWO_CASE(BF, B, R)                                                                                    \

@@ -291,6 +291,9 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             }
             // MFMA family: dense rank-32 contractions on the matrix cores
             if (!sketch && rank == 32 && dtype == 1 && bits == 4 && block == 128 && d.m % 128 == 0 && d.m <= (1 << 24)) d.path = kPathMfma;
+            // octet family: the err pass with the residual on the fp32 matrix cores, in strips of 128 columns (256 for blocks of 256)
+            d.err_tile = (d.path == kPathOctet && !sketch && (rank == 4 || rank == 8) && block <= 256 &&
+                          d.m % (block == 256 ? 256 : 128) == 0) ? 1 : 0;
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
@@ -399,7 +402,15 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                     for (int32_t st = 0; st < qstrips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
                 const int64_t rows_item = (int64_t)std::max(err_rows, rw);
-                for (int64_t r0 = 0; r0 < d.n && !sketch; r0 += rows_item)
+                // the err pass with the residual on the fp32 matrix cores: strips of 128 columns (256 for blocks of 256)
+                const int64_t tile_cols = block == 256 ? 256 : 128;
+                if (d.err_tile) {
+                    const int64_t rows_t = d.n >= 1024 ? 128 : 64;
+                    for (int64_t r0 = 0; r0 < d.n; r0 += rows_t)
+                        for (int32_t st = 0; st < (int32_t)(d.m / tile_cols); ++st)
+                            plan.err_t_items.push_back({l, st, (int32_t)r0, (int32_t)std::min<int64_t>(rows_t, d.n - r0)});
+                }
+                for (int64_t r0 = 0; r0 < d.n && !sketch && !d.err_tile; r0 += rows_item)
                     for (int32_t st = 0; st < strips; ++st)
                         plan.err_f_items.push_back({l, st, (int32_t)r0, (int32_t)std::min<int64_t>(rows_item, d.n - r0)});
                 if (d.n_p_chunks > 1)
@@ -580,6 +591,11 @@ bool check_plan(const Plan &plan)
         for (const WorkItem &it : plan.err_items) c.add_elems(plan, it, (int64_t)it.a * plan.block, (int64_t)4 * it.b * plan.block);
         for (const WorkItem &it : plan.err_f_items) {
             const int64_t strip = (int64_t)8 << plan.mats[it.mat].lr_shift;
+            c.add(plan, it, it.b, it.c, (int64_t)it.a * strip, strip);
+        }
+        for (const WorkItem &it : plan.err_t_items) {
+            const int64_t strip = plan.block == 256 ? 256 : 128;
+            if (!plan.mats[it.mat].err_tile) return false;
             c.add(plan, it, it.b, it.c, (int64_t)it.a * strip, strip);
         }
         for (const WorkItem &it : plan.err_m_items) c.add(plan, it, it.a, kErrRows, (int64_t)it.b * 128, (int64_t)it.c * 128);

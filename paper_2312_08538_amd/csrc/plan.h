@@ -54,6 +54,7 @@ struct MatDesc {
     int64_t bptr_off;               // offset of its w + 1 entries in bucket_ptr
     int32_t cs_cols;                // columns per item of the sketch update pass
     // random-block gradient compressor
+    int32_t err_tile, err_pad;      // octet family: the err pass runs in strips with the residual on the fp32 matrix cores
     int64_t rb_k;                   // coordinates kept per step (0: not configured)
     int64_t rb_delta_off;           // offset of the matrix's kept values in the flat Delta buffer
     // random-k gradient compressor (stratified: one coordinate kept per stratum of rk_g consecutive ones)
@@ -102,6 +103,8 @@ struct Plan {
     std::vector<WorkItem> p_f_items;    // (mat, first row, column chunk), one workgroup each
     std::vector<WorkItem> q_f_items;    // (mat, 64-column strip, row tile)
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
+    std::vector<WorkItem> err_t_items;  // (mat, strip of 128 or 256 columns, first row, rows): matrices of the octet family whose
+                                        // err pass forms the residual on the fp32 matrix cores (rank 4 or 8, block <= 256)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
     std::vector<WorkItem> p_m_items;    // (mat, first row), 128 rows per workgroup; eight lists of one length, one per XCD (mat = -1: padding)
     std::vector<WorkItem> q_m_items;    // (mat, pair of column blocks of 128, row tile)

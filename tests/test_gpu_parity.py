@@ -142,6 +142,20 @@ def test_ranks(env, rank):
     _run_model(env, w, layout, 2, f"rank{rank}")
 
 
+@pytest.mark.parametrize("rank,bits,block,dtype", [(8, 4, 64, wl.F32), (4, 8, 64, wl.BF16), (8, 2, 256, wl.F32),
+                                                   (4, 2, 128, wl.BF16), (8, 8, 256, wl.BF16), (4, 4, 128, wl.F32)])
+def test_error_pass_with_the_residual_on_the_fp32_matrix_cores(env, rank, bits, block, dtype):
+    """Rank 4 and 8 on shapes whose error pass runs in strips of 128 (blocks of 256: 256) columns with the fp32 fma
+    chain of the residual on the matrix cores: row counts that are not a multiple of the 16 rows of a trip or of an item,
+    one and several strips, beside a matrix of the same model that stays on the vector-ALU kernel (columns not a multiple
+    of the strip).  Three free-running steps, bit for bit like every kernel of this family."""
+    strip = 256 if block == 256 else 128
+    layout = [(300, strip), (77, 3 * strip), (1100, 2 * strip), (16, strip), (130, strip + 64)]
+    layout = [(n, m) for n, m in layout if m % block == 0]
+    w = wl.Workload("strips", 9, tuple(layout), rank, bits, block, dtype, "normal", 1.0, 0x51715)
+    assert _run_model(env, w, layout, 3, f"strips-r{rank}-b{bits}-B{block}-dt{dtype}") == 0
+
+
 def test_stage_parity_bit_exact_error_pass(env):
     """Each stage fed the oracle's inputs: raw P, orthonormal P^ and Q+ within 2e-6; the error pass
     fed the oracle's P^ and Q+ must give bit-identical codes and scales (same fma chain)."""
