@@ -12,6 +12,7 @@ the CPU oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -537,16 +538,43 @@ def calibrate_copy(w):
           file=sys.stderr)
 
 
-def load_traffic(workload: str, stage: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if
-    one exists for this workload (profiles/hbm_traffic.json), else None."""
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak, published
+
+
+def kernels_digest(w) -> str:
+    """Digest of the sources that the pass kernels of this workload's kernel family and their launch tables are built from:
+    counter values measured on other sources are not this build's (profiles/hbm_traffic.json records the digest of the
+    run it was measured on)."""
+    if w.rank == 32 and w.grad_dtype == 1 and w.bits == 4 and w.block == 128:
+        family = "kernels_mfma.hip"
+    elif w.rank in (2, 4, 8):
+        family = "kernels_octet.hip"
+    else:
+        family = "kernels_generic.hip"
+    d = os.path.join(ROOT, "paper_2312_08538_amd", "csrc")
+    h = hashlib.sha256()
+    for name in (family, "device_common.h", "kernels.h", "plan.h", "plan.cpp"):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_counters(w, stage: str):
+    """What the committed rocprofv3 --pmc summaries hold for the dominant kernel of this workload
+    (profiles/hbm_traffic.json: HBM bytes per launch, matrix-core busy fraction), if they were measured on the kernel
+    sources of this build; else None, with the reason."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary committed"
     try:
-        return json.load(open(path)).get(workload, {}).get(stage)
+        rec = json.load(open(path)).get(w.name)
     except Exception:
-        return None
+        return None, "counter summary unreadable"
+    if not rec or rec.get("stage") != stage:
+        return None, "no counter summary for this workload's dominant kernel"
+    if rec.get("kernels_digest") != kernels_digest(w):
+        return None, f"counter summary measured on other kernel sources ({rec.get('kernels_digest')})"
+    return rec, None
 
 
 def main():
@@ -605,7 +633,7 @@ def main():
         return
     if a.random_k:
         r = run_random_k(w, 10, a.steps)
-        print(json.dumps({"metric": "random-k ConEF step throughput: gradient GB/s processed",
+        print(json.dumps({"metric": "stratified random-k ConEF step throughput: gradient GB/s processed",
                           "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
                           "steps": a.steps, "config": {"workload": w.name, "group": 10}, **r}), flush=True)
         return
@@ -636,6 +664,7 @@ def main():
     dom = max(("p", "q", "err"), key=lambda s: stage_ms[s])
     dom_bytes = stage_bytes(w, dom)
     achieved = dom_bytes / (stage_ms[dom] * 1e-3) / 1e9
+    counters, why_not = load_counters(w, dom)
     out = {
         "metric": "ConEF step throughput: gradient GB/s processed",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -652,8 +681,21 @@ def main():
         "roofline": {"kernel": KERNEL_OF_STAGE[dom], "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "bytes_per_launch": int(dom_bytes), "ms_per_launch": round(stage_ms[dom], 4),
-                     "traffic": load_traffic(w.name, dom)},
+                     "traffic": counters["bytes"] if counters else None},
+        "kernels_digest": kernels_digest(w),
     }
+    if counters:
+        out["roofline"]["traffic_source"] = {"kernel": counters["kernel"], "kernels_digest": counters["kernels_digest"]}
+    else:
+        out["roofline"]["traffic_note"] = why_not
+    if w.rank == 32 and w.grad_dtype == 1 and w.bits == 4 and w.block == 128:
+        # the bf16 matrix-core kernels: every pass multiplies three bf16 splits of a factor with the gradient and with the
+        # codes, 6 products of 2 * 32 flops per element
+        flops = 384.0 * w.elements
+        tf = flops / (stage_ms[dom] * 1e-3) / 1e12
+        out["roofline"]["mfma"] = {"flops_per_launch": int(flops), "achieved": round(tf, 1), "peak": MFMA_PEAK_TFLOPS,
+                                   "unit": "TFLOP/s", "frac": round(tf / MFMA_PEAK_TFLOPS, 4),
+                                   "busy_frac": counters.get("mfma_busy_frac") if counters else None}
     if not a.no_extra:
         out["apply_update"] = run_update(w)
         extra = {}

@@ -5,7 +5,7 @@
  * quantiser of Section 4.2.1, eq. (3) (max-norm variant, Section 5.1) as the error
  * compressor; further down, the other compressors of the paper: the count sketch as the
  * error compressor with the partial update of Algorithm 4 (conef_cs_*), the element-wise
- * gradient compressors random block, random-k and scaled sign (conef_rb_*, conef_rk_*,
+ * gradient compressors random block, stratified random-k and scaled sign (conef_rb_*, conef_rk_*,
  * conef_ss_*), and improved contractive error feedback, Algorithm 3 (conef_i_*).
  *
  * Conventions
@@ -29,7 +29,7 @@
  *   - Random draws: Philox4x32-10, counter (j>>3, l, lo32(step), hi32(step)), key
  *     (lo32(seed), hi32(seed)); element j uses 16 bits: half (j&1) of output word (j&7)>>1.
  *     Other draws use counters of their own, stated with the calls: (l, 2^32-1, step) the random
- *     block's start, (i>>2, l + 2^30, step) the random-k strata, (j>>3, l + 2^31, step) the second
+ *     block's start, (i>>2, l + 2^30, step) the strata of the stratified random-k, (j>>3, l + 2^31, step) the second
  *     rounding of Algorithm 3, (i, l, 2^32-1, 2^32-1) the sketch's row hash.
  *   - Calls on one context must not overlap in time (they share the workspace).
  */
@@ -221,8 +221,8 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
                      void *hip_stream);
 
-/* ---- Random-k gradient compressor (the compressor of the paper's iConEF experiment in the appendix, which names it
- * and its rate only) in place of the rank-r one, unscaled like the random block, with either error compressor and
+/* ---- Stratified random-k gradient compressor (standing in for the random-k of the paper's iConEF experiment in the
+ * appendix, which names the compressor and its rate only; NOT a uniformly drawn k-subset) in place of the rank-r one, unscaled like the random block, with either error compressor and
  * with improved contractive error feedback.  Reading built here, "stratified": the flat row-major index range of
  * matrix l is cut into strata of group[l] consecutive coordinates (the last one may be shorter) and one coordinate of
  * every stratum is kept, drawn uniformly within its stratum and independently of the others, the same on every
@@ -277,7 +277,7 @@ int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *s
  * e~ (err_codes, err_scales) and q (err2_codes, err2_scales), both zero at the start:
  *   p     = g + e~ + q                   (Algorithm 3 line 5; p_j = fma(d2, c2_j, fma(d1, c1_j, g_j)))
  *   Delta = Q(p)                         (line 6: the random block of conef_rb_step, the scaled sign of conef_ss_step
- *                                        or the random-k of conef_rk_step)
+ *                                        or the stratified random-k of conef_rk_step)
  *   e~+   = C(p - Delta)                 (line 10; p - Delta is 0 on the kept block, p - (+-c) for the scaled sign)
  *   q+    = C(p - Delta - e~+)           (line 14; the decoded e~+ is rounded to fp32, then subtracted)
  * The second quantisation draws its own random numbers: element j uses the 16-bit draw it has in conef_step, taken
@@ -298,7 +298,7 @@ int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
                     float *err2_scales, float *delta_out, uint64_t step, void *hip_stream);
 
 /* ---- Improved contractive error feedback, version 2 (Algorithm 3 of Section 3.2 with its "else" branch), around the
- * random-block and random-k gradient compressors: the FIRST error compressor is a contractive compressor of the
+ * random-block and stratified random-k gradient compressors: the FIRST error compressor is a contractive compressor of the
  * gradient compressor's class (Assumption 4), the second is the error compressor C.  Per matrix, with
  * x = p - Delta:
  *   p     = eta*g + e~ + q
