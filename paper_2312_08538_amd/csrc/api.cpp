@@ -88,6 +88,17 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_rb_g = (int)pl.rb_g_items.size();
     if ((rc = upload(ctx, pl.cs_err_items, &d.cs_err_items))) return rc;
     if ((rc = upload(ctx, pl.cs_err_f_items, &d.cs_err_f_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_t_items, &d.cs_t_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_qt_items, &d.cs_qt_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_u_items, &d.cs_u_items))) return rc;
+    if ((rc = upload(ctx, pl.cs_lin_items, &d.cs_lin_items))) return rc;
+    d.n_cs_t = (int)pl.cs_t_items.size();
+    d.n_cs_qt = (int)pl.cs_qt_items.size();
+    d.n_cs_u = (int)pl.cs_u_items.size();
+    d.n_cs_lin = (int)pl.cs_lin_items.size();
+    d.n_cs_err_f_old = 0;
+    for (const MatDesc &m : pl.mats)
+        if (pl.sketch && m.path == kPathOctet && !m.cs_lin) d.n_cs_err_f_old += 1;
     d.n_cs_err_f = (int)pl.cs_err_f_items.size();
     if ((rc = upload(ctx, pl.row_hash, &d.row_hash))) return rc;
     if ((rc = upload(ctx, pl.bucket_ptr, &d.bucket_ptr))) return rc;
@@ -863,8 +874,8 @@ int conef_cs_step_err(conef_ctx *ctx, const void *grads, void *table, const floa
         return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
-    return hip_rc(launch_cs_pass_err(ctx->dev, grads, table, P_hat, Q_new, static_cast<hipStream_t>(hip_stream),
-                                     stage_span(ctx, 3)));
+    return hip_rc(launch_cs_pass_err(ctx->dev, grads, table, P_hat, Q_new, ws_doubles(ctx, workspace),
+                                     static_cast<hipStream_t>(hip_stream), stage_span(ctx, 3)));
 }
 
 int conef_cs_step(conef_ctx *ctx, const void *grads, void *table, const float *Q_state, float *P_out, float *Q_out,

@@ -20,6 +20,9 @@ struct DevicePlan {
     int n_rb = 0, n_rb_g = 0;
     // count-sketch mode
     const WorkItem *cs_err_items = nullptr, *cs_err_f_items = nullptr;
+    const WorkItem *cs_t_items = nullptr, *cs_qt_items = nullptr, *cs_u_items = nullptr, *cs_lin_items = nullptr;   // linear form
+    int n_cs_t = 0, n_cs_qt = 0, n_cs_u = 0, n_cs_lin = 0;
+    int n_cs_err_f_old = 0;     // matrices of the octet path that are NOT in the linear form (0: skip their update launch)
     const int32_t *row_hash = nullptr, *bucket_ptr = nullptr, *bucket_rows = nullptr;
     int n_cs_err = 0, n_cs_err_f = 0;
     int table_dtype = 0;            // 0 fp32, 1 fp16
@@ -95,7 +98,10 @@ hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void 
 hipError_t launch_cs_pass_q(const DevicePlan &dp, const void *grads, const void *table, const float *Phat, float *Qout,
                             double *ws, hipStream_t st, Span span = Span());
 hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *table, const float *Phat, const float *Qn,
-                              hipStream_t st, Span span = Span());
+                              double *ws, hipStream_t st, Span span = Span());
+// the count sketch in its linear form on the bf16 matrix cores (rank 32): see kernels_sketch.hip
+void mfma_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P, double *ws, hipStream_t st);
+void mfma_cs_pass_q(const DevicePlan &dp, const void *grads, const void *table, const float *Phat, double *ws, hipStream_t st);
 hipError_t launch_cs_decode(const DevicePlan &dp, const void *table, float *e_out, hipStream_t st);
 hipError_t launch_decode(const DevicePlan &dp, const uint32_t *codes, const float *scales, float *e_out,
                          hipStream_t st);

@@ -59,6 +59,8 @@ __device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ float half_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
+
 // 8 consecutive rows of one column (two transposing reads of 4 rows each)
 __device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
 {
@@ -107,27 +109,38 @@ constexpr int kCStride = kCodeGroup / 8 + 4; // code words per row in LDS (144 b
 constexpr int kScaleGroup = 32 * 128;       // columns per scale group: 32 scales are one 128-byte line per row
 constexpr int kSStride = 33;                // scales per row in LDS (+1: rows fall on distinct banks)
 
-// GRAD = false, ACCUM = true: the contribution of a compressed vector alone (no gradient) added to a P that an
-// earlier launch has written: P = (g + second) Q, then P += first Q, for the two error vectors of Algorithm 3.
-template <bool GRAD, bool ACCUM>
+// MODE 0: P = (g + e) Q, the quantiser's step.
+// MODE 1: the contribution of a compressed vector alone (no gradient) added to a P that an earlier launch has written:
+//         P = (g + second) Q, then P += first Q, for the two error vectors of Algorithm 3.
+// MODE 2 and 3, the count sketch in its linear form (no codes, no scales; `codes` is the fp16 table, `ws` the workspace):
+//         3: T = S Q over the table's rows (an fp16 entry is the sum of two bf16 values, exactly: two operand tiles), fp64 to
+//            the workspace;  2: P = g Q + (1 - beta) s(i) T[h(i)].
+constexpr int kPModeStep = 0, kPModeCodes = 1, kPModeGrad = 2, kPModeTable = 3;
+
+template <int MODE>
 __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                const float *__restrict__ Q, float *P)
+                                                const float *__restrict__ Q, float *P, double *ws)
 {
+    constexpr bool GRAD = MODE != kPModeCodes, ACCUM = MODE == kPModeCodes;
+    constexpr bool CODES = MODE == kPModeStep || MODE == kPModeCodes, TABLE = MODE == kPModeTable;
     __shared__ __attribute__((aligned(16))) uint16_t sg[kMfmaRows * kGStride];
     __shared__ __attribute__((aligned(16))) uint32_t sc[kMfmaRows * kCStride];
     __shared__ __attribute__((aligned(16))) uint16_t sq[3 * kStage * 32];      // splits of Q, [split][column of the stage][c]
     __shared__ float ss[kMfmaRows * kSStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // the table holds one list per XCD (workgroup b runs on XCD b % 8), each inside an address range of its own
-    const WorkItem it = dp.p_m_items[(blockIdx.x & 7) * (dp.n_p_m >> 3) + (blockIdx.x >> 3)];
+    const WorkItem it = TABLE ? dp.cs_t_items[blockIdx.x] : dp.p_m_items[(blockIdx.x & 7) * (dp.n_p_m >> 3) + (blockIdx.x >> 3)];
     if (it.mat < 0) return;                          // padding of a shorter list
-    const MatDesc d = dp.mats[it.mat];
+    MatDesc d = dp.mats[it.mat];
+    if (MODE == kPModeGrad && !d.cs_lin) return;     // (a count-sketch plan may hold matrices of both forms)
+    if (TABLE) d.n = d.w;                            // the rows walked are the table's
     const int64_t row0 = it.a;
     const int m = (int)d.m;
-    const uint16_t *g = grads + d.grad_off;
+    const uint16_t *g = TABLE ? reinterpret_cast<const uint16_t *>(codes) + d.table_off : grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
     const float *qf = Q + d.q_off;
+    uint16_t *sg2 = reinterpret_cast<uint16_t *>(sc);      // MODE 3: the second operand tile, laid out like sg
 
     // A stage's global loads are held in registers until its turn in LDS; two stages are in flight.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -201,11 +214,28 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         r.q1 = qp[1];
     };
     auto store_stage = [&](const StageRegs &r) {
-        if (GRAD) {
+        if (GRAD && !TABLE) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
                 *reinterpret_cast<u32x4 *>(sg + rr * kGStride + oct * 8) = r.g[s];
+            }
+        }
+        if (TABLE) {
+            // fp16 -> fp32 (exact) -> upper half (bf16 by truncation) and what is left (at most 3 significant bits)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int idx = tid + 256 * s, rr = idx >> 3, oct = idx & 7;
+                u32x4 hi, lo;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float x0 = half_bits_to_f32(r.g[s][e2] & 0xFFFFu), x1 = half_bits_to_f32(r.g[s][e2] >> 16);
+                    const float h0 = trunc_bf16(x0), h1 = trunc_bf16(x1);
+                    hi[e2] = pack_hi16(h0, h1);
+                    lo[e2] = pack_hi16(x0 - h0, x1 - h1);
+                }
+                *reinterpret_cast<u32x4 *>(sg + rr * kGStride + oct * 8) = hi;
+                *reinterpret_cast<u32x4 *>(sg2 + rr * kGStride + oct * 8) = lo;
             }
         }
         {
@@ -243,27 +273,30 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
         for (int ks = 0; ks < kStage / 16; ++ks) {
             Frag bg, bq, a0, a1, a2;
             if (GRAD) bg.u = *reinterpret_cast<const uint4 *>(sg + my_row_in_tile * kGStride + ks * 16 + kg * 8);
-            const uint32_t w = sc[my_row_in_tile * kCStride + ((k0 & (kCodeGroup - 1)) >> 3) + ks * 2 + kg];
-            float q16[8];
-            fields_over_16(w, q16);                  // sixteenths of small integers: exact in bf16
-            bq.u = make_uint4(pack_hi16(q16[0], q16[1]), pack_hi16(q16[2], q16[3]), pack_hi16(q16[4], q16[5]),
-                              pack_hi16(q16[6], q16[7]));
+            if (CODES) {
+                const uint32_t w = sc[my_row_in_tile * kCStride + ((k0 & (kCodeGroup - 1)) >> 3) + ks * 2 + kg];
+                float q16[8];
+                fields_over_16(w, q16);                  // sixteenths of small integers: exact in bf16
+                bq.u = make_uint4(pack_hi16(q16[0], q16[1]), pack_hi16(q16[2], q16[3]), pack_hi16(q16[4], q16[5]),
+                                  pack_hi16(q16[6], q16[7]));
+            }
+            if (TABLE) bq.u = *reinterpret_cast<const uint4 *>(sg2 + my_row_in_tile * kGStride + ks * 16 + kg * 8);
             a0.u = lds_read_tr16x8(sq + 0 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a1.u = lds_read_tr16x8(sq + 1 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             a2.u = lds_read_tr16x8(sq + 2 * kStage * 32 + tr_a + ks * 16 * 32, 32);
             if (GRAD) accP = mfma(a0, bg, accP);
-            accS = mfma(a0, bq, accS);
+            if (CODES || TABLE) accS = mfma(a0, bq, accS);
             if (GRAD) accP = mfma(a1, bg, accP);
-            accS = mfma(a1, bq, accS);
+            if (CODES || TABLE) accS = mfma(a1, bq, accS);
             if (GRAD) accP = mfma(a2, bg, accP);
-            accS = mfma(a2, bq, accS);
+            if (CODES || TABLE) accS = mfma(a2, bq, accS);
         }
         if (((k0 + kStage) & 127) == 0) {
             // end of a scale block: fold the code part in with this row's step size
-            const float blk_scale = ss[my_row_in_tile * kSStride + ((k0 >> 7) & 31)];
+            const float blk_scale = CODES ? ss[my_row_in_tile * kSStride + ((k0 >> 7) & 31)] : 0.0f;
             // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
             const float dstep = (my_row < d.n) ? (blk_scale * inv_levels(4) * dp.omb) * 16.0f : 0.0f;
-            const double dd = (double)dstep;
+            const double dd = TABLE ? 1.0 : (double)dstep;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 acc64[v] += (double)accP[v] + dd * (double)accS[v];
@@ -276,14 +309,14 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     // m is a multiple of 128, so the number of stages is even: two stages per trip, one register set each
     StageRegs ra, rb;
     CodeRegs cg;
-    load_codes(cg, 0);
+    if (CODES) load_codes(cg, 0);
     load_stage(ra, 0);
     load_stage(rb, kStage);
     // two stages per trip, one register set each; two trips per code group
     auto trip = [&](int k0, auto new_group) {
         __syncthreads();                 // everybody is done reading the previous stage
         store_stage(ra);
-        if constexpr (decltype(new_group)::value) {
+        if constexpr (decltype(new_group)::value && CODES) {
             // the group's words have been in registers since the last group was stored
             store_codes(cg);
             load_codes(cg, (k0 + kCodeGroup < m) ? k0 + kCodeGroup : k0);      // the last group re-reads itself (unused)
@@ -301,12 +334,32 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
     // inner loop: inside it, it would make every wait of the loop a wait for all loads in flight.
     for (int ks0 = 0; ks0 < m; ks0 += kScaleGroup) {
         __syncthreads();                 // everybody is done with the previous group's scales
-        fetch_scales(ks0);
+        if (CODES) fetch_scales(ks0);
         const int ks1 = (ks0 + kScaleGroup < m) ? ks0 + kScaleGroup : m;
         for (int k0 = ks0; k0 < ks1; k0 += kCodeGroup) {
             trip(k0, std::true_type());
             if (k0 + 2 * kStage < m) trip(k0 + 2 * kStage, std::false_type());
         }
+    }
+    if (TABLE) {
+        if (my_row < d.n) {
+            double *out = ws + d.cs_t_off + my_row * 32;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[8 * g4 + 4 * kg + j] = acc64[4 * g4 + j];
+        }
+        return;
+    }
+    if (MODE == kPModeGrad && my_row < d.n) {
+        // the sketch's share: (1 - beta) s(i) T[h(i)]
+        const int32_t hv = dp.row_hash[d.hash_off + my_row];
+        const double somb = hv < 0 ? -(double)dp.omb : (double)dp.omb;
+        const double *t = ws + d.cs_t_off + (int64_t)(hv & INT32_MAX) * 32;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc64[4 * g4 + j] += somb * t[8 * g4 + 4 * kg + j];
     }
     if (my_row < d.n) {
         float *out = P + d.p_off + my_row * 32;
@@ -400,18 +453,25 @@ constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / co
 // GRAD = false, ACCUM = true: the contribution of a compressed vector alone (no gradient; its scales in the second
 // column-block-major region) added to what an earlier launch has left: Q+ = (g + second)^T P^, then
 // Q+ += first^T P^, for the two error vectors of Algorithm 3.
-template <bool GRAD, bool ACCUM>
+// MODE 2 and 3, the count sketch in its linear form (`codes` is the fp16 table): 2: the gradient's share g^T P^ alone;
+// 3: the table's share (1 - beta) S^T U over the table's rows (two operand tiles per entry, see the P pass), U from the
+// workspace; its row tiles follow the gradient's in the partial sums, which the reduction kernel adds in order.
+template <int MODE>
 __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
                                                 const float *__restrict__ Phat, double *ws, float *Qout)
 {
+    constexpr bool GRAD = MODE != kPModeCodes, ACCUM = MODE == kPModeCodes;
+    constexpr bool CODES = MODE == kPModeStep || MODE == kPModeCodes, TABLE = MODE == kPModeTable;
     __shared__ __attribute__((aligned(16))) uint16_t tg[kQRows * kTPitch];      // gradient rows, raw bf16
     __shared__ __attribute__((aligned(16))) uint16_t tq[kQRows * kTPitch];      // codes as bf16 integers
     __shared__ __attribute__((aligned(16))) uint16_t sb[3 * kQRows * 32];       // splits of P^, [split][row][c]
     __shared__ __attribute__((aligned(16))) uint16_t sd[3 * kQRows * 32];       // splits of d_i P^, [split][row][c]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const WorkItem it = dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
-    const MatDesc d = dp.mats[it.mat];
+    const WorkItem it = TABLE ? dp.cs_qt_items[blockIdx.x] : dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
+    MatDesc d = dp.mats[it.mat];
+    if (MODE == kPModeGrad && !d.cs_lin) return;     // (a count-sketch plan may hold matrices of both forms)
+    if (TABLE) d.n = d.w;                            // the rows walked are the table's
     const int m = (int)d.m;
     // The item is a PAIR of neighbouring column blocks, A = 2 it.a and B = A + 1, worked on in turn
     // chunk by chunk: the chunk's rows of P^ are fetched and split once for both (the splits of d_i P^
@@ -423,10 +483,10 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const int cbB = has_b ? cbA + 1 : cbA;
     const int64_t row0 = (int64_t)it.b * d.q_tile_rows;
     const int64_t row1 = (row0 + d.q_tile_rows < d.n) ? row0 + d.q_tile_rows : d.n;
-    const uint16_t *g = grads + d.grad_off;
+    const uint16_t *g = TABLE ? reinterpret_cast<const uint16_t *>(codes) + d.table_off : grads + d.grad_off;
     const uint32_t *cw = codes + d.word_off;
     const float *scT = reinterpret_cast<const float *>(ws + (GRAD ? d.scT_off : d.scT2_off));       // [block][row]
-    const float *ph = Phat + d.p_off;
+    const float *ph = TABLE ? reinterpret_cast<const float *>(ws + d.cs_u_off) : Phat + d.p_off;
 
     // A block-chunk's loads are held in registers until its turn in LDS; two are in flight (block A and
     // block B of a chunk, or B and the next chunk's A).  Every load is unconditional (rows at or beyond
@@ -452,10 +512,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     };
     auto load_chunk = [&](ChunkRegs &r, int64_t i0, int cb) {
         const int64_t last = row1 - 1;
+        if (CODES) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
-            r.sc[j] = scT[(int64_t)cb * d.n + row];
+            for (int j = 0; j < 8; ++j) {
+                const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
+                r.sc[j] = scT[(int64_t)cb * d.n + row];
+            }
         }
         int64_t e[4];
 #pragma unroll
@@ -469,10 +531,12 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
             r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2] + goct * 8);
             r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3] + goct * 8);
         }
-        r.cw0 = cw[(e[0] >> 3) + goct];
-        r.cw1 = cw[(e[1] >> 3) + goct];
-        r.cw2 = cw[(e[2] >> 3) + goct];
-        r.cw3 = cw[(e[3] >> 3) + goct];
+        if (CODES) {
+            r.cw0 = cw[(e[0] >> 3) + goct];
+            r.cw1 = cw[(e[1] >> 3) + goct];
+            r.cw2 = cw[(e[2] >> 3) + goct];
+            r.cw3 = cw[(e[3] >> 3) + goct];
+        }
     };
     // splits of 8 rows of one column, in operand order: [split][16 rows][lane] x 8 bf16
     auto store_split = [&](uint16_t *o, const float (&x)[8]) {
@@ -492,6 +556,33 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     auto store_chunk = [&](const ChunkRegs &r, const float (&pv)[8], bool with_p) {
         const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
         const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
+        if (!CODES) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (TABLE) {
+                    // fp16 -> fp32 (exact) -> upper half (bf16 by truncation) and what is left
+                    u32x4 hi, lo;
+#pragma unroll
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const float x0 = half_bits_to_f32(gs[s][e2] & 0xFFFFu), x1 = half_bits_to_f32(gs[s][e2] >> 16);
+                        const float h0 = trunc_bf16(x0), h1 = trunc_bf16(x1);
+                        hi[e2] = pack_hi16(h0, h1);
+                        lo[e2] = pack_hi16(x0 - h0, x1 - h1);
+                    }
+                    *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = hi;
+                    *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = lo;
+                } else {
+                    *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
+                }
+            }
+            if (with_p) {
+                float pw[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) pw[j] = TABLE ? dp.omb * pv[j] : pv[j];
+                store_split(sb, pw);
+            }
+            return;
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             float q16[8];
@@ -535,18 +626,19 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         for (int ks = 0; ks < kQRows / 16; ++ks) {
             Frag bg, bq, aP[3], aD[3];
             if (GRAD) bg.u = lds_read_tr16x8(tg + tr_t + ks * 16 * kTPitch, kTPitch);
-            bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
+            if (CODES || TABLE) bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
                 if (GRAD) aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
-                aD[s].u = *reinterpret_cast<const uint4 *>(sd + s * kQRows * 32 + (ks * 64 + lane) * 8);
+                if (CODES) aD[s].u = *reinterpret_cast<const uint4 *>(sd + s * kQRows * 32 + (ks * 64 + lane) * 8);
+                if (TABLE) aD[s].u = aP[s].u;          // both tiles of a table entry meet the same factor
             }
             if (GRAD) acc = mfma(aP[0], bg, acc);
-            acc = mfma(aD[0], bq, acc);
+            if (CODES || TABLE) acc = mfma(aD[0], bq, acc);
             if (GRAD) acc = mfma(aP[1], bg, acc);
-            acc = mfma(aD[1], bq, acc);
+            if (CODES || TABLE) acc = mfma(aD[1], bq, acc);
             if (GRAD) acc = mfma(aP[2], bg, acc);
-            acc = mfma(aD[2], bq, acc);
+            if (CODES || TABLE) acc = mfma(aD[2], bq, acc);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
@@ -578,6 +670,13 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
     auto write_block = [&](const double (&acc64)[16], int cb) {
         const int kcol = cb * 128 + 32 * wave + r32;
+        if (!CODES) {
+            // linear form of the count sketch: always partial sums, the table's row tiles behind the gradient's
+            double *out = ws + d.qpart_off + ((int64_t)((TABLE ? d.cs_q_tiles_g : 0) + it.b) * m + kcol) * 32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
+            return;
+        }
         if (d.n_q_tiles == 1) {
             // the only row tile of this matrix: Q+ and its operand splits are final
             float *qo = Qout + d.q_off + (int64_t)kcol * 32;
@@ -950,12 +1049,22 @@ void mfma_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                  const float *Q, float *P, hipStream_t st)
 {
     if (dp.n_p_m <= 0) return;
-    hipLaunchKernelGGL((k_p_mfma<true, false>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
-                       codes, scales, Q, P);
+    hipLaunchKernelGGL((k_p_mfma<kPModeStep>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       codes, scales, Q, P, (double *)nullptr);
     // Algorithm 3: the other error vector's share, added to what the launch above has written
     if (dp.i_codes)
-        hipLaunchKernelGGL((k_p_mfma<false, true>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
-                           dp.i_codes, dp.i_scales, Q, P);
+        hipLaunchKernelGGL((k_p_mfma<kPModeCodes>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                           dp.i_codes, dp.i_scales, Q, P, (double *)nullptr);
+}
+
+// The count sketch in its linear form: T = S Q, then P = g Q + (1 - beta) s(i) T[h(i)]
+void mfma_cs_pass_p(const DevicePlan &dp, const void *grads, const void *table, const float *Q, float *P, double *ws, hipStream_t st)
+{
+    if (dp.n_cs_t <= 0) return;
+    hipLaunchKernelGGL((k_p_mfma<kPModeTable>), dim3(dp.n_cs_t), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       reinterpret_cast<const uint32_t *>(table), (const float *)nullptr, Q, P, ws);
+    hipLaunchKernelGGL((k_p_mfma<kPModeGrad>), dim3(dp.n_p_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       reinterpret_cast<const uint32_t *>(table), (const float *)nullptr, Q, P, ws);
 }
 
 void mfma_transpose_scales(const DevicePlan &dp, const float *scales, double *ws, bool second, hipStream_t st)
@@ -968,12 +1077,23 @@ void mfma_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes,
                  const float *Phat, double *ws, float *Qout, hipStream_t st)
 {
     if (dp.n_q_m <= 0) return;
-    hipLaunchKernelGGL((k_q_mfma<true, false>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
+    hipLaunchKernelGGL((k_q_mfma<kPModeStep>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads), codes,
                        scales, Phat, ws, Qout);
     // Algorithm 3: the other error vector's share (its scales transposed into the second region by the caller)
     if (dp.i_codes)
-        hipLaunchKernelGGL((k_q_mfma<false, true>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+        hipLaunchKernelGGL((k_q_mfma<kPModeCodes>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
                            dp.i_codes, dp.i_scales, Phat, ws, Qout);
+}
+
+// The count sketch in its linear form: partial sums of g^T P^ and of (1 - beta) S^T U (U in the workspace); the
+// reduction kernel adds them
+void mfma_cs_pass_q(const DevicePlan &dp, const void *grads, const void *table, const float *Phat, double *ws, hipStream_t st)
+{
+    if (dp.n_cs_qt <= 0) return;
+    hipLaunchKernelGGL((k_q_mfma<kPModeGrad>), dim3(dp.n_q_m), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       reinterpret_cast<const uint32_t *>(table), (const float *)nullptr, Phat, ws, (float *)nullptr);
+    hipLaunchKernelGGL((k_q_mfma<kPModeTable>), dim3(dp.n_cs_qt), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                       reinterpret_cast<const uint32_t *>(table), (const float *)nullptr, Phat, ws, (float *)nullptr);
 }
 
 void mfma_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, const float *Phat,

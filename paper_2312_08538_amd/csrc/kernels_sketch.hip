@@ -563,6 +563,7 @@ __global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, co
     const int tid = threadIdx.x;
     const WorkItem it = dp.cs_err_f_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
+    if (d.cs_lin) return;                             // updated in the linear form (k_cs_lin_update)
     const int r = dp.rank;
     const int64_t colw = (int64_t)it.c * 512 + tid * CPL;
     const bool active = colw < d.m;                   // cols % 8 == 0: a thread's CPL columns are all inside or all outside
@@ -697,6 +698,154 @@ __global__ __launch_bounds__(512 / CPL) void k_cs_update_octet(DevicePlan dp, co
                     *reinterpret_cast<float2 *>(dst) = make_float2(out[0], out[1]);
                 }
             }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ linear form (rank 32, bf16 gradients, fp16 table)
+// The sketch is linear, so its share of the rank-32 products need not be formed per element of the matrix:
+//   P  = g Q + (1 - beta) s(i) T[h(i)],            T = S Q                              (w rows instead of n)
+//   Q+ = g^T P^ + (1 - beta) S^T U,                U[b] = sum over the rows i of bucket b, ascending, of s(i) P^[i]
+//   S[b] <- (beta + (1 - beta) |b|) S[b] + sum over the rows of b of s(i) g[i] - U[b] Q+^T
+// (the last line is beta S + C(p - P^ Q+^T) with p = g + (1 - beta) s(i) S[h(i)] written out).  The big products are the
+// bf16 matrix-core passes of the quantiser's rank-32 family on the gradient alone and on the table (mfma_cs_pass_p / _q);
+// here are the bucket sums U and the update.  The rounding points differ from the per-element form (no fp32 p per
+// element), so the table agrees with it to an fp16 unit in the last place, not bit for bit.
+
+// U: one workgroup per run of up to 8 buckets; thread (bucket, c) adds its bucket's rows in ascending order in fp64.
+__global__ __launch_bounds__(256) void k_cs_bucket_sums(DevicePlan dp, const float *__restrict__ Phat, double *ws)
+{
+    const WorkItem it = dp.cs_u_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int j = threadIdx.x >> 5, c = threadIdx.x & 31;
+    if (j >= it.b) return;
+    const int b = it.a + j;
+    const int32_t e0 = dp.bucket_ptr[d.bptr_off + b], e1 = dp.bucket_ptr[d.bptr_off + b + 1];
+    const int32_t *rows = dp.bucket_rows + d.hash_off;
+    double u = 0.0;
+    for (int32_t e = e0; e < e1; ++e) {
+        const int32_t hv = rows[e];
+        const double v = (double)Phat[d.p_off + (int64_t)(hv & INT32_MAX) * 32 + c];
+        u = hv < 0 ? u - v : u + v;
+    }
+    reinterpret_cast<float *>(ws + d.cs_u_off)[(int64_t)b * 32 + c] = (float)u;
+}
+
+// Update: one wave per (strip of 128 columns, run of buckets), 16 buckets per trip.  The lanes are laid out for the fp32
+// matrix cores (v_mfma_f32_16x16x4_f32: lane l holds A[l%16][l/16], B[l/16][l%16] and D[4(l/16) + v][l%16]; tile t takes
+// column 8 cc + t of every octet cc = l % 16, so lane (cc, kg) owns buckets 4 kg + v, v = 0..3, and the 8 columns of its
+// octet).  A trip first gathers: each 16-lane group walks the row lists of its four buckets, four entries of each at a
+// time (16 row indices, then 16 gradient octets in flight), adding signed octets in ascending row order; then the matrix
+// cores subtract U Q+^T from the sums (accumulator in, A = -U); then the four table octets are rewritten.  The strip's
+// rows of Q+ (16 KB) sit in a wave-private piece of LDS in operand order ([t][q][kg][cc]: a wave's read of one operand is
+// 256 contiguous bytes) rather than in 64 registers per lane: the gather needs the waves.
+typedef float lin_f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_cs_lin_update(DevicePlan dp, const uint16_t *__restrict__ grads, uint16_t *table,
+                                                       const float *__restrict__ Qn, const double *ws)
+{
+    __shared__ float s_q[4][8 * 8 * 64];
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_cs_lin) return;
+    const WorkItem it = dp.cs_lin_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int cc = lane & 15, kg = lane >> 4;
+    float *sq = s_q[threadIdx.x >> 6];
+    {
+        // the strip's 128 rows of Q+ are contiguous: coalesced reads, scattered into operand order
+        const float *src = Qn + d.q_off + (int64_t)it.a * 128 * 32;
+#pragma unroll 8
+        for (int i = 0; i < 64; ++i) {
+            const int idx = i * 64 + lane, col = idx >> 5, c = idx & 31;
+            sq[(((col & 7) * 8 + (c >> 2)) * 4 + (c & 3)) * 16 + (col >> 3)] = src[idx];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    const int64_t col0 = (int64_t)it.a * 128 + 8 * cc;
+    const int b_end = it.b + it.c;
+    const float *U = reinterpret_cast<const float *>(ws + d.cs_u_off);
+    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
+    const int32_t *rows = dp.bucket_rows + d.hash_off;
+    const uint16_t *g = grads + d.grad_off + col0;
+    uint16_t *tab = table + d.table_off + col0;
+
+    for (int b1 = it.b; b1 < b_end; b1 += 16) {
+        int32_t e0[4], e1[4];
+        uint4 told[4];
+        lin_f32x4 acc[8];                           // acc[t][v]: bucket 4 kg + v, column col0 + t
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = lin_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        int32_t len = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int b = b1 + 4 * kg + v;
+            const int bc = b < b_end ? b : b_end - 1;     // buckets beyond the run: the last one, with an empty list, not stored
+            e0[v] = ptr[bc];
+            e1[v] = b < b_end ? ptr[bc + 1] : e0[v];
+            told[v] = *reinterpret_cast<const uint4 *>(tab + (int64_t)bc * d.m);
+            len = (e1[v] - e0[v] > len) ? e1[v] - e0[v] : len;
+        }
+        for (int32_t c = 0; c < len; c += 4) {
+            int32_t hv[4][4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t k = e0[v] + c + j;
+                    hv[v][j] = rows[k < e1[v] ? k : 0];        // (entry 0 of the matrix's list always exists)
+                }
+            uint4 go[4][4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) go[v][j] = *reinterpret_cast<const uint4 *>(g + (int64_t)(hv[v][j] & INT32_MAX) * d.m);
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool live = e0[v] + c + j < e1[v];
+                    const uint32_t w4[4] = {go[v][j].x, go[v][j].y, go[v][j].z, go[v][j].w};
+                    const uint32_t flip = hv[v][j] < 0 ? 0x80000000u : 0u;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t bits = (e & 1) ? (w4[e >> 1] & 0xFFFF0000u) : (w4[e >> 1] << 16);
+                        acc[e][v] = acc[e][v] + (live ? __uint_as_float(bits ^ flip) : 0.0f);
+                    }
+                }
+        }
+        // ... minus U Q+^T: A = -U[b1 + cc][4 q + kg], B = Q+[col0 + t][4 q + kg]
+        {
+            const int ub = b1 + cc < b_end ? b1 + cc : b_end - 1;
+            float a[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a[q] = -U[(int64_t)ub * 32 + 4 * q + kg];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                float bq[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) bq[q] = sq[(t * 8 + q) * 64 + lane];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], bq[q], acc[t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int b = b1 + 4 * kg + v;
+            if (b >= b_end) continue;
+            const float coef = __builtin_fmaf(dp.omb, (float)(e1[v] - e0[v]), dp.beta);
+            const uint32_t tw[4] = {told[v].x, told[v].y, told[v].z, told[v].w};
+            uint32_t ow[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                float o0 = __builtin_fmaf(coef, half_bits_to_f32(tw[e2] & 0xFFFFu), acc[2 * e2][v]);
+                float o1 = __builtin_fmaf(coef, half_bits_to_f32(tw[e2] >> 16), acc[2 * e2 + 1][v]);
+                asm volatile("" : "+v"(o0), "+v"(o1));      // round to fp32 first, then to fp16 (see k_cs_update_octet)
+                ow[e2] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)o0) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)o1) << 16);
+            }
+            *reinterpret_cast<uint4 *>(tab + (int64_t)b * d.m) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
     }
 }
@@ -915,6 +1064,7 @@ hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void 
                             double *ws, hipStream_t st, Span span)
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_cs_pass_p(dp, grads, table, Q, P, ws, st);
     if (dp.n_p_f > 0) CONEF_CS_OCTET_DISPATCH(k_cs_p_octet, dim3(dp.n_p_f), st, dp, grads, table, Q, P, ws);
     if (dp.n_p > 0) CONEF_CS_DISPATCH_RP(k_cs_p_generic, dim3(dp.n_p), dim3(256), st, dp, grads, table, Q, P);
     if (span.end) (void)hipEventRecord(span.end, st);
@@ -925,7 +1075,9 @@ hipError_t launch_cs_pass_p(const DevicePlan &dp, const void *grads, const void 
 hipError_t launch_cs_pass_q(const DevicePlan &dp, const void *grads, const void *table, const float *Phat, float *Qout,
                             double *ws, hipStream_t st, Span span)
 {
+    if (dp.n_cs_u > 0) hipLaunchKernelGGL(k_cs_bucket_sums, dim3(dp.n_cs_u), dim3(256), 0, st, dp, Phat, ws);
     if (span.begin) (void)hipEventRecord(span.begin, st);
+    mfma_cs_pass_q(dp, grads, table, Phat, ws, st);
     if (dp.n_q_f > 0) CONEF_CS_OCTET_DISPATCH(k_cs_q_octet, dim3((dp.n_q_f + 3) / 4), st, dp, grads, table, Phat, ws);
     if (dp.n_q > 0) CONEF_CS_DISPATCH_RP(k_cs_q_generic, dim3(dp.n_q), dim3(kGenQCols), st, dp, grads, table, Phat, ws);
     if (span.end) (void)hipEventRecord(span.end, st);
@@ -934,10 +1086,15 @@ hipError_t launch_cs_pass_q(const DevicePlan &dp, const void *grads, const void 
 }
 
 hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *table, const float *Phat, const float *Qn,
-                              hipStream_t st, Span span)
+                              double *ws, hipStream_t st, Span span)
 {
+    // linear form: the bucket sums of the P^ handed in (whatever an earlier stage call has left in the workspace)
+    if (dp.n_cs_u > 0) hipLaunchKernelGGL(k_cs_bucket_sums, dim3(dp.n_cs_u), dim3(256), 0, st, dp, Phat, ws);
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    if (dp.n_cs_err_f > 0) {
+    if (dp.n_cs_lin > 0)
+        hipLaunchKernelGGL(k_cs_lin_update, dim3((dp.n_cs_lin + 3) / 4), dim3(256), 0, st, dp, reinterpret_cast<const uint16_t *>(grads),
+                           reinterpret_cast<uint16_t *>(table), Qn, ws);
+    if (dp.n_cs_err_f > 0 && dp.n_cs_err_f_old > 0) {
         const dim3 grid(dp.n_cs_err_f);
         const bool bf = dp.dtype == 1, fh = dp.table_dtype == 1;
         if (bf && fh) CONEF_CS_UPDATE_RP(true, true, grid, st, dp, grads, table, Phat, Qn);

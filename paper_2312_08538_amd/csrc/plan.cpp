@@ -22,13 +22,13 @@ inline int log2i(int64_t v) { int s = 0; while ((int64_t(1) << s) < v) ++s; retu
 
 namespace {
 int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
-                   int dtype, uint64_t seed, bool sketch);
+                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok);
 }
 
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,
               int block, int dtype, uint64_t seed)
 {
-    return make_plan_impl(plan, rows, cols, n_mats, rank, bits, block, dtype, seed, false);
+    return make_plan_impl(plan, rows, cols, n_mats, rank, bits, block, dtype, seed, false, false);
 }
 
 namespace {
@@ -153,7 +153,8 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
     for (int l = 0; l < n_mats; ++l)
         if (sketch_rows[l] < 1 || sketch_rows[l] > rows[l]) return kEinval;
     // the quantiser's parameters are not used in this mode; any valid pair will do
-    int rc = make_plan_impl(plan, rows, cols, n_mats, rank, 8, 4, dtype, seed, true);
+    // the linear form (see MatDesc::cs_lin) needs an fp16 table: its entries split into two bf16 operands exactly
+    int rc = make_plan_impl(plan, rows, cols, n_mats, rank, 8, 4, dtype, seed, true, table_dtype == 1);
     if (rc != kOk) return rc;
     try {
         plan.sketch = true; plan.beta = beta; plan.table_dtype = table_dtype;
@@ -216,6 +217,24 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
             plan.mats[l].st_part_off = wd;
             wd += plan.mats[l].st_slots;
         }
+        // the linear form: T and U, partial sums of the Q+ pass for the table's row tiles behind the gradient's, work tables
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            if (!d.cs_lin) continue;
+            d.cs_t_off = wd; wd += round_up(d.w * 32, 32);
+            d.cs_u_off = wd; wd += round_up(d.w * 32 / 2, 32);
+            d.cs_q_tiles_g = d.n_q_tiles;
+            const int32_t tiles_t = (int32_t)ceil_div(d.w, d.q_tile_rows);
+            d.n_q_tiles = d.cs_q_tiles_g + tiles_t;
+            d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * 32, 32);
+            for (int64_t r0 = 0; r0 < d.w; r0 += kMfmaRows) plan.cs_t_items.push_back({l, (int32_t)r0, 0, 0});
+            for (int32_t rt = 0; rt < tiles_t; ++rt)
+                for (int32_t cp = 0; cp < (int32_t)((d.m / 128 + 1) / 2); ++cp) plan.cs_qt_items.push_back({l, cp, rt, 0});
+            for (int64_t b0 = 0; b0 < d.w; b0 += 8) plan.cs_u_items.push_back({l, (int32_t)b0, (int32_t)std::min<int64_t>(8, d.w - b0), 0});
+            for (int64_t b0 = 0; b0 < d.w; b0 += 128)
+                for (int32_t st = 0; st < (int32_t)(d.m / 128); ++st)
+                    plan.cs_lin_items.push_back({l, st, (int32_t)b0, (int32_t)std::min<int64_t>(128, d.w - b0)});
+        }
         plan.ws_doubles = (size_t)round_up(wd, 32);
         plan.workspace_bytes = (size_t)round_up((int64_t)plan.ws_doubles * 8, 256);
     } catch (const std::bad_alloc &) {
@@ -226,7 +245,7 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
 
 namespace {
 int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
-                   int dtype, uint64_t seed, bool sketch)
+                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok)
 {
     if (!rows || !cols || n_mats < 1) return kEinval;
     if (rank < 1 || rank > kMaxRank) return kEinval;
@@ -281,6 +300,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             const bool sketch_octet = sketch && d.m % 8 == 0;
             d.m8 = (int32_t)(d.m / 8);
             d.lb_shift = block_ok ? log2i(block / 8) : 0;
+            d.cs_lin = (sketch && cs_lin_ok && rank == 32 && dtype == 1 && d.m % 128 == 0 && d.m <= (1 << 24)) ? 1 : 0;
             if (sketch_octet) d.path = kPathOctet;
             else if (d.path == kPathOctet) {
                 // lanes per row segment: the largest power of two <= 64 that divides m/8 and holds a block
@@ -311,12 +331,12 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             // generic family: short row tiles for small matrices (their workgroups are latency bound,
             // so parallelism has to come from the number of tiles)
             const int gen_q_rows = d.n <= 1024 ? 16 : kGenQRows;
-            d.q_tile_rows = d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : gen_q_rows;
+            d.q_tile_rows = d.cs_lin ? 2048 : d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : gen_q_rows;
             d.n_q_tiles = (int32_t)ceil_div(d.n, d.q_tile_rows);
             d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * rank, 32);
             d.n_p_chunks = 1;
             d.p_chunk_cols = (int32_t)d.m;
-            if (d.path == kPathOctet) {
+            if (d.path == kPathOctet && !d.cs_lin) {
                 d.p_chunk_cols = p_cols;
                 d.n_p_chunks = (int32_t)ceil_div(d.m, d.p_chunk_cols);
                 if (d.n_p_chunks > 1) {
@@ -359,7 +379,8 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             const MatDesc &d = plan.mats[l];
             // passes of the MFMA family that exist; the others fall back to the generic kernels
             const bool mf = d.path == kPathMfma;
-            const bool mf_p = mf && (kMfmaPasses & 1), mf_q = mf && (kMfmaPasses & 2), mf_e = mf && (kMfmaPasses & 4);
+            const bool mf_p = (mf && (kMfmaPasses & 1)) || d.cs_lin, mf_q = (mf && (kMfmaPasses & 2)) || d.cs_lin,
+                       mf_e = mf && (kMfmaPasses & 4);
             if (mf_p) {
                 for (int64_t r0 = 0; r0 < d.n; r0 += kMfmaRows) plan.p_m_items.push_back({l, (int32_t)r0, 0, 0});
             }
@@ -368,7 +389,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                 for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
                     for (int32_t cp = 0; cp < (int32_t)((d.m / 128 + 1) / 2); ++cp) plan.q_m_items.push_back({l, cp, rt, 0});
             }
-            if (mf_q || mf_e)
+            if ((mf_q || mf_e) && mf)
                 for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.split_p_items.push_back({l, (int32_t)(r0 / 64), 0, 0});
             if (mf_e) {
                 for (int64_t k0 = 0; k0 < d.m; k0 += 64) plan.split_qn_items.push_back({l, (int32_t)(k0 / 64), 0, 0});
@@ -391,7 +412,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                     for (int64_t b0 = 0; b0 < d.nblk; b0 += 4 * per_wave)
                         plan.err_items.push_back({l, (int32_t)b0, per_wave, 0});
                 }
-            } else {
+            } else if (!d.cs_lin) {
                 const int lr = 1 << d.lr_shift, rw = 64 / lr;
                 const int32_t strips = d.m8 / lr;
                 // consecutive items are the column chunks of one row tile: they run side by side on one
@@ -419,7 +440,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             for (int32_t t = 0; t < d.n_gram_tiles; ++t) plan.gram_items.push_back({l, t, 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
             // a matrix-core matrix with a single row tile gets its Q+ straight from the Q+ pass
-            if (!(mf_q && d.n_q_tiles == 1))
+            if (!(mf_q && d.n_q_tiles == 1) || d.cs_lin)
                 for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += kUpdRows)
@@ -439,7 +460,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
         if (!plan.p_m_items.empty()) {
             std::vector<int> order;                         // matrix-core matrices, longest rows first, then by shape
             for (int l = 0; l < n_mats; ++l)
-                if (plan.mats[l].path == kPathMfma && (kMfmaPasses & 1)) order.push_back(l);
+                if ((plan.mats[l].path == kPathMfma && (kMfmaPasses & 1)) || plan.mats[l].cs_lin) order.push_back(l);
             std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
                 const MatDesc &a = plan.mats[x], &b = plan.mats[y];
                 return a.m != b.m ? a.m > b.m : a.n > b.n;

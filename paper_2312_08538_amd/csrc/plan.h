@@ -53,6 +53,12 @@ struct MatDesc {
     int64_t hash_off;               // offset of the matrix's n entries in row_hash and bucket_rows
     int64_t bptr_off;               // offset of its w + 1 entries in bucket_ptr
     int32_t cs_cols;                // columns per item of the sketch update pass
+    // count sketch in its linear form (rank 32, bf16 gradients, fp16 table, columns a multiple of 128): the sketch is
+    // never decoded per element; T = S Q and U = (signed bucket sums of P^) carry its share of the factors
+    int32_t cs_lin;                 // 1: this matrix takes the linear form
+    int32_t cs_q_tiles_g;           // row tiles of the Q+ pass over the gradient; the table's tiles follow them
+    int64_t cs_t_off;               // workspace offset (doubles) of T, w x 32 fp64
+    int64_t cs_u_off;               // workspace offset (doubles) of U, w x 32 fp32
     // random-block gradient compressor
     int32_t err_tile, err_pad;      // octet family: the err pass runs in strips with the residual on the fp32 matrix cores
     int64_t rb_k;                   // coordinates kept per step (0: not configured)
@@ -90,6 +96,9 @@ struct Plan {
     std::vector<int32_t> bucket_rows;   // per matrix n entries: row index (bit 31: sign -1), ascending within a bucket
     std::vector<WorkItem> cs_err_items; // sketch update: (mat, first bucket, buckets, column tile of cs_cols)
     std::vector<WorkItem> cs_err_f_items;  // the same for matrices of the octet path (wider tiles)
+    // linear form: (mat, first table row, 0, 0) tiles of 128 table rows for T = S Q; (mat, pair of column blocks, table row
+    // tile, 0) for S^T U; (mat, first bucket, buckets, 0) for U; (mat, strip of 128 columns, first bucket, buckets) for the update
+    std::vector<WorkItem> cs_t_items, cs_qt_items, cs_u_items, cs_lin_items;
     std::vector<MatDesc> mats;
     size_t grad_elems = 0, code_words = 0, n_scales = 0, p_elems = 0, q_elems = 0;
     bool any_octet = false, any_generic = false, any_p_chunks = false, any_mfma = false;

