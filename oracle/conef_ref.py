@@ -1,6 +1,7 @@
 """ctypes face of the CPU oracle: oracle/conef_ref.c (the step of Algorithm 2), sketch_ref.c (count sketch, partial
 update), randblock_ref.c (random block, scaled sign), iconef_ref.c (Algorithm 3, version 1), randk_ref.c (random-k) and
-iconef2_ref.c (Algorithm 3, version 2), built into one shared library with gcc.
+iconef2_ref.c (Algorithm 3, version 2) and sketch_col_ref.c (count sketch, column form), built into one shared library
+with gcc.
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
 bench.py's cpu_baseline leg.  The product package never imports this module.
@@ -25,6 +26,7 @@ _SRC_RB = os.path.join(_HERE, "randblock_ref.c")
 _SRC_I = os.path.join(_HERE, "iconef_ref.c")
 _SRC_RK = os.path.join(_HERE, "randk_ref.c")
 _SRC_I2 = os.path.join(_HERE, "iconef2_ref.c")
+_SRC_CSC = os.path.join(_HERE, "sketch_col_ref.c")
 _LIB = os.path.join(_HERE, "libconef_ref.so")
 
 F32, BF16 = 0, 1
@@ -33,10 +35,10 @@ F32, BF16 = 0, 1
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off: every fused multiply-add
     in the source is an explicit fmaf(), nothing else may be contracted."""
-    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2))
+    newest = max(os.path.getmtime(f) for f in (_SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2, _SRC_CSC))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2, "-lm"]
+               "-mfma", "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_SKETCH, _SRC_RB, _SRC_I, _SRC_RK, _SRC_I2, _SRC_CSC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -126,6 +128,14 @@ def lib() -> ctypes.CDLL:
         L.ref_cs_rk_step_matrix.restype = None
         L.ref_i_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp, vp]
         L.ref_i_rk_step_matrix.restype = None
+        L.ref_csc_decode.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp]
+        L.ref_csc_decode.restype = None
+        L.ref_csc_form_p.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, f32, vp]
+        L.ref_csc_form_p.restype = None
+        L.ref_csc_update.argtypes = [vp, i64, i64, vp, vp, i64, f32, vp, i32]
+        L.ref_csc_update.restype = None
+        L.ref_csc_step_matrix.argtypes = [vp, i32, i64, i64, i32, i64, f32, u64, u32, vp, i32, vp, vp, vp, vp]
+        L.ref_csc_step_matrix.restype = None
         L.ref_i2_start.argtypes = [u64, u32, u64, i64, i64]
         L.ref_i2_start.restype = i64
         L.ref_i2_rb_step_matrix.argtypes = [vp, i32, i64, i64, i64, i32, i32, u64, u32, u64, vp, vp, vp, vp, vp]
@@ -570,6 +580,53 @@ def i_rk_step_matrix(g, codes, scales, codes2, scales2, G: int, bits: int, block
     lib().ref_i_rk_step_matrix(_p(ga), dt, N, G, bits, block, seed, mat, step, _p(codes), _p(scales), _p(codes2),
                                _p(scales2), _p(delta), _p(work))
     return delta
+
+
+# ---------------------------------------------------------------- count sketch, column form (oracle/sketch_col_ref.c)
+# The table is n x w; bucket / sign come from cs_hash(seed, mat, m, w): one hash per column.
+def csc_decode(table, bucket, sign, m: int) -> np.ndarray:
+    ta, tt = table_array(table)
+    n, w = ta.shape
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    e = np.empty((n, m), np.float32)
+    lib().ref_csc_decode(_p(ta), tt, n, m, w, _p(b), _p(s), _p(e))
+    return e
+
+
+def csc_form_p(g, table, bucket, sign, beta: float) -> np.ndarray:
+    ga, dt = grad_array(g)
+    ta, tt = table_array(table)
+    n, m = g.shape
+    assert ta.shape[0] == n
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    p = np.empty((n, m), np.float32)
+    lib().ref_csc_form_p(_p(ga), dt, _p(ta), tt, n, m, ta.shape[1], _p(b), _p(s), beta, _p(p))
+    return p
+
+
+def csc_update(x, bucket, sign, beta: float, table) -> None:
+    """table (n x w) <- beta * table + column sketch of x, in place."""
+    xa = _c(x, np.float32)
+    n, m = xa.shape
+    assert table.flags.c_contiguous and table.shape[0] == n
+    _, tt = table_array(table)
+    b, s = _c(bucket, np.int32), _c(sign, np.int8)
+    lib().ref_csc_update(_p(xa), n, m, _p(b), _p(s), table.shape[1], beta, _p(table), tt)
+
+
+def csc_step_matrix(g, table, Q, rank: int, beta: float, seed: int, mat: int):
+    """One partial-ConEF step with the column count sketch on one matrix; `table` (n x w) updated in place; returns
+    (Phat, Qn)."""
+    ga, dt = grad_array(g)
+    n, m = g.shape
+    assert table.flags.c_contiguous and table.shape[0] == n
+    _, tt = table_array(table)
+    Qs = np.ascontiguousarray(Q, np.float32)
+    P, Qn = np.empty((n, rank), np.float32), np.empty((m, rank), np.float32)
+    work = np.empty(2 * n * m, np.float32)
+    lib().ref_csc_step_matrix(_p(ga), dt, n, m, rank, table.shape[1], beta, seed, mat, _p(table), tt, _p(Qs), _p(P), _p(Qn),
+                              _p(work))
+    return P, Qn
 
 
 # ---------------------------------------------------------------- iConEF version 2 (oracle/iconef2_ref.c)
