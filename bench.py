@@ -160,15 +160,17 @@ def sketch_bytes(w, keep: float, table_bytes: int = 2) -> int:
     return int(tot)
 
 
-def run_sketch(w, keep: float, beta: float, steps: int = 10, warmup: int = 3):
+def run_sketch(w, keep: float, beta: float, steps: int = 10, warmup: int = 3, columns: bool = False):
     """Times the step with the count sketch as the error compressor (Section 4.2.2, Algorithm 4) on the
-    workload's layout: fp16 table of `keep` x rows buckets per matrix, HIP events around the stages."""
+    workload's layout: fp16 table of `keep` x rows buckets per matrix (columns: the column form of Section 5.3, `keep` x
+    cols buckets), HIP events around the stages."""
     import torch
 
     from paper_2312_08538_amd import binding as B
     from paper_2312_08538_amd import workloads as wl
 
-    model = B.SketchModel(w.layout, wl.sketch_rows(w.layout, keep), w.rank, beta, B.TABLE_F16, w.grad_dtype, w.lib_seed)
+    buckets = [max(1, int(m * keep)) for _, m in w.layout] if columns else wl.sketch_rows(w.layout, keep)
+    model = B.SketchModel(w.layout, buckets, w.rank, beta, B.TABLE_F16, w.grad_dtype, w.lib_seed, columns=columns)
     buf = model.alloc("cuda:0")
     goffs = [o["grad_off"] for o in model.offsets]
     n_sets = max(2, min(8, int(512 * 2**20 // max(1, w.grad_bytes)) + 1))
@@ -585,6 +587,7 @@ def main():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--columns", action="store_true", help="with --count-sketch: the column form of the sketch")
     ap.add_argument("--count-sketch", action="store_true",
                     help="time only the step with the count sketch as the error compressor (fp16 table, keep 0.2, "
                          "beta 0.9) on --workload and print its line; for profiling that mode on its own")
@@ -650,10 +653,11 @@ def main():
                           "steps": a.steps, "config": {"workload": w.name, "fraction": 0.1}, **r}), flush=True)
         return
     if a.count_sketch:
-        r = run_sketch(w, 0.2, 0.9, a.steps, a.warmup)
+        r = run_sketch(w, 0.2, 0.9, a.steps, a.warmup, columns=a.columns)
         print(json.dumps({"metric": "ConEF-CS step throughput: gradient GB/s processed", "value": r["grad_GB/s"],
                           "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-                          "config": {"workload": w.name, "rank": w.rank, "keep": 0.2, "beta": 0.9, "table": "f16"},
+                          "config": {"workload": w.name, "rank": w.rank, "keep": 0.2, "beta": 0.9, "table": "f16",
+                                     "form": "column" if a.columns else "row"},
                           **r}), flush=True)
         return
     ms, stage_ms, finite, stats = run_gpu(w, a.steps, a.warmup)
@@ -711,6 +715,8 @@ def main():
         # the count sketch as the error compressor (fp16 table with a fifth of the rows: 90 % of an fp32 error
         # vector saved, beta = 0.9, the setting of Section 5.2), beside the step, not inside `value`
         out["count_sketch"] = {"keep": 0.2, "beta": 0.9, "table": "f16",
+                               "column_form": {name: run_sketch(wl.WORKLOADS[name], 0.2, 0.9, columns=True)
+                                               for name in ("cnn", "lm")},
                                "workloads": {name: run_sketch(wl.WORKLOADS[name], 0.2, 0.9)
                                              for name in ("cnn", "lm", "translation", "large")}}
         # the unscaled random-block gradient compressor in place of the rank-r one (a tenth of the coordinates kept)

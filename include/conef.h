@@ -183,6 +183,17 @@ int conef_apply_update(conef_ctx *ctx, const float *P_hat, const float *Q_new, f
 enum { CONEF_TABLE_F32 = 0, CONEF_TABLE_F16 = 1 };
 int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
                   float beta, int table_dtype, int grad_dtype, uint64_t seed);
+/* The same sketch in the COLUMN form of Section 5.3 (the paper saw no difference between the two): a whole column is one
+ * entry of the sketched vector, so there is one hash per column (column k of matrix l: the Philox call above with k for
+ * i) and the table of a matrix is rows x sketch_cols, row-major:
+ *   e[:, k] = s(k) * table[:, h(k)],   table[i, b] <- fma(beta, table[i, b], sum over the columns k of bucket b,
+ *                                                        ascending, of s(k) * (p - P^ Q+^T)[i, k])
+ *   sketch_cols[n_mats]  buckets per matrix, 1 <= sketch_cols[l] <= cols[l]; cols[l] <= 16384 (CONEF_EINVAL otherwise)
+ * conef_cs_sizes, conef_cs_offsets (returns sketch_cols), conef_cs_hash (cols entries), conef_cs_step and its stage
+ * calls and conef_cs_decode_error serve such a context as they serve the row form; the element-wise gradient
+ * compressors (conef_cs_rb_step, conef_cs_rk_step, conef_cs_ss_step) are not built for it: CONEF_ESTATE. */
+int conef_csc_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_cols, int n_mats, int rank,
+                   float beta, int table_dtype, int grad_dtype, uint64_t seed);
 int conef_cs_sizes(const conef_ctx *ctx, size_t *table_elems);                 /* elements of the flat table buffer */
 int conef_cs_offsets(const conef_ctx *ctx, int mat, size_t *table_off, int64_t *sketch_rows);
 /* bucket_out[rows], sign_out[rows] (+1 / -1): host arrays owned by the caller. */

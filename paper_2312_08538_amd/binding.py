@@ -27,7 +27,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step", "conef_i_step_p", "conef_i_step_q", "conef_i_step_err", "conef_i_step",
            "conef_i2_configure", "conef_i2_sizes", "conef_i2_offsets", "conef_i2_start", "conef_i2_rb_step", "conef_i2_rk_step",
            "conef_rk_configure", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
-           "conef_cs_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
+           "conef_cs_init", "conef_csc_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
 
@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
     L.conef_decompress.argtypes = [vp, vp, vp, vp, vp]
     L.conef_apply_update.argtypes = [vp, vp, vp, vp, vp]
     L.conef_cs_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), ctypes.POINTER(ctypes.c_int64), i32, i32,
+                                ctypes.c_float, i32, i32, u64]
+    L.conef_csc_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(conef_mat), ctypes.POINTER(ctypes.c_int64), i32, i32,
                                 ctypes.c_float, i32, i32, u64]
     L.conef_cs_sizes.argtypes = [vp, szp]
     L.conef_cs_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
@@ -379,15 +381,20 @@ def conef_apply_update(ctx, P_hat, Q_new, params, stream=0):
 
 # count-sketch mode
 def conef_cs_init(layout: Sequence[Tuple[int, int]], sketch_rows: Sequence[int], rank: int, beta: float,
-                  table_dtype: int, grad_dtype: int, seed: int):
+                  table_dtype: int, grad_dtype: int, seed: int, columns: bool = False):
+    """columns: the column form (conef_csc_init; sketch_rows then holds the buckets per matrix, at most its columns)."""
     arr = (conef_mat * max(1, len(layout)))()
     for i, (n, m) in enumerate(layout):
         arr[i].rows, arr[i].cols = n, m
     w = (ctypes.c_int64 * max(1, len(sketch_rows)))(*[int(x) for x in sketch_rows])
     ctx = ctypes.c_void_p()
-    _check(lib().conef_cs_init(ctypes.byref(ctx), arr, w, len(layout), rank, beta, table_dtype, grad_dtype, seed),
-           "conef_cs_init")
+    fn, name = (lib().conef_csc_init, "conef_csc_init") if columns else (lib().conef_cs_init, "conef_cs_init")
+    _check(fn(ctypes.byref(ctx), arr, w, len(layout), rank, beta, table_dtype, grad_dtype, seed), name)
     return ctx
+
+
+def conef_csc_init(layout, sketch_cols, rank: int, beta: float, table_dtype: int, grad_dtype: int, seed: int):
+    return conef_cs_init(layout, sketch_cols, rank, beta, table_dtype, grad_dtype, seed, columns=True)
 
 
 def conef_cs_sizes(ctx) -> dict:
@@ -500,11 +507,12 @@ class Model:
 class SketchModel:
     """One count-sketch context plus its sizes and per-matrix offsets (see Model)."""
 
-    def __init__(self, layout, sketch_rows, rank, beta, table_dtype, grad_dtype, seed):
+    def __init__(self, layout, sketch_rows, rank, beta, table_dtype, grad_dtype, seed, columns=False):
         self.layout = [tuple(x) for x in layout]
         self.sketch_rows = [int(x) for x in sketch_rows]
         self.rank, self.beta, self.table_dtype, self.grad_dtype, self.seed = rank, beta, table_dtype, grad_dtype, seed
-        self.ctx = conef_cs_init(self.layout, self.sketch_rows, rank, beta, table_dtype, grad_dtype, seed)
+        self.columns = columns
+        self.ctx = conef_cs_init(self.layout, self.sketch_rows, rank, beta, table_dtype, grad_dtype, seed, columns)
         self.sizes = conef_sizes(self.ctx)
         self.sizes.update(conef_cs_sizes(self.ctx))
         self.offsets = [dict(conef_offsets(self.ctx, l), **conef_cs_offsets(self.ctx, l))

@@ -96,6 +96,9 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_cs_qt = (int)pl.cs_qt_items.size();
     d.n_cs_u = (int)pl.cs_u_items.size();
     d.n_cs_lin = (int)pl.cs_lin_items.size();
+    d.cs_cols_mode = pl.sketch_cols ? 1 : 0;
+    d.cs_max_cols = 0;
+    for (const MatDesc &m : pl.mats) d.cs_max_cols = std::max<int>(d.cs_max_cols, (int)std::min<int64_t>(m.m, kCscMaxCols));
     d.n_cs_err_f_old = 0;
     for (const MatDesc &m : pl.mats)
         if (pl.sketch && m.path == kPathOctet && !m.cs_lin) d.n_cs_err_f_old += 1;
@@ -189,8 +192,26 @@ int conef_init(conef_ctx **out, const conef_mat *layout, int n_mats, int rank, i
     return CONEF_OK;
 }
 
+namespace {
+int cs_init_impl(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
+                 float beta, int table_dtype, int grad_dtype, uint64_t seed, bool columns);
+}
+
 int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
                   float beta, int table_dtype, int grad_dtype, uint64_t seed)
+{
+    return cs_init_impl(out, layout, sketch_rows, n_mats, rank, beta, table_dtype, grad_dtype, seed, false);
+}
+
+int conef_csc_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_cols, int n_mats, int rank,
+                   float beta, int table_dtype, int grad_dtype, uint64_t seed)
+{
+    return cs_init_impl(out, layout, sketch_cols, n_mats, rank, beta, table_dtype, grad_dtype, seed, true);
+}
+
+namespace {
+int cs_init_impl(conef_ctx **out, const conef_mat *layout, const int64_t *sketch_rows, int n_mats, int rank,
+                 float beta, int table_dtype, int grad_dtype, uint64_t seed, bool columns)
 {
     if (!out) return CONEF_EINVAL;
     *out = nullptr;
@@ -202,7 +223,7 @@ int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketc
         std::vector<int64_t> rows(n_mats), cols(n_mats);
         for (int l = 0; l < n_mats; ++l) { rows[l] = layout[l].rows; cols[l] = layout[l].cols; }
         rc = make_sketch_plan(ctx->plan, rows.data(), cols.data(), sketch_rows, n_mats, rank, beta, table_dtype,
-                              grad_dtype, seed);
+                              grad_dtype, seed, columns);
     } catch (const std::bad_alloc &) {
         rc = CONEF_ENOMEM;
     }
@@ -210,6 +231,7 @@ int conef_cs_init(conef_ctx **out, const conef_mat *layout, const int64_t *sketc
     *out = ctx;
     return CONEF_OK;
 }
+}  // namespace
 
 int conef_cs_sizes(const conef_ctx *ctx, size_t *table_elems)
 {
@@ -233,7 +255,8 @@ int conef_cs_hash(const conef_ctx *ctx, int mat, int32_t *bucket_out, int8_t *si
     if (!ctx || mat < 0 || mat >= (int)ctx->plan.mats.size() || !bucket_out || !sign_out) return CONEF_EINVAL;
     if (!ctx->plan.sketch) return CONEF_ESTATE;
     const MatDesc &d = ctx->plan.mats[mat];
-    for (int64_t i = 0; i < d.n; ++i) {
+    const int64_t hashed = ctx->plan.sketch_cols ? d.m : d.n;       // one hash per row, or per column in the column form
+    for (int64_t i = 0; i < hashed; ++i) {
         const int32_t hv = ctx->plan.row_hash[(size_t)(d.hash_off + i)];
         bucket_out[i] = hv & INT32_MAX;
         sign_out[i] = hv < 0 ? -1 : 1;
@@ -619,7 +642,7 @@ int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
 {
     if (!ctx || !grads || !table || !delta_out) return CONEF_EINVAL;
-    if (!ctx->plan.sketch || ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
+    if (!ctx->plan.sketch || ctx->plan.sketch_cols || ctx->plan.rb_delta_elems == 0) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(delta_out, 4)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
@@ -768,7 +791,7 @@ int conef_i2_rk_step(conef_ctx *ctx, const void *grads, const float *e_in, float
 int conef_cs_rk_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step, void *hip_stream)
 {
     if (!ctx || !grads || !table || !delta_out) return CONEF_EINVAL;
-    if (!ctx->plan.sketch || ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
+    if (!ctx->plan.sketch || ctx->plan.sketch_cols || ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(delta_out, 4)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
@@ -825,7 +848,7 @@ int conef_cs_ss_step(conef_ctx *ctx, const void *grads, void *table, uint32_t *s
                      void *workspace, void *hip_stream)
 {
     if (!ctx || !grads || !table || !sign_out || !scale_out || !workspace) return CONEF_EINVAL;
-    if (!ctx->plan.sketch) return CONEF_ESTATE;
+    if (!ctx->plan.sketch || ctx->plan.sketch_cols) return CONEF_ESTATE;
     if (misaligned(grads, 16) || misaligned(table, 16) || misaligned(sign_out, 4) || misaligned(scale_out, 4) ||
         misaligned(workspace, 256))
         return CONEF_EINVAL;

@@ -22,6 +22,8 @@ struct DevicePlan {
     const WorkItem *cs_err_items = nullptr, *cs_err_f_items = nullptr;
     const WorkItem *cs_t_items = nullptr, *cs_qt_items = nullptr, *cs_u_items = nullptr, *cs_lin_items = nullptr;   // linear form
     int n_cs_t = 0, n_cs_qt = 0, n_cs_u = 0, n_cs_lin = 0;
+    int cs_max_cols = 0;        // column form: columns of the widest matrix (LDS floats of the update pass)
+    int cs_cols_mode = 0;       // count sketch in the column form: row_hash / bucket lists are over columns, tables rows x w
     int n_cs_err_f_old = 0;     // matrices of the octet path that are NOT in the linear form (0: skip their update launch)
     const int32_t *row_hash = nullptr, *bucket_ptr = nullptr, *bucket_rows = nullptr;
     int n_cs_err = 0, n_cs_err_f = 0;

@@ -53,14 +53,17 @@ __global__ __launch_bounds__(256) void k_cs_p_generic(DevicePlan dp, const void 
     const int64_t row = (int64_t)it.a + (threadIdx.x >> 6);
     if (row >= d.n) return;
     const int r = dp.rank;
-    const int32_t hv = dp.row_hash[d.hash_off + row];
-    const float somb = signed_omb(dp, hv);
-    const int64_t trow = d.table_off + (int64_t)(hv & INT32_MAX) * d.m;
+    // row form: the row's bucket and sign; column form (cs_cols_mode): the column's, the table row is the matrix row's
+    const bool colm = dp.cs_cols_mode != 0;
+    const int32_t hv_row = colm ? 0 : dp.row_hash[d.hash_off + row];
+    const int64_t trow = colm ? d.table_off + row * d.w : d.table_off + (int64_t)(hv_row & INT32_MAX) * d.m;
     double acc[RP];
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
     for (int64_t k = lane; k < d.m; k += 64) {
-        const float t = table_load(table, dp.table_dtype, trow + k);
+        const int32_t hv = colm ? dp.row_hash[d.hash_off + k] : hv_row;
+        const float somb = signed_omb(dp, hv);
+        const float t = table_load(table, dp.table_dtype, colm ? trow + (hv & INT32_MAX) : trow + k);
         const double pv = (double)__builtin_fmaf(somb, t, load_grad(grads, dp.dtype, d.grad_off + row * d.m + k));
         const float *qrow = Q + d.q_off + k * r;
 #pragma unroll
@@ -93,9 +96,12 @@ __global__ __launch_bounds__(kGenQCols) void k_cs_q_generic(DevicePlan dp, const
     double acc[RP];
 #pragma unroll
     for (int c = 0; c < RP; ++c) acc[c] = 0.0;
+    const bool colm = dp.cs_cols_mode != 0;
+    const int32_t hv_col = colm ? dp.row_hash[d.hash_off + k] : 0;
     for (int64_t i = row0; i < row1; ++i) {
-        const int32_t hv = dp.row_hash[d.hash_off + i];
-        const float t = table_load(table, dp.table_dtype, d.table_off + (int64_t)(hv & INT32_MAX) * d.m + k);
+        const int32_t hv = colm ? hv_col : dp.row_hash[d.hash_off + i];
+        const float t = table_load(table, dp.table_dtype, colm ? d.table_off + i * d.w + (hv & INT32_MAX)
+                                                                : d.table_off + (int64_t)(hv & INT32_MAX) * d.m + k);
         const double pv = (double)__builtin_fmaf(signed_omb(dp, hv), t, load_grad(grads, dp.dtype, d.grad_off + i * d.m + k));
         const float *prow = Phat + d.p_off + i * r;
 #pragma unroll
@@ -145,6 +151,49 @@ __global__ __launch_bounds__(kCsCols) void k_cs_update_generic(DevicePlan dp, co
     }
 }
 
+// Column form (Section 5.3, "row or column"): the table is n x w, column k has bucket h(k) and sign s(k),
+//   S[i, b] <- fma(beta, S[i, b], sum over the columns k of bucket b, ascending, of s(k) (p - P^ Q+^T)[i, k]).
+// One workgroup per row of the matrix: the row of the table and then the row of the residual are staged in LDS (columns
+// strided over the threads, coalesced), then the threads take buckets and walk their column lists.
+template <int RP>
+__global__ __launch_bounds__(256) void k_csc_update(DevicePlan dp, const void *grads, void *table, const float *Phat,
+                                                    const float *Qn)
+{
+    extern __shared__ float s_x[];          // the widest matrix's columns (the launcher sizes it)
+    const WorkItem it = dp.cs_err_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int r = dp.rank;
+    const int64_t i = it.a;
+    float ph[RP];
+#pragma unroll
+    for (int c = 0; c < RP; ++c) ph[c] = (c < r) ? Phat[d.p_off + i * r + c] : 0.0f;
+    const int64_t trow = d.table_off + i * d.w;
+    for (int64_t k = threadIdx.x; k < d.m; k += 256) {
+        const int32_t hv = dp.row_hash[d.hash_off + k];
+        const float t = table_load(table, dp.table_dtype, trow + (hv & INT32_MAX));
+        const float pv = __builtin_fmaf(signed_omb(dp, hv), t, load_grad(grads, dp.dtype, d.grad_off + i * d.m + k));
+        const float *qrow = Qn + d.q_off + k * r;
+        float rec = 0.0f;
+#pragma unroll
+        for (int c = 0; c < RP; ++c)
+            if (c < r) rec = __builtin_fmaf(ph[c], qrow[c], rec);
+        s_x[k] = pv - rec;
+    }
+    __syncthreads();            // the whole row of the old table has been read, the whole residual row is in LDS
+    const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
+    const int32_t *cols = dp.bucket_rows + d.hash_off;
+    for (int64_t b = threadIdx.x; b < d.w; b += 256) {
+        float acc = 0.0f;
+        for (int32_t e = ptr[b]; e < ptr[b + 1]; ++e) {
+            const int32_t hv = cols[e];
+            const float x = s_x[hv & INT32_MAX];
+            acc = hv < 0 ? acc - x : acc + x;
+        }
+        const float s_old = table_load(table, dp.table_dtype, trow + b);
+        table_store(table, dp.table_dtype, trow + b, __builtin_fmaf(dp.beta, s_old, acc));
+    }
+}
+
 // e[i, :] = s(i) S[h(i), :] in fp32, for tests and export
 __global__ __launch_bounds__(256) void k_cs_decode(DevicePlan dp, const void *table, float *e_out)
 {
@@ -154,8 +203,10 @@ __global__ __launch_bounds__(256) void k_cs_decode(DevicePlan dp, const void *ta
         const int64_t j = ((int64_t)it.a << 10) + t * 256 + threadIdx.x;
         if (j >= d.N) return;
         const int64_t i = j / d.m, k = j - i * d.m;
-        const int32_t hv = dp.row_hash[d.hash_off + i];
-        const float v = table_load(table, dp.table_dtype, d.table_off + (int64_t)(hv & INT32_MAX) * d.m + k);
+        const bool colm = dp.cs_cols_mode != 0;
+        const int32_t hv = dp.row_hash[d.hash_off + (colm ? k : i)];
+        const float v = table_load(table, dp.table_dtype, colm ? d.table_off + i * d.w + (hv & INT32_MAX)
+                                                                : d.table_off + (int64_t)(hv & INT32_MAX) * d.m + k);
         e_out[d.grad_off + j] = hv < 0 ? -v : v;
     }
 }
@@ -1102,7 +1153,16 @@ hipError_t launch_cs_pass_err(const DevicePlan &dp, const void *grads, void *tab
         else if (fh) CONEF_CS_UPDATE_RP(false, true, grid, st, dp, grads, table, Phat, Qn);
         else CONEF_CS_UPDATE_RP(false, false, grid, st, dp, grads, table, Phat, Qn);
     }
-    if (dp.n_cs_err > 0)
+    if (dp.n_cs_err > 0 && dp.cs_cols_mode) {
+        const size_t lds = (size_t)dp.cs_max_cols * sizeof(float);
+        switch (dp.rpad) {
+        case 4: hipLaunchKernelGGL(k_csc_update<4>, dim3(dp.n_cs_err), dim3(256), lds, st, dp, grads, table, Phat, Qn); break;
+        case 8: hipLaunchKernelGGL(k_csc_update<8>, dim3(dp.n_cs_err), dim3(256), lds, st, dp, grads, table, Phat, Qn); break;
+        case 16: hipLaunchKernelGGL(k_csc_update<16>, dim3(dp.n_cs_err), dim3(256), lds, st, dp, grads, table, Phat, Qn); break;
+        default: hipLaunchKernelGGL(k_csc_update<32>, dim3(dp.n_cs_err), dim3(256), lds, st, dp, grads, table, Phat, Qn); break;
+        }
+    }
+    else if (dp.n_cs_err > 0)
         CONEF_CS_DISPATCH_RP(k_cs_update_generic, dim3(dp.n_cs_err), dim3(kCsCols), st, dp, grads, table, Phat, Qn);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();

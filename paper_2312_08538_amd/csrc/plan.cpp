@@ -22,7 +22,7 @@ inline int log2i(int64_t v) { int s = 0; while ((int64_t(1) << s) < v) ++s; retu
 
 namespace {
 int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
-                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok);
+                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok, bool all_generic = false);
 }
 
 int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits,
@@ -145,9 +145,66 @@ int configure_random_k(Plan &plan, const int64_t *group)
     return kOk;
 }
 
-int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
-                     int rank, float beta, int table_dtype, int dtype, uint64_t seed)
+namespace {
+// The column form: every matrix on the kernels for any shape; table rows x w; one hash per column; the update walks one row
+// of the matrix per workgroup, over the bucket lists of columns.
+int make_sketch_plan_columns(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *buckets, int n_mats, int rank,
+                             float beta, int table_dtype, int dtype, uint64_t seed)
 {
+    for (int l = 0; l < n_mats; ++l)
+        if (buckets[l] < 1 || buckets[l] > cols[l] || cols[l] > kCscMaxCols) return kEinval;
+    int rc = make_plan_impl(plan, rows, cols, n_mats, rank, 8, 4, dtype, seed, true, false, true);
+    if (rc != kOk) return rc;
+    try {
+        plan.sketch = true; plan.sketch_cols = true; plan.beta = beta; plan.table_dtype = table_dtype;
+        plan.code_words = 0; plan.n_scales = 0;
+        int64_t t = 0, h = 0, bp = 0;
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            d.w = buckets[l];
+            d.table_off = t; t += round_up(d.n * d.w, kAlign);
+            d.hash_off = h;  h += d.m;
+            d.bptr_off = bp; bp += d.w + 1;
+        }
+        plan.table_elems = (size_t)t;
+        plan.row_hash.assign((size_t)h, 0);
+        plan.bucket_rows.assign((size_t)h, 0);
+        plan.bucket_ptr.assign((size_t)bp, 0);
+        for (int l = 0; l < n_mats; ++l) {
+            MatDesc &d = plan.mats[l];
+            int32_t *ptr = plan.bucket_ptr.data() + d.bptr_off;
+            for (int64_t k = 0; k < d.m; ++k) {
+                int32_t b; bool neg;
+                sketch_hash(seed, (uint32_t)l, (uint32_t)k, d.w, &b, &neg);
+                plan.row_hash[(size_t)(d.hash_off + k)] = b | (neg ? INT32_MIN : 0);
+                ptr[b + 1] += 1;
+            }
+            for (int64_t b = 0; b < d.w; ++b) ptr[b + 1] += ptr[b];
+            std::vector<int32_t> fill(ptr, ptr + d.w);            // columns in ascending order within each bucket
+            for (int64_t k = 0; k < d.m; ++k) {
+                const int32_t hv = plan.row_hash[(size_t)(d.hash_off + k)];
+                plan.bucket_rows[(size_t)(d.hash_off + fill[hv & INT32_MAX]++)] = (int32_t)k | (hv & INT32_MIN);
+            }
+            d.cs_cols = (int32_t)d.m;
+            d.st_first = (int32_t)plan.cs_err_items.size();
+            for (int64_t i = 0; i < d.n; ++i) plan.cs_err_items.push_back({l, (int32_t)i, 1, 0});
+            d.st_slots = 0;
+        }
+    } catch (const std::bad_alloc &) {
+        return kEnomem;
+    }
+    return kOk;
+}
+}  // namespace
+
+int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
+                     int rank, float beta, int table_dtype, int dtype, uint64_t seed, bool columns)
+{
+    if (columns) {
+        if (!sketch_rows || !(beta >= 0.0f && beta < 1.0f) || (table_dtype != 0 && table_dtype != 1)) return kEinval;
+        if (!rows || !cols || n_mats < 1) return kEinval;
+        return make_sketch_plan_columns(plan, rows, cols, sketch_rows, n_mats, rank, beta, table_dtype, dtype, seed);
+    }
     if (!sketch_rows || !(beta >= 0.0f && beta < 1.0f) || (table_dtype != 0 && table_dtype != 1)) return kEinval;
     if (!rows || n_mats < 1) return kEinval;
     for (int l = 0; l < n_mats; ++l)
@@ -245,7 +302,7 @@ int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const
 
 namespace {
 int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, int rank, int bits, int block,
-                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok)
+                   int dtype, uint64_t seed, bool sketch, bool cs_lin_ok, bool all_generic)
 {
     if (!rows || !cols || n_mats < 1) return kEinval;
     if (rank < 1 || rank > kMaxRank) return kEinval;
@@ -297,7 +354,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                                                                                              : kPathGeneric;
             // count-sketch mode: the octet path needs whole octets per row only (16-byte aligned rows of
             // the gradient and of the table), at any rank
-            const bool sketch_octet = sketch && d.m % 8 == 0;
+            const bool sketch_octet = sketch && !all_generic && d.m % 8 == 0;
             d.m8 = (int32_t)(d.m / 8);
             d.lb_shift = block_ok ? log2i(block / 8) : 0;
             d.cs_lin = (sketch && cs_lin_ok && rank == 32 && dtype == 1 && d.m % 128 == 0 && d.m <= (1 << 24)) ? 1 : 0;
@@ -577,6 +634,31 @@ bool check_plan(const Plan &plan)
             c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 256, 256);
         if (!c.complete(plan)) return false;
     }
+    // pass 3 of the count-sketch mode, column form: every row of every matrix once; bucket lists hold every column once, ascending
+    if (plan.sketch && plan.sketch_cols) {
+        std::vector<int64_t> rows_seen(nm, 0);
+        for (const WorkItem &it : plan.cs_err_items) {
+            if (it.mat < 0 || it.mat >= (int)nm || it.a < 0 || it.a >= plan.mats[it.mat].n || it.b != 1) return false;
+            rows_seen[it.mat] += 1;
+        }
+        for (size_t l = 0; l < nm; ++l) {
+            const MatDesc &d = plan.mats[l];
+            if (rows_seen[l] != d.n || d.m > kCscMaxCols || d.path != kPathGeneric) return false;
+            const int32_t *ptr = plan.bucket_ptr.data() + d.bptr_off;
+            if (ptr[0] != 0 || ptr[d.w] != d.m) return false;
+            std::vector<char> seen(d.m, 0);
+            for (int64_t b = 0; b < d.w; ++b) {
+                if (ptr[b + 1] < ptr[b]) return false;
+                for (int32_t k = ptr[b]; k < ptr[b + 1]; ++k) {
+                    const int32_t hv = plan.bucket_rows[(size_t)(d.hash_off + k)], c = hv & INT32_MAX;
+                    if (c >= d.m || seen[c]) return false;
+                    if (k > ptr[b] && c <= (plan.bucket_rows[(size_t)(d.hash_off + k - 1)] & INT32_MAX)) return false;
+                    if (plan.row_hash[(size_t)(d.hash_off + c)] != ((int32_t)b | (hv & INT32_MIN))) return false;
+                    seen[c] = 1;
+                }
+            }
+        }
+    } else
     // pass 3 of the count-sketch mode: every table entry once; bucket lists hold every row once, ascending
     if (plan.sketch) {
         std::vector<int64_t> area(nm, 0);

@@ -131,6 +131,7 @@ struct Plan {
     size_t sign_words = 0;
     size_t rb_delta_elems = 0;      // set by configure_random_block
     size_t rk_delta_elems = 0;      // set by configure_random_k
+    bool sketch_cols = false;       // count sketch in the column form: tables are rows x w, hashes and bucket lists are over columns
     size_t i2_elems = 0;            // set by configure_i2 (never 0 once configured)
     bool i2_configured = false;
     std::vector<WorkItem> rb_items;     // matrices of whole power-of-two blocks: (mat, first run of 512 elements, runs), one item per wave
@@ -150,8 +151,10 @@ int make_plan(Plan &plan, const int64_t *rows, const int64_t *cols, int n_mats, 
 // The same for the count-sketch error compressor: sketch_rows[l] buckets (1 .. rows[l]) for matrix l,
 // beta in [0, 1), table_dtype 0 (fp32) or 1 (fp16).  Also computes the hash of every row and the
 // bucket lists.
+// columns: the column form (sketch_rows then holds the number of buckets per matrix, at most its columns)
 int make_sketch_plan(Plan &plan, const int64_t *rows, const int64_t *cols, const int64_t *sketch_rows, int n_mats,
-                     int rank, float beta, int table_dtype, int dtype, uint64_t seed);
+                     int rank, float beta, int table_dtype, int dtype, uint64_t seed, bool columns = false);
+constexpr int kCscMaxCols = 16384;  // column form: a row of the residual is staged in LDS
 
 // Random-block gradient compressor: keep[l] coordinates of matrix l per step (1 .. rows * cols).  Sets the
 // per-matrix fields, the Delta layout and (for a quantiser plan) the work tables.  Returns 0 or a negative code.

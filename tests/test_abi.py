@@ -173,6 +173,35 @@ def test_sketch_init_rejects_bad_arguments():
     assert B.lib().conef_cs_init(ctypes.byref(ctx), arr, None, 1, 2, 0.5, 0, 0, 0) == B.EINVAL     # null sketch_rows
 
 
+def test_column_sketch_init_plan_and_hash(ref):
+    """The column form of the count sketch (host side): argument checks, table sizes and offsets (rows x buckets), the
+    hash of the columns against the oracle's, the plan's self-check."""
+    L = B.lib()
+    layout = [(64, 147), (300, 256), (3, 5)]
+    buckets = [30, 256, 1]
+    seed = 0xFEED5
+    ctx = B.conef_csc_init(layout, buckets, 2, 0.5, B.TABLE_F16, B.BF16, seed)
+    B.conef_check_plan(ctx)
+    off = 0
+    for l, (n, m) in enumerate(layout):
+        o = B.conef_cs_offsets(ctx, l)
+        assert (o["table_off"], o["sketch_rows"]) == (off, buckets[l])
+        off += (n * buckets[l] + 63) // 64 * 64
+        b, s = B.conef_cs_hash(ctx, l, m)
+        rb, rs = ref.cs_hash(seed, l, m, buckets[l])
+        assert np.array_equal(b, rb) and np.array_equal(s, rs)
+    assert B.conef_cs_sizes(ctx)["table_elems"] == off
+    A = 512
+    assert L.conef_cs_rb_step(ctx, A, A, A, 0, 0) == B.ESTATE
+    assert L.conef_cs_ss_step(ctx, A, A, A, A, A, 0) == B.ESTATE
+    assert L.conef_step(ctx, A, A, A, A, A, A, A, 0, 0) == B.ESTATE         # a sketch context all the same
+    B.conef_destroy(ctx)
+    for bad_layout, bad_buckets in (([(64, 64)], [65]), ([(64, 64)], [0]), ([(8, 16392)], [10])):
+        with pytest.raises(B.ConefError) as e:
+            B.conef_csc_init(bad_layout, bad_buckets, 2, 0.5, B.TABLE_F32, B.F32, 1)
+        assert e.value.code == B.EINVAL
+
+
 def test_sketch_and_quantiser_contexts_refuse_each_others_calls():
     sk = B.conef_cs_init([(64, 64)], [16], 4, 0.5, B.TABLE_F32, B.F32, 0)
     qc = B.conef_init([(64, 64)], 4, 4, 64, B.F32, 0)
