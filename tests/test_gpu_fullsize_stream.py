@@ -25,17 +25,22 @@ def env():
 
 
 @pytest.mark.parametrize("which", ["random_block", "scaled_sign", "random_k", "iconef_random_block", "iconef_scaled_sign",
-                                   "iconef_random_k"])
+                                   "iconef_random_k", "iconef2_random_k"])
 def test_large_whole_model_stream_step_against_the_oracle(env, which):
     R, B, torch = env
     w = wl.WORKLOADS["large"]
     bits, block, W, seed = w.bits, w.block, 32 // w.bits, w.lib_seed
-    two, block_mode, strata = which.startswith("iconef"), which.endswith("random_block"), which.endswith("random_k")
+    v2 = which.startswith("iconef2")         # Algorithm 3, version 2: a random block of 5 % of every matrix as the first error vector
+    two, block_mode, strata = which.startswith("iconef") and not v2, which.endswith("random_block"), which.endswith("random_k")
     keep = wl.random_block_keep(w.layout, 0.1)
     group = [10] * len(w.layout)
     model = B.Model(w.layout, w.rank, bits, block, w.grad_dtype, seed)
     B.conef_rb_configure(model.ctx, keep)
     B.conef_rk_configure(model.ctx, group)
+    keep_e = [(n * m) // 20 for n, m in w.layout]
+    if v2:
+        B.conef_i2_configure(model.ctx, keep_e)
+        e_bufs = [torch.zeros(B.conef_i2_sizes(model.ctx)["e_elems"], dtype=torch.float32, device="cuda:0") for _ in range(2)]
     buf = model.alloc()
     codes2 = torch.zeros_like(buf["codes"]) if two else None
     scales2 = torch.zeros_like(buf["scales"]) if two else None
@@ -58,6 +63,8 @@ def test_large_whole_model_stream_step_against_the_oracle(env, which):
             B.conef_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], delta, t, st)
         elif which == "iconef_random_k":
             B.conef_i_rk_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, delta, t, st)
+        elif v2:
+            B.conef_i2_rk_step(model.ctx, buf["grads"], e_bufs[t % 2], e_bufs[(t + 1) % 2], buf["codes"], buf["scales"], delta, t, st)
         else:
             B.conef_i_ss_step(model.ctx, buf["grads"], buf["codes"], buf["scales"], codes2, scales2, signs, cs, buf["ws"], t, st)
         torch.cuda.synchronize()
@@ -71,9 +78,13 @@ def test_large_whole_model_stream_step_against_the_oracle(env, which):
     wl.device_fill_gradients(w, 0, buf["grads"], goffs)
     launch(0)
     before = download()
+    e_before = e_bufs[1].cpu().numpy() if v2 else None          # what step 0 left and step 1 reads
     wl.device_fill_gradients(w, 1, buf["grads"], goffs)
     launch(1)
     after = download()
+    e_after = e_bufs[0].cpu().numpy() if v2 else None
+    if v2:
+        assert np.any(e_before != 0)
     delta_h = delta.cpu().numpy()
     signs_h = signs.cpu().numpy().view(np.uint32)
     cs_h = cs.cpu().numpy()
@@ -101,6 +112,12 @@ def test_large_whole_model_stream_step_against_the_oracle(env, which):
             want_delta = R.rk_step_matrix(g, state[0], state[1], group[l], bits, block, 0.0, seed, l, 1)
         elif which == "iconef_random_k":
             want_delta = R.i_rk_step_matrix(g, *state, group[l], bits, block, seed, l, 1)
+        elif v2:
+            eo = B.conef_i2_offsets(model.ctx, l)
+            e_vals = e_before[eo["e_off"]:eo["e_off"] + keep_e[l]].copy()
+            want_delta = R.i2_rk_step_matrix(g, e_vals, state[0], state[1], group[l], bits, block, seed, l, 1)
+            got_e = e_after[eo["e_off"]:eo["e_off"] + keep_e[l]]
+            assert np.array_equal(got_e.view(np.uint32), e_vals.view(np.uint32)), f"{tag}: first error vector"
         else:
             words, c = R.i_ss_step_matrix(g, *state, bits, block, seed, l, 1)
         if block_mode or strata:
