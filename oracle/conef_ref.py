@@ -120,6 +120,10 @@ def lib() -> ctypes.CDLL:
         L.ref_i_ss_step_matrix.restype = f32
         L.ref_rk_count.argtypes = [i64, i64]
         L.ref_rk_count.restype = i64
+        L.ref_rku_perm.argtypes = [u64, u32, u64, i64, i64]
+        L.ref_rku_perm.restype = i64
+        L.ref_rku_inverse.argtypes = [u64, u32, u64, i64, i64]
+        L.ref_rku_inverse.restype = i64
         L.ref_rk_indices.argtypes = [u64, u32, u64, i64, i64, vp]
         L.ref_rk_indices.restype = None
         L.ref_rk_step_matrix.argtypes = [vp, i32, i64, i64, i32, i32, f32, u64, u32, u64, vp, vp, vp, vp]
@@ -540,8 +544,18 @@ def rk_count(N: int, G: int) -> int:
     return int(lib().ref_rk_count(N, G))
 
 
+def rku_perm(seed: int, mat: int, step: int, N: int, j: int) -> int:
+    """pi(j) of the uniformly drawn subset's keyed permutation (kept iff below k; the slot of the kept value)."""
+    return int(lib().ref_rku_perm(seed, mat, step, N, j))
+
+
+def rku_inverse(seed: int, mat: int, step: int, N: int, i: int) -> int:
+    return int(lib().ref_rku_inverse(seed, mat, step, N, i))
+
+
 def rk_indices(seed: int, mat: int, step: int, N: int, G: int) -> np.ndarray:
-    """Kept coordinate of every stratum (int64, ascending)."""
+    """Kept coordinate of every stratum (int64, ascending); G < 0: the coordinates of the uniformly drawn subset of -G,
+    in slot order.  Every rk step routine below takes G < 0 in that sense."""
     idx = np.empty(rk_count(N, G), np.int64)
     lib().ref_rk_indices(seed, mat, step, N, G, _p(idx))
     return idx

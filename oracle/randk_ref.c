@@ -24,6 +24,10 @@
  * with the arithmetic of the random-block step: quantiser: g + e (one fma) off the kept coordinates, beta * e
  * on them; count sketch: beta S + C(p - Delta); iConEF: p - Delta is 0 on the kept coordinates.
  *
+ * The uniformly drawn k-subset itself also exists (further down; every step routine takes G < 0 for "-G coordinates,
+ * uniformly drawn"): a keyed permutation per matrix and step, which costs a cipher evaluation per coordinate and
+ * scatters the kept values over the message.
+ *
  * Parity pins (tests/test_oracle_randk.py): one kept coordinate per stratum, the stated function of the pinned
  * Philox, uniform within its stratum (chi-square), neighbouring strata uncorrelated, short last stratum; Delta is
  * p there; the contraction identity on average; conservation g + e = Delta + e+ with an exact error compressor;
@@ -51,13 +55,121 @@ void ref_i_form_p(const void *g, int dtype, const uint32_t *codes, const float *
 void ref_i_error(float *x, int64_t N, int bits, int block, uint64_t seed, uint32_t mat, uint64_t step,
                  uint32_t *codes, float *scales, uint32_t *codes2, float *scales2, float *tmp);
 
-/* Number of strata (= kept coordinates) of a matrix of N coordinates with strata of G. */
-int64_t ref_rk_count(int64_t N, int64_t G) { return (N + G - 1) / G; }
+/* ------------------------------------------------------------------ */
+/* The textbook random-k: a uniformly drawn k-subset, the same on every worker that uses the same seed.  Reading
+ * taken here: a keyed bijection pi of [0, N) per matrix and step; coordinate j is kept iff pi(j) < k and its value
+ * goes to slot pi(j) of the message (so slot i holds coordinate pi^-1(i)).  pi is an alternating six-round Feistel
+ * network on Z_a x Z_b (a = ceil(sqrt(N)), b = ceil(N / a), so a b >= N and a b - N < a + b), walked again while the
+ * result is >= N (cycle walking: the restriction of a bijection of [0, a b) to the cycle structure over [0, N)):
+ *     (L, R) = (x / b, x mod b)
+ *     round i even:  L = (L + floor(mix(R xor key_i) a / 2^32)) mod a
+ *     round i odd:   R = (R + floor(mix(L xor key_i) b / 2^32)) mod b          i = 0..5
+ *     pi_once(x) = L b + R
+ *     mix(u): u *= 0x9E3779B1; u ^= u >> 15; u *= 0x85EBCA77; u ^= u >> 13      (32-bit)
+ * keys 0..3 are the words of the Philox4x32-10 call with counter (l, 2^32 - 3, lo32(step), hi32(step)), keys 4..5 the
+ * first two words of the call with 2^32 - 4 there (no other draw uses these counters).  A family of permutations
+ * indexed by 192 key bits is not all N! of them: "uniform" is meant in the statistical sense the pins check
+ * (inclusion of single coordinates and of pairs, neighbours included, at the rates k / N and k (k-1) / (N (N-1))).
+ * N < 2^32.
+ * ------------------------------------------------------------------ */
+static uint32_t rku_mix(uint32_t u)
+{
+    u *= 0x9E3779B1u; u ^= u >> 15; u *= 0x85EBCA77u; u ^= u >> 13;
+    return u;
+}
 
-/* idx[i] = kept coordinate of stratum i, i < ref_rk_count(N, G); ascending. */
+/* a = ceil(sqrt(N)) (exact integer arithmetic), b = ceil(N / a) */
+void ref_rku_shape(int64_t N, uint32_t *a, uint32_t *b)
+{
+    uint64_t r = (uint64_t)sqrt((double)N);
+    while (r * r < (uint64_t)N) ++r;
+    while (r > 1 && (r - 1) * (r - 1) >= (uint64_t)N) --r;
+    *a = (uint32_t)r;
+    *b = (uint32_t)(((uint64_t)N + r - 1) / r);
+}
+
+void ref_rku_keys(uint64_t seed, uint32_t mat, uint64_t step, uint32_t keys[6])
+{
+    const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    const uint32_t c0[4] = { mat, 0xFFFFFFFDu, (uint32_t)step, (uint32_t)(step >> 32) };
+    const uint32_t c1[4] = { mat, 0xFFFFFFFCu, (uint32_t)step, (uint32_t)(step >> 32) };
+    uint32_t o0[4], o1[4];
+    ref_philox4x32_10(c0, key, o0);
+    ref_philox4x32_10(c1, key, o1);
+    keys[0] = o0[0]; keys[1] = o0[1]; keys[2] = o0[2]; keys[3] = o0[3]; keys[4] = o1[0]; keys[5] = o1[1];
+}
+
+static uint32_t rku_once(uint32_t x, uint32_t a, uint32_t b, const uint32_t keys[6])
+{
+    uint32_t L = x / b, R = x % b;
+    for (int i = 0; i < 6; ++i) {
+        if ((i & 1) == 0) {
+            L += (uint32_t)(((uint64_t)rku_mix(R ^ keys[i]) * a) >> 32);
+            if (L >= a) L -= a;
+        } else {
+            R += (uint32_t)(((uint64_t)rku_mix(L ^ keys[i]) * b) >> 32);
+            if (R >= b) R -= b;
+        }
+    }
+    return L * b + R;
+}
+
+static uint32_t rku_once_inverse(uint32_t y, uint32_t a, uint32_t b, const uint32_t keys[6])
+{
+    uint32_t L = y / b, R = y % b;
+    for (int i = 5; i >= 0; --i) {
+        if ((i & 1) == 0) {
+            const uint32_t f = (uint32_t)(((uint64_t)rku_mix(R ^ keys[i]) * a) >> 32);
+            L = L >= f ? L - f : L + a - f;
+        } else {
+            const uint32_t f = (uint32_t)(((uint64_t)rku_mix(L ^ keys[i]) * b) >> 32);
+            R = R >= f ? R - f : R + b - f;
+        }
+    }
+    return L * b + R;
+}
+
+/* pi(j) and pi^-1(i) for one matrix and step */
+int64_t ref_rku_perm(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t j)
+{
+    uint32_t a, b, keys[6];
+    ref_rku_shape(N, &a, &b);
+    ref_rku_keys(seed, mat, step, keys);
+    uint32_t x = (uint32_t)j;
+    do x = rku_once(x, a, b, keys); while ((int64_t)x >= N);
+    return (int64_t)x;
+}
+
+int64_t ref_rku_inverse(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t i)
+{
+    uint32_t a, b, keys[6];
+    ref_rku_shape(N, &a, &b);
+    ref_rku_keys(seed, mat, step, keys);
+    uint32_t x = (uint32_t)i;
+    do x = rku_once_inverse(x, a, b, keys); while ((int64_t)x >= N);
+    return (int64_t)x;
+}
+
+/* Number of kept coordinates of a matrix of N coordinates: strata of G (one each), or, for G < 0, the uniformly drawn
+ * subset of -G coordinates. */
+int64_t ref_rk_count(int64_t N, int64_t G) { return G < 0 ? -G : (N + G - 1) / G; }
+
+/* idx[i] = kept coordinate of stratum i, i < ref_rk_count(N, G), ascending; for G < 0 the coordinate pi^-1(i) that goes
+ * to slot i of the uniformly drawn subset (in slot order, not ascending). */
 void ref_rk_indices(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t G, int64_t *idx)
 {
     const int64_t k = ref_rk_count(N, G);
+    if (G < 0) {
+        uint32_t a, b, keys[6];
+        ref_rku_shape(N, &a, &b);
+        ref_rku_keys(seed, mat, step, keys);
+        for (int64_t i = 0; i < k; ++i) {
+            uint32_t x = (uint32_t)i;
+            do x = rku_once_inverse(x, a, b, keys); while ((int64_t)x >= N);
+            idx[i] = (int64_t)x;
+        }
+        return;
+    }
     const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
     for (int64_t i = 0; i < k; ++i) {
         const uint32_t ctr[4] = { (uint32_t)(i >> 2), mat + 0x40000000u, (uint32_t)step, (uint32_t)(step >> 32) };

@@ -1,5 +1,6 @@
 // MFMA kernel family: rank-32 contractions on the matrix cores (v_mfma_f32_32x32x16_bf16) for
-// bf16 gradients, 4-bit codes, block 128, cols % 128 == 0.
+// bf16 gradients, 4-bit codes, block 128, cols % 128 == 0; also the two big products of the count sketch's linear
+// form at rank 32 (modes 2 and 3 of the P and Q+ kernels).
 //
 // fp32-level accuracy from bf16 matrix cores comes from exact operand splits:
 //   - a factor entry x (fp32) is written as hi + mid + lo, three bf16 values obtained by
@@ -450,9 +451,10 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 constexpr int kQRows = 64;                  // rows per chunk
 constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
 
-// GRAD = false, ACCUM = true: the contribution of a compressed vector alone (no gradient; its scales in the second
-// column-block-major region) added to what an earlier launch has left: Q+ = (g + second)^T P^, then
-// Q+ += first^T P^, for the two error vectors of Algorithm 3.
+// MODE 0: Q+ = (g + e)^T P^, the quantiser's step.
+// MODE 1: the contribution of a compressed vector alone (no gradient; its scales in the second column-block-major
+//         region) added to what an earlier launch has left: Q+ = (g + second)^T P^, then Q+ += first^T P^, for the two
+//         error vectors of Algorithm 3.
 // MODE 2 and 3, the count sketch in its linear form (`codes` is the fp16 table): 2: the gradient's share g^T P^ alone;
 // 3: the table's share (1 - beta) S^T U over the table's rows (two operand tiles per entry, see the P pass), U from the
 // workspace; its row tiles follow the gradient's in the partial sums, which the reduction kernel adds in order.

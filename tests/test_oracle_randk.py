@@ -163,3 +163,98 @@ def test_iconef_around_it():
         step2 = (s2.astype(np.float64) / s)[np.arange(N) // block]
         assert np.all(np.abs(x - e) <= step2 * (1 + 1e-5) + 1e-7 * np.abs(x))
         assert np.all(e[idx] == 0)
+
+
+# ---------------------------------------------------------------- the uniformly drawn k-subset (G < 0 in the oracle's routines)
+def test_uniform_subset_is_a_bijection_with_its_inverse_and_exactly_k_kept():
+    for N, k, seed, mat, step in [(37, 5, 1, 0, 0), (1000, 100, 9, 3, 7), (4097, 1, 2, 1, 2 ** 40 + 5), (64, 64, 3, 2, 1)]:
+        images = [R.rku_perm(seed, mat, step, N, j) for j in range(N)]
+        assert sorted(images) == list(range(N))
+        assert all(R.rku_inverse(seed, mat, step, N, images[j]) == j for j in range(0, N, max(1, N // 97)))
+        idx = R.rk_indices(seed, mat, step, N, -k)
+        assert idx.size == k == R.rk_count(N, -k) and len(set(idx.tolist())) == k
+        assert [images[int(j)] for j in idx] == list(range(k))          # slot i holds the coordinate that pi sends to i
+    # another step, matrix or seed: another subset
+    base = set(R.rk_indices(9, 3, 7, 1000, -100).tolist())
+    for other in (R.rk_indices(9, 3, 8, 1000, -100), R.rk_indices(9, 4, 7, 1000, -100), R.rk_indices(10, 3, 7, 1000, -100)):
+        assert len(base & set(other.tolist())) < 40
+
+
+def test_uniform_subset_is_the_stated_function_of_the_generator():
+    """pi recomputed here with Python integers from the pinned Philox: six alternating rounds on Z_a x Z_b."""
+    def mix(u):
+        u = (u * 0x9E3779B1) & 0xFFFFFFFF; u ^= u >> 15; u = (u * 0x85EBCA77) & 0xFFFFFFFF; u ^= u >> 13
+        return u
+    seed, mat, step, N = 0x1234_5678_9ABC_DEF0, 2, 2 ** 33 + 1, 5000
+    key = np.array([seed & 0xFFFFFFFF, seed >> 32], np.uint32)
+    o0 = R.philox4x32_10(np.array([mat, 0xFFFFFFFD, step & 0xFFFFFFFF, step >> 32], np.uint32), key)
+    o1 = R.philox4x32_10(np.array([mat, 0xFFFFFFFC, step & 0xFFFFFFFF, step >> 32], np.uint32), key)
+    keys = [int(o0[0]), int(o0[1]), int(o0[2]), int(o0[3]), int(o1[0]), int(o1[1])]
+    a = 71                                             # ceil(sqrt(5000)): 70^2 = 4900 < 5000 <= 71^2
+    b = -(-N // a)
+    for j in (0, 1, 70, 71, 4999, 2500):
+        x = j
+        while True:
+            L, Rr = divmod(x, b)
+            for i in range(6):
+                if i % 2 == 0:
+                    L = (L + ((mix(Rr ^ keys[i]) * a) >> 32)) % a
+                else:
+                    Rr = (Rr + ((mix(L ^ keys[i]) * b) >> 32)) % b
+            x = L * b + Rr
+            if x < N:
+                break
+        assert R.rku_perm(seed, mat, step, N, j) == x
+
+
+def test_uniform_subset_keeps_single_coordinates_and_pairs_at_the_uniform_rates():
+    """Over many steps every coordinate is kept at the rate k / N and every pair, neighbours included, at
+    k (k-1) / (N (N-1)): what distinguishes it from the stratified form, which never keeps two of one stratum."""
+    N, k, T, seed = 37, 5, 40000, 77
+    inc, pair = np.zeros(N), np.zeros((N, N))
+    for t in range(T):
+        kept = np.zeros(N)
+        kept[R.rk_indices(seed, 0, t, N, -k)] = 1.0
+        inc += kept
+        pair += np.outer(kept, kept)
+    p1, p2 = k / N, k * (k - 1) / (N * (N - 1))
+    z1 = (inc / T - p1) / np.sqrt(p1 * (1 - p1) / T)
+    assert np.abs(z1).max() < 4.5
+    z2 = (pair / T - p2) / np.sqrt(p2 * (1 - p2) / T)
+    np.fill_diagonal(z2, 0.0)
+    assert np.abs(z2).max() < 5.0 and (z2 ** 2).sum() / (N * (N - 1)) < 1.25
+    # the stratified form with the same rate fails this by far: neighbours of one stratum are never kept together
+    G = 8
+    pair_s = np.zeros((N, N))
+    for t in range(4000):
+        kept = np.zeros(N)
+        kept[R.rk_indices(seed, 0, t, N, G)] = 1.0
+        pair_s += np.outer(kept, kept)
+    assert pair_s[0, 1] == 0
+
+
+def test_uniform_subset_step_is_the_stratified_step_with_other_coordinates():
+    """Delta = p on the kept coordinates (in slot order), the error compressor gets p - Delta with beta e kept on them:
+    checked against the stated construction with the pinned quantiser, and the contraction on average."""
+    rng = np.random.default_rng(3)
+    N, k, bits, block, seed, mat = 1024, 100, 4, 64, 5, 1
+    codes, scales = np.zeros(R.n_words(N, bits), np.uint32), np.zeros(R.n_blocks(N, block), np.float32)
+    ratio = []
+    for t in range(5):
+        g = rng.standard_normal((1, N)).astype(np.float32)
+        p = R.form_p(g, codes, scales, bits, block).ravel()
+        e = R.decode(codes, scales, N, bits, block)
+        idx = R.rk_indices(seed, mat, t, N, -k)
+        d = R.rk_step_matrix(g, codes, scales, -k, bits, block, 0.0, seed, mat, t)
+        assert np.array_equal(d, p[idx])
+        x = p.copy()
+        x[idx] = 0.0 * e[idx]
+        wc, ws = R.quantise(x, bits, block, seed, mat, t)
+        assert np.array_equal(codes, wc) and np.array_equal(scales, ws)
+        ratio.append(((p ** 2).sum() - (d ** 2).sum()) / (p ** 2).sum())
+    assert abs(np.mean(ratio) - (1 - k / N)) < 0.05
+    # around it: the two-vector forms take the same subset
+    c1, s1, c2, s2 = codes.copy(), scales.copy(), np.zeros_like(codes), np.zeros_like(scales)
+    g = rng.standard_normal((1, N)).astype(np.float32)
+    d = R.i_rk_step_matrix(g, c1, s1, c2, s2, -k, bits, block, seed, mat, 9)
+    assert np.array_equal(d, R.form_p(g, codes, scales, bits, block).ravel()[R.rk_indices(seed, mat, 9, N, -k)])
