@@ -317,9 +317,10 @@ def run_scaled_sign(w, reps: int = 10):
     return out
 
 
-def run_random_k(w, group: int = 10, reps: int = 10):
+def run_random_k(w, group: int = 10, reps: int = 10, uniform: bool = False):
     """Times one step with the random-k gradient compressor (stratified: one coordinate kept of every `group`
-    consecutive ones) in place of the rank-r one: with the workload's quantiser (beta = 0), with the count sketch (fp16
+    consecutive ones; uniform: a uniformly drawn subset of the same size, one evaluation of a keyed permutation per
+    coordinate) in place of the rank-r one: with the workload's quantiser (beta = 0), with the count sketch (fp16
     table, keep 0.2, beta 0.9), with iConEF-v1 (the quantiser twice) and with iConEF-v2 (first error vector: a random block
     of 5 % of every matrix kept in fp32, as large as the appendix experiment's; second: the quantiser).  One streaming pass
     each; HIP events on the launch stream."""
@@ -339,7 +340,10 @@ def run_random_k(w, group: int = 10, reps: int = 10):
         else:
             model = B.Model(w.layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed)
             state_bytes = sum(n * m * (w.bits / 8 + 4.0 / w.block) for n, m in w.layout) * (2 if kind == "iconef_v1" else 1)
-        B.conef_rk_configure(model.ctx, [group] * len(w.layout))
+        if uniform:
+            B.conef_rk_configure_uniform(model.ctx, [-(-(n * m) // group) for n, m in w.layout])
+        else:
+            B.conef_rk_configure(model.ctx, [group] * len(w.layout))
         buf = model.alloc("cuda:0")
         delta = torch.zeros(B.conef_rk_sizes(model.ctx)["delta_elems"], dtype=torch.float32, device="cuda:0")
         if kind == "iconef_v1":
@@ -600,6 +604,8 @@ def main():
     ap.add_argument("--random-k", action="store_true",
                     help="time only the step with the random-k gradient compressor (stratified, one coordinate of every "
                          "ten kept; quantiser, count sketch, iConEF-v1 and iConEF-v2) on --workload and print its line")
+    ap.add_argument("--uniform", action="store_true",
+                    help="with --random-k: the uniformly drawn subset of a tenth of every matrix instead of the strata")
     ap.add_argument("--iconef", action="store_true",
                     help="time only the iConEF-v1 step (two compressed error vectors, the quantiser twice) with the "
                          "random-block and scaled-sign gradient compressors on --workload and print its line")
@@ -635,8 +641,8 @@ def main():
                           "steps": a.steps, "config": {"workload": w.name, "rank": w.rank}, **r}), flush=True)
         return
     if a.random_k:
-        r = run_random_k(w, 10, a.steps)
-        print(json.dumps({"metric": "stratified random-k ConEF step throughput: gradient GB/s processed",
+        r = run_random_k(w, 10, a.steps, a.uniform)
+        print(json.dumps({"metric": ("uniform-subset" if a.uniform else "stratified") + " random-k ConEF step throughput: gradient GB/s processed",
                           "value": round(w.grad_bytes / (r["quantiser"]["ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
                           "steps": a.steps, "config": {"workload": w.name, "group": 10}, **r}), flush=True)
         return
@@ -726,6 +732,9 @@ def main():
                                             for name in ("cnn", "lm", "translation", "large")}}
         out["random_k"] = {"group": 10, "workloads": {name: run_random_k(wl.WORKLOADS[name])
                                                       for name in ("cnn", "lm", "translation", "large")}}
+        # ... as a uniformly drawn subset of the same size (a keyed permutation evaluated for every coordinate)
+        out["random_k_uniform"] = {"fraction": 0.1, "workloads": {name: run_random_k(wl.WORKLOADS[name], uniform=True)
+                                                                  for name in ("lm", "large")}}
         # improved contractive error feedback, version 1: a second compressed vector, the quantiser twice
         out["iconef_v1"] = {"fraction": 0.1, "workloads": {name: run_iconef(wl.WORKLOADS[name])
                                                            for name in ("cnn", "lm", "translation", "large")}}

@@ -232,9 +232,10 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
 int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delta_out, uint64_t step,
                      void *hip_stream);
 
-/* ---- Stratified random-k gradient compressor (standing in for the random-k of the paper's iConEF experiment in the
- * appendix, which names the compressor and its rate only; NOT a uniformly drawn k-subset) in place of the rank-r one, unscaled like the random block, with either error compressor and
- * with improved contractive error feedback.  Reading built here, "stratified": the flat row-major index range of
+/* ---- Random-k gradient compressor (the paper's iConEF experiment in the appendix names the compressor and its rate
+ * only) in place of the rank-r one, unscaled like the random block, with either error compressor and with improved
+ * contractive error feedback.  Two readings are built: a stratified one (conef_rk_configure, the cheap one, NOT a
+ * uniformly drawn k-subset) and the uniformly drawn k-subset (conef_rk_configure_uniform, further down).  "Stratified": the flat row-major index range of
  * matrix l is cut into strata of group[l] consecutive coordinates (the last one may be shorter) and one coordinate of
  * every stratum is kept, drawn uniformly within its stratum and independently of the others, the same on every
  * worker that uses the same seed.  Every coordinate is kept with probability 1 / group[l], exactly
@@ -251,8 +252,28 @@ int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delt
  * delta_out           device, out: flat fp32, matrix l at delta_off of conef_rk_offsets (multiples of 64), keep values
  * conef_rk_step and conef_i_rk_step are for quantiser contexts, conef_cs_rk_step for count-sketch contexts;
  * CONEF_ESTATE on the other kind or before conef_rk_configure (and for conef_i_rk_step unless beta is 0).
- * Pointers, alignment, asynchrony and errors as for conef_step; the error state is updated in place. */
+ * Pointers, alignment, asynchrony and errors as for conef_step; the error state is updated in place.
+ *
+ * conef_rk_configure_uniform: the other reading, a uniformly drawn subset of exactly keep[l] coordinates of matrix l (every
+ * subset of that size equally likely, up to the quality of the keyed permutation below; two coordinates are kept
+ * together with probability k (k - 1) / (N (N - 1))).  It replaces the strata for every later conef_rk_step,
+ * conef_i_rk_step, conef_i2_rk_step and conef_cs_rk_step of the context (and conef_rk_configure replaces it again).
+ *   N = rows cols, a = ceil(sqrt(N)), b = ceil(N / a); a keyed bijection of [0, a b), six alternating Feistel rounds:
+ *     (L, R) = (x div b, x mod b);  round i = 0, 2, 4: L = (L + floor(mix(R xor key_i) a / 2^32)) mod a;
+ *     round i = 1, 3, 5: R = (R + floor(mix(L xor key_i) b / 2^32)) mod b;  result L b + R
+ *     mix(u): u *= 0x9E3779B1; u ^= u >> 15; u *= 0x85EBCA77; u ^= u >> 13   (32-bit)
+ *     key_0..3 = the Philox4x32-10 call with counter (l, 2^32 - 3, lo32(step), hi32(step)) and the context's key,
+ *     key_4..5 = words 0..1 of the call with 2^32 - 4 as the second word
+ *   pi(j) = the bijection applied to j again and again until the result is below N (a permutation of [0, N)).
+ *   Coordinate j is kept iff pi(j) < keep[l]; its value goes to slot pi(j) of the matrix's part of delta_out, so
+ *   the kept coordinates appear there in a random order, the same on every worker with the same seed and step;
+ *   conef_rk_index(ctx, l, step, i) returns the coordinate in slot i, pi^-1(i) (host; its argument "stratum" is the slot).
+ *   conef_rk_offsets reports keep[l] as keep.  Everything else as above.
+ * keep[n_mats] with 1 <= keep[l] <= rows*cols, rows*cols < 2^32 (CONEF_EINVAL otherwise); host only; may be called
+ * again.  Cost: the permutation is evaluated for every coordinate (about 70 integer operations), against one Philox
+ * call per four strata for the stratified form. */
 int conef_rk_configure(conef_ctx *ctx, const int64_t *group);
+int conef_rk_configure_uniform(conef_ctx *ctx, const int64_t *keep);
 int conef_rk_sizes(const conef_ctx *ctx, size_t *delta_elems);
 int conef_rk_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *keep);
 int conef_rk_index(const conef_ctx *ctx, int mat, uint64_t step, int64_t stratum, int64_t *index);

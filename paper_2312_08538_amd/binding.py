@@ -26,7 +26,7 @@ EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_st
            "conef_rb_configure", "conef_rb_sizes", "conef_rb_offsets", "conef_rb_start", "conef_rb_step", "conef_cs_rb_step",
            "conef_i_rb_step", "conef_i_ss_step", "conef_i_rk_step", "conef_i_step_p", "conef_i_step_q", "conef_i_step_err", "conef_i_step",
            "conef_i2_configure", "conef_i2_sizes", "conef_i2_offsets", "conef_i2_start", "conef_i2_rb_step", "conef_i2_rk_step",
-           "conef_rk_configure", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
+           "conef_rk_configure", "conef_rk_configure_uniform", "conef_rk_sizes", "conef_rk_offsets", "conef_rk_index", "conef_rk_step", "conef_cs_rk_step",
            "conef_cs_init", "conef_csc_init", "conef_cs_sizes", "conef_cs_offsets", "conef_cs_hash", "conef_cs_step",
            "conef_cs_step_p", "conef_cs_step_q", "conef_cs_step_err", "conef_cs_decode_error"]
 
@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
     L.conef_i2_rb_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_i2_rk_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, vp]
     L.conef_rk_configure.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
+    L.conef_rk_configure_uniform.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rk_sizes.argtypes = [vp, szp]
     L.conef_rk_offsets.argtypes = [vp, i32, szp, ctypes.POINTER(ctypes.c_int64)]
     L.conef_rk_index.argtypes = [vp, i32, u64, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
@@ -255,6 +256,12 @@ def conef_i_step(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_s
 def conef_rk_configure(ctx, group: Sequence[int]) -> None:
     arr = (ctypes.c_int64 * max(1, len(group)))(*[int(x) for x in group])
     _check(lib().conef_rk_configure(ctx, arr), "conef_rk_configure")
+
+
+def conef_rk_configure_uniform(ctx, keep: Sequence[int]) -> None:
+    """random-k as a uniformly drawn subset of keep[l] coordinates of matrix l (replaces the strata for the context)"""
+    arr = (ctypes.c_int64 * max(1, len(keep)))(*[int(x) for x in keep])
+    _check(lib().conef_rk_configure_uniform(ctx, arr), "conef_rk_configure_uniform")
 
 
 def conef_rk_sizes(ctx) -> dict:

@@ -620,7 +620,7 @@ int conef_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, false,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, kModeBlock,
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -635,7 +635,7 @@ int conef_i_rb_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, false,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, kModeBlock,
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -647,16 +647,29 @@ int conef_cs_rb_step(conef_ctx *ctx, const void *grads, void *table, float *delt
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, false, static_cast<hipStream_t>(hip_stream)));
+    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, kModeBlock, static_cast<hipStream_t>(hip_stream)));
 }
 
-// ---------------------------------------------------------------- random-k gradient compressor (stratified)
+// ---------------------------------------------------------------- random-k gradient compressor (stratified, or a uniform subset)
+namespace {
+int rk_mode(const conef_ctx *ctx) { return ctx->plan.rk_uniform ? kModeUniform : kModeStrata; }
+}  // namespace
+
 int conef_rk_configure(conef_ctx *ctx, const int64_t *group)
 {
     if (!ctx || !group) return CONEF_EINVAL;
     int rc = configure_random_k(ctx->plan, group);
     if (rc) return rc;
     ctx->rb_uploaded = false;       // the descriptors are uploaded again before the next step
+    return CONEF_OK;
+}
+
+int conef_rk_configure_uniform(conef_ctx *ctx, const int64_t *keep)
+{
+    if (!ctx || !keep) return CONEF_EINVAL;
+    int rc = configure_random_k_uniform(ctx->plan, keep);
+    if (rc) return rc;
+    ctx->rb_uploaded = false;
     return CONEF_OK;
 }
 
@@ -674,7 +687,7 @@ int conef_rk_offsets(const conef_ctx *ctx, int mat, size_t *delta_off, int64_t *
     if (ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
     const MatDesc &d = ctx->plan.mats[mat];
     if (delta_off) *delta_off = (size_t)d.rk_delta_off;
-    if (keep) *keep = (d.N + d.rk_g - 1) / d.rk_g;
+    if (keep) *keep = ctx->plan.rk_uniform ? (int64_t)d.rk_uk : (d.N + d.rk_g - 1) / d.rk_g;
     return CONEF_OK;
 }
 
@@ -683,6 +696,11 @@ int conef_rk_index(const conef_ctx *ctx, int mat, uint64_t step, int64_t stratum
     if (!ctx || !index || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
     if (ctx->plan.rk_delta_elems == 0) return CONEF_ESTATE;
     const MatDesc &d = ctx->plan.mats[mat];
+    if (ctx->plan.rk_uniform) {
+        if (stratum < 0 || stratum >= (int64_t)d.rk_uk) return CONEF_EINVAL;
+        *index = random_k_uniform_index(ctx->plan.seed, (uint32_t)mat, step, d, stratum);
+        return CONEF_OK;
+    }
     if (stratum < 0 || stratum >= (d.N + d.rk_g - 1) / d.rk_g) return CONEF_EINVAL;
     *index = random_k_index(ctx->plan.seed, (uint32_t)mat, step, d.N, d.rk_g, stratum);
     return CONEF_OK;
@@ -698,7 +716,7 @@ int conef_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float 
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, true,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, rk_mode(ctx),
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -713,7 +731,7 @@ int conef_i_rk_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, floa
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, true,
+    return hip_rc(launch_rb_step(ctx->dev, grads, err_codes, err_scales, delta_out, step, err2_codes, err2_scales, rk_mode(ctx),
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -771,7 +789,7 @@ int i2_step_impl(conef_ctx *ctx, const void *grads, const float *e_in, float *e_
     DevicePlan dp = ctx->dev;
     dp.i2_in = e_in;
     dp.i2_out = e_out;
-    return hip_rc(launch_rb_step(dp, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, strata,
+    return hip_rc(launch_rb_step(dp, grads, err_codes, err_scales, delta_out, step, nullptr, nullptr, strata ? rk_mode(ctx) : kModeBlock,
                                  static_cast<hipStream_t>(hip_stream)));
 }
 }  // namespace
@@ -796,7 +814,7 @@ int conef_cs_rk_step(conef_ctx *ctx, const void *grads, void *table, float *delt
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     if ((rc = ensure_rb_uploaded(ctx))) return rc;
-    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, true, static_cast<hipStream_t>(hip_stream)));
+    return hip_rc(launch_cs_rb_step(ctx->dev, grads, table, delta_out, step, rk_mode(ctx), static_cast<hipStream_t>(hip_stream)));
 }
 
 // ---------------------------------------------------------------- scaled-sign gradient compressor

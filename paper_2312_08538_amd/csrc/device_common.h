@@ -115,6 +115,55 @@ __device__ __forceinline__ uint32_t strata_kept_octet(uint32_t j0, uint32_t N, u
     return bits;
 }
 
+// Random-k gradient compressor as a uniformly drawn k-subset: a keyed bijection pi of [0, N) per matrix and step;
+// coordinate j is kept iff pi(j) < k, and its value goes to slot pi(j) of the message.  pi: six alternating Feistel
+// rounds on Z_a x Z_b (a = ceil(sqrt(N)), b = ceil(N / a)), walked again while the result is >= N:
+//   (L, R) = (x / b, x mod b);  even round i: L = (L + floor(mix(R ^ key_i) a / 2^32)) mod a;
+//   odd round i: R = (R + floor(mix(L ^ key_i) b / 2^32)) mod b;  pi_once(x) = L b + R
+// keys 0..3: the Philox call with counter (matrix, ~0 - 2, step), keys 4..5: words 0..1 of the call with ~0 - 3 there.
+struct RkuKeys {
+    uint32_t k[6];
+};
+
+__device__ __forceinline__ RkuKeys rku_keys(uint32_t mat, uint32_t step_lo, uint32_t step_hi, uint32_t seed_lo, uint32_t seed_hi)
+{
+    uint32_t o0[4], o1[4];
+    philox4x32_10(mat, 0xFFFFFFFDu, step_lo, step_hi, seed_lo, seed_hi, o0);
+    philox4x32_10(mat, 0xFFFFFFFCu, step_lo, step_hi, seed_lo, seed_hi, o1);
+    RkuKeys r;
+    r.k[0] = o0[0]; r.k[1] = o0[1]; r.k[2] = o0[2]; r.k[3] = o0[3]; r.k[4] = o1[0]; r.k[5] = o1[1];
+    return r;
+}
+
+__device__ __forceinline__ uint32_t rku_mix(uint32_t u)
+{
+    u *= 0x9E3779B1u; u ^= u >> 15; u *= 0x85EBCA77u; u ^= u >> 13;
+    return u;
+}
+
+// magic_b = floor(2^64 / b) + 1: x / b = mulhi64(x, magic_b) for every x < 2^32 (see stratum_of)
+// The walk leaves [0, N) at most a b - N times before it comes back (a bijection of [0, a b)): the loop is bounded by that.
+__device__ __forceinline__ uint32_t rku_perm(uint32_t x, uint32_t N, uint32_t a, uint32_t b, uint64_t magic_b, const RkuKeys &key)
+{
+    uint32_t outside = a * b - N;          // modulo 2^32, also right for a b = 2^32
+    do {
+        uint32_t L = b == 1 ? x : (uint32_t)__umul64hi((uint64_t)x, magic_b);
+        uint32_t R = x - L * b;
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            if ((i & 1) == 0) {
+                L += __umulhi(rku_mix(R ^ key.k[i]), a);
+                L = L >= a ? L - a : L;
+            } else {
+                R += __umulhi(rku_mix(L ^ key.k[i]), b);
+                R = R >= b ? R - b : R;
+            }
+        }
+        x = L * b + R;
+    } while (x >= N && outside-- > 0);
+    return x;
+}
+
 // The same question for one coordinate j: is it the kept one of its stratum (*stratum)?
 __device__ __forceinline__ bool strata_kept(uint32_t j, uint32_t N, uint32_t g, uint64_t magic, uint32_t mat, uint32_t step_lo,
                                             uint32_t step_hi, uint32_t seed_lo, uint32_t seed_hi, uint32_t *stratum)

@@ -77,12 +77,15 @@ hipError_t launch_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t
                                hipStream_t st, Span span);
 void octet_pass_err_two(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, uint32_t *codes2,
                         float *scales2, const float *Phat, const float *Qn, uint64_t step, hipStream_t st);
+// The element-wise gradient compressors of the streaming kernels: random block, the two passes of the scaled sign (l1
+// norm, then sign bits), random-k with one coordinate per stratum, random-k as a uniformly drawn subset.
+constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3, kModeUniform = 4;
 // codes2 / scales2 (here, in octet_stream_step and in launch_ss_step): the second error vector of Algorithm 3, or null;
-// strata: the random-k gradient compressor (one coordinate per stratum) instead of the random block
+// mode: kModeBlock, kModeStrata or kModeUniform
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, uint32_t *codes2, float *scales2, bool strata, hipStream_t st);
+                          uint64_t step, uint32_t *codes2, float *scales2, int mode, hipStream_t st);
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
-                             bool strata, hipStream_t st);
+                             int mode, hipStream_t st);
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
                        uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
                        float *scales2, hipStream_t st);

@@ -252,12 +252,15 @@ __global__ __launch_bounds__(256) void k_pass_err_generic(DevicePlan dp, const v
 // rounding of the whole block, so the block is swept three times: maximum, maximum of what the rounding leaves,
 // and both roundings again with the stores.
 // MODE 3, random-k (stratified, see strata_kept): as MODE 0 with the kept coordinates scattered.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
+// MODE 4, random-k as a uniformly drawn subset (see rku_perm): the same, the kept value of coordinate j in slot pi(j).
+
+template <int MODE>
+constexpr bool rb_sparse() { return MODE == kModeBlock || MODE == kModeStrata || MODE == kModeUniform; }
 
 // Is coordinate j kept by the gradient compressor at this step, and where in the Delta buffer does its value go?
 template <int MODE>
 __device__ __forceinline__ bool rb_kept(const DevicePlan &dp, const MatDesc &d, int mat, int64_t j, int64_t start,
-                                        uint32_t step_lo, uint32_t step_hi, int64_t *slot)
+                                        uint32_t step_lo, uint32_t step_hi, const RkuKeys &ku, int64_t *slot)
 {
     if (MODE == kModeBlock) {
         *slot = d.rb_delta_off + (j - start);
@@ -270,6 +273,11 @@ __device__ __forceinline__ bool rb_kept(const DevicePlan &dp, const MatDesc &d, 
         *slot = d.rk_delta_off + i;
         return kept;
     }
+    if (MODE == kModeUniform) {
+        const uint32_t i = rku_perm((uint32_t)j, (uint32_t)d.N, d.rk_ua, d.rk_ub, d.rk_umagic, ku);
+        *slot = d.rk_delta_off + i;
+        return i < d.rk_uk;
+    }
     *slot = 0;
     return false;
 }
@@ -278,7 +286,8 @@ template <int MODE, bool TWO>
 __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc &d, const void *grads, const uint32_t *codes,
                                              const float *scales, int64_t j, int64_t start, float *delta, bool write,
                                              float c, uint32_t *sign_words, const uint32_t *codes2, const float *scales2,
-                                             int mat, uint32_t step_lo, uint32_t step_hi, int64_t e_from, int64_t e_to)
+                                             int mat, uint32_t step_lo, uint32_t step_hi, int64_t e_from, int64_t e_to,
+                                             const RkuKeys &ku)
 {
     const int W = 32 / dp.bits;
     const int q = code_field(codes[d.word_off + j / W], (int)(j % W), dp.bits);
@@ -288,9 +297,9 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
         const int q2 = code_field(codes2[d.word_off + j / W], (int)(j % W), dp.bits);
         const float dstep2 = scales2[d.scale_off + j / dp.block] * inv_levels(dp.bits);
         const float pv = __builtin_fmaf(dstep2, (float)q2, __builtin_fmaf(dstep, (float)q, g));
-        if (MODE == kModeBlock || MODE == kModeStrata) {
+        if (rb_sparse<MODE>()) {
             int64_t slot;
-            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, ku, &slot)) {
                 if (write) delta[slot] = pv;
                 return 0.0f;
             }
@@ -301,7 +310,7 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
         if (write && neg) atomicOr(sign_words + d.sign_off + j / 32, 1u << (j % 32));
         return pv - (neg ? -c : c);
     }
-    if (MODE == kModeBlock || MODE == kModeStrata) {
+    if (rb_sparse<MODE>()) {
         int64_t slot;
         if (dp.i2_out) {
             // Algorithm 3, version 2: p = g + q, + e~ on the block e~ was taken from; Delta = p on the kept coordinates;
@@ -309,7 +318,7 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
             float pv = __builtin_fmaf(dstep, (float)q, g);
             if (j >= e_from && j < e_from + d.i2_k) pv = pv + dp.i2_in[d.i2_off + (j - e_from)];
             const bool mine = j >= e_to && j < e_to + d.i2_k;
-            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+            if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, ku, &slot)) {
                 if (write) {
                     delta[slot] = pv;
                     if (mine) dp.i2_out[d.i2_off + (j - e_to)] = 0.0f;
@@ -322,7 +331,7 @@ __device__ __forceinline__ float rb_argument(const DevicePlan &dp, const MatDesc
             }
             return pv;
         }
-        if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, &slot)) {
+        if (rb_kept<MODE>(dp, d, mat, j, start, step_lo, step_hi, ku, &slot)) {
             if (write) delta[slot] = __builtin_fmaf(dstep * dp.omb, (float)q, g);
             return dp.beta * (dstep * (float)q);
         }
@@ -350,7 +359,9 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
     // Algorithm 3, version 2: the block the incoming first error vector was taken from (drawn one step ago) and the new one's
     int64_t e_from = 0, e_to = 0;
-    if ((MODE == kModeBlock || MODE == kModeStrata) && !TWO && dp.i2_out) {
+    RkuKeys ku = {};
+    if (MODE == kModeUniform) ku = rku_keys((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi);
+    if (rb_sparse<MODE>() && !TWO && dp.i2_out) {
         const uint64_t prev = (((uint64_t)step_hi << 32) | step_lo) - 1;
         e_from = i2_block_start((uint32_t)it.mat, (uint32_t)prev, (uint32_t)(prev >> 32), dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
         e_to = i2_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
@@ -363,7 +374,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
         const int cnt = (int)((d.N - j0 < B) ? d.N - j0 : B);
         float a = 0.0f;
         for (int e = lane; e < cnt; e += 64) {
-            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
+            const float v = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j0 + e, start, delta, true, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to, ku);
             if (MODE == kModeNorm) l1 += (double)fabsf(v);
             a = fmaxf(a, fabsf(v));
         }
@@ -376,7 +387,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             const float dnew = a * inv_levels(bits);
             // argument of the second rounding: x minus the decoded first rounding of x
             auto second_argument = [&](int64_t j, uint32_t &f1) {
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to, ku);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 f1 = quantise_field(x, inv16, draw16(out, (int)(j & 7)), mask);
@@ -422,7 +433,7 @@ __global__ __launch_bounds__(256) void k_rb_generic(DevicePlan dp, const void *g
             uint32_t field = 0;
             if (e < cnt && a > 0.0f) {
                 const int64_t j = j0 + e;
-                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to);
+                const float x = rb_argument<MODE, TWO>(dp, d, grads, codes, scales, j, start, delta, false, c, sign_words, codes2, scales2, it.mat, step_lo, step_hi, e_from, e_to, ku);
                 uint32_t out[4];
                 philox4x32_10((uint32_t)(j >> 3), (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, out);
                 field = quantise_field(x, inv16, draw16(out, (int)(j & 7)), (1u << bits) - 1u) << (bits * (e % W));
@@ -623,13 +634,12 @@ hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *co
     return hipGetLastError();
 }
 
-// codes2 / scales2: the second error vector of Algorithm 3, or null (here and in launch_ss_step); strata: the
-// random-k compressor instead of the random block
+// codes2 / scales2: the second error vector of Algorithm 3, or null (here and in launch_ss_step); mode: the random
+// block or one of the two random-k compressors
 hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales, float *delta,
-                          uint64_t step, uint32_t *codes2, float *scales2, bool strata, hipStream_t st)
+                          uint64_t step, uint32_t *codes2, float *scales2, int mode, hipStream_t st)
 {
-    octet_stream_step(dp, strata ? kModeStrata : kModeBlock, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, codes2,
-                      scales2, st);
+    octet_stream_step(dp, mode, grads, codes, scales, delta, step, nullptr, nullptr, nullptr, codes2, scales2, st);
     auto generic = [&](auto mode) {
         constexpr int M = decltype(mode)::value;
         if (codes2)
@@ -642,7 +652,8 @@ hipError_t launch_rb_step(const DevicePlan &dp, const void *grads, uint32_t *cod
                                (double *)nullptr, codes2, scales2);
     };
     if (dp.n_rb_g > 0) {
-        if (strata) generic(std::integral_constant<int, kModeStrata>{});
+        if (mode == kModeStrata) generic(std::integral_constant<int, kModeStrata>{});
+        else if (mode == kModeUniform) generic(std::integral_constant<int, kModeUniform>{});
         else generic(std::integral_constant<int, kModeBlock>{});
     }
     return hipGetLastError();

@@ -814,7 +814,8 @@ void k_p_octet(DevicePlan dp, const void *__restrict__ grads, const uint32_t *__
 // word of the Philox counter + 2^31), all in registers.
 // MODE 3, random-k (stratified: one coordinate kept per stratum of rk_g consecutive ones, see strata_kept_octet):
 // as MODE 0 with the kept coordinates scattered; the kept values go to the Delta buffer in stratum order.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
+// MODE 4, random-k as a uniformly drawn subset (see rku_perm): the same; coordinate j is kept iff pi(j) < rk_uk and its value
+// goes to slot pi(j).  Eight evaluations of the keyed permutation per octet: several times the arithmetic of MODE 3.
 
 // V2: improved contractive error feedback, version 2 (Algorithm 3, no beta), for MODE 0 and 3: the first error vector
 // is a random block of every matrix kept as it is (i2_k values, dp.i2_in; taken from the block drawn one step ago), the
@@ -826,7 +827,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
                                                   uint32_t *__restrict__ sign_words, const float *__restrict__ c_scale, double *ws,
                                                   uint32_t *codes2, float *scales2)
 {
-    constexpr bool SPARSE = MODE == kModeBlock || MODE == kModeStrata;      // Delta keeps a few coordinates as they are
+    constexpr bool SPARSE = MODE == kModeBlock || MODE == kModeStrata || MODE == kModeUniform;      // Delta keeps a few coordinates as they are
     const int lane = threadIdx.x & 63;
     const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
     if (item >= dp.n_rb) return;
@@ -841,6 +842,8 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
         e_from = i2_block_start((uint32_t)it.mat, (uint32_t)prev, (uint32_t)(prev >> 32), dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
         e_to = i2_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.i2_k);
     }
+    RkuKeys ku = {};
+    if (MODE == kModeUniform) ku = rku_keys((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi);
     double l1 = 0.0;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     // The last run of a matrix may be short: octets at or beyond the end re-read the last octet and store
@@ -896,6 +899,15 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
                                       dp.seed_lo, dp.seed_hi, &kfirst);
             kslot = d.rk_delta_off + kfirst;
         }
+        uint32_t kpos[8];                                               // MODE 4: pi of the octet's coordinates
+        if (MODE == kModeUniform) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                kpos[e] = rku_perm((uint32_t)(o * 8 + e), (uint32_t)d.N, d.rk_ua, d.rk_ub, d.rk_umagic, ku);
+                kbits |= (kpos[e] < d.rk_uk ? 1u : 0u) << e;
+            }
+            kslot = d.rk_delta_off;
+        }
         // x: the argument of the error compressor.  First as if nothing were kept: g + e (= beta e + p), or p = g + e~ + q
         float x[8];
         uint32_t neg_bits = 0;
@@ -935,7 +947,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if ((kbits >> e) & 1u) {
-                    const int64_t slot = kslot + __popc(kbits & ((1u << e) - 1u));
+                    const int64_t slot = kslot + (MODE == kModeUniform ? kpos[e] : (uint32_t)__popc(kbits & ((1u << e) - 1u)));
                     if (TWO || V2) {
                         if (valid) delta[slot] = x[e];
                         x[e] = 0.0f;
@@ -1002,7 +1014,7 @@ __global__ __launch_bounds__(256) void k_rb_octet(DevicePlan dp, const void *__r
 
 }  // namespace
 
-// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign, 3 random-k; codes2 / scales2: the second error
+// mode: 0 random block, 1 l1-norm partials of the scaled sign, 2 scaled sign, 3 and 4 random-k; codes2 / scales2: the second error
 // vector of Algorithm 3, or null for plain contractive error feedback
 void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32_t *codes, float *scales, float *delta,
                        uint64_t step, uint32_t *sign_words, const float *c_scale, double *ws, uint32_t *codes2,
@@ -1029,6 +1041,7 @@ void octet_stream_step(const DevicePlan &dp, int mode, const void *grads, uint32
     case ((BF ? 1 : 0) << 8) | B:                                                                                                  \
         if (mode == kModeBlock) CONEF_STREAM_MODE_V2(BF, B, kModeBlock);                                                           \
         else if (mode == kModeStrata) CONEF_STREAM_MODE_V2(BF, B, kModeStrata);                                                    \
+        else if (mode == kModeUniform) CONEF_STREAM_MODE_V2(BF, B, kModeUniform);                                                  \
         else if (mode == kModeNorm) CONEF_STREAM_MODE(BF, B, kModeNorm);                                                           \
         else CONEF_STREAM_MODE(BF, B, kModeSign);                                                                                  \
         break;

@@ -908,8 +908,8 @@ __global__ __launch_bounds__(256) void k_cs_lin_update(DevicePlan dp, const uint
 // Scaled sign (Section 5.1), Delta = c sign(p) with c = ||p||_1 / N per matrix, takes two passes of the same walk:
 // MODE 1 adds up |p| in fp64 (one partial sum per wave; the scale kernel adds them in item order), MODE 2 reads
 // c, writes the sign bits (one byte per octet on this path) and sketches p - Delta on top of beta S.
-// MODE 3, random-k (stratified, see strata_kept_octet): as MODE 0 with the kept coordinates scattered.
-constexpr int kModeBlock = 0, kModeNorm = 1, kModeSign = 2, kModeStrata = 3;
+// MODE 3, random-k (stratified, see strata_kept_octet): as MODE 0 with the kept coordinates scattered; MODE 4, random-k as a
+// uniformly drawn subset (see rku_perm): the same, the value of a kept coordinate j in slot pi(j).
 
 template <bool BF16, bool F16, int MODE>
 __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *__restrict__ grads, void *table,
@@ -925,6 +925,8 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
     const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
     const int64_t stop = MODE == kModeBlock ? start + d.rb_k : 0;
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    RkuKeys ku = {};
+    if (MODE == kModeUniform) ku = rku_keys((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi);
     double l1 = 0.0;
     const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
     const int32_t *rows = dp.bucket_rows + d.hash_off;
@@ -973,6 +975,11 @@ __global__ __launch_bounds__(64) void k_cs_rb_octet(DevicePlan dp, const void *_
                 } else if (MODE == kModeStrata) {
                     const bool inside = ((kbits >> j) & 1u) != 0;
                     if (inside && active) delta[d.rk_delta_off + kfirst + __popc(kbits & ((1u << j) - 1u))] = pv;
+                    x = inside ? 0.0f : pv;
+                } else if (MODE == kModeUniform) {
+                    const uint32_t pi = rku_perm((uint32_t)(j0 + j), (uint32_t)d.N, d.rk_ua, d.rk_ub, d.rk_umagic, ku);
+                    const bool inside = pi < d.rk_uk;
+                    if (inside && active) delta[d.rk_delta_off + pi] = pv;
                     x = inside ? 0.0f : pv;
                 } else if (MODE == kModeNorm) {
                     l1 += active ? (double)fabsf(pv) : 0.0;
@@ -1028,6 +1035,8 @@ __global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const 
     const bool active = k < d.m;
     const int64_t start = MODE == kModeBlock ? random_block_start((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, d.N, d.rb_k) : 0;
     const float c = MODE == kModeSign ? c_scale[it.mat] : 0.0f;
+    RkuKeys ku = {};
+    if (MODE == kModeUniform) ku = rku_keys((uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi);
     double l1 = 0.0;
     const int32_t *ptr = dp.bucket_ptr + d.bptr_off;
     const int32_t *rows = dp.bucket_rows + d.hash_off;
@@ -1049,6 +1058,11 @@ __global__ __launch_bounds__(kCsCols) void k_cs_rb_generic(DevicePlan dp, const 
                 const bool inside = strata_kept((uint32_t)j, (uint32_t)d.N, d.rk_g, d.rk_magic, (uint32_t)it.mat, step_lo, step_hi,
                                                 dp.seed_lo, dp.seed_hi, &si);
                 if (inside) delta[d.rk_delta_off + si] = pv;
+                x = inside ? 0.0f : pv;
+            } else if (MODE == kModeUniform) {
+                const uint32_t pi = rku_perm((uint32_t)j, (uint32_t)d.N, d.rk_ua, d.rk_ub, d.rk_umagic, ku);
+                const bool inside = pi < d.rk_uk;
+                if (inside) delta[d.rk_delta_off + pi] = pv;
                 x = inside ? 0.0f : pv;
             } else if (MODE == kModeNorm) {
                 l1 += (double)fabsf(pv);
@@ -1188,10 +1202,12 @@ void cs_stream_pass(const DevicePlan &dp, const void *grads, void *table, float 
 }  // namespace
 
 hipError_t launch_cs_rb_step(const DevicePlan &dp, const void *grads, void *table, float *delta, uint64_t step,
-                             bool strata, hipStream_t st)
+                             int mode, hipStream_t st)
 {
-    if (strata)
+    if (mode == kModeStrata)
         cs_stream_pass<kModeStrata>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
+    else if (mode == kModeUniform)
+        cs_stream_pass<kModeUniform>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
     else
         cs_stream_pass<kModeBlock>(dp, grads, table, delta, (uint32_t)step, (uint32_t)(step >> 32), nullptr, nullptr, nullptr, st);
     return hipGetLastError();

@@ -2,6 +2,7 @@
 
 #include <array>
 #include <climits>
+#include <cmath>
 #include <cstdint>
 #include <utility>
 
@@ -142,7 +143,66 @@ int configure_random_k(Plan &plan, const int64_t *group)
         off += round_up((d.N + group[l] - 1) / group[l], kAlign);
     }
     plan.rk_delta_elems = (size_t)off;
+    plan.rk_uniform = false;
     return kOk;
+}
+
+namespace {
+uint32_t rku_mix(uint32_t u)
+{
+    u *= 0x9E3779B1u; u ^= u >> 15; u *= 0x85EBCA77u; u ^= u >> 13;
+    return u;
+}
+}  // namespace
+
+int configure_random_k_uniform(Plan &plan, const int64_t *keep)
+{
+    if (!keep) return kEinval;
+    const int n_mats = (int)plan.mats.size();
+    for (int l = 0; l < n_mats; ++l)
+        if (keep[l] < 1 || keep[l] > plan.mats[l].N || plan.mats[l].N >= ((int64_t)1 << 32)) return kEinval;
+    int64_t off = 0;
+    for (int l = 0; l < n_mats; ++l) {
+        MatDesc &d = plan.mats[l];
+        d.rk_g = 0;
+        d.rk_uk = (uint32_t)keep[l];
+        uint64_t a = (uint64_t)std::sqrt((double)d.N);              // a = ceil(sqrt(N)), exactly
+        while (a * a < (uint64_t)d.N) ++a;
+        while (a > 1 && (a - 1) * (a - 1) >= (uint64_t)d.N) --a;
+        d.rk_ua = (uint32_t)a;
+        d.rk_ub = (uint32_t)(((uint64_t)d.N + a - 1) / a);
+        d.rk_umagic = d.rk_ub == 1 ? 0 : ~(uint64_t)0 / d.rk_ub + 1;     // (a power of two: 2^64 / b, also exact)
+        if (d.rk_ub > 1 && (d.rk_ub & (d.rk_ub - 1)) == 0) d.rk_umagic = ((uint64_t)1 << 63) / (d.rk_ub >> 1);
+        d.rk_delta_off = off;
+        off += round_up(keep[l], kAlign);
+    }
+    plan.rk_delta_elems = (size_t)off;
+    plan.rk_uniform = true;
+    return kOk;
+}
+
+int64_t random_k_uniform_index(uint64_t seed, uint32_t mat, uint64_t step, const MatDesc &d, int64_t i)
+{
+    uint32_t o0[4], o1[4];
+    host_philox4x32_10(mat, 0xFFFFFFFDu, (uint32_t)step, (uint32_t)(step >> 32), seed, o0);
+    host_philox4x32_10(mat, 0xFFFFFFFCu, (uint32_t)step, (uint32_t)(step >> 32), seed, o1);
+    const uint32_t key[6] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1]};
+    const uint32_t a = d.rk_ua, b = d.rk_ub;
+    uint32_t x = (uint32_t)i;
+    do {                                                    // the rounds backwards, walked again while outside [0, N)
+        uint32_t L = x / b, R = x % b;
+        for (int r = 5; r >= 0; --r) {
+            if ((r & 1) == 0) {
+                const uint32_t f = (uint32_t)(((uint64_t)rku_mix(R ^ key[r]) * a) >> 32);
+                L = L >= f ? L - f : L + a - f;
+            } else {
+                const uint32_t f = (uint32_t)(((uint64_t)rku_mix(L ^ key[r]) * b) >> 32);
+                R = R >= f ? R - f : R + b - f;
+            }
+        }
+        x = L * b + R;
+    } while ((int64_t)x >= d.N);
+    return (int64_t)x;
 }
 
 namespace {
@@ -600,7 +660,22 @@ bool check_plan(const Plan &plan)
 {
     const size_t nm = plan.mats.size();
     // random-k: the multiply-high division by the stratum length, on the coordinates around every kind of boundary
-    if (plan.rk_delta_elems != 0)
+    if (plan.rk_delta_elems != 0 && plan.rk_uniform)
+        for (const MatDesc &d : plan.mats) {
+            // the keyed permutation's shape and its division by b, on the coordinates around every kind of boundary
+            if (d.rk_g != 0 || d.rk_uk < 1 || d.rk_uk > d.N || d.N >= ((int64_t)1 << 32)) return false;
+            const uint64_t a = d.rk_ua, b = d.rk_ub;
+            if (a * a < (uint64_t)d.N || (a > 1 && (a - 1) * (a - 1) >= (uint64_t)d.N) || b != ((uint64_t)d.N + a - 1) / a) return false;
+            if (b == 1) continue;
+            const uint64_t last = a * b - 1;
+            const uint64_t probes[] = {0, 1, b - 1, b, b + 1, 2 * b - 1, last / 2, last / b * b - 1, last / b * b, last - 1, last,
+                                       0xFFFFFFFFull / b * b - 1, 0xFFFFFFFFull / b * b, 0xFFFFFFFFull};
+            for (uint64_t j : probes) {
+                j &= 0xFFFFFFFFull;
+                if ((uint64_t)(((unsigned __int128)j * d.rk_umagic) >> 64) != j / b) return false;
+            }
+        }
+    else if (plan.rk_delta_elems != 0)
         for (const MatDesc &d : plan.mats) {
             if (d.rk_g < 1 || d.rk_g > d.N || d.N >= ((int64_t)1 << 32)) return false;
             if (d.rk_g == 1) continue;

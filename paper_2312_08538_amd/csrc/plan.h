@@ -68,6 +68,9 @@ struct MatDesc {
     uint32_t rk_pad;
     uint64_t rk_magic;              // floor(2^64 / rk_g) + 1: j / rk_g = mulhi64(j, rk_magic) for j < 2^32 (unused for rk_g = 1)
     int64_t rk_delta_off;           // offset of the matrix's kept values (one per stratum) in the flat Delta buffer
+    // ... or a uniformly drawn subset (rk_g = 0): rk_uk coordinates kept, the keyed permutation's shape a x b
+    uint32_t rk_uk, rk_ua, rk_ub, rk_upad;
+    uint64_t rk_umagic;             // floor(2^64 / rk_ub) + 1
     // Algorithm 3, version 2: the first error vector is a random block of the matrix, kept as it is
     int64_t i2_k;                   // coordinates it keeps (0: none)
     int64_t i2_off;                 // offset of the matrix's kept values in the flat buffer of first error vectors
@@ -130,7 +133,8 @@ struct Plan {
     // element-wise gradient compressors with the quantiser: stream tables (made with the plan)
     size_t sign_words = 0;
     size_t rb_delta_elems = 0;      // set by configure_random_block
-    size_t rk_delta_elems = 0;      // set by configure_random_k
+    size_t rk_delta_elems = 0;      // set by configure_random_k / configure_random_k_uniform
+    bool rk_uniform = false;        // the latter
     bool sketch_cols = false;       // count sketch in the column form: tables are rows x w, hashes and bucket lists are over columns
     size_t i2_elems = 0;            // set by configure_i2 (never 0 once configured)
     bool i2_configured = false;
@@ -166,6 +170,9 @@ int64_t random_k_index(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, in
 
 // First coordinate of the kept block of a matrix of N elements at `step` (Philox4x32-10 of (matrix, ~0, step)).
 int64_t random_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t k);
+// random-k as a uniformly drawn subset of keep[l] coordinates; the coordinate that goes to slot i (pi^-1(i))
+int configure_random_k_uniform(Plan &plan, const int64_t *keep);
+int64_t random_k_uniform_index(uint64_t seed, uint32_t mat, uint64_t step, const MatDesc &d, int64_t i);
 // Algorithm 3, version 2: sizes of the first error vectors (keep_e[l] in 0 .. N_l) and where each one's block starts
 int configure_i2(Plan &plan, const int64_t *keep_e);
 int64_t i2_block_start(uint64_t seed, uint32_t mat, uint64_t step, int64_t N, int64_t ke);

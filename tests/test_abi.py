@@ -334,6 +334,54 @@ def test_random_k_layout_and_kept_coordinates_match_the_oracle(ref):
     B.conef_destroy(ctx)
 
 
+def test_uniform_random_k_layout_and_slots_match_the_oracle(ref):
+    """The uniformly drawn k-subset (host side): sizes, offsets, the coordinate of every slot (the inverse of the keyed
+    permutation), and that the coordinates of the k slots are distinct."""
+    layout = [(64, 147), (512, 1024), (3, 5), (256, 256), (1, 1)]
+    keep = [941, 52429, 15, 1, 1]
+    seed = 0xC0FFEE123
+    for ctx in (B.conef_init(layout, 1, 4, 128, B.BF16, seed),
+                B.conef_cs_init(layout, [8, 100, 3, 7, 1], 1, 0.5, B.TABLE_F16, B.BF16, seed)):
+        L = B.lib()
+        assert L.conef_rk_sizes(ctx, None) == B.ESTATE
+        B.conef_rk_configure_uniform(ctx, keep)
+        off = 0
+        for l, (n, m) in enumerate(layout):
+            N, k = n * m, keep[l]
+            o = B.conef_rk_offsets(ctx, l)
+            assert (o["delta_off"], o["keep"]) == (off, k)
+            off += (k + 63) // 64 * 64
+            for step in (0, 7, 2 ** 33 + 1):
+                want = ref.rk_indices(seed, l, step, N, -k)
+                assert len(set(want.tolist())) == k and want.min() >= 0 and want.max() < N
+                for i in sorted({0, 1 % k, k // 2, k - 1}):
+                    j = B.conef_rk_index(ctx, l, step, i)
+                    assert j == want[i] and ref.rku_perm(seed, l, step, N, j) == i
+            with pytest.raises(B.ConefError) as e:
+                B.conef_rk_index(ctx, l, 0, k)
+            assert e.value.code == B.EINVAL
+        assert B.conef_rk_sizes(ctx)["delta_elems"] == off
+        B.conef_check_plan(ctx)
+        for bad in ([0, 1, 1, 1, 1], [1, 1, 16, 1, 1], [-3, 1, 1, 1, 1]):
+            with pytest.raises(B.ConefError) as e:
+                B.conef_rk_configure_uniform(ctx, bad)
+            assert e.value.code == B.EINVAL
+        assert L.conef_rk_configure_uniform(ctx, None) == B.EINVAL
+        # the stratified form replaces it, and the other way round
+        B.conef_rk_configure(ctx, [10, 16, 4, 3, 1])
+        assert B.conef_rk_offsets(ctx, 0)["keep"] == -(-64 * 147 // 10)
+        B.conef_check_plan(ctx)
+        B.conef_rk_configure_uniform(ctx, keep)
+        assert B.conef_rk_offsets(ctx, 0)["keep"] == keep[0]
+        B.conef_check_plan(ctx)
+        B.conef_destroy(ctx)
+    ctx = B.conef_init([(65536, 65536)], 2, 4, 128, B.BF16, 1)
+    with pytest.raises(B.ConefError) as e:
+        B.conef_rk_configure_uniform(ctx, [10])
+    assert e.value.code == B.EINVAL
+    B.conef_destroy(ctx)
+
+
 def test_first_error_vector_layout_and_start_match_the_oracle(ref):
     """Algorithm 3, version 2: sizes, offsets and block starts of the first error vectors (host side)."""
     layout = [(64, 147), (512, 1024), (3, 5)]

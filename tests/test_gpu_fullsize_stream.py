@@ -25,18 +25,24 @@ def env():
 
 
 @pytest.mark.parametrize("which", ["random_block", "scaled_sign", "random_k", "iconef_random_block", "iconef_scaled_sign",
-                                   "iconef_random_k", "iconef2_random_k"])
+                                   "iconef_random_k", "iconef2_random_k", "random_k_uniform", "iconef2_random_k_uniform"])
 def test_large_whole_model_stream_step_against_the_oracle(env, which):
     R, B, torch = env
+    uniform = which.endswith("_uniform")     # random-k as a uniformly drawn subset of a tenth of every matrix
+    which = which[:-len("_uniform")] if uniform else which
     w = wl.WORKLOADS["large"]
     bits, block, W, seed = w.bits, w.block, 32 // w.bits, w.lib_seed
     v2 = which.startswith("iconef2")         # Algorithm 3, version 2: a random block of 5 % of every matrix as the first error vector
     two, block_mode, strata = which.startswith("iconef") and not v2, which.endswith("random_block"), which.endswith("random_k")
     keep = wl.random_block_keep(w.layout, 0.1)
-    group = [10] * len(w.layout)
+    group = [-(-(n * m) // 10) for n, m in w.layout] if uniform else [10] * len(w.layout)
     model = B.Model(w.layout, w.rank, bits, block, w.grad_dtype, seed)
     B.conef_rb_configure(model.ctx, keep)
-    B.conef_rk_configure(model.ctx, group)
+    if uniform:
+        B.conef_rk_configure_uniform(model.ctx, group)
+        group = [-k for k in group]           # the oracle's way of saying so
+    else:
+        B.conef_rk_configure(model.ctx, group)
     keep_e = [(n * m) // 20 for n, m in w.layout]
     if v2:
         B.conef_i2_configure(model.ctx, keep_e)
