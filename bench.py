@@ -552,14 +552,16 @@ def kernels_digest(w) -> str:
     counter values measured on other sources are not this build's (profiles/hbm_traffic.json records the digest of the
     run it was measured on)."""
     if w.rank == 32 and w.grad_dtype == 1 and w.bits == 4 and w.block == 128:
-        family = "kernels_mfma.hip"
+        family = ("kernels_mfma.hip", "mfma_common.h")
+    elif w.rank in (2, 4, 8) and w.grad_dtype == 1 and w.bits in (2, 4) and w.block >= 128:
+        family = ("kernels_octet.hip", "kernels_pack.hip", "mfma_common.h")        # packed-split P and Q+, the octet family's err pass
     elif w.rank in (2, 4, 8):
-        family = "kernels_octet.hip"
+        family = ("kernels_octet.hip",)
     else:
-        family = "kernels_generic.hip"
+        family = ("kernels_generic.hip",)
     d = os.path.join(ROOT, "paper_2312_08538_amd", "csrc")
     h = hashlib.sha256()
-    for name in (family, "device_common.h", "kernels.h", "plan.h", "plan.cpp"):
+    for name in (*family, "device_common.h", "kernels.h", "plan.h", "plan.cpp"):
         h.update(name.encode())
         h.update(open(os.path.join(d, name), "rb").read())
     return h.hexdigest()[:16]

@@ -402,6 +402,22 @@ int conef_get_timing(conef_ctx *ctx, float ms[4]);
  * workspace_bytes.  Returns CONEF_OK, or CONEF_ESTATE if the plan is inconsistent. */
 int conef_check_plan(const conef_ctx *ctx);
 
+/* Which kernel family the planner has chosen for matrix `mat` (host only; diagnostic, no passage of the paper), and with
+ * it which agreement with a plain fp64 evaluation of Algorithm 2 lines 3 and 5 its factors have:
+ *   CONEF_FAMILY_GENERIC 0, CONEF_FAMILY_OCTET 1: P and Q+ are accumulated in fp64 (products of fp32 values are exact
+ *     there): last-bit agreement, and free-running runs keep identical codes;
+ *   CONEF_FAMILY_MFMA 2 (rank 32, bf16 gradients, 4-bit codes, blocks of 128, columns a multiple of 128) and
+ *   CONEF_FAMILY_PACKED 3 (ranks 2, 4, 8 with bf16 gradients, 2- or 4-bit codes, power-of-two blocks of 128 to 512,
+ *     columns a multiple of 128 and of the block): exact operands on the bf16 matrix cores, fp32 sums over one scale
+ *     block or 64 rows, fp64 beyond: about 1e-6 relative.  The err pass of family 3 is family 1's.  Setting CONEF_PACK=0
+ *     in the environment before conef_init keeps family 1 for these matrices.
+ * Count-sketch contexts report 0 or 1.  Errors: CONEF_EINVAL (null pointers, mat out of range). */
+#define CONEF_FAMILY_GENERIC 0
+#define CONEF_FAMILY_OCTET 1
+#define CONEF_FAMILY_MFMA 2
+#define CONEF_FAMILY_PACKED 3
+int conef_matrix_family(const conef_ctx *ctx, int mat, int *family);
+
 void conef_destroy(conef_ctx *ctx);
 const char *conef_strerror(int code);
 

@@ -19,7 +19,7 @@ STATIC_WORKSPACE_BYTES = 32 << 20
 
 EXPORTS = ["conef_init", "conef_sizes", "conef_offsets", "conef_step", "conef_step_static", "conef_step_p",
            "conef_orthonormalise", "conef_step_q", "conef_step_err", "conef_reset_error",
-           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_decompress",
+           "conef_decode_error", "conef_set_timing", "conef_get_timing", "conef_check_plan", "conef_matrix_family", "conef_decompress",
            "conef_apply_update", "conef_destroy",
            "conef_strerror", "conef_set_beta",
            "conef_ss_sizes", "conef_ss_offsets", "conef_ss_step", "conef_cs_ss_step",
@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
     L.conef_set_timing.argtypes = [vp, i32]
     L.conef_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.conef_check_plan.argtypes = [vp]
+    L.conef_matrix_family.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_int)]
     L.conef_set_beta.argtypes = [vp, ctypes.c_float]
     L.conef_ss_sizes.argtypes = [vp, szp]
     L.conef_ss_offsets.argtypes = [vp, i32, szp]
@@ -331,6 +332,17 @@ def conef_set_beta(ctx, beta: float) -> None:
 
 def conef_check_plan(ctx) -> None:
     _check(lib().conef_check_plan(ctx), "conef_check_plan")
+
+
+FAMILY_GENERIC, FAMILY_OCTET, FAMILY_MFMA, FAMILY_PACKED = 0, 1, 2, 3
+
+
+def conef_matrix_family(ctx, mat: int) -> int:
+    """kernel family of a matrix: 0 generic, 1 octet (both accumulate the factors in fp64), 2 rank-32 matrix cores,
+    3 octet with the packed-split P and Q+ passes on the bf16 matrix cores (fp32 sums)"""
+    v = ctypes.c_int()
+    _check(lib().conef_matrix_family(ctx, mat, ctypes.byref(v)), "conef_matrix_family")
+    return v.value
 
 
 def conef_offsets(ctx, mat: int) -> dict:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconef.so")
-SOURCES = ["api.cpp", "plan.cpp", "kernels_generic.hip", "kernels_orth.hip", "kernels_octet.hip", "kernels_mfma.hip", "kernels_sketch.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "kernels_generic.hip", "kernels_orth.hip", "kernels_octet.hip", "kernels_mfma.hip", "kernels_pack.hip", "kernels_sketch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -ffp-contract=off: the quantiser's decisions are taken in fp32 in a fixed order, every

@@ -74,6 +74,8 @@ int ensure_uploaded(conef_ctx *ctx)
     if ((rc = upload(ctx, pl.err_t_items, &d.err_t_items))) return rc;
     if ((rc = upload(ctx, pl.p_m_items, &d.p_m_items))) return rc;
     if ((rc = upload(ctx, pl.q_m_items, &d.q_m_items))) return rc;
+    if ((rc = upload(ctx, pl.p_k_items, &d.p_k_items))) return rc;
+    if ((rc = upload(ctx, pl.q_k_items, &d.q_k_items))) return rc;
     if ((rc = upload(ctx, pl.err_m_items, &d.err_m_items))) return rc;
     if ((rc = upload(ctx, pl.split_p_items, &d.split_p_items))) return rc;
     if ((rc = upload(ctx, pl.split_qn_items, &d.split_qn_items))) return rc;
@@ -121,6 +123,8 @@ int ensure_uploaded(conef_ctx *ctx)
     d.n_err_t = (int)pl.err_t_items.size();
     d.n_p_m = (int)pl.p_m_items.size();
     d.n_q_m = (int)pl.q_m_items.size();
+    d.n_p_k = (int)pl.p_k_items.size();
+    d.n_q_k = (int)pl.q_k_items.size();
     d.n_err_m = (int)pl.err_m_items.size();
     d.n_split_p = (int)pl.split_p_items.size();
     d.n_split_qn = (int)pl.split_qn_items.size();
@@ -278,6 +282,15 @@ int conef_check_plan(const conef_ctx *ctx)
 {
     if (!ctx) return CONEF_EINVAL;
     return check_plan(ctx->plan) ? CONEF_OK : CONEF_ESTATE;
+}
+
+int conef_matrix_family(const conef_ctx *ctx, int mat, int *family)
+{
+    if (!ctx || !family || mat < 0 || mat >= (int)ctx->plan.mats.size()) return CONEF_EINVAL;
+    const MatDesc &d = ctx->plan.mats[mat];
+    *family = d.path == kPathMfma ? CONEF_FAMILY_MFMA : d.pack ? CONEF_FAMILY_PACKED : d.path == kPathOctet ? CONEF_FAMILY_OCTET
+                                                                                                            : CONEF_FAMILY_GENERIC;
+    return CONEF_OK;
 }
 
 int conef_sizes(const conef_ctx *ctx, size_t *grad_elems, size_t *code_words, size_t *n_scales,

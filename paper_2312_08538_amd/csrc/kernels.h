@@ -13,6 +13,7 @@ struct DevicePlan {
     const WorkItem *p_f_items = nullptr, *q_f_items = nullptr, *err_f_items = nullptr;    // octet family
     const WorkItem *err_t_items = nullptr;      // octet family, err pass with the residual on the fp32 matrix cores
     const WorkItem *p_m_items = nullptr, *q_m_items = nullptr, *err_m_items = nullptr;    // MFMA family
+    const WorkItem *p_k_items = nullptr, *q_k_items = nullptr;                            // packed-split passes
     const WorkItem *split_p_items = nullptr, *split_qn_items = nullptr;
     const WorkItem *upd_items = nullptr;                                                   // decompress / update
     // random-block gradient compressor
@@ -34,6 +35,7 @@ struct DevicePlan {
     int n_mats = 0;
     int n_p = 0, n_q = 0, n_err = 0, n_p_f = 0, n_q_f = 0, n_err_f = 0, n_err_t = 0;
     int n_p_m = 0, n_q_m = 0, n_err_m = 0, n_split_p = 0, n_split_qn = 0;
+    int n_p_k = 0, n_q_k = 0;
     int n_upd = 0;
     int n_pred = 0, n_gram = 0, n_apply = 0, n_qred = 0, n_elem = 0;
     int rank = 0, rpad = 0, bits = 0, block = 0, dtype = 0;
@@ -114,6 +116,11 @@ hipError_t launch_reset(const DevicePlan &dp, uint32_t *codes, float *scales, si
                         hipStream_t st);
 
 // Kernel families (each enqueues its own grouped launches; no-ops when their tables are empty).
+// packed-split P and Q+ passes on the bf16 matrix cores (ranks 2, 4, 8; kernels_pack.hip); dp.i_codes as in mfma_pass_p
+void pack_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, const float *Q, float *P,
+                 hipStream_t st);
+void pack_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales, const float *Phat,
+                 double *ws, float *Qout, hipStream_t st);
 void generic_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                     const float *Q, float *P, hipStream_t st);
 void generic_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,

@@ -593,6 +593,7 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
 {
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_p(dp, grads, codes, scales, Q, P, st);
+    pack_pass_p(dp, grads, codes, scales, Q, P, st);
     octet_pass_p(dp, grads, codes, scales, Q, P, ws, st);
     generic_pass_p(dp, grads, codes, scales, Q, P, st);
     if (span.end) (void)hipEventRecord(span.end, st);
@@ -609,6 +610,7 @@ hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t
     if (dp.i_codes) mfma_transpose_scales(dp, dp.i_scales, ws, true, st);     // the first vector of Algorithm 3
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
+    pack_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
     octet_pass_q(dp, grads, codes, scales, Phat, ws, st);
     generic_pass_q(dp, grads, codes, scales, Phat, ws, st);
     if (span.end) (void)hipEventRecord(span.end, st);

@@ -19,81 +19,13 @@
 
 #include "device_common.h"
 #include "kernels.h"
+#include "mfma_common.h"
 
 namespace conef {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 constexpr int kErrTileElems = 3 * 128 * 32;    // bf16 entries of one column block's splits of Q+
-
-union Frag {
-    bf16x8 v;
-    uint4 u;
-};
-
-__device__ __forceinline__ f32x16 mfma(const Frag &a, const Frag &b, f32x16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
-}
-
-// two fp32 values -> their upper halves (bf16 by truncation) packed: lo in bits 0..15, hi in 16..31
-__device__ __forceinline__ uint32_t pack_hi16(float lo, float hi)
-{
-    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-
-__device__ __forceinline__ float trunc_bf16(float x) { return __uint_as_float(__float_as_uint(x) & 0xFFFF0000u); }
-
-// x = h + m + l with h, m, l representable in bf16 (truncation; each remainder is exact in fp32)
-// (24 significant bits: 8 go to h, 8 to m, and the last remainder has at most 8 left, so it needs
-// no truncation)
-__device__ __forceinline__ void split3(float x, float &h, float &m, float &l)
-{
-    h = trunc_bf16(x);
-    const float r1 = x - h;
-    m = trunc_bf16(r1);
-    l = r1 - m;
-}
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float half_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
-
-// 8 consecutive rows of one column (two transposing reads of 4 rows each)
-__device__ __forceinline__ uint4 lds_read_tr16x8(const uint16_t *p, int pitch)
-{
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    union { s16x4 v; uint2 u; } lo, hi;
-    lo.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    hi.v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * pitch));
-    return make_uint4(lo.u.x, lo.u.y, hi.u.x, hi.u.y);
-}
-
-// signed 4-bit field in the low nibble of byte `byte` of w, divided by 16 (exact), as fp32: the
-// conversion instruction reads the nibble through its byte selector, so no shift or mask is spent
-template <int byte>
-__device__ __forceinline__ float nibble_over_16(uint32_t w)
-{
-    float r;
-    if constexpr (byte == 0) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
-    else if constexpr (byte == 1) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(r) : "v"(w));
-    else if constexpr (byte == 2) asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
-    else asm("v_cvt_off_f32_i4_sdwa %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
-    return r;
-}
-
-// the eight fields of a code word, each divided by 16
-__device__ __forceinline__ void fields_over_16(uint32_t w, float q[8])
-{
-    const uint32_t w4 = w >> 4;
-    q[0] = nibble_over_16<0>(w); q[1] = nibble_over_16<0>(w4);
-    q[2] = nibble_over_16<1>(w); q[3] = nibble_over_16<1>(w4);
-    q[4] = nibble_over_16<2>(w); q[5] = nibble_over_16<2>(w4);
-    q[6] = nibble_over_16<3>(w); q[7] = nibble_over_16<3>(w4);
-}
 
 // ------------------------------------------------------------------ P pass
 // One workgroup per 128 rows (wave w owns rows 32w..32w+31), walking the whole row in stages of

@@ -4,6 +4,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <utility>
 
 #include <algorithm>
@@ -14,6 +15,7 @@ namespace conef {
 namespace {
 constexpr int kOk = 0, kEinval = -1, kEnomem = -2;
 constexpr int kMfmaPasses = 7;      // bit 0: P pass, bit 1: Q+ pass, bit 2: err pass
+constexpr int kPackQRows = 512;     // rows per partial of Q+ of the packed-split Q+ pass
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t v, int64_t a) { return (v + a - 1) / a; }
@@ -386,6 +388,10 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
         // each) per block, at most one wave wide, and rank 2, 4 or 8.  Its P pass stages codes and scales
         // in 128-byte lines: blocks of at least 64 elements and rows of a multiple of 64 columns.
         const bool block_ok = block % 8 == 0 && is_pow2(block / 8) && block / 8 <= 64 && block >= 64;
+        // CONEF_PACK=0 in the environment keeps the octet family's own P and Q+ passes (fp64 matrix cores, results that agree
+        // with a plain fp64 loop to the last bits) for the matrices that would otherwise take the packed-split passes
+        const char *pack_env = std::getenv("CONEF_PACK");
+        const bool pack_enabled = !(pack_env && pack_env[0] == '0');
         int64_t total_elems = 0;
         for (int l = 0; l < n_mats; ++l) total_elems += rows[l] * cols[l];
         // rows per wave item of the err pass: aim at >= ~8192 wave items over the model (measured on 124 M and
@@ -431,6 +437,9 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             // octet family: the err pass with the residual on the fp32 matrix cores, in strips of 128 columns (256 for blocks of 256)
             d.err_tile = (d.path == kPathOctet && !sketch && (rank == 4 || rank == 8) && block <= 256 &&
                           d.m % (block == 256 ? 256 : 128) == 0) ? 1 : 0;
+            // octet family: the P and Q+ passes on the bf16 matrix cores with packed factor splits
+            d.pack = (pack_enabled && d.path == kPathOctet && !sketch && dtype == 1 && (bits == 2 || bits == 4) && block >= 128 &&
+                      d.m % 128 == 0 && d.m <= (1 << 24)) ? 1 : 0;
             if (d.path == kPathOctet) plan.any_octet = true;
             else if (d.path == kPathMfma) plan.any_mfma = true;
             else plan.any_generic = true;
@@ -448,12 +457,12 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             // generic family: short row tiles for small matrices (their workgroups are latency bound,
             // so parallelism has to come from the number of tiles)
             const int gen_q_rows = d.n <= 1024 ? 16 : kGenQRows;
-            d.q_tile_rows = d.cs_lin ? 2048 : d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : gen_q_rows;
+            d.q_tile_rows = d.cs_lin ? 2048 : d.pack ? kPackQRows : d.path == kPathOctet ? q_rows : (d.path == kPathMfma && (kMfmaPasses & 2)) ? 2048 : gen_q_rows;
             d.n_q_tiles = (int32_t)ceil_div(d.n, d.q_tile_rows);
             d.qpart_off = wd; wd += round_up((int64_t)d.n_q_tiles * d.m * rank, 32);
             d.n_p_chunks = 1;
             d.p_chunk_cols = (int32_t)d.m;
-            if (d.path == kPathOctet && !d.cs_lin) {
+            if (d.path == kPathOctet && !d.cs_lin && !d.pack) {
                 d.p_chunk_cols = p_cols;
                 d.n_p_chunks = (int32_t)ceil_div(d.m, d.p_chunk_cols);
                 if (d.n_p_chunks > 1) {
@@ -534,11 +543,17 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
                 const int32_t strips = d.m8 / lr;
                 // consecutive items are the column chunks of one row tile: they run side by side on one
                 // XCD and share the lines of block scales that span several chunks
-                for (int64_t r0 = 0; r0 < d.n; r0 += kPTileRows)
+                for (int64_t r0 = 0; r0 < d.n && !d.pack; r0 += kPTileRows)
                     for (int32_t cc = 0; cc < d.n_p_chunks; ++cc) plan.p_f_items.push_back({l, (int32_t)r0, cc, 0});
                 const int32_t qstrips = (int32_t)ceil_div(d.m, 64);
-                for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
+                for (int32_t rt = 0; rt < d.n_q_tiles && !d.pack; ++rt)
                     for (int32_t st = 0; st < qstrips; ++st) plan.q_f_items.push_back({l, st, rt, 0});
+                if (d.pack) {
+                    // one item per 128 rows (dealt to the XCDs further down); one per pair of neighbouring column blocks and row tile
+                    for (int64_t r0 = 0; r0 < d.n; r0 += kMfmaRows) plan.p_k_items.push_back({l, (int32_t)r0, 0, 0});
+                    for (int32_t rt = 0; rt < d.n_q_tiles; ++rt)
+                        for (int32_t cp = 0; cp < (int32_t)((d.m / 128 + 1) / 2); ++cp) plan.q_k_items.push_back({l, cp, rt, 0});
+                }
                 const int64_t rows_item = (int64_t)std::max(err_rows, rw);
                 // the err pass with the residual on the fp32 matrix cores: strips of 128 columns (256 for blocks of 256)
                 const int64_t tile_cols = block == 256 ? 256 : 128;
@@ -557,7 +572,7 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             for (int32_t t = 0; t < d.n_gram_tiles; ++t) plan.gram_items.push_back({l, t, 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
             // a matrix-core matrix with a single row tile gets its Q+ straight from the Q+ pass
-            if (!(mf_q && d.n_q_tiles == 1) || d.cs_lin)
+            if (!((mf_q || d.pack) && d.n_q_tiles == 1) || d.cs_lin)
                 for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += kUpdRows)
@@ -574,10 +589,11 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
         //     grows with the number of columns, and the last workgroups to start should be the short ones); the
         //     lists have the same shapes at the same positions, so the XCDs stay in step;
         //   - lists are padded to one length L with empty items (mat = -1).
-        if (!plan.p_m_items.empty()) {
-            std::vector<int> order;                         // matrix-core matrices, longest rows first, then by shape
+        auto xcd_lists = [&](std::vector<WorkItem> &table, auto member) {
+            if (table.empty()) return;
+            std::vector<int> order;                         // the family's matrices, longest rows first, then by shape
             for (int l = 0; l < n_mats; ++l)
-                if ((plan.mats[l].path == kPathMfma && (kMfmaPasses & 1)) || plan.mats[l].cs_lin) order.push_back(l);
+                if (member(plan.mats[l])) order.push_back(l);
             std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
                 const MatDesc &a = plan.mats[x], &b = plan.mats[y];
                 return a.m != b.m ? a.m > b.m : a.n > b.n;
@@ -606,12 +622,14 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             }
             size_t L = 0;
             for (const auto &v : lists) L = std::max(L, v.size());
-            plan.p_m_items.clear();
+            table.clear();
             for (auto &v : lists) {
                 v.resize(L, WorkItem{-1, 0, 0, 0});
-                plan.p_m_items.insert(plan.p_m_items.end(), v.begin(), v.end());
+                table.insert(table.end(), v.begin(), v.end());
             }
-        }
+        };
+        xcd_lists(plan.p_m_items, [](const MatDesc &d) { return (d.path == kPathMfma && (kMfmaPasses & 1)) || d.cs_lin; });
+        xcd_lists(plan.p_k_items, [](const MatDesc &d) { return d.pack != 0; });
     } catch (const std::bad_alloc &) {
         return kEnomem;
     }
@@ -696,6 +714,12 @@ bool check_plan(const Plan &plan)
         if (plan.p_m_items.size() % 8 != 0) return false;                  // eight lists of one length
         for (const WorkItem &it : plan.p_m_items)
             if (it.mat >= 0) c.add(plan, it, it.a, kMfmaRows, 0, INT64_MAX);           // (mat = -1: padding)
+        if (plan.p_k_items.size() % 8 != 0) return false;
+        for (const WorkItem &it : plan.p_k_items)
+            if (it.mat >= 0) {
+                if (!plan.mats[it.mat].pack) return false;
+                c.add(plan, it, it.a, kMfmaRows, 0, INT64_MAX);
+            }
         if (!c.complete(plan)) return false;
     }
     // pass 2: Q+ = p^T P^
@@ -706,6 +730,8 @@ bool check_plan(const Plan &plan)
         for (const WorkItem &it : plan.q_f_items)
             c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 64, 64);
         for (const WorkItem &it : plan.q_m_items)
+            c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 256, 256);
+        for (const WorkItem &it : plan.q_k_items)
             c.add(plan, it, (int64_t)it.b * plan.mats[it.mat].q_tile_rows, plan.mats[it.mat].q_tile_rows, (int64_t)it.a * 256, 256);
         if (!c.complete(plan)) return false;
     }
@@ -796,7 +822,10 @@ bool check_plan(const Plan &plan)
     for (size_t l = 0; l < nm; ++l) {
         const MatDesc &d = plan.mats[l];
         if (gram[l] != d.n_gram_tiles || apply[l] != (d.n + 63) / 64) return false;
-        const bool direct_q = d.path == kPathMfma && d.n_q_tiles == 1;
+        const bool direct_q = (d.path == kPathMfma || d.pack) && d.n_q_tiles == 1;
+        if (d.pack && (d.path != kPathOctet || d.n_p_chunks != 1 || (d.m & 127) != 0 || plan.block < 128 || plan.dtype != 1 ||
+                       (plan.bits != 2 && plan.bits != 4)))
+            return false;
         if (qred[l] != (direct_q ? 0 : (d.m * plan.rank + 255) / 256)) return false;
         if (pred[l] != (d.n_p_chunks > 1 ? (d.n * plan.rank + 255) / 256 : 0)) return false;
         regions.push_back({d.gram_off, d.gram_off + (int64_t)d.n_gram_tiles * plan.rank * plan.rank});

@@ -60,7 +60,8 @@ struct MatDesc {
     int64_t cs_t_off;               // workspace offset (doubles) of T, w x 32 fp64
     int64_t cs_u_off;               // workspace offset (doubles) of U, w x 32 fp32
     // random-block gradient compressor
-    int32_t err_tile, err_pad;      // octet family: the err pass runs in strips with the residual on the fp32 matrix cores
+    int32_t err_tile;               // octet family: the err pass runs in strips with the residual on the fp32 matrix cores
+    int32_t pack;                   // octet family: the P and Q+ passes run on the bf16 matrix cores with packed factor splits
     int64_t rb_k;                   // coordinates kept per step (0: not configured)
     int64_t rb_delta_off;           // offset of the matrix's kept values in the flat Delta buffer
     // random-k gradient compressor (stratified: one coordinate kept per stratum of rk_g consecutive ones)
@@ -117,6 +118,9 @@ struct Plan {
     std::vector<WorkItem> err_f_items;  // (mat, strip, first row, rows)
     std::vector<WorkItem> err_t_items;  // (mat, strip of 128 or 256 columns, first row, rows): matrices of the octet family whose
                                         // err pass forms the residual on the fp32 matrix cores (rank 4 or 8, block <= 256)
+    // packed-split passes (matrices of the octet family with bf16 gradients, 2- or 4-bit codes, blocks and rows of 128 or more)
+    std::vector<WorkItem> p_k_items;    // (mat, first row), 128 rows per workgroup; eight lists of one length, one per XCD (mat = -1: padding)
+    std::vector<WorkItem> q_k_items;    // (mat, pair of column blocks of 128, row tile)
     // MFMA family (rank 32, bf16 gradients, 4-bit codes, block 128)
     std::vector<WorkItem> p_m_items;    // (mat, first row), 128 rows per workgroup; eight lists of one length, one per XCD (mat = -1: padding)
     std::vector<WorkItem> q_m_items;    // (mat, pair of column blocks of 128, row tile)

@@ -156,6 +156,12 @@ class GpuModel:
         self.m.step(self.buf, step)
         self.torch.cuda.synchronize()
 
+    def fp32_factors(self, l=None):
+        """Does matrix l (any matrix, if None) take a kernel family whose P and Q+ passes add up in fp32 on the bf16
+        matrix cores (about 1e-6 relative) instead of in fp64 (last-bit agreement with the oracle)?"""
+        mats = range(len(self.m.layout)) if l is None else [l]
+        return any(B.conef_matrix_family(self.m.ctx, i) in (B.FAMILY_MFMA, B.FAMILY_PACKED) for i in mats)
+
     def mat_P(self, l):
         n, _ = self.m.layout[l]
         off = self.m.offsets[l]["p_off"]
@@ -189,11 +195,15 @@ class GpuModel:
         self.buf["scales"][o["scale_off"]:o["scale_off"] + scales.size] = torch.from_numpy(scales).to(dev)
 
 
-def compare_step(gpu: GpuModel, oracle_out, oracle: OracleModel, step, pq_tol, what="", fp32_factors=False):
+def compare_step(gpu: GpuModel, oracle_out, oracle: OracleModel, step, pq_tol, what="", fp32_factors=None):
     """Compares P, Q, scales and codes of every matrix after a step; returns total excused codes.
-    fp32_factors: the path under test accumulates the factors in fp32 (matrix cores), see check_codes."""
+    fp32_factors: the path under test accumulates the factors in fp32 (matrix cores), see check_codes; None: asked of
+    the library, matrix by matrix."""
     excused = 0
+    ask = fp32_factors is None
     for l, (Ph, Qn, x) in enumerate(oracle_out):
+        if ask:
+            fp32_factors = gpu.fp32_factors(l)
         st = oracle.states[l]
         N = st.n * st.m
         tag = f"{what} mat {l} ({st.n}x{st.m}) step {step}"

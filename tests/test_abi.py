@@ -382,6 +382,37 @@ def test_uniform_random_k_layout_and_slots_match_the_oracle(ref):
     B.conef_destroy(ctx)
 
 
+def test_kernel_family_of_a_matrix_is_reported(monkeypatch):
+    """conef_matrix_family: which matrices accumulate their factors in fp64 (families 0 and 1) and which on the bf16 matrix
+    cores (2: rank 32; 3: packed splits at ranks 2, 4, 8), and that CONEF_PACK=0 keeps family 1."""
+    layout = [(64, 147), (300, 512), (40, 256), (128, 128)]
+    cases = [  # rank, bits, block, dtype -> families
+        (8, 2, 256, B.BF16, [0, 3, 3, 0]),           # 128 columns do not hold a block of 256
+        (8, 2, 256, B.F32, [0, 1, 1, 0]),
+        (4, 4, 128, B.BF16, [0, 3, 3, 3]),
+        (4, 8, 128, B.BF16, [0, 1, 1, 1]),           # 8-bit codes stay on the octet family
+        (4, 4, 64, B.BF16, [0, 1, 1, 1]),            # so do blocks below 128
+        (32, 4, 128, B.BF16, [0, 2, 2, 2]),
+        (16, 4, 128, B.BF16, [0, 0, 0, 0]),
+    ]
+    for rank, bits, block, dt, want in cases:
+        ctx = B.conef_init(layout, rank, bits, block, dt, 5)
+        assert [B.conef_matrix_family(ctx, l) for l in range(len(layout))] == want, (rank, bits, block, dt)
+        B.conef_check_plan(ctx)
+        with pytest.raises(B.ConefError) as e:
+            B.conef_matrix_family(ctx, len(layout))
+        assert e.value.code == B.EINVAL
+        B.conef_destroy(ctx)
+    monkeypatch.setenv("CONEF_PACK", "0")
+    ctx = B.conef_init(layout, 8, 2, 256, B.BF16, 5)
+    assert [B.conef_matrix_family(ctx, l) for l in range(len(layout))] == [0, 1, 1, 0]
+    B.conef_check_plan(ctx)
+    B.conef_destroy(ctx)
+    sk = B.conef_cs_init(layout, [8, 100, 8, 16], 8, 0.5, B.TABLE_F16, B.BF16, 5)
+    assert all(B.conef_matrix_family(sk, l) in (0, 1) for l in range(len(layout)))
+    B.conef_destroy(sk)
+
+
 def test_first_error_vector_layout_and_start_match_the_oracle(ref):
     """Algorithm 3, version 2: sizes, offsets and block starts of the first error vectors (host side)."""
     layout = [(64, 147), (512, 1024), (3, 5)]

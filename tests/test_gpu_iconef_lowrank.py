@@ -36,6 +36,9 @@ CASES = [
     ([(100, 192), (33, 64)], 2, 8, 64),
     ([(70, 200), (256, 384)], 12, 4, 200),                     # a rank outside 2/4/8 and an odd block length
     ([(500, 768), (64, 147)], 8, 8, 128),                      # both families in one model
+    # bf16 gradients: the packed-split P and Q+ passes on the bf16 matrix cores, each vector's share in a launch of its own
+    ([(300, 256), (77, 384), (1100, 128)], 4, 4, 128),         # an odd number of column blocks, partial sums of Q+
+    ([(130, 1536), (520, 512)], 2, 2, 512),
 ]
 
 

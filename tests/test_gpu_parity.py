@@ -33,10 +33,10 @@ def _run_model(env, w, layout, steps, what, grads_fn=None, q0_fn=None, resync=Tr
     scales, Q) is reset to the oracle's before every step, so that each step is compared on
     identical inputs (`lockstep`)."""
     R, B, U = env
-    if lockstep is None:
-        lockstep = (w.rank == 32 and w.grad_dtype == wl.BF16)
     Q0s = [(q0_fn(l) if q0_fn else wl.host_q0(w, l, shape=layout[l])) for l in range(len(layout))]
     gpu = U.GpuModel(layout, w.rank, w.bits, w.block, w.grad_dtype, w.lib_seed, Q0s, beta=beta)
+    if lockstep is None:
+        lockstep = gpu.fp32_factors()
     ora = U.OracleModel(layout, w.rank, w.bits, w.block, w.lib_seed, Q0s, beta=beta)
     total_excused = 0
     for t in range(steps):
@@ -50,7 +50,7 @@ def _run_model(env, w, layout, steps, what, grads_fn=None, q0_fn=None, resync=Tr
         print(f"[{what}] step {t}: launching", flush=True)
         gpu.step(t)
         out = ora.step(grads, t)
-        ex = U.compare_step(gpu, out, ora, t, PQ_TOL[w.grad_dtype], what, fp32_factors=lockstep)
+        ex = U.compare_step(gpu, out, ora, t, PQ_TOL[w.grad_dtype], what)
         total_excused += ex
         if ex and resync:
             # an excused one-level difference would otherwise be carried into every later step
