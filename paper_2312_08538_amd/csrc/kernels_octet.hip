@@ -303,7 +303,7 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 typedef float tile_f32x4 __attribute__((ext_vector_type(4)));
 
 template <bool BF16, int BITS, int RP, bool WIDE, bool TWO>
-__global__ __launch_bounds__(256) void k_err_tile(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
+__global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *__restrict__ grads, uint32_t *codes, float *scales,
                                                   const float *__restrict__ Phat, const float *__restrict__ Qn,
                                                   uint32_t step_lo, uint32_t step_hi, uint32_t *codes_first, float *scales_first)
 {
@@ -319,14 +319,22 @@ __global__ __launch_bounds__(256) void k_err_tile(DevicePlan dp, const void *__r
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     const int lb = WIDE ? 4 : d.lb_shift;                   // lanes of one DPP row that share a scale block
 
-    // B operand: Q+[column 8 (oc0 + 16 h) + t][4 q + kg]
+    // B operand: Q+[column 8 (oc0 + 16 h) + t][4 q + kg].  It does not change over the strip's rows: in registers, or, for
+    // the wide strips, whose two tiles need the registers for a second set of inputs, in LDS of the wave's own (one entry
+    // per lane and operand: conflict-free 4-byte reads, no barrier: a lane reads back what it wrote)
+    __shared__ float s_bq[WIDE ? 4 * NT * 8 * NQ * 64 : 1];
     float bq[NT][8][NQ];
+    float *my_bq = s_bq + (WIDE ? (threadIdx.x >> 6) * (NT * 8 * NQ * 64) + lane : 0);
 #pragma unroll
     for (int h = 0; h < NT; ++h)
 #pragma unroll
         for (int t = 0; t < 8; ++t)
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) bq[h][t][q] = Qn[d.q_off + ((int64_t)(oc0 + 16 * h) * 8 + t) * RP + 4 * q + kg];
+            for (int q = 0; q < NQ; ++q) {
+                const float v = Qn[d.q_off + ((int64_t)(oc0 + 16 * h) * 8 + t) * RP + 4 * q + kg];
+                if (WIDE) my_bq[((h * 8 + t) * NQ + q) * 64] = v;
+                else bq[h][t][q] = v;
+            }
 
     struct TripIn {
         RawOctet<BF16, BITS> o[NT][4];
@@ -357,7 +365,9 @@ __global__ __launch_bounds__(256) void k_err_tile(DevicePlan dp, const void *__r
             for (int t = 0; t < 8; ++t) {
                 acc[h][t] = tile_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) acc[h][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.a[q], bq[h][t][q], acc[h][t], 0, 0, 0);
+                for (int q = 0; q < NQ; ++q)
+                    acc[h][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(in.a[q], WIDE ? my_bq[((h * 8 + t) * NQ + q) * 64] : bq[h][t][q],
+                                                                     acc[h][t], 0, 0, 0);
             }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -417,15 +427,6 @@ __global__ __launch_bounds__(256) void k_err_tile(DevicePlan dp, const void *__r
             }
         }
     };
-    if (WIDE) {
-        // two tiles of inputs and accumulators leave no room for a second set: the other waves of the SIMD cover the loads
-        for (int r0 = it.b; r0 < row_end; r0 += 16) {
-            TripIn t;
-            load_trip(t, r0);
-            process(t, r0);
-        }
-        return;
-    }
     // the next trip is loaded before the current one is worked on; two register sets take turns
     TripIn ta, tb;
     load_trip(ta, it.b);
