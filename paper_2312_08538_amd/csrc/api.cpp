@@ -335,18 +335,21 @@ int conef_step_p(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
 }
 
 namespace {
-int orthonormalise_impl(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
+// tr_a / tr_b: block scales of the error vector(s) of a full step, copied column block by column block for the rank-32
+// family's Q+ and err passes inside this stage's launches (null in the stage call)
+int orthonormalise_impl(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream, const float *tr_a = nullptr,
+                        const float *tr_b = nullptr)
 {
     if (!ctx || !P_inout || !workspace) return CONEF_EINVAL;
     if (misaligned(P_inout, 16) || misaligned(workspace, 256)) return CONEF_EINVAL;
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st, stage_span(ctx, 1)));
+    return hip_rc(launch_orthonormalise(ctx->dev, P_inout, ws_doubles(ctx, workspace), st, stage_span(ctx, 1), tr_a, tr_b));
 }
 
 int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
-                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused);
+                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool scales_ready);
 }  // namespace
 
 int conef_orthonormalise(conef_ctx *ctx, float *P_inout, void *workspace, void *hip_stream)
@@ -362,7 +365,7 @@ int conef_step_q(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, c
 
 namespace {
 int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, const float *err_scales,
-                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused)
+                const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool scales_ready)
 {
     if (!ctx || !grads || !err_codes || !err_scales || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
     if (ctx->plan.sketch) return CONEF_ESTATE;
@@ -372,7 +375,7 @@ int step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *err_codes, co
     int rc = ensure_uploaded(ctx);
     if (rc) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_doubles(ctx, workspace), fused, st,
+    return hip_rc(launch_pass_q(ctx->dev, grads, err_codes, err_scales, P_hat, Q_out, ws_doubles(ctx, workspace), scales_ready, st,
                                 stage_span(ctx, 2)));
 }
 
@@ -406,7 +409,8 @@ int conef_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *er
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = conef_step_p(ctx, grads, err_codes, err_scales, Q_state, P_out, workspace, hip_stream))) return rc;
     /* exchange point 1: mean of P over the workers -- identity for one worker */
-    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
+    if (!err_scales) return CONEF_EINVAL;
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, err_scales))) return rc;
     if ((rc = step_q_impl(ctx, grads, err_codes, err_scales, P_out, Q_out, workspace, hip_stream, true))) return rc;
     /* exchange point 2: mean of Q over the workers -- identity for one worker; the operand splits
        of P^ and Q+ made by the Q+ stage are therefore still valid for the err stage */
@@ -497,7 +501,7 @@ int i_step_p_impl(conef_ctx *ctx, const void *grads, const uint32_t *c1, const f
 }
 
 int i_step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *c1, const float *s1, const uint32_t *c2, const float *s2,
-                  const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool fused)
+                  const float *P_hat, float *Q_out, void *workspace, void *hip_stream, bool scales_ready)
 {
     if (!ctx || !grads || !c1 || !s1 || !c2 || !s2 || !P_hat || !Q_out || !workspace) return CONEF_EINVAL;
     int rc = i_lowrank_state(ctx);
@@ -505,7 +509,7 @@ int i_step_q_impl(conef_ctx *ctx, const void *grads, const uint32_t *c1, const f
     if (i_bad_state_pointers(grads, c1, s1, c2, s2) || misaligned(P_hat, 16) || misaligned(Q_out, 16) || misaligned(workspace, 256))
         return CONEF_EINVAL;
     if ((rc = ensure_uploaded(ctx))) return rc;
-    return hip_rc(launch_pass_q(PlanWithFirst(ctx, c1, s1).dp, grads, c2, s2, P_hat, Q_out, ws_doubles(ctx, workspace), fused,
+    return hip_rc(launch_pass_q(PlanWithFirst(ctx, c1, s1).dp, grads, c2, s2, P_hat, Q_out, ws_doubles(ctx, workspace), scales_ready,
                                 static_cast<hipStream_t>(hip_stream), stage_span(ctx, 2)));
 }
 }  // namespace
@@ -558,7 +562,8 @@ int conef_i_step(conef_ctx *ctx, const void *grads, uint32_t *err_codes, float *
     if (ctx && ctx->timing) { ctx->slot = (int)(ctx->steps_timed % kTimingSlots); ++ctx->steps_timed; }
     if ((rc = i_step_p_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, Q_state, P_out, workspace, hip_stream)))
         return rc;
-    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream))) return rc;
+    // the second vector's scales go to the first workspace region, the first vector's to the second (as launch_pass_q does)
+    if ((rc = orthonormalise_impl(ctx, P_out, workspace, hip_stream, err2_scales, err_scales))) return rc;
     if ((rc = i_step_q_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, hip_stream, true)))
         return rc;
     return i_step_err_impl(ctx, grads, err_codes, err_scales, err2_codes, err2_scales, P_out, Q_out, workspace, step, hip_stream,

@@ -60,10 +60,13 @@ struct Span {
 // Each launcher enqueues on `st` and returns hipGetLastError().  `ws` is the caller's workspace.
 hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
                          const float *Q, float *P, double *ws, hipStream_t st, Span span = Span());
+// tr_a / tr_b (the full step only): block scales of the error vector(s) whose column-block-major copies are made for
+// the rank-32 family alongside the factorisations (into the first / the second workspace region); launch_pass_q is then
+// called with scales_ready
 hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st,
-                                 Span span = Span());
+                                 Span span = Span(), const float *tr_a = nullptr, const float *tr_b = nullptr);
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, bool fused, hipStream_t st,
+                         const float *Phat, float *Qout, double *ws, bool scales_ready, hipStream_t st,
                          Span span = Span());
 hipError_t launch_pass_err(const DevicePlan &dp, const void *grads, uint32_t *codes, float *scales,
                            const float *Phat, const float *Qn, uint64_t step, double *ws, bool splits_ready,

@@ -602,12 +602,14 @@ hipError_t launch_pass_p(const DevicePlan &dp, const void *grads, const uint32_t
 }
 
 hipError_t launch_pass_q(const DevicePlan &dp, const void *grads, const uint32_t *codes, const float *scales,
-                         const float *Phat, float *Qout, double *ws, bool fused, hipStream_t st, Span span)
+                         const float *Phat, float *Qout, double *ws, bool scales_ready, hipStream_t st, Span span)
 {
-    (void)fused;
     // the matrix-core family reads the block scales of the incoming error state column block by column block
-    mfma_transpose_scales(dp, scales, ws, false, st);
-    if (dp.i_codes) mfma_transpose_scales(dp, dp.i_scales, ws, true, st);     // the first vector of Algorithm 3
+    // (scales_ready: the orthonormalisation's launches have made these copies)
+    if (!scales_ready) {
+        mfma_transpose_scales(dp, scales, ws, false, st);
+        if (dp.i_codes) mfma_transpose_scales(dp, dp.i_scales, ws, true, st);     // the first vector of Algorithm 3
+    }
     if (span.begin) (void)hipEventRecord(span.begin, st);
     mfma_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);
     pack_pass_q(dp, grads, codes, scales, Phat, ws, Qout, st);

@@ -310,33 +310,12 @@ __global__ __launch_bounds__(256) void k_p_mfma(DevicePlan dp, const uint16_t *_
 }
 
 // ------------------------------------------------------------------ splits of P^ and Q+
-// Column-block-major copy of the block scales of a matrix, scT[block of the row][row]: the Q+ and err
-// passes need, per 128-column block, the scales of consecutive rows, which are a row pitch apart
-// (a 128-byte line each) in the state's own row-major order.  One workgroup per 64 rows.
-// (second: into the region kept for the other error vector of Algorithm 3)
+// Column-block-major copy of the block scales (transpose_scales_tile), one workgroup per 64 rows.  The full step does
+// this inside the orthonormalisation's launches instead; this kernel serves the stage calls.
 __global__ __launch_bounds__(256) void k_transpose_scales(DevicePlan dp, const float *__restrict__ scales, double *ws, int second)
 {
     __shared__ float tile[64 * 33];
-    const WorkItem it = dp.split_p_items[blockIdx.x];
-    const MatDesc d = dp.mats[it.mat];
-    const int64_t row0 = (int64_t)it.a * 64;
-    const int nblk_row = (int)(d.m >> 7), tid = threadIdx.x;
-    const float *src = scales + d.scale_off;
-    float *dst = reinterpret_cast<float *>(ws + (second ? d.scT2_off : d.scT_off));
-    for (int b0 = 0; b0 < nblk_row; b0 += 32) {
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int idx = tid + 256 * s, rr = idx >> 5, j = idx & 31;
-            tile[rr * 33 + j] = (row0 + rr < d.n && b0 + j < nblk_row) ? src[(row0 + rr) * nblk_row + b0 + j] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int idx = tid + 256 * s, j = idx >> 6, rr = idx & 63;
-            if (row0 + rr < d.n && b0 + j < nblk_row) dst[(int64_t)(b0 + j) * d.n + row0 + rr] = tile[rr * 33 + j];
-        }
-        __syncthreads();
-    }
+    transpose_scales_tile(dp, scales, ws, (int)blockIdx.x, second, tile);
 }
 
 // Q+ (m x 32): splits for the err pass, in the order its matrix-core tiles read them:

@@ -1,16 +1,20 @@
 // Orthonormalisation of all left factors of a model: P^ = thin-QR factor of P with positive
 // diagonal of R, by Cholesky-QR in fp64:  G = P^T P,  G = R^T R,  P^ = P R^-1.  In exact arithmetic
 // this is the matrix Gram-Schmidt produces.  Four grouped launches:
-//   k_gram_partial      fp64 Gram matrices of row tiles (4 x 4 register blocks per thread),
+//   k_gram_partial      fp64 Gram matrices of row tiles (4 x 4 register blocks per thread); at rank 32
+//                       k_gram_mfma32 does the same on the fp64 matrix cores, straight from global memory,
 //   k_gram_reduce       the tiles of a matrix added up: 16 interleaved partial sums per entry, each
 //                       in tile order, then those in order,
 //   k_cholesky_inverse  per matrix: factorisation and inversion of the triangle inside one wave (a
 //                       lane owns a column; rows are broadcast with v_readlane, no LDS traffic and
-//                       no barriers in the O(r^3) part),
+//                       no barriers in the O(r^3) part).  This launch leaves the chip almost empty, so
+//                       the full step hands it the copy of the block scales that the rank-32 family's
+//                       Q+ and err passes read (extra workgroups behind the matrices'),
 //   k_apply_rinv        P^ = P R^-1 on 64-row tiles staged through LDS.
 // All sums run in a fixed order.
 #include "device_common.h"
 #include "kernels.h"
+#include "mfma_common.h"
 
 namespace conef {
 
@@ -102,6 +106,61 @@ __global__ __launch_bounds__(256) void k_gram_partial(DevicePlan dp, const float
     }
 }
 
+// ---------------------------------------------------------------- partial Gram matrices, rank 32, fp64 matrix cores
+// v_mfma_f64_16x16x4_f64 (D 16x16 += A 16x4 * B 4x16): lane l supplies A[l%16][l/16] and B[l/16][l%16] and holds
+// D[l/16 + 4v][l%16], v = 0..3.  With A = (4 rows of P)^T and B = the same 4 rows, a lane's A and B entries are one and the
+// same element of P, so the operands come straight from a coalesced load with no staging: lane l loads the two
+// neighbouring entries 2 (l%16), 2 (l%16) + 1 of row l/16 of the piece; the even columns form one 16-column block, the
+// odd columns the other, and three products per 4 rows give G_ee, G_eo and G_oo (G_oe is G_eo transposed).  Wave w of
+// the workgroup takes the w-th quarter of the tile's rows; the four waves' sums are added in wave order.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void k_gram_mfma32(DevicePlan dp, const float *__restrict__ P, double *ws)
+{
+    __shared__ double red[4][3][256];
+    const WorkItem it = dp.gram_items[blockIdx.x];
+    const MatDesc d = dp.mats[it.mat];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int quarter = d.gram_tile_rows >> 2;                 // a multiple of 32
+    const int64_t w0 = (int64_t)it.a * d.gram_tile_rows + (int64_t)wave * quarter;
+    const float *src = P + d.p_off + 2 * (lane & 15);
+    f64x4 ee = {0.0, 0.0, 0.0, 0.0}, eo = ee, oo = ee;
+    for (int64_t r0 = w0; r0 < w0 + quarter && r0 < d.n; r0 += 32) {
+        float2 v[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int64_t row = r0 + 4 * s + (lane >> 4);
+            v[s] = *reinterpret_cast<const float2 *>(src + ((row < d.n) ? row : d.n - 1) * 32);
+            if (row >= d.n) v[s] = make_float2(0.0f, 0.0f);
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const double e = (double)v[s].x, o = (double)v[s].y;
+            ee = __builtin_amdgcn_mfma_f64_16x16x4f64(e, e, ee, 0, 0, 0);
+            eo = __builtin_amdgcn_mfma_f64_16x16x4f64(e, o, eo, 0, 0, 0);
+            oo = __builtin_amdgcn_mfma_f64_16x16x4f64(o, o, oo, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        red[wave][0][lane * 4 + v] = ee[v];
+        red[wave][1][lane * 4 + v] = eo[v];
+        red[wave][2][lane * 4 + v] = oo[v];
+    }
+    __syncthreads();
+    double *out = ws + d.gram_off + (int64_t)it.a * 1024;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int e = t + 256 * s, a = e >> 5, b = e & 31;
+        // entry (a, b) = block (a%2, b%2) at (a/2, b/2); the odd-even block is the even-odd one transposed
+        const int blk = (a & 1) + (b & 1);                     // 0: ee, 1: eo (or its transpose), 2: oo
+        const bool tr = (a & 1) && !(b & 1);
+        const int i = tr ? (b >> 1) : (a >> 1), j = tr ? (a >> 1) : (b >> 1);
+        const int idx = (16 * (i & 3) + j) * 4 + (i >> 2);     // D[i][j]: lane 16 (i%4) + j, register i/4
+        out[e] = ((red[0][blk][idx] + red[1][blk][idx]) + red[2][blk][idx]) + red[3][blk][idx];
+    }
+}
+
 // ---------------------------------------------------------------- sum of the partial Gram matrices
 // One workgroup per (matrix, 16 entries of the r x r matrix): thread (entry, part) adds the tiles
 // part, part + 16, ... in that order, then the 16 parts are added in order.  (One thread per entry
@@ -138,18 +197,41 @@ __global__ __launch_bounds__(256) void k_gram_reduce(DevicePlan dp, double *ws)
 }
 
 // ---------------------------------------------------------------- Cholesky factor and its inverse
-// One wave per matrix factors G = R^T R and inverts R with lane j holding column j in registers.
-// A column whose squared norm after projection is not above 1e-12 of its squared norm is linearly
-// dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.
+// 1 / sqrt(x) in fp64: the hardware's approximation and two Newton steps (a few units in the last place)
+__device__ __forceinline__ double rsqrt_f64(double x)
+{
+    double y = __builtin_amdgcn_rsq(x);
+    const double h = 0.5 * x;
+    y = __builtin_fma(y, __builtin_fma(-h * y, y, 0.5), y);
+    y = __builtin_fma(y, __builtin_fma(-h * y, y, 0.5), y);
+    return y;
+}
+
+// Workgroups 0 .. n_mats - 1: the first wave of each factors G = R^T R of one matrix and inverts R with lane j holding
+// column j in registers.  A column whose squared norm after projection is not above 1e-12 of its squared norm is
+// linearly dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.  Divisions and square roots are
+// replaced by one reciprocal square root per column.
+// Workgroups behind those (the full step only): the column-block-major copy of the block scales for the rank-32 family
+// (n_tr tiles of tr_a into the first region, then n_tr tiles of tr_b into the second if tr_b is given), which fills
+// the chip while the factorisations run.
 template <int RP>
-__global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *ws)
+__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws, const float *__restrict__ tr_a,
+                                                          const float *__restrict__ tr_b, int n_tr)
 {
     __shared__ double G[RP * RP];
+    __shared__ float tile[64 * 33];
+    if ((int)blockIdx.x >= dp.n_mats) {
+        const int item = (int)blockIdx.x - dp.n_mats;
+        if (item < n_tr) transpose_scales_tile(dp, tr_a, ws, item, 0, tile);
+        else transpose_scales_tile(dp, tr_b, ws, item - n_tr, 1, tile);
+        return;
+    }
     const MatDesc d = dp.mats[blockIdx.x];
     const int r = dp.rank;
     const int t = threadIdx.x;
-    for (int e = t; e < r * r; e += 64) G[(e / r) * RP + (e % r)] = ws[d.gsum_off + e];
+    for (int e = t; e < r * r; e += 256) G[(e / r) * RP + (e % r)] = ws[d.gsum_off + e];
     __syncthreads();
+    if (t >= 64) return;
     const int j = t;                                   // this lane's column (lanes >= r idle along)
     double col[RP];
 #pragma unroll
@@ -158,16 +240,17 @@ __global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *
 #pragma unroll
     for (int i = 0; i < RP; ++i) dg = (i == j) ? col[i] : dg;
     bool dead_j = false;
+    double dinv = 0.0;                                 // 1 / R[j][j]
     // right-looking Cholesky: after step c, col[c] holds R[c][j]
 #pragma unroll
     for (int c = 0; c < RP; ++c) {
         if (c < r) {                                   // uniform
             const double dcc = bcast(col[c], c), gcc = bcast(dg, c);
             const bool dead = !(dcc > 1e-12 * gcc);
-            const double rcc = dead ? 1.0 : sqrt(dcc);
+            const double ri = dead ? 1.0 : rsqrt_f64(dcc);     // 1 / R[c][c]
             double rcj = 0.0;
-            if (j == c) { rcj = rcc; dead_j = dead; }
-            else if (j > c && !dead) rcj = col[c] / rcc;
+            if (j == c) { rcj = dead ? 1.0 : dcc * ri; dead_j = dead; dinv = ri; }
+            else if (j > c && !dead) rcj = col[c] * ri;
             col[c] = rcj;
 #pragma unroll
             for (int i = c + 1; i < RP; ++i)
@@ -175,9 +258,6 @@ __global__ __launch_bounds__(64) void k_cholesky_inverse(DevicePlan dp, double *
         }
     }
     // inverse of the upper triangle: x[i] = (R^-1)[i][j]
-    double dinv = 0.0;                                 // 1 / R[j][j]
-#pragma unroll
-    for (int i = 0; i < RP; ++i) dinv = (i == j) ? 1.0 / col[i] : dinv;
     double x[RP];
 #pragma unroll
     for (int i = 0; i < RP; ++i) x[i] = (i == j && !dead_j) ? dinv : 0.0;
@@ -234,7 +314,14 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     const int64_t row0 = it.a;
     const int rows = (int)((d.n - row0 < 64) ? d.n - row0 : 64);
     float *base = P + d.p_off + row0 * r;
-    if (r == RP) {
+    if (r == RP && rows == 64) {
+        // a whole tile: every load is issued before the first is waited for
+        float v[RP / 4];
+#pragma unroll
+        for (int s = 0; s < RP / 4; ++s) v[s] = base[t + 256 * s];
+#pragma unroll
+        for (int s = 0; s < RP / 4; ++s) tin[((t + 256 * s) / RP) * kS + ((t + 256 * s) % RP)] = v[s];
+    } else if (r == RP) {
         for (int e = t; e < rows * RP; e += 256) tin[(e / RP) * kS + (e % RP)] = base[e];
     } else {
         for (int e = t; e < rows * r; e += 256) tin[(e / r) * kS + (e % r)] = base[e];
@@ -254,7 +341,10 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
         }
     }
     __syncthreads();
-    if (r == RP) {
+    if (r == RP && rows == 64) {
+#pragma unroll
+        for (int s = 0; s < RP / 4; ++s) base[t + 256 * s] = tout[((t + 256 * s) / RP) * kS + ((t + 256 * s) % RP)];
+    } else if (r == RP) {
         for (int e = t; e < rows * RP; e += 256) base[e] = tout[(e / RP) * kS + (e % RP)];
     } else {
         for (int e = t; e < rows * r; e += 256) base[e] = tout[(e / r) * kS + (e % r)];
@@ -273,18 +363,25 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
         }                                                                                         \
     } while (0)
 
-hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span)
+hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hipStream_t st, Span span, const float *tr_a,
+                                 const float *tr_b)
 {
     // the span covers all kernels of this stage
     if (span.begin) (void)hipEventRecord(span.begin, st);
-    CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), 256, st, dp, (const float *)P, ws);
+    if (dp.rpad == 32 && dp.rank == 32)
+        hipLaunchKernelGGL(k_gram_mfma32, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws);
+    else
+        CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), 256, st, dp, (const float *)P, ws);
     switch (dp.rpad) {
     case 4: hipLaunchKernelGGL(k_gram_reduce<4>, dim3(dp.n_mats), dim3(256), 0, st, dp, ws); break;
     case 8: hipLaunchKernelGGL(k_gram_reduce<8>, dim3(dp.n_mats * 4), dim3(256), 0, st, dp, ws); break;
     case 16: hipLaunchKernelGGL(k_gram_reduce<16>, dim3(dp.n_mats * 16), dim3(256), 0, st, dp, ws); break;
     default: hipLaunchKernelGGL(k_gram_reduce<32>, dim3(dp.n_mats * 64), dim3(256), 0, st, dp, ws); break;
     }
-    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats), 64, st, dp, ws);
+    // tr_a / tr_b: block scales whose column-block-major copies the rank-32 family's later passes read
+    const int n_tr = tr_a ? dp.n_split_p : 0;
+    const int n_extra = n_tr * (tr_b ? 2 : 1);
+    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats + n_extra), 256, st, dp, ws, tr_a, tr_b, n_tr);
     CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), 256, st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();

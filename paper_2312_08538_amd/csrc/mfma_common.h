@@ -7,6 +7,7 @@
 #pragma once
 
 #include "device_common.h"
+#include "kernels.h"
 
 namespace conef {
 
@@ -86,6 +87,35 @@ __device__ __forceinline__ uint4 fields2_bf16(uint32_t h)
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[e] = (float)((int32_t)(h << (30 - 2 * e)) >> 30);
     return make_uint4(pack_hi16(q[0], q[1]), pack_hi16(q[2], q[3]), pack_hi16(q[4], q[5]), pack_hi16(q[6], q[7]));
+}
+
+// Column-block-major copy of the block scales of 64 rows of a matrix of the rank-32 family, scT[block of the row][row]:
+// the Q+ and err passes need, per 128-column block, the scales of consecutive rows, which are a row pitch apart (a
+// 128-byte line each) in the state's own row-major order.  For one workgroup of 256 threads; `tile` is 64 x 33 floats
+// of LDS.  (second: into the region kept for the other error vector of Algorithm 3)
+__device__ __forceinline__ void transpose_scales_tile(const DevicePlan &dp, const float *__restrict__ scales, double *ws,
+                                                      int item, int second, float *tile)
+{
+    const WorkItem it = dp.split_p_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int64_t row0 = (int64_t)it.a * 64;
+    const int nblk_row = (int)(d.m >> 7), tid = threadIdx.x;
+    const float *src = scales + d.scale_off;
+    float *dst = reinterpret_cast<float *>(ws + (second ? d.scT2_off : d.scT_off));
+    for (int b0 = 0; b0 < nblk_row; b0 += 32) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int idx = tid + 256 * s, rr = idx >> 5, j = idx & 31;
+            tile[rr * 33 + j] = (row0 + rr < d.n && b0 + j < nblk_row) ? src[(row0 + rr) * nblk_row + b0 + j] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int idx = tid + 256 * s, j = idx >> 6, rr = idx & 63;
+            if (row0 + rr < d.n && b0 + j < nblk_row) dst[(int64_t)(b0 + j) * d.n + row0 + rr] = tile[rr * 33 + j];
+        }
+        __syncthreads();
+    }
 }
 
 }  // namespace conef
