@@ -416,14 +416,50 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     // go to LDS in operand order with one 16-byte store each and come back with one 16-byte load
     const int fc = tid & 31, frg = tid >> 5;
     const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
-    auto load_factor = [&](float (&pf)[8], int64_t i0) {
+    // Loads of a chunk that lies whole inside the tile: a scalar base per array (the chunk's first row, the column
+    // block) plus a 32-bit lane offset that never changes; rows 16 s further down and the 8 rows of a factor role are
+    // reached through the scalar base and the instruction's immediate offset, so no address is computed per lane.
+    const uint32_t foff = (uint32_t)((8 * frg) * 32 + fc) * 4u;                 // P^: rows 8 frg + j, column fc
+    const uint32_t soff = (uint32_t)(8 * frg) * 4u;                             // scales of rows 8 frg + j
+    const uint32_t goff = ((uint32_t)grow * (uint32_t)m + (uint32_t)goct * 8u) * 2u;    // gradient octet of row grow
+    const uint32_t woff = ((uint32_t)grow * (uint32_t)(m >> 3) + (uint32_t)goct) * 4u;  // code word of row grow
+    auto load_factor_whole = [&](float (&pf)[8], int64_t i0) {
+        const char *pb = reinterpret_cast<const char *>(ph + i0 * 32) + foff;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pf[j] = *reinterpret_cast<const float *>(pb + j * 128);
+    };
+    auto load_factor_clamped = [&](float (&pf)[8], int64_t i0) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : row1 - 1;
             pf[j] = ph[row * 32 + fc];
         }
     };
-    auto load_chunk = [&](ChunkRegs &r, int64_t i0, int cb) {
+    auto load_chunk_whole = [&](ChunkRegs &r, int64_t i0, int cb) {
+        if (CODES) {
+            const char *sb = reinterpret_cast<const char *>(scT + (int64_t)cb * d.n + i0) + soff;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) r.sc[j] = *reinterpret_cast<const float *>(sb + j * 4);
+        }
+        const int64_t e0 = i0 * m + cb * 128;                                   // uniform
+        if (GRAD) {
+            const char *gb = reinterpret_cast<const char *>(g + e0);
+            const int64_t pitch16 = (int64_t)m * 32;                            // bytes of 16 rows
+            r.g0 = *reinterpret_cast<const u32x4 *>(gb + goff);
+            r.g1 = *reinterpret_cast<const u32x4 *>(gb + pitch16 + goff);
+            r.g2 = *reinterpret_cast<const u32x4 *>(gb + 2 * pitch16 + goff);
+            r.g3 = *reinterpret_cast<const u32x4 *>(gb + 3 * pitch16 + goff);
+        }
+        if (CODES) {
+            const char *wb = reinterpret_cast<const char *>(cw + (e0 >> 3));
+            const int64_t pitch16 = (int64_t)m * 8;                             // bytes of 16 rows of code words
+            r.cw0 = *reinterpret_cast<const uint32_t *>(wb + woff);
+            r.cw1 = *reinterpret_cast<const uint32_t *>(wb + pitch16 + woff);
+            r.cw2 = *reinterpret_cast<const uint32_t *>(wb + 2 * pitch16 + woff);
+            r.cw3 = *reinterpret_cast<const uint32_t *>(wb + 3 * pitch16 + woff);
+        }
+    };
+    auto load_chunk_clamped = [&](ChunkRegs &r, int64_t i0, int cb) {
         const int64_t last = row1 - 1;
         if (CODES) {
 #pragma unroll
@@ -511,7 +547,8 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
-            const float dstep = (r.sc[j] * inv_levels(4) * dp.omb) * 16.0f;
+            // (the product with 16 is exact, so it can be taken with the constant: fl(fl(s c) omb) 16 = fl(fl(s 16 c) omb))
+            const float dstep = (r.sc[j] * (inv_levels(4) * 16.0f)) * dp.omb;
             dp8[j] = dstep * pv[j];                      // pv is zero for rows beyond the tile
         }
         store_split(sd, dp8);
@@ -558,28 +595,42 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         __builtin_amdgcn_s_setprio(2);
     };
 
-    // One chunk per trip: block A, then block B with the same rows of P^.
+    // One chunk per trip: block A, then block B with the same rows of P^.  A trip loads the chunk after its own:
+    // whole-chunk loads as long as that chunk lies inside the tile, clamped ones in the last trips (a chunk cut off
+    // by the tile's end; beyond it, rows that clamp to the tile's last row and are not used).  The two kinds of trip
+    // are separate loops, so that no load sits behind a branch.
     ChunkRegs ra, rb;
     float np[8];                        // the next chunk's entries of P^
-    load_factor(np, row0);
-    load_chunk(ra, row0, cbA);
-    load_chunk(rb, row0, cbB);
-    for (int64_t i0 = row0; i0 < row1; i0 += kQRows) {
+    if (row0 + kQRows <= row1) {
+        load_factor_whole(np, row0);
+        load_chunk_whole(ra, row0, cbA);
+        load_chunk_whole(rb, row0, cbB);
+    } else {
+        load_factor_clamped(np, row0);
+        load_chunk_clamped(ra, row0, cbA);
+        load_chunk_clamped(rb, row0, cbB);
+    }
+    auto trip = [&](int64_t i0, auto whole) {
+        constexpr bool W = decltype(whole)::value;
         float pv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pv[j] = (i0 + 8 * frg + j < row1) ? np[j] : 0.0f;
+        for (int j = 0; j < 8; ++j) pv[j] = (W || i0 + 8 * frg + j < row1) ? np[j] : 0.0f;
         __syncthreads();                // everybody is done reading the previous block-chunk
         store_chunk(ra, pv, true);
         __syncthreads();
-        load_factor(np, i0 + kQRows);
-        load_chunk(ra, i0 + kQRows, cbA);
+        if (W) { load_factor_whole(np, i0 + kQRows); load_chunk_whole(ra, i0 + kQRows, cbA); }
+        else { load_factor_clamped(np, i0 + kQRows); load_chunk_clamped(ra, i0 + kQRows, cbA); }
         compute_chunk(accA);
         __syncthreads();
         store_chunk(rb, pv, false);
         __syncthreads();
-        load_chunk(rb, i0 + kQRows, cbB);
+        if (W) load_chunk_whole(rb, i0 + kQRows, cbB);
+        else load_chunk_clamped(rb, i0 + kQRows, cbB);
         compute_chunk(accB);
-    }
+    };
+    int64_t i0 = row0;
+    for (; i0 + 2 * kQRows <= row1; i0 += kQRows) trip(i0, std::true_type());       // this chunk and the next are whole
+    for (; i0 < row1; i0 += kQRows) trip(i0, std::false_type());
     // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
     auto write_block = [&](const double (&acc64)[16], int cb) {
         const int kcol = cb * 128 + 32 * wave + r32;
