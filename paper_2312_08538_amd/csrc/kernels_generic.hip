@@ -38,12 +38,19 @@ __device__ __forceinline__ float form_p(const DevicePlan &dp, const MatDesc &d, 
     return __builtin_fmaf(scales[d.scale_off + j / dp.block] * inv_levels(dp.bits), (float)q, inner);
 }
 
-// Sum of T values src[0], src[stride], ... added in index order; loads are issued 8 at a time so
-// the chain of additions, not the memory latency, sets the pace.
+// Sum of T values src[0], src[stride], ... added in index order; loads are issued 32 (then 8) at a time so
+// the chain of additions, not the memory latency, sets the pace (a tall matrix has about a hundred partial sums).
 __device__ __forceinline__ double ordered_sum(const double *src, int T, int64_t stride)
 {
     double s = 0.0;
     int t = 0;
+    for (; t + 32 <= T; t += 32) {
+        double v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = src[(int64_t)(t + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) s += v[u];
+    }
     for (; t + 8 <= T; t += 8) {
         double v[8];
 #pragma unroll

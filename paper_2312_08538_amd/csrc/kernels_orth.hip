@@ -207,32 +207,14 @@ __device__ __forceinline__ double rsqrt_f64(double x)
     return y;
 }
 
-// Workgroups 0 .. n_mats - 1: the first wave of each factors G = R^T R of one matrix and inverts R with lane j holding
-// column j in registers.  A column whose squared norm after projection is not above 1e-12 of its squared norm is
-// linearly dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.  Divisions and square roots are
-// replaced by one reciprocal square root per column.
-// Workgroups behind those (the full step only): the column-block-major copy of the block scales for the rank-32 family
-// (n_tr tiles of tr_a into the first region, then n_tr tiles of tr_b into the second if tr_b is given), which fills
-// the chip while the factorisations run.
+// One wave factors G = R^T R of one matrix and inverts R with lane j holding column j in registers (G: the r x r Gram
+// matrix in LDS with row pitch RP).  A column whose squared norm after projection is not above 1e-12 of its squared
+// norm is linearly dependent on the earlier ones: its column of R^-1 (and so of P^) is zero.  Divisions and square
+// roots are replaced by one reciprocal square root per column.
 template <int RP>
-__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws, const float *__restrict__ tr_a,
-                                                          const float *__restrict__ tr_b, int n_tr)
+__device__ __forceinline__ void cholesky_inverse_wave(const double *G, int r, double *rinv)
 {
-    __shared__ double G[RP * RP];
-    __shared__ float tile[64 * 33];
-    if ((int)blockIdx.x >= dp.n_mats) {
-        const int item = (int)blockIdx.x - dp.n_mats;
-        if (item < n_tr) transpose_scales_tile(dp, tr_a, ws, item, 0, tile);
-        else transpose_scales_tile(dp, tr_b, ws, item - n_tr, 1, tile);
-        return;
-    }
-    const MatDesc d = dp.mats[blockIdx.x];
-    const int r = dp.rank;
-    const int t = threadIdx.x;
-    for (int e = t; e < r * r; e += 256) G[(e / r) * RP + (e % r)] = ws[d.gsum_off + e];
-    __syncthreads();
-    if (t >= 64) return;
-    const int j = t;                                   // this lane's column (lanes >= r idle along)
+    const int j = threadIdx.x;                         // this lane's column (lanes >= r idle along)
     double col[RP];
 #pragma unroll
     for (int i = 0; i < RP; ++i) col[i] = (i < r && j < r) ? G[i * RP + j] : 0.0;
@@ -272,12 +254,74 @@ __global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double 
             if (i < j && !dead_j) x[i] = -s * di;
         }
     }
-    double *rinv = ws + d.rinv_off;
     if (j < r) {
 #pragma unroll
         for (int i = 0; i < RP; ++i)
             if (i < r) rinv[i * r + j] = x[i];
     }
+}
+
+// Workgroups 0 .. n_mats - 1: the factorisation of one matrix each (first wave).  Workgroups behind those (the full
+// step only): the column-block-major copy of the block scales for the rank-32 family (n_tr tiles of tr_a into the
+// first region, then n_tr tiles of tr_b into the second if tr_b is given), which fills the chip while the
+// factorisations run.
+template <int RP>
+__global__ __launch_bounds__(256) void k_cholesky_inverse(DevicePlan dp, double *ws, const float *__restrict__ tr_a,
+                                                          const float *__restrict__ tr_b, int n_tr)
+{
+    __shared__ double G[RP * RP];
+    __shared__ float tile[64 * 33];
+    if ((int)blockIdx.x >= dp.n_mats) {
+        const int item = (int)blockIdx.x - dp.n_mats;
+        if (item < n_tr) transpose_scales_tile(dp, tr_a, ws, item, 0, tile);
+        else transpose_scales_tile(dp, tr_b, ws, item - n_tr, 1, tile);
+        return;
+    }
+    const MatDesc d = dp.mats[blockIdx.x];
+    const int r = dp.rank;
+    const int t = threadIdx.x;
+    for (int e = t; e < r * r; e += 256) G[(e / r) * RP + (e % r)] = ws[d.gsum_off + e];
+    __syncthreads();
+    if (t >= 64) return;
+    cholesky_inverse_wave<RP>(G, r, ws + d.rinv_off);
+}
+
+// Ranks up to 8: the sum of a matrix's partial Gram matrices (as k_gram_reduce adds them: thread (entry, part) adds
+// the tiles part, part + 16, ... in that order, then the 16 parts are added in order) and the factorisation in one
+// launch, one workgroup of 16 threads per entry per matrix.
+template <int RP>
+__global__ __launch_bounds__(16 * RP * RP) void k_gram_sum_cholesky(DevicePlan dp, double *ws)
+{
+    __shared__ double red[16][RP * RP];
+    __shared__ double G[RP * RP];
+    const MatDesc d = dp.mats[blockIdx.x];
+    const int r = dp.rank, t = threadIdx.x;
+    // thread = (slice of 16 entries, part, entry of the slice), the roles of k_gram_reduce's workgroups and threads
+    const int e = (t >> 8) * 16 + (t & 15), part = (t >> 4) & 15;
+    const bool live = e < r * r;
+    const int64_t stride = (int64_t)r * r;
+    const double *src = ws + d.gram_off + (live ? e : 0);
+    const int T = d.n_gram_tiles;
+    double s = 0.0;
+    int k = part;
+    for (; k + 48 < T; k += 64) {
+        const double v0 = src[(int64_t)k * stride], v1 = src[(int64_t)(k + 16) * stride];
+        const double v2 = src[(int64_t)(k + 32) * stride], v3 = src[(int64_t)(k + 48) * stride];
+        s = ((s + v0) + v1) + v2;
+        s += v3;
+    }
+    for (; k < T; k += 16) s += src[(int64_t)k * stride];
+    red[part][e < RP * RP ? e : 0] = (e < RP * RP) ? s : 0.0;
+    __syncthreads();
+    if (part == 0 && live) {
+        double a = red[0][e];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) a += red[q][e];
+        G[(e / r) * RP + (e % r)] = a;
+    }
+    __syncthreads();
+    if (t >= 64) return;
+    cholesky_inverse_wave<RP>(G, r, ws + d.rinv_off);
 }
 
 // ---------------------------------------------------------------- P^ = P R^-1
@@ -372,16 +416,21 @@ hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hip
         hipLaunchKernelGGL(k_gram_mfma32, dim3(dp.n_gram), dim3(256), 0, st, dp, (const float *)P, ws);
     else
         CONEF_ORTH_DISPATCH(k_gram_partial, dim3(dp.n_gram), 256, st, dp, (const float *)P, ws);
-    switch (dp.rpad) {
-    case 4: hipLaunchKernelGGL(k_gram_reduce<4>, dim3(dp.n_mats), dim3(256), 0, st, dp, ws); break;
-    case 8: hipLaunchKernelGGL(k_gram_reduce<8>, dim3(dp.n_mats * 4), dim3(256), 0, st, dp, ws); break;
-    case 16: hipLaunchKernelGGL(k_gram_reduce<16>, dim3(dp.n_mats * 16), dim3(256), 0, st, dp, ws); break;
-    default: hipLaunchKernelGGL(k_gram_reduce<32>, dim3(dp.n_mats * 64), dim3(256), 0, st, dp, ws); break;
-    }
     // tr_a / tr_b: block scales whose column-block-major copies the rank-32 family's later passes read
     const int n_tr = tr_a ? dp.n_split_p : 0;
     const int n_extra = n_tr * (tr_b ? 2 : 1);
-    CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats + n_extra), 256, st, dp, ws, tr_a, tr_b, n_tr);
+    if (dp.rpad <= 8 && n_extra == 0) {
+        if (dp.rpad == 4) hipLaunchKernelGGL(k_gram_sum_cholesky<4>, dim3(dp.n_mats), dim3(256), 0, st, dp, ws);
+        else hipLaunchKernelGGL(k_gram_sum_cholesky<8>, dim3(dp.n_mats), dim3(1024), 0, st, dp, ws);
+    } else {
+        switch (dp.rpad) {
+        case 4: hipLaunchKernelGGL(k_gram_reduce<4>, dim3(dp.n_mats), dim3(256), 0, st, dp, ws); break;
+        case 8: hipLaunchKernelGGL(k_gram_reduce<8>, dim3(dp.n_mats * 4), dim3(256), 0, st, dp, ws); break;
+        case 16: hipLaunchKernelGGL(k_gram_reduce<16>, dim3(dp.n_mats * 16), dim3(256), 0, st, dp, ws); break;
+        default: hipLaunchKernelGGL(k_gram_reduce<32>, dim3(dp.n_mats * 64), dim3(256), 0, st, dp, ws); break;
+        }
+        CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats + n_extra), 256, st, dp, ws, tr_a, tr_b, n_tr);
+    }
     CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), 256, st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
