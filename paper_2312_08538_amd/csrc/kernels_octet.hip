@@ -160,6 +160,15 @@ __device__ __forceinline__ void store_code_words(const MatDesc &d, uint32_t *cod
     else reinterpret_cast<uint16_t *>(codes + d.word_off)[o] = (uint16_t)w[0];
 }
 
+// the code words of the neighbouring octets o (even) and o + 1 in one store
+template <int BITS>
+__device__ __forceinline__ void store_code_pair(const MatDesc &d, uint32_t *codes, int64_t o, const uint32_t w0[2], const uint32_t w1[2])
+{
+    if (BITS == 8) *reinterpret_cast<uint4 *>(codes + d.word_off + o * 2) = make_uint4(w0[0], w0[1], w1[0], w1[1]);
+    else if (BITS == 4) *reinterpret_cast<uint2 *>(codes + d.word_off + o) = make_uint2(w0[0], w1[0]);
+    else codes[d.word_off + (o >> 1)] = (w0[0] & 0xFFFFu) | (w1[0] << 16);
+}
+
 // max over the 2^lb_shift lanes of a scale block (aligned group of lanes)
 __device__ __forceinline__ float block_max(float a, int lb_shift)
 {
@@ -300,6 +309,8 @@ __global__ __launch_bounds__(256) void k_err_octet(DevicePlan dp, const void *__
 // after eight tiles lane (cc, kg = l / 16) holds rows 4 kg + v, columns 8 cc .. 8 cc + 7: the octets it loads.  The
 // strip's rows of Q+ stay in registers in operand order for the whole item; a trip loads 16 rows of P^ (one or two
 // floats per lane).  A scale block is 2^lb_shift <= 16 lanes of one DPP row (WIDE: the row's 16 lanes, both tiles).
+// WIDE: lane cc takes the neighbouring octets 2 cc and 2 cc + 1 of the strip, one per tile, so that its two gradient
+// loads are adjacent, its code bits are one load and one store, and its block scale is loaded once.
 typedef float tile_f32x4 __attribute__((ext_vector_type(4)));
 
 template <bool BF16, int BITS, int RP, bool WIDE, bool TWO>
@@ -314,12 +325,14 @@ __global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *
     const WorkItem it = dp.err_t_items[item];
     const MatDesc d = dp.mats[it.mat];
     const int cc = lane & 15, kg = lane >> 4;
-    const int oc0 = it.a * 16 * NT + cc;                    // the lane's octet column in tile 0 (tile 1: + 16)
+    // the lane's octet column in tile h: octet cc of the strip, or (WIDE) the neighbours 2 cc and 2 cc + 1
+    const int oc0 = it.a * 16 * NT + (WIDE ? 2 * cc : cc);
+    auto oct_col = [&](int h) { return oc0 + h; };
     const int row_end = it.b + it.c;
     const float s_f = (float)((1 << (BITS - 1)) - 1);
     const int lb = WIDE ? 4 : d.lb_shift;                   // lanes of one DPP row that share a scale block
 
-    // B operand: Q+[column 8 (oc0 + 16 h) + t][4 q + kg].  It does not change over the strip's rows: in registers, or, for
+    // B operand: Q+[column 8 oct_col(h) + t][4 q + kg].  It does not change over the strip's rows: in registers, or, for
     // the wide strips, whose two tiles need the registers for a second set of inputs, in LDS of the wave's own (one entry
     // per lane and operand: conflict-free 4-byte reads, no barrier: a lane reads back what it wrote)
     __shared__ float s_bq[WIDE ? 4 * NT * 8 * NQ * 64 : 1];
@@ -331,7 +344,7 @@ __global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *
         for (int t = 0; t < 8; ++t)
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                const float v = Qn[d.q_off + ((int64_t)(oc0 + 16 * h) * 8 + t) * RP + 4 * q + kg];
+                const float v = Qn[d.q_off + ((int64_t)oct_col(h) * 8 + t) * RP + 4 * q + kg];
                 if (WIDE) my_bq[((h * 8 + t) * NQ + q) * 64] = v;
                 else bq[h][t][q] = v;
             }
@@ -349,11 +362,38 @@ __global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = r0 + 4 * kg + v < row_end ? r0 + 4 * kg + v : row_end - 1;
+            if (WIDE) {
+                // both octets at once: o is even
+                const int64_t o = (int64_t)row * d.m8 + oc0;
+                const uint32_t *cw = (TWO ? codes_first : codes) + d.word_off;
+                RawOctet<BF16, BITS> &a0 = in.o[0][v], &a1 = in.o[NT - 1][v];
+                a0.g1 = a1.g1 = make_uint4(0, 0, 0, 0); a0.c1 = a1.c1 = 0;
+                if (BF16) {
+                    const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(grads) + d.grad_off + o * 8);
+                    a0.g0 = gp[0]; a1.g0 = gp[1];
+                } else {
+                    const uint4 *gp = reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(grads) + d.grad_off + o * 8);
+                    a0.g0 = gp[0]; a0.g1 = gp[1]; a1.g0 = gp[2]; a1.g1 = gp[3];
+                }
+                if (BITS == 8) {
+                    const uint4 c = *reinterpret_cast<const uint4 *>(cw + o * 2);
+                    a0.c0 = c.x; a0.c1 = c.y; a1.c0 = c.z; a1.c1 = c.w;
+                } else if (BITS == 4) {
+                    const uint2 c = *reinterpret_cast<const uint2 *>(cw + o);
+                    a0.c0 = c.x; a1.c0 = c.y;
+                } else {
+                    const uint32_t c = cw[o >> 1];          // the fields of the first octet are the low half
+                    a0.c0 = c; a1.c0 = c >> 16;
+                }
+                a0.scale = a1.scale = (TWO ? scales_first : scales)[d.scale_off + (o >> d.lb_shift)];
+                if (TWO) {
 #pragma unroll
-            for (int h = 0; h < NT; ++h) {
-                const int64_t o = (int64_t)row * d.m8 + oc0 + 16 * h;
-                in.o[h][v] = load_octet_always<BF16, BITS>(d, grads, TWO ? codes_first : codes, TWO ? scales_first : scales, o);
-                if (TWO) in.o2[TWO ? h : 0][TWO ? v : 0] = load_codes_always<BITS>(d, codes, scales, o);
+                    for (int h = 0; h < NT; ++h) in.o2[TWO ? h : 0][TWO ? v : 0] = load_codes_always<BITS>(d, codes, scales, o + h);
+                }
+            } else {
+                const int64_t o = (int64_t)row * d.m8 + oc0;
+                in.o[0][v] = load_octet_always<BF16, BITS>(d, grads, TWO ? codes_first : codes, TWO ? scales_first : scales, o);
+                if (TWO) in.o2[0][TWO ? v : 0] = load_codes_always<BITS>(d, codes, scales, o);
             }
         }
     };
@@ -393,12 +433,12 @@ __global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *
             uint32_t w[NT][2];
 #pragma unroll
             for (int h = 0; h < NT; ++h) {
-                const int64_t o = (int64_t)rowc * d.m8 + oc0 + 16 * h;
+                const int64_t o = (int64_t)rowc * d.m8 + oct_col(h);
                 uint32_t rnd[4];
                 philox4x32_10((uint32_t)o, (uint32_t)it.mat, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
                 quantise_octet<BITS>(x[h], inv16, rnd, w[h]);
                 if (valid) {
-                    store_code_words<BITS>(d, TWO ? codes_first : codes, o, w[h]);
+                    if (!WIDE) store_code_words<BITS>(d, TWO ? codes_first : codes, o, w[h]);
                     if (h == 0 && (cc & ((1 << lb) - 1)) == 0) (TWO ? scales_first : scales)[d.scale_off + (o >> d.lb_shift)] = a;
                 }
                 if (TWO) {
@@ -410,12 +450,13 @@ __global__ __launch_bounds__(256, 2) void k_err_tile(DevicePlan dp, const void *
                     }
                 }
             }
+            if (WIDE && valid) store_code_pair<BITS>(d, TWO ? codes_first : codes, (int64_t)rowc * d.m8 + oc0, w[0], w[NT - 1]);
             if (TWO) {
                 a2 = block_max(a2, lb);
                 const float inv16_2 = (a2 > 0.0f) ? (s_f / a2) * 65536.0f : 0.0f;
 #pragma unroll
                 for (int h = 0; h < NT; ++h) {
-                    const int64_t o = (int64_t)rowc * d.m8 + oc0 + 16 * h;
+                    const int64_t o = (int64_t)rowc * d.m8 + oct_col(h);
                     uint32_t rnd[4];
                     philox4x32_10((uint32_t)o, (uint32_t)it.mat | 0x80000000u, step_lo, step_hi, dp.seed_lo, dp.seed_hi, rnd);
                     quantise_octet<BITS>(x[h], inv16_2, rnd, w[h]);
