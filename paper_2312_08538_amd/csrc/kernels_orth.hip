@@ -10,7 +10,8 @@
 //                       no barriers in the O(r^3) part).  This launch leaves the chip almost empty, so
 //                       the full step hands it the copy of the block scales that the rank-32 family's
 //                       Q+ and err passes read (extra workgroups behind the matrices'),
-//   k_apply_rinv        P^ = P R^-1 on 64-row tiles staged through LDS.
+//   k_apply_rinv        P^ = P R^-1 on 64-row tiles staged through LDS; at rank 32 k_apply_mfma32 on the fp64
+//                       matrix cores, a wave per 64 rows, straight from and to global memory.
 // All sums run in a fixed order.
 #include "device_common.h"
 #include "kernels.h"
@@ -395,6 +396,64 @@ __global__ __launch_bounds__(256) void k_apply_rinv(DevicePlan dp, float *P, con
     }
 }
 
+// ---------------------------------------------------------------- P^ = P R^-1, rank 32, fp64 matrix cores
+// One wave per 64 rows, no LDS and no barriers.  D (16 x 16) += A (16 x 4) * B (4 x 16) with A from (R^-1)^T and B from
+// P^T; lane l supplies A[l%16][l/16] and B[l/16][l%16] and holds D[l/16 + 4v][l%16].  Which k a lane group supplies in
+// which of the eight steps, and which column of R^-1 a row of A stands for, is free as long as A and B agree, and is
+// chosen so that every access is a 16-byte piece: in step s lane group kq = l/16 supplies k = 8 kq + s (the lane's eight
+// values of P are two neighbouring 16-byte loads of its row l%16), and row i of A stands for column 4 (i%4) + i/4 of the
+// column block, so that the lane ends up with the four neighbouring entries c = 16 cb + 4 kq + v of its row (one store
+// per column block).  The entries of (R^-1)^T do not depend on the rows and stay in registers.  A wave reads the 16
+// rows of a group completely before it overwrites them (P^ replaces P in place).
+__global__ __launch_bounds__(256) void k_apply_mfma32(DevicePlan dp, float *P, const double *__restrict__ ws)
+{
+    const int lane = threadIdx.x & 63;
+    const int item = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (item >= dp.n_apply) return;
+    const WorkItem it = dp.apply_items[item];
+    const MatDesc d = dp.mats[it.mat];
+    const int jr = lane & 15, kq = lane >> 4;
+    const double *rinv = ws + d.rinv_off;
+    const int ca = 4 * (jr & 3) + (jr >> 2);         // the column (of a block of 16) that row jr of A stands for
+    double a0[8], a1[8];
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) {
+        a0[s8] = rinv[(8 * kq + s8) * 32 + ca];
+        a1[s8] = rinv[(8 * kq + s8) * 32 + 16 + ca];
+    }
+    float *base = P + d.p_off;
+    auto load_group = [&](float4 (&b)[2], int64_t r0) {
+        const int64_t row = (r0 + jr < d.n) ? r0 + jr : d.n - 1;
+        const float4 *src = reinterpret_cast<const float4 *>(base + row * 32 + 8 * kq);
+        b[0] = src[0];
+        b[1] = src[1];
+    };
+    const int64_t row0 = it.a;
+    float4 b[2], nb[2];
+    load_group(b, row0);
+#pragma unroll 1
+    for (int g = 0; g < 4; ++g) {
+        const int64_t r0 = row0 + 16 * g;
+        if (r0 >= d.n) break;                        // uniform
+        load_group(nb, (g < 3 && r0 + 16 < d.n) ? r0 + 16 : r0);      // past the end: a reload that is not used
+        const float bs[8] = {b[0].x, b[0].y, b[0].z, b[0].w, b[1].x, b[1].y, b[1].z, b[1].w};
+        f64x4 d0 = {0.0, 0.0, 0.0, 0.0}, d1 = d0;
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+            const double bv = (double)bs[s8];
+            d0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[s8], bv, d0, 0, 0, 0);
+            d1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[s8], bv, d1, 0, 0, 0);
+        }
+        if (r0 + jr < d.n) {
+            float4 *dst = reinterpret_cast<float4 *>(base + (r0 + jr) * 32 + 4 * kq);
+            dst[0] = make_float4((float)d0[0], (float)d0[1], (float)d0[2], (float)d0[3]);
+            dst[4] = make_float4((float)d1[0], (float)d1[1], (float)d1[2], (float)d1[3]);
+        }
+        b[0] = nb[0];
+        b[1] = nb[1];
+    }
+}
+
 }  // namespace
 
 #define CONEF_ORTH_DISPATCH(KERNEL, GRID, THREADS, ST, ...)                                       \
@@ -431,7 +490,10 @@ hipError_t launch_orthonormalise(const DevicePlan &dp, float *P, double *ws, hip
         }
         CONEF_ORTH_DISPATCH(k_cholesky_inverse, dim3(dp.n_mats + n_extra), 256, st, dp, ws, tr_a, tr_b, n_tr);
     }
-    CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), 256, st, dp, P, (const double *)ws);
+    if (dp.rpad == 32 && dp.rank == 32)
+        hipLaunchKernelGGL(k_apply_mfma32, dim3((dp.n_apply + 3) / 4), dim3(256), 0, st, dp, P, (const double *)ws);
+    else
+        CONEF_ORTH_DISPATCH(k_apply_rinv, dim3(dp.n_apply), 256, st, dp, P, (const double *)ws);
     if (span.end) (void)hipEventRecord(span.end, st);
     return hipGetLastError();
 }
