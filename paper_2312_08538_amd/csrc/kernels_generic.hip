@@ -38,28 +38,26 @@ __device__ __forceinline__ float form_p(const DevicePlan &dp, const MatDesc &d, 
     return __builtin_fmaf(scales[d.scale_off + j / dp.block] * inv_levels(dp.bits), (float)q, inner);
 }
 
-// Sum of T values src[0], src[stride], ... added in index order; loads are issued 32 (then 8) at a time so
-// the chain of additions, not the memory latency, sets the pace (a tall matrix has about a hundred partial sums).
-__device__ __forceinline__ double ordered_sum(const double *src, int T, int64_t stride)
+// Sum of T values src[0], src[stride], ... added in index order; loads are issued 8 (few values) or 32 at a time so
+// the chain of additions, not the memory latency, sets the pace (a tall matrix has up to about a hundred partial
+// sums).  Slots beyond T add 0.0, which changes nothing.
+template <int BATCH>
+__device__ __forceinline__ double ordered_sum_batches(const double *src, int T, int64_t stride)
 {
     double s = 0.0;
-    int t = 0;
-    for (; t + 32 <= T; t += 32) {
-        double v[32];
+    for (int t = 0; t < T; t += BATCH) {
+        double v[BATCH];
 #pragma unroll
-        for (int u = 0; u < 32; ++u) v[u] = src[(int64_t)(t + u) * stride];
+        for (int u = 0; u < BATCH; ++u) v[u] = (t + u < T) ? src[(int64_t)(t + u) * stride] : 0.0;
 #pragma unroll
-        for (int u = 0; u < 32; ++u) s += v[u];
+        for (int u = 0; u < BATCH; ++u) s += v[u];
     }
-    for (; t + 8 <= T; t += 8) {
-        double v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(t + u) * stride];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
-    }
-    for (; t < T; ++t) s += src[(int64_t)t * stride];
     return s;
+}
+
+__device__ __forceinline__ double ordered_sum(const double *src, int T, int64_t stride)
+{
+    return T <= 8 ? ordered_sum_batches<8>(src, T, stride) : ordered_sum_batches<32>(src, T, stride);
 }
 
 // ---------------------------------------------------------------- pass 1: P = p * Q

@@ -340,27 +340,25 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 //     Q+[k,c] = sum_i g[i,k] P^[i,c]  +  sum_i q[i,k] (d_i P^[i,c])
 // Both sums run on v_mfma_f32_32x32x16_bf16 with exact operands: g is bf16, q is a small integer,
 // P^ and the fp32 products d_i P^[i,c] are split into three bf16 parts.  Nothing is decoded or split
-// per element; the step sizes enter through 32 products per row (the workgroup's 128 columns are
-// one scale block).
+// per element; the step sizes enter through 32 products per row and scale block.
 //
-// One workgroup per (128-column block, row tile); wave w owns columns 32w..32w+31 of the block.
-// Rows are walked in chunks of 64.  The contraction runs over rows, so the matrix operand B[i][k]
-// needs, per lane, 8 rows of ONE column: the raw gradient rows and the codes (as bf16 integers) go
-// row-major into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16
-// (within 16 lanes: lane i supplies the address of 4 consecutive columns of row i / 4, chunk i % 4;
-// lane n receives column n of those 4 rows).  The splits of P^ and of d_i P^ are made once per chunk
-// by the whole workgroup from the fp32 entries of P^: a thread takes 8 rows of one column, which is
-// what one lane of a matrix-core operand holds, so the splits are stored in operand order (one
-// 16-byte store each) and read back with one 16-byte load per operand.  The only factor data a chunk
-// fetches are 8 KB of P^ and its 64 block scales (from the column-block-major copy of the scales).
-// What a wave can get out of the LDS is bounded by the number of its LDS instructions (one comes back
-// every ~17 ns, whatever its width), so operands that need no transposing read come as one
-// instruction, not two.  Everything a workgroup loads passes through the L2,
-// whose bandwidth bounds this pass: tables of ready-made splits would cost more of it than the
-// splitting costs in arithmetic.  fp32 sums of the matrix cores cover one chunk; chunks are added
-// in fp64.
-constexpr int kQRows = 64;                  // rows per chunk
-constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / code tiles: 320 bytes, conflict-free transposing reads
+// One workgroup per (pair of neighbouring 128-column blocks, row tile), walking the rows in chunks of 32: a chunk
+// is 32 rows x 256 columns (512 contiguous bytes of gradient and one 128-byte line of codes per row).  Waves 0 and 1
+// take the first block of the pair, waves 2 and 3 the second; each wave owns 64 columns, two matrix-core tiles, so
+// that a factor operand read from LDS serves two products.  The contraction runs over rows, so the matrix operand
+// B[i][k] needs, per lane, 8 rows of ONE column: the raw gradient rows and the codes (as bf16 integers) go row-major
+// into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16 (within 16 lanes: lane i supplies
+// the address of 4 consecutive columns of row i / 4, chunk i % 4; lane n receives column n of those 4 rows).  The
+// splits of P^ (once for both blocks) and of d_i P^ (per block: the step sizes differ) are made once per chunk by the
+// whole workgroup from the fp32 entries of P^: a thread takes 8 rows of one column, which is what one lane of a
+// matrix-core operand holds, so the splits are stored in operand order and read back with one 16-byte load per
+// operand.  The only factor data a chunk fetches are 4 KB of P^ and its 64 block scales (from the column-block-major
+// copy of the scales).  What limits the pass on the chip is the LDS: the fewer bytes a product reads from it, the
+// better.  Everything a workgroup loads passes through the L2: tables of ready-made splits would cost more of its
+// bandwidth than the splitting costs in arithmetic.  fp32 sums of the matrix cores cover two chunks (64 rows); beyond
+// that the sums are fp64.
+constexpr int kQRows = 32;                  // rows per chunk
+constexpr int kTPitch = 256 + 32;           // bf16 per row of the gradient / code tiles: 576 bytes, conflict-free transposing reads
 
 // MODE 0: Q+ = (g + e)^T P^, the quantiser's step.
 // MODE 1: the contribution of a compressed vector alone (no gradient; its scales in the second column-block-major
@@ -370,7 +368,7 @@ constexpr int kTPitch = 128 + 32;           // bf16 per row of the gradient / co
 // 3: the table's share (1 - beta) S^T U over the table's rows (two operand tiles per entry, see the P pass), U from the
 // workspace; its row tiles follow the gradient's in the partial sums, which the reduction kernel adds in order.
 template <int MODE>
-__global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
+__global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
                                                 const uint32_t *__restrict__ codes, const float *__restrict__ scales,
                                                 const float *__restrict__ Phat, double *ws, float *Qout)
 {
@@ -378,19 +376,17 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     constexpr bool CODES = MODE == kPModeStep || MODE == kPModeCodes, TABLE = MODE == kPModeTable;
     __shared__ __attribute__((aligned(16))) uint16_t tg[kQRows * kTPitch];      // gradient rows, raw bf16
     __shared__ __attribute__((aligned(16))) uint16_t tq[kQRows * kTPitch];      // codes as bf16 integers
-    __shared__ __attribute__((aligned(16))) uint16_t sb[3 * kQRows * 32];       // splits of P^, [split][row][c]
-    __shared__ __attribute__((aligned(16))) uint16_t sd[3 * kQRows * 32];       // splits of d_i P^, [split][row][c]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) uint16_t sb[3 * kQRows * 32];       // splits of P^, [split][16 rows][lane] x 8
+    __shared__ __attribute__((aligned(16))) uint16_t sd[2 * 3 * kQRows * 32];   // splits of d_i P^ of the two blocks
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const WorkItem it = TABLE ? dp.cs_qt_items[blockIdx.x] : dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
     MatDesc d = dp.mats[it.mat];
     if (MODE == kPModeGrad && !d.cs_lin) return;     // (a count-sketch plan may hold matrices of both forms)
     if (TABLE) d.n = d.w;                            // the rows walked are the table's
     const int m = (int)d.m;
-    // The item is a PAIR of neighbouring column blocks, A = 2 it.a and B = A + 1, worked on in turn
-    // chunk by chunk: the chunk's rows of P^ are fetched and split once for both (the splits of d_i P^
-    // differ, the step sizes are per block), and the two halves of the rows' code lines (128 columns
-    // of 4-bit codes are 64 bytes) are fetched close together in time.  A matrix with an odd number of
-    // blocks ends with a pair whose B does not exist: it re-reads A and is not written.
+    // The item is a PAIR of neighbouring column blocks, A = 2 it.a and B = A + 1.  A matrix with an odd number of
+    // blocks ends with a pair whose B does not exist: its half of the chunk re-reads A and is not written.
     const int cbA = 2 * it.a, nblk_row = m >> 7;
     const bool has_b = cbA + 1 < nblk_row;
     const int cbB = has_b ? cbA + 1 : cbA;
@@ -401,93 +397,81 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
     const float *scT = reinterpret_cast<const float *>(ws + (GRAD ? d.scT_off : d.scT2_off));       // [block][row]
     const float *ph = TABLE ? reinterpret_cast<const float *>(ws + d.cs_u_off) : Phat + d.p_off;
 
-    // A block-chunk's loads are held in registers until its turn in LDS; two are in flight (block A and
-    // block B of a chunk, or B and the next chunk's A).  Every load is unconditional (rows at or beyond
-    // the end of the tile re-read its last row and get zero factor operands instead): the waits on one
-    // can then leave the younger one's loads pending.
+    // A chunk's loads are held in registers until its turn in LDS; two chunks are in flight.  Every load is
+    // unconditional (rows at or beyond the end of the tile re-read its last row and get zero factor operands
+    // instead): the waits on one chunk can then leave the younger one's loads pending.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct ChunkRegs {
-        u32x4 g0, g1, g2, g3;
-        uint32_t cw0, cw1, cw2, cw3;
-        float sc[8];
+        u32x4 g0, g1, g2, g3;   // gradient: 16-byte pieces of rows grow + 8 s
+        u32x4 cwq;              // 32 code fields of row crow
+        float sc[8];            // block scales of the rows of the factor role
+        float pf[8];            // P^ of the rows of the factor role
     };
-    // factor roles: column fc of P^ and the 8 rows 8 frg .. 8 frg + 7 of the chunk: exactly what one lane of a
-    // matrix-core operand holds (lane = 32 (frg % 2) + fc of the operand of rows 16 (frg / 2) ..), so the splits
-    // go to LDS in operand order with one 16-byte store each and come back with one 16-byte load
-    const int fc = tid & 31, frg = tid >> 5;
-    const int grow = tid >> 4, goct = tid & 15;     // gradient / code roles: rows grow + 16 s, octet of the block
-    // Loads of a chunk that lies whole inside the tile: a scalar base per array (the chunk's first row, the column
-    // block) plus a 32-bit lane offset that never changes; rows 16 s further down and the 8 rows of a factor role are
-    // reached through the scalar base and the instruction's immediate offset, so no address is computed per lane.
+    // factor roles: column fc of P^ and the 8 rows 8 frg .. 8 frg + 7 of the chunk, for the column block fblk of the
+    // pair: exactly what one lane of a matrix-core operand holds (lane 32 (frg % 2) + fc of the operand of rows
+    // 16 (frg / 2) ..), so the splits go to LDS in operand order.  The splits of P^ itself serve both blocks: the
+    // threads of block 0 make those of rows 8 frg .. + 3, the threads of block 1 those of rows 8 frg + 4 .. + 7.
+    const int fc = tid & 31, frg = (tid >> 5) & 3, fblk = tid >> 7;
+    const int fcb = fblk ? cbB : cbA;
+    // gradient roles: 16-byte piece gpc (0..31) of the chunk's 512-byte rows grow + 8 s; pieces 16.. are block B's
+    const int grow = tid >> 5, gpc = tid & 31;
+    const int gcol = ((gpc < 16) ? cbA : cbB) * 128 + (gpc & 15) * 8;          // first column of the piece
+    // code roles: 16-byte piece (32 fields) cq (0..7) of the 128-byte line of row crow; pieces 4.. are block B's
+    const int crow = tid >> 3, cq = tid & 7;
+    const int ccol = ((cq < 4) ? cbA : cbB) * 128 + (cq & 3) * 32;
+    // Loads of a chunk that lies whole inside the tile: a scalar base per array (the chunk's first row) plus a 32-bit
+    // lane offset that never changes; rows 8 s further down and the 8 rows of a factor role are reached through the
+    // scalar base and the instruction's immediate offset, so no address is computed per lane.
     const uint32_t foff = (uint32_t)((8 * frg) * 32 + fc) * 4u;                 // P^: rows 8 frg + j, column fc
     const uint32_t soff = (uint32_t)(8 * frg) * 4u;                             // scales of rows 8 frg + j
-    const uint32_t goff = ((uint32_t)grow * (uint32_t)m + (uint32_t)goct * 8u) * 2u;    // gradient octet of row grow
-    const uint32_t woff = ((uint32_t)grow * (uint32_t)(m >> 3) + (uint32_t)goct) * 4u;  // code word of row grow
-    auto load_factor_whole = [&](float (&pf)[8], int64_t i0) {
+    const uint32_t goff = ((uint32_t)grow * (uint32_t)m + (uint32_t)gcol) * 2u;
+    const uint32_t woff = (((uint32_t)crow * (uint32_t)m + (uint32_t)ccol) >> 3) * 4u;
+    auto load_chunk_whole = [&](ChunkRegs &r, int64_t i0) {
         const char *pb = reinterpret_cast<const char *>(ph + i0 * 32) + foff;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) pf[j] = *reinterpret_cast<const float *>(pb + j * 128);
-    };
-    auto load_factor_clamped = [&](float (&pf)[8], int64_t i0) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : row1 - 1;
-            pf[j] = ph[row * 32 + fc];
-        }
-    };
-    auto load_chunk_whole = [&](ChunkRegs &r, int64_t i0, int cb) {
+        for (int j = 0; j < 8; ++j) r.pf[j] = *reinterpret_cast<const float *>(pb + j * 128);
         if (CODES) {
-            const char *sb = reinterpret_cast<const char *>(scT + (int64_t)cb * d.n + i0) + soff;
+            const char *sb8 = reinterpret_cast<const char *>(scT + (int64_t)fcb * d.n + i0) + soff;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) r.sc[j] = *reinterpret_cast<const float *>(sb + j * 4);
+            for (int j = 0; j < 8; ++j) r.sc[j] = *reinterpret_cast<const float *>(sb8 + j * 4);
         }
-        const int64_t e0 = i0 * m + cb * 128;                                   // uniform
+        const int64_t e0 = i0 * m;                                              // uniform
         if (GRAD) {
             const char *gb = reinterpret_cast<const char *>(g + e0);
-            const int64_t pitch16 = (int64_t)m * 32;                            // bytes of 16 rows
+            const int64_t pitch8 = (int64_t)m * 16;                             // bytes of 8 rows
             r.g0 = *reinterpret_cast<const u32x4 *>(gb + goff);
-            r.g1 = *reinterpret_cast<const u32x4 *>(gb + pitch16 + goff);
-            r.g2 = *reinterpret_cast<const u32x4 *>(gb + 2 * pitch16 + goff);
-            r.g3 = *reinterpret_cast<const u32x4 *>(gb + 3 * pitch16 + goff);
+            r.g1 = *reinterpret_cast<const u32x4 *>(gb + pitch8 + goff);
+            r.g2 = *reinterpret_cast<const u32x4 *>(gb + 2 * pitch8 + goff);
+            r.g3 = *reinterpret_cast<const u32x4 *>(gb + 3 * pitch8 + goff);
         }
-        if (CODES) {
-            const char *wb = reinterpret_cast<const char *>(cw + (e0 >> 3));
-            const int64_t pitch16 = (int64_t)m * 8;                             // bytes of 16 rows of code words
-            r.cw0 = *reinterpret_cast<const uint32_t *>(wb + woff);
-            r.cw1 = *reinterpret_cast<const uint32_t *>(wb + pitch16 + woff);
-            r.cw2 = *reinterpret_cast<const uint32_t *>(wb + 2 * pitch16 + woff);
-            r.cw3 = *reinterpret_cast<const uint32_t *>(wb + 3 * pitch16 + woff);
-        }
+        if (CODES) r.cwq = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(cw + (e0 >> 3)) + woff);
     };
-    auto load_chunk_clamped = [&](ChunkRegs &r, int64_t i0, int cb) {
+    auto load_chunk_clamped = [&](ChunkRegs &r, int64_t i0) {
         const int64_t last = row1 - 1;
-        if (CODES) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
-                r.sc[j] = scT[(int64_t)cb * d.n + row];
-            }
-        }
-        int64_t e[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int64_t row = (i0 + grow + 16 * s < row1) ? i0 + grow + 16 * s : last;
-            e[s] = row * m + cb * 128;
+        for (int j = 0; j < 8; ++j) {
+            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
+            r.pf[j] = ph[row * 32 + fc];
+            if (CODES) r.sc[j] = scT[(int64_t)fcb * d.n + row];
         }
         if (GRAD) {
-            r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0] + goct * 8);
-            r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1] + goct * 8);
-            r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2] + goct * 8);
-            r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3] + goct * 8);
+            int64_t e[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int64_t row = (i0 + grow + 8 * s < row1) ? i0 + grow + 8 * s : last;
+                e[s] = row * m + gcol;
+            }
+            r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0]);
+            r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1]);
+            r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2]);
+            r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3]);
         }
         if (CODES) {
-            r.cw0 = cw[(e[0] >> 3) + goct];
-            r.cw1 = cw[(e[1] >> 3) + goct];
-            r.cw2 = cw[(e[2] >> 3) + goct];
-            r.cw3 = cw[(e[3] >> 3) + goct];
+            const int64_t row = (i0 + crow < row1) ? i0 + crow : last;
+            r.cwq = *reinterpret_cast<const u32x4 *>(cw + ((row * m + ccol) >> 3));
         }
     };
-    // splits of 8 rows of one column, in operand order: [split][16 rows][lane] x 8 bf16
+    // splits of 8 (or 4: `half`) rows of one column, in operand order: [split][16 rows][lane] x 8 bf16
     auto store_split = [&](uint16_t *o, const float (&x)[8]) {
         float hh[8], mm[8], ll[8];
 #pragma unroll
@@ -500,14 +484,26 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
         *reinterpret_cast<uint4 *>(dst + 2 * kQRows * 32) =
             make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
     };
-    // pv: the thread's 8 entries of its column of P^ (zero for rows at or beyond the end of the tile,
-    // whatever the re-read row holds); with_p: also store the splits of P^ itself (first block of a chunk)
-    auto store_chunk = [&](const ChunkRegs &r, const float (&pv)[8], bool with_p) {
+    auto store_split_half = [&](uint16_t *o, const float (&x)[4], int half) {
+        float hh[4], mm[4], ll[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) split3(x[j], hh[j], mm[j], ll[j]);
+        uint16_t *dst = o + ((frg >> 1) * 64 + (frg & 1) * 32 + fc) * 8 + 4 * half;
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]));
+        *reinterpret_cast<uint2 *>(dst + kQRows * 32) = make_uint2(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]));
+        *reinterpret_cast<uint2 *>(dst + 2 * kQRows * 32) = make_uint2(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]));
+    };
+    // a chunk's registers go to LDS; the factor entries of rows at or beyond the end of the tile count as zero,
+    // whatever the re-read row holds
+    auto store_chunk = [&](const ChunkRegs &r, int64_t i0) {
         const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
-        const uint32_t cs[4] = {r.cw0, r.cw1, r.cw2, r.cw3};
-        if (!CODES) {
+        float pv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pv[j] = (i0 + 8 * frg + j < row1) ? r.pf[j] : 0.0f;
+        if (GRAD) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
+                uint16_t *dg = tg + (grow + 8 * s) * kTPitch + gpc * 8;
                 if (TABLE) {
                     // fp16 -> fp32 (exact) -> upper half (bf16 by truncation) and what is left
                     u32x4 hi, lo;
@@ -518,128 +514,144 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
                         hi[e2] = pack_hi16(h0, h1);
                         lo[e2] = pack_hi16(x0 - h0, x1 - h1);
                     }
-                    *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = hi;
-                    *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = lo;
+                    *reinterpret_cast<u32x4 *>(dg) = hi;
+                    *reinterpret_cast<u32x4 *>(tq + (grow + 8 * s) * kTPitch + gpc * 8) = lo;
                 } else {
-                    *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
+                    *reinterpret_cast<u32x4 *>(dg) = gs[s];
                 }
             }
-            if (with_p) {
-                float pw[8];
+        }
+        if (CODES) {
+            // 32 code fields -> 32 bf16 sixteenths of small integers (exact), four 16-byte pieces
+            uint16_t *dq = tq + crow * kTPitch + ((cq < 4) ? 0 : 128) + (cq & 3) * 32;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) pw[j] = TABLE ? dp.omb * pv[j] : pv[j];
-                store_split(sb, pw);
+            for (int s = 0; s < 4; ++s) {
+                float q16[8];
+                fields_over_16(r.cwq[s], q16);
+                u32x4 qb;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) qb[e2] = pack_hi16(q16[2 * e2], q16[2 * e2 + 1]);
+                *reinterpret_cast<u32x4 *>(dq + 8 * s) = qb;
             }
-            return;
         }
+        // P^ itself: both halves of the workgroup share the work (4 rows each)
+        if (GRAD) {
+            float ph4[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            float q16[8];
-            fields_over_16(cs[s], q16);                  // sixteenths of small integers: exact in bf16
-            u32x4 qb;
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) qb[e2] = pack_hi16(q16[2 * e2], q16[2 * e2 + 1]);
-            if (GRAD) *reinterpret_cast<u32x4 *>(tg + (grow + 16 * s) * kTPitch + goct * 8) = gs[s];
-            *reinterpret_cast<u32x4 *>(tq + (grow + 16 * s) * kTPitch + goct * 8) = qb;
+            for (int j = 0; j < 4; ++j) {
+                const float x = fblk ? pv[4 + j] : pv[j];
+                ph4[j] = TABLE ? dp.omb * x : x;
+            }
+            store_split_half(sb, ph4, fblk);
         }
-        if (GRAD && with_p) store_split(sb, pv);
-        float dp8[8];
+        if (CODES) {
+            float dp8[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
-            // (the product with 16 is exact, so it can be taken with the constant: fl(fl(s c) omb) 16 = fl(fl(s 16 c) omb))
-            const float dstep = (r.sc[j] * (inv_levels(4) * 16.0f)) * dp.omb;
-            dp8[j] = dstep * pv[j];                      // pv is zero for rows beyond the tile
+            for (int j = 0; j < 8; ++j) {
+                // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
+                // (the product with 16 is exact, so it can be taken with the constant: fl(fl(s c) omb) 16 = fl(fl(s 16 c) omb))
+                const float dstep = (r.sc[j] * (inv_levels(4) * 16.0f)) * dp.omb;
+                dp8[j] = dstep * pv[j];                      // pv is zero for rows beyond the tile
+            }
+            store_split(sd + fblk * (3 * kQRows * 32), dp8);
         }
-        store_split(sd, dp8);
     };
 
-    // the matrix cores accumulate one 64-row chunk in fp32; chunks are added up in fp64
-    f32x16 acc;
-    double accA[16], accB[16];
+    // the matrix cores accumulate two chunks (64 rows) in fp32; beyond that the sums are fp64
+    f32x16 acc[2];
+    double acc64[2][16];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { acc[v] = 0.0f; accA[v] = 0.0; accB[v] = 0.0; }
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc[t][v] = 0.0f; acc64[t][v] = 0.0; }
     const int r32 = lane & 31, ig = lane >> 5;
+    const int wblk = wave >> 1, wcol = 128 * wblk + 64 * (wave & 1);     // the wave's block of the pair, its first column in the tiles
     // transposing reads: 16-lane group gq covers columns 16 (gq & 1) .. of the 32-wide operand and
     // rows 8 (gq >> 1) ..; lane li of the group addresses row li / 4, columns 4 (li % 4) ..
     const int gq = lane >> 4, li = lane & 15;
     const int tr_row = 8 * (gq >> 1) + (li >> 2), tr_col = 16 * (gq & 1) + 4 * (li & 3);
-    const int tr_t = tr_row * kTPitch + 32 * wave + tr_col;     // gradient / code tiles
+    const int tr_t = tr_row * kTPitch + wcol + tr_col;     // gradient / code tiles
+    const uint16_t *sdw = sd + wblk * (3 * kQRows * 32);
 
     // Wave priority: the phases that issue loads and fill LDS run at a higher priority than the
     // matrix-core phase, so that the workgroup that is feeding the memory pipeline is not held up by
-    // the other workgroup of the CU, which is computing (measured: 3 % for this pass; the same in the
-    // P pass costs 3 %, and there it is not done).
-    auto compute_chunk = [&](double (&acc64)[16]) {
+    // the other workgroup of the CU, which is computing.
+    auto compute_chunk = [&]() {
         __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int ks = 0; ks < kQRows / 16; ++ks) {
-            Frag bg, bq, aP[3], aD[3];
-            if (GRAD) bg.u = lds_read_tr16x8(tg + tr_t + ks * 16 * kTPitch, kTPitch);
-            if (CODES || TABLE) bq.u = lds_read_tr16x8(tq + tr_t + ks * 16 * kTPitch, kTPitch);
+            Frag aP[3], aD[3];
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
                 if (GRAD) aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
-                if (CODES) aD[s].u = *reinterpret_cast<const uint4 *>(sd + s * kQRows * 32 + (ks * 64 + lane) * 8);
+                if (CODES) aD[s].u = *reinterpret_cast<const uint4 *>(sdw + s * kQRows * 32 + (ks * 64 + lane) * 8);
                 if (TABLE) aD[s].u = aP[s].u;          // both tiles of a table entry meet the same factor
             }
-            if (GRAD) acc = mfma(aP[0], bg, acc);
-            if (CODES || TABLE) acc = mfma(aD[0], bq, acc);
-            if (GRAD) acc = mfma(aP[1], bg, acc);
-            if (CODES || TABLE) acc = mfma(aD[1], bq, acc);
-            if (GRAD) acc = mfma(aP[2], bg, acc);
-            if (CODES || TABLE) acc = mfma(aD[2], bq, acc);
-        }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { acc64[v] += (double)acc[v]; acc[v] = 0.0f; }
+            for (int t = 0; t < 2; ++t) {
+                Frag bg, bq;
+                if (GRAD) bg.u = lds_read_tr16x8(tg + tr_t + 32 * t + ks * 16 * kTPitch, kTPitch);
+                if (CODES || TABLE) bq.u = lds_read_tr16x8(tq + tr_t + 32 * t + ks * 16 * kTPitch, kTPitch);
+                if (GRAD) acc[t] = mfma(aP[0], bg, acc[t]);
+                if (CODES || TABLE) acc[t] = mfma(aD[0], bq, acc[t]);
+                if (GRAD) acc[t] = mfma(aP[1], bg, acc[t]);
+                if (CODES || TABLE) acc[t] = mfma(aD[1], bq, acc[t]);
+                if (GRAD) acc[t] = mfma(aP[2], bg, acc[t]);
+                if (CODES || TABLE) acc[t] = mfma(aD[2], bq, acc[t]);
+            }
+        }
         __builtin_amdgcn_s_setprio(2);
     };
+    auto fold = [&]() {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { acc64[t][v] += (double)acc[t][v]; acc[t][v] = 0.0f; }
+    };
 
-    // One chunk per trip: block A, then block B with the same rows of P^.  A trip loads the chunk after its own:
-    // whole-chunk loads as long as that chunk lies inside the tile, clamped ones in the last trips (a chunk cut off
-    // by the tile's end; beyond it, rows that clamp to the tile's last row and are not used).  The two kinds of trip
-    // are separate loops, so that no load sits behind a branch.
+    // Two chunks per trip, one register set each.  A trip loads the two chunks after its own: whole-chunk loads as
+    // long as those lie inside the tile, clamped ones in the last trips (a chunk cut off by the tile's end; beyond
+    // it, rows that clamp to the tile's last row and are not used).  The two kinds of trip are separate loops, so
+    // that no load sits behind a branch.
     ChunkRegs ra, rb;
-    float np[8];                        // the next chunk's entries of P^
-    if (row0 + kQRows <= row1) {
-        load_factor_whole(np, row0);
-        load_chunk_whole(ra, row0, cbA);
-        load_chunk_whole(rb, row0, cbB);
+    if (row0 + 2 * kQRows <= row1) {
+        load_chunk_whole(ra, row0);
+        load_chunk_whole(rb, row0 + kQRows);
     } else {
-        load_factor_clamped(np, row0);
-        load_chunk_clamped(ra, row0, cbA);
-        load_chunk_clamped(rb, row0, cbB);
+        load_chunk_clamped(ra, row0);
+        load_chunk_clamped(rb, row0 + kQRows);
     }
     auto trip = [&](int64_t i0, auto whole) {
         constexpr bool W = decltype(whole)::value;
-        float pv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) pv[j] = (W || i0 + 8 * frg + j < row1) ? np[j] : 0.0f;
-        __syncthreads();                // everybody is done reading the previous block-chunk
-        store_chunk(ra, pv, true);
+        __syncthreads();                // everybody is done reading the previous chunk
+        store_chunk(ra, i0);
         __syncthreads();
-        if (W) { load_factor_whole(np, i0 + kQRows); load_chunk_whole(ra, i0 + kQRows, cbA); }
-        else { load_factor_clamped(np, i0 + kQRows); load_chunk_clamped(ra, i0 + kQRows, cbA); }
-        compute_chunk(accA);
+        if (W) load_chunk_whole(ra, i0 + 2 * kQRows);
+        else load_chunk_clamped(ra, i0 + 2 * kQRows);
+        compute_chunk();
         __syncthreads();
-        store_chunk(rb, pv, false);
+        store_chunk(rb, i0 + kQRows);
         __syncthreads();
-        if (W) load_chunk_whole(rb, i0 + kQRows, cbB);
-        else load_chunk_clamped(rb, i0 + kQRows, cbB);
-        compute_chunk(accB);
+        if (W) load_chunk_whole(rb, i0 + 3 * kQRows);
+        else load_chunk_clamped(rb, i0 + 3 * kQRows);
+        compute_chunk();
+        fold();
     };
     int64_t i0 = row0;
-    for (; i0 + 2 * kQRows <= row1; i0 += kQRows) trip(i0, std::true_type());       // this chunk and the next are whole
-    for (; i0 < row1; i0 += kQRows) trip(i0, std::false_type());
-    // D[c][k]: lane holds column k = lane % 32 of the wave's 32 and c = 8 (v / 4) + 4 (lane / 32) + v % 4
-    auto write_block = [&](const double (&acc64)[16], int cb) {
-        const int kcol = cb * 128 + 32 * wave + r32;
+    for (; i0 + 4 * kQRows <= row1; i0 += 2 * kQRows) trip(i0, std::true_type());       // these chunks and the next two are whole
+    for (; i0 < row1; i0 += 2 * kQRows) trip(i0, std::false_type());
+    // D[c][k]: lane holds column k = lane % 32 of a tile and c = 8 (v / 4) + 4 (lane / 32) + v % 4
+    if (wblk && !has_b) return;
+    const int cb = wblk ? cbB : cbA;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int kcol = cb * 128 + 64 * (wave & 1) + 32 * t + r32;
         if (!CODES) {
             // linear form of the count sketch: always partial sums, the table's row tiles behind the gradient's
             double *out = ws + d.qpart_off + ((int64_t)((TABLE ? d.cs_q_tiles_g : 0) + it.b) * m + kcol) * 32;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[v];
-            return;
+            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[t][v];
+            continue;
         }
         if (d.n_q_tiles == 1) {
             // the only row tile of this matrix: Q+ and its operand splits are final
@@ -647,7 +659,7 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-                const float x = (float)(ACCUM ? acc64[v] + (double)qo[c] : acc64[v]);
+                const float x = (float)(ACCUM ? acc64[t][v] + (double)qo[c] : acc64[t][v]);
                 qo[c] = x;
                 mfma_store_q_split(d, ws, kcol, c, x);
             }
@@ -657,12 +669,10 @@ __global__ __launch_bounds__(256) void k_q_mfma(DevicePlan dp, const uint16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-                out[c] = ACCUM ? out[c] + acc64[v] : acc64[v];
+                out[c] = ACCUM ? out[c] + acc64[t][v] : acc64[t][v];
             }
         }
-    };
-    write_block(accA, cbA);
-    if (has_b) write_block(accB, cbB);
+    }
 }
 
 // ------------------------------------------------------------------ err pass
