@@ -342,23 +342,47 @@ __global__ __launch_bounds__(256) void k_split_q_new(DevicePlan dp, const float 
 // P^ and the fp32 products d_i P^[i,c] are split into three bf16 parts.  Nothing is decoded or split
 // per element; the step sizes enter through 32 products per row and scale block.
 //
-// One workgroup per (pair of neighbouring 128-column blocks, row tile), walking the rows in chunks of 32: a chunk
-// is 32 rows x 256 columns (512 contiguous bytes of gradient and one 128-byte line of codes per row).  Waves 0 and 1
+// One workgroup per (pair of neighbouring 128-column blocks, row tile), walking the rows in chunks of 16: a chunk
+// is 16 rows x 256 columns (512 contiguous bytes of gradient and one 128-byte line of codes per row).  Waves 0 and 1
 // take the first block of the pair, waves 2 and 3 the second; each wave owns 64 columns, two matrix-core tiles, so
 // that a factor operand read from LDS serves two products.  The contraction runs over rows, so the matrix operand
 // B[i][k] needs, per lane, 8 rows of ONE column: the raw gradient rows and the codes (as bf16 integers) go row-major
 // into LDS tiles and come back through the transposing LDS load ds_read_b64_tr_b16 (within 16 lanes: lane i supplies
 // the address of 4 consecutive columns of row i / 4, chunk i % 4; lane n receives column n of those 4 rows).  The
 // splits of P^ (once for both blocks) and of d_i P^ (per block: the step sizes differ) are made once per chunk by the
-// whole workgroup from the fp32 entries of P^: a thread takes 8 rows of one column, which is what one lane of a
-// matrix-core operand holds, so the splits are stored in operand order and read back with one 16-byte load per
-// operand.  The only factor data a chunk fetches are 4 KB of P^ and its 64 block scales (from the column-block-major
-// copy of the scales).  What limits the pass on the chip is the LDS: the fewer bytes a product reads from it, the
-// better.  Everything a workgroup loads passes through the L2: tables of ready-made splits would cost more of its
-// bandwidth than the splitting costs in arithmetic.  fp32 sums of the matrix cores cover two chunks (64 rows); beyond
-// that the sums are fp64.
-constexpr int kQRows = 32;                  // rows per chunk
+// whole workgroup from the fp32 entries of P^ and stored in the order of the matrix-core operand (lane l of the
+// operand holds column l % 32, rows 8 (l / 32) .. + 7), so that they come back with one 16-byte load per operand.  The
+// only factor data a chunk fetches are 2 KB of P^ and its 32 block scales (from the column-block-major copy of the
+// scales).  The LDS tiles are double buffered: while the matrix cores work on chunk i out of one buffer, the same
+// waves decode, split and store chunk i + 1 into the other, so one barrier per chunk is enough and a wave's vector and
+// LDS-store work runs in the shadow of its own matrix-core instructions instead of in a phase of its own.  Four chunks
+// are in flight in registers.  Everything a workgroup loads passes through the L2: tables of ready-made splits would
+// cost more of its bandwidth than the splitting costs in arithmetic.  fp32 sums of the matrix cores cover four chunks
+// (64 rows); beyond that the sums are fp64.
+// the value of lane (lane ^ 1) / (lane ^ 2) of the quad
+__device__ __forceinline__ float quad_xor1(float a)
+{
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_xor2(float a)
+{
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(a), 0x4E, 0xF, 0xF, true));
+}
+
+// the value of lane j (0..3, a constant) of the quad
+__device__ __forceinline__ float quad_lane(float a, int j)
+{
+    const uint32_t x = __float_as_uint(a);
+    return __uint_as_float(j == 0 ? __builtin_amdgcn_update_dpp(0, x, 0x00, 0xF, 0xF, true)
+                           : j == 1 ? __builtin_amdgcn_update_dpp(0, x, 0x55, 0xF, 0xF, true)
+                           : j == 2 ? __builtin_amdgcn_update_dpp(0, x, 0xAA, 0xF, 0xF, true)
+                                    : __builtin_amdgcn_update_dpp(0, x, 0xFF, 0xF, 0xF, true));
+}
+
+constexpr int kQRows = 16;                  // rows per chunk
+constexpr int kQTrip = 4 * kQRows;          // rows per trip of the main loop (four chunks, one register set each)
 constexpr int kTPitch = 256 + 32;           // bf16 per row of the gradient / code tiles: 576 bytes, conflict-free transposing reads
+constexpr int kQSplit = kQRows * 32;        // bf16 entries of one split of a chunk's rows of P^
 
 // MODE 0: Q+ = (g + e)^T P^, the quantiser's step.
 // MODE 1: the contribution of a compressed vector alone (no gradient; its scales in the second column-block-major
@@ -369,15 +393,15 @@ constexpr int kTPitch = 256 + 32;           // bf16 per row of the gradient / co
 // workspace; its row tiles follow the gradient's in the partial sums, which the reduction kernel adds in order.
 template <int MODE>
 __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t *__restrict__ grads,
-                                                const uint32_t *__restrict__ codes, const float *__restrict__ scales,
-                                                const float *__restrict__ Phat, double *ws, float *Qout)
+                                                   const uint32_t *__restrict__ codes, const float *__restrict__ scales,
+                                                   const float *__restrict__ Phat, double *ws, float *Qout)
 {
     constexpr bool GRAD = MODE != kPModeCodes, ACCUM = MODE == kPModeCodes;
     constexpr bool CODES = MODE == kPModeStep || MODE == kPModeCodes, TABLE = MODE == kPModeTable;
-    __shared__ __attribute__((aligned(16))) uint16_t tg[kQRows * kTPitch];      // gradient rows, raw bf16
-    __shared__ __attribute__((aligned(16))) uint16_t tq[kQRows * kTPitch];      // codes as bf16 integers
-    __shared__ __attribute__((aligned(16))) uint16_t sb[3 * kQRows * 32];       // splits of P^, [split][16 rows][lane] x 8
-    __shared__ __attribute__((aligned(16))) uint16_t sd[2 * 3 * kQRows * 32];   // splits of d_i P^ of the two blocks
+    __shared__ __attribute__((aligned(16))) uint16_t tg[2][kQRows * kTPitch];   // gradient rows, raw bf16
+    __shared__ __attribute__((aligned(16))) uint16_t tq[2][kQRows * kTPitch];   // codes as bf16 integers
+    __shared__ __attribute__((aligned(16))) uint16_t sb[2][3 * kQSplit];        // splits of P^, [split][lane of the operand] x 8
+    __shared__ __attribute__((aligned(16))) uint16_t sd[2][2 * 3 * kQSplit];    // splits of d_i P^ of the two blocks
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const WorkItem it = TABLE ? dp.cs_qt_items[blockIdx.x] : dp.q_m_items[xcd_contiguous_item(blockIdx.x, dp.n_q_m)];
@@ -397,113 +421,96 @@ __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t
     const float *scT = reinterpret_cast<const float *>(ws + (GRAD ? d.scT_off : d.scT2_off));       // [block][row]
     const float *ph = TABLE ? reinterpret_cast<const float *>(ws + d.cs_u_off) : Phat + d.p_off;
 
-    // A chunk's loads are held in registers until its turn in LDS; two chunks are in flight.  Every load is
-    // unconditional (rows at or beyond the end of the tile re-read its last row and get zero factor operands
-    // instead): the waits on one chunk can then leave the younger one's loads pending.
+    // A chunk's loads are held in registers until its turn in LDS.  Every load is unconditional (rows at or beyond the
+    // end of the tile re-read its last row and get zero factor operands instead): the waits on one chunk can then
+    // leave the younger ones' loads pending.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4q __attribute__((ext_vector_type(4)));
     struct ChunkRegs {
-        u32x4 g0, g1, g2, g3;   // gradient: 16-byte pieces of rows grow + 8 s
-        u32x4 cwq;              // 32 code fields of row crow
-        float sc[8];            // block scales of the rows of the factor role
-        float pf[8];            // P^ of the rows of the factor role
+        u32x4 g0, g1;           // gradient: 16-byte pieces of rows grow, grow + 8
+        uint2 cwd;              // 16 code fields of row crow
+        float scq;              // block scale of row frow + lane % 4 of the lane's block (handed round inside the quad when stored)
+        f32x4q pf;              // P^: row frow + lane % 4, columns 4 (fc / 4) .. + 3 (transposed inside the quad when stored)
     };
-    // factor roles: column fc of P^ and the 8 rows 8 frg .. 8 frg + 7 of the chunk, for the column block fblk of the
-    // pair: exactly what one lane of a matrix-core operand holds (lane 32 (frg % 2) + fc of the operand of rows
-    // 16 (frg / 2) ..), so the splits go to LDS in operand order.  The splits of P^ itself serve both blocks: the
-    // threads of block 0 make those of rows 8 frg .. + 3, the threads of block 1 those of rows 8 frg + 4 .. + 7.
-    const int fc = tid & 31, frg = (tid >> 5) & 3, fblk = tid >> 7;
+    // factor roles: column fc of P^ and the 4 rows frow .. frow + 3 of the chunk, for the column block fblk of the
+    // pair.  Lane 32 fh + fc of a matrix-core operand holds column fc, rows 8 fh .. 8 fh + 7 of the chunk, so a thread
+    // makes half a lane's operand of the splits of d_i P^ of its block (4 rows), and a quarter of a lane's operand
+    // of the splits of P^ itself, which serve both blocks (2 of its rows: the first two for block 0, the others for 1).
+    // The rows are the same for a whole wave (wave w: rows 4 w .. 4 w + 3; its lanes 0..31 work for block 0, the others
+    // for block 1): a lane loads ONE scale (row frow + lane % 4 of its block) and ONE 16-byte piece of P^ (that row, four
+    // columns); the four lanes of a quad hand the scales round and transpose the 4 x 4 entries of P^ among themselves.
+    // Loads of 4 bytes per lane cost this pass as much as the wide ones, and there were eight of them per chunk against
+    // three wide ones.  (Reading the scales through the scalar cache instead was slower: its loads and the LDS
+    // operations are waited for through one counter.)
+    const int fc = lane & 31, fblk = lane >> 5;
+    const int frow = 4 * wave, fh = wave >> 1, fj = wave & 1;
     const int fcb = fblk ? cbB : cbA;
-    // gradient roles: 16-byte piece gpc (0..31) of the chunk's 512-byte rows grow + 8 s; pieces 16.. are block B's
+    const int fq = lane & 3;                         // the row (of the wave's four) whose entries of P^ the lane loads
+    // gradient roles: 16-byte piece gpc (0..31) of the chunk's 512-byte rows grow, grow + 8; pieces 16.. are block B's
     const int grow = tid >> 5, gpc = tid & 31;
     const int gcol = ((gpc < 16) ? cbA : cbB) * 128 + (gpc & 15) * 8;          // first column of the piece
-    // code roles: 16-byte piece (32 fields) cq (0..7) of the 128-byte line of row crow; pieces 4.. are block B's
-    const int crow = tid >> 3, cq = tid & 7;
-    const int ccol = ((cq < 4) ? cbA : cbB) * 128 + (cq & 3) * 32;
+    // code roles: 8-byte piece (16 fields) cq (0..15) of the 128-byte line of row crow; pieces 8.. are block B's
+    const int crow = tid >> 4, cq = tid & 15;
+    const int ccol = ((cq < 8) ? cbA : cbB) * 128 + (cq & 7) * 16;
     // Loads of a chunk that lies whole inside the tile: a scalar base per array (the chunk's first row) plus a 32-bit
-    // lane offset that never changes; rows 8 s further down and the 8 rows of a factor role are reached through the
-    // scalar base and the instruction's immediate offset, so no address is computed per lane.
-    const uint32_t foff = (uint32_t)((8 * frg) * 32 + fc) * 4u;                 // P^: rows 8 frg + j, column fc
-    const uint32_t soff = (uint32_t)(8 * frg) * 4u;                             // scales of rows 8 frg + j
+    // lane offset that never changes; the other rows of a role are reached through the scalar base and the
+    // instruction's immediate offset, so no address is computed per lane.
+    const uint32_t foff = (uint32_t)((frow + fq) * 32 + (fc & ~3)) * 4u;        // P^: row frow + fq, columns 4 (fc / 4) ..
+    const uint32_t soff = (uint32_t)(fcb * (int)d.n + frow + fq) * 4u;          // scale of row frow + fq, block fcb (from scT + i0)
     const uint32_t goff = ((uint32_t)grow * (uint32_t)m + (uint32_t)gcol) * 2u;
     const uint32_t woff = (((uint32_t)crow * (uint32_t)m + (uint32_t)ccol) >> 3) * 4u;
     auto load_chunk_whole = [&](ChunkRegs &r, int64_t i0) {
-        const char *pb = reinterpret_cast<const char *>(ph + i0 * 32) + foff;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r.pf[j] = *reinterpret_cast<const float *>(pb + j * 128);
-        if (CODES) {
-            const char *sb8 = reinterpret_cast<const char *>(scT + (int64_t)fcb * d.n + i0) + soff;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) r.sc[j] = *reinterpret_cast<const float *>(sb8 + j * 4);
-        }
+        r.pf = *reinterpret_cast<const f32x4q *>(reinterpret_cast<const char *>(ph + i0 * 32) + foff);
+        if (CODES) r.scq = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(scT + i0) + soff);
         const int64_t e0 = i0 * m;                                              // uniform
         if (GRAD) {
             const char *gb = reinterpret_cast<const char *>(g + e0);
-            const int64_t pitch8 = (int64_t)m * 16;                             // bytes of 8 rows
             r.g0 = *reinterpret_cast<const u32x4 *>(gb + goff);
-            r.g1 = *reinterpret_cast<const u32x4 *>(gb + pitch8 + goff);
-            r.g2 = *reinterpret_cast<const u32x4 *>(gb + 2 * pitch8 + goff);
-            r.g3 = *reinterpret_cast<const u32x4 *>(gb + 3 * pitch8 + goff);
+            r.g1 = *reinterpret_cast<const u32x4 *>(gb + (int64_t)m * 16 + goff);       // 8 rows further down
         }
-        if (CODES) r.cwq = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(cw + (e0 >> 3)) + woff);
+        if (CODES) r.cwd = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(cw + (e0 >> 3)) + woff);
     };
     auto load_chunk_clamped = [&](ChunkRegs &r, int64_t i0) {
         const int64_t last = row1 - 1;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t row = (i0 + 8 * frg + j < row1) ? i0 + 8 * frg + j : last;
-            r.pf[j] = ph[row * 32 + fc];
-            if (CODES) r.sc[j] = scT[(int64_t)fcb * d.n + row];
+        {
+            const int64_t row = (i0 + frow + fq < row1) ? i0 + frow + fq : last;
+            r.pf = *reinterpret_cast<const f32x4q *>(ph + row * 32 + (fc & ~3));
+        }
+        if (CODES) {
+            const int64_t row = (i0 + frow + fq < row1) ? i0 + frow + fq : last;
+            r.scq = scT[(int64_t)fcb * d.n + row];
         }
         if (GRAD) {
-            int64_t e[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int64_t row = (i0 + grow + 8 * s < row1) ? i0 + grow + 8 * s : last;
-                e[s] = row * m + gcol;
-            }
-            r.g0 = *reinterpret_cast<const u32x4 *>(g + e[0]);
-            r.g1 = *reinterpret_cast<const u32x4 *>(g + e[1]);
-            r.g2 = *reinterpret_cast<const u32x4 *>(g + e[2]);
-            r.g3 = *reinterpret_cast<const u32x4 *>(g + e[3]);
+            const int64_t ra = (i0 + grow < row1) ? i0 + grow : last, rb = (i0 + grow + 8 < row1) ? i0 + grow + 8 : last;
+            r.g0 = *reinterpret_cast<const u32x4 *>(g + ra * m + gcol);
+            r.g1 = *reinterpret_cast<const u32x4 *>(g + rb * m + gcol);
         }
         if (CODES) {
             const int64_t row = (i0 + crow < row1) ? i0 + crow : last;
-            r.cwq = *reinterpret_cast<const u32x4 *>(cw + ((row * m + ccol) >> 3));
+            r.cwd = *reinterpret_cast<const uint2 *>(cw + ((row * m + ccol) >> 3));
         }
     };
-    // splits of 8 (or 4: `half`) rows of one column, in operand order: [split][16 rows][lane] x 8 bf16
-    auto store_split = [&](uint16_t *o, const float (&x)[8]) {
-        float hh[8], mm[8], ll[8];
+    // a chunk's registers go to LDS buffer `buf`; the factor entries of rows at or beyond the end of the tile count as
+    // zero, whatever the re-read row holds
+    auto store_chunk = [&](const ChunkRegs &r, int64_t i0, int buf) {
+        // the quad's 4 x 4 entries of P^ (lane q: row q, four columns) transposed (lane q: column q, four rows): an
+        // exchange with the neighbour, then with the lane two further on
+        float pv[4];
+        {
+            const bool o1 = (fq & 1) != 0, o2 = (fq & 2) != 0;
+            const float a0 = r.pf[0], a1 = r.pf[1], a2 = r.pf[2], a3 = r.pf[3];
+            const float y0 = quad_xor1(o1 ? a0 : a1), y1 = quad_xor1(o1 ? a2 : a3);
+            const float b0 = o1 ? y0 : a0, b1 = o1 ? a1 : y0, b2 = o1 ? y1 : a2, b3 = o1 ? a3 : y1;
+            const float z0 = quad_xor2(o2 ? b0 : b2), z1 = quad_xor2(o2 ? b1 : b3);
+            pv[0] = o2 ? z0 : b0; pv[1] = o2 ? z1 : b1; pv[2] = o2 ? b2 : z0; pv[3] = o2 ? b3 : z1;
+        }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) split3(x[j], hh[j], mm[j], ll[j]);
-        uint16_t *dst = o + ((frg >> 1) * 64 + (frg & 1) * 32 + fc) * 8;
-        *reinterpret_cast<uint4 *>(dst) =
-            make_uint4(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]), pack_hi16(hh[4], hh[5]), pack_hi16(hh[6], hh[7]));
-        *reinterpret_cast<uint4 *>(dst + kQRows * 32) =
-            make_uint4(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]), pack_hi16(mm[4], mm[5]), pack_hi16(mm[6], mm[7]));
-        *reinterpret_cast<uint4 *>(dst + 2 * kQRows * 32) =
-            make_uint4(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]), pack_hi16(ll[4], ll[5]), pack_hi16(ll[6], ll[7]));
-    };
-    auto store_split_half = [&](uint16_t *o, const float (&x)[4], int half) {
-        float hh[4], mm[4], ll[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) split3(x[j], hh[j], mm[j], ll[j]);
-        uint16_t *dst = o + ((frg >> 1) * 64 + (frg & 1) * 32 + fc) * 8 + 4 * half;
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]));
-        *reinterpret_cast<uint2 *>(dst + kQRows * 32) = make_uint2(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]));
-        *reinterpret_cast<uint2 *>(dst + 2 * kQRows * 32) = make_uint2(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]));
-    };
-    // a chunk's registers go to LDS; the factor entries of rows at or beyond the end of the tile count as zero,
-    // whatever the re-read row holds
-    auto store_chunk = [&](const ChunkRegs &r, int64_t i0) {
-        const u32x4 gs[4] = {r.g0, r.g1, r.g2, r.g3};
-        float pv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) pv[j] = (i0 + 8 * frg + j < row1) ? r.pf[j] : 0.0f;
+        for (int j = 0; j < 4; ++j) pv[j] = (i0 + frow + j < row1) ? pv[j] : 0.0f;
         if (GRAD) {
+            const u32x4 gs[2] = {r.g0, r.g1};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                uint16_t *dg = tg + (grow + 8 * s) * kTPitch + gpc * 8;
+            for (int s = 0; s < 2; ++s) {
+                uint16_t *dg = tg[buf] + (grow + 8 * s) * kTPitch + gpc * 8;
                 if (TABLE) {
                     // fp16 -> fp32 (exact) -> upper half (bf16 by truncation) and what is left
                     u32x4 hi, lo;
@@ -515,49 +522,56 @@ __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t
                         lo[e2] = pack_hi16(x0 - h0, x1 - h1);
                     }
                     *reinterpret_cast<u32x4 *>(dg) = hi;
-                    *reinterpret_cast<u32x4 *>(tq + (grow + 8 * s) * kTPitch + gpc * 8) = lo;
+                    *reinterpret_cast<u32x4 *>(tq[buf] + (grow + 8 * s) * kTPitch + gpc * 8) = lo;
                 } else {
                     *reinterpret_cast<u32x4 *>(dg) = gs[s];
                 }
             }
         }
         if (CODES) {
-            // 32 code fields -> 32 bf16 sixteenths of small integers (exact), four 16-byte pieces
-            uint16_t *dq = tq + crow * kTPitch + ((cq < 4) ? 0 : 128) + (cq & 3) * 32;
+            // 16 code fields -> 16 bf16 sixteenths of small integers (exact), two 16-byte pieces
+            uint16_t *dq = tq[buf] + crow * kTPitch + ((cq < 8) ? 0 : 128) + (cq & 7) * 16;
+            const uint32_t wd[2] = {r.cwd.x, r.cwd.y};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < 2; ++s) {
                 float q16[8];
-                fields_over_16(r.cwq[s], q16);
+                fields_over_16(wd[s], q16);
                 u32x4 qb;
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) qb[e2] = pack_hi16(q16[2 * e2], q16[2 * e2 + 1]);
                 *reinterpret_cast<u32x4 *>(dq + 8 * s) = qb;
             }
         }
-        // P^ itself: both halves of the workgroup share the work (4 rows each)
+        const int slot = (32 * fh + fc) * 8 + 4 * fj;       // the thread's 4 rows inside the operand of lane 32 fh + fc
         if (GRAD) {
-            float ph4[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float x = fblk ? pv[4 + j] : pv[j];
-                ph4[j] = TABLE ? dp.omb * x : x;
-            }
-            store_split_half(sb, ph4, fblk);
+            // P^ itself: two of the thread's four rows
+            const float x0 = fblk ? pv[2] : pv[0], x1 = fblk ? pv[3] : pv[1];
+            const float y0 = TABLE ? dp.omb * x0 : x0, y1 = TABLE ? dp.omb * x1 : x1;
+            float h0, m0, l0, h1, m1, l1;
+            split3(y0, h0, m0, l0);
+            split3(y1, h1, m1, l1);
+            uint16_t *dst = sb[buf] + slot + 2 * fblk;
+            *reinterpret_cast<uint32_t *>(dst) = pack_hi16(h0, h1);
+            *reinterpret_cast<uint32_t *>(dst + kQSplit) = pack_hi16(m0, m1);
+            *reinterpret_cast<uint32_t *>(dst + 2 * kQSplit) = pack_hi16(l0, l1);
         }
         if (CODES) {
-            float dp8[8];
+            float hh[4], mm[4], ll[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < 4; ++j) {
                 // omb: 1 - beta (Algorithm 4 line 5); times 16 (exact) because the code operands are sixteenths
                 // (the product with 16 is exact, so it can be taken with the constant: fl(fl(s c) omb) 16 = fl(fl(s 16 c) omb))
-                const float dstep = (r.sc[j] * (inv_levels(4) * 16.0f)) * dp.omb;
-                dp8[j] = dstep * pv[j];                      // pv is zero for rows beyond the tile
+                const float dstep = (quad_lane(r.scq, j) * (inv_levels(4) * 16.0f)) * dp.omb;
+                split3(dstep * pv[j], hh[j], mm[j], ll[j]);          // pv is zero for rows beyond the tile
             }
-            store_split(sd + fblk * (3 * kQRows * 32), dp8);
+            uint16_t *dst = sd[buf] + fblk * (3 * kQSplit) + slot;
+            *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]));
+            *reinterpret_cast<uint2 *>(dst + kQSplit) = make_uint2(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]));
+            *reinterpret_cast<uint2 *>(dst + 2 * kQSplit) = make_uint2(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]));
         }
     };
 
-    // the matrix cores accumulate two chunks (64 rows) in fp32; beyond that the sums are fp64
+    // the matrix cores accumulate four chunks (64 rows) in fp32; beyond that the sums are fp64
     f32x16 acc[2];
     double acc64[2][16];
 #pragma unroll
@@ -571,36 +585,28 @@ __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t
     const int gq = lane >> 4, li = lane & 15;
     const int tr_row = 8 * (gq >> 1) + (li >> 2), tr_col = 16 * (gq & 1) + 4 * (li & 3);
     const int tr_t = tr_row * kTPitch + wcol + tr_col;     // gradient / code tiles
-    const uint16_t *sdw = sd + wblk * (3 * kQRows * 32);
 
-    // Wave priority: the phases that issue loads and fill LDS run at a higher priority than the
-    // matrix-core phase, so that the workgroup that is feeding the memory pipeline is not held up by
-    // the other workgroup of the CU, which is computing.
-    auto compute_chunk = [&]() {
-        __builtin_amdgcn_s_setprio(0);
+    auto compute_chunk = [&](int buf) {
+        Frag aP[3], aD[3];
+        const uint16_t *sdw = sd[buf] + wblk * (3 * kQSplit);
 #pragma unroll
-        for (int ks = 0; ks < kQRows / 16; ++ks) {
-            Frag aP[3], aD[3];
-#pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                if (GRAD) aP[s].u = *reinterpret_cast<const uint4 *>(sb + s * kQRows * 32 + (ks * 64 + lane) * 8);
-                if (CODES) aD[s].u = *reinterpret_cast<const uint4 *>(sdw + s * kQRows * 32 + (ks * 64 + lane) * 8);
-                if (TABLE) aD[s].u = aP[s].u;          // both tiles of a table entry meet the same factor
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                Frag bg, bq;
-                if (GRAD) bg.u = lds_read_tr16x8(tg + tr_t + 32 * t + ks * 16 * kTPitch, kTPitch);
-                if (CODES || TABLE) bq.u = lds_read_tr16x8(tq + tr_t + 32 * t + ks * 16 * kTPitch, kTPitch);
-                if (GRAD) acc[t] = mfma(aP[0], bg, acc[t]);
-                if (CODES || TABLE) acc[t] = mfma(aD[0], bq, acc[t]);
-                if (GRAD) acc[t] = mfma(aP[1], bg, acc[t]);
-                if (CODES || TABLE) acc[t] = mfma(aD[1], bq, acc[t]);
-                if (GRAD) acc[t] = mfma(aP[2], bg, acc[t]);
-                if (CODES || TABLE) acc[t] = mfma(aD[2], bq, acc[t]);
-            }
+        for (int s = 0; s < 3; ++s) {
+            if (GRAD) aP[s].u = *reinterpret_cast<const uint4 *>(sb[buf] + s * kQSplit + lane * 8);
+            if (CODES) aD[s].u = *reinterpret_cast<const uint4 *>(sdw + s * kQSplit + lane * 8);
+            if (TABLE) aD[s].u = aP[s].u;          // both tiles of a table entry meet the same factor
         }
-        __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            Frag bg, bq;
+            if (GRAD) bg.u = lds_read_tr16x8(tg[buf] + tr_t + 32 * t, kTPitch);
+            if (CODES || TABLE) bq.u = lds_read_tr16x8(tq[buf] + tr_t + 32 * t, kTPitch);
+            if (GRAD) acc[t] = mfma(aP[0], bg, acc[t]);
+            if (CODES || TABLE) acc[t] = mfma(aD[0], bq, acc[t]);
+            if (GRAD) acc[t] = mfma(aP[1], bg, acc[t]);
+            if (CODES || TABLE) acc[t] = mfma(aD[1], bq, acc[t]);
+            if (GRAD) acc[t] = mfma(aP[2], bg, acc[t]);
+            if (CODES || TABLE) acc[t] = mfma(aD[2], bq, acc[t]);
+        }
     };
     auto fold = [&]() {
 #pragma unroll
@@ -609,37 +615,51 @@ __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t
             for (int v = 0; v < 16; ++v) { acc64[t][v] += (double)acc[t][v]; acc[t][v] = 0.0f; }
     };
 
-    // Two chunks per trip, one register set each.  A trip loads the two chunks after its own: whole-chunk loads as
-    // long as those lie inside the tile, clamped ones in the last trips (a chunk cut off by the tile's end; beyond
-    // it, rows that clamp to the tile's last row and are not used).  The two kinds of trip are separate loops, so
-    // that no load sits behind a branch.
-    ChunkRegs ra, rb;
-    if (row0 + 2 * kQRows <= row1) {
-        load_chunk_whole(ra, row0);
-        load_chunk_whole(rb, row0 + kQRows);
+    // Four chunks per trip, one register set each; chunk j of a trip is computed out of buffer j % 2 while chunk j + 1
+    // goes into the other one, and a register set is reloaded, with the chunk four further on, as soon as it has been
+    // stored.  Whole-chunk loads as long as the next trip's chunks lie inside the tile, clamped ones in the last trips
+    // (a chunk cut off by the tile's end; beyond it, rows that clamp to the tile's last row and are not used).  The two
+    // kinds of trip are separate loops, so that no load sits behind a branch.
+    ChunkRegs r0, r1, r2, r3;
+    if (row0 + kQTrip <= row1) {
+        load_chunk_whole(r0, row0);
+        load_chunk_whole(r1, row0 + kQRows);
+        load_chunk_whole(r2, row0 + 2 * kQRows);
+        load_chunk_whole(r3, row0 + 3 * kQRows);
     } else {
-        load_chunk_clamped(ra, row0);
-        load_chunk_clamped(rb, row0 + kQRows);
+        load_chunk_clamped(r0, row0);
+        load_chunk_clamped(r1, row0 + kQRows);
+        load_chunk_clamped(r2, row0 + 2 * kQRows);
+        load_chunk_clamped(r3, row0 + 3 * kQRows);
     }
+    store_chunk(r0, row0, 0);
     auto trip = [&](int64_t i0, auto whole) {
         constexpr bool W = decltype(whole)::value;
-        __syncthreads();                // everybody is done reading the previous chunk
-        store_chunk(ra, i0);
+        auto reload = [&](ChunkRegs &r, int64_t at) {
+            if (W) load_chunk_whole(r, at);
+            else load_chunk_clamped(r, at);
+        };
+        reload(r0, i0 + kQTrip);            // r0 went to LDS before this trip
+        __syncthreads();                    // chunk 0 is in buffer 0; everybody is done with buffer 1
+        store_chunk(r1, i0 + kQRows, 1);
+        reload(r1, i0 + kQTrip + kQRows);
+        compute_chunk(0);
         __syncthreads();
-        if (W) load_chunk_whole(ra, i0 + 2 * kQRows);
-        else load_chunk_clamped(ra, i0 + 2 * kQRows);
-        compute_chunk();
+        store_chunk(r2, i0 + 2 * kQRows, 0);
+        reload(r2, i0 + kQTrip + 2 * kQRows);
+        compute_chunk(1);
         __syncthreads();
-        store_chunk(rb, i0 + kQRows);
+        store_chunk(r3, i0 + 3 * kQRows, 1);
+        reload(r3, i0 + kQTrip + 3 * kQRows);
+        compute_chunk(0);
         __syncthreads();
-        if (W) load_chunk_whole(rb, i0 + 3 * kQRows);
-        else load_chunk_clamped(rb, i0 + 3 * kQRows);
-        compute_chunk();
+        store_chunk(r0, i0 + kQTrip, 0);    // the next trip's first chunk
+        compute_chunk(1);
         fold();
     };
     int64_t i0 = row0;
-    for (; i0 + 4 * kQRows <= row1; i0 += 2 * kQRows) trip(i0, std::true_type());       // these chunks and the next two are whole
-    for (; i0 < row1; i0 += 2 * kQRows) trip(i0, std::false_type());
+    for (; i0 + 2 * kQTrip <= row1; i0 += kQTrip) trip(i0, std::true_type());       // the next trip's chunks are whole too
+    for (; i0 < row1; i0 += kQTrip) trip(i0, std::false_type());
     // D[c][k]: lane holds column k = lane % 32 of a tile and c = 8 (v / 4) + 4 (lane / 32) + v % 4
     if (wblk && !has_b) return;
     const int cb = wblk ? cbB : cbA;
