@@ -670,26 +670,56 @@ __global__ __launch_bounds__(256, 2) void k_q_mfma(DevicePlan dp, const uint16_t
             // linear form of the count sketch: always partial sums, the table's row tiles behind the gradient's
             double *out = ws + d.qpart_off + ((int64_t)((TABLE ? d.cs_q_tiles_g : 0) + it.b) * m + kcol) * 32;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) out[8 * (v >> 2) + 4 * ig + (v & 3)] = acc64[t][v];
+            for (int g4 = 0; g4 < 4; ++g4) {
+                double2 *o2 = reinterpret_cast<double2 *>(out + 8 * g4 + 4 * ig);
+                o2[0] = make_double2(acc64[t][4 * g4], acc64[t][4 * g4 + 1]);
+                o2[1] = make_double2(acc64[t][4 * g4 + 2], acc64[t][4 * g4 + 3]);
+            }
             continue;
         }
         if (d.n_q_tiles == 1) {
-            // the only row tile of this matrix: Q+ and its operand splits are final
+            // the only row tile of this matrix: Q+ and its operand splits are final.  A lane's sixteen entries are
+            // four runs of four neighbouring c: one 16-byte store of Q+ and one 8-byte store per split for each run
+            // (entry by entry, these stores were an eighth of the pass)
             float *qo = Qout + d.q_off + (int64_t)kcol * 32;
+            uint16_t *so = reinterpret_cast<uint16_t *>(ws + d.qs_off) + (int64_t)(kcol >> 7) * (3 * 128 * 32) +
+                           ((kcol & 7) * 16 + ((kcol >> 3) & 15)) * 32;          // as mfma_store_q_split lays them out
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-                const float x = (float)(ACCUM ? acc64[t][v] + (double)qo[c] : acc64[t][v]);
-                qo[c] = x;
-                mfma_store_q_split(d, ws, kcol, c, x);
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int c0 = 8 * g4 + 4 * ig;
+                float4 *q4 = reinterpret_cast<float4 *>(qo + c0);
+                float x[4];
+                if (ACCUM) {
+                    const float4 old = *q4;
+                    x[0] = (float)(acc64[t][4 * g4] + (double)old.x); x[1] = (float)(acc64[t][4 * g4 + 1] + (double)old.y);
+                    x[2] = (float)(acc64[t][4 * g4 + 2] + (double)old.z); x[3] = (float)(acc64[t][4 * g4 + 3] + (double)old.w);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x[j] = (float)acc64[t][4 * g4 + j];
+                }
+                *q4 = make_float4(x[0], x[1], x[2], x[3]);
+                float hh[4], mm[4], ll[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) split3(x[j], hh[j], mm[j], ll[j]);
+                *reinterpret_cast<uint2 *>(so + c0) = make_uint2(pack_hi16(hh[0], hh[1]), pack_hi16(hh[2], hh[3]));
+                *reinterpret_cast<uint2 *>(so + 128 * 32 + c0) = make_uint2(pack_hi16(mm[0], mm[1]), pack_hi16(mm[2], mm[3]));
+                *reinterpret_cast<uint2 *>(so + 2 * 128 * 32 + c0) = make_uint2(pack_hi16(ll[0], ll[1]), pack_hi16(ll[2], ll[3]));
             }
         } else {
             // partial sums of this row tile, added in tile order by the reduction kernel
             double *out = ws + d.qpart_off + ((int64_t)it.b * m + kcol) * 32;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int c = 8 * (v >> 2) + 4 * ig + (v & 3);
-                out[c] = ACCUM ? out[c] + acc64[t][v] : acc64[t][v];
+            for (int g4 = 0; g4 < 4; ++g4) {
+                double2 *o2 = reinterpret_cast<double2 *>(out + 8 * g4 + 4 * ig);
+                double y[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) y[j] = acc64[t][4 * g4 + j];
+                if (ACCUM) {
+                    const double2 a = o2[0], b = o2[1];
+                    y[0] += a.x; y[1] += a.y; y[2] += b.x; y[3] += b.y;
+                }
+                o2[0] = make_double2(y[0], y[1]);
+                o2[1] = make_double2(y[2], y[3]);
             }
         }
     }
