@@ -1,6 +1,7 @@
 // Orthonormalisation of all left factors of a model: P^ = thin-QR factor of P with positive
 // diagonal of R, by Cholesky-QR in fp64:  G = P^T P,  G = R^T R,  P^ = P R^-1.  In exact arithmetic
-// this is the matrix Gram-Schmidt produces.  Four grouped launches:
+// this is the matrix Gram-Schmidt produces.  Four grouped launches (three for ranks up to 8, where
+// k_gram_sum_cholesky does the work of the second and the third):
 //   k_gram_partial      fp64 Gram matrices of row tiles (4 x 4 register blocks per thread); at rank 32
 //                       k_gram_mfma32 does the same on the fp64 matrix cores, straight from global memory,
 //   k_gram_reduce       the tiles of a matrix added up: 16 interleaved partial sums per entry, each
