@@ -121,12 +121,41 @@ __global__ __launch_bounds__(kGenQCols) void k_pass_q_generic(DevicePlan dp, con
         if (c < r) out[c] = acc[c];
 }
 
+// Adds the row-tile partial sums of Q+ and rounds once to fp32.  item.c = 0: 256 entries, a thread per entry, the tiles
+// in order.  item.c = 1 (a tall matrix: kQredManyTiles tiles or more): 16 entries; thread (entry, part) adds the tiles
+// part, part + 16, ... in that order, then the 16 parts are added in order (the order of k_gram_reduce).
 __global__ __launch_bounds__(256) void k_q_reduce(DevicePlan dp, const double *ws, double *ws_rw, float *Qout)
 {
+    __shared__ double red[16][16];
     const WorkItem it = dp.qred_items[blockIdx.x];
     const MatDesc d = dp.mats[it.mat];
-    const int64_t e = (int64_t)it.a + threadIdx.x;
     const int64_t len = d.m * dp.rank;
+    if (it.c) {
+        const int t = threadIdx.x, part = t >> 4;
+        const int64_t e16 = (int64_t)it.a + (t & 15);
+        const bool live = e16 < len;
+        const double *src = ws + d.qpart_off + (live ? e16 : 0);
+        double s = 0.0;
+        int k = part;
+        for (; k + 48 < d.n_q_tiles; k += 64) {
+            const double v0 = src[(int64_t)k * len], v1 = src[(int64_t)(k + 16) * len];
+            const double v2 = src[(int64_t)(k + 32) * len], v3 = src[(int64_t)(k + 48) * len];
+            s = ((s + v0) + v1) + v2;
+            s += v3;
+        }
+        for (; k < d.n_q_tiles; k += 16) s += src[(int64_t)k * len];
+        red[part][t & 15] = s;
+        __syncthreads();
+        if (t >= 16 || !live) return;
+        double a = red[0][t];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) a += red[q][t];
+        const float v = (float)a;
+        Qout[d.q_off + e16] = v;
+        if (d.path == kPathMfma) mfma_store_q_split(d, ws_rw, (int)(e16 >> 5), (int)(e16 & 31), v);
+        return;
+    }
+    const int64_t e = (int64_t)it.a + threadIdx.x;
     if (e >= len) return;
     const float v = (float)ordered_sum(ws + d.qpart_off + e, d.n_q_tiles, len);
     Qout[d.q_off + e] = v;

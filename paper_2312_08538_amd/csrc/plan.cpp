@@ -573,7 +573,13 @@ int make_plan_impl(Plan &plan, const int64_t *rows, const int64_t *cols, int n_m
             for (int64_t r0 = 0; r0 < d.n; r0 += 64) plan.apply_items.push_back({l, (int32_t)r0, 0, 0});
             // a matrix-core matrix with a single row tile gets its Q+ straight from the Q+ pass
             if (!((mf_q || d.pack) && d.n_q_tiles == 1) || d.cs_lin)
-                for (int64_t e0 = 0; e0 < d.m * rank; e0 += 256) plan.qred_items.push_back({l, (int32_t)e0, 0, 0});
+            {
+                // 256 entries per workgroup, a thread per entry; with kQredManyTiles partial sums or more per entry, 16
+                // entries per workgroup and 16 threads per entry (item.c = 1)
+                const int per = (!d.cs_lin && d.n_q_tiles >= kQredManyTiles) ? 16 : 256;      // (the sketch's linear form adds tiles later)
+                for (int64_t e0 = 0; e0 < d.m * rank; e0 += per)
+                    plan.qred_items.push_back({l, (int32_t)e0, 0, per == 16 ? 1 : 0});
+            }
             for (int64_t e0 = 0; e0 < d.N; e0 += 1024) plan.elem_items.push_back({l, (int32_t)(e0 >> 10), 0, 0});
             for (int64_t r0 = 0; r0 < d.n; r0 += kUpdRows)
                 for (int64_t c0 = 0; c0 < d.m; c0 += kUpdCols)
@@ -845,7 +851,8 @@ bool check_plan(const Plan &plan)
         if (d.pack && (d.path != kPathOctet || d.n_p_chunks != 1 || (d.m & 127) != 0 || plan.block < 128 || plan.dtype != 1 ||
                        (plan.bits != 2 && plan.bits != 4)))
             return false;
-        if (qred[l] != (direct_q ? 0 : (d.m * plan.rank + 255) / 256)) return false;
+        const int64_t qper = (!d.cs_lin && d.n_q_tiles >= kQredManyTiles) ? 16 : 256;
+        if (qred[l] != (direct_q ? 0 : (d.m * plan.rank + qper - 1) / qper)) return false;
         if (pred[l] != (d.n_p_chunks > 1 ? (d.n * plan.rank + 255) / 256 : 0)) return false;
         regions.push_back({d.gram_off, d.gram_off + (int64_t)d.n_gram_tiles * plan.rank * plan.rank});
         regions.push_back({d.gsum_off, d.gsum_off + (int64_t)plan.rank * plan.rank});

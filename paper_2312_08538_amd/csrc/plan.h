@@ -10,6 +10,7 @@ namespace conef {
 constexpr int kAlign = 64;          // every per-matrix offset is a multiple of 64 elements
 constexpr int kMaxRank = 32;
 constexpr int kGramRows = 256;      // rows per LDS piece of the Gram kernel
+constexpr int kQredManyTiles = 32;  // partial sums of Q+ per entry from which 16 threads share an entry's sum
 constexpr int kGenQRows = 128;      // rows per partial of Q+ in the generic pass 2
 constexpr int kGenQCols = 256;      // columns per workgroup in the generic pass 2
 constexpr int kFastMaxRank = 8;     // the octet family holds rank <= 8 in registers
